@@ -1,0 +1,142 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Loads ``liboracle.so`` built from ``sprnn_oracle.c`` (plain C, gcc) and exposes
+the oracle's functions on numpy arrays.  Nothing in the product package may
+import this module; only ``tests/``, the smoke check and the benchmark's
+CPU-baseline leg do.  It imports nothing from the product package.
+
+Cells and equations: see the header of ``sprnn_oracle.c`` (Eq. 2 of the paper
+for the vanilla cell; Appendix B's four-gate LSTM).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sprnn_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+ACT = {"relu": 0, "tanh": 1, "identity": 2}
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fused multiply-add contraction) and return the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+               "-fopenmp", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        ci = ctypes.c_int
+        lib.oracle_half_bits_to_float.restype = ctypes.c_float
+        lib.oracle_half_bits_to_float.argtypes = [ctypes.c_uint16]
+        lib.oracle_rnn_forward.restype = ci
+        lib.oracle_rnn_forward.argtypes = [ci, ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, ci]
+        lib.oracle_rnn_forward_f64.restype = ci
+        lib.oracle_rnn_forward_f64.argtypes = [ci, ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f64p, ci]
+        lib.oracle_lstm_forward.restype = ci
+        lib.oracle_lstm_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f32p, ci]
+        lib.oracle_lstm_forward_f64.restype = ci
+        lib.oracle_lstm_forward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, f64p, ci]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray], ctype):
+    if a is None:
+        return ctypes.cast(None, ctypes.POINTER(ctype))
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _csr(row_ptr, col_idx, val_bits, rows, cols):
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    val_bits = np.ascontiguousarray(val_bits, dtype=np.uint16)
+    if row_ptr.shape != (rows + 1,) or row_ptr[0] != 0 or np.any(np.diff(row_ptr) < 0):
+        raise ValueError("malformed row_ptr")
+    nnz = int(row_ptr[-1])
+    if col_idx.shape != (nnz,) or val_bits.shape != (nnz,):
+        raise ValueError("col_idx / val_bits length differs from row_ptr[-1]")
+    if nnz and (col_idx.min() < 0 or col_idx.max() >= cols):
+        raise ValueError("column index out of range")
+    # keep ctypes happy for empty arrays
+    if nnz == 0:
+        col_idx = np.zeros(1, dtype=np.int32)
+        val_bits = np.zeros(1, dtype=np.uint16)
+    return row_ptr, col_idx, val_bits
+
+
+def half_bits_to_float(bits) -> np.ndarray:
+    """Decode binary16 bit patterns with the oracle's own decoder (element by element)."""
+    lib = _load()
+    bits = np.asarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float32)
+    flat_in, flat_out = bits.reshape(-1), out.reshape(-1)
+    for i in range(flat_in.size):
+        flat_out[i] = lib.oracle_half_bits_to_float(int(flat_in[i]))
+    return out
+
+
+def rnn_forward(hidden: int, batch: int, act: str, row_ptr, col_idx, val_bits, x, h0=None,
+                f64: bool = False, threads: int = 1) -> np.ndarray:
+    """All hidden states [T, B, H] of the vanilla cell (Eq. 2); float32, or float64 for the twin."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, hidden, hidden)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T = x.shape[0]
+    if x.shape != (T, batch, hidden):
+        raise ValueError("x must be [T, B, H]")
+    if h0 is not None:
+        h0 = np.ascontiguousarray(h0, dtype=np.float32)
+        if h0.shape != (batch, hidden):
+            raise ValueError("h0 must be [B, H]")
+    out = np.empty((T, batch, hidden), dtype=np.float64 if f64 else np.float32)
+    fn = lib.oracle_rnn_forward_f64 if f64 else lib.oracle_rnn_forward
+    rc = fn(hidden, batch, T, ACT[act], _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+            _ptr(val_bits, ctypes.c_uint16), _ptr(x, ctypes.c_float), _ptr(h0, ctypes.c_float),
+            _ptr(out, ctypes.c_double if f64 else ctypes.c_float), int(threads))
+    if rc != 0:
+        raise RuntimeError("oracle_rnn_forward failed")
+    return out
+
+
+def lstm_forward(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, h0=None, c0=None,
+                 f64: bool = False, threads: int = 1):
+    """(h [T, B, H], c [T, B, H]) of the four-gate LSTM cell; gate row blocks i | f | g | o."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, 4 * hidden, hidden)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T = x.shape[0]
+    if x.shape != (T, batch, 4 * hidden):
+        raise ValueError("x must be [T, B, 4H]")
+    if h0 is not None:
+        h0 = np.ascontiguousarray(h0, dtype=np.float32)
+    if c0 is not None:
+        c0 = np.ascontiguousarray(c0, dtype=np.float32)
+    dt = np.float64 if f64 else np.float32
+    ct = ctypes.c_double if f64 else ctypes.c_float
+    h = np.empty((T, batch, hidden), dtype=dt)
+    c = np.empty((T, batch, hidden), dtype=dt)
+    fn = lib.oracle_lstm_forward_f64 if f64 else lib.oracle_lstm_forward
+    rc = fn(hidden, batch, T, _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+            _ptr(val_bits, ctypes.c_uint16), _ptr(x, ctypes.c_float), _ptr(h0, ctypes.c_float),
+            _ptr(c0, ctypes.c_float), _ptr(h, ct), _ptr(c, ct), int(threads))
+    if rc != 0:
+        raise RuntimeError("oracle_lstm_forward failed")
+    return h, c

@@ -1,0 +1,223 @@
+/*
+ * CPU oracle for the sparse recurrent step.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the plain definition of what the persistent sparse recurrent
+ * kernel must compute, written out slowly and without any blocking, fusion or
+ * reordering.  It shares no code with the HIP path and nothing in the product
+ * may call it; only tests, the smoke check and the benchmark's CPU-baseline leg
+ * use it.
+ *
+ * What it follows:
+ *   - Vanilla cell: Eq. 2 of the paper, h_t = g(U_r h_{t-1} + b'), with b' (the
+ *     input projection plus bias, Section 3.1) handed in as x[t].
+ *   - The method of Sections 3.3 / 4 only re-orders a sparse dot product and
+ *     pads it with zeros, so its result is the plain CSR row dot product; this
+ *     file therefore evaluates each row in CSR order, left to right.
+ *   - LSTM cell: Appendix B says only that every hidden unit has four gate rows
+ *     with different activations; the standard cell without peepholes is used
+ *     (gate row blocks i | f | g | o):
+ *         c_t = sigmoid(p_f) * c_{t-1} + sigmoid(p_i) * tanh(p_g)
+ *         h_t = sigmoid(p_o) * tanh(c_t)
+ *     with p_* = W_* h_{t-1} + x_*[t].
+ *
+ * Precision: weights are IEEE binary16 bit patterns decoded exactly to binary32
+ * (Section 6 names 16-bit weights as the compressed format); activations, the
+ * products and the running sums are binary32 (one rounding per multiply and per
+ * add: build with -ffp-contract=off); activation functions are evaluated with
+ * the C library's single-precision routines.  The *_f64 twins do every
+ * operation in binary64 and keep the state in binary64; they bound the
+ * rounding error of the binary32 versions.
+ *
+ * Pins (tests/test_oracle_pins.py): exhaustive binary16 decode against numpy,
+ * dense special case against a float64 matrix product and against
+ * torch.nn.RNNCell / LSTMCell, identity and permutation closed forms (bit
+ * exact), all-zero weights, exact rational brute force on tiny sizes,
+ * homogeneity / batch-independence / time-composition invariants, and a
+ * hand-worked integer example under tests/golden/.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_ACT_RELU 0
+#define ORACLE_ACT_TANH 1
+#define ORACLE_ACT_IDENTITY 2
+
+/* Exact decode of an IEEE 754 binary16 bit pattern (subnormals, infinities and NaNs included). */
+float oracle_half_bits_to_float(uint16_t h) {
+  const uint32_t sign = (uint32_t)(h >> 15) & 1u;
+  const uint32_t expo = (uint32_t)(h >> 10) & 0x1Fu;
+  const uint32_t frac = (uint32_t)h & 0x3FFu;
+  float mag;
+  if (expo == 0u) {
+    mag = ldexpf((float)frac, -24); /* zero or subnormal: frac * 2^-24 */
+  } else if (expo == 31u) {
+    mag = frac ? NAN : INFINITY;
+  } else {
+    mag = ldexpf((float)(1024u + frac), (int)expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
+  }
+  return sign ? -mag : mag;
+}
+
+static float act_f32(int act, float pre) {
+  switch (act) {
+    case ORACLE_ACT_RELU: return (pre > 0.0f) ? pre : 0.0f;
+    case ORACLE_ACT_TANH: return tanhf(pre);
+    default: return pre;
+  }
+}
+
+static double act_f64(int act, double pre) {
+  switch (act) {
+    case ORACLE_ACT_RELU: return (pre > 0.0) ? pre : 0.0;
+    case ORACLE_ACT_TANH: return tanh(pre);
+    default: return pre;
+  }
+}
+
+static float sigmoid_f32(float z) { return 1.0f / (1.0f + expf(-z)); }
+static double sigmoid_f64(double z) { return 1.0 / (1.0 + exp(-z)); }
+
+/*
+ * Vanilla cell, Eq. 2.  x is [T][B][H], h0 is [B][H] or NULL (zeros), h_out is [T][B][H].
+ * threads > 1 splits the rows of one timestep over OpenMP threads (timesteps stay sequential).
+ * Returns 0, or -1 on a malformed argument.
+ */
+int oracle_rnn_forward(int H, int B, int T, int act, const int32_t* row_ptr, const int32_t* col_idx,
+                       const uint16_t* val_bits, const float* x, const float* h0, float* h_out, int threads) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out) return -1;
+  float* zeros = (float*)calloc((size_t)B * H, sizeof(float));
+  if (!zeros) return -1;
+  for (int t = 0; t < T; ++t) {
+    const float* h_prev = (t == 0) ? (h0 ? h0 : zeros) : h_out + (size_t)(t - 1) * B * H;
+    float* h_cur = h_out + (size_t)t * B * H;
+    const float* x_t = x + (size_t)t * B * H;
+#pragma omp parallel for num_threads(threads) if (threads > 1) schedule(static)
+    for (int i = 0; i < H; ++i) {
+      for (int b = 0; b < B; ++b) {
+        float acc = 0.0f;
+        for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) {
+          const float w = oracle_half_bits_to_float(val_bits[k]);
+          const float prod = w * h_prev[(size_t)b * H + col_idx[k]];
+          acc = acc + prod;
+        }
+        const float pre = acc + x_t[(size_t)b * H + i];
+        h_cur[(size_t)b * H + i] = act_f32(act, pre);
+      }
+    }
+  }
+  free(zeros);
+  return 0;
+}
+
+/* Binary64 twin of oracle_rnn_forward: same inputs, state and outputs in double. */
+int oracle_rnn_forward_f64(int H, int B, int T, int act, const int32_t* row_ptr, const int32_t* col_idx,
+                           const uint16_t* val_bits, const float* x, const float* h0, double* h_out, int threads) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out) return -1;
+  double* first = (double*)calloc((size_t)B * H, sizeof(double));
+  if (!first) return -1;
+  if (h0) for (size_t j = 0; j < (size_t)B * H; ++j) first[j] = (double)h0[j];
+  for (int t = 0; t < T; ++t) {
+    const double* h_prev = (t == 0) ? first : h_out + (size_t)(t - 1) * B * H;
+    double* h_cur = h_out + (size_t)t * B * H;
+    const float* x_t = x + (size_t)t * B * H;
+#pragma omp parallel for num_threads(threads) if (threads > 1) schedule(static)
+    for (int i = 0; i < H; ++i) {
+      for (int b = 0; b < B; ++b) {
+        double acc = 0.0;
+        for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) {
+          acc += (double)oracle_half_bits_to_float(val_bits[k]) * h_prev[(size_t)b * H + col_idx[k]];
+        }
+        h_cur[(size_t)b * H + i] = act_f64(act, acc + (double)x_t[(size_t)b * H + i]);
+      }
+    }
+  }
+  free(first);
+  return 0;
+}
+
+/*
+ * LSTM cell.  W is [4H][H] in CSR with row blocks i | f | g | o; x is [T][B][4H] in the same block
+ * order; h0, c0 are [B][H] or NULL (zeros); h_out, c_out are [T][B][H].
+ */
+int oracle_lstm_forward(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                        const uint16_t* val_bits, const float* x, const float* h0, const float* c0,
+                        float* h_out, float* c_out, int threads) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out || !c_out) return -1;
+  float* zeros = (float*)calloc((size_t)B * H, sizeof(float));
+  if (!zeros) return -1;
+  for (int t = 0; t < T; ++t) {
+    const float* h_prev = (t == 0) ? (h0 ? h0 : zeros) : h_out + (size_t)(t - 1) * B * H;
+    const float* c_prev = (t == 0) ? (c0 ? c0 : zeros) : c_out + (size_t)(t - 1) * B * H;
+    float* h_cur = h_out + (size_t)t * B * H;
+    float* c_cur = c_out + (size_t)t * B * H;
+    const float* x_t = x + (size_t)t * B * 4 * H;
+#pragma omp parallel for num_threads(threads) if (threads > 1) schedule(static)
+    for (int j = 0; j < H; ++j) {
+      for (int b = 0; b < B; ++b) {
+        float p[4];
+        for (int g = 0; g < 4; ++g) {
+          const int row = g * H + j;
+          float acc = 0.0f;
+          for (int32_t k = row_ptr[row]; k < row_ptr[row + 1]; ++k) {
+            const float w = oracle_half_bits_to_float(val_bits[k]);
+            const float prod = w * h_prev[(size_t)b * H + col_idx[k]];
+            acc = acc + prod;
+          }
+          p[g] = acc + x_t[(size_t)b * 4 * H + row];
+        }
+        const float gi = sigmoid_f32(p[0]);
+        const float gf = sigmoid_f32(p[1]);
+        const float gg = tanhf(p[2]);
+        const float go = sigmoid_f32(p[3]);
+        const float keep = gf * c_prev[(size_t)b * H + j];
+        const float add = gi * gg;
+        const float c = keep + add;
+        c_cur[(size_t)b * H + j] = c;
+        h_cur[(size_t)b * H + j] = go * tanhf(c);
+      }
+    }
+  }
+  free(zeros);
+  return 0;
+}
+
+/* Binary64 twin of oracle_lstm_forward. */
+int oracle_lstm_forward_f64(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                            const uint16_t* val_bits, const float* x, const float* h0, const float* c0,
+                            double* h_out, double* c_out, int threads) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out || !c_out) return -1;
+  double* hfirst = (double*)calloc((size_t)B * H, sizeof(double));
+  double* cfirst = (double*)calloc((size_t)B * H, sizeof(double));
+  if (!hfirst || !cfirst) { free(hfirst); free(cfirst); return -1; }
+  if (h0) for (size_t j = 0; j < (size_t)B * H; ++j) hfirst[j] = (double)h0[j];
+  if (c0) for (size_t j = 0; j < (size_t)B * H; ++j) cfirst[j] = (double)c0[j];
+  for (int t = 0; t < T; ++t) {
+    const double* h_prev = (t == 0) ? hfirst : h_out + (size_t)(t - 1) * B * H;
+    const double* c_prev = (t == 0) ? cfirst : c_out + (size_t)(t - 1) * B * H;
+    double* h_cur = h_out + (size_t)t * B * H;
+    double* c_cur = c_out + (size_t)t * B * H;
+    const float* x_t = x + (size_t)t * B * 4 * H;
+#pragma omp parallel for num_threads(threads) if (threads > 1) schedule(static)
+    for (int j = 0; j < H; ++j) {
+      for (int b = 0; b < B; ++b) {
+        double p[4];
+        for (int g = 0; g < 4; ++g) {
+          const int row = g * H + j;
+          double acc = 0.0;
+          for (int32_t k = row_ptr[row]; k < row_ptr[row + 1]; ++k) {
+            acc += (double)oracle_half_bits_to_float(val_bits[k]) * h_prev[(size_t)b * H + col_idx[k]];
+          }
+          p[g] = acc + (double)x_t[(size_t)b * 4 * H + row];
+        }
+        const double c = sigmoid_f64(p[1]) * c_prev[(size_t)b * H + j] + sigmoid_f64(p[0]) * tanh(p[2]);
+        c_cur[(size_t)b * H + j] = c;
+        h_cur[(size_t)b * H + j] = sigmoid_f64(p[3]) * tanh(c);
+      }
+    }
+  }
+  free(hfirst);
+  free(cfirst);
+  return 0;
+}

@@ -1,0 +1,333 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something that is NOT the oracle.
+
+The paper prints no worked numeric example for the recurrent step (Eq. 2), so the oracle is pinned by
+  * a hand-evaluated integer example of Eq. 2 (tests/golden/eq2_hand_example.json),
+  * the dense special case against numpy float64 matmul and torch.nn.RNNCell / LSTMCell,
+  * closed forms: identity matrix (running sum), permutation matrices (bit exact), zero weights,
+  * exact rational brute force on tiny sizes,
+  * invariants: positive homogeneity, batch independence, time composition, fp64 twin bound,
+  * exhaustive binary16 decode against numpy.
+"""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1804_10223_amd import workloads as wl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def f16bits(a):
+    return np.asarray(a, dtype=np.float16).view(np.uint16)
+
+
+def dense_csr(w16):
+    """CSR that stores EVERY entry of the float16 matrix (also zeros), density 1.0."""
+    rows, cols = w16.shape
+    row_ptr = (np.arange(rows + 1) * cols).astype(np.int32)
+    col_idx = np.tile(np.arange(cols, dtype=np.int32), rows)
+    return row_ptr, col_idx, w16.reshape(-1).view(np.uint16).copy()
+
+
+# ----------------------------------------------------------------------------- binary16 decode
+def test_half_decode_exhaustive_matches_numpy():
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.half_bits_to_float(bits)
+    want = bits.view(np.float16).astype(np.float32)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))  # bit exact, incl. -0 and subnormals
+
+
+# ----------------------------------------------------------------------------- hand example (golden)
+def test_golden_hand_example_eq2():
+    with open(os.path.join(HERE, "golden", "eq2_hand_example.json")) as f:
+        g = json.load(f)
+    w16 = np.array(g["U_r"], dtype=np.float16)
+    row_ptr, col_idx, vals = wl.csr_from_dense(w16)
+    x = np.array(g["b_prime"], dtype=np.float32)
+    h0 = np.array(g["h0"], dtype=np.float32)
+    h = oracle.rnn_forward(g["hidden"], g["batch"], "relu", row_ptr, col_idx, vals, x, h0)
+    assert np.array_equal(h, np.array(g["h"], dtype=np.float32))
+
+
+# ----------------------------------------------------------------------------- dense special case
+@pytest.mark.parametrize("act", ["relu", "tanh", "identity"])
+def test_dense_matches_float64_matmul(act):
+    rng = np.random.default_rng(11)
+    H, B, T = 37, 3, 5
+    w16 = (rng.standard_normal((H, H)) / np.sqrt(H)).astype(np.float16)
+    row_ptr, col_idx, vals = dense_csr(w16)
+    x = rng.standard_normal((T, B, H)).astype(np.float32)
+    h0 = rng.standard_normal((B, H)).astype(np.float32)
+    got = oracle.rnn_forward(H, B, act, row_ptr, col_idx, vals, x, h0)
+    W = w16.astype(np.float64)
+    h = h0.astype(np.float64)
+    f = {"relu": lambda z: np.maximum(z, 0.0), "tanh": np.tanh, "identity": lambda z: z}[act]
+    for t in range(T):
+        h = f(h @ W.T + x[t].astype(np.float64))   # row i of W dotted with h: NOT the transpose
+        np.testing.assert_allclose(got[t], h, rtol=0, atol=2e-5 * max(1.0, np.abs(h).max()))
+    # a transposed operand must be far outside that tolerance (the pin is sensitive to it)
+    hT = f(h0.astype(np.float64) @ W + x[0].astype(np.float64))
+    assert np.abs(hT - got[0]).max() > 1e-2
+
+
+def test_dense_matches_torch_rnncell():
+    rng = np.random.default_rng(5)
+    H, B, T = 24, 2, 4
+    w16 = (rng.standard_normal((H, H)) / np.sqrt(H)).astype(np.float16)
+    row_ptr, col_idx, vals = dense_csr(w16)
+    x = rng.standard_normal((T, B, H)).astype(np.float32)
+    h0 = rng.standard_normal((B, H)).astype(np.float32)
+    got = oracle.rnn_forward(H, B, "relu", row_ptr, col_idx, vals, x, h0)
+    cell = torch.nn.RNNCell(H, H, bias=False, nonlinearity="relu").double()
+    with torch.no_grad():
+        cell.weight_hh.copy_(torch.from_numpy(w16.astype(np.float64)))
+        cell.weight_ih.copy_(torch.eye(H, dtype=torch.float64))
+        h = torch.from_numpy(h0.astype(np.float64))
+        for t in range(T):
+            h = cell(torch.from_numpy(x[t].astype(np.float64)), h)
+            np.testing.assert_allclose(got[t], h.numpy(), rtol=0, atol=2e-5)
+
+
+def test_dense_lstm_matches_torch_lstmcell_gate_order_and_equations():
+    rng = np.random.default_rng(6)
+    H, B, T = 19, 3, 4
+    w16 = (rng.standard_normal((4 * H, H)) / np.sqrt(H)).astype(np.float16)
+    row_ptr, col_idx, vals = dense_csr(w16)
+    x = rng.standard_normal((T, B, 4 * H)).astype(np.float32)
+    h0 = rng.standard_normal((B, H)).astype(np.float32)
+    c0 = rng.standard_normal((B, H)).astype(np.float32)
+    gh, gc = oracle.lstm_forward(H, B, row_ptr, col_idx, vals, x, h0, c0)
+    cell = torch.nn.LSTMCell(4 * H, H, bias=False).double()   # gate order i, f, g, o
+    with torch.no_grad():
+        cell.weight_hh.copy_(torch.from_numpy(w16.astype(np.float64)))
+        cell.weight_ih.copy_(torch.eye(4 * H, dtype=torch.float64))
+        h = torch.from_numpy(h0.astype(np.float64))
+        c = torch.from_numpy(c0.astype(np.float64))
+        for t in range(T):
+            h, c = cell(torch.from_numpy(x[t].astype(np.float64)), (h, c))
+            np.testing.assert_allclose(gh[t], h.numpy(), rtol=0, atol=2e-5)
+            np.testing.assert_allclose(gc[t], c.numpy(), rtol=0, atol=2e-5)
+    # swapping two gate blocks must be visible at this tolerance
+    xs = x.copy()
+    xs[:, :, 0:H], xs[:, :, H:2 * H] = x[:, :, H:2 * H], x[:, :, 0:H]
+    sh, _ = oracle.lstm_forward(H, B, row_ptr, col_idx, vals, xs, h0, c0)
+    assert np.abs(sh - gh).max() > 1e-2
+
+
+# ----------------------------------------------------------------------------- closed forms
+def test_identity_matrix_is_running_sum():
+    rng = np.random.default_rng(2)
+    H, B, T = 50, 2, 7
+    row_ptr = np.arange(H + 1, dtype=np.int32)
+    col_idx = np.arange(H, dtype=np.int32)
+    vals = f16bits(np.ones(H))
+    x = rng.integers(0, 5, size=(T, B, H)).astype(np.float32)        # x >= 0: ReLU never clips
+    h0 = rng.integers(0, 5, size=(B, H)).astype(np.float32)
+    got = oracle.rnn_forward(H, B, "relu", row_ptr, col_idx, vals, x, h0)
+    want = h0[None] + np.cumsum(x, axis=0)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("H", [7, 4099, 65535])
+def test_permutation_matrix_moves_values_bit_exactly(H):
+    rng = np.random.default_rng(H)
+    perm = rng.permutation(H).astype(np.int32)          # row i reads column perm[i]
+    row_ptr = np.arange(H + 1, dtype=np.int32)
+    vals = f16bits(np.ones(H))
+    B, T = 2, 3
+    x = np.zeros((T, B, H), dtype=np.float32)
+    h0 = np.abs(rng.standard_normal((B, H))).astype(np.float32)
+    got = oracle.rnn_forward(H, B, "relu", row_ptr, perm, vals, x, h0)
+    cur = h0
+    for t in range(T):
+        cur = cur[:, perm]
+        assert np.array_equal(got[t].view(np.uint32), cur.view(np.uint32))
+
+
+def test_permutation_cycle_returns_to_start():
+    H = 12
+    perm = np.roll(np.arange(H, dtype=np.int32), 1)      # one 12-cycle
+    row_ptr = np.arange(H + 1, dtype=np.int32)
+    x = np.zeros((H, 1, H), dtype=np.float32)
+    h0 = np.arange(1, H + 1, dtype=np.float32)[None]
+    got = oracle.rnn_forward(H, 1, "relu", row_ptr, perm, f16bits(np.ones(H)), x, h0)
+    assert np.array_equal(got[-1], h0)
+    assert not np.array_equal(got[0], h0)
+
+
+@pytest.mark.parametrize("act", ["relu", "tanh", "identity"])
+def test_zero_weights_give_act_of_x(act):
+    rng = np.random.default_rng(3)
+    H, B, T = 33, 2, 3
+    x = rng.standard_normal((T, B, H)).astype(np.float32)
+    h0 = rng.standard_normal((B, H)).astype(np.float32)
+    f = {"relu": lambda z: np.maximum(z, np.float32(0)), "tanh": np.tanh, "identity": lambda z: z}[act]
+    # (a) no stored entries at all, (b) stored zeros
+    empty = (np.zeros(H + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16))
+    stored = dense_csr(np.zeros((H, H), dtype=np.float16))
+    for row_ptr, col_idx, vals in (empty, stored):
+        got = oracle.rnn_forward(H, B, act, row_ptr, col_idx, vals, x, h0)
+        if act == "tanh":
+            np.testing.assert_allclose(got, f(x.astype(np.float64)), rtol=0, atol=1e-6)
+        else:
+            assert np.array_equal(got, f(x))
+
+
+def test_zero_weight_lstm_closed_form():
+    rng = np.random.default_rng(4)
+    H, B, T = 9, 2, 3
+    x = rng.standard_normal((T, B, 4 * H))
+    c0 = rng.standard_normal((B, H))
+    row_ptr = np.zeros(4 * H + 1, dtype=np.int32)
+    gh, gc = oracle.lstm_forward(H, B, row_ptr, np.zeros(0, np.int32), np.zeros(0, np.uint16),
+                                 x.astype(np.float32), None, c0.astype(np.float32))
+    sig = lambda z: 1.0 / (1.0 + np.exp(-z))
+    c = c0.astype(np.float32).astype(np.float64)
+    x = x.astype(np.float32).astype(np.float64)
+    for t in range(T):
+        i, f, g, o = (x[t][:, k * H:(k + 1) * H] for k in range(4))
+        c = sig(f) * c + sig(i) * np.tanh(g)
+        h = sig(o) * np.tanh(c)
+        np.testing.assert_allclose(gc[t], c, rtol=0, atol=1e-6)
+        np.testing.assert_allclose(gh[t], h, rtol=0, atol=1e-6)
+
+
+# ----------------------------------------------------------------------------- exact brute force
+def _brute_force_rnn(W, x, h0, relu):
+    """Eq. 2 in exact rational arithmetic from the dense matrix (pure Python)."""
+    H = len(W)
+    T, B = len(x), len(x[0])
+    h = [[Fraction(v) for v in row] for row in h0]
+    out = []
+    for t in range(T):
+        new = []
+        for b in range(B):
+            row = []
+            for i in range(H):
+                s = sum(Fraction(W[i][j]) * h[b][j] for j in range(H)) + Fraction(x[t][b][i])
+                row.append(max(s, Fraction(0)) if relu else s)
+            new.append(row)
+        h = new
+        out.append(h)
+    return out
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_exact_rational_brute_force_tiny(seed):
+    rng = np.random.default_rng(100 + seed)
+    H = int(rng.integers(1, 9)); B = int(rng.integers(1, 3)); T = int(rng.integers(1, 4))
+    relu = bool(seed % 2 == 0)
+    # dyadic values with few bits: every product and sum is exact in binary32, so equality is bit exact
+    W = (rng.integers(-8, 9, size=(H, H)) / 8.0) * (rng.random((H, H)) < 0.6)
+    x = rng.integers(-16, 17, size=(T, B, H)) / 4.0
+    h0 = rng.integers(-8, 9, size=(B, H)) / 2.0
+    w16 = W.astype(np.float16)
+    assert np.array_equal(w16.astype(np.float64), W)
+    row_ptr, col_idx, vals = wl.csr_from_dense(w16)
+    got = oracle.rnn_forward(H, B, "relu" if relu else "identity", row_ptr, col_idx, vals,
+                             x.astype(np.float32), h0.astype(np.float32))
+    want = _brute_force_rnn(W.tolist(), x.tolist(), h0.tolist(), relu)
+    for t in range(T):
+        for b in range(B):
+            for i in range(H):
+                assert Fraction(float(got[t, b, i])) == want[t][b][i], (t, b, i)
+
+
+# ----------------------------------------------------------------------------- invariants
+def _small_sparse(seed=0, cell="relu", H=96, B=3, T=6, density=0.2):
+    return wl.make_workload("t", cell, H, B, T, density, seed=seed, h0_std=0.5)
+
+
+def test_relu_positive_homogeneity_is_bit_exact():
+    w = _small_sparse(1)
+    a = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0)
+    for k in (-3, 5):
+        s = np.float32(2.0 ** k)
+        b = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x * s, w.h0 * s)
+        assert np.array_equal(b, a * s)
+
+
+def test_batch_columns_are_independent():
+    w = _small_sparse(2)
+    full = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0)
+    for b in range(w.batch):
+        one = oracle.rnn_forward(w.hidden, 1, "relu", w.row_ptr, w.col_idx, w.val_bits,
+                                 w.x[:, b:b + 1].copy(), w.h0[b:b + 1].copy())
+        assert np.array_equal(one[:, 0], full[:, b])
+
+
+def test_time_composition():
+    w = _small_sparse(3, T=9)
+    full = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0)
+    first = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x[:4].copy(), w.h0)
+    second = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x[4:].copy(), first[-1].copy())
+    assert np.array_equal(np.concatenate([first, second]), full)
+
+
+def test_lstm_time_composition_and_batch_independence():
+    w = _small_sparse(4, cell="lstm", H=40, B=2, T=6)
+    h, c = oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, None)
+    h1, c1 = oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x[:2].copy(), w.h0, None)
+    h2, c2 = oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x[2:].copy(), h1[-1].copy(), c1[-1].copy())
+    assert np.array_equal(np.concatenate([h1, h2]), h) and np.array_equal(np.concatenate([c1, c2]), c)
+    hb, cb = oracle.lstm_forward(w.hidden, 1, w.row_ptr, w.col_idx, w.val_bits, w.x[:, 1:2].copy(), w.h0[1:2].copy(), None)
+    assert np.array_equal(hb[:, 0], h[:, 1]) and np.array_equal(cb[:, 0], c[:, 1])
+
+
+@pytest.mark.parametrize("cell", ["relu", "tanh", "lstm"])
+def test_fp64_twin_bounds_fp32_rounding(cell):
+    w = wl.make_workload("t", cell, 256, 2, 12, 0.3, seed=7, h0_std=0.3, gain=0.9 if cell != "lstm" else 1.0)
+    if cell == "lstm":
+        a, ac = oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, None)
+        d, dc = oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, None, f64=True)
+        pairs = [(a, d), (ac, dc)]
+    else:
+        a = oracle.rnn_forward(w.hidden, w.batch, cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0)
+        d = oracle.rnn_forward(w.hidden, w.batch, cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, f64=True)
+        pairs = [(a, d)]
+    for got, ref in pairs:
+        for t in range(w.steps):
+            assert np.abs(got[t] - ref[t]).max() <= 2e-5 * np.abs(ref[t]).max()   # 50x inside the 1e-3 parity bound
+
+
+def test_fp64_twin_on_dense_float64_reference():
+    # the twin itself is pinned against numpy float64 to ~1e-13
+    rng = np.random.default_rng(8)
+    H, B, T = 31, 2, 4
+    w16 = (rng.standard_normal((H, H)) / np.sqrt(H)).astype(np.float16)
+    row_ptr, col_idx, vals = dense_csr(w16)
+    x = rng.standard_normal((T, B, H)).astype(np.float32)
+    got = oracle.rnn_forward(H, B, "tanh", row_ptr, col_idx, vals, x, None, f64=True)
+    h = np.zeros((B, H))
+    for t in range(T):
+        h = np.tanh(h @ w16.astype(np.float64).T + x[t].astype(np.float64))
+        np.testing.assert_allclose(got[t], h, rtol=0, atol=1e-12)
+
+
+def test_openmp_rows_do_not_change_results():
+    w = _small_sparse(9, H=200, T=5)
+    a = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=1)
+    b = oracle.rnn_forward(w.hidden, w.batch, "relu", w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=4)
+    assert np.array_equal(a, b)
+
+
+# ----------------------------------------------------------------------------- generator sanity
+def test_generator_shapes_and_determinism():
+    a = wl.make_config("cfg1")
+    b = wl.make_config("cfg1")
+    assert a.hidden == 256 and a.batch == 1 and a.steps == 16 and a.h0 is None
+    assert np.all(np.diff(a.row_ptr) == 26)
+    assert np.array_equal(a.col_idx, b.col_idx) and np.array_equal(a.val_bits, b.val_bits) and np.array_equal(a.x, b.x)
+    for r in range(a.rows):
+        cols = a.col_idx[a.row_ptr[r]:a.row_ptr[r + 1]]
+        assert np.all(np.diff(cols) > 0) and cols.min() >= 0 and cols.max() < a.hidden
+    l = wl.make_workload("l", "lstm", 16, 2, 3, 0.25, seed=1)
+    assert l.x.shape == (3, 2, 64) and l.row_ptr.shape == (65,)
+    assert abs(float(l.x[:, :, 16:32].mean()) - 1.0) < 0.5      # forget-gate bias folded into b'
