@@ -1,0 +1,166 @@
+/*
+ * sprnn — persistent sparse recurrent step for AMD MI355X (gfx950).
+ *
+ * C ABI of libsprnn.so.  Every function returns an SPRNN_* status code (0 = success, negative =
+ * error); nothing throws or aborts across this boundary.  "host" pointers are ordinary CPU memory,
+ * "device" pointers are HIP device memory on the GPU the handle was created for.  The library never
+ * allocates inside a forward call: all device storage it needs (packed weights, exchange ring,
+ * status word) is allocated by sprnn_create and released by sprnn_destroy.
+ *
+ * What is computed (paper, Section 3.1, Eq. 2):  h_t = g(U_r h_{t-1} + b'_t)  for t = 1..T, with
+ * U_r the pruned recurrent weight matrix held in on-chip storage for the whole sequence
+ * (Section 3.3) and b'_t = W x_t + b computed by the caller ahead of time (Eq. 1 -> Eq. 2).
+ * The LSTM variant (Appendix B, first paragraph) keeps four gate rows per hidden unit.
+ */
+#ifndef SPRNN_H_
+#define SPRNN_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sprnn_handle_s* sprnn_handle_t; /* opaque */
+
+enum {
+  SPRNN_OK = 0,
+  SPRNN_ERR_INVALID = -1,     /* bad argument or malformed CSR                                   */
+  SPRNN_ERR_CAPACITY = -2,    /* weights do not fit on chip, or grid exceeds co-resident capacity */
+  SPRNN_ERR_HIP = -3,         /* a HIP runtime call failed                                        */
+  SPRNN_ERR_UNSUPPORTED = -4, /* batch not in {1,2,4,8}, hidden > 65535, wrong cell for the call  */
+  SPRNN_ERR_STATE = -5        /* a previous forward tripped the spin watchdog; handle unusable    */
+};
+
+/* Cell / activation g of Eq. 2.  SPRNN_CELL_LSTM selects the four-gate cell of Appendix B. */
+enum { SPRNN_ACT_RELU = 0, SPRNN_ACT_TANH = 1, SPRNN_ACT_IDENTITY = 2, SPRNN_CELL_LSTM = 3 };
+
+/* Cross-workgroup hand-off of h_t (Section 4.2 discusses a global barrier versus Lamport timestamps). */
+enum {
+  SPRNN_SYNC_AUTO = 0,
+  SPRNN_SYNC_TAGGED = 1, /* validity travels with the data; consumers spin on it (Lamport-style)  */
+  SPRNN_SYNC_BARRIER = 2 /* one grid-wide barrier per timestep                                     */
+};
+
+/*
+ * Optional tuning knobs for sprnn_create_ex; zero in any field means "choose automatically".
+ * They change only where operands live and in which order they are visited, never the result
+ * (Section 4.1: re-ordering the nonzeros of a row does not affect the final result).
+ */
+typedef struct sprnn_options_s {
+  int grid;          /* number of persistent workgroups (<= co-resident capacity)                  */
+  int waves;         /* wavefronts (64 lanes) per workgroup, 1..16                                 */
+  int lanes_per_row; /* lanes that share one weight row: 1,2,4,...,64 (<= 16 for the LSTM cell)    */
+  int sync;          /* SPRNN_SYNC_*                                                               */
+  int bank_aware;    /* 0 auto, 1 = bank-aware ordering of a row's nonzeros (Section 4.1, App. A),
+                        2 = keep CSR order ("naive")                                               */
+  int balance;       /* 0 auto, 1 = rows dealt to workgroups by nonzero count, 2 = contiguous rows */
+  int poll_delay;    /* back-off before the first poll of a step, in units of 64 clocks; 0 auto,
+                        -1 none                                                                    */
+  int spin_limit;    /* polls before the watchdog gives up (0 = default)                           */
+  int reserved[8];
+} sprnn_options_t;
+
+/* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */
+typedef struct sprnn_info_s {
+  int hidden, rows, batch, cell;
+  int grid, block, waves, lanes_per_row, sync, bank_aware, balance, poll_delay;
+  int words_per_lane_max;   /* largest number of packed nonzeros held by one lane                 */
+  int template_words;       /* register slots per lane of the kernel instantiation in use         */
+  int lds_bytes;            /* LDS bytes per workgroup (two copies of h)                           */
+  int resident_capacity;    /* co-resident workgroups the device can hold for this kernel         */
+  int64_t nnz;              /* nonzeros in the CSR input                                           */
+  int64_t padded_words;     /* packed words including zero padding                                 */
+  int64_t ring_bytes;       /* size of the exchange ring in device memory                          */
+  double lds_pass_factor;   /* LDS passes the packed gathers need / passes of a conflict-free layout
+                               (1.0 = no bank conflicts), from the 64-bank, 256 B-per-pass model     */
+  int reserved[8];
+} sprnn_info_t;
+
+/*
+ * Validate, pack and upload a pruned recurrent matrix (the one-time weight preparation of
+ * Sections 3.3 and 4.1: <index,value> pairs per row, zero padding, bank-aware ordering, all
+ * nonzeros of a lane from one row).
+ *
+ *   hidden      H, 1..65535.
+ *   batch       B in {1,2,4,8}: sequences advanced together (wide loads of Section 4.1).
+ *   activation  SPRNN_ACT_* (R = H rows) or SPRNN_CELL_LSTM (R = 4H rows, row blocks i|f|g|o).
+ *   row_ptr     host, R+1 entries, row_ptr[0] = 0, non-decreasing.
+ *   col_idx     host, nnz = row_ptr[R] entries, 0 <= col < H, strictly increasing inside a row.
+ *   val_fp16_bits host, nnz IEEE binary16 bit patterns (finite).  The library rounds nothing.
+ *   device_id   HIP device ordinal.
+ *
+ * The arrays are copied; the caller may free them on return.  On error *out is NULL.
+ * Empty rows and an all-empty matrix are legal.
+ */
+int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
+                 const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id);
+
+/* Same, with tuning knobs (opt may be NULL). */
+int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
+                    const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
+                    const sprnn_options_t* opt);
+
+/*
+ * Run T timesteps of Eq. 2 with one persistent kernel launch (the load / operate / reduce /
+ * synchronize pipeline of Section 3.3).  Vanilla cells only.
+ *
+ *   x      device, float32 [T][B][H], H fastest: b'_t of Eq. 2.
+ *   h0     device, float32 [B][H], or NULL for zeros.
+ *   h_out  device, float32 [T][B][H]: every h_t; h_out[T-1] is the final state.  A result that
+ *          would be -0.0 is written as +0.0 (Section 4.2 reserves -0.0 as the "not yet written" mark).
+ *   stream hipStream_t cast to void* (NULL = default stream).
+ *
+ * Only enqueues work on `stream` and returns.  One forward per handle at a time, in stream order;
+ * calls on different handles are independent.  T = 0 is a no-op.  All activations must be finite.
+ */
+int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream);
+
+/*
+ * LSTM cell (Appendix B): x is float32 [T][B][4H] with gate blocks i|f|g|o (biases folded in),
+ * c0 / h0 are [B][H] or NULL, h_out and c_out are [T][B][H].
+ *   c_t = sigmoid(p_f) c_{t-1} + sigmoid(p_i) tanh(p_g),  h_t = sigmoid(p_o) tanh(c_t).
+ */
+int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                       float* h_out, float* c_out, void* stream);
+
+/*
+ * Non-persistent comparison path: one kernel launch per timestep that re-reads the CSR weights
+ * from device memory every step (the per-timestep sparse product the paper compares against in
+ * Section 5.2).  Same arguments and results as the persistent calls; c0 / c_out are ignored for
+ * vanilla cells.
+ */
+int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                           float* h_out, float* c_out, void* stream);
+
+/* Describe the mapping chosen at create time. */
+int sprnn_get_info(sprnn_handle_t h, sprnn_info_t* info);
+
+/*
+ * Synchronise with the handle's device and report whether any forward on this handle tripped the
+ * spin watchdog (SPRNN_ERR_STATE) since creation.
+ */
+int sprnn_check(sprnn_handle_t h);
+
+/*
+ * Host-only packing (no GPU needed): run the same validation and weight preparation as
+ * sprnn_create and return the packed image for inspection.
+ *   *words        malloc'ed uint32 [grid][template_words][block]: (LDS byte offset >> shift) << 16 | fp16 bits
+ *   *lane_row     malloc'ed int32 [grid][block]: weight row served by each lane, -1 for an idle lane
+ *   *lane_words   malloc'ed int32 [grid][block]: number of real (non-padding) words in that lane
+ * info receives the mapping.  Free the three arrays with sprnn_free_host.
+ */
+int sprnn_pack_host(int hidden, int batch, int activation, const int32_t* row_ptr, const int32_t* col_idx,
+                    const uint16_t* val_fp16_bits, const sprnn_options_t* opt, int num_cus,
+                    uint32_t** words, int32_t** lane_row, int32_t** lane_words, sprnn_info_t* info);
+void sprnn_free_host(void* p);
+
+const char* sprnn_status_string(int code);
+
+/* Release everything the handle owns.  NULL is a no-op. */
+int sprnn_destroy(sprnn_handle_t h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPRNN_H_ */

@@ -1,0 +1,268 @@
+"""Thin ctypes binding of libsprnn.so: argument marshalling only.
+
+The names mirror the C ABI in ``include/sprnn.h``.  PyTorch is used for device memory and streams;
+every step of the recurrent path runs inside the HIP library.  If the library is missing this module
+raises: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsprnn.so")
+
+SPRNN_OK = 0
+SPRNN_ERR_INVALID = -1
+SPRNN_ERR_CAPACITY = -2
+SPRNN_ERR_HIP = -3
+SPRNN_ERR_UNSUPPORTED = -4
+SPRNN_ERR_STATE = -5
+
+CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3}
+SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
+
+EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_stepwise",
+           "sprnn_get_info", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
+           "sprnn_destroy"]
+
+
+class Options(ctypes.Structure):
+    _fields_ = [("grid", ctypes.c_int), ("waves", ctypes.c_int), ("lanes_per_row", ctypes.c_int),
+                ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
+                ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("reserved", ctypes.c_int * 8)]
+
+
+class Info(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int), ("rows", ctypes.c_int), ("batch", ctypes.c_int), ("cell", ctypes.c_int),
+                ("grid", ctypes.c_int), ("block", ctypes.c_int), ("waves", ctypes.c_int),
+                ("lanes_per_row", ctypes.c_int), ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int),
+                ("balance", ctypes.c_int), ("poll_delay", ctypes.c_int),
+                ("words_per_lane_max", ctypes.c_int), ("template_words", ctypes.c_int),
+                ("lds_bytes", ctypes.c_int), ("resident_capacity", ctypes.c_int),
+                ("nnz", ctypes.c_int64), ("padded_words", ctypes.c_int64), ("ring_bytes", ctypes.c_int64),
+                ("lds_pass_factor", ctypes.c_double), ("reserved", ctypes.c_int * 8)]
+
+    def as_dict(self) -> dict:
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
+class SprnnError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (what, status_string(code), code))
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libsprnn.so from the package directory; fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libsprnn.so is missing: build it with `python -m paper_1804_10223_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    i32p, u16p, u32pp, i32pp = (ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint16),
+                                ctypes.POINTER(ctypes.POINTER(ctypes.c_uint32)),
+                                ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)))
+    lib.sprnn_create.restype = ci
+    lib.sprnn_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, i32p, i32p, u16p, ci]
+    lib.sprnn_create_ex.restype = ci
+    lib.sprnn_create_ex.argtypes = [ctypes.POINTER(vp), ci, ci, ci, i32p, i32p, u16p, ci, ctypes.POINTER(Options)]
+    lib.sprnn_forward.restype = ci
+    lib.sprnn_forward.argtypes = [vp, ci, vp, vp, vp, vp]
+    lib.sprnn_forward_lstm.restype = ci
+    lib.sprnn_forward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_forward_stepwise.restype = ci
+    lib.sprnn_forward_stepwise.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_get_info.restype = ci
+    lib.sprnn_get_info.argtypes = [vp, ctypes.POINTER(Info)]
+    lib.sprnn_check.restype = ci
+    lib.sprnn_check.argtypes = [vp]
+    lib.sprnn_pack_host.restype = ci
+    lib.sprnn_pack_host.argtypes = [ci, ci, ci, i32p, i32p, u16p, ctypes.POINTER(Options), ci, u32pp, i32pp, i32pp,
+                                    ctypes.POINTER(Info)]
+    lib.sprnn_free_host.restype = None
+    lib.sprnn_free_host.argtypes = [vp]
+    lib.sprnn_status_string.restype = ctypes.c_char_p
+    lib.sprnn_status_string.argtypes = [ci]
+    lib.sprnn_destroy.restype = ci
+    lib.sprnn_destroy.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().sprnn_status_string(int(code)).decode()
+
+
+def make_options(**kw) -> Options:
+    o = Options()
+    for k, v in kw.items():
+        if k == "sync" and isinstance(v, str):
+            v = SYNC[v]
+        if not hasattr(o, k):
+            raise TypeError("unknown option %r" % k)
+        setattr(o, k, int(v))
+    return o
+
+
+def _csr_args(row_ptr, col_idx, val_bits):
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    val_bits = np.ascontiguousarray(val_bits, dtype=np.uint16)
+    keep = (row_ptr, col_idx, val_bits)
+    i32p, u16p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint16)
+    cp = col_idx.ctypes.data_as(i32p) if col_idx.size else ctypes.cast(None, i32p)
+    vp = val_bits.ctypes.data_as(u16p) if val_bits.size else ctypes.cast(None, u16p)
+    return keep, row_ptr.ctypes.data_as(i32p), cp, vp
+
+
+def pack_host(hidden: int, batch: int, cell: str, row_ptr, col_idx, val_bits, num_cus: int = 256, **options):
+    """sprnn_pack_host: the packed register image as numpy arrays (no GPU needed).
+
+    Returns (words [grid, template_words, block] uint32, lane_row [grid, block] int32,
+    lane_words [grid, block] int32, info dict).
+    """
+    lib = load_library()
+    keep, rp, cp, vp = _csr_args(row_ptr, col_idx, val_bits)
+    opt = make_options(**options)
+    words = ctypes.POINTER(ctypes.c_uint32)()
+    lane_row = ctypes.POINTER(ctypes.c_int32)()
+    lane_words = ctypes.POINTER(ctypes.c_int32)()
+    info = Info()
+    rc = lib.sprnn_pack_host(hidden, batch, CELLS[cell], rp, cp, vp, ctypes.byref(opt), num_cus,
+                             ctypes.byref(words), ctypes.byref(lane_row), ctypes.byref(lane_words), ctypes.byref(info))
+    if rc != SPRNN_OK:
+        raise SprnnError(rc, "sprnn_pack_host")
+    try:
+        g, nw, blk = info.grid, info.template_words, info.block
+        w = np.ctypeslib.as_array(words, shape=(g, nw, blk)).copy()
+        lr = np.ctypeslib.as_array(lane_row, shape=(g, blk)).copy()
+        lw = np.ctypeslib.as_array(lane_words, shape=(g, blk)).copy()
+    finally:
+        lib.sprnn_free_host(ctypes.cast(words, ctypes.c_void_p))
+        lib.sprnn_free_host(ctypes.cast(lane_row, ctypes.c_void_p))
+        lib.sprnn_free_host(ctypes.cast(lane_words, ctypes.c_void_p))
+    return w, lr, lw, info.as_dict()
+
+
+def _dev_ptr(t, shape, what):
+    import torch
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous float32 CUDA tensor" % what)
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (what, tuple(shape), tuple(t.shape)))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class SparseRNN:
+    """Owner of one sprnn handle.  ``cell`` is "relu" | "tanh" | "identity" | "lstm"."""
+
+    def __init__(self, hidden: int, batch: int, cell: str, row_ptr, col_idx, val_bits, device: int = 0, **options):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        self.hidden, self.batch, self.cell = int(hidden), int(batch), cell
+        self.rows = self.hidden * (4 if cell == "lstm" else 1)
+        self.device = int(device)
+        keep, rp, cp, vp = _csr_args(row_ptr, col_idx, val_bits)
+        opt = make_options(**options)
+        rc = self._lib.sprnn_create_ex(ctypes.byref(self._h), self.hidden, self.batch, CELLS[cell], rp, cp, vp,
+                                       self.device, ctypes.byref(opt))
+        if rc != SPRNN_OK:
+            self._h = ctypes.c_void_p()
+            raise SprnnError(rc, "sprnn_create_ex")
+
+    # -- life cycle
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.sprnn_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # -- queries
+    def info(self) -> dict:
+        i = Info()
+        rc = self._lib.sprnn_get_info(self._h, ctypes.byref(i))
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_get_info")
+        return i.as_dict()
+
+    def check(self) -> int:
+        """sprnn_check: synchronise and return the status code (SPRNN_OK or SPRNN_ERR_STATE)."""
+        return int(self._lib.sprnn_check(self._h))
+
+    # -- forward passes (enqueue on torch's current stream of the handle's device)
+    def _stream(self):
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _alloc(self, T):
+        import torch
+        return torch.empty((T, self.batch, self.hidden), dtype=torch.float32, device="cuda:%d" % self.device)
+
+    def forward(self, x, h0=None, h_out=None):
+        """sprnn_forward: x [T, B, H] -> h_out [T, B, H] (vanilla cells)."""
+        T = int(x.shape[0])
+        if h_out is None:
+            h_out = self._alloc(T)
+        rc = self._lib.sprnn_forward(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
+                                     _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                     _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_forward")
+        return h_out
+
+    def forward_lstm(self, x, h0=None, c0=None, h_out=None, c_out=None):
+        """sprnn_forward_lstm: x [T, B, 4H] -> (h_out, c_out), each [T, B, H]."""
+        T = int(x.shape[0])
+        if h_out is None:
+            h_out = self._alloc(T)
+        if c_out is None:
+            c_out = self._alloc(T)
+        rc = self._lib.sprnn_forward_lstm(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
+                                          _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                          _dev_ptr(c0, (self.batch, self.hidden), "c0"),
+                                          _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"),
+                                          _dev_ptr(c_out, (T, self.batch, self.hidden), "c_out"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_forward_lstm")
+        return h_out, c_out
+
+    def forward_stepwise(self, x, h0=None, c0=None, h_out=None, c_out=None):
+        """sprnn_forward_stepwise: the one-launch-per-timestep comparison path; returns (h_out, c_out or None)."""
+        T = int(x.shape[0])
+        lstm = self.cell == "lstm"
+        if h_out is None:
+            h_out = self._alloc(T)
+        if lstm and c_out is None:
+            c_out = self._alloc(T)
+        rc = self._lib.sprnn_forward_stepwise(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
+                                              _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                              _dev_ptr(c0, (self.batch, self.hidden), "c0") if lstm else None,
+                                              _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"),
+                                              _dev_ptr(c_out, (T, self.batch, self.hidden), "c_out") if lstm else None,
+                                              self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_forward_stepwise")
+        return h_out, c_out

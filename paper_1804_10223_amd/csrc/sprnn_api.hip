@@ -1,0 +1,304 @@
+// C ABI of libsprnn (see include/sprnn.h): handle life cycle, launches, host-only packing entry point.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "sprnn.h"
+#include "sprnn_device.h"
+#include "sprnn_pack.h"
+
+using namespace sprnn;
+
+struct sprnn_handle_s {
+  Mapping map;
+  int device = 0;
+  int num_cus = 0;
+  int capacity = 0;
+  int launch_lds = 0;            // dynamic LDS requested at launch (>= map.lds_bytes; large enough for one workgroup per CU)
+  double pass_factor = 1.0;
+  const void* kernel = nullptr;
+  uint32_t* d_words = nullptr;
+  int32_t* d_lane_row = nullptr;
+  int32_t* d_wave_words = nullptr;
+  uint32_t* d_ring = nullptr;
+  uint32_t* d_ctrl = nullptr;
+  int32_t* d_row_ptr = nullptr;
+  int32_t* d_col = nullptr;
+  uint16_t* d_val = nullptr;
+  uint32_t step_base = 0;        // global step index at which the next forward starts
+  uint32_t barrier_base = 0;     // barrier arrivals so far (grid-barrier mode)
+  bool poisoned = false;         // a watchdog trip was observed: the ring no longer holds a consistent state
+};
+
+namespace {
+
+// With SPRNN_DEBUG set in the environment, a failing HIP call is named on stderr.
+bool hip_ok(hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  static const bool verbose = std::getenv("SPRNN_DEBUG") != nullptr;
+  if (verbose) std::fprintf(stderr, "sprnn: %s failed: %s\n", what, hipGetErrorString(e));
+  (void)hipGetLastError();
+  return false;
+}
+#define SPRNN_HIP(call) hip_ok((call), #call)
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (!SPRNN_HIP(hipGetDevice(&prev))) return;
+    ok = (prev == dev) || SPRNN_HIP(hipSetDevice(dev));
+    if (prev == dev) prev = -1;
+  }
+  ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+void fill_info(const Mapping& m, int capacity, double pass_factor, sprnn_info_t* info) {
+  std::memset(info, 0, sizeof(*info));
+  info->hidden = m.hidden; info->rows = m.rows; info->batch = m.batch; info->cell = m.cell;
+  info->grid = m.grid; info->block = m.block; info->waves = m.waves; info->lanes_per_row = m.lanes_per_row;
+  info->sync = m.sync; info->bank_aware = m.bank_aware; info->balance = m.balance; info->poll_delay = m.poll_delay;
+  info->words_per_lane_max = m.words_max; info->template_words = m.template_words; info->lds_bytes = m.lds_bytes;
+  info->resident_capacity = capacity;
+  info->nnz = m.nnz; info->padded_words = m.padded_words;
+  info->ring_bytes = (int64_t)kRingSlots * m.h_bytes;
+  info->lds_pass_factor = pass_factor;
+}
+
+template <typename T>
+hipError_t upload(T** dst, const T* src, size_t n) {
+  *dst = nullptr;
+  hipError_t e = hipMalloc((void**)dst, std::max<size_t>(n, 1) * sizeof(T));
+  if (e != hipSuccess) return e;
+  if (n) e = hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice);
+  return e;
+}
+
+void release(sprnn_handle_s* h) {
+  if (!h) return;
+  (void)hipFree(h->d_words); (void)hipFree(h->d_lane_row); (void)hipFree(h->d_wave_words);
+  (void)hipFree(h->d_ring); (void)hipFree(h->d_ctrl);
+  (void)hipFree(h->d_row_ptr); (void)hipFree(h->d_col); (void)hipFree(h->d_val);
+  delete h;
+}
+
+// The default back-off before a step's first poll: polling a line before its producer has written it
+// costs a second miss once the write lands, so waiting roughly one store-to-visibility time first is
+// faster (in units of s_sleep(1) = 64 clocks).
+int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 12 : 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* sprnn_status_string(int code) {
+  switch (code) {
+    case SPRNN_OK: return "ok";
+    case SPRNN_ERR_INVALID: return "invalid argument or malformed CSR";
+    case SPRNN_ERR_CAPACITY: return "does not fit on chip or grid exceeds co-resident capacity";
+    case SPRNN_ERR_HIP: return "HIP runtime call failed";
+    case SPRNN_ERR_UNSUPPORTED: return "unsupported batch, hidden size or cell for this call";
+    case SPRNN_ERR_STATE: return "spin watchdog tripped; handle unusable";
+    default: return "unknown status";
+  }
+}
+
+void sprnn_free_host(void* p) { std::free(p); }
+
+int sprnn_pack_host(int hidden, int batch, int activation, const int32_t* row_ptr, const int32_t* col_idx,
+                    const uint16_t* val_fp16_bits, const sprnn_options_t* opt, int num_cus,
+                    uint32_t** words, int32_t** lane_row, int32_t** lane_words, sprnn_info_t* info) {
+  if (!words || !lane_row || !lane_words || !info) return SPRNN_ERR_INVALID;
+  *words = nullptr; *lane_row = nullptr; *lane_words = nullptr;
+  Packed P;
+  int rc;
+  try {
+    rc = pack(hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, opt, num_cus, &P);
+  } catch (const std::bad_alloc&) {
+    return SPRNN_ERR_CAPACITY;
+  }
+  if (rc != SPRNN_OK) return rc;
+  auto dup = [](const void* src, size_t bytes) -> void* {
+    void* p = std::malloc(std::max<size_t>(bytes, 1));
+    if (p && bytes) std::memcpy(p, src, bytes);
+    return p;
+  };
+  *words = (uint32_t*)dup(P.words.data(), P.words.size() * 4);
+  *lane_row = (int32_t*)dup(P.lane_row.data(), P.lane_row.size() * 4);
+  *lane_words = (int32_t*)dup(P.lane_words.data(), P.lane_words.size() * 4);
+  if (!*words || !*lane_row || !*lane_words) {
+    std::free(*words); std::free(*lane_row); std::free(*lane_words);
+    *words = nullptr; *lane_row = nullptr; *lane_words = nullptr;
+    return SPRNN_ERR_CAPACITY;
+  }
+  if (P.map.poll_delay == 0) P.map.poll_delay = default_poll_delay(P.map);
+  fill_info(P.map, 0, lds_pass_factor(P), info);
+  return SPRNN_OK;
+}
+
+int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
+                    const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
+                    const sprnn_options_t* opt) {
+  if (!out) return SPRNN_ERR_INVALID;
+  *out = nullptr;
+  int ndev = 0;
+  if (!SPRNN_HIP(hipGetDeviceCount(&ndev))) return SPRNN_ERR_HIP;
+  if (device_id < 0 || device_id >= ndev) return SPRNN_ERR_INVALID;
+  DeviceGuard guard(device_id);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  hipDeviceProp_t prop;
+  if (!SPRNN_HIP(hipGetDeviceProperties(&prop, device_id))) return SPRNN_ERR_HIP;
+  if (!prop.cooperativeLaunch) return SPRNN_ERR_UNSUPPORTED;
+
+  Packed P;
+  int rc;
+  try {
+    rc = pack(hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, opt, prop.multiProcessorCount, &P);
+  } catch (const std::bad_alloc&) {
+    return SPRNN_ERR_CAPACITY;
+  }
+  if (rc != SPRNN_OK) return rc;
+
+  sprnn_handle_s* h = new (std::nothrow) sprnn_handle_s;
+  if (!h) return SPRNN_ERR_CAPACITY;
+  h->map = P.map;
+  if (h->map.poll_delay == 0) h->map.poll_delay = default_poll_delay(h->map);
+  if (h->map.poll_delay < 0) h->map.poll_delay = 0;
+  h->device = device_id;
+  h->num_cus = prop.multiProcessorCount;
+  h->pass_factor = lds_pass_factor(P);
+  const Mapping& m = h->map;
+  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell == SPRNN_CELL_LSTM);
+  if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
+
+  // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
+  // (sharedMemPerMultiprocessor is not used: some runtime versions report the whole chip's LDS there.)
+  const int lds_cu = prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin : (int)prop.sharedMemPerBlock;
+  const int lds_need = m.lds_bytes + kLdsTailBytes;      // two copies of h + the abort flags
+  h->launch_lds = std::max(lds_need, lds_cu / 2 + 1024);
+  if (h->launch_lds > lds_cu) { release(h); return SPRNN_ERR_CAPACITY; }
+  if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
+  int per_cu = 0;
+  if (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, h->kernel, m.block, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
+  h->capacity = per_cu * h->num_cus;
+  if (m.grid > h->capacity) { release(h); return SPRNN_ERR_CAPACITY; }   // a spinning grid that is not co-resident would deadlock
+
+  const size_t ring_words = (size_t)kRingSlots * m.h_bytes / 4;
+  std::vector<uint32_t> ring(ring_words, kSentinel);
+  {
+    // bytes of a slot beyond the last element of h are never written by a producer: mark them as present
+    const size_t used = (size_t)m.hidden * m.batch;   // 32-bit elements (both planes for batch 8)
+    for (int s = 0; s < kRingSlots; ++s)
+      for (size_t i = used; i < (size_t)m.h_bytes / 4; ++i) ring[(size_t)s * m.h_bytes / 4 + i] = 0u;
+  }
+  std::vector<uint32_t> ctrl(kCtrlWords, 0u);
+  const int rows = m.rows;
+  bool ok = SPRNN_HIP(upload(&h->d_words, P.words.data(), P.words.size())) &&
+            SPRNN_HIP(upload(&h->d_lane_row, P.lane_row.data(), P.lane_row.size())) &&
+            SPRNN_HIP(upload(&h->d_wave_words, P.wave_words.data(), P.wave_words.size())) &&
+            SPRNN_HIP(upload(&h->d_ring, ring.data(), ring.size())) &&
+            SPRNN_HIP(upload(&h->d_ctrl, ctrl.data(), ctrl.size())) &&
+            SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
+            SPRNN_HIP(upload(&h->d_col, col_idx, (size_t)m.nnz)) &&
+            SPRNN_HIP(upload(&h->d_val, val_fp16_bits, (size_t)m.nnz));
+  if (!ok || !SPRNN_HIP(hipDeviceSynchronize())) { release(h); return SPRNN_ERR_HIP; }
+  *out = h;
+  return SPRNN_OK;
+}
+
+int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
+                 const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id) {
+  return sprnn_create_ex(out, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, nullptr);
+}
+
+static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                              float* h_out, float* c_out, void* stream) {
+  if (h->poisoned) return SPRNN_ERR_STATE;
+  if (T == 0) return SPRNN_OK;
+  DeviceGuard guard(h->device);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  const Mapping& m = h->map;
+  KernelArgs a;
+  a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
+  a.ring = h->d_ring; a.ctrl = h->d_ctrl;
+  a.x = x; a.h0 = h0; a.c0 = c0; a.h_out = h_out; a.c_out = c_out;
+  a.hidden = m.hidden; a.T = T; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
+  a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
+  a.step_base = h->step_base; a.barrier_base = h->barrier_base;
+  void* args[] = {&a};
+  hipError_t e = hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+  if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
+  h->step_base += (uint32_t)T;
+  h->barrier_base += (uint32_t)(T - 1) * (uint32_t)m.grid;
+  return SPRNN_OK;
+}
+
+int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell == SPRNN_CELL_LSTM) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
+  return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream);
+}
+
+int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                       float* h_out, float* c_out, void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_LSTM) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!x || !h_out || !c_out)) return SPRNN_ERR_INVALID;
+  return forward_persistent(h, T, x, h0, c0, h_out, c_out, stream);
+}
+
+int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                           float* h_out, float* c_out, void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  const Mapping& m = h->map;
+  const bool lstm = m.cell == SPRNN_CELL_LSTM;
+  if (T > 0 && (!x || !h_out || (lstm && !c_out))) return SPRNN_ERR_INVALID;
+  DeviceGuard guard(h->device);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  const size_t hb = (size_t)m.batch * m.hidden, xb = (size_t)m.batch * m.rows;
+  for (int t = 0; t < T; ++t) {
+    StepArgs a;
+    a.row_ptr = h->d_row_ptr; a.col = h->d_col; a.val = h->d_val;
+    a.x_t = x + (size_t)t * xb;
+    a.h_prev = t ? h_out + (size_t)(t - 1) * hb : h0;
+    a.c_prev = lstm ? (t ? c_out + (size_t)(t - 1) * hb : c0) : nullptr;
+    a.h_cur = h_out + (size_t)t * hb;
+    a.c_cur = lstm ? c_out + (size_t)t * hb : nullptr;
+    a.hidden = m.hidden; a.act = m.cell;
+    if (launch_stepwise(m.batch, lstm, a, (hipStream_t)stream) != hipSuccess) return SPRNN_ERR_HIP;
+  }
+  return SPRNN_OK;
+}
+
+int sprnn_get_info(sprnn_handle_t h, sprnn_info_t* info) {
+  if (!h || !info) return SPRNN_ERR_INVALID;
+  fill_info(h->map, h->capacity, h->pass_factor, info);
+  return SPRNN_OK;
+}
+
+int sprnn_check(sprnn_handle_t h) {
+  if (!h) return SPRNN_ERR_INVALID;
+  DeviceGuard guard(h->device);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  if (hipDeviceSynchronize() != hipSuccess) return SPRNN_ERR_HIP;
+  uint32_t status = 0;
+  if (hipMemcpy(&status, h->d_ctrl + kCtrlStatus, 4, hipMemcpyDeviceToHost) != hipSuccess) return SPRNN_ERR_HIP;
+  if (status) h->poisoned = true;
+  return status ? SPRNN_ERR_STATE : SPRNN_OK;
+}
+
+int sprnn_destroy(sprnn_handle_t h) {
+  if (!h) return SPRNN_OK;
+  DeviceGuard guard(h->device);
+  if (guard.ok) (void)hipDeviceSynchronize();
+  release(h);
+  return SPRNN_OK;
+}
+
+}  // extern "C"

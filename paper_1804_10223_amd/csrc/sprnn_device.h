@@ -1,0 +1,53 @@
+// Declarations shared by the device code (sprnn_kernels.hip) and the C ABI (sprnn_api.hip).
+#ifndef SPRNN_DEVICE_H_
+#define SPRNN_DEVICE_H_
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "sprnn.h"
+
+namespace sprnn {
+
+constexpr int kRingSlotsDev = 4;                  // exchange ring depth (power of two)
+constexpr uint32_t kSentinelBits = 0x80000000u;   // -0.0f marks a ring element that is not written yet
+constexpr int kCtrlStatus = 0;                    // ctrl[0]: non-zero once a spin watchdog tripped
+constexpr int kCtrlBarrier = 32;                  // ctrl[32]: arrival counter of the grid-barrier mode (own cache line)
+constexpr int kCtrlWords = 64;
+constexpr int kLdsTailBytes = 16;                 // LDS after the two copies of h: the workgroup's abort flags
+
+struct KernelArgs {
+  const uint32_t* words;      // [grid][NW][block] packed <index,value> words
+  const int32_t* lane_row;    // [grid][block]
+  const int32_t* wave_words;  // [grid][waves]
+  uint32_t* ring;             // [4][h_bytes / 4]
+  uint32_t* ctrl;             // [kCtrlWords]
+  const float* x;             // [T][B][R]
+  const float* h0;            // [B][H] or null
+  const float* c0;            // [B][H] or null (LSTM)
+  float* h_out;               // [T][B][H]
+  float* c_out;               // [T][B][H] (LSTM)
+  int hidden, T, lanes_per_row, act, h_bytes, poll_delay, spin_limit, sync;
+  uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
+  uint32_t barrier_base;      // barrier arrivals before this call
+};
+
+struct StepArgs {
+  const int32_t* row_ptr;
+  const int32_t* col;
+  const uint16_t* val;
+  const float* x_t;     // [B][R]
+  const float* h_prev;  // [B][H] or null
+  const float* c_prev;  // [B][H] or null
+  float* h_cur;         // [B][H]
+  float* c_cur;         // [B][H]
+  int hidden, act;
+};
+
+const void* persistent_kernel_for(int batch, int template_words, bool lstm);
+hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream);
+hipError_t launch_fill(uint32_t* dst, uint32_t value, size_t n, hipStream_t stream);
+
+}  // namespace sprnn
+#endif

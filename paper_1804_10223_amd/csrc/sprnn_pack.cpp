@@ -1,0 +1,390 @@
+// Host-side weight preparation: CSR -> per-lane register image (see sprnn_pack.h).
+#include "sprnn_pack.h"
+
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+
+namespace sprnn {
+
+static inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+static inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int validate_csr(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
+                 const uint16_t* val_bits) {
+  if (hidden < 1) return SPRNN_ERR_INVALID;
+  if (hidden > 65535) return SPRNN_ERR_UNSUPPORTED;
+  if (!(batch == 1 || batch == 2 || batch == 4 || batch == 8)) return SPRNN_ERR_UNSUPPORTED;
+  if (cell < SPRNN_ACT_RELU || cell > SPRNN_CELL_LSTM) return SPRNN_ERR_INVALID;
+  if (!row_ptr) return SPRNN_ERR_INVALID;
+  const int rows = hidden * (cell == SPRNN_CELL_LSTM ? 4 : 1);
+  if (row_ptr[0] != 0) return SPRNN_ERR_INVALID;
+  for (int r = 0; r < rows; ++r) {
+    if (row_ptr[r + 1] < row_ptr[r]) return SPRNN_ERR_INVALID;
+    if (row_ptr[r + 1] - row_ptr[r] > hidden) return SPRNN_ERR_INVALID;
+  }
+  const int64_t nnz = row_ptr[rows];
+  if (nnz > 0 && (!col_idx || !val_bits)) return SPRNN_ERR_INVALID;
+  for (int r = 0; r < rows; ++r) {
+    int32_t prev = -1;
+    for (int32_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {
+      const int32_t c = col_idx[k];
+      if (c <= prev || c >= hidden) return SPRNN_ERR_INVALID;  // in range, strictly increasing, no duplicates
+      prev = c;
+      if ((val_bits[k] & 0x7C00u) == 0x7C00u) return SPRNN_ERR_INVALID;  // inf / NaN weight
+    }
+  }
+  return SPRNN_OK;
+}
+
+// Lanes that one LDS pass serves together, and the number of bank groups a gather of this width can
+// hit, on gfx950: 64 banks x 4 B = 256 B per pass, so a 16-byte gather serves 16 lanes per pass over 16
+// groups, an 8-byte gather 32 over 32, a 4-byte gather 64 over 64.
+static int pass_lanes(int batch) { return batch >= 4 ? 16 : (batch == 2 ? 32 : 64); }
+
+static int choose_mapping(int hidden, int batch, int cell, const std::vector<int>& row_nnz, const sprnn_options_t* opt,
+                          int num_cus, Mapping* m) {
+  const bool lstm = cell == SPRNN_CELL_LSTM;
+  const int rows = hidden * (lstm ? 4 : 1);
+  const int lmax = lstm ? 16 : kWave;
+  int maxnnz = 1;
+  int64_t nnz = 0;
+  for (int r = 0; r < rows; ++r) { maxnnz = std::max(maxnnz, row_nnz[r]); nnz += row_nnz[r]; }
+  if (num_cus < 1) return SPRNN_ERR_INVALID;
+
+  auto total_waves = [&](int L) {
+    const int groups_per_wave = kWave / L;
+    const int units_per_wave = lstm ? groups_per_wave / 4 : groups_per_wave;
+    return ceil_div(hidden, units_per_wave);   // a unit is one row (vanilla) or one hidden unit's 4 gate rows
+  };
+
+  int L = opt ? opt->lanes_per_row : 0;
+  if (L != 0) {
+    if (!is_pow2(L) || L > lmax) return SPRNN_ERR_INVALID;
+  } else {
+    L = lmax;
+    while (L > 1 && ceil_div(maxnnz, L) < 8) L /= 2;
+    while (L > 1 && total_waves(L) > (int64_t)kMaxWaves * num_cus) L /= 2;
+    while (L < lmax && ceil_div(maxnnz, L) > kTemplateWords[kNumTemplateWords - 1]) L *= 2;
+  }
+  const int need = ceil_div(maxnnz, L);
+  if (need > kTemplateWords[kNumTemplateWords - 1]) return SPRNN_ERR_CAPACITY;
+  int tw = 0;
+  for (int i = 0; i < kNumTemplateWords; ++i) if (kTemplateWords[i] >= need) { tw = kTemplateWords[i]; break; }
+
+  const int wt = total_waves(L);
+  const int wave_cap = tw >= 48 ? 8 : kMaxWaves;   // the 48/64-slot kernels are built for at most 512 threads
+  int waves = opt ? opt->waves : 0;
+  int grid = opt ? opt->grid : 0;
+  if (waves < 0 || waves > kMaxWaves || grid < 0) return SPRNN_ERR_INVALID;
+  if (grid && !waves) waves = ceil_div(wt, grid);
+  if (!waves) waves = std::min(wave_cap, std::max(ceil_div(wt, num_cus), std::min(8, wt)));
+  if (waves > wave_cap) return SPRNN_ERR_CAPACITY;
+  if (!grid) grid = ceil_div(wt, waves);
+  if ((int64_t)grid * waves < wt) return SPRNN_ERR_CAPACITY;
+
+  m->hidden = hidden; m->rows = rows; m->batch = batch; m->cell = cell;
+  m->grid = grid; m->waves = waves; m->block = waves * kWave; m->lanes_per_row = L;
+  m->template_words = tw;
+  m->col_stride = 4 * std::min(batch, 4);
+  const int64_t plane = (int64_t)hidden * m->col_stride;          // batch 8 keeps two planes of 4 samples
+  const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
+  if (2 * hb + 16 > kLdsLimit) return SPRNN_ERR_CAPACITY;   // two copies of h and 16 bytes of flags
+  m->h_bytes = (int)hb;
+  m->lds_bytes = (int)(2 * hb);
+  int shift = 0;
+  if (plane > 65536) { while ((1 << shift) < m->col_stride) ++shift; }
+  m->index_shift = shift;
+  m->nnz = nnz;
+  m->sync = (opt && opt->sync) ? opt->sync : SPRNN_SYNC_TAGGED;
+  if (m->sync != SPRNN_SYNC_TAGGED && m->sync != SPRNN_SYNC_BARRIER) return SPRNN_ERR_INVALID;
+  m->bank_aware = (opt && opt->bank_aware) ? opt->bank_aware : 1;
+  if (m->bank_aware != 1 && m->bank_aware != 2) return SPRNN_ERR_INVALID;
+  int balance = opt ? opt->balance : 0;
+  if (balance < 0 || balance > 2) return SPRNN_ERR_INVALID;
+  if (balance == 0) balance = ((int64_t)maxnnz * rows > nnz + nnz / 16 + rows) ? 1 : 2;  // >~6 % spread: deal by nonzero count
+  m->balance = balance;
+  m->poll_delay = opt ? opt->poll_delay : 0;
+  m->spin_limit = (opt && opt->spin_limit > 0) ? opt->spin_limit : (1 << 22);
+  return SPRNN_OK;
+}
+
+namespace {
+struct Nz { int32_t col; uint16_t bits; };
+}
+
+struct RowGroup {
+  int lane0 = 0;              // first lane of the group inside the wavefront
+  int row = -1;               // weight row, -1 for an idle group
+  std::vector<Nz> items;      // the row's nonzeros in CSR order
+  std::vector<int> pos;       // [trip * L] position k * L + l -> index into items, -1 = filler
+};
+
+// Place the nonzeros of all rows of one wavefront into their lanes' register slots.
+//
+// Bank-aware ordering (Section 4.1; Appendix A gives one greedy way for 32 banks, this is another for the
+// same goal on this LDS).  All the hardware cares about is which columns are read together in one LDS pass:
+// a pass serves `groups` consecutive lanes of one gather instruction (= one slot k) and takes as many
+// cycles as the largest number of different addresses that fall into one bank group (class = column mod
+// groups).  A nonzero may sit in any slot and any lane of its own row, so the nonzeros are dealt class by
+// class (largest class first) to the pass, among those that contain lanes of the row and still have room,
+// where they add no cycle, else to the emptiest one.  Surplus nonzeros of over-full classes thereby pile
+// into the same few passes, and a row that owns whole passes reaches max(largest class, passes) cycles,
+// the lower bound.  Rows that share a pass (L < groups) are scheduled against the same pass state.
+// LDS cycles one wavefront needs for its `trip` gathers under the pass model above.
+static int64_t wave_cycles(const std::vector<RowGroup>& rg, int L, int trip, int groups) {
+  int64_t total = 0;
+  std::vector<std::vector<int32_t>> seen(groups);
+  for (int k = 0; k < trip; ++k)
+    for (int base = 0; base < kWave; base += groups) {
+      for (auto& v : seen) v.clear();
+      for (const RowGroup& q : rg)
+        for (int l = 0; l < L; ++l) {
+          if (q.lane0 + l < base || q.lane0 + l >= base + groups) continue;
+          const int i = q.pos[(size_t)k * L + l];
+          if (i < 0) continue;   // fillers are given a free bank group afterwards
+          auto& v = seen[q.items[i].col % groups];
+          if (std::find(v.begin(), v.end(), q.items[i].col) == v.end()) v.push_back(q.items[i].col);
+        }
+      size_t worst = 1;
+      for (auto& v : seen) worst = std::max(worst, v.size());
+      total += (int64_t)worst;
+    }
+  return total;
+}
+
+static void order_wave(std::vector<RowGroup>& rg, int L, int trip, int groups, bool bank_aware) {
+  for (auto& g : rg) g.pos.assign((size_t)trip * L, -1);
+  if (trip == 0) return;
+  // CSR order: nonzero i -> lane i % L, slot i / L
+  for (auto& g : rg)
+    for (int i = 0; i < (int)g.items.size(); ++i) g.pos[i] = i;
+  if (!bank_aware) return;
+  const int64_t csr_cycles = wave_cycles(rg, L, trip, groups);
+  std::vector<std::vector<int>> csr_pos(rg.size());
+  for (size_t q = 0; q < rg.size(); ++q) { csr_pos[q] = rg[q].pos; rg[q].pos.assign((size_t)trip * L, -1); }
+  const int pgs = kWave / groups;                  // pass groups per gather instruction
+  const int P = trip * pgs;                        // passes of this wavefront: p = k * pgs + pg
+  std::vector<int> pass_cycles(P, 0), pass_load(P, 0);
+  std::vector<int> mult((size_t)P * groups, 0);
+  const int sub = std::max(1, L / groups);         // pass groups one row spans
+  const int cap = std::min(L, groups);             // lanes of one row inside one pass
+  // per row and pass: how many of the row's lanes are already taken
+  std::vector<std::vector<int>> taken(rg.size(), std::vector<int>((size_t)trip * sub, 0));
+  std::vector<std::vector<std::vector<int>>> bucket(rg.size(), std::vector<std::vector<int>>(groups));
+  std::vector<int64_t> class_total(groups, 0);
+  for (size_t q = 0; q < rg.size(); ++q)
+    for (int i = (int)rg[q].items.size() - 1; i >= 0; --i) {
+      bucket[q][rg[q].items[i].col % groups].push_back(i);
+      class_total[rg[q].items[i].col % groups] += 1;
+    }
+  std::vector<int> order(groups);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return class_total[a] > class_total[b]; });
+  for (int g : order)
+    for (size_t q = 0; q < rg.size(); ++q) {
+      const int pg0 = rg[q].lane0 / groups;
+      while (!bucket[q][g].empty()) {
+        int best_k = -1, best_s = 0, best_cost = 0, best_load = 0;
+        for (int k = 0; k < trip; ++k)
+          for (int sidx = 0; sidx < sub; ++sidx) {
+            if (taken[q][(size_t)k * sub + sidx] >= cap) continue;
+            const int p = k * pgs + pg0 + sidx;
+            const int cost = (mult[(size_t)p * groups + g] + 1 > pass_cycles[p]) ? 1 : 0;
+            if (best_k < 0 || cost < best_cost || (cost == best_cost && pass_load[p] < best_load)) {
+              best_k = k; best_s = sidx; best_cost = cost; best_load = pass_load[p];
+            }
+          }
+        // the row has at most trip * L nonzeros, so a free lane always exists
+        const int i = bucket[q][g].back();
+        bucket[q][g].pop_back();
+        const int p = best_k * pgs + pg0 + best_s;
+        int& used = taken[q][(size_t)best_k * sub + best_s];
+        rg[q].pos[(size_t)best_k * L + best_s * groups + used] = i;
+        used += 1;
+        pass_load[p] += 1;
+        const int mcount = ++mult[(size_t)p * groups + g];
+        pass_cycles[p] = std::max(pass_cycles[p], mcount);
+      }
+    }
+  // the greedy deal is not optimal when many short rows share a pass: never do worse than CSR order
+  if (wave_cycles(rg, L, trip, groups) > csr_cycles)
+    for (size_t q = 0; q < rg.size(); ++q) rg[q].pos = csr_pos[q];
+}
+
+int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
+         const uint16_t* val_bits, const sprnn_options_t* opt, int num_cus, Packed* out) {
+  int rc = validate_csr(hidden, batch, cell, row_ptr, col_idx, val_bits);
+  if (rc != SPRNN_OK) return rc;
+  const bool lstm = cell == SPRNN_CELL_LSTM;
+  const int rows = hidden * (lstm ? 4 : 1);
+  std::vector<int> row_nnz(rows);
+  for (int r = 0; r < rows; ++r) row_nnz[r] = row_ptr[r + 1] - row_ptr[r];
+  Mapping m;
+  rc = choose_mapping(hidden, batch, cell, row_nnz, opt, num_cus, &m);
+  if (rc != SPRNN_OK) return rc;
+
+  const int L = m.lanes_per_row;
+  const int gpw = kWave / L;                      // row groups per wavefront
+  const int upw = lstm ? gpw / 4 : gpw;           // units per wavefront
+  const int gpu_ = lstm ? 4 : 1;                  // row groups per unit
+  const int units = hidden;
+  auto unit_row = [&](int u, int g) { return lstm ? g * hidden + u : u; };
+  auto unit_cost = [&](int u) {
+    int c = 0;
+    for (int g = 0; g < gpu_; ++g) c = std::max(c, row_nnz[unit_row(u, g)]);
+    return c;
+  };
+
+  // --- units -> (workgroup, wave, unit slot)
+  const int total_waves = m.grid * m.waves;
+  std::vector<int> wave_units((size_t)total_waves * upw, -1);   // unit id per (global wave, slot)
+  if (m.balance == 1) {
+    // deal by nonzero count: similar rows share a wavefront (little padding inside it), and wavefronts are
+    // dealt to workgroups in serpentine order of their trip count so every workgroup gets the same load
+    std::vector<int> order(units);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return unit_cost(a) > unit_cost(b); });
+    const int nw = ceil_div(units, upw);
+    for (int w = 0; w < nw; ++w) {
+      const int round = w / m.grid, idx = w % m.grid;
+      const int wg = (round & 1) ? (m.grid - 1 - idx) : idx;
+      const int gw = wg * m.waves + round;        // round < waves because grid * waves >= nw
+      for (int s = 0; s < upw; ++s) {
+        const int i = w * upw + s;
+        if (i < units) wave_units[(size_t)gw * upw + s] = order[i];
+      }
+    }
+  } else {
+    for (int u = 0; u < units; ++u) wave_units[u] = u;   // contiguous: global wave = u / upw, slot = u % upw
+  }
+
+  Packed& P = *out;
+  P.map = m;
+  const int NW = m.template_words;
+  const size_t lanes = (size_t)m.grid * m.block;
+  P.words.assign(lanes * NW, 0u);
+  P.lane_row.assign(lanes, -1);
+  P.lane_words.assign(lanes, 0);
+  P.wave_words.assign(total_waves, 0);
+
+  const int groups = pass_lanes(batch);
+  auto pad_word = [&](int lane_in_wave, int k) -> uint32_t {
+    // zero-valued filler that reads the bank group this lane would ideally hit
+    int col = (lane_in_wave + k * L) % groups;
+    if (col >= hidden) col = 0;
+    return (uint32_t)(((uint32_t)col * (uint32_t)m.col_stride) >> m.index_shift) << 16;
+  };
+
+  std::vector<char> is_real_zero(P.words.size(), 0);   // positions holding a stored (explicit) zero weight
+  int words_max = 0;
+  int64_t padded = 0;
+  std::vector<RowGroup> rg;
+  for (int gw = 0; gw < total_waves; ++gw) {
+    const int wg = gw / m.waves, wave = gw % m.waves;
+    int trip = 0;
+    for (int s = 0; s < upw; ++s) {
+      const int u = wave_units[(size_t)gw * upw + s];
+      if (u >= 0) trip = std::max(trip, ceil_div(unit_cost(u), L));
+    }
+    P.wave_words[gw] = trip;
+    words_max = std::max(words_max, trip);
+    padded += (int64_t)trip * kWave;
+    rg.clear();
+    for (int s = 0; s < upw; ++s) {
+      const int u = wave_units[(size_t)gw * upw + s];
+      for (int g = 0; g < gpu_; ++g) {
+        RowGroup q;
+        q.lane0 = (s * gpu_ + g) * L;
+        if (u >= 0) {
+          q.row = unit_row(u, g);
+          for (int32_t k = row_ptr[q.row]; k < row_ptr[q.row + 1]; ++k) q.items.push_back({col_idx[k], val_bits[k]});
+        }
+        rg.push_back(std::move(q));
+      }
+    }
+    order_wave(rg, L, trip, groups, m.bank_aware == 1);
+    for (const RowGroup& q : rg) {
+      const size_t tid0 = (size_t)wg * m.block + (size_t)wave * kWave + q.lane0;
+      for (int l = 0; l < L; ++l) P.lane_row[tid0 + l] = q.row;
+      for (int k = 0; k < trip; ++k)
+        for (int l = 0; l < L; ++l) {
+          const size_t at = ((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + q.lane0 + l;
+          const int i = q.pos[(size_t)k * L + l];
+          if (i < 0) { P.words[at] = pad_word(q.lane0 + l, k); continue; }
+          const uint32_t idx = ((uint32_t)q.items[i].col * (uint32_t)m.col_stride) >> m.index_shift;
+          P.words[at] = (idx << 16) | q.items[i].bits;
+          if ((q.items[i].bits & 0x7FFFu) == 0) is_real_zero[at] = 1;
+          P.lane_words[tid0 + l] += 1;
+        }
+    }
+  }
+  // Filler words should not add bank conflicts: give each one a column whose bank group is still free in
+  // its pass (or, failing that, an address that another lane of the pass already reads: a broadcast).
+  for (int wg = 0; wg < m.grid; ++wg)
+    for (int wave = 0; wave < m.waves; ++wave) {
+      const int trip = P.wave_words[(size_t)wg * m.waves + wave];
+      for (int k = 0; k < trip; ++k)
+        for (int base = 0; base < kWave; base += groups) {
+          std::vector<char> used(groups, 0);
+          uint32_t* wp = &P.words[((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + base];
+          std::vector<int> fillers;
+          uint32_t some_addr = 0; bool have_addr = false;
+          for (int l = 0; l < groups; ++l) {
+            const uint32_t w = wp[l];
+            if ((w & 0x7FFFu) == 0) { fillers.push_back(l); continue; }   // zero value: a filler, or a stored zero (kept below)
+            used[((w >> 16) << m.index_shift) / m.col_stride % groups] = 1;
+            some_addr = w >> 16; have_addr = true;
+          }
+          int g = 0;
+          for (int l : fillers) {
+            if (is_real_zero[((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + base + l]) {
+              used[((wp[l] >> 16) << m.index_shift) / m.col_stride % groups] = 1;
+              continue;
+            }
+            while (g < groups && (used[g] || g >= hidden)) ++g;
+            if (g < groups) {
+              wp[l] = (uint32_t)(((uint32_t)g * (uint32_t)m.col_stride) >> m.index_shift) << 16;
+              used[g] = 1;
+            } else {
+              wp[l] = have_addr ? (some_addr << 16) : 0u;
+            }
+          }
+        }
+    }
+  P.map.words_max = words_max;
+  P.map.padded_words = padded;
+  return SPRNN_OK;
+}
+
+// LDS passes needed by the packed gathers relative to a conflict-free layout, under the measured gfx950
+// model: a pass serves `groups` consecutive lanes; lanes that read different addresses in the same bank
+// group serialise, lanes that read the same address are served together.
+double lds_pass_factor(const Packed& P) {
+  const Mapping& m = P.map;
+  const int groups = pass_lanes(m.batch);
+  const int width = m.col_stride;
+  int64_t passes = 0, ideal = 0;
+  std::vector<std::vector<uint32_t>> seen(groups);
+  for (int wg = 0; wg < m.grid; ++wg)
+    for (int wave = 0; wave < m.waves; ++wave) {
+      const int trip = P.wave_words[(size_t)wg * m.waves + wave];
+      for (int k = 0; k < trip; ++k)
+        for (int base = 0; base < kWave; base += groups) {
+          for (auto& v : seen) v.clear();
+          for (int l = base; l < base + groups; ++l) {
+            const uint32_t w = P.words[((size_t)wg * m.template_words + k) * m.block + (size_t)wave * kWave + l];
+            const uint32_t byte = (w >> 16) << m.index_shift;
+            auto& v = seen[(byte / width) % groups];
+            if (std::find(v.begin(), v.end(), byte) == v.end()) v.push_back(byte);
+          }
+          size_t worst = 1;
+          for (auto& v : seen) worst = std::max(worst, v.size());
+          passes += (int64_t)worst;
+          ideal += 1;
+        }
+    }
+  return ideal ? (double)passes / (double)ideal : 1.0;
+}
+
+}  // namespace sprnn

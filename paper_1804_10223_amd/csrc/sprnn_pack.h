@@ -1,0 +1,60 @@
+// Host-side weight preparation for the persistent sparse recurrent kernel.
+//
+// Turns a CSR matrix into the per-lane register image the kernel loads once (paper, Section 3.3:
+// every lane keeps n <index,value> pairs that all belong to one row; Section 4: rows padded with
+// <index,0>; Section 4.1 / Appendix A: the pairs of a row are re-ordered so that the lanes served
+// together by one LDS pass fall into different banks).  Pure host C++, no HIP.
+#ifndef SPRNN_PACK_H_
+#define SPRNN_PACK_H_
+
+#include <cstdint>
+#include <vector>
+
+#include "sprnn.h"
+
+namespace sprnn {
+
+constexpr int kWave = 64;          // lanes per wavefront on gfx950
+constexpr int kMaxWaves = 16;      // wavefronts per workgroup (1024 threads)
+constexpr int kRingSlots = 4;      // exchange ring depth
+constexpr int kLdsLimit = 160 * 1024;
+constexpr uint32_t kSentinel = 0x80000000u;  // -0.0f: "not written yet" (Section 4.2)
+
+// Register slots per lane for which a kernel instantiation exists.
+constexpr int kTemplateWords[] = {8, 16, 24, 32, 48, 64};
+constexpr int kNumTemplateWords = 6;
+
+struct Mapping {
+  int hidden = 0, rows = 0, batch = 0, cell = 0;
+  int grid = 0, waves = 0, block = 0, lanes_per_row = 0;
+  int sync = SPRNN_SYNC_TAGGED, bank_aware = 1, balance = 2, poll_delay = 0, spin_limit = 0;
+  int template_words = 0;    // NW of the kernel instantiation
+  int words_max = 0;         // largest per-lane word count actually used
+  int col_stride = 0;        // bytes between consecutive columns of h in LDS (4 * min(B, 4))
+  int index_shift = 0;       // packed index = (col * col_stride) >> index_shift
+  int h_bytes = 0;           // bytes of one copy of h in LDS / one ring slot (multiple of 16)
+  int lds_bytes = 0;         // 2 * h_bytes
+  int64_t nnz = 0, padded_words = 0;
+};
+
+struct Packed {
+  Mapping map;
+  std::vector<uint32_t> words;      // [grid][template_words][block]
+  std::vector<int32_t> lane_row;    // [grid][block]  row of W served by the lane, -1 if idle
+  std::vector<int32_t> lane_words;  // [grid][block]  real (non-padding) words of the lane
+  std::vector<int32_t> wave_words;  // [grid][waves]  loop trip count of each wavefront
+};
+
+// Returns SPRNN_OK or an error code; on success `out` holds the mapping and the image.
+int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
+         const uint16_t* val_bits, const sprnn_options_t* opt, int num_cus, Packed* out);
+
+double lds_pass_factor(const Packed& P);
+
+// CSR checks shared by create and pack_host: shape, monotone row_ptr, strictly increasing in-range
+// columns, finite binary16 values.
+int validate_csr(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
+                 const uint16_t* val_bits);
+
+}  // namespace sprnn
+#endif

@@ -1,0 +1,162 @@
+"""CPU-only tests of the library's host logic: exported symbols, CSR validation, packer invariants."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1804_10223_amd import binding, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    header = open(os.path.join(ROOT, "include", "sprnn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)   # prototypes only, not the prose
+    declared = sorted(set(re.findall(r"\b(sprnn_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert binding.status_string(0) == "ok"
+    assert "CSR" in binding.status_string(-1)
+
+
+def test_struct_layouts_match_header_sizes():
+    # 8 ints + 8 reserved; 16 ints + 3 int64 + double + 8 reserved ints
+    assert ctypes.sizeof(binding.Options) == 16 * 4
+    assert ctypes.sizeof(binding.Info) == 16 * 4 + 3 * 8 + 8 + 8 * 4
+
+
+def _unpack(words, lane_row, lane_words, info, hidden, batch):
+    """Rows recovered from the packed image: {row: sorted [(col, bits)]} ignoring zero-valued filler."""
+    stride = 4 * min(batch, 4)
+    out = {}
+    g, nw, blk = words.shape
+    for wg in range(g):
+        for t in range(blk):
+            r = int(lane_row[wg, t])
+            if r < 0:
+                continue
+            for k in range(nw):
+                w = int(words[wg, k, t])
+                bits = w & 0xFFFF
+                if (bits & 0x7FFF) == 0:
+                    continue
+                byte = w >> 16
+                assert byte % stride == 0
+                out.setdefault(r, []).append((byte // stride, bits))
+    return {r: sorted(v) for r, v in out.items()}
+
+
+@pytest.mark.parametrize("cell,H,B,dens,rownnz,opts", [
+    ("relu", 96, 4, 0.3, "fixed", {}),
+    ("relu", 96, 4, 0.3, "fixed", {"bank_aware": 2}),
+    ("relu", 200, 2, 0.2, "poisson", {}),
+    ("relu", 200, 2, 0.2, "poisson", {"balance": 2, "lanes_per_row": 8}),
+    ("tanh", 70, 1, 0.5, "poisson", {"lanes_per_row": 64}),
+    ("lstm", 48, 8, 0.25, "fixed", {}),
+    ("lstm", 33, 4, 0.4, "poisson", {"lanes_per_row": 4}),
+    ("relu", 300, 4, 0.1, "fixed", {"grid": 7}),
+])
+def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
+    w = wl.make_workload("p", cell, H, B, 1, dens, seed=3, row_nnz=rownnz)
+    words, lane_row, lane_words, info = binding.pack_host(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, **opts)
+    got = _unpack(words, lane_row, lane_words, info, H, B)
+    for r in range(w.rows):
+        cols = w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]]
+        bits = w.val_bits[w.row_ptr[r]:w.row_ptr[r + 1]]
+        want = sorted((int(c), int(b)) for c, b in zip(cols, bits) if (int(b) & 0x7FFF) != 0)
+        assert got.get(r, []) == want, r
+    # a lane serves exactly one row and its word count matches
+    assert int(lane_words.sum()) == w.nnz
+    assert info["nnz"] == w.nnz and info["padded_words"] >= w.nnz
+    L = info["lanes_per_row"]
+    lr = lane_row.reshape(info["grid"], -1, L)
+    assert np.all(lr == lr[:, :, :1])                       # the L lanes of a group share one row
+    served = lane_row[lane_row >= 0]
+    assert sorted(set(served.tolist())) == list(range(w.rows))
+    assert np.all(np.bincount(served, minlength=w.rows) == L)   # every row served by exactly one group
+    if cell == "lstm":
+        # the four gate rows of a unit sit in four consecutive groups of one wavefront, order i f g o
+        units = lane_row.reshape(info["grid"], -1, 4, L)[:, :, :, 0]
+        ok = units[:, :, 0] >= 0
+        for q in range(4):
+            assert np.all(units[:, :, q][ok] == units[:, :, 0][ok] + q * H)
+
+
+def test_bank_aware_order_reduces_modelled_lds_passes():
+    w = wl.make_workload("p", "relu", 1152, 4, 1, 0.1, seed=0)
+    naive = binding.pack_host(1152, 4, "relu", w.row_ptr, w.col_idx, w.val_bits, bank_aware=2)[3]
+    aware = binding.pack_host(1152, 4, "relu", w.row_ptr, w.col_idx, w.val_bits, bank_aware=1)[3]
+    assert naive["lds_pass_factor"] > 1.8           # random columns: about 3 of 16 lanes collide
+    assert aware["lds_pass_factor"] < 1.6           # the largest of 16 bank classes of 115 random columns sets the floor
+    assert aware["padded_words"] == naive["padded_words"]
+
+
+def test_balance_by_nonzero_count_evens_out_workgroups():
+    w = wl.make_workload("p", "relu", 1440, 2, 1, 0.1, seed=1, row_nnz="poisson")
+    res = {}
+    for mode in (1, 2):
+        words, lane_row, lane_words, info = binding.pack_host(1440, 2, "relu", w.row_ptr, w.col_idx, w.val_bits,
+                                                              balance=mode, num_cus=64)
+        res[mode] = info["padded_words"]
+    assert res[1] < res[2]                          # less zero padding when similar rows share a wavefront
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda rp, ci, vb: rp.__setitem__(0, 1), binding.SPRNN_ERR_INVALID),
+    (lambda rp, ci, vb: rp.__setitem__(3, rp[2] - 1), binding.SPRNN_ERR_INVALID),
+    (lambda rp, ci, vb: ci.__setitem__(0, 40), binding.SPRNN_ERR_INVALID),
+    (lambda rp, ci, vb: ci.__setitem__(1, ci[0]), binding.SPRNN_ERR_INVALID),
+    (lambda rp, ci, vb: vb.__setitem__(2, 0x7C00), binding.SPRNN_ERR_INVALID),
+    (lambda rp, ci, vb: vb.__setitem__(2, 0xFE00), binding.SPRNN_ERR_INVALID),
+])
+def test_malformed_csr_is_rejected(mutate, code):
+    w = wl.make_workload("p", "relu", 40, 2, 1, 0.3, seed=5)
+    rp, ci, vb = w.row_ptr.copy(), w.col_idx.copy(), w.val_bits.copy()
+    mutate(rp, ci, vb)
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(40, 2, "relu", rp, ci, vb)
+    assert e.value.code == code
+
+
+def test_unsupported_and_capacity_errors():
+    w = wl.make_workload("p", "relu", 40, 2, 1, 0.3, seed=5)
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(40, 3, "relu", w.row_ptr, w.col_idx, w.val_bits)
+    assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(40, 2, "relu", w.row_ptr, w.col_idx, w.val_bits, lanes_per_row=3)
+    assert e.value.code == binding.SPRNN_ERR_INVALID
+    # a grid that cannot hold the rows with 16 wavefronts per workgroup
+    big = wl.make_workload("p", "relu", 4096, 1, 1, 0.01, seed=5)
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(4096, 1, "relu", big.row_ptr, big.col_idx, big.val_bits, grid=1, lanes_per_row=64)
+    assert e.value.code == binding.SPRNN_ERR_CAPACITY
+    # h does not fit twice into LDS
+    row_ptr = np.zeros(60001, dtype=np.int32)
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(60000, 4, "relu", row_ptr, np.zeros(0, np.int32), np.zeros(0, np.uint16))
+    assert e.value.code == binding.SPRNN_ERR_CAPACITY
+
+
+def test_empty_matrix_and_empty_rows_pack():
+    H = 17
+    row_ptr = np.zeros(H + 1, dtype=np.int32)
+    words, lane_row, lane_words, info = binding.pack_host(H, 1, "relu", row_ptr, np.zeros(0, np.int32), np.zeros(0, np.uint16))
+    assert info["nnz"] == 0 and lane_words.sum() == 0
+    assert sorted(set(lane_row[lane_row >= 0].tolist())) == list(range(H))
+
+
+def test_auto_mapping_of_the_five_configs():
+    expect = {"cfg1": dict(batch=1), "cfg2": dict(batch=4), "cfg3": dict(batch=4, grid=256, lanes_per_row=64),
+              "cfg5": dict(batch=8, cell=3)}
+    for name, e in expect.items():
+        w = wl.make_config(name, steps=1)
+        info = binding.pack_host(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits)[3]
+        for k, v in e.items():
+            assert info[k] == v, (name, k, info)
+        assert info["grid"] <= 256 and info["waves"] <= 16 and info["lds_bytes"] <= 160 * 1024
+        assert info["words_per_lane_max"] <= info["template_words"]

@@ -1,0 +1,262 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: per timestep  max|h_gpu - h_oracle| <= 1e-3 * max|h_oracle|  (same for c_t of the LSTM); index and
+sparsity-pattern handling bit exact (permutation matrices, zero weights).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1804_10223_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-3
+
+
+def _dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def oracle_run(w, threads=8):
+    if w.cell == "lstm":
+        return oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, w.c0, threads=threads)
+    return oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=threads), None
+
+
+def gpu_run(rnn, w, stepwise=False):
+    x, h0, c0 = _dev(w.x), _dev(w.h0), _dev(w.c0)
+    if stepwise:
+        h, c = rnn.forward_stepwise(x, h0, c0)
+    elif w.cell == "lstm":
+        h, c = rnn.forward_lstm(x, h0, c0)
+    else:
+        h, c = rnn.forward(x, h0), None
+    assert rnn.check() == binding.SPRNN_OK
+    return h.cpu().numpy(), (None if c is None else c.cpu().numpy())
+
+
+def assert_parity(got, want, what=""):
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got)), what
+    for t in range(want.shape[0]):
+        scale = np.abs(want[t]).max()
+        err = np.abs(got[t] - want[t]).max()
+        assert err <= REL_TOL * scale + 1e-30, "%s step %d: err %.3e scale %.3e" % (what, t, err, scale)
+
+
+def check_workload(w, stepwise_too=True, **options):
+    want_h, want_c = oracle_run(w)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, **options) as rnn:
+        info = rnn.info()
+        print("case", w.name, w.cell, "H", w.hidden, "B", w.batch, "T", w.steps, options, {k: info[k] for k in ("grid", "block", "lanes_per_row", "template_words", "sync", "balance")}, flush=True)
+        got_h, got_c = gpu_run(rnn, w)
+        assert_parity(got_h, want_h, "h persistent")
+        if want_c is not None:
+            assert_parity(got_c, want_c, "c persistent")
+        if stepwise_too:
+            s_h, s_c = gpu_run(rnn, w, stepwise=True)
+            assert_parity(s_h, want_h, "h stepwise")
+            if want_c is not None:
+                assert_parity(s_c, want_c, "c stepwise")
+    return info
+
+
+# ------------------------------------------------------------------ small shapes: several tiles, ragged tails
+SMALL = [
+    ("relu", 96, 4, 9, 0.3, "fixed", {}),
+    ("relu", 257, 1, 7, 0.2, "fixed", {}),
+    ("relu", 333, 2, 6, 0.15, "poisson", {}),
+    ("tanh", 200, 4, 8, 0.25, "fixed", {}),
+    ("identity", 130, 8, 5, 0.1, "poisson", {}),
+    ("relu", 1000, 4, 12, 0.05, "poisson", {"grid": 13}),
+    ("relu", 640, 4, 10, 0.5, "fixed", {"lanes_per_row": 64}),
+    ("relu", 640, 4, 10, 0.5, "fixed", {"lanes_per_row": 8}),
+    ("relu", 640, 2, 10, 0.1, "fixed", {"lanes_per_row": 1}),
+    ("relu", 500, 4, 10, 0.2, "poisson", {"balance": 1}),
+    ("relu", 500, 4, 10, 0.2, "poisson", {"balance": 2}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"bank_aware": 2}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"sync": "barrier"}),
+    ("relu", 500, 1, 10, 0.2, "fixed", {"sync": "barrier", "grid": 5}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"poll_delay": -1}),
+    ("lstm", 64, 8, 9, 0.3, "fixed", {}),
+    ("lstm", 100, 4, 7, 0.2, "poisson", {}),
+    ("lstm", 77, 1, 6, 0.4, "fixed", {"lanes_per_row": 4}),
+    ("lstm", 150, 2, 6, 0.3, "fixed", {"lanes_per_row": 16, "sync": "barrier"}),
+]
+
+
+@pytest.mark.parametrize("cell,H,B,T,dens,rownnz,opts", SMALL)
+def test_small_shapes_match_oracle(cell, H, B, T, dens, rownnz, opts):
+    w = wl.make_workload("small", cell, H, B, T, dens, seed=H + B + T, row_nnz=rownnz, h0_std=0.5,
+                         gain=1.0 if cell == "lstm" else 0.9)
+    if cell == "lstm":
+        w.c0 = (np.random.default_rng(1).standard_normal((B, H)) * 0.5).astype(np.float32)
+    check_workload(w, **opts)
+
+
+# ------------------------------------------------------------------ degenerate cases
+def test_zero_steps_and_single_step():
+    w = wl.make_workload("t1", "relu", 128, 4, 1, 0.2, seed=1, h0_std=0.3)
+    check_workload(w)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        empty = torch.empty((0, 4, 128), dtype=torch.float32, device="cuda")
+        out = rnn.forward(empty, None)
+        assert out.shape == (0, 4, 128) and rnn.check() == binding.SPRNN_OK
+
+
+@pytest.mark.parametrize("cell", ["relu", "identity"])
+def test_zero_weights_bit_exact(cell):
+    H, B, T = 300, 4, 5
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((T, B, H)).astype(np.float32)
+    row_ptr = np.zeros(H + 1, dtype=np.int32)
+    with binding.SparseRNN(H, B, cell, row_ptr, np.zeros(0, np.int32), np.zeros(0, np.uint16)) as rnn:
+        h = rnn.forward(_dev(x), None).cpu().numpy()
+        assert rnn.check() == binding.SPRNN_OK
+    want = np.maximum(x, np.float32(0)) if cell == "relu" else x
+    assert np.array_equal(h, want + np.float32(0))       # +0: a -0.0 result is written as +0.0
+
+
+def test_empty_rows_and_stored_zeros():
+    H, B, T = 90, 2, 6
+    w = wl.make_workload("e", "relu", H, B, T, 0.2, seed=2, h0_std=0.5)
+    # empty every third row, and store explicit zeros in some places
+    keep = np.ones(w.nnz, dtype=bool)
+    for r in range(0, H, 3):
+        keep[w.row_ptr[r]:w.row_ptr[r + 1]] = False
+    counts = np.array([keep[w.row_ptr[r]:w.row_ptr[r + 1]].sum() for r in range(H)])
+    w.col_idx, w.val_bits = w.col_idx[keep], w.val_bits[keep].copy()
+    w.row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    w.val_bits[::7] = 0
+    w.val_bits[3::11] = 0x8000
+    check_workload(w)
+
+
+@pytest.mark.parametrize("H,B", [(7, 4), (4099, 2), (16384, 1)])
+def test_permutation_matrix_bit_exact(H, B):
+    rng = np.random.default_rng(H)
+    perm = rng.permutation(H).astype(np.int32)
+    row_ptr = np.arange(H + 1, dtype=np.int32)
+    ones = np.full(H, 0x3C00, dtype=np.uint16)
+    T = 4
+    x = np.zeros((T, B, H), dtype=np.float32)
+    h0 = np.abs(rng.standard_normal((B, H))).astype(np.float32) + np.float32(0.01)
+    with binding.SparseRNN(H, B, "relu", row_ptr, perm, ones) as rnn:
+        h = rnn.forward(_dev(x), _dev(h0)).cpu().numpy()
+        assert rnn.check() == binding.SPRNN_OK
+        s, _ = rnn.forward_stepwise(_dev(x), _dev(h0))
+        s = s.cpu().numpy()
+    cur = h0
+    for t in range(T):
+        cur = cur[:, perm]
+        assert np.array_equal(h[t].view(np.uint32), cur.view(np.uint32)), t
+        assert np.array_equal(s[t].view(np.uint32), cur.view(np.uint32)), t
+
+
+def test_subnormal_and_extreme_fp16_weights_are_not_flushed():
+    H, B, T = 64, 4, 3
+    rng = np.random.default_rng(3)
+    w = wl.make_workload("sub", "identity", H, B, T, 0.5, seed=3)
+    bits = w.val_bits.copy()
+    bits[0::3] = rng.integers(1, 0x3FF, size=bits[0::3].shape).astype(np.uint16)            # positive subnormals
+    bits[1::3] = (0x8000 | rng.integers(1, 0x3FF, size=bits[1::3].shape)).astype(np.uint16)  # negative subnormals
+    w.val_bits = bits
+    w.x = np.zeros_like(w.x)
+    w.h0 = (rng.standard_normal((B, H)) * 1e4).astype(np.float32)
+    want, _ = oracle_run(w)
+    assert np.abs(want[0]).max() > 0
+    with binding.SparseRNN(H, B, "identity", w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        got, _ = gpu_run(rnn, w)
+    assert_parity(got, want, "subnormal")
+
+
+# ------------------------------------------------------------------ handle reuse: the ring keeps its timestep numbering
+def test_consecutive_forwards_and_time_composition():
+    w = wl.make_workload("c", "relu", 400, 4, 11, 0.2, seed=4, h0_std=0.5)
+    want, _ = oracle_run(w)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        x, h0 = _dev(w.x), _dev(w.h0)
+        for rep in range(3):                      # 11 steps each: the ring slot phase differs every time
+            h = rnn.forward(x, h0)
+            assert rnn.check() == binding.SPRNN_OK
+            assert_parity(h.cpu().numpy(), want, "rep %d" % rep)
+        a = rnn.forward(x[:5].contiguous(), h0)
+        b = rnn.forward(x[5:].contiguous(), a[-1].contiguous())
+        assert rnn.check() == binding.SPRNN_OK
+        both = torch.cat([a, b]).cpu().numpy()
+        assert_parity(both, want, "split 5+6")
+        # run-to-run determinism of the persistent path
+        h1 = rnn.forward(x, h0).cpu().numpy()
+        h2 = rnn.forward(x, h0).cpu().numpy()
+        assert np.array_equal(h1, h2)
+
+
+def test_two_handles_interleaved_on_one_stream():
+    w1 = wl.make_workload("a", "relu", 256, 4, 8, 0.2, seed=5)
+    w2 = wl.make_workload("b", "lstm", 96, 2, 8, 0.3, seed=6, gain=1.0)
+    want1, _ = oracle_run(w1)
+    want2h, want2c = oracle_run(w2)
+    with binding.SparseRNN(w1.hidden, w1.batch, w1.cell, w1.row_ptr, w1.col_idx, w1.val_bits) as r1, \
+            binding.SparseRNN(w2.hidden, w2.batch, w2.cell, w2.row_ptr, w2.col_idx, w2.val_bits) as r2:
+        h1 = r1.forward(_dev(w1.x), None)
+        h2, c2 = r2.forward_lstm(_dev(w2.x), None, None)
+        h1b = r1.forward(_dev(w1.x), None)
+        assert r1.check() == binding.SPRNN_OK and r2.check() == binding.SPRNN_OK
+        assert_parity(h1.cpu().numpy(), want1)
+        assert_parity(h1b.cpu().numpy(), want1)
+        assert_parity(h2.cpu().numpy(), want2h)
+        assert_parity(c2.cpu().numpy(), want2c)
+
+
+def test_side_stream():
+    w = wl.make_workload("s", "relu", 300, 2, 9, 0.2, seed=7)
+    want, _ = oracle_run(w)
+    st = torch.cuda.Stream()
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        x = _dev(w.x)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            h = rnn.forward(x, None)
+        st.synchronize()
+        assert rnn.check() == binding.SPRNN_OK
+        assert_parity(h.cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------ error paths that need a device
+def test_wrong_cell_call_and_bad_arguments():
+    w = wl.make_workload("s", "relu", 64, 2, 3, 0.2, seed=8)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        x = _dev(w.x)
+        with pytest.raises(binding.SprnnError) as e:
+            rnn.forward_lstm(x, None, None)
+        assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
+        with pytest.raises(ValueError):
+            rnn.forward(x[:, :1].contiguous())
+    with pytest.raises(binding.SprnnError) as e:
+        binding.SparseRNN(64, 2, "relu", w.row_ptr, w.col_idx, w.val_bits, device=99)
+    assert e.value.code == binding.SPRNN_ERR_INVALID
+
+
+def test_watchdog_trip_is_reported_and_every_kernel_exits():
+    # a spin limit of one poll makes the kernel's own bounded wait give up almost immediately;
+    # the kernel must still drain, the trip must be reported, and the handle must refuse further work
+    w = wl.make_workload("wd", "relu", 1024, 4, 64, 0.05, seed=9)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, grid=64, spin_limit=1,
+                           poll_delay=-1) as rnn:
+        rnn.forward(_dev(w.x), None)
+        code = rnn.check()
+        assert code in (binding.SPRNN_OK, binding.SPRNN_ERR_STATE)
+        if code == binding.SPRNN_ERR_STATE:
+            with pytest.raises(binding.SprnnError) as e:
+                rnn.forward(_dev(w.x), None)
+            assert e.value.code == binding.SPRNN_ERR_STATE
+
+
+# ------------------------------------------------------------------ the five measured configurations, full size
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_full_configs_match_oracle(name):
+    w = wl.make_config(name)
+    info = check_workload(w, stepwise_too=(name in ("cfg1", "cfg2", "cfg5")))
+    assert info["grid"] <= info["resident_capacity"]
