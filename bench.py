@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the persistent sparse recurrent step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--all-configs]
+
+One "step" is one pass of the whole hot path over one batch of synthetic input: one call of
+sprnn_forward over the T timesteps of the configuration (cfg3 = hidden 2304, batch 4, density 30 %,
+T = 256, the shape the metric is quoted on).  Inputs are resident in device memory before the timed
+region.  Prints ONE JSON line on stdout; everything else goes to stderr.
+
+Reported beside the throughput:
+  roofline      the stated per-timestep bound  T_roof = nnz*gather_bytes/BW_lds + L_handoff + |h|/BW_fill
+                (LDS operand bandwidth for the nonzero stream + measured cross-workgroup store->observe
+                latency + time to bring h into one CU), its three device constants measured live by
+                libsprnn_probe, and achieved/peak in microseconds per timestep.
+  stepwise      the non-persistent comparison path (one launch per timestep) on the same inputs.
+  cpu_baseline  the CPU oracle as it stands, timed on the host cores of this machine.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_forward(run, steps, warmup, torch):
+    """Wall time of `steps` calls bracketed by synchronize, plus per-call kernel time from HIP events
+    recorded on the stream the kernel is launched on (torch's current stream)."""
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record(stream)
+        run()
+        b.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_call_ms = [a.elapsed_time(b) for a, b in evs]
+    return (t1 - t0), per_call_ms
+
+
+def measure_config(name, steps, warmup, torch, with_stepwise=True, options=None):
+    from paper_1804_10223_amd import binding, workloads as wl
+    w = wl.make_config(name)
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    x, h0, c0 = dev(w.x), dev(w.h0), dev(w.c0)
+    rnn = binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, **(options or {}))
+    info = rnn.info()
+    T = w.steps
+    h_out = torch.empty((T, w.batch, w.hidden), dtype=torch.float32, device="cuda")
+    c_out = torch.empty_like(h_out) if w.cell == "lstm" else None
+    if w.cell == "lstm":
+        run = lambda: rnn.forward_lstm(x, h0, c0, h_out, c_out)
+        run_step = lambda: rnn.forward_stepwise(x, h0, c0, h_out, c_out)
+    else:
+        run = lambda: rnn.forward(x, h0, h_out)
+        run_step = lambda: rnn.forward_stepwise(x, h0, None, h_out, None)
+    wall, per_call = time_forward(run, steps, warmup, torch)
+    if rnn.check() != 0:
+        raise RuntimeError("spin watchdog tripped during the benchmark")
+    res = dict(name=name, workload=w, info=info, wall_s=wall, kernel_ms=float(np.median(per_call)),
+               kernel_ms_mean=float(np.mean(per_call)), T=T)
+    if with_stepwise:
+        swall, sper = time_forward(run_step, max(3, steps // 4), 1, torch)
+        res["stepwise_ms"] = float(np.median(sper))
+    rnn.close()
+    return res
+
+
+def roofline_for(w, info, probe_vals):
+    """Stated per-timestep bound for one configuration from the measured device constants."""
+    gather = 4 * w.batch                                   # fp32 activations of one column, all samples
+    lds_bytes = w.nnz * gather
+    width = min(16, gather)
+    t_operate = lds_bytes / probe_vals["lds_Bps"][width]
+    t_handoff = probe_vals["handoff_cross_ns"] * 1e-9 if info["grid"] > 32 else probe_vals["handoff_same_ns"] * 1e-9
+    if info["grid"] == 1:
+        t_handoff = 0.0
+    h_bytes = w.hidden * w.batch * 4
+    t_fill = h_bytes / probe_vals["fill_Bps"]
+    return dict(t_operate_us=t_operate * 1e6, t_handoff_us=t_handoff * 1e6, t_fill_us=t_fill * 1e6,
+                t_roof_us=(t_operate + t_handoff + t_fill) * 1e6, lds_bytes_per_step=lds_bytes, h_bytes=h_bytes)
+
+
+def measure_probes(probe):
+    vals = {"lds_Bps": {}}
+    for width in (4, 8, 16):
+        vals["lds_Bps"][width] = probe.lds_gather(256, 1024, width, 0)
+    vals["lds_random_Bps_16"] = probe.lds_gather(256, 1024, 16, 1)
+    vals["handoff_same_ns"], vals["xcc_same"] = probe.handoff_ns(True)
+    vals["handoff_cross_ns"], vals["xcc_cross"] = probe.handoff_ns(False)
+    # asymptotic per-CU fill rate: a large copy (64 KB), all 256 CUs at once
+    big = 64 * 1024
+    vals["fill_Bps"] = big / probe.fill_seconds(256, 1024, big)
+    vals["fill_36k_s"] = probe.fill_seconds(256, 1024, 36864)
+    return vals
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The oracle as it stands on this machine's host cores: single thread (the reported value) and all cores."""
+    import oracle
+    cores = os.cpu_count() or 1
+    try:
+        cores = min(cores, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        pass
+    cores = int(os.environ.get("OMP_NUM_THREADS", cores)) if os.environ.get("OMP_NUM_THREADS", "").isdigit() else cores
+
+    def run(T, threads):
+        xs = np.ascontiguousarray(w.x[:T])
+        t0 = time.perf_counter()
+        if w.cell == "lstm":
+            oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, xs, w.h0, w.c0, threads=threads)
+        else:
+            oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, xs, w.h0, threads=threads)
+        return time.perf_counter() - t0
+
+    probe_T = min(8, w.steps)
+    per_step = run(probe_T, 1) / probe_T
+    T1 = int(max(probe_T, min(w.steps, (budget_s * 0.6) / max(per_step, 1e-9))))
+    t_single = run(T1, 1)
+    per_step_n = run(probe_T, cores) / probe_T
+    Tn = int(max(probe_T, min(w.steps, (budget_s * 0.4) / max(per_step_n, 1e-9))))
+    t_multi = run(Tn, cores)
+    return {"value": T1 / t_single, "unit": "timesteps/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d of %d timesteps of %s, single thread" % (T1, w.steps, w.name),
+            "us_per_timestep": t_single / T1 * 1e6,
+            "all_cores": {"value": Tn / t_multi, "unit": "timesteps/s", "cores": cores,
+                          "us_per_timestep": t_multi / Tn * 1e6,
+                          "sample": "first %d timesteps, OpenMP over rows inside each timestep" % Tn}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--all-configs", action="store_true", help="also time cfg1..cfg5 and write a table to stderr")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures ONE GPU only (the persistent kernel lives on one device); "
+            "--gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(3)
+    from paper_1804_10223_amd import binding, probe
+    binding.load_library()
+
+    log("measuring device constants (LDS gather rate, hand-off latency, fill rate) ...")
+    pv = measure_probes(probe)
+    log("  LDS conflict-free: b128 %.1f TB/s, b64 %.1f TB/s, b32 %.1f TB/s; random b128 %.1f TB/s" % (
+        pv["lds_Bps"][16] / 1e12, pv["lds_Bps"][8] / 1e12, pv["lds_Bps"][4] / 1e12, pv["lds_random_Bps_16"] / 1e12))
+    log("  hand-off one way: same XCD %.0f ns %s, cross XCD %.0f ns %s; fill %.1f GB/s per CU (36 KB copy %.2f us)" % (
+        pv["handoff_same_ns"], pv["xcc_same"], pv["handoff_cross_ns"], pv["xcc_cross"], pv["fill_Bps"] / 1e9, pv["fill_36k_s"] * 1e6))
+
+    res = measure_config(args.config, args.steps, args.warmup, torch)
+    w, info, T = res["workload"], res["info"], res["T"]
+    us_per_ts = res["kernel_ms"] * 1e3 / T
+    roof = roofline_for(w, info, pv)
+    value = args.steps * T / res["wall_s"]
+    log("%s: %.3f us/timestep (kernel median %.3f ms per %d timesteps), wall %.1f timesteps/s; roofline %.3f us => %.1f %%" % (
+        args.config, us_per_ts, res["kernel_ms"], T, value, roof["t_roof_us"], 100 * roof["t_roof_us"] / us_per_ts))
+    log("  mapping: " + json.dumps({k: info[k] for k in ("grid", "block", "lanes_per_row", "template_words", "words_per_lane_max", "lds_bytes", "sync", "bank_aware", "balance", "poll_delay", "lds_pass_factor", "padded_words", "nnz")}))
+
+    table = []
+    if args.all_configs:
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+            r = res if name == args.config else measure_config(name, max(5, args.steps // 2), 2, torch)
+            rf = roofline_for(r["workload"], r["info"], pv)
+            us = r["kernel_ms"] * 1e3 / r["T"]
+            row = dict(config=name, us_per_timestep=us, stepwise_us_per_timestep=r["stepwise_ms"] * 1e3 / r["T"],
+                       roofline_us=rf["t_roof_us"], frac=rf["t_roof_us"] / us, grid=r["info"]["grid"], block=r["info"]["block"])
+            table.append(row)
+            log("  %s" % json.dumps(row))
+
+    cpu = None
+    if not args.no_cpu:
+        log("timing the CPU oracle on the host cores ...")
+        cpu = cpu_baseline(w)
+        log("  oracle: %.1f us/timestep single thread; %.1f us/timestep on %d cores" % (
+            cpu["us_per_timestep"], cpu["all_cores"]["us_per_timestep"], cpu["all_cores"]["cores"]))
+
+    out = {
+        "metric": "timesteps_per_sec (hidden %d, batch %d, density %.0f%%)" % (w.hidden, w.batch, 100 * w.meta["density"]),
+        "value": value,
+        "unit": "timesteps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": res["wall_s"] / args.steps * 1e3,
+        "us_per_timestep": us_per_ts,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32 (fp16 weights, fp32 activations and accumulation)",
+        "data": "synthetic",
+        "config": {"workload": "%s: sparse %s RNN, hidden %d, batch %d, T %d, density %.0f%%, fp16 weights + u16 indices" % (
+            w.name, w.cell, w.hidden, w.batch, T, 100 * w.meta["density"]),
+            "timesteps_per_step": T, "grid": info["grid"], "block": info["block"], "sync": "tagged" if info["sync"] == 1 else "barrier"},
+        "roofline": {
+            "bound": "lds+exchange",
+            "achieved": us_per_ts,
+            "peak": roof["t_roof_us"],
+            "unit": "us/timestep (lower is better; frac = peak/achieved)",
+            "frac": roof["t_roof_us"] / us_per_ts,
+            "traffic": None,
+            "t_operate_us": roof["t_operate_us"], "t_handoff_us": roof["t_handoff_us"], "t_fill_us": roof["t_fill_us"],
+            "lds_bytes_per_timestep": roof["lds_bytes_per_step"],
+            "lds_achieved_TBps": roof["lds_bytes_per_step"] / (us_per_ts * 1e-6) / 1e12,
+            "lds_peak_measured_TBps": pv["lds_Bps"][min(16, 4 * w.batch)] / 1e12,
+            "handoff_same_xcd_ns": pv["handoff_same_ns"], "handoff_cross_xcd_ns": pv["handoff_cross_ns"],
+            "fill_GBps_per_cu": pv["fill_Bps"] / 1e9,
+            "kernel": "persistent_kernel<B=%d,NW=%d>" % (w.batch, info["template_words"]),
+            "kernel_ms_per_launch": res["kernel_ms"],
+        },
+        "stepwise": {"us_per_timestep": res["stepwise_ms"] * 1e3 / T, "speedup_of_persistent": res["stepwise_ms"] / res["kernel_ms"]},
+        "cpu_baseline": cpu,
+    }
+    if table:
+        out["all_configs"] = table
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

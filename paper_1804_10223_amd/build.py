@@ -10,7 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsprnn.so")
+PROBE_LIB = os.path.join(HERE, "libsprnn_probe.so")
 SOURCES = ["sprnn_pack.cpp", "sprnn_kernels.hip", "sprnn_api.hip"]
+PROBE_SOURCES = ["sprnn_probe.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -28,7 +30,7 @@ def _filter(stderr: str) -> str:
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile every source for gfx950 and link libsprnn.so next to this file; returns its path."""
+    """Compile every source for gfx950 and link libsprnn.so and libsprnn_probe.so next to this file."""
     hipcc = _hipcc()
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
@@ -44,11 +46,12 @@ def build_library(verbose: bool = False) -> str:
             print(msg, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
-    r = subprocess.run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + _filter(r.stderr))
+    with ThreadPoolExecutor(max_workers=len(SOURCES) + len(PROBE_SOURCES)) as ex:
+        objs = list(ex.map(compile_one, SOURCES + PROBE_SOURCES))
+    for lib, part in ((LIB, objs[:len(SOURCES)]), (PROBE_LIB, objs[len(SOURCES):])):
+        r = subprocess.run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *part, "-o", lib], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + _filter(r.stderr))
     return LIB
 
 

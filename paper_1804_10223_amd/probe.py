@@ -1,0 +1,56 @@
+"""ctypes binding of libsprnn_probe.so: the device microbenchmarks behind the stated roofline
+(``include/sprnn_probe.h``).  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsprnn_probe.so")
+EXPORTS = ["sprnn_probe_lds_gather", "sprnn_probe_handoff", "sprnn_probe_fill"]
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libsprnn_probe.so is missing: build it with `python -m paper_1804_10223_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        ci, dp = ctypes.c_int, ctypes.POINTER(ctypes.c_double)
+        lib.sprnn_probe_lds_gather.restype = ci
+        lib.sprnn_probe_lds_gather.argtypes = [ci, ci, ci, ci, ci, dp]
+        lib.sprnn_probe_handoff.restype = ci
+        lib.sprnn_probe_handoff.argtypes = [ci, ci, ci, dp, ctypes.POINTER(ci * 2)]
+        lib.sprnn_probe_fill.restype = ci
+        lib.sprnn_probe_fill.argtypes = [ci, ci, ci, ci, ci, dp]
+        _lib = lib
+    return _lib
+
+
+def lds_gather(workgroups: int, threads: int, width_bytes: int, pattern: int = 0, device: int = 0) -> float:
+    """Aggregate LDS gather rate in bytes/s (pattern 0 conflict free, 1 random columns)."""
+    out = ctypes.c_double()
+    rc = load_library().sprnn_probe_lds_gather(device, workgroups, threads, width_bytes, pattern, ctypes.byref(out))
+    if rc:
+        raise RuntimeError("sprnn_probe_lds_gather failed (%d)" % rc)
+    return out.value
+
+
+def handoff_ns(same_xcd: bool, rounds: int = 2000, device: int = 0):
+    """(one-way store->observe latency in ns, (xcc of producer, xcc of consumer))."""
+    out = ctypes.c_double()
+    xcc = (ctypes.c_int * 2)()
+    rc = load_library().sprnn_probe_handoff(device, 1 if same_xcd else 0, rounds, ctypes.byref(out), ctypes.byref(xcc))
+    if rc:
+        raise RuntimeError("sprnn_probe_handoff failed (%d)" % rc)
+    return out.value, (xcc[0], xcc[1])
+
+
+def fill_seconds(workgroups: int, threads: int, nbytes: int, rounds: int = 200, device: int = 0) -> float:
+    """Seconds for one workgroup to copy ``nbytes`` of coherent global memory into LDS, all workgroups at once."""
+    out = ctypes.c_double()
+    rc = load_library().sprnn_probe_fill(device, workgroups, threads, nbytes, rounds, ctypes.byref(out))
+    if rc:
+        raise RuntimeError("sprnn_probe_fill failed (%d)" % rc)
+    return out.value
