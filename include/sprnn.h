@@ -49,7 +49,7 @@ enum {
  */
 typedef struct sprnn_options_s {
   int grid;          /* number of persistent workgroups (<= co-resident capacity)                  */
-  int waves;         /* wavefronts (64 lanes) per workgroup, 1..16                                 */
+  int waves;         /* wavefronts (64 lanes) per workgroup, 1..12                                 */
   int lanes_per_row; /* lanes that share one weight row: 1,2,4,...,64 (<= 16 for the LSTM cell)    */
   int sync;          /* SPRNN_SYNC_*                                                               */
   int bank_aware;    /* 0 auto, 1 = bank-aware ordering of a row's nonzeros (Section 4.1, App. A),
@@ -58,7 +58,8 @@ typedef struct sprnn_options_s {
   int poll_delay;    /* back-off before the first poll of a step, in units of 64 clocks; 0 auto,
                         -1 none                                                                    */
   int spin_limit;    /* polls before the watchdog gives up (0 = default)                           */
-  int reserved[8];
+  int timeline;      /* 1 = workgroup 0..grid-1 accumulate per-phase times (see sprnn_read_timeline) */
+  int reserved[7];
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */
@@ -132,6 +133,19 @@ int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0,
  */
 int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                            float* h_out, float* c_out, void* stream);
+
+/*
+ * Phase timing of the persistent kernel (only for handles created with options.timeline = 1).
+ * Copies grid x 16 accumulators to `out` (host, capacity in 64-bit words, >= grid * 16) and clears them:
+ * per workgroup, wall-clock ticks (see `*ticks_per_second`) spent by its first wavefront in
+ * [0] operate, [1] reduce + epilogue arithmetic, [2] publish + outputs + next b' prefetch, [3] unused, [4] back-off,
+ * [5] first poll, [6] re-polls and LDS writes, [7] waiting for the workgroup's other wavefronts;
+ * [8] = number of re-polls, [9] = timesteps counted, [10] = ticks of 16 back-to-back clock reads
+ * (the cost of the instrumentation itself, summed over launches), [11] / [12] = shader-clock ticks and
+ * wall-clock ticks over whole launches (their ratio is the shader clock delivered), [13..15] unused.
+ * Synchronises with the device.
+ */
+int sprnn_read_timeline(sprnn_handle_t h, uint64_t* out, int capacity_words, double* ticks_per_second);
 
 /* Describe the mapping chosen at create time. */
 int sprnn_get_info(sprnn_handle_t h, sprnn_info_t* info);

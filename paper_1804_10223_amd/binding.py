@@ -26,14 +26,15 @@ CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_stepwise",
-           "sprnn_get_info", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
+           "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
 
 
 class Options(ctypes.Structure):
     _fields_ = [("grid", ctypes.c_int), ("waves", ctypes.c_int), ("lanes_per_row", ctypes.c_int),
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
-                ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("reserved", ctypes.c_int * 8)]
+                ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
+                ("reserved", ctypes.c_int * 7)]
 
 
 class Info(ctypes.Structure):
@@ -86,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_get_info.argtypes = [vp, ctypes.POINTER(Info)]
     lib.sprnn_check.restype = ci
     lib.sprnn_check.argtypes = [vp]
+    lib.sprnn_read_timeline.restype = ci
+    lib.sprnn_read_timeline.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ci, ctypes.POINTER(ctypes.c_double)]
     lib.sprnn_pack_host.restype = ci
     lib.sprnn_pack_host.argtypes = [ci, ci, ci, i32p, i32p, u16p, ctypes.POINTER(Options), ci, u32pp, i32pp, i32pp,
                                     ctypes.POINTER(Info)]
@@ -207,6 +210,17 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_get_info")
         return i.as_dict()
+
+    def read_timeline(self):
+        """sprnn_read_timeline: (ticks [grid, 16] uint64, ticks_per_second); clears the accumulators."""
+        g = self.info()["grid"]
+        buf = np.zeros((g, 16), dtype=np.uint64)
+        hz = ctypes.c_double()
+        rc = self._lib.sprnn_read_timeline(self._h, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), g * 16,
+                                           ctypes.byref(hz))
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_read_timeline")
+        return buf, hz.value
 
     def check(self) -> int:
         """sprnn_check: synchronise and return the status code (SPRNN_OK or SPRNN_ERR_STATE)."""

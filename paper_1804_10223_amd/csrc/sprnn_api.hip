@@ -27,6 +27,7 @@ struct sprnn_handle_s {
   int32_t* d_wave_words = nullptr;
   uint32_t* d_ring = nullptr;
   uint32_t* d_ctrl = nullptr;
+  unsigned long long* d_timeline = nullptr;   // [grid][16], only with options.timeline
   int32_t* d_row_ptr = nullptr;
   int32_t* d_col = nullptr;
   uint16_t* d_val = nullptr;
@@ -82,7 +83,7 @@ hipError_t upload(T** dst, const T* src, size_t n) {
 void release(sprnn_handle_s* h) {
   if (!h) return;
   (void)hipFree(h->d_words); (void)hipFree(h->d_lane_row); (void)hipFree(h->d_wave_words);
-  (void)hipFree(h->d_ring); (void)hipFree(h->d_ctrl);
+  (void)hipFree(h->d_ring); (void)hipFree(h->d_ctrl); (void)hipFree(h->d_timeline);
   (void)hipFree(h->d_row_ptr); (void)hipFree(h->d_col); (void)hipFree(h->d_val);
   delete h;
 }
@@ -206,6 +207,10 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
             SPRNN_HIP(upload(&h->d_col, col_idx, (size_t)m.nnz)) &&
             SPRNN_HIP(upload(&h->d_val, val_fp16_bits, (size_t)m.nnz));
+  if (ok && m.timeline) {
+    std::vector<unsigned long long> zeros((size_t)m.grid * kTimelineSlots, 0ull);
+    ok = SPRNN_HIP(upload(&h->d_timeline, zeros.data(), zeros.size()));
+  }
   if (!ok || !SPRNN_HIP(hipDeviceSynchronize())) { release(h); return SPRNN_ERR_HIP; }
   *out = h;
   return SPRNN_OK;
@@ -223,18 +228,31 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
   DeviceGuard guard(h->device);
   if (!guard.ok) return SPRNN_ERR_HIP;
   const Mapping& m = h->map;
-  KernelArgs a;
-  a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
-  a.ring = h->d_ring; a.ctrl = h->d_ctrl;
-  a.x = x; a.h0 = h0; a.c0 = c0; a.h_out = h_out; a.c_out = c_out;
-  a.hidden = m.hidden; a.T = T; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
-  a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
-  a.step_base = h->step_base; a.barrier_base = h->barrier_base;
-  void* args[] = {&a};
-  hipError_t e = hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
-  if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
-  h->step_base += (uint32_t)T;
-  h->barrier_base += (uint32_t)(T - 1) * (uint32_t)m.grid;
+  // The kernel addresses x and the outputs with 32-bit byte offsets from the start of the call, so a very
+  // long sequence is run as several launches, each continuing from the last state of the one before.
+  const size_t step_bytes = (size_t)m.batch * m.rows * 4;
+  const int t_max = (int)std::max<size_t>(1, ((size_t)1 << 30) / step_bytes);
+  const size_t hb = (size_t)m.batch * m.hidden;
+  for (int t0 = 0; t0 < T; t0 += t_max) {
+    const int tn = std::min(t_max, T - t0);
+    KernelArgs a;
+    a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
+    a.ring = h->d_ring; a.ctrl = h->d_ctrl;
+    a.x = x + (size_t)t0 * m.batch * m.rows;
+    a.h0 = t0 ? h_out + (size_t)(t0 - 1) * hb : h0;
+    a.c0 = t0 ? (c_out ? c_out + (size_t)(t0 - 1) * hb : nullptr) : c0;
+    a.h_out = h_out + (size_t)t0 * hb;
+    a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
+    a.timeline = h->d_timeline;
+    a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
+    a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
+    a.step_base = h->step_base; a.barrier_base = h->barrier_base;
+    void* args[] = {&a};
+    hipError_t e = hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+    if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
+    h->step_base += (uint32_t)tn;
+    h->barrier_base += (uint32_t)(tn - 1) * (uint32_t)m.grid;
+  }
   return SPRNN_OK;
 }
 
@@ -272,6 +290,24 @@ int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float*
     a.c_cur = lstm ? c_out + (size_t)t * hb : nullptr;
     a.hidden = m.hidden; a.act = m.cell;
     if (launch_stepwise(m.batch, lstm, a, (hipStream_t)stream) != hipSuccess) return SPRNN_ERR_HIP;
+  }
+  return SPRNN_OK;
+}
+
+int sprnn_read_timeline(sprnn_handle_t h, uint64_t* out, int capacity_words, double* ticks_per_second) {
+  if (!h || !out) return SPRNN_ERR_INVALID;
+  if (!h->d_timeline) return SPRNN_ERR_UNSUPPORTED;
+  const size_t n = (size_t)h->map.grid * kTimelineSlots;
+  if (capacity_words < (int)n) return SPRNN_ERR_INVALID;
+  DeviceGuard guard(h->device);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  if (!SPRNN_HIP(hipDeviceSynchronize())) return SPRNN_ERR_HIP;
+  if (!SPRNN_HIP(hipMemcpy(out, h->d_timeline, n * 8, hipMemcpyDeviceToHost))) return SPRNN_ERR_HIP;
+  if (!SPRNN_HIP(hipMemset(h->d_timeline, 0, n * 8))) return SPRNN_ERR_HIP;
+  if (ticks_per_second) {
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, h->device) != hipSuccess || khz <= 0) khz = 100000;
+    *ticks_per_second = khz * 1e3;
   }
   return SPRNN_OK;
 }

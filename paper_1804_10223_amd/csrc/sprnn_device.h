@@ -15,7 +15,8 @@ constexpr uint32_t kSentinelBits = 0x80000000u;   // -0.0f marks a ring element 
 constexpr int kCtrlStatus = 0;                    // ctrl[0]: non-zero once a spin watchdog tripped
 constexpr int kCtrlBarrier = 32;                  // ctrl[32]: arrival counter of the grid-barrier mode (own cache line)
 constexpr int kCtrlWords = 64;
-constexpr int kLdsTailBytes = 16;                 // LDS after the two copies of h: the workgroup's abort flags
+constexpr int kTimelineSlots = 16;                // 64-bit accumulators per workgroup in the phase timeline
+constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after the two copies of h: abort flags, timeline sums
 
 struct KernelArgs {
   const uint32_t* words;      // [grid][NW][block] packed <index,value> words
@@ -28,6 +29,7 @@ struct KernelArgs {
   const float* c0;            // [B][H] or null (LSTM)
   float* h_out;               // [T][B][H]
   float* c_out;               // [T][B][H] (LSTM)
+  unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)
   int hidden, T, lanes_per_row, act, h_bytes, poll_delay, spin_limit, sync;
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
   uint32_t barrier_base;      // barrier arrivals before this call

@@ -37,31 +37,67 @@ __device__ __forceinline__ float dpp_add(float v) {
   return v + __builtin_bit_cast(float, moved);
 }
 
-// Sum over the L consecutive lanes (L a power of two, aligned) that share a row; every lane gets the total.
-__device__ __forceinline__ float group_sum(float v, int L, int lane) {
-  if (L >= 2) v = dpp_add<0xB1>(v);     // quad_perm [1,0,3,2]
-  if (L >= 4) v = dpp_add<0x4E>(v);     // quad_perm [2,3,0,1]
-  if (L >= 8) v = dpp_add<0x141>(v);    // row_half_mirror: the other quad of the octet
-  if (L >= 16) v = dpp_add<0x140>(v);   // row_mirror: the other octet of the row of 16
-  if (L >= 32) v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));  // lane ^ 16
-  if (L >= 64) v += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, v)));
+// Sum over the L consecutive lanes (L a power of two, aligned) that share a row.  The LAST lane of the group
+// ends up with the total (for L <= 16 every lane does).  All steps are DPP modifiers on VALU adds: butterflies
+// inside a row of 16 lanes, then row_bcast:15 / row_bcast:31 to carry row sums into the following rows.
+template <int L>
+__device__ __forceinline__ float group_sum(float v) {
+  if constexpr (L >= 2) v = dpp_add<0xB1>(v);     // quad_perm [1,0,3,2]
+  if constexpr (L >= 4) v = dpp_add<0x4E>(v);     // quad_perm [2,3,0,1]
+  if constexpr (L >= 8) v = dpp_add<0x141>(v);    // row_half_mirror: the other quad of the octet
+  if constexpr (L >= 16) v = dpp_add<0x140>(v);   // row_mirror: the other octet of the row of 16
+  if constexpr (L >= 32) {                        // rows 1 and 3 add the sum of the row before them
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xa, 0xf, false);
+    v += __builtin_bit_cast(float, moved);
+  }
+  if constexpr (L >= 64) {                        // rows 2 and 3 add lane 31 (= rows 0 + 1)
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xc, 0xf, false);
+    v += __builtin_bit_cast(float, moved);
+  }
   return v;
+}
+
+template <int L, int B>
+__device__ __forceinline__ void group_sum_all(float (&acc)[B]) {
+#pragma unroll
+  for (int b = 0; b < B; ++b) acc[b] = group_sum<L>(acc[b]);
+}
+
+// One jump on the (kernel-uniform) lanes-per-row, then straight-line DPP code.
+template <int B>
+__device__ __forceinline__ void reduce_rows(float (&acc)[B], int L) {
+  switch (L) {
+    case 64: group_sum_all<64, B>(acc); break;
+    case 32: group_sum_all<32, B>(acc); break;
+    case 16: group_sum_all<16, B>(acc); break;
+    case 8: group_sum_all<8, B>(acc); break;
+    case 4: group_sum_all<4, B>(acc); break;
+    case 2: group_sum_all<2, B>(acc); break;
+    default: break;
+  }
+}
+
+// Logistic function and tanh from the hardware exp2 / reciprocal instructions (about 1 ulp each):
+// absolute error of a few 1e-7, far inside the 1e-3 parity bound, at a handful of instructions.
+__device__ __forceinline__ float sigmoidf_(float z) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
+__device__ __forceinline__ float tanhf_(float z) {
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * z));
 }
 
 __device__ __forceinline__ float activate(int act, float pre) {
   float h;
   if (act == SPRNN_ACT_RELU) h = fmaxf(pre, 0.0f);
-  else if (act == SPRNN_ACT_TANH) h = tanhf(pre);
+  else if (act == SPRNN_ACT_TANH) h = tanhf_(pre);
   else h = pre;
   return h + 0.0f;   // -0.0 -> +0.0: -0.0 is reserved as the "not written" mark
 }
 
-__device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + expf(-z)); }
-
-__device__ __forceinline__ bool all_written(i32x4 v) {
-  return ((uint32_t)v.x != kSentinelBits) & ((uint32_t)v.y != kSentinelBits) & ((uint32_t)v.z != kSentinelBits) &
-         ((uint32_t)v.w != kSentinelBits);
-}
+// The "not written" mark 0x80000000 is the smallest signed integer, so a chunk (or several) is completely
+// written exactly when the signed minimum of its words is larger than that.
+__device__ __forceinline__ int min_word(i32x4 v) { return min(min(v.x, v.y), min(v.z, v.w)); }
+__device__ __forceinline__ bool all_written(i32x4 v) { return min_word(v) != (int)kSentinelBits; }
 
 // LDS byte offset of h[col j][sample b]
 template <int B>
@@ -70,83 +106,129 @@ __device__ __forceinline__ int lds_offset(int j, int b, int H) {
   return (j * B + b) * 4;
 }
 
+// One gathered column of h for all B samples (two planes of four samples when B == 8).
 template <int B>
-__device__ __forceinline__ void mac_word(float (&acc)[B], uint32_t w, const unsigned char* hb, int plane_bytes) {
-  const uint32_t off = w >> 16;
-  const float wv = half_bits_to_float(w);
+struct Column {
+  f32x4 lo, hi;
+};
+
+template <int B>
+__device__ __forceinline__ Column<B> gather_column(const unsigned char* hb, uint32_t off, int plane_bytes) {
+  Column<B> c;
   if constexpr (B == 1) {
-    const float h = *reinterpret_cast<const float*>(hb + off);
-    acc[0] = fmaf(wv, h, acc[0]);
+    c.lo.x = *reinterpret_cast<const float*>(hb + off);
   } else if constexpr (B == 2) {
-    const f32x2 h = *reinterpret_cast<const f32x2*>(hb + off);
-    acc[0] = fmaf(wv, h.x, acc[0]);
-    acc[1] = fmaf(wv, h.y, acc[1]);
+    const f32x2 v = *reinterpret_cast<const f32x2*>(hb + off);
+    c.lo.x = v.x; c.lo.y = v.y;
   } else if constexpr (B == 4) {
-    const f32x4 h = *reinterpret_cast<const f32x4*>(hb + off);
-    acc[0] = fmaf(wv, h.x, acc[0]);
-    acc[1] = fmaf(wv, h.y, acc[1]);
-    acc[2] = fmaf(wv, h.z, acc[2]);
-    acc[3] = fmaf(wv, h.w, acc[3]);
+    c.lo = *reinterpret_cast<const f32x4*>(hb + off);
   } else {
-    const f32x4 h0 = *reinterpret_cast<const f32x4*>(hb + off);
-    const f32x4 h1 = *reinterpret_cast<const f32x4*>(hb + plane_bytes + off);
-    acc[0] = fmaf(wv, h0.x, acc[0]);
-    acc[1] = fmaf(wv, h0.y, acc[1]);
-    acc[2] = fmaf(wv, h0.z, acc[2]);
-    acc[3] = fmaf(wv, h0.w, acc[3]);
-    acc[4] = fmaf(wv, h1.x, acc[4]);
-    acc[5] = fmaf(wv, h1.y, acc[5]);
-    acc[6] = fmaf(wv, h1.z, acc[6]);
-    acc[7] = fmaf(wv, h1.w, acc[7]);
+    c.lo = *reinterpret_cast<const f32x4*>(hb + off);
+    c.hi = *reinterpret_cast<const f32x4*>(hb + plane_bytes + off);
+  }
+  return c;
+}
+
+template <int B>
+__device__ __forceinline__ void mac_column(float (&acc)[B], float wv, const Column<B>& c) {
+  acc[0] = fmaf(wv, c.lo.x, acc[0]);
+  if constexpr (B >= 2) acc[1] = fmaf(wv, c.lo.y, acc[1]);
+  if constexpr (B >= 4) {
+    acc[2] = fmaf(wv, c.lo.z, acc[2]);
+    acc[3] = fmaf(wv, c.lo.w, acc[3]);
+  }
+  if constexpr (B == 8) {
+    acc[4] = fmaf(wv, c.hi.x, acc[4]);
+    acc[5] = fmaf(wv, c.hi.y, acc[5]);
+    acc[6] = fmaf(wv, c.hi.z, acc[6]);
+    acc[7] = fmaf(wv, c.hi.w, acc[7]);
   }
 }
 
-// Publish the B outputs of one row into a ring slot (same layout as the LDS copy of h).
+// N (1..4) words of one lane: all N gathers are issued back to back, then the multiply-adds follow.
+// The scheduling barrier keeps the compiler from sinking a gather below the arithmetic of an earlier one,
+// so a wavefront has N wide LDS reads in flight instead of one.
+template <int B, int N>
+__device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, const float* wv, const unsigned char* hb,
+                                          int plane_bytes) {
+  Column<B> c[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) c[j] = gather_column<B>(hb, off[j], plane_bytes);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < N; ++j) mac_column<B>(acc, wv[j], c[j]);
+}
+
+// Publish the B outputs of one row into a ring slot (same layout as the LDS copy of h).  `voff` is the lane's
+// byte offset of its row inside a slot, or an out-of-range offset for lanes that own no row: the buffer
+// bounds check then drops the store, so no branch is needed.
 template <int B>
-__device__ __forceinline__ void ring_store(__amdgpu_buffer_rsrc_t ring, int slot_byte, int row, int H, const float (&v)[B]) {
+__device__ __forceinline__ void ring_store(__amdgpu_buffer_rsrc_t ring, int voff, int slot_byte, int plane_bytes, const float (&v)[B]) {
   if constexpr (B == 1) {
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v[0]), ring, slot_byte + row * 4, 0, kAuxCoherent);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v[0]), ring, voff, slot_byte, kAuxCoherent);
   } else if constexpr (B == 2) {
     i32x2 p = {__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1])};
-    __builtin_amdgcn_raw_buffer_store_b64(p, ring, slot_byte + row * 8, 0, kAuxCoherent);
+    __builtin_amdgcn_raw_buffer_store_b64(p, ring, voff, slot_byte, kAuxCoherent);
   } else if constexpr (B == 4) {
     i32x4 p = {__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1]), __builtin_bit_cast(int, v[2]), __builtin_bit_cast(int, v[3])};
-    __builtin_amdgcn_raw_buffer_store_b128(p, ring, slot_byte + row * 16, 0, kAuxCoherent);
+    __builtin_amdgcn_raw_buffer_store_b128(p, ring, voff, slot_byte, kAuxCoherent);
   } else {
     i32x4 p = {__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1]), __builtin_bit_cast(int, v[2]), __builtin_bit_cast(int, v[3])};
     i32x4 q = {__builtin_bit_cast(int, v[4]), __builtin_bit_cast(int, v[5]), __builtin_bit_cast(int, v[6]), __builtin_bit_cast(int, v[7])};
-    __builtin_amdgcn_raw_buffer_store_b128(p, ring, slot_byte + row * 16, 0, kAuxCoherent);
-    __builtin_amdgcn_raw_buffer_store_b128(q, ring, slot_byte + H * 16 + row * 16, 0, kAuxCoherent);
+    __builtin_amdgcn_raw_buffer_store_b128(p, ring, voff, slot_byte, kAuxCoherent);
+    __builtin_amdgcn_raw_buffer_store_b128(q, ring, voff, slot_byte + plane_bytes, kAuxCoherent);
   }
 }
 
+constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer this kernel addresses
+
 template <int B, int NW, bool LSTM>
-__global__ __launch_bounds__(NW >= 48 ? 512 : 1024) void persistent_kernel(const KernelArgs p) {
-  extern __shared__ __align__(16) unsigned char lds[];   // [h copy 0][h copy 1][abort flags]
+__global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const KernelArgs p) {
+  extern __shared__ __align__(16) unsigned char lds[];   // [h copy 0][h copy 1][abort flags][timeline]
   // abort flags, indexed by step parity so that a fast wave's next-step flag cannot be read one step early
   volatile int* s_abort = reinterpret_cast<volatile int*>(lds + 2 * p.h_bytes);
+  unsigned long long* s_tl = reinterpret_cast<unsigned long long*>(lds + 2 * p.h_bytes + 16);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
   const int block = blockDim.x, wg = blockIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid) >> 6;
   const int H = p.hidden, L = p.lanes_per_row;
   const int R = LSTM ? 4 * H : H;
   const int plane_bytes = H * 16;   // used only for B == 8
 
-  // ---- one-time weight load: NW register slots per lane, all of one row (Section 3.3)
+  // ---- one-time weight load: NW register slots per lane, all of one row (Section 3.3).
+  // Each word is unpacked once into an LDS byte offset and an fp32 value (two registers per nonzero): the
+  // hot loop then spends its VALU issue slots on the multiply-adds only.
   const int n_w = __builtin_amdgcn_readfirstlane(p.wave_words[wg * (block >> 6) + wave]);
-  uint32_t w[NW];
+  uint32_t w_off[NW];
+  float w_val[NW];
 #pragma unroll
-  for (int k = 0; k < NW; ++k) w[k] = (k < n_w) ? p.words[((size_t)wg * NW + k) * block + tid] : 0u;
+  for (int k = 0; k < NW; ++k) {
+    const uint32_t word = (k < n_w) ? p.words[((size_t)wg * NW + k) * block + tid] : 0u;
+    w_off[k] = word >> 16;
+    w_val[k] = half_bits_to_float(word);
+  }
+  // The last lane of a row group receives the reduced sum; for the LSTM the last lane of the unit's fourth
+  // group (gate o) gathers the other three gates from the last lanes of the groups before it.
   const int row = p.lane_row[(size_t)wg * block + tid];
-  const bool group_leader = row >= 0 && (lane & (L - 1)) == 0;
-  const bool unit_leader = LSTM ? (row >= 0 && (lane & (4 * L - 1)) == 0) : group_leader;
+  const bool group_leader = row >= 0 && (lane & (L - 1)) == L - 1;
+  const bool unit_leader = LSTM ? (row >= 0 && (lane & (4 * L - 1)) == 4 * L - 1) : group_leader;
   const int unit = LSTM ? (row >= 0 ? row % H : 0) : row;   // hidden-unit index of the row
+  // Per-lane byte offsets for the buffer accesses of the epilogue; lanes without a row point out of range,
+  // where loads return zero and stores are dropped.
+  const int x_voff = group_leader ? row * 4 : kOutOfRange;
+  const int out_voff = unit_leader ? unit * 4 : kOutOfRange;
+  const int ring_voff = unit_leader ? unit * (B >= 4 ? 16 : 4 * B) : kOutOfRange;
 
-  __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
-  __amdgpu_buffer_rsrc_t ctrl = __builtin_amdgcn_make_buffer_rsrc(p.ctrl, 0, 256, kBufWord3);
+  const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
+  const __amdgpu_buffer_rsrc_t ctrl = __builtin_amdgcn_make_buffer_rsrc(p.ctrl, 0, 256, kBufWord3);
+  const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * R * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(LSTM ? p.c_out : p.h_out, 0, p.T * B * H * 4, kBufWord3);
 
   // ---- h_0 into LDS copy 0, cell state into registers
-  if (tid == 0) { s_abort[0] = 0; s_abort[1] = 0; }
+  if (tid < 2) s_abort[tid] = 0;
+  if (tid < kTimelineSlots) s_tl[tid] = 0ull;
   for (int e = tid; e < H * B; e += block) {
     const int j = e / B, b = e % B;
     const float v = p.h0 ? p.h0[(size_t)b * H + j] : 0.0f;
@@ -155,19 +237,38 @@ __global__ __launch_bounds__(NW >= 48 ? 512 : 1024) void persistent_kernel(const
   float c_state[B];
 #pragma unroll
   for (int b = 0; b < B; ++b) c_state[b] = (LSTM && unit_leader && p.c0) ? p.c0[(size_t)b * H + unit] : 0.0f;
+
+  // b'_t of this row is fetched one step ahead: a first-touch read from HBM takes about as long as a
+  // whole timestep, so the load for step t+1 is issued before step t's wait for h_t.
+  // (scalar offsets select the timestep and the sample; the host keeps one launch below 1 GiB of x, so an
+  // out-of-range lane offset stays out of range whatever scalar offset is added to it)
+  float xn[B];
+#pragma unroll
+  for (int b = 0; b < B; ++b) xn[b] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, b * R * 4, 0));
   __syncthreads();
 
+  const bool tl_on = p.timeline != nullptr && wave == 0;
+  long long tl_launch_core = 0, tl_launch_wall = 0, tl_clock_cost = 0;
+  if (tl_on) {   // cost of reading the clock itself: 16 back-to-back reads
+    const long long c0 = wall_clock64();
+    long long c1 = c0;
+#pragma unroll
+    for (int i = 0; i < 15; ++i) c1 = wall_clock64();
+    tl_clock_cost = c1 - c0;
+    tl_launch_core = (long long)clock64();
+    tl_launch_wall = (long long)wall_clock64();
+  }
+
+  const int n4 = p.h_bytes >> 4;               // 16-byte chunks in one copy of h
+  const int last_chunk = n4 - 1;
+  const int chunk_rounds = (n4 + block - 1) / block;
   int cur = 0;
-  bool failed = false;
   for (int t = 0; t < p.T; ++t) {
     const uint32_t g = p.step_base + (uint32_t)t;         // global step index: the slot number is the timestep tag
     const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
     const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
-
-    // b'_t of this row, fetched early so the loads overlap the operate stage
-    float xv[B];
-#pragma unroll
-    for (int b = 0; b < B; ++b) xv[b] = group_leader ? p.x[((size_t)t * B + b) * R + row] : 0.0f;
+    long long ts0 = 0, ts1 = 0, ts2 = 0, ts3 = 0, ts4 = 0, ts5 = 0, ts6 = 0;
+    if (tl_on) ts0 = wall_clock64();
 
     // ---- operate: n_w gathers, in groups of four so the LDS reads are issued back to back
     const unsigned char* hb = lds + cur * p.h_bytes;
@@ -177,63 +278,72 @@ __global__ __launch_bounds__(NW >= 48 ? 512 : 1024) void persistent_kernel(const
 #pragma unroll
     for (int k = 0; k < NW; k += 4) {
       if (k + 4 <= n_w) {
-        mac_word<B>(acc, w[k], hb, plane_bytes);
-        mac_word<B>(acc, w[k + 1], hb, plane_bytes);
-        mac_word<B>(acc, w[k + 2], hb, plane_bytes);
-        mac_word<B>(acc, w[k + 3], hb, plane_bytes);
-      } else if (k < n_w) {   // ragged tail of 1..3 words (no early exit: keeps every w[] index static)
-        mac_word<B>(acc, w[k], hb, plane_bytes);
-        if (k + 1 < n_w) mac_word<B>(acc, w[k + 1], hb, plane_bytes);
-        if (k + 2 < n_w) mac_word<B>(acc, w[k + 2], hb, plane_bytes);
+        mac_words<B, 4>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+      } else if (k < n_w) {   // ragged tail of 1..3 words (no early exit: keeps every register index static)
+        const int rem = n_w - k;
+        if (rem == 3) mac_words<B, 3>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+        else if (rem == 2) mac_words<B, 2>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+        else mac_words<B, 1>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
       }
     }
+    if (tl_on) ts1 = wall_clock64();
 
     // ---- reduce over the lanes of the row
-#pragma unroll
-    for (int b = 0; b < B; ++b) acc[b] = group_sum(acc[b], L, lane);
+    reduce_rows<B>(acc, L);
 
-    // ---- epilogue + hand-off
+    // ---- epilogue (every lane computes, only leaders' stores land)
     float hv[B];
     if constexpr (LSTM) {
       float pg[4][B];
 #pragma unroll
       for (int b = 0; b < B; ++b) {
-        const float pre = acc[b] + xv[b];   // complete pre-activation sits in each gate's group leader
+        const float pre = acc[b] + xn[b];   // complete pre-activation sits in each gate's group leader
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          pg[q][b] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane + q * L) << 2, __builtin_bit_cast(int, pre)));
+          pg[q][b] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane - (3 - q) * L) << 2, __builtin_bit_cast(int, pre)));
       }
 #pragma unroll
       for (int b = 0; b < B; ++b) {
-        const float c = sigmoidf_(pg[1][b]) * c_state[b] + sigmoidf_(pg[0][b]) * tanhf(pg[2][b]);
+        const float c = sigmoidf_(pg[1][b]) * c_state[b] + sigmoidf_(pg[0][b]) * tanhf_(pg[2][b]);
         c_state[b] = c;
-        hv[b] = sigmoidf_(pg[3][b]) * tanhf(c) + 0.0f;
+        hv[b] = sigmoidf_(pg[3][b]) * tanhf_(c) + 0.0f;
       }
     } else {
 #pragma unroll
-      for (int b = 0; b < B; ++b) hv[b] = activate(p.act, acc[b] + xv[b]);
+      for (int b = 0; b < B; ++b) hv[b] = activate(p.act, acc[b] + xn[b]);
     }
-    if (unit_leader) {
-      // the re-arm stores issued one step ago must be performed before this step's data can be seen
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      ring_store<B>(ring, slot_byte, unit, H, hv);
+    if (tl_on) ts2 = wall_clock64();
+
+    // ---- hand-off: publish h_t, write the outputs, re-arm the slot two steps ahead.
+    // The re-arm stores issued one step ago must be performed before this step's data can be seen.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    ring_store<B>(ring, ring_voff, slot_byte, plane_bytes, hv);
+    {
+      const int out_soff = t * B * H * 4;
 #pragma unroll
       for (int b = 0; b < B; ++b) {
-        __builtin_nontemporal_store(hv[b], &p.h_out[((size_t)t * B + b) * H + unit]);
-        if constexpr (LSTM) __builtin_nontemporal_store(c_state[b], &p.c_out[((size_t)t * B + b) * H + unit]);
-      }
-      if (p.sync == SPRNN_SYNC_TAGGED) {
-        float mark[B];
-#pragma unroll
-        for (int b = 0; b < B; ++b) mark[b] = __builtin_bit_cast(float, kSentinelBits);
-        ring_store<B>(ring, rearm_byte, unit, H, mark);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hv[b]), hbuf, out_voff, out_soff + b * H * 4, 0);
+        if constexpr (LSTM) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c_state[b]), cbuf, out_voff, out_soff + b * H * 4, 0);
       }
     }
+    if (p.sync == SPRNN_SYNC_TAGGED) {
+      float mark[B];
+#pragma unroll
+      for (int b = 0; b < B; ++b) mark[b] = __builtin_bit_cast(float, kSentinelBits);
+      ring_store<B>(ring, ring_voff, rearm_byte, plane_bytes, mark);
+    }
     if (t + 1 == p.T) break;
+    {
+      const int x_soff = (t + 1) * B * R * 4;
+#pragma unroll
+      for (int b = 0; b < B; ++b) xn[b] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, x_soff + b * R * 4, 0));
+    }
+    if (tl_on) ts3 = wall_clock64();
 
     // ---- load h_t for the next step into the other LDS copy
     unsigned char* dst = lds + (cur ^ 1) * p.h_bytes;
-    const int n4 = p.h_bytes >> 4;
+    bool failed = false;
+    unsigned long long repolls = 0;
     if (p.sync == SPRNN_SYNC_BARRIER) {
       // grid barrier (Section 3.2): all stores performed, one arrival per workgroup, wait for everyone
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -253,51 +363,44 @@ __global__ __launch_bounds__(NW >= 48 ? 512 : 1024) void persistent_kernel(const
       }
       __syncthreads();
       for (int ci = tid; ci < n4; ci += block) {
-        const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ring, slot_byte + ci * 16, 0, kAuxCoherent);
+        const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ring, ci * 16, slot_byte, kAuxCoherent);
         *reinterpret_cast<i32x4*>(dst + ci * 16) = v;
       }
     } else {
       for (int d = 0; d < p.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
-      for (int base = tid; base < n4; base += 4 * block) {
+      if (tl_on) ts4 = wall_clock64();
+      // Four chunks per lane are in flight at a time.  Chunk indices past the end are clamped to the last
+      // chunk (a few lanes then copy it twice), which keeps this path free of per-lane branches.
+      for (int r0 = 0; r0 < chunk_rounds; r0 += 4) {
+        int off[4];
         i32x4 v[4];
-        bool ok[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int ci = base + c * block;
-          ok[c] = ci >= n4;
-          if (!ok[c]) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, slot_byte + ci * 16, 0, kAuxCoherent);
-        }
-        int spins = 0;
-        for (;;) {
-          bool all = true;
+        for (int c = 0; c < 4; ++c) off[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            if (!ok[c]) {
-              if (all_written(v[c])) ok[c] = true;
-              else all = false;
+        for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
+        int low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
+        if (tl_on && r0 == 0) ts5 = wall_clock64();
+        if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0) {
+          // slow path: some producer has not published yet; poll again (bounded)
+          int spins = 0;
+          while (low == (int)kSentinelBits) {
+            ++spins;
+            ++repolls;
+            if (spins > p.spin_limit ||
+                ((spins & 1023) == 0 && __builtin_amdgcn_raw_buffer_load_b32(ctrl, kCtrlStatus * 4, 0, kAuxCoherent) != 0)) {
+              failed = true;
+              break;
             }
-          }
-          if (all) break;
-          ++spins;
-          if (spins > p.spin_limit ||
-              ((spins & 1023) == 0 && __builtin_amdgcn_raw_buffer_load_b32(ctrl, kCtrlStatus * 4, 0, kAuxCoherent) != 0)) {
-            failed = true;
-            break;
-          }
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const int ci = base + c * block;
-            if (!ok[c]) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, slot_byte + ci * 16, 0, kAuxCoherent);
+            for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
+            low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
           }
         }
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int ci = base + c * block;
-          if (ci < n4) *reinterpret_cast<i32x4*>(dst + ci * 16) = v[c];
-        }
-        if (failed) break;
+        for (int c = 0; c < 4; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
       }
     }
+    if (tl_on) ts6 = wall_clock64();
     if (failed) {
       s_abort[t & 1] = 1;
       __hip_atomic_store(p.ctrl + kCtrlStatus, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -305,6 +408,27 @@ __global__ __launch_bounds__(NW >= 48 ? 512 : 1024) void persistent_kernel(const
     __syncthreads();
     if (s_abort[t & 1]) break;   // every wave of the workgroup leaves together; other workgroups see the status word
     cur ^= 1;
+    if (tl_on) {
+      const long long ts7 = wall_clock64();
+      if (lane == 0) {
+        s_tl[0] += (unsigned long long)(ts1 - ts0);   // operate (issue)
+        s_tl[1] += (unsigned long long)(ts2 - ts1);   // reduce + epilogue arithmetic
+        s_tl[2] += (unsigned long long)(ts3 - ts2);   // publish, outputs, re-arm, next b' prefetch
+        s_tl[4] += (unsigned long long)(ts4 - ts3);   // back-off before the first poll
+        s_tl[5] += (unsigned long long)(ts5 - ts4);   // first poll in flight
+        s_tl[6] += (unsigned long long)(ts6 - ts5);   // re-polls until every chunk is valid, LDS writes
+        s_tl[7] += (unsigned long long)(ts7 - ts6);   // wait for the other waves of the workgroup
+        s_tl[8] += repolls;
+        s_tl[9] += 1ull;                              // steps counted
+      }
+    }
+  }
+  if (tl_on && lane == 0) {
+    s_tl[10] = (unsigned long long)tl_clock_cost;
+    s_tl[11] = (unsigned long long)((long long)clock64() - tl_launch_core);
+    s_tl[12] = (unsigned long long)((long long)wall_clock64() - tl_launch_wall);
+#pragma unroll
+    for (int i = 0; i < kTimelineSlots; ++i) p.timeline[(size_t)wg * kTimelineSlots + i] += s_tl[i];
   }
 }
 
@@ -344,9 +468,9 @@ __global__ __launch_bounds__(256) void stepwise_kernel(const StepArgs p) {
   for (int b = 0; b < B; ++b) {
     if constexpr (LSTM) {
       const float cp = p.c_prev ? p.c_prev[(size_t)b * H + unit] : 0.0f;
-      const float c = sigmoidf_(pre[1][b]) * cp + sigmoidf_(pre[0][b]) * tanhf(pre[2][b]);
+      const float c = sigmoidf_(pre[1][b]) * cp + sigmoidf_(pre[0][b]) * tanhf_(pre[2][b]);
       p.c_cur[(size_t)b * H + unit] = c;
-      p.h_cur[(size_t)b * H + unit] = sigmoidf_(pre[3][b]) * tanhf(c) + 0.0f;
+      p.h_cur[(size_t)b * H + unit] = sigmoidf_(pre[3][b]) * tanhf_(c) + 0.0f;
     } else {
       p.h_cur[(size_t)b * H + unit] = activate(p.act, pre[0][b]);
     }

@@ -73,7 +73,7 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   for (int i = 0; i < kNumTemplateWords; ++i) if (kTemplateWords[i] >= need) { tw = kTemplateWords[i]; break; }
 
   const int wt = total_waves(L);
-  const int wave_cap = tw >= 48 ? 8 : kMaxWaves;   // the 48/64-slot kernels are built for at most 512 threads
+  const int wave_cap = tw >= 48 ? 4 : kMaxWaves;   // the 48/64-slot kernels are built for at most 256 threads
   int waves = opt ? opt->waves : 0;
   int grid = opt ? opt->grid : 0;
   if (waves < 0 || waves > kMaxWaves || grid < 0) return SPRNN_ERR_INVALID;
@@ -89,7 +89,7 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   m->col_stride = 4 * std::min(batch, 4);
   const int64_t plane = (int64_t)hidden * m->col_stride;          // batch 8 keeps two planes of 4 samples
   const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
-  if (2 * hb + 16 > kLdsLimit) return SPRNN_ERR_CAPACITY;   // two copies of h and 16 bytes of flags
+  if (2 * hb + 256 > kLdsLimit) return SPRNN_ERR_CAPACITY;   // two copies of h and a small tail of flags
   m->h_bytes = (int)hb;
   m->lds_bytes = (int)(2 * hb);
   int shift = 0;
@@ -106,6 +106,7 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   m->balance = balance;
   m->poll_delay = opt ? opt->poll_delay : 0;
   m->spin_limit = (opt && opt->spin_limit > 0) ? opt->spin_limit : (1 << 22);
+  m->timeline = (opt && opt->timeline) ? 1 : 0;
   return SPRNN_OK;
 }
 

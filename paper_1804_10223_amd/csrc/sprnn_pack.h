@@ -15,7 +15,7 @@
 namespace sprnn {
 
 constexpr int kWave = 64;          // lanes per wavefront on gfx950
-constexpr int kMaxWaves = 16;      // wavefronts per workgroup (1024 threads)
+constexpr int kMaxWaves = 12;      // wavefronts per workgroup (768 threads: 168 registers per lane)
 constexpr int kRingSlots = 4;      // exchange ring depth
 constexpr int kLdsLimit = 160 * 1024;
 constexpr uint32_t kSentinel = 0x80000000u;  // -0.0f: "not written yet" (Section 4.2)
@@ -27,7 +27,7 @@ constexpr int kNumTemplateWords = 6;
 struct Mapping {
   int hidden = 0, rows = 0, batch = 0, cell = 0;
   int grid = 0, waves = 0, block = 0, lanes_per_row = 0;
-  int sync = SPRNN_SYNC_TAGGED, bank_aware = 1, balance = 2, poll_delay = 0, spin_limit = 0;
+  int sync = SPRNN_SYNC_TAGGED, bank_aware = 1, balance = 2, poll_delay = 0, spin_limit = 0, timeline = 0;
   int template_words = 0;    // NW of the kernel instantiation
   int words_max = 0;         // largest per-lane word count actually used
   int col_stride = 0;        // bytes between consecutive columns of h in LDS (4 * min(B, 4))

@@ -130,7 +130,7 @@ def test_unsupported_and_capacity_errors():
     with pytest.raises(binding.SprnnError) as e:
         binding.pack_host(40, 2, "relu", w.row_ptr, w.col_idx, w.val_bits, lanes_per_row=3)
     assert e.value.code == binding.SPRNN_ERR_INVALID
-    # a grid that cannot hold the rows with 16 wavefronts per workgroup
+    # a grid that cannot hold the rows with 12 wavefronts per workgroup
     big = wl.make_workload("p", "relu", 4096, 1, 1, 0.01, seed=5)
     with pytest.raises(binding.SprnnError) as e:
         binding.pack_host(4096, 1, "relu", big.row_ptr, big.col_idx, big.val_bits, grid=1, lanes_per_row=64)
@@ -158,5 +158,5 @@ def test_auto_mapping_of_the_five_configs():
         info = binding.pack_host(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits)[3]
         for k, v in e.items():
             assert info[k] == v, (name, k, info)
-        assert info["grid"] <= 256 and info["waves"] <= 16 and info["lds_bytes"] <= 160 * 1024
+        assert info["grid"] <= 256 and info["waves"] <= 12 and info["lds_bytes"] <= 160 * 1024
         assert info["words_per_lane_max"] <= info["template_words"]

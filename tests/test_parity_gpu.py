@@ -78,7 +78,7 @@ SMALL = [
     ("relu", 500, 4, 10, 0.2, "poisson", {"balance": 2}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"bank_aware": 2}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"sync": "barrier"}),
-    ("relu", 500, 1, 10, 0.2, "fixed", {"sync": "barrier", "grid": 5}),
+    ("relu", 500, 1, 10, 0.2, "fixed", {"sync": "barrier", "grid": 6}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"poll_delay": -1}),
     ("lstm", 64, 8, 9, 0.3, "fixed", {}),
     ("lstm", 100, 4, 7, 0.2, "poisson", {}),
