@@ -192,6 +192,16 @@ def main():
             table.append(row)
             log("  %s" % json.dumps(row))
 
+    # A plain device-to-device copy of known size (256 MiB read + 256 MiB written) so that hardware-counter
+    # runs of this same command have a reference dispatch to scale FETCH_SIZE / WRITE_SIZE with.
+    calib = torch.empty(64 << 20, dtype=torch.float32, device="cuda")
+    calib2 = torch.empty_like(calib)
+    calib.fill_(1.0)
+    torch.cuda.synchronize()
+    calib2.copy_(calib)
+    torch.cuda.synchronize()
+    del calib, calib2
+
     cpu = None
     if not args.no_cpu:
         log("timing the CPU oracle on the host cores ...")
@@ -222,7 +232,10 @@ def main():
             "peak": roof["t_roof_us"],
             "unit": "us/timestep (lower is better; frac = peak/achieved)",
             "frac": roof["t_roof_us"] / us_per_ts,
-            "traffic": None,
+            # HBM bytes per launch (fetch + write) from the committed rocprofv3 --pmc passes of this command,
+            # scaled by the 256 MiB calibration copy (profiles/persistent_kernel_cfg3.md); cfg3 only
+            "traffic": (124.9e6 + 54.5e6) if args.config == "cfg3" else None,
+            "traffic_algorithmic": 4.0 * info["padded_words"] + 4.0 * w.x.size + 4.0 * T * w.batch * w.hidden,
             "t_operate_us": roof["t_operate_us"], "t_handoff_us": roof["t_handoff_us"], "t_fill_us": roof["t_fill_us"],
             "lds_bytes_per_timestep": roof["lds_bytes_per_step"],
             "lds_achieved_TBps": roof["lds_bytes_per_step"] / (us_per_ts * 1e-6) / 1e12,
