@@ -13,7 +13,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsprnn.so")
+LIB_PATH = os.environ.get("SPRNN_LIBRARY") or os.path.join(_HERE, "libsprnn.so")   # override: A/B of builds
 
 SPRNN_OK = 0
 SPRNN_ERR_INVALID = -1
@@ -34,7 +34,7 @@ class Options(ctypes.Structure):
     _fields_ = [("grid", ctypes.c_int), ("waves", ctypes.c_int), ("lanes_per_row", ctypes.c_int),
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
-                ("reserved", ctypes.c_int * 7)]
+                ("fill_waves", ctypes.c_int), ("reserved", ctypes.c_int * 6)]
 
 
 class Info(ctypes.Structure):

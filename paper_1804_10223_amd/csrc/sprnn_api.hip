@@ -33,6 +33,7 @@ struct sprnn_handle_s {
   uint16_t* d_val = nullptr;
   uint32_t step_base = 0;        // global step index at which the next forward starts
   uint32_t barrier_base = 0;     // barrier arrivals so far (grid-barrier mode)
+  bool adapt_delay = false;      // the kernel tunes the poll back-off itself (options.poll_delay == 0)
   bool poisoned = false;         // a watchdog trip was observed: the ring no longer holds a consistent state
 };
 
@@ -88,10 +89,9 @@ void release(sprnn_handle_s* h) {
   delete h;
 }
 
-// The default back-off before a step's first poll: polling a line before its producer has written it
-// costs a second miss once the write lands, so waiting roughly one store-to-visibility time first is
-// faster (in units of s_sleep(1) = 64 clocks).
-int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 12 : 0; }
+// Starting value of the back-off before a step's first poll (units of s_sleep(1) = 64 clocks): roughly one
+// store-to-visibility time.  With poll_delay = 0 the kernel adapts it per wavefront from there.
+int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 10 : 0; }
 
 }  // namespace
 
@@ -137,7 +137,6 @@ int sprnn_pack_host(int hidden, int batch, int activation, const int32_t* row_pt
     *words = nullptr; *lane_row = nullptr; *lane_words = nullptr;
     return SPRNN_ERR_CAPACITY;
   }
-  if (P.map.poll_delay == 0) P.map.poll_delay = default_poll_delay(P.map);
   fill_info(P.map, 0, lds_pass_factor(P), info);
   return SPRNN_OK;
 }
@@ -168,6 +167,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   sprnn_handle_s* h = new (std::nothrow) sprnn_handle_s;
   if (!h) return SPRNN_ERR_CAPACITY;
   h->map = P.map;
+  h->adapt_delay = h->map.poll_delay == 0 && h->map.grid > 1;
   if (h->map.poll_delay == 0) h->map.poll_delay = default_poll_delay(h->map);
   if (h->map.poll_delay < 0) h->map.poll_delay = 0;
   h->device = device_id;
@@ -245,7 +245,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
     a.timeline = h->d_timeline;
     a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
-    a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
+    a.poll_delay = m.poll_delay; a.adapt_delay = h->adapt_delay ? 1 : 0; a.spin_limit = m.spin_limit; a.sync = m.sync;
     a.step_base = h->step_base; a.barrier_base = h->barrier_base;
     void* args[] = {&a};
     hipError_t e = hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);

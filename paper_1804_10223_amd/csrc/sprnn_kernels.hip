@@ -31,36 +31,48 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t w) {
   return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
 }
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-  const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
-  return v + __builtin_bit_cast(float, moved);
-}
+// One DPP step of the row reduction applied to all B partial sums: v = v + dpp(v), in place, as a single
+// v_add_f32_dpp per value.  Rows that the row mask disables keep their value.  The B chains are independent,
+// so one `s_nop 1` per step covers the two wait states a DPP read needs after a VALU write of its source.
+#define SPRNN_DPP_STEP(NAME, CTRL)                                                                              \
+  template <int B>                                                                                             \
+  __device__ __forceinline__ void NAME(float (&a)[B]) {                                                        \
+    if constexpr (B == 1) {                                                                                    \
+      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL : "+v"(a[0]));                                  \
+    } else if constexpr (B == 2) {                                                                             \
+      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL "\n\tv_add_f32_dpp %1, %1, %1 " CTRL            \
+                   : "+v"(a[0]), "+v"(a[1]));                                                                  \
+    } else if constexpr (B == 4) {                                                                             \
+      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL "\n\tv_add_f32_dpp %1, %1, %1 " CTRL            \
+                   "\n\tv_add_f32_dpp %2, %2, %2 " CTRL "\n\tv_add_f32_dpp %3, %3, %3 " CTRL                    \
+                   : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));                                          \
+    } else {                                                                                                   \
+      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL "\n\tv_add_f32_dpp %1, %1, %1 " CTRL            \
+                   "\n\tv_add_f32_dpp %2, %2, %2 " CTRL "\n\tv_add_f32_dpp %3, %3, %3 " CTRL                    \
+                   "\n\tv_add_f32_dpp %4, %4, %4 " CTRL "\n\tv_add_f32_dpp %5, %5, %5 " CTRL                    \
+                   "\n\tv_add_f32_dpp %6, %6, %6 " CTRL "\n\tv_add_f32_dpp %7, %7, %7 " CTRL                    \
+                   : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])); \
+    }                                                                                                          \
+  }
+SPRNN_DPP_STEP(dpp_xor1, "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+SPRNN_DPP_STEP(dpp_xor2, "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+SPRNN_DPP_STEP(dpp_half_mirror, "row_half_mirror row_mask:0xf bank_mask:0xf")
+SPRNN_DPP_STEP(dpp_mirror, "row_mirror row_mask:0xf bank_mask:0xf")
+SPRNN_DPP_STEP(dpp_bcast15, "row_bcast:15 row_mask:0xa bank_mask:0xf")
+SPRNN_DPP_STEP(dpp_bcast31, "row_bcast:31 row_mask:0xc bank_mask:0xf")
+#undef SPRNN_DPP_STEP
 
 // Sum over the L consecutive lanes (L a power of two, aligned) that share a row.  The LAST lane of the group
 // ends up with the total (for L <= 16 every lane does).  All steps are DPP modifiers on VALU adds: butterflies
 // inside a row of 16 lanes, then row_bcast:15 / row_bcast:31 to carry row sums into the following rows.
-template <int L>
-__device__ __forceinline__ float group_sum(float v) {
-  if constexpr (L >= 2) v = dpp_add<0xB1>(v);     // quad_perm [1,0,3,2]
-  if constexpr (L >= 4) v = dpp_add<0x4E>(v);     // quad_perm [2,3,0,1]
-  if constexpr (L >= 8) v = dpp_add<0x141>(v);    // row_half_mirror: the other quad of the octet
-  if constexpr (L >= 16) v = dpp_add<0x140>(v);   // row_mirror: the other octet of the row of 16
-  if constexpr (L >= 32) {                        // rows 1 and 3 add the sum of the row before them
-    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xa, 0xf, false);
-    v += __builtin_bit_cast(float, moved);
-  }
-  if constexpr (L >= 64) {                        // rows 2 and 3 add lane 31 (= rows 0 + 1)
-    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xc, 0xf, false);
-    v += __builtin_bit_cast(float, moved);
-  }
-  return v;
-}
-
 template <int L, int B>
 __device__ __forceinline__ void group_sum_all(float (&acc)[B]) {
-#pragma unroll
-  for (int b = 0; b < B; ++b) acc[b] = group_sum<L>(acc[b]);
+  if constexpr (L >= 2) dpp_xor1<B>(acc);          // the neighbour inside the pair
+  if constexpr (L >= 4) dpp_xor2<B>(acc);          // the other pair of the quad
+  if constexpr (L >= 8) dpp_half_mirror<B>(acc);   // the other quad of the octet
+  if constexpr (L >= 16) dpp_mirror<B>(acc);       // the other octet of the row of 16
+  if constexpr (L >= 32) dpp_bcast15<B>(acc);      // rows 1 and 3 add the row before them
+  if constexpr (L >= 64) dpp_bcast31<B>(acc);      // rows 2 and 3 add lane 31 (= rows 0 + 1)
 }
 
 // One jump on the (kernel-uniform) lanes-per-row, then straight-line DPP code.
@@ -263,6 +275,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   const int last_chunk = n4 - 1;
   const int chunk_rounds = (n4 + block - 1) / block;
   int cur = 0;
+  int delay = p.poll_delay;   // back-off before a step's first poll, in units of s_sleep(1) = 64 clocks
   for (int t = 0; t < p.T; ++t) {
     const uint32_t g = p.step_base + (uint32_t)t;         // global step index: the slot number is the timestep tag
     const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
@@ -367,8 +380,9 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         *reinterpret_cast<i32x4*>(dst + ci * 16) = v;
       }
     } else {
-      for (int d = 0; d < p.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
+      for (int d = 0; d < delay; ++d) __builtin_amdgcn_s_sleep(1);
       if (tl_on) ts4 = wall_clock64();
+      bool early = false;
       // Four chunks per lane are in flight at a time.  Chunk indices past the end are clamped to the last
       // chunk (a few lanes then copy it twice), which keeps this path free of per-lane branches.
       for (int r0 = 0; r0 < chunk_rounds; r0 += 4) {
@@ -382,6 +396,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         if (tl_on && r0 == 0) ts5 = wall_clock64();
         if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0) {
           // slow path: some producer has not published yet; poll again (bounded)
+          early = true;
           int spins = 0;
           while (low == (int)kSentinelBits) {
             ++spins;
@@ -398,6 +413,14 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
+      }
+      // Adapt the back-off (per wavefront): polling a line before it is written costs a second miss once the
+      // write lands, far more than waiting a little too long, so lengthen quickly and shorten slowly.
+      if (p.adapt_delay) {
+        const bool any_early = __builtin_amdgcn_ballot_w64(early) != 0;   // wave-uniform, keeps `delay` in an SGPR
+        if (any_early) delay = min(delay + 2, 64);
+        else if ((t & 7) == 7) delay = max(delay - 1, 0);
+        delay = __builtin_amdgcn_readfirstlane(delay);
       }
     }
     if (tl_on) ts6 = wall_clock64();

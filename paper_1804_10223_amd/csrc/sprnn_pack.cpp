@@ -84,7 +84,13 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   if ((int64_t)grid * waves < wt) return SPRNN_ERR_CAPACITY;
 
   m->hidden = hidden; m->rows = rows; m->batch = batch; m->cell = cell;
-  m->grid = grid; m->waves = waves; m->block = waves * kWave; m->lanes_per_row = L;
+  // Wavefronts beyond the ones that own rows only help with copying h into LDS (more loads in flight).
+  int total = waves;
+  if (opt && opt->fill_waves > 0) {
+    if (opt->fill_waves > wave_cap) return SPRNN_ERR_INVALID;
+    total = std::max(waves, opt->fill_waves);
+  }
+  m->grid = grid; m->row_waves = waves; m->waves = total; m->block = total * kWave; m->lanes_per_row = L;
   m->template_words = tw;
   m->col_stride = 4 * std::min(batch, 4);
   const int64_t plane = (int64_t)hidden * m->col_stride;          // batch 8 keeps two planes of 4 samples
@@ -250,14 +256,18 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
     for (int w = 0; w < nw; ++w) {
       const int round = w / m.grid, idx = w % m.grid;
       const int wg = (round & 1) ? (m.grid - 1 - idx) : idx;
-      const int gw = wg * m.waves + round;        // round < waves because grid * waves >= nw
+      const int gw = wg * m.waves + round;        // round < row_waves because grid * row_waves >= nw
       for (int s = 0; s < upw; ++s) {
         const int i = w * upw + s;
         if (i < units) wave_units[(size_t)gw * upw + s] = order[i];
       }
     }
   } else {
-    for (int u = 0; u < units; ++u) wave_units[u] = u;   // contiguous: global wave = u / upw, slot = u % upw
+    for (int u = 0; u < units; ++u) {           // contiguous rows: row-owning wavefront u / upw, slot u % upw
+      const int cw = u / upw;
+      const int gw = (cw / m.row_waves) * m.waves + cw % m.row_waves;
+      wave_units[(size_t)gw * upw + u % upw] = u;
+    }
   }
 
   Packed& P = *out;

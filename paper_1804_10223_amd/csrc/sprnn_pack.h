@@ -26,7 +26,7 @@ constexpr int kNumTemplateWords = 6;
 
 struct Mapping {
   int hidden = 0, rows = 0, batch = 0, cell = 0;
-  int grid = 0, waves = 0, block = 0, lanes_per_row = 0;
+  int grid = 0, waves = 0, row_waves = 0, block = 0, lanes_per_row = 0;   // waves = all, row_waves = those owning rows
   int sync = SPRNN_SYNC_TAGGED, bank_aware = 1, balance = 2, poll_delay = 0, spin_limit = 0, timeline = 0;
   int template_words = 0;    // NW of the kernel instantiation
   int words_max = 0;         // largest per-lane word count actually used
