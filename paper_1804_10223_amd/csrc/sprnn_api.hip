@@ -33,7 +33,6 @@ struct sprnn_handle_s {
   uint16_t* d_val = nullptr;
   uint32_t step_base = 0;        // global step index at which the next forward starts
   uint32_t barrier_base = 0;     // barrier arrivals so far (grid-barrier mode)
-  bool adapt_delay = false;      // the kernel tunes the poll back-off itself (options.poll_delay == 0)
   bool poisoned = false;         // a watchdog trip was observed: the ring no longer holds a consistent state
 };
 
@@ -89,9 +88,9 @@ void release(sprnn_handle_s* h) {
   delete h;
 }
 
-// Starting value of the back-off before a step's first poll (units of s_sleep(1) = 64 clocks): roughly one
-// store-to-visibility time.  With poll_delay = 0 the kernel adapts it per wavefront from there.
-int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 10 : 0; }
+// Default back-off before a step's first poll (units of s_sleep(1) = 64 clocks): the spread of the workgroups'
+// publish times plus the time a store needs to reach the memory side, measured on MI355X.
+int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 12 : 0; }
 
 }  // namespace
 
@@ -167,14 +166,13 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   sprnn_handle_s* h = new (std::nothrow) sprnn_handle_s;
   if (!h) return SPRNN_ERR_CAPACITY;
   h->map = P.map;
-  h->adapt_delay = h->map.poll_delay == 0 && h->map.grid > 1;
   if (h->map.poll_delay == 0) h->map.poll_delay = default_poll_delay(h->map);
   if (h->map.poll_delay < 0) h->map.poll_delay = 0;
   h->device = device_id;
   h->num_cus = prop.multiProcessorCount;
   h->pass_factor = lds_pass_factor(P);
   const Mapping& m = h->map;
-  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell == SPRNN_CELL_LSTM);
+  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell == SPRNN_CELL_LSTM, m.timeline != 0);
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
@@ -245,13 +243,13 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
     a.timeline = h->d_timeline;
     a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
-    a.poll_delay = m.poll_delay; a.adapt_delay = h->adapt_delay ? 1 : 0; a.spin_limit = m.spin_limit; a.sync = m.sync;
+    a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
     a.step_base = h->step_base; a.barrier_base = h->barrier_base;
     void* args[] = {&a};
     hipError_t e = hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
     h->step_base += (uint32_t)tn;
-    h->barrier_base += (uint32_t)(tn - 1) * (uint32_t)m.grid;
+    h->barrier_base += (uint32_t)(tn - 1) * (uint32_t)m.grid;   // one barrier before every step but the first
   }
   return SPRNN_OK;
 }

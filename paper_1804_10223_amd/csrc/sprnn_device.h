@@ -30,7 +30,7 @@ struct KernelArgs {
   float* h_out;               // [T][B][H]
   float* c_out;               // [T][B][H] (LSTM)
   unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)
-  int hidden, T, lanes_per_row, act, h_bytes, poll_delay, adapt_delay, spin_limit, sync;
+  int hidden, T, lanes_per_row, act, h_bytes, poll_delay, spin_limit, sync;
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
   uint32_t barrier_base;      // barrier arrivals before this call
 };
@@ -47,7 +47,7 @@ struct StepArgs {
   int hidden, act;
 };
 
-const void* persistent_kernel_for(int batch, int template_words, bool lstm);
+const void* persistent_kernel_for(int batch, int template_words, bool lstm, bool timeline);
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream);
 hipError_t launch_fill(uint32_t* dst, uint32_t value, size_t n, hipStream_t stream);
 

@@ -194,7 +194,47 @@ __device__ __forceinline__ void ring_store(__amdgpu_buffer_rsrc_t ring, int voff
 
 constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer this kernel addresses
 
-template <int B, int NW, bool LSTM>
+// Vanilla-cell epilogue for all B samples: one jump on the (kernel-uniform) activation, then straight-line code.
+template <int B>
+__device__ __forceinline__ void activate_all(int act, const float (&acc)[B], const float (&x)[B], float (&h)[B]) {
+  if (act == SPRNN_ACT_RELU) {
+#pragma unroll
+    for (int b = 0; b < B; ++b) h[b] = fmaxf(acc[b] + x[b], 0.0f) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
+  } else if (act == SPRNN_ACT_TANH) {
+#pragma unroll
+    for (int b = 0; b < B; ++b) h[b] = tanhf_(acc[b] + x[b]) + 0.0f;
+  } else {
+#pragma unroll
+    for (int b = 0; b < B; ++b) h[b] = (acc[b] + x[b]) + 0.0f;
+  }
+}
+
+// The n_w (wavefront-uniform) packed words of a lane against one copy of h: gathers in groups of four so the
+// LDS reads are issued back to back; no early exit, so every register index stays static.
+template <int B, int NW>
+__device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w,
+                                        const unsigned char* hb, int plane_bytes) {
+#pragma unroll
+  for (int k = 0; k < NW; k += 4) {
+    if (k + 4 <= n_w) {
+      mac_words<B, 4>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+    } else if (k < n_w) {   // ragged tail of 1..3 words
+      const int rem = n_w - k;
+      if (rem == 3) mac_words<B, 3>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+      else if (rem == 2) mac_words<B, 2>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+      else mac_words<B, 1>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+    }
+  }
+}
+
+// Timestamps of the optional phase timeline (TL): wall-clock reads that vanish from the TL = false kernels.
+template <bool TL>
+__device__ __forceinline__ long long tick(bool on) {
+  if constexpr (TL) return on ? (long long)wall_clock64() : 0;
+  return 0;
+}
+
+template <int B, int NW, bool LSTM, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const KernelArgs p) {
   extern __shared__ __align__(16) unsigned char lds[];   // [h copy 0][h copy 1][abort flags][timeline]
   // abort flags, indexed by step parity so that a fast wave's next-step flag cannot be read one step early
@@ -233,14 +273,12 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   const int ring_voff = unit_leader ? unit * (B >= 4 ? 16 : 4 * B) : kOutOfRange;
 
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
-  const __amdgpu_buffer_rsrc_t ctrl = __builtin_amdgcn_make_buffer_rsrc(p.ctrl, 0, 256, kBufWord3);
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * R * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
-  const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(LSTM ? p.c_out : p.h_out, 0, p.T * B * H * 4, kBufWord3);
 
   // ---- h_0 into LDS copy 0, cell state into registers
   if (tid < 2) s_abort[tid] = 0;
-  if (tid < kTimelineSlots) s_tl[tid] = 0ull;
+  if (TL && tid < kTimelineSlots) s_tl[tid] = 0ull;
   for (int e = tid; e < H * B; e += block) {
     const int j = e / B, b = e % B;
     const float v = p.h0 ? p.h0[(size_t)b * H + j] : 0.0f;
@@ -257,11 +295,22 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   float xn[B];
 #pragma unroll
   for (int b = 0; b < B; ++b) xn[b] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, b * R * 4, 0));
+
+  // ---- the copy of h into LDS: 16-byte chunks, chunk c of a lane is chunk tid + c * block of the slot.
+  // Up to four chunks per lane have their offsets precomputed (the common case: one round of four loads in
+  // flight); indices past the end are clamped to the last chunk (a few lanes then copy it twice), which keeps
+  // the copy free of per-lane branches.
+  const int n4 = p.h_bytes >> 4;               // 16-byte chunks in one copy of h
+  const int last_chunk = n4 - 1;
+  const int chunk_rounds = (n4 + block - 1) / block;
+  int foff[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) foff[c] = min(tid + c * block, last_chunk) * 16;
   __syncthreads();
 
-  const bool tl_on = p.timeline != nullptr && wave == 0;
+  const bool tl_on = TL && p.timeline != nullptr && wave == 0;
   long long tl_launch_core = 0, tl_launch_wall = 0, tl_clock_cost = 0;
-  if (tl_on) {   // cost of reading the clock itself: 16 back-to-back reads
+  if (TL && tl_on) {   // cost of reading the clock itself: 16 back-to-back reads
     const long long c0 = wall_clock64();
     long long c1 = c0;
 #pragma unroll
@@ -271,35 +320,98 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     tl_launch_wall = (long long)wall_clock64();
   }
 
-  const int n4 = p.h_bytes >> 4;               // 16-byte chunks in one copy of h
-  const int last_chunk = n4 - 1;
-  const int chunk_rounds = (n4 + block - 1) / block;
   int cur = 0;
-  int delay = p.poll_delay;   // back-off before a step's first poll, in units of s_sleep(1) = 64 clocks
+  long long tl_prev = 0;
   for (int t = 0; t < p.T; ++t) {
     const uint32_t g = p.step_base + (uint32_t)t;         // global step index: the slot number is the timestep tag
-    const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
-    const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
-    long long ts0 = 0, ts1 = 0, ts2 = 0, ts3 = 0, ts4 = 0, ts5 = 0, ts6 = 0;
-    if (tl_on) ts0 = wall_clock64();
+    long long ts0 = 0, ts1 = 0, ts2 = 0, ts3 = 0, ts4 = 0, ts5 = 0, ts6 = 0, ts7 = 0;
+    unsigned long long repolls = 0;
 
-    // ---- operate: n_w gathers, in groups of four so the LDS reads are issued back to back
-    const unsigned char* hb = lds + cur * p.h_bytes;
+    // ---- load: h_{t-1} (published by every workgroup in step t-1) into the other LDS copy
+    if (t > 0) {
+      const int slot_byte = (int)((g - 1) & (kRingSlotsDev - 1)) * p.h_bytes;
+      unsigned char* dst = lds + (cur ^ 1) * p.h_bytes;
+      bool failed = false;
+      if (p.sync == SPRNN_SYNC_BARRIER) {
+        // grid barrier (Section 3.2): all stores performed, one arrival per workgroup, wait for everyone
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+          __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const uint32_t target = p.barrier_base + (uint32_t)t * (uint32_t)gridDim.x;
+          int spins = 0;
+          for (;;) {
+            const uint32_t seen = __hip_atomic_load(p.ctrl + kCtrlBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((int)(seen - target) >= 0) break;
+            if (++spins > p.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(p.ctrl + kCtrlStatus, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+              failed = true;
+              break;
+            }
+          }
+        }
+        __syncthreads();
+        for (int ci = tid; ci < n4; ci += block) {
+          const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ring, ci * 16, slot_byte, kAuxCoherent);
+          *reinterpret_cast<i32x4*>(dst + ci * 16) = v;
+        }
+      } else {
+        // Polling a line before its producer wrote it installs a stale copy in this XCD's L2 that has to be
+        // invalidated and fetched again, which costs more than waiting a little too long: back off first.
+        for (int d = 0; d < p.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
+        ts4 = tick<TL>(tl_on);
+        for (int r0 = 0; r0 < chunk_rounds; r0 += 4) {
+          int off[4];
+          i32x4 v[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) off[c] = foff[c];
+          if (r0 != 0) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) off[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
+          }
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
+          int low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
+          if (r0 == 0) ts5 = tick<TL>(tl_on);
+          if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0) {
+            // slow path: some producer has not published yet; poll again (bounded)
+            int spins = 0;
+            while (low == (int)kSentinelBits) {
+              ++spins;
+              ++repolls;
+              if (spins > p.spin_limit ||
+                  ((spins & 1023) == 0 && __hip_atomic_load(p.ctrl + kCtrlStatus, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                failed = true;
+                break;
+              }
+#pragma unroll
+              for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
+              low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
+            }
+          }
+#pragma unroll
+          for (int c = 0; c < 4; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
+        }
+      }
+      ts6 = tick<TL>(tl_on);
+      if (failed) {
+        s_abort[t & 1] = 1;
+        __hip_atomic_store(p.ctrl + kCtrlStatus, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      __syncthreads();
+      // every wave of the workgroup leaves together; other workgroups see the status word
+      // (readfirstlane: the flag is the same for every lane, and a scalar exit keeps the loop counter scalar)
+      if (__builtin_amdgcn_readfirstlane(s_abort[t & 1])) break;
+      cur ^= 1;
+      ts7 = tick<TL>(tl_on);
+    }
+    ts0 = tick<TL>(tl_on);
+
+    // ---- operate
     float acc[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) acc[b] = 0.0f;
-#pragma unroll
-    for (int k = 0; k < NW; k += 4) {
-      if (k + 4 <= n_w) {
-        mac_words<B, 4>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
-      } else if (k < n_w) {   // ragged tail of 1..3 words (no early exit: keeps every register index static)
-        const int rem = n_w - k;
-        if (rem == 3) mac_words<B, 3>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
-        else if (rem == 2) mac_words<B, 2>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
-        else mac_words<B, 1>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
-      }
-    }
-    if (tl_on) ts1 = wall_clock64();
+    operate<B, NW>(acc, w_off, w_val, n_w, lds + cur * p.h_bytes, plane_bytes);
+    ts1 = tick<TL>(tl_on);
 
     // ---- reduce over the lanes of the row
     reduce_rows<B>(acc, L);
@@ -322,136 +434,72 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         hv[b] = sigmoidf_(pg[3][b]) * tanhf_(c) + 0.0f;
       }
     } else {
-#pragma unroll
-      for (int b = 0; b < B; ++b) hv[b] = activate(p.act, acc[b] + xn[b]);
+      activate_all<B>(p.act, acc, xn, hv);
     }
-    if (tl_on) ts2 = wall_clock64();
+    ts2 = tick<TL>(tl_on);
 
     // ---- hand-off: publish h_t, write the outputs, re-arm the slot two steps ahead.
     // The re-arm stores issued one step ago must be performed before this step's data can be seen.
+    const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     ring_store<B>(ring, ring_voff, slot_byte, plane_bytes, hv);
     {
       const int out_soff = t * B * H * 4;
 #pragma unroll
-      for (int b = 0; b < B; ++b) {
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hv[b]), hbuf, out_voff, out_soff + b * H * 4, 0);
-        if constexpr (LSTM) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c_state[b]), cbuf, out_voff, out_soff + b * H * 4, 0);
+      for (int b = 0; b < B; ++b) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hv[b]), hbuf, out_voff, out_soff + b * H * 4, 0);
+      if constexpr (LSTM) {
+        const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
+#pragma unroll
+        for (int b = 0; b < B; ++b) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c_state[b]), cbuf, out_voff, out_soff + b * H * 4, 0);
       }
     }
     if (p.sync == SPRNN_SYNC_TAGGED) {
+      const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
       float mark[B];
 #pragma unroll
       for (int b = 0; b < B; ++b) mark[b] = __builtin_bit_cast(float, kSentinelBits);
       ring_store<B>(ring, ring_voff, rearm_byte, plane_bytes, mark);
     }
-    if (t + 1 == p.T) break;
-    {
+    if (t + 1 < p.T) {
       const int x_soff = (t + 1) * B * R * 4;
 #pragma unroll
       for (int b = 0; b < B; ++b) xn[b] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, x_soff + b * R * 4, 0));
     }
-    if (tl_on) ts3 = wall_clock64();
+    ts3 = tick<TL>(tl_on);
 
-    // ---- load h_t for the next step into the other LDS copy
-    unsigned char* dst = lds + (cur ^ 1) * p.h_bytes;
-    bool failed = false;
-    unsigned long long repolls = 0;
-    if (p.sync == SPRNN_SYNC_BARRIER) {
-      // grid barrier (Section 3.2): all stores performed, one arrival per workgroup, wait for everyone
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      if (tid == 0) {
-        __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t target = p.barrier_base + (uint32_t)(t + 1) * (uint32_t)gridDim.x;
-        int spins = 0;
-        for (;;) {
-          const uint32_t seen = __hip_atomic_load(p.ctrl + kCtrlBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if ((int)(seen - target) >= 0) break;
-          if (++spins > p.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(p.ctrl + kCtrlStatus, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-            failed = true;
-            break;
-          }
+    if constexpr (TL) {
+      if (tl_on && lane == 0) {
+        if (t == (p.T >> 1)) {   // absolute times of one step, to compare workgroups with each other
+          s_tl[13] = (unsigned long long)ts2;   // results ready, about to publish
+          s_tl[14] = (unsigned long long)ts4;   // first poll issued
+          s_tl[15] = (unsigned long long)ts7;   // h_{t-1} complete in LDS (after the workgroup barrier)
         }
-      }
-      __syncthreads();
-      for (int ci = tid; ci < n4; ci += block) {
-        const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ring, ci * 16, slot_byte, kAuxCoherent);
-        *reinterpret_cast<i32x4*>(dst + ci * 16) = v;
-      }
-    } else {
-      for (int d = 0; d < delay; ++d) __builtin_amdgcn_s_sleep(1);
-      if (tl_on) ts4 = wall_clock64();
-      bool early = false;
-      // Four chunks per lane are in flight at a time.  Chunk indices past the end are clamped to the last
-      // chunk (a few lanes then copy it twice), which keeps this path free of per-lane branches.
-      for (int r0 = 0; r0 < chunk_rounds; r0 += 4) {
-        int off[4];
-        i32x4 v[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) off[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
-        int low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
-        if (tl_on && r0 == 0) ts5 = wall_clock64();
-        if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0) {
-          // slow path: some producer has not published yet; poll again (bounded)
-          early = true;
-          int spins = 0;
-          while (low == (int)kSentinelBits) {
-            ++spins;
-            ++repolls;
-            if (spins > p.spin_limit ||
-                ((spins & 1023) == 0 && __builtin_amdgcn_raw_buffer_load_b32(ctrl, kCtrlStatus * 4, 0, kAuxCoherent) != 0)) {
-              failed = true;
-              break;
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
-            low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
-          }
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
-      }
-      // Adapt the back-off (per wavefront): polling a line before it is written costs a second miss once the
-      // write lands, far more than waiting a little too long, so lengthen quickly and shorten slowly.
-      if (p.adapt_delay) {
-        const bool any_early = __builtin_amdgcn_ballot_w64(early) != 0;   // wave-uniform, keeps `delay` in an SGPR
-        if (any_early) delay = min(delay + 2, 64);
-        else if ((t & 7) == 7) delay = max(delay - 1, 0);
-        delay = __builtin_amdgcn_readfirstlane(delay);
-      }
-    }
-    if (tl_on) ts6 = wall_clock64();
-    if (failed) {
-      s_abort[t & 1] = 1;
-      __hip_atomic_store(p.ctrl + kCtrlStatus, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (s_abort[t & 1]) break;   // every wave of the workgroup leaves together; other workgroups see the status word
-    cur ^= 1;
-    if (tl_on) {
-      const long long ts7 = wall_clock64();
-      if (lane == 0) {
         s_tl[0] += (unsigned long long)(ts1 - ts0);   // operate (issue)
         s_tl[1] += (unsigned long long)(ts2 - ts1);   // reduce + epilogue arithmetic
         s_tl[2] += (unsigned long long)(ts3 - ts2);   // publish, outputs, re-arm, next b' prefetch
-        s_tl[4] += (unsigned long long)(ts4 - ts3);   // back-off before the first poll
-        s_tl[5] += (unsigned long long)(ts5 - ts4);   // first poll in flight
-        s_tl[6] += (unsigned long long)(ts6 - ts5);   // re-polls until every chunk is valid, LDS writes
-        s_tl[7] += (unsigned long long)(ts7 - ts6);   // wait for the other waves of the workgroup
-        s_tl[8] += repolls;
-        s_tl[9] += 1ull;                              // steps counted
+        if (t > 0 && p.sync == SPRNN_SYNC_TAGGED) {
+          s_tl[4] += (unsigned long long)(ts4 - tl_prev);   // back-off before the first poll
+          s_tl[5] += (unsigned long long)(ts5 - ts4);       // first poll in flight
+          s_tl[6] += (unsigned long long)(ts6 - ts5);       // re-polls until every chunk is valid, LDS writes
+          s_tl[7] += (unsigned long long)(ts7 - ts6);       // wait for the other waves of the workgroup
+          s_tl[8] += repolls;
+        }
+        s_tl[9] += 1ull;                                    // steps counted
       }
+      tl_prev = ts3;
     }
   }
-  if (tl_on && lane == 0) {
-    s_tl[10] = (unsigned long long)tl_clock_cost;
-    s_tl[11] = (unsigned long long)((long long)clock64() - tl_launch_core);
-    s_tl[12] = (unsigned long long)((long long)wall_clock64() - tl_launch_wall);
+  if constexpr (TL) {
+    if (tl_on && lane == 0) {
+      s_tl[10] = (unsigned long long)tl_clock_cost;
+      s_tl[11] = (unsigned long long)((long long)clock64() - tl_launch_core);
+      s_tl[12] = (unsigned long long)((long long)wall_clock64() - tl_launch_wall);
 #pragma unroll
-    for (int i = 0; i < kTimelineSlots; ++i) p.timeline[(size_t)wg * kTimelineSlots + i] += s_tl[i];
+      for (int i = 0; i < kTimelineSlots; ++i) {
+        unsigned long long* dst = p.timeline + (size_t)wg * kTimelineSlots + i;
+        *dst = (i >= 13) ? s_tl[i] : *dst + s_tl[i];
+      }
+    }
   }
 }
 
@@ -506,32 +554,33 @@ __global__ void fill_kernel(uint32_t* dst, uint32_t value, size_t n) {
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int B, bool LSTM>
+template <int B, bool LSTM, bool TL>
 static const void* pick_nw(int nw) {
   switch (nw) {
-    case 8: return (const void*)persistent_kernel<B, 8, LSTM>;
-    case 16: return (const void*)persistent_kernel<B, 16, LSTM>;
-    case 24: return (const void*)persistent_kernel<B, 24, LSTM>;
-    case 32: return (const void*)persistent_kernel<B, 32, LSTM>;
-    case 48: return (const void*)persistent_kernel<B, 48, LSTM>;
-    case 64: return (const void*)persistent_kernel<B, 64, LSTM>;
+    case 8: return (const void*)persistent_kernel<B, 8, LSTM, TL>;
+    case 16: return (const void*)persistent_kernel<B, 16, LSTM, TL>;
+    case 24: return (const void*)persistent_kernel<B, 24, LSTM, TL>;
+    case 32: return (const void*)persistent_kernel<B, 32, LSTM, TL>;
+    case 48: return (const void*)persistent_kernel<B, 48, LSTM, TL>;
+    case 64: return (const void*)persistent_kernel<B, 64, LSTM, TL>;
     default: return nullptr;
   }
 }
 
-template <bool LSTM>
+template <bool LSTM, bool TL>
 static const void* pick_b(int batch, int nw) {
   switch (batch) {
-    case 1: return pick_nw<1, LSTM>(nw);
-    case 2: return pick_nw<2, LSTM>(nw);
-    case 4: return pick_nw<4, LSTM>(nw);
-    case 8: return pick_nw<8, LSTM>(nw);
+    case 1: return pick_nw<1, LSTM, TL>(nw);
+    case 2: return pick_nw<2, LSTM, TL>(nw);
+    case 4: return pick_nw<4, LSTM, TL>(nw);
+    case 8: return pick_nw<8, LSTM, TL>(nw);
     default: return nullptr;
   }
 }
 
-const void* persistent_kernel_for(int batch, int template_words, bool lstm) {
-  return lstm ? pick_b<true>(batch, template_words) : pick_b<false>(batch, template_words);
+const void* persistent_kernel_for(int batch, int template_words, bool lstm, bool timeline) {
+  if (timeline) return lstm ? pick_b<true, true>(batch, template_words) : pick_b<false, true>(batch, template_words);
+  return lstm ? pick_b<true, false>(batch, template_words) : pick_b<false, false>(batch, template_words);
 }
 
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream) {
