@@ -50,7 +50,7 @@ enum {
 typedef struct sprnn_options_s {
   int grid;          /* number of persistent workgroups (<= co-resident capacity)                  */
   int waves;         /* wavefronts (64 lanes) per workgroup, 1..12                                 */
-  int lanes_per_row; /* lanes that share one weight row: 1,2,4,...,64 (<= 16 for the LSTM cell)    */
+  int lanes_per_row; /* lanes that share one weight row: 1,2,4,...,64 (LSTM cell: batch/4 .. 16)   */
   int sync;          /* SPRNN_SYNC_*                                                               */
   int bank_aware;    /* 0 auto, 1 = bank-aware ordering of a row's nonzeros (Section 4.1, App. A),
                         2 = keep CSR order ("naive")                                               */

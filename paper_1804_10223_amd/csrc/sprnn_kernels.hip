@@ -260,17 +260,29 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     w_off[k] = word >> 16;
     w_val[k] = half_bits_to_float(word);
   }
-  // The last lane of a row group receives the reduced sum; for the LSTM the last lane of the unit's fourth
-  // group (gate o) gathers the other three gates from the last lanes of the groups before it.
+  // The last lane of a row group receives the reduced sum and adds b'_t (group leader).
+  // Vanilla cells: the group leader also applies g and stores the B results of its row.
+  // LSTM: the four gate rows of a hidden unit sit in four consecutive groups; the leaders hand their B
+  // pre-activations to "cell lanes" through a small per-wavefront LDS area, so that lane u * B + b owns
+  // sample b of the wavefront's unit slot u: one cell update per lane instead of B in one lane.
   const int row = p.lane_row[(size_t)wg * block + tid];
   const bool group_leader = row >= 0 && (lane & (L - 1)) == L - 1;
-  const bool unit_leader = LSTM ? (row >= 0 && (lane & (4 * L - 1)) == 4 * L - 1) : group_leader;
-  const int unit = LSTM ? (row >= 0 ? row % H : 0) : row;   // hidden-unit index of the row
-  // Per-lane byte offsets for the buffer accesses of the epilogue; lanes without a row point out of range,
-  // where loads return zero and stores are dropped.
   const int x_voff = group_leader ? row * 4 : kOutOfRange;
-  const int out_voff = unit_leader ? unit * 4 : kOutOfRange;
-  const int ring_voff = unit_leader ? unit * (B >= 4 ? 16 : 4 * B) : kOutOfRange;
+  int out_voff, ring_voff;      // per-lane byte offsets of the outputs; lanes that store nothing point out of range,
+  int cell_unit = -1;           // where loads return zero and stores are dropped
+  if constexpr (LSTM) {
+    const int cells = (64 / (4 * L)) * B;   // <= 64: the host keeps L >= B / 4 for this cell
+    if (lane < cells) {
+      const int r = p.lane_row[(size_t)wg * block + (tid & ~63) + (lane / B) * 4 * L];
+      cell_unit = r >= 0 ? r % H : -1;
+    }
+    const int b = lane % B;
+    out_voff = cell_unit >= 0 ? (b * H + cell_unit) * 4 : kOutOfRange;
+    ring_voff = cell_unit >= 0 ? lds_offset<B>(cell_unit, b, H) : kOutOfRange;
+  } else {
+    out_voff = group_leader ? row * 4 : kOutOfRange;
+    ring_voff = group_leader ? row * (B >= 4 ? 16 : 4 * B) : kOutOfRange;
+  }
 
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * R * 4, kBufWord3);
@@ -284,9 +296,11 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     const float v = p.h0 ? p.h0[(size_t)b * H + j] : 0.0f;
     *reinterpret_cast<float*>(lds + lds_offset<B>(j, b, H)) = v;
   }
-  float c_state[B];
-#pragma unroll
-  for (int b = 0; b < B; ++b) c_state[b] = (LSTM && unit_leader && p.c0) ? p.c0[(size_t)b * H + unit] : 0.0f;
+  float c_state = (LSTM && cell_unit >= 0 && p.c0) ? p.c0[(size_t)(lane % B) * H + cell_unit] : 0.0f;
+  // hand-over area of this wavefront: [unit slot][sample][gate] floats, after the flags and the timeline sums
+  float* const stage = reinterpret_cast<float*>(lds + 2 * p.h_bytes + kLdsTailBytes) + (LSTM ? wave * (64 / (4 * L)) * B * 4 : 0);
+  const int stage_write = ((lane / (4 * L)) * B * 4) + ((lane / L) & 3);   // + 4 * sample
+  const int stage_read = min(lane, (64 / (4 * L)) * B - 1) * 4;
 
   // b'_t of this row is fetched one step ahead: a first-touch read from HBM takes about as long as a
   // whole timestep, so the load for step t+1 is issued before step t's wait for h_t.
@@ -416,49 +430,49 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     // ---- reduce over the lanes of the row
     reduce_rows<B>(acc, L);
 
-    // ---- epilogue (every lane computes, only leaders' stores land)
-    float hv[B];
+    // ---- epilogue and hand-off: publish h_t, write the outputs (only the owners' stores land).
+    // The re-arm stores issued one step ago must be performed before this step's data can be seen, hence the wait.
+    const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
     if constexpr (LSTM) {
-      float pg[4][B];
+      if (group_leader) {
 #pragma unroll
-      for (int b = 0; b < B; ++b) {
-        const float pre = acc[b] + xn[b];   // complete pre-activation sits in each gate's group leader
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          pg[q][b] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane - (3 - q) * L) << 2, __builtin_bit_cast(int, pre)));
+        for (int b = 0; b < B; ++b) stage[stage_write + 4 * b] = acc[b] + xn[b];
       }
-#pragma unroll
-      for (int b = 0; b < B; ++b) {
-        const float c = sigmoidf_(pg[1][b]) * c_state[b] + sigmoidf_(pg[0][b]) * tanhf_(pg[2][b]);
-        c_state[b] = c;
-        hv[b] = sigmoidf_(pg[3][b]) * tanhf_(c) + 0.0f;
+      // LDS serves the operations of one wavefront in order: no hardware barrier between these writes and the
+      // read, only a fence that keeps the compiler from moving one across the other
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      const f32x4 gates = *reinterpret_cast<const f32x4*>(stage + stage_read);   // i, f, g, o of this lane's sample
+      const float c = sigmoidf_(gates.y) * c_state + sigmoidf_(gates.x) * tanhf_(gates.z);
+      c_state = c;
+      const float hval = sigmoidf_(gates.w) * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
+      ts2 = tick<TL>(tl_on);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
+      const int out_soff = t * B * H * 4;
+      const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c), cbuf, out_voff, out_soff, 0);
+      if (p.sync == SPRNN_SYNC_TAGGED) {
+        const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
+        __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
       }
     } else {
+      float hv[B];
       activate_all<B>(p.act, acc, xn, hv);
-    }
-    ts2 = tick<TL>(tl_on);
-
-    // ---- hand-off: publish h_t, write the outputs, re-arm the slot two steps ahead.
-    // The re-arm stores issued one step ago must be performed before this step's data can be seen.
-    const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    ring_store<B>(ring, ring_voff, slot_byte, plane_bytes, hv);
-    {
+      ts2 = tick<TL>(tl_on);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      ring_store<B>(ring, ring_voff, slot_byte, plane_bytes, hv);
       const int out_soff = t * B * H * 4;
 #pragma unroll
       for (int b = 0; b < B; ++b) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hv[b]), hbuf, out_voff, out_soff + b * H * 4, 0);
-      if constexpr (LSTM) {
-        const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
+      if (p.sync == SPRNN_SYNC_TAGGED) {
+        const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
+        float mark[B];
 #pragma unroll
-        for (int b = 0; b < B; ++b) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c_state[b]), cbuf, out_voff, out_soff + b * H * 4, 0);
+        for (int b = 0; b < B; ++b) mark[b] = __builtin_bit_cast(float, kSentinelBits);
+        ring_store<B>(ring, ring_voff, rearm_byte, plane_bytes, mark);
       }
-    }
-    if (p.sync == SPRNN_SYNC_TAGGED) {
-      const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
-      float mark[B];
-#pragma unroll
-      for (int b = 0; b < B; ++b) mark[b] = __builtin_bit_cast(float, kSentinelBits);
-      ring_store<B>(ring, ring_voff, rearm_byte, plane_bytes, mark);
     }
     if (t + 1 < p.T) {
       const int x_soff = (t + 1) * B * R * 4;

@@ -58,13 +58,15 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
     return ceil_div(hidden, units_per_wave);   // a unit is one row (vanilla) or one hidden unit's 4 gate rows
   };
 
+  // LSTM: a wavefront's (units x samples) cell updates are spread over its lanes, one each: 64 / (4 L) * B <= 64
+  const int lmin = lstm ? std::max(1, batch / 4) : 1;
   int L = opt ? opt->lanes_per_row : 0;
   if (L != 0) {
-    if (!is_pow2(L) || L > lmax) return SPRNN_ERR_INVALID;
+    if (!is_pow2(L) || L > lmax || L < lmin) return SPRNN_ERR_INVALID;
   } else {
     L = lmax;
-    while (L > 1 && ceil_div(maxnnz, L) < 8) L /= 2;
-    while (L > 1 && total_waves(L) > (int64_t)kMaxWaves * num_cus) L /= 2;
+    while (L > lmin && ceil_div(maxnnz, L) < 8) L /= 2;
+    while (L > lmin && total_waves(L) > (int64_t)kMaxWaves * num_cus) L /= 2;
     while (L < lmax && ceil_div(maxnnz, L) > kTemplateWords[kNumTemplateWords - 1]) L *= 2;
   }
   const int need = ceil_div(maxnnz, L);
@@ -95,7 +97,8 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   m->col_stride = 4 * std::min(batch, 4);
   const int64_t plane = (int64_t)hidden * m->col_stride;          // batch 8 keeps two planes of 4 samples
   const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
-  if (2 * hb + 256 > kLdsLimit) return SPRNN_ERR_CAPACITY;   // two copies of h and a small tail of flags
+  m->stage_bytes = lstm ? total * (kWave / (4 * L)) * batch * 16 : 0;   // [wave][unit slot][sample][4 gates] floats
+  if (2 * hb + 256 + m->stage_bytes > kLdsLimit) return SPRNN_ERR_CAPACITY;   // two copies of h, a small tail of flags, the LSTM hand-over area
   m->h_bytes = (int)hb;
   m->lds_bytes = (int)(2 * hb);
   int shift = 0;

@@ -34,6 +34,7 @@ struct Mapping {
   int index_shift = 0;       // packed index = (col * col_stride) >> index_shift
   int h_bytes = 0;           // bytes of one copy of h in LDS / one ring slot (multiple of 16)
   int lds_bytes = 0;         // 2 * h_bytes
+  int stage_bytes = 0;       // LSTM: per-workgroup LDS area through which gate sums reach the cell lanes
   int64_t nnz = 0, padded_words = 0;
 };
 
