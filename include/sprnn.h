@@ -50,13 +50,13 @@ enum {
 typedef struct sprnn_options_s {
   int grid;          /* number of persistent workgroups (<= co-resident capacity)                  */
   int waves;         /* wavefronts (64 lanes) per workgroup, 1..12                                 */
-  int lanes_per_row; /* lanes that share one weight row: 1,2,4,...,64 (LSTM cell: batch/4 .. 16)   */
+  int lanes_per_row; /* lanes that share one weight row: batch,...,32,64 (<= 16 for the LSTM cell) */
   int sync;          /* SPRNN_SYNC_*                                                               */
   int bank_aware;    /* 0 auto, 1 = bank-aware ordering of a row's nonzeros (Section 4.1, App. A),
                         2 = keep CSR order ("naive")                                               */
   int balance;       /* 0 auto, 1 = rows dealt to workgroups by nonzero count, 2 = contiguous rows */
-  int poll_delay;    /* back-off before the first poll of a step, in units of 64 clocks; 0 auto,
-                        -1 none                                                                    */
+  int poll_delay;    /* back-off before the first poll of a step, in units of 64 clocks; 0 = measured
+                        at create time on a short zero-input run (a few ms), -1 none               */
   int spin_limit;    /* polls before the watchdog gives up (0 = default)                           */
   int timeline;      /* 1 = workgroup 0..grid-1 accumulate per-phase times (see sprnn_read_timeline) */
   int fill_waves;    /* total wavefronts per workgroup when larger than `waves`: the extra ones own no

@@ -88,11 +88,16 @@ void release(sprnn_handle_s* h) {
   delete h;
 }
 
-// Default back-off before a step's first poll (units of s_sleep(1) = 64 clocks): the spread of the workgroups'
-// publish times plus the time a store needs to reach the memory side, measured on MI355X.
-int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 12 : 0; }
+// Fallback back-off before a step's first poll (units of s_sleep(1) = 64 clocks) when the calibration at create
+// time cannot run: the spread of the workgroups' publish times plus the time a store needs to reach the memory
+// side, as measured on MI355X.
+int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 6 : 0; }
 
 }  // namespace
+
+static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                              float* h_out, float* c_out, void* stream);
+static int calibrate_poll_delay(sprnn_handle_s* h);
 
 extern "C" {
 
@@ -166,6 +171,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   sprnn_handle_s* h = new (std::nothrow) sprnn_handle_s;
   if (!h) return SPRNN_ERR_CAPACITY;
   h->map = P.map;
+  const bool calibrate = h->map.poll_delay == 0 && h->map.grid > 1 && h->map.sync == SPRNN_SYNC_TAGGED;
   if (h->map.poll_delay == 0) h->map.poll_delay = default_poll_delay(h->map);
   if (h->map.poll_delay < 0) h->map.poll_delay = 0;
   h->device = device_id;
@@ -210,6 +216,10 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     ok = SPRNN_HIP(upload(&h->d_timeline, zeros.data(), zeros.size()));
   }
   if (!ok || !SPRNN_HIP(hipDeviceSynchronize())) { release(h); return SPRNN_ERR_HIP; }
+  if (calibrate) {
+    const int rc2 = calibrate_poll_delay(h);
+    if (rc2 != SPRNN_OK) { release(h); return rc2; }
+  }
   *out = h;
   return SPRNN_OK;
 }
@@ -252,6 +262,46 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     h->barrier_base += (uint32_t)(tn - 1) * (uint32_t)m.grid;   // one barrier before every step but the first
   }
   return SPRNN_OK;
+}
+
+// The best back-off depends on how far apart the workgroups of this matrix finish a step (row lengths, LDS bank
+// conflicts, cell type).  Polling too early is far more expensive than polling late, and the sweet spot moves
+// from 3 to 12 units between the measured shapes, so it is measured once per handle: a short run on zero input
+// for a handful of candidates, keeping the fastest.  Timing does not depend on the data.
+static int calibrate_poll_delay(sprnn_handle_s* h) {
+  const Mapping& m = h->map;
+  const int T = 48;
+  const size_t xn = (size_t)T * m.batch * m.rows, hn = (size_t)T * m.batch * m.hidden;
+  float *d_x = nullptr, *d_h = nullptr, *d_c = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  const bool lstm = m.cell == SPRNN_CELL_LSTM;
+  bool ok = SPRNN_HIP(hipMalloc((void**)&d_x, xn * 4)) && SPRNN_HIP(hipMemset(d_x, 0, xn * 4)) &&
+            SPRNN_HIP(hipMalloc((void**)&d_h, hn * 4)) && (!lstm || SPRNN_HIP(hipMalloc((void**)&d_c, hn * 4))) &&
+            SPRNN_HIP(hipEventCreate(&e0)) && SPRNN_HIP(hipEventCreate(&e1));
+  int best = h->map.poll_delay;
+  int rc = SPRNN_OK;
+  if (ok) {
+    static const int candidates[] = {2, 3, 4, 6, 8, 10, 12, 16};
+    float best_ms = 0.0f;
+    for (int c : candidates) {
+      h->map.poll_delay = c;
+      float ms = 0.0f;
+      for (int rep = 0; rep < 2 && rc == SPRNN_OK; ++rep) {   // the first run of a setting warms up, the second is timed
+        if (!SPRNN_HIP(hipEventRecord(e0, nullptr))) { ok = false; break; }
+        rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, d_c, nullptr);
+        if (rc != SPRNN_OK) break;
+        if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
+      }
+      if (!ok || rc != SPRNN_OK) break;
+      if (best_ms == 0.0f || ms < best_ms) { best_ms = ms; best = c; }
+    }
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(d_x); (void)hipFree(d_h); (void)hipFree(d_c);
+  h->map.poll_delay = (ok && rc == SPRNN_OK) ? best : default_poll_delay(h->map);
+  if (rc == SPRNN_OK && sprnn_check(h) != SPRNN_OK) rc = SPRNN_ERR_STATE;
+  return rc;   // allocation or timing trouble is not fatal: the fallback value is used
 }
 
 int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream) {

@@ -31,62 +31,99 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t w) {
   return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
 }
 
-// One DPP step of the row reduction applied to all B partial sums: v = v + dpp(v), in place, as a single
-// v_add_f32_dpp per value.  Rows that the row mask disables keep their value.  The B chains are independent,
-// so one `s_nop 1` per step covers the two wait states a DPP read needs after a VALU write of its source.
-#define SPRNN_DPP_STEP(NAME, CTRL)                                                                              \
-  template <int B>                                                                                             \
-  __device__ __forceinline__ void NAME(float (&a)[B]) {                                                        \
-    if constexpr (B == 1) {                                                                                    \
-      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL : "+v"(a[0]));                                  \
-    } else if constexpr (B == 2) {                                                                             \
-      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL "\n\tv_add_f32_dpp %1, %1, %1 " CTRL            \
-                   : "+v"(a[0]), "+v"(a[1]));                                                                  \
-    } else if constexpr (B == 4) {                                                                             \
-      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL "\n\tv_add_f32_dpp %1, %1, %1 " CTRL            \
-                   "\n\tv_add_f32_dpp %2, %2, %2 " CTRL "\n\tv_add_f32_dpp %3, %3, %3 " CTRL                    \
-                   : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));                                          \
-    } else {                                                                                                   \
-      asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 " CTRL "\n\tv_add_f32_dpp %1, %1, %1 " CTRL            \
-                   "\n\tv_add_f32_dpp %2, %2, %2 " CTRL "\n\tv_add_f32_dpp %3, %3, %3 " CTRL                    \
-                   "\n\tv_add_f32_dpp %4, %4, %4 " CTRL "\n\tv_add_f32_dpp %5, %5, %5 " CTRL                    \
-                   "\n\tv_add_f32_dpp %6, %6, %6 " CTRL "\n\tv_add_f32_dpp %7, %7, %7 " CTRL                    \
-                   : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])); \
-    }                                                                                                          \
+// ---- reduction over the L lanes of a row, scattering the B samples over the lanes (reduce-scatter) -------------
+// Every lane enters with B partial sums (one per sample).  The first log2(B) butterfly stages are halving
+// exchanges: a lane keeps one half of its values and hands the other half to its partner, so after them a
+// lane holds ONE value; the remaining stages are plain butterflies.  At the end every lane of the row holds
+// the complete sum for sample  sample_of_lane<B>(lane)  and nothing else: about 2 B + log2(L) additions per
+// lane instead of B log2(L), and the epilogue (b'_t, activation, stores) handles one value per lane.
+// Partner of stage K is lane ^ (1 << K): quad permutes (K = 0, 1), masked row shifts (K = 2), a row rotation
+// (K = 3) and the row-swap instructions of gfx950 (K = 4, 5).
+template <int K>
+__device__ __forceinline__ float from_partner(float give) {
+  const int g = __builtin_bit_cast(int, give);
+  if constexpr (K == 0) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, g, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+  if constexpr (K == 1) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, g, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+  if constexpr (K == 2) {   // lanes of quads 0, 2 read four lanes up, lanes of quads 1, 3 four lanes down
+    const int up = __builtin_amdgcn_update_dpp(0, g, 0x104, 0xf, 0x5, false);     // row_shl:4, banks 0 and 2
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(up, g, 0x114, 0xf, 0xa, false));   // row_shr:4, banks 1 and 3
   }
-SPRNN_DPP_STEP(dpp_xor1, "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
-SPRNN_DPP_STEP(dpp_xor2, "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
-SPRNN_DPP_STEP(dpp_half_mirror, "row_half_mirror row_mask:0xf bank_mask:0xf")
-SPRNN_DPP_STEP(dpp_mirror, "row_mirror row_mask:0xf bank_mask:0xf")
-SPRNN_DPP_STEP(dpp_bcast15, "row_bcast:15 row_mask:0xa bank_mask:0xf")
-SPRNN_DPP_STEP(dpp_bcast31, "row_bcast:31 row_mask:0xc bank_mask:0xf")
-#undef SPRNN_DPP_STEP
-
-// Sum over the L consecutive lanes (L a power of two, aligned) that share a row.  The LAST lane of the group
-// ends up with the total (for L <= 16 every lane does).  All steps are DPP modifiers on VALU adds: butterflies
-// inside a row of 16 lanes, then row_bcast:15 / row_bcast:31 to carry row sums into the following rows.
-template <int L, int B>
-__device__ __forceinline__ void group_sum_all(float (&acc)[B]) {
-  if constexpr (L >= 2) dpp_xor1<B>(acc);          // the neighbour inside the pair
-  if constexpr (L >= 4) dpp_xor2<B>(acc);          // the other pair of the quad
-  if constexpr (L >= 8) dpp_half_mirror<B>(acc);   // the other quad of the octet
-  if constexpr (L >= 16) dpp_mirror<B>(acc);       // the other octet of the row of 16
-  if constexpr (L >= 32) dpp_bcast15<B>(acc);      // rows 1 and 3 add the row before them
-  if constexpr (L >= 64) dpp_bcast31<B>(acc);      // rows 2 and 3 add lane 31 (= rows 0 + 1)
+  if constexpr (K == 3) return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, g, 0x128, 0xf, 0xf, false));  // row_ror:8
+  return 0.0f;
 }
 
-// One jump on the (kernel-uniform) lanes-per-row, then straight-line DPP code.
+// Plain butterfly across rows of 16 lanes (K = 4) or halves of the wavefront (K = 5): copy, swap the odd rows of
+// one copy with the even rows of the other, add.  (v_permlane16_swap / v_permlane32_swap: VALU, no LDS.)
+template <int K>
+__device__ __forceinline__ float cross_row_sum(float v) {
+  float a = v, b;
+  if constexpr (K == 4) asm volatile("v_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "=&v"(b));
+  else asm volatile("v_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "=&v"(b));
+  return a + b;
+}
+
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+
+// Sample whose sum a lane holds after reduce_scatter: stage K hands the upper half of the value list to the lanes
+// with bit K set.
 template <int B>
-__device__ __forceinline__ void reduce_rows(float (&acc)[B], int L) {
+__device__ __forceinline__ int sample_of_lane(int lane) {
+  int s = 0;
+#pragma unroll
+  for (int k = 0; k < ilog2(B); ++k) s += ((lane >> k) & 1) * (B >> (k + 1));
+  return s;
+}
+
+template <int B, int N, int K>
+__device__ __forceinline__ void halving_stage(float (&v)[B], int lane) {
+  if constexpr (N > 1) {
+    const bool upper = (lane >> K) & 1;
+#pragma unroll
+    for (int j = 0; j < N / 2; ++j) {
+      const float keep = upper ? v[j + N / 2] : v[j];
+      const float give = upper ? v[j] : v[j + N / 2];
+      v[j] = keep + from_partner<K>(give);
+    }
+  }
+}
+
+template <int L, int B>
+__device__ __forceinline__ float reduce_scatter(float (&v)[B], int lane) {
+  static_assert(L >= B, "a row needs at least as many lanes as there are samples");
+  constexpr int SPLITS = ilog2(B), STAGES = ilog2(L);
+  if constexpr (SPLITS >= 1) halving_stage<B, B, 0>(v, lane);
+  if constexpr (SPLITS >= 2) halving_stage<B, B / 2, 1>(v, lane);
+  if constexpr (SPLITS >= 3) halving_stage<B, B / 4, 2>(v, lane);
+  float t = v[0];
+  if constexpr (SPLITS <= 0 && STAGES > 0) t += from_partner<0>(t);
+  if constexpr (SPLITS <= 1 && STAGES > 1) t += from_partner<1>(t);
+  if constexpr (SPLITS <= 2 && STAGES > 3) {
+    // both in-row stages are plain: two rotations sum the four lanes that share lane % 4
+    t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x124, 0xf, 0xf, false));   // row_ror:4
+    t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x128, 0xf, 0xf, false));   // row_ror:8
+  } else {
+    if constexpr (SPLITS <= 2 && STAGES > 2) t += from_partner<2>(t);
+    if constexpr (STAGES > 3) t += from_partner<3>(t);
+  }
+  if constexpr (STAGES > 4) t = cross_row_sum<4>(t);
+  if constexpr (STAGES > 5) t = cross_row_sum<5>(t);
+  return t;
+}
+
+// One jump on the (kernel-uniform) lanes-per-row, then straight-line code.
+template <int B>
+__device__ __forceinline__ float reduce_rows(float (&acc)[B], int L, int lane) {
   switch (L) {
-    case 64: group_sum_all<64, B>(acc); break;
-    case 32: group_sum_all<32, B>(acc); break;
-    case 16: group_sum_all<16, B>(acc); break;
-    case 8: group_sum_all<8, B>(acc); break;
-    case 4: group_sum_all<4, B>(acc); break;
-    case 2: group_sum_all<2, B>(acc); break;
+    case 64: return reduce_scatter<64, B>(acc, lane);
+    case 32: return reduce_scatter<32, B>(acc, lane);
+    case 16: return reduce_scatter<16, B>(acc, lane);
+    case 8: return reduce_scatter<8, B>(acc, lane);
+    case 4: if constexpr (B <= 4) return reduce_scatter<4, B>(acc, lane); else break;
+    case 2: if constexpr (B <= 2) return reduce_scatter<2, B>(acc, lane); else break;
+    case 1: if constexpr (B <= 1) return acc[0]; else break;
     default: break;
   }
+  return 0.0f;
 }
 
 // Logistic function and tanh from the hardware exp2 / reciprocal instructions (about 1 ulp each):
@@ -171,43 +208,7 @@ __device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, 
   for (int j = 0; j < N; ++j) mac_column<B>(acc, wv[j], c[j]);
 }
 
-// Publish the B outputs of one row into a ring slot (same layout as the LDS copy of h).  `voff` is the lane's
-// byte offset of its row inside a slot, or an out-of-range offset for lanes that own no row: the buffer
-// bounds check then drops the store, so no branch is needed.
-template <int B>
-__device__ __forceinline__ void ring_store(__amdgpu_buffer_rsrc_t ring, int voff, int slot_byte, int plane_bytes, const float (&v)[B]) {
-  if constexpr (B == 1) {
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v[0]), ring, voff, slot_byte, kAuxCoherent);
-  } else if constexpr (B == 2) {
-    i32x2 p = {__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1])};
-    __builtin_amdgcn_raw_buffer_store_b64(p, ring, voff, slot_byte, kAuxCoherent);
-  } else if constexpr (B == 4) {
-    i32x4 p = {__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1]), __builtin_bit_cast(int, v[2]), __builtin_bit_cast(int, v[3])};
-    __builtin_amdgcn_raw_buffer_store_b128(p, ring, voff, slot_byte, kAuxCoherent);
-  } else {
-    i32x4 p = {__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1]), __builtin_bit_cast(int, v[2]), __builtin_bit_cast(int, v[3])};
-    i32x4 q = {__builtin_bit_cast(int, v[4]), __builtin_bit_cast(int, v[5]), __builtin_bit_cast(int, v[6]), __builtin_bit_cast(int, v[7])};
-    __builtin_amdgcn_raw_buffer_store_b128(p, ring, voff, slot_byte, kAuxCoherent);
-    __builtin_amdgcn_raw_buffer_store_b128(q, ring, voff, slot_byte + plane_bytes, kAuxCoherent);
-  }
-}
-
 constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer this kernel addresses
-
-// Vanilla-cell epilogue for all B samples: one jump on the (kernel-uniform) activation, then straight-line code.
-template <int B>
-__device__ __forceinline__ void activate_all(int act, const float (&acc)[B], const float (&x)[B], float (&h)[B]) {
-  if (act == SPRNN_ACT_RELU) {
-#pragma unroll
-    for (int b = 0; b < B; ++b) h[b] = fmaxf(acc[b] + x[b], 0.0f) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
-  } else if (act == SPRNN_ACT_TANH) {
-#pragma unroll
-    for (int b = 0; b < B; ++b) h[b] = tanhf_(acc[b] + x[b]) + 0.0f;
-  } else {
-#pragma unroll
-    for (int b = 0; b < B; ++b) h[b] = (acc[b] + x[b]) + 0.0f;
-  }
-}
 
 // The n_w (wavefront-uniform) packed words of a lane against one copy of h: gathers in groups of four so the
 // LDS reads are issued back to back; no early exit, so every register index stays static.
@@ -260,18 +261,20 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     w_off[k] = word >> 16;
     w_val[k] = half_bits_to_float(word);
   }
-  // The last lane of a row group receives the reduced sum and adds b'_t (group leader).
-  // Vanilla cells: the group leader also applies g and stores the B results of its row.
-  // LSTM: the four gate rows of a hidden unit sit in four consecutive groups; the leaders hand their B
-  // pre-activations to "cell lanes" through a small per-wavefront LDS area, so that lane u * B + b owns
-  // sample b of the wavefront's unit slot u: one cell update per lane instead of B in one lane.
+  // After the reduction (reduce_scatter) the first B lanes of a row group each own one sample of the row: they
+  // add b'_t and, for vanilla cells, apply g and store the result ("owner lanes").
+  // LSTM: the four gate rows of a hidden unit sit in four consecutive groups; the owners hand their
+  // pre-activation to "cell lanes" through a small per-wavefront LDS area, so that lane u * B + b owns sample b
+  // of the wavefront's unit slot u: one cell update per lane.
+  // Lanes that load or store nothing point out of range, where loads return zero and stores are dropped.
   const int row = p.lane_row[(size_t)wg * block + tid];
-  const bool group_leader = row >= 0 && (lane & (L - 1)) == L - 1;
-  const int x_voff = group_leader ? row * 4 : kOutOfRange;
-  int out_voff, ring_voff;      // per-lane byte offsets of the outputs; lanes that store nothing point out of range,
-  int cell_unit = -1;           // where loads return zero and stores are dropped
+  const int sample = sample_of_lane<B>(lane);
+  const bool owner = row >= 0 && (lane & (L - 1)) < B;
+  const int x_voff = owner ? (sample * R + row) * 4 : kOutOfRange;
+  int out_voff, ring_voff;
+  int cell_unit = -1;
   if constexpr (LSTM) {
-    const int cells = (64 / (4 * L)) * B;   // <= 64: the host keeps L >= B / 4 for this cell
+    const int cells = (64 / (4 * L)) * B;   // <= 64 because L >= B
     if (lane < cells) {
       const int r = p.lane_row[(size_t)wg * block + (tid & ~63) + (lane / B) * 4 * L];
       cell_unit = r >= 0 ? r % H : -1;
@@ -280,10 +283,9 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     out_voff = cell_unit >= 0 ? (b * H + cell_unit) * 4 : kOutOfRange;
     ring_voff = cell_unit >= 0 ? lds_offset<B>(cell_unit, b, H) : kOutOfRange;
   } else {
-    out_voff = group_leader ? row * 4 : kOutOfRange;
-    ring_voff = group_leader ? row * (B >= 4 ? 16 : 4 * B) : kOutOfRange;
+    out_voff = owner ? (sample * H + row) * 4 : kOutOfRange;
+    ring_voff = owner ? lds_offset<B>(row, sample, H) : kOutOfRange;
   }
-
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * R * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
@@ -299,16 +301,14 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   float c_state = (LSTM && cell_unit >= 0 && p.c0) ? p.c0[(size_t)(lane % B) * H + cell_unit] : 0.0f;
   // hand-over area of this wavefront: [unit slot][sample][gate] floats, after the flags and the timeline sums
   float* const stage = reinterpret_cast<float*>(lds + 2 * p.h_bytes + kLdsTailBytes) + (LSTM ? wave * (64 / (4 * L)) * B * 4 : 0);
-  const int stage_write = ((lane / (4 * L)) * B * 4) + ((lane / L) & 3);   // + 4 * sample
+  const int stage_write = ((lane / (4 * L)) * B + sample) * 4 + ((lane / L) & 3);   // [unit slot][sample][gate]
   const int stage_read = min(lane, (64 / (4 * L)) * B - 1) * 4;
 
   // b'_t of this row is fetched one step ahead: a first-touch read from HBM takes about as long as a
   // whole timestep, so the load for step t+1 is issued before step t's wait for h_t.
   // (scalar offsets select the timestep and the sample; the host keeps one launch below 1 GiB of x, so an
   // out-of-range lane offset stays out of range whatever scalar offset is added to it)
-  float xn[B];
-#pragma unroll
-  for (int b = 0; b < B; ++b) xn[b] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, b * R * 4, 0));
+  float xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, 0, 0));
 
   // ---- the copy of h into LDS: 16-byte chunks, chunk c of a lane is chunk tid + c * block of the slot.
   // Up to four chunks per lane have their offsets precomputed (the common case: one round of four loads in
@@ -371,6 +371,10 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       } else {
         // Polling a line before its producer wrote it installs a stale copy in this XCD's L2 that has to be
         // invalidated and fetched again, which costs more than waiting a little too long: back off first.
+        // The wavefronts of a workgroup finish a step at different times; they wait for each other here, so that
+        // the back-off counts from the moment the whole workgroup has published (the skew inside a workgroup would
+        // otherwise have to be covered by a longer back-off in every workgroup).
+        __syncthreads();
         for (int d = 0; d < p.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
         ts4 = tick<TL>(tl_on);
         for (int r0 = 0; r0 < chunk_rounds; r0 += 4) {
@@ -387,9 +391,9 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
           int low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
           if (r0 == 0) ts5 = tick<TL>(tl_on);
           if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0) {
-            // slow path: some producer has not published yet; poll again (bounded)
+            // slow path: some producer has not published yet; the whole wavefront polls again (bounded)
             int spins = 0;
-            while (low == (int)kSentinelBits) {
+            do {
               ++spins;
               ++repolls;
               if (spins > p.spin_limit ||
@@ -400,7 +404,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
 #pragma unroll
               for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
               low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
-            }
+            } while (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0);
           }
 #pragma unroll
           for (int c = 0; c < 4; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
@@ -427,17 +431,17 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     operate<B, NW>(acc, w_off, w_val, n_w, lds + cur * p.h_bytes, plane_bytes);
     ts1 = tick<TL>(tl_on);
 
-    // ---- reduce over the lanes of the row
-    reduce_rows<B>(acc, L);
+    // ---- reduce over the lanes of the row: every lane ends up with the sum of its own sample
+    const float pre = reduce_rows<B>(acc, L, lane) + xn;
 
     // ---- epilogue and hand-off: publish h_t, write the outputs (only the owners' stores land).
     // The re-arm stores issued one step ago must be performed before this step's data can be seen, hence the wait.
     const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
+    const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
+    const int out_soff = t * B * H * 4;
+    float hval;
     if constexpr (LSTM) {
-      if (group_leader) {
-#pragma unroll
-        for (int b = 0; b < B; ++b) stage[stage_write + 4 * b] = acc[b] + xn[b];
-      }
+      if (owner) stage[stage_write] = pre;
       // LDS serves the operations of one wavefront in order: no hardware barrier between these writes and the
       // read, only a fence that keeps the compiler from moving one across the other
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -445,39 +449,19 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       const f32x4 gates = *reinterpret_cast<const f32x4*>(stage + stage_read);   // i, f, g, o of this lane's sample
       const float c = sigmoidf_(gates.y) * c_state + sigmoidf_(gates.x) * tanhf_(gates.z);
       c_state = c;
-      const float hval = sigmoidf_(gates.w) * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
-      ts2 = tick<TL>(tl_on);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
-      const int out_soff = t * B * H * 4;
+      hval = sigmoidf_(gates.w) * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
       const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
       __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c), cbuf, out_voff, out_soff, 0);
-      if (p.sync == SPRNN_SYNC_TAGGED) {
-        const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
-        __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
-      }
     } else {
-      float hv[B];
-      activate_all<B>(p.act, acc, xn, hv);
-      ts2 = tick<TL>(tl_on);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      ring_store<B>(ring, ring_voff, slot_byte, plane_bytes, hv);
-      const int out_soff = t * B * H * 4;
-#pragma unroll
-      for (int b = 0; b < B; ++b) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hv[b]), hbuf, out_voff, out_soff + b * H * 4, 0);
-      if (p.sync == SPRNN_SYNC_TAGGED) {
-        const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
-        float mark[B];
-#pragma unroll
-        for (int b = 0; b < B; ++b) mark[b] = __builtin_bit_cast(float, kSentinelBits);
-        ring_store<B>(ring, ring_voff, rearm_byte, plane_bytes, mark);
-      }
+      hval = activate(p.act, pre);
     }
+    ts2 = tick<TL>(tl_on);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
+    if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
     if (t + 1 < p.T) {
-      const int x_soff = (t + 1) * B * R * 4;
-#pragma unroll
-      for (int b = 0; b < B; ++b) xn[b] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, x_soff + b * R * 4, 0));
+      xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, (t + 1) * B * R * 4, 0));
     }
     ts3 = tick<TL>(tl_on);
 

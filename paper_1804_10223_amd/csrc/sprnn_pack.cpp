@@ -58,8 +58,8 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
     return ceil_div(hidden, units_per_wave);   // a unit is one row (vanilla) or one hidden unit's 4 gate rows
   };
 
-  // LSTM: a wavefront's (units x samples) cell updates are spread over its lanes, one each: 64 / (4 L) * B <= 64
-  const int lmin = lstm ? std::max(1, batch / 4) : 1;
+  // The reduction leaves one sample per lane, so a row needs at least `batch` lanes.
+  const int lmin = batch;
   int L = opt ? opt->lanes_per_row : 0;
   if (L != 0) {
     if (!is_pow2(L) || L > lmax || L < lmin) return SPRNN_ERR_INVALID;

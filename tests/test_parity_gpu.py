@@ -73,7 +73,10 @@ SMALL = [
     ("relu", 1000, 4, 12, 0.05, "poisson", {"grid": 13}),
     ("relu", 640, 4, 10, 0.5, "fixed", {"lanes_per_row": 64}),
     ("relu", 640, 4, 10, 0.5, "fixed", {"lanes_per_row": 8}),
-    ("relu", 640, 2, 10, 0.1, "fixed", {"lanes_per_row": 1}),
+    ("relu", 640, 1, 10, 0.1, "fixed", {"lanes_per_row": 1}),
+    ("relu", 640, 2, 10, 0.1, "fixed", {"lanes_per_row": 2}),
+    ("identity", 300, 8, 6, 0.2, "fixed", {"lanes_per_row": 8}),
+    ("relu", 300, 8, 6, 0.5, "poisson", {"lanes_per_row": 32}),
     ("relu", 500, 4, 10, 0.2, "poisson", {"balance": 1}),
     ("relu", 500, 4, 10, 0.2, "poisson", {"balance": 2}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"bank_aware": 2}),
