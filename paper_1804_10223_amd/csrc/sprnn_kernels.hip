@@ -334,6 +334,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     tl_launch_wall = (long long)wall_clock64();
   }
 
+  const bool solo = gridDim.x == 1;   // no other workgroup to exchange with
   int cur = 0;
   long long tl_prev = 0;
   for (int t = 0; t < p.T; ++t) {
@@ -342,7 +343,13 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     unsigned long long repolls = 0;
 
     // ---- load: h_{t-1} (published by every workgroup in step t-1) into the other LDS copy
-    if (t > 0) {
+    if (solo) {
+      // a single workgroup keeps h in LDS: the owners wrote h_{t-1} straight into the other copy
+      if (t > 0) {
+        __syncthreads();
+        cur ^= 1;
+      }
+    } else if (t > 0) {
       const int slot_byte = (int)((g - 1) & (kRingSlotsDev - 1)) * p.h_bytes;
       unsigned char* dst = lds + (cur ^ 1) * p.h_bytes;
       bool failed = false;
@@ -456,10 +463,14 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       hval = activate(p.act, pre);
     }
     ts2 = tick<TL>(tl_on);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
+    if (solo) {
+      if (ring_voff != kOutOfRange) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.h_bytes + ring_voff) = hval;
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
+      if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
+    }
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
-    if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
     if (t + 1 < p.T) {
       xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, (t + 1) * B * R * 4, 0));
     }

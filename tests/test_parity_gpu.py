@@ -84,6 +84,9 @@ SMALL = [
     ("relu", 500, 1, 10, 0.2, "fixed", {"sync": "barrier", "grid": 6}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"poll_delay": -1}),
     ("lstm", 64, 8, 9, 0.3, "fixed", {}),
+    ("lstm", 40, 2, 9, 0.3, "fixed", {"grid": 1, "sync": "barrier"}),
+    ("tanh", 88, 4, 9, 0.3, "poisson", {"grid": 1}),
+    ("relu", 192, 4, 9, 0.2, "poisson", {"grid": 2}),
     ("lstm", 100, 4, 7, 0.2, "poisson", {}),
     ("lstm", 77, 1, 6, 0.4, "fixed", {"lanes_per_row": 4}),
     ("lstm", 150, 2, 6, 0.3, "fixed", {"lanes_per_row": 16, "sync": "barrier"}),
