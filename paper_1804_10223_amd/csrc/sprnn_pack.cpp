@@ -80,7 +80,17 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   int grid = opt ? opt->grid : 0;
   if (waves < 0 || waves > kMaxWaves || grid < 0) return SPRNN_ERR_INVALID;
   if (grid && !waves) waves = ceil_div(wt, grid);
-  if (!waves) waves = std::min(wave_cap, std::max(ceil_div(wt, num_cus), std::min(8, wt)));
+  if (!waves) {
+    // Eight wavefronts per workgroup copy h into LDS efficiently; but when the gathers of one step would keep a
+    // CU's LDS busy for long (about 0.25 us: 600 clocks), spreading the rows over more CUs with four wavefronts
+    // each is faster.  LDS clocks per step and CU ~ nonzeros * passes per gather / 64 lanes / workgroups.
+    waves = std::min(wave_cap, std::max(ceil_div(wt, num_cus), std::min(8, wt)));
+    if (!grid) {
+      const int passes = (batch >= 4 ? 4 : batch) * (batch == 8 ? 2 : 1);
+      auto lds_clocks = [&](int w) { return (double)nnz * passes * 1.3 / 64.0 / ceil_div(wt, w); };
+      while (waves > 4 && ceil_div(wt, waves / 2) <= num_cus && lds_clocks(waves) > 600.0) waves /= 2;
+    }
+  }
   if (waves > wave_cap) return SPRNN_ERR_CAPACITY;
   if (!grid) grid = ceil_div(wt, waves);
   if ((int64_t)grid * waves < wt) return SPRNN_ERR_CAPACITY;
