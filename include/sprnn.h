@@ -70,7 +70,7 @@ typedef struct sprnn_info_s {
   int grid, block, waves, lanes_per_row, sync, bank_aware, balance, poll_delay;
   int words_per_lane_max;   /* largest number of packed nonzeros held by one lane                 */
   int template_words;       /* register slots per lane of the kernel instantiation in use         */
-  int lds_bytes;            /* LDS bytes per workgroup (two copies of h)                           */
+  int lds_bytes;            /* LDS bytes per workgroup for h (one copy; two when grid is 1)        */
   int resident_capacity;    /* co-resident workgroups the device can hold for this kernel         */
   int64_t nnz;              /* nonzeros in the CSR input                                           */
   int64_t padded_words;     /* packed words including zero padding                                 */

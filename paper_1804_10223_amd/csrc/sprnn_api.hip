@@ -184,7 +184,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
   // (sharedMemPerMultiprocessor is not used: some runtime versions report the whole chip's LDS there.)
   const int lds_cu = prop.sharedMemPerBlockOptin > 0 ? (int)prop.sharedMemPerBlockOptin : (int)prop.sharedMemPerBlock;
-  const int lds_need = m.lds_bytes + kLdsTailBytes + m.stage_bytes;      // two copies of h + the abort flags (+ the LSTM hand-over area)
+  const int lds_need = m.lds_bytes + kLdsTailBytes + m.stage_bytes;      // h + the abort flags (+ the LSTM hand-over area)
   h->launch_lds = std::max(lds_need, lds_cu / 2 + 1024);
   if (h->launch_lds > lds_cu) { release(h); return SPRNN_ERR_CAPACITY; }
   if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }

@@ -16,7 +16,7 @@ constexpr int kCtrlStatus = 0;                    // ctrl[0]: non-zero once a sp
 constexpr int kCtrlBarrier = 32;                  // ctrl[32]: arrival counter of the grid-barrier mode (own cache line)
 constexpr int kCtrlWords = 64;
 constexpr int kTimelineSlots = 16;                // 64-bit accumulators per workgroup in the phase timeline
-constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after the two copies of h: abort flags, timeline sums
+constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after h: abort flags, timeline sums
 
 struct KernelArgs {
   const uint32_t* words;      // [grid][NW][block] packed <index,value> words

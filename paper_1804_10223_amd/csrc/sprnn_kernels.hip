@@ -228,6 +228,35 @@ __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)
   }
 }
 
+// Copy D 16-byte chunks per lane from a ring slot into LDS, all D loads in flight at once.  A chunk that still
+// holds the "not written" mark makes the whole wavefront poll again (bounded by spin_limit; a tripped watchdog
+// anywhere ends the wait).  Returns false when the wait was given up.
+template <int D>
+__device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slot_byte, const int (&off)[D], unsigned char* dst,
+                                            int spin_limit, const uint32_t* status_word, unsigned long long& repolls) {
+  i32x4 v[D];
+  bool ok = true;
+  int spins = 0;
+  for (;;) {
+#pragma unroll
+    for (int c = 0; c < D; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
+    int low = min_word(v[0]);
+#pragma unroll
+    for (int c = 1; c < D; ++c) low = min(low, min_word(v[c]));
+    if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) == 0) break;
+    // some producer has not published yet
+    ++spins;
+    ++repolls;
+    if (spins > spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(status_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+      ok = false;
+      break;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < D; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
+  return ok;
+}
+
 // Timestamps of the optional phase timeline (TL): wall-clock reads that vanish from the TL = false kernels.
 template <bool TL>
 __device__ __forceinline__ long long tick(bool on) {
@@ -237,10 +266,15 @@ __device__ __forceinline__ long long tick(bool on) {
 
 template <int B, int NW, bool LSTM, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const KernelArgs p) {
-  extern __shared__ __align__(16) unsigned char lds[];   // [h copy 0][h copy 1][abort flags][timeline]
+  // LDS: [h][abort flags][timeline sums][LSTM hand-over area].  A single workgroup (no exchange) keeps two copies of
+  // h and writes h_t straight into the other one; otherwise one copy is enough, because the workgroup barrier
+  // before a step's first poll also separates the last gather of step t from the first write of h_t.
+  extern __shared__ __align__(16) unsigned char lds[];
+  const bool solo = gridDim.x == 1;   // no other workgroup to exchange with
+  unsigned char* const lds_tail = lds + (solo ? 2 : 1) * p.h_bytes;
   // abort flags, indexed by step parity so that a fast wave's next-step flag cannot be read one step early
-  volatile int* s_abort = reinterpret_cast<volatile int*>(lds + 2 * p.h_bytes);
-  unsigned long long* s_tl = reinterpret_cast<unsigned long long*>(lds + 2 * p.h_bytes + 16);
+  volatile int* s_abort = reinterpret_cast<volatile int*>(lds_tail);
+  unsigned long long* s_tl = reinterpret_cast<unsigned long long*>(lds_tail + 16);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int block = blockDim.x, wg = blockIdx.x;
@@ -300,7 +334,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   }
   float c_state = (LSTM && cell_unit >= 0 && p.c0) ? p.c0[(size_t)(lane % B) * H + cell_unit] : 0.0f;
   // hand-over area of this wavefront: [unit slot][sample][gate] floats, after the flags and the timeline sums
-  float* const stage = reinterpret_cast<float*>(lds + 2 * p.h_bytes + kLdsTailBytes) + (LSTM ? wave * (64 / (4 * L)) * B * 4 : 0);
+  float* const stage = reinterpret_cast<float*>(lds_tail + kLdsTailBytes) + (LSTM ? wave * (64 / (4 * L)) * B * 4 : 0);
   const int stage_write = ((lane / (4 * L)) * B + sample) * 4 + ((lane / L) & 3);   // [unit slot][sample][gate]
   const int stage_read = min(lane, (64 / (4 * L)) * B - 1) * 4;
 
@@ -334,8 +368,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     tl_launch_wall = (long long)wall_clock64();
   }
 
-  const bool solo = gridDim.x == 1;   // no other workgroup to exchange with
-  int cur = 0;
+  int cur = 0;   // LDS copy that holds h_{t-1}; stays 0 unless solo
   long long tl_prev = 0;
   for (int t = 0; t < p.T; ++t) {
     const uint32_t g = p.step_base + (uint32_t)t;         // global step index: the slot number is the timestep tag
@@ -351,7 +384,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       }
     } else if (t > 0) {
       const int slot_byte = (int)((g - 1) & (kRingSlotsDev - 1)) * p.h_bytes;
-      unsigned char* dst = lds + (cur ^ 1) * p.h_bytes;
+      unsigned char* dst = lds;
       bool failed = false;
       if (p.sync == SPRNN_SYNC_BARRIER) {
         // grid barrier (Section 3.2): all stores performed, one arrival per workgroup, wait for everyone
@@ -365,16 +398,13 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
             const uint32_t seen = __hip_atomic_load(p.ctrl + kCtrlBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((int)(seen - target) >= 0) break;
             if (++spins > p.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(p.ctrl + kCtrlStatus, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-              failed = true;
+              s_abort[t & 1] = 1;
               break;
             }
           }
         }
         __syncthreads();
-        for (int ci = tid; ci < n4; ci += block) {
-          const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ring, ci * 16, slot_byte, kAuxCoherent);
-          *reinterpret_cast<i32x4*>(dst + ci * 16) = v;
-        }
+        failed = __builtin_amdgcn_readfirstlane(s_abort[t & 1]) != 0;   // the same for every lane of the workgroup
       } else {
         // Polling a line before its producer wrote it installs a stale copy in this XCD's L2 that has to be
         // invalidated and fetched again, which costs more than waiting a little too long: back off first.
@@ -383,39 +413,21 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         // otherwise have to be covered by a longer back-off in every workgroup).
         __syncthreads();
         for (int d = 0; d < p.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
-        ts4 = tick<TL>(tl_on);
-        for (int r0 = 0; r0 < chunk_rounds; r0 += 4) {
-          int off[4];
-          i32x4 v[4];
+      }
+      ts4 = tick<TL>(tl_on);
+      if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
+        if (chunk_rounds <= 4) {
+          failed = !copy_chunks<4>(ring, slot_byte, foff, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+        } else {
+          // a large h or a small workgroup: eight loads per lane in flight, as many rounds as it takes
+          for (int r0 = 0; r0 < chunk_rounds && !failed; r0 += 8) {
+            int off[8];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) off[c] = foff[c];
-          if (r0 != 0) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) off[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
+            for (int c = 0; c < 8; ++c) off[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
+            failed = !copy_chunks<8>(ring, slot_byte, off, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
           }
-#pragma unroll
-          for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
-          int low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
-          if (r0 == 0) ts5 = tick<TL>(tl_on);
-          if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0) {
-            // slow path: some producer has not published yet; the whole wavefront polls again (bounded)
-            int spins = 0;
-            do {
-              ++spins;
-              ++repolls;
-              if (spins > p.spin_limit ||
-                  ((spins & 1023) == 0 && __hip_atomic_load(p.ctrl + kCtrlStatus, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                failed = true;
-                break;
-              }
-#pragma unroll
-              for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
-              low = min(min(min_word(v[0]), min_word(v[1])), min(min_word(v[2]), min_word(v[3])));
-            } while (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) != 0);
-          }
-#pragma unroll
-          for (int c = 0; c < 4; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
         }
+        ts5 = ts4;
       }
       ts6 = tick<TL>(tl_on);
       if (failed) {
@@ -426,7 +438,6 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       // every wave of the workgroup leaves together; other workgroups see the status word
       // (readfirstlane: the flag is the same for every lane, and a scalar exit keeps the loop counter scalar)
       if (__builtin_amdgcn_readfirstlane(s_abort[t & 1])) break;
-      cur ^= 1;
       ts7 = tick<TL>(tl_on);
     }
     ts0 = tick<TL>(tl_on);

@@ -108,9 +108,10 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   const int64_t plane = (int64_t)hidden * m->col_stride;          // batch 8 keeps two planes of 4 samples
   const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
   m->stage_bytes = lstm ? total * (kWave / (4 * L)) * batch * 16 : 0;   // [wave][unit slot][sample][4 gates] floats
-  if (2 * hb + 256 + m->stage_bytes > kLdsLimit) return SPRNN_ERR_CAPACITY;   // two copies of h, a small tail of flags, the LSTM hand-over area
+  const int copies = grid == 1 ? 2 : 1;   // a single workgroup double-buffers h in LDS, several exchange it through the ring
+  if (copies * hb + 256 + m->stage_bytes > kLdsLimit) return SPRNN_ERR_CAPACITY;   // h, a small tail of flags, the LSTM hand-over area
   m->h_bytes = (int)hb;
-  m->lds_bytes = (int)(2 * hb);
+  m->lds_bytes = (int)(copies * hb);
   int shift = 0;
   if (plane > 65536) { while ((1 << shift) < m->col_stride) ++shift; }
   m->index_shift = shift;

@@ -33,7 +33,7 @@ struct Mapping {
   int col_stride = 0;        // bytes between consecutive columns of h in LDS (4 * min(B, 4))
   int index_shift = 0;       // packed index = (col * col_stride) >> index_shift
   int h_bytes = 0;           // bytes of one copy of h in LDS / one ring slot (multiple of 16)
-  int lds_bytes = 0;         // 2 * h_bytes
+  int lds_bytes = 0;         // LDS taken by h: h_bytes, or 2 * h_bytes for a single workgroup
   int stage_bytes = 0;       // LSTM: per-workgroup LDS area through which gate sums reach the cell lanes
   int64_t nnz = 0, padded_words = 0;
 };

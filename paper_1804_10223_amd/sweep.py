@@ -1,0 +1,128 @@
+#!/usr/bin/env python3
+"""Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
+
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,batch,steps] [--reps 8]
+
+Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
+closed libraries on other hardware and are not reproduced):
+
+  ablation   Table 1's shape (hidden 1152, batch 4, density 10 %, T 256) and the headline shape (2304, 30 %):
+             per-timestep launches -> persistent with a grid barrier and CSR-order nonzeros -> bank-aware
+             ordering -> tagged hand-off, with the packer's LDS pass model as the bank-conflict figure.
+  density / size / batch / steps
+             the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
+
+Prints markdown tables on stdout.  Needs a GPU; every number comes from the HIP library.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+import numpy as np
+
+
+def _time_us_per_step(torch, run, T, reps):
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3 / T)
+    return float(np.median(ts))
+
+
+def measure(torch, w, reps, stepwise=False, **options):
+    """Microseconds per timestep of one workload (whole launch / T) and the mapping the library chose."""
+    from . import binding
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    x, h0, c0 = dev(w.x), dev(w.h0), dev(w.c0)
+    T = w.steps
+    h_out = torch.empty((T, w.batch, w.hidden), dtype=torch.float32, device="cuda")
+    c_out = torch.empty_like(h_out) if w.cell == "lstm" else None
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, **options) as rnn:
+        info = rnn.info()
+        if stepwise:
+            run = lambda: rnn.forward_stepwise(x, h0, c0, h_out, c_out)
+        elif w.cell == "lstm":
+            run = lambda: rnn.forward_lstm(x, h0, c0, h_out, c_out)
+        else:
+            run = lambda: rnn.forward(x, h0, h_out)
+        us = _time_us_per_step(torch, run, T, max(3, reps // 2) if stepwise else reps)
+        if rnn.check() != 0:
+            raise RuntimeError("spin watchdog tripped")
+    return us, info
+
+
+def ablation(torch, wl, reps):
+    print("## Ablation (cf. Table 1): microseconds per timestep, whole launch / T\n")
+    print("| shape | per-timestep launches | persistent, grid barrier, CSR order | + bank-aware order | tagged hand-off, CSR order | + bank-aware order (default) | LDS passes per gather: CSR order / bank-aware |")
+    print("|---|---|---|---|---|---|---|")
+    for name in ("cfg2", "cfg3"):
+        w = wl.make_config(name)
+        step, _ = measure(torch, w, reps, stepwise=True)
+        bn, i_n = measure(torch, w, reps, sync="barrier", bank_aware=2)
+        ba, i_a = measure(torch, w, reps, sync="barrier", bank_aware=1)
+        tn, _ = measure(torch, w, reps, sync="tagged", bank_aware=2)
+        ta, _ = measure(torch, w, reps, sync="tagged", bank_aware=1)
+        print("| %s: hidden %d, batch %d, density %.0f %%, T %d | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f / %.2f |" % (
+            name, w.hidden, w.batch, 100 * w.meta["density"], w.steps, step, bn, ba, tn, ta,
+            i_n["lds_pass_factor"], i_a["lds_pass_factor"]), flush=True)
+    print()
+    w = wl.make_config("cfg4")
+    b1, i1 = measure(torch, w, reps, balance=1)
+    b2, i2 = measure(torch, w, reps, balance=2)
+    print("Load balance (cf. Section 6), cfg4 (hidden 5760, batch 2, Poisson(576) rows): rows dealt by nonzero count "
+          "%.2f us/step with %.1f %% padding; contiguous rows %.2f us/step with %.1f %% padding.\n" % (
+              b1, 100.0 * (i1["padded_words"] / max(i1["nnz"], 1) - 1), b2, 100.0 * (i2["padded_words"] / max(i2["nnz"], 1) - 1)), flush=True)
+
+
+def axis(torch, wl, reps, title, cases):
+    print("## %s\n" % title)
+    print("| hidden | batch | density | T | nonzeros | persistent us/step | per-timestep launches us/step | ratio | grid x block | lanes/row | back-off |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    for (H, B, dens, T) in cases:
+        w = wl.make_workload("sweep", "relu", H, B, T, dens, seed=0)
+        try:
+            us, info = measure(torch, w, reps)
+        except Exception as e:  # a shape that does not fit on chip is part of the picture
+            print("| %d | %d | %.0f %% | %d | %d | does not fit: %s | | | | | |" % (H, B, 100 * dens, T, w.nnz, e), flush=True)
+            continue
+        st, _ = measure(torch, w, reps, stepwise=True)
+        print("| %d | %d | %.0f %% | %d | %d | %.2f | %.2f | %.1fx | %d x %d | %d | %d |" % (
+            H, B, 100 * dens, T, w.nnz, us, st, st / us, info["grid"], info["block"], info["lanes_per_row"], info["poll_delay"]), flush=True)
+    print()
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--what", default="ablation,density,size,batch,steps")
+    ap.add_argument("--reps", type=int, default=8)
+    args = ap.parse_args()
+    import torch
+    if not torch.cuda.is_available():
+        print("sweep: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    from . import workloads as wl
+    what = args.what.split(",")
+    if "ablation" in what:
+        ablation(torch, wl, args.reps)
+    if "density" in what:
+        axis(torch, wl, args.reps, "Density (cf. Section 5.2, first sweep): hidden 1792, batch 4, T 256",
+             [(1792, 4, d, 256) for d in (0.01, 0.05, 0.10, 0.20, 0.30)])
+    if "size" in what:
+        axis(torch, wl, args.reps, "Layer size (cf. Sections 5.2 and 5.3): density 10 %, batch 4, T 256",
+             [(H, 4, 0.10, 256) for H in (1024, 1792, 2304, 3072, 4096, 5120)] + [(5760, 2, 0.10, 256), (11520, 1, 0.01, 256)])
+    if "batch" in what:
+        axis(torch, wl, args.reps, "Batch size: hidden 1792, density 10 %, T 256", [(1792, B, 0.10, 256) for B in (1, 2, 4, 8)])
+    if "steps" in what:
+        axis(torch, wl, args.reps, "Timesteps: hidden 1792, batch 4, density 10 %", [(1792, 4, 0.10, T) for T in (16, 64, 256, 1024)])
+
+
+if __name__ == "__main__":
+    main()
