@@ -292,7 +292,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
 #pragma unroll
   for (int k = 0; k < NW; ++k) {
     const uint32_t word = (k < n_w) ? p.words[((size_t)wg * NW + k) * block + tid] : 0u;
-    w_off[k] = word >> 16;
+    w_off[k] = (word >> 16) << p.index_shift;   // (the 16-bit index counts columns when byte offsets would not fit)
     w_val[k] = half_bits_to_float(word);
   }
   // After the reduction (reduce_scatter) the first B lanes of a row group each own one sample of the row: they

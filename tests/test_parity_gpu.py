@@ -102,6 +102,13 @@ def test_small_shapes_match_oracle(cell, H, B, T, dens, rownnz, opts):
     check_workload(w, **opts)
 
 
+def test_large_layer_whose_columns_need_scaled_indices():
+    # h of 4608 x 4 samples is 72 KB: byte offsets of columns no longer fit 16 bits, the packed index counts columns
+    w = wl.make_workload("big", "relu", 4608, 4, 6, 0.02, seed=11, h0_std=0.5)
+    info = check_workload(w, stepwise_too=False)
+    assert info["lds_bytes"] == 4608 * 16
+
+
 # ------------------------------------------------------------------ degenerate cases
 def test_zero_steps_and_single_step():
     w = wl.make_workload("t1", "relu", 128, 4, 1, 0.2, seed=1, h0_std=0.3)
@@ -140,7 +147,7 @@ def test_empty_rows_and_stored_zeros():
     check_workload(w)
 
 
-@pytest.mark.parametrize("H,B", [(7, 4), (4099, 2), (16384, 1)])
+@pytest.mark.parametrize("H,B", [(7, 4), (4099, 2), (16384, 1), (4100, 4), (9000, 2), (20000, 1), (5000, 8)])
 def test_permutation_matrix_bit_exact(H, B):
     rng = np.random.default_rng(H)
     perm = rng.permutation(H).astype(np.int32)
