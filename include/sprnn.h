@@ -61,7 +61,11 @@ typedef struct sprnn_options_s {
   int timeline;      /* 1 = workgroup 0..grid-1 accumulate per-phase times (see sprnn_read_timeline) */
   int fill_waves;    /* total wavefronts per workgroup when larger than `waves`: the extra ones own no
                         rows and only help to copy h into LDS                                      */
-  int reserved[6];
+  int plain_launch;  /* 1 = ordinary kernel launch instead of a cooperative one: about 10 us less per
+                        forward call, but the caller must then guarantee that nothing else runs on the
+                        device meanwhile (the workgroups spin on each other and must all be resident;
+                        the spin watchdog still bounds every wait)                                 */
+  int reserved[5];
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */

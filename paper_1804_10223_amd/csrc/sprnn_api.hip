@@ -256,7 +256,9 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.index_shift = m.index_shift; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
     a.step_base = h->step_base; a.barrier_base = h->barrier_base;
     void* args[] = {&a};
-    hipError_t e = hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+    const bool plain = m.plain_launch != 0;
+    hipError_t e = plain ? hipLaunchKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
+                         : hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
     h->step_base += (uint32_t)tn;
     h->barrier_base += (uint32_t)(tn - 1) * (uint32_t)m.grid;   // one barrier before every step but the first

@@ -83,6 +83,7 @@ SMALL = [
     ("relu", 500, 4, 10, 0.2, "fixed", {"sync": "barrier"}),
     ("relu", 500, 1, 10, 0.2, "fixed", {"sync": "barrier", "grid": 6}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"poll_delay": -1}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"plain_launch": 1}),
     ("lstm", 64, 8, 9, 0.3, "fixed", {}),
     ("lstm", 40, 2, 9, 0.3, "fixed", {"grid": 1, "sync": "barrier"}),
     ("tanh", 88, 4, 9, 0.3, "poisson", {"grid": 1}),
