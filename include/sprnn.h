@@ -65,7 +65,11 @@ typedef struct sprnn_options_s {
                         forward call, but the caller must then guarantee that nothing else runs on the
                         device meanwhile (the workgroups spin on each other and must all be resident;
                         the spin watchdog still bounds every wait)                                 */
-  int reserved[5];
+  int jitter;        /* test aid: non-zero seeds pseudo-random pauses (0..15 x 64 clocks) of every
+                        wavefront before it publishes, before it polls and after it has copied h,
+                        different in every step, to widen the windows of any race in the hand-off;
+                        results must not change                                                   */
+  int reserved[4];
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */

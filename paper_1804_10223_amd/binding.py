@@ -34,7 +34,7 @@ class Options(ctypes.Structure):
     _fields_ = [("grid", ctypes.c_int), ("waves", ctypes.c_int), ("lanes_per_row", ctypes.c_int),
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
-                ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("reserved", ctypes.c_int * 5)]
+                ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
 
 
 class Info(ctypes.Structure):

@@ -253,7 +253,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
     a.timeline = h->d_timeline;
     a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
-    a.index_shift = m.index_shift; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
+    a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
     a.step_base = h->step_base; a.barrier_base = h->barrier_base;
     void* args[] = {&a};
     const bool plain = m.plain_launch != 0;

@@ -31,6 +31,7 @@ struct KernelArgs {
   float* c_out;               // [T][B][H] (LSTM)
   unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)
   int hidden, T, lanes_per_row, act, h_bytes, poll_delay, spin_limit, sync;
+  int jitter;                 // test aid: seed of pseudo-random pauses (0 = none)
   int index_shift;            // LDS byte offset of a packed word = (word >> 16) << index_shift
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
   uint32_t barrier_base;      // barrier arrivals before this call

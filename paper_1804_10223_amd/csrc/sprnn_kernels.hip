@@ -257,6 +257,15 @@ __device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slo
   return ok;
 }
 
+// Test aid: a pause of 0..15 x 64 clocks that differs per wavefront, step and call site (seed != 0 only).
+__device__ __forceinline__ void jitter_pause(int seed, uint32_t wave_id, uint32_t step, uint32_t site) {
+  if (seed == 0) return;
+  uint32_t x = (uint32_t)seed * 0x9E3779B9u ^ (wave_id * 0x85EBCA6Bu) ^ (step * 0xC2B2AE35u) ^ (site * 0x27D4EB2Fu);
+  x ^= x >> 15; x *= 0x2C1B3C6Du; x ^= x >> 12;
+  const int n = (int)__builtin_amdgcn_readfirstlane(x & 15u);
+  for (int i = 0; i < n; ++i) __builtin_amdgcn_s_sleep(1);
+}
+
 // Timestamps of the optional phase timeline (TL): wall-clock reads that vanish from the TL = false kernels.
 template <bool TL>
 __device__ __forceinline__ long long tick(bool on) {
@@ -368,6 +377,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     tl_launch_wall = (long long)wall_clock64();
   }
 
+  const uint32_t wave_id = (uint32_t)(wg * (block >> 6) + wave);
   int cur = 0;   // LDS copy that holds h_{t-1}; stays 0 unless solo
   long long tl_prev = 0;
   for (int t = 0; t < p.T; ++t) {
@@ -413,6 +423,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         // otherwise have to be covered by a longer back-off in every workgroup).
         __syncthreads();
         for (int d = 0; d < p.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
+        jitter_pause(p.jitter, wave_id, g, 1);
       }
       ts4 = tick<TL>(tl_on);
       if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
@@ -429,6 +440,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         }
         ts5 = ts4;
       }
+      jitter_pause(p.jitter, wave_id, g, 2);
       ts6 = tick<TL>(tl_on);
       if (failed) {
         s_abort[t & 1] = 1;
@@ -474,6 +486,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       hval = activate(p.act, pre);
     }
     ts2 = tick<TL>(tl_on);
+    jitter_pause(p.jitter, wave_id, g, 3);
     if (solo) {
       if (ring_voff != kOutOfRange) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.h_bytes + ring_voff) = hval;
     } else {

@@ -131,6 +131,7 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   m->spin_limit = (opt && opt->spin_limit > 0) ? opt->spin_limit : (1 << 22);
   m->timeline = (opt && opt->timeline) ? 1 : 0;
   m->plain_launch = (opt && opt->plain_launch) ? 1 : 0;
+  m->jitter = opt ? opt->jitter : 0;
   return SPRNN_OK;
 }
 

@@ -207,6 +207,47 @@ def test_consecutive_forwards_and_time_composition():
         assert np.array_equal(h1, h2)
 
 
+@pytest.mark.parametrize("cell,H,B,opts", [
+    ("relu", 1152, 4, {}),
+    ("relu", 1152, 4, {"sync": "barrier"}),
+    ("relu", 2000, 2, {"grid": 250, "poll_delay": 2}),
+    ("lstm", 512, 8, {}),
+    ("tanh", 96, 4, {"grid": 1}),
+])
+def test_random_pauses_in_the_hand_off_do_not_change_results(cell, H, B, opts):
+    # every wavefront pauses pseudo-randomly before publishing, before polling and after copying h, differently in
+    # every step: any race in the hand-off (ring re-arm, single LDS copy, barrier placement) would show as a mismatch
+    T = 160
+    w = wl.make_workload("jit", cell, H, B, T, 0.1, seed=12, gain=1.0 if cell == "lstm" else 0.9, h0_std=0.3)
+    want_h, want_c = oracle_run(w)
+    ref = None
+    for seed in (0, 1, 2, 3):
+        with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, jitter=seed, **opts) as rnn:
+            got_h, got_c = gpu_run(rnn, w)
+        assert_parity(got_h, want_h, "jitter %d" % seed)
+        if want_c is not None:
+            assert_parity(got_c, want_c, "jitter %d (c)" % seed)
+        if ref is None:
+            ref = got_h
+        else:
+            assert np.array_equal(ref, got_h), "jitter seed %d changed the result" % seed
+
+
+def test_long_sequence_is_deterministic_and_matches_in_pieces():
+    w = wl.make_workload("long", "relu", 1024, 4, 3000, 0.1, seed=13)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        x = _dev(w.x)
+        a = rnn.forward(x, None).cpu().numpy()
+        b = rnn.forward(x, None).cpu().numpy()
+        p1 = rnn.forward(x[:1234].contiguous(), None)
+        p2 = rnn.forward(x[1234:].contiguous(), p1[-1].contiguous())
+        assert rnn.check() == binding.SPRNN_OK
+    assert np.array_equal(a, b)
+    assert np.array_equal(a, torch.cat([p1, p2]).cpu().numpy())
+    want = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, np.ascontiguousarray(w.x[:64]), None, threads=8)
+    assert_parity(a[:64], want, "first 64 steps")
+
+
 def test_two_handles_interleaved_on_one_stream():
     w1 = wl.make_workload("a", "relu", 256, 4, 8, 0.2, seed=5)
     w2 = wl.make_workload("b", "lstm", 96, 2, 8, 0.3, seed=6, gain=1.0)
