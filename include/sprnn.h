@@ -69,7 +69,10 @@ typedef struct sprnn_options_s {
                         wavefront before it publishes, before it polls and after it has copied h,
                         different in every step, to widen the windows of any race in the hand-off;
                         results must not change                                                   */
-  int reserved[4];
+  int compact;       /* column compaction: a workgroup copies only the 16-byte pieces of h that its rows
+                        read, into consecutive LDS positions.  0 auto (when all of h does not fit in
+                        LDS, or every workgroup needs less than 60 % of it), 1 on, 2 off            */
+  int reserved[3];
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */
@@ -78,14 +81,16 @@ typedef struct sprnn_info_s {
   int grid, block, waves, lanes_per_row, sync, bank_aware, balance, poll_delay;
   int words_per_lane_max;   /* largest number of packed nonzeros held by one lane                 */
   int template_words;       /* register slots per lane of the kernel instantiation in use         */
-  int lds_bytes;            /* LDS bytes per workgroup for h (one copy; two when grid is 1)        */
+  int lds_bytes;            /* LDS bytes per workgroup for h (one copy; two when grid is 1; less
+                               with column compaction)                                               */
   int resident_capacity;    /* co-resident workgroups the device can hold for this kernel         */
   int64_t nnz;              /* nonzeros in the CSR input                                           */
   int64_t padded_words;     /* packed words including zero padding                                 */
   int64_t ring_bytes;       /* size of the exchange ring in device memory                          */
   double lds_pass_factor;   /* LDS passes the packed gathers need / passes of a conflict-free layout
                                (1.0 = no bank conflicts), from the 64-bank, 256 B-per-pass model     */
-  int reserved[8];
+  int compact;              /* 1 if column compaction is in use                                      */
+  int reserved[7];
 } sprnn_info_t;
 
 /*

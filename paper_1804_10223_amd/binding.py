@@ -34,7 +34,7 @@ class Options(ctypes.Structure):
     _fields_ = [("grid", ctypes.c_int), ("waves", ctypes.c_int), ("lanes_per_row", ctypes.c_int),
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
-                ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
+                ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
 
 
 class Info(ctypes.Structure):
@@ -45,7 +45,7 @@ class Info(ctypes.Structure):
                 ("words_per_lane_max", ctypes.c_int), ("template_words", ctypes.c_int),
                 ("lds_bytes", ctypes.c_int), ("resident_capacity", ctypes.c_int),
                 ("nnz", ctypes.c_int64), ("padded_words", ctypes.c_int64), ("ring_bytes", ctypes.c_int64),
-                ("lds_pass_factor", ctypes.c_double), ("reserved", ctypes.c_int * 8)]
+                ("lds_pass_factor", ctypes.c_double), ("compact", ctypes.c_int), ("reserved", ctypes.c_int * 7)]
 
     def as_dict(self) -> dict:
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}

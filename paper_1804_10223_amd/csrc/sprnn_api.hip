@@ -25,6 +25,8 @@ struct sprnn_handle_s {
   uint32_t* d_words = nullptr;
   int32_t* d_lane_row = nullptr;
   int32_t* d_wave_words = nullptr;
+  uint32_t* d_fill_src = nullptr;    // column compaction only
+  int32_t* d_wg_plane = nullptr;
   uint32_t* d_ring = nullptr;
   uint32_t* d_ctrl = nullptr;
   unsigned long long* d_timeline = nullptr;   // [grid][16], only with options.timeline
@@ -69,6 +71,7 @@ void fill_info(const Mapping& m, int capacity, double pass_factor, sprnn_info_t*
   info->nnz = m.nnz; info->padded_words = m.padded_words;
   info->ring_bytes = (int64_t)kRingSlots * m.h_bytes;
   info->lds_pass_factor = pass_factor;
+  info->compact = m.compact;
 }
 
 template <typename T>
@@ -83,6 +86,7 @@ hipError_t upload(T** dst, const T* src, size_t n) {
 void release(sprnn_handle_s* h) {
   if (!h) return;
   (void)hipFree(h->d_words); (void)hipFree(h->d_lane_row); (void)hipFree(h->d_wave_words);
+  (void)hipFree(h->d_fill_src); (void)hipFree(h->d_wg_plane);
   (void)hipFree(h->d_ring); (void)hipFree(h->d_ctrl); (void)hipFree(h->d_timeline);
   (void)hipFree(h->d_row_ptr); (void)hipFree(h->d_col); (void)hipFree(h->d_val);
   delete h;
@@ -206,6 +210,8 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   bool ok = SPRNN_HIP(upload(&h->d_words, P.words.data(), P.words.size())) &&
             SPRNN_HIP(upload(&h->d_lane_row, P.lane_row.data(), P.lane_row.size())) &&
             SPRNN_HIP(upload(&h->d_wave_words, P.wave_words.data(), P.wave_words.size())) &&
+            (!m.compact || (SPRNN_HIP(upload(&h->d_fill_src, P.fill_src.data(), P.fill_src.size())) &&
+                            SPRNN_HIP(upload(&h->d_wg_plane, P.wg_plane.data(), P.wg_plane.size())))) &&
             SPRNN_HIP(upload(&h->d_ring, ring.data(), ring.size())) &&
             SPRNN_HIP(upload(&h->d_ctrl, ctrl.data(), ctrl.size())) &&
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
@@ -245,6 +251,8 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     const int tn = std::min(t_max, T - t0);
     KernelArgs a;
     a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
+    a.fill_src = h->d_fill_src; a.wg_plane = h->d_wg_plane; a.fill_rows = m.fill_rows;
+    a.lds_h_bytes = m.grid == 1 ? m.lds_bytes / 2 : m.lds_bytes;
     a.ring = h->d_ring; a.ctrl = h->d_ctrl;
     a.x = x + (size_t)t0 * m.batch * m.rows;
     a.h0 = t0 ? h_out + (size_t)(t0 - 1) * hb : h0;

@@ -22,6 +22,8 @@ struct KernelArgs {
   const uint32_t* words;      // [grid][NW][block] packed <index,value> words
   const int32_t* lane_row;    // [grid][block]
   const int32_t* wave_words;  // [grid][waves]
+  const uint32_t* fill_src;   // column compaction: [grid][fill_rows][block] copy list, or null
+  const int32_t* wg_plane;    // column compaction: [grid] bytes of one plane of the workgroup's LDS copy
   uint32_t* ring;             // [4][h_bytes / 4]
   uint32_t* ctrl;             // [kCtrlWords]
   const float* x;             // [T][B][R]
@@ -31,6 +33,8 @@ struct KernelArgs {
   float* c_out;               // [T][B][H] (LSTM)
   unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)
   int hidden, T, lanes_per_row, act, h_bytes, poll_delay, spin_limit, sync;
+  int fill_rows;              // rounds in the copy list (column compaction)
+  int lds_h_bytes;            // bytes of one LDS copy of h (= h_bytes without column compaction)
   int jitter;                 // test aid: seed of pseudo-random pauses (0 = none)
   int index_shift;            // LDS byte offset of a packed word = (word >> 16) << index_shift
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)

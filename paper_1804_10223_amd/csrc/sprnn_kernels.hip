@@ -228,12 +228,13 @@ __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)
   }
 }
 
-// Copy D 16-byte chunks per lane from a ring slot into LDS, all D loads in flight at once.  A chunk that still
+// Copy D 16-byte chunks per lane from a ring slot (byte offsets `off`) into LDS (byte offsets `to`), all D loads in
+// flight at once.  A chunk that still
 // holds the "not written" mark makes the whole wavefront poll again (bounded by spin_limit; a tripped watchdog
 // anywhere ends the wait).  Returns false when the wait was given up.
 template <int D>
-__device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slot_byte, const int (&off)[D], unsigned char* dst,
-                                            int spin_limit, const uint32_t* status_word, unsigned long long& repolls) {
+__device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slot_byte, const int (&off)[D], const int (&to)[D],
+                                            unsigned char* dst, int spin_limit, const uint32_t* status_word, unsigned long long& repolls) {
   i32x4 v[D];
   bool ok = true;
   int spins = 0;
@@ -253,7 +254,7 @@ __device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slo
     }
   }
 #pragma unroll
-  for (int c = 0; c < D; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
+  for (int c = 0; c < D; ++c) *reinterpret_cast<i32x4*>(dst + to[c]) = v[c];
   return ok;
 }
 
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   // before a step's first poll also separates the last gather of step t from the first write of h_t.
   extern __shared__ __align__(16) unsigned char lds[];
   const bool solo = gridDim.x == 1;   // no other workgroup to exchange with
-  unsigned char* const lds_tail = lds + (solo ? 2 : 1) * p.h_bytes;
+  unsigned char* const lds_tail = lds + (solo ? 2 : 1) * p.lds_h_bytes;
   // abort flags, indexed by step parity so that a fast wave's next-step flag cannot be read one step early
   volatile int* s_abort = reinterpret_cast<volatile int*>(lds_tail);
   unsigned long long* s_tl = reinterpret_cast<unsigned long long*>(lds_tail + 16);
@@ -290,7 +291,9 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   const int wave = __builtin_amdgcn_readfirstlane(tid) >> 6;
   const int H = p.hidden, L = p.lanes_per_row;
   const int R = LSTM ? 4 * H : H;
-  const int plane_bytes = H * 16;   // used only for B == 8
+  const bool compacted = p.fill_src != nullptr;   // LDS holds only the chunks of h that this workgroup's rows read
+  // distance of the two planes of a batch-8 layout inside the LDS copy (the ring always uses H * 16)
+  const int plane_bytes = (B == 8 && compacted) ? __builtin_amdgcn_readfirstlane(p.wg_plane[wg]) : H * 16;
 
   // ---- one-time weight load: NW register slots per lane, all of one row (Section 3.3).
   // Each word is unpacked once into an LDS byte offset and an fp32 value (two registers per nonzero): the
@@ -333,13 +336,51 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * R * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
 
+  // ---- the copy of h into LDS: 16-byte chunks; chunk c of a lane comes from ring offset fsrc[c] and goes to LDS
+  // offset fdst[c].  Without compaction LDS mirrors the ring slot: chunk tid + c * block, indices past the end
+  // clamped to the last chunk (a few lanes then copy it twice), which keeps the copy free of per-lane branches.
+  // With compaction the sources come from the workgroup's copy list and the destinations are consecutive.
+  // Up to four chunks per lane have their offsets in registers (the common case: one round of four loads).
+  const int n4 = p.h_bytes >> 4;               // 16-byte chunks in a ring slot
+  const int last_chunk = n4 - 1;
+  const int chunk_rounds = compacted ? p.fill_rows : (n4 + block - 1) / block;
+  const uint32_t* const my_list = compacted ? p.fill_src + (size_t)wg * p.fill_rows * block + tid : nullptr;
+  auto list_entry = [&](int c, int& src, int& dst) {   // entry c of this lane in the copy list
+    const uint32_t e = my_list[(size_t)c * block];
+    src = (int)(e & ~15u);
+    dst = (e & 1u) ? tid * 16 : (tid + c * block) * 16;
+  };
+  int fsrc[4], fdst[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (compacted) list_entry(c, fsrc[c], fdst[c]);
+    else fsrc[c] = fdst[c] = min(tid + c * block, last_chunk) * 16;
+  }
+
   // ---- h_0 into LDS copy 0, cell state into registers
   if (tid < 2) s_abort[tid] = 0;
   if (TL && tid < kTimelineSlots) s_tl[tid] = 0ull;
-  for (int e = tid; e < H * B; e += block) {
-    const int j = e / B, b = e % B;
-    const float v = p.h0 ? p.h0[(size_t)b * H + j] : 0.0f;
-    *reinterpret_cast<float*>(lds + lds_offset<B>(j, b, H)) = v;
+  if (!compacted) {
+    for (int e = tid; e < H * B; e += block) {
+      const int j = e / B, b = e % B;
+      const float v = p.h0 ? p.h0[(size_t)b * H + j] : 0.0f;
+      *reinterpret_cast<float*>(lds + lds_offset<B>(j, b, H)) = v;
+    }
+  } else {
+    // the same chunks the step loop will copy, taken from the caller's [B][H] array
+    for (int c = 0; c < chunk_rounds; ++c) {
+      int src, dst;
+      list_entry(c, src, dst);
+      f32x4 v;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int f = (src >> 2) + i;             // element of the slot layout: [H][B], or [2][H][4] for batch 8
+        const int j = B == 8 ? (f % (H * 4)) / 4 : f / B;
+        const int b = B == 8 ? (f / (H * 4)) * 4 + (f & 3) : f % B;
+        v[i] = (p.h0 && j < H) ? p.h0[(size_t)b * H + j] : 0.0f;
+      }
+      *reinterpret_cast<f32x4*>(lds + dst) = v;
+    }
   }
   float c_state = (LSTM && cell_unit >= 0 && p.c0) ? p.c0[(size_t)(lane % B) * H + cell_unit] : 0.0f;
   // hand-over area of this wavefront: [unit slot][sample][gate] floats, after the flags and the timeline sums
@@ -353,16 +394,6 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   // out-of-range lane offset stays out of range whatever scalar offset is added to it)
   float xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, 0, 0));
 
-  // ---- the copy of h into LDS: 16-byte chunks, chunk c of a lane is chunk tid + c * block of the slot.
-  // Up to four chunks per lane have their offsets precomputed (the common case: one round of four loads in
-  // flight); indices past the end are clamped to the last chunk (a few lanes then copy it twice), which keeps
-  // the copy free of per-lane branches.
-  const int n4 = p.h_bytes >> 4;               // 16-byte chunks in one copy of h
-  const int last_chunk = n4 - 1;
-  const int chunk_rounds = (n4 + block - 1) / block;
-  int foff[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) foff[c] = min(tid + c * block, last_chunk) * 16;
   __syncthreads();
 
   const bool tl_on = TL && p.timeline != nullptr && wave == 0;
@@ -428,14 +459,18 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       ts4 = tick<TL>(tl_on);
       if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
         if (chunk_rounds <= 4) {
-          failed = !copy_chunks<4>(ring, slot_byte, foff, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+          failed = !copy_chunks<4>(ring, slot_byte, fsrc, fdst, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
         } else {
           // a large h or a small workgroup: eight loads per lane in flight, as many rounds as it takes
+          // (a copy list has a multiple of eight rounds)
           for (int r0 = 0; r0 < chunk_rounds && !failed; r0 += 8) {
-            int off[8];
+            int off[8], to[8];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) off[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
-            failed = !copy_chunks<8>(ring, slot_byte, off, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            for (int c = 0; c < 8; ++c) {
+              if (compacted) list_entry(r0 + c, off[c], to[c]);
+              else off[c] = to[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
+            }
+            failed = !copy_chunks<8>(ring, slot_byte, off, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
           }
         }
         ts5 = ts4;
@@ -458,7 +493,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     float acc[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) acc[b] = 0.0f;
-    operate<B, NW>(acc, w_off, w_val, n_w, lds + cur * p.h_bytes, plane_bytes);
+    operate<B, NW>(acc, w_off, w_val, n_w, lds + cur * p.lds_h_bytes, plane_bytes);
     ts1 = tick<TL>(tl_on);
 
     // ---- reduce over the lanes of the row: every lane ends up with the sum of its own sample
@@ -488,7 +523,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     ts2 = tick<TL>(tl_on);
     jitter_pause(p.jitter, wave_id, g, 3);
     if (solo) {
-      if (ring_voff != kOutOfRange) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.h_bytes + ring_voff) = hval;
+      if (ring_voff != kOutOfRange) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = hval;
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);

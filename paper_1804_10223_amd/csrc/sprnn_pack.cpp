@@ -108,13 +108,11 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   const int64_t plane = (int64_t)hidden * m->col_stride;          // batch 8 keeps two planes of 4 samples
   const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
   m->stage_bytes = lstm ? total * (kWave / (4 * L)) * batch * 16 : 0;   // [wave][unit slot][sample][4 gates] floats
-  const int copies = grid == 1 ? 2 : 1;   // a single workgroup double-buffers h in LDS, several exchange it through the ring
-  if (copies * hb + 256 + m->stage_bytes > kLdsLimit) return SPRNN_ERR_CAPACITY;   // h, a small tail of flags, the LSTM hand-over area
-  m->h_bytes = (int)hb;
-  m->lds_bytes = (int)(copies * hb);
-  int shift = 0;
-  if (plane > 65536) { while ((1 << shift) < m->col_stride) ++shift; }
-  m->index_shift = shift;
+  if (hb * kRingSlots > ((int64_t)1 << 30)) return SPRNN_ERR_CAPACITY;
+  m->h_bytes = (int)hb;       // the LDS footprint of h and the index scaling are settled by pack() (column compaction)
+  int compact = opt ? opt->compact : 0;
+  if (compact < 0 || compact > 2) return SPRNN_ERR_INVALID;
+  m->compact = compact;       // still the request here: 0 auto, 1 on, 2 off
   m->nnz = nnz;
   m->sync = (opt && opt->sync) ? opt->sync : SPRNN_SYNC_TAGGED;
   if (m->sync != SPRNN_SYNC_TAGGED && m->sync != SPRNN_SYNC_BARRIER) return SPRNN_ERR_INVALID;
@@ -289,9 +287,81 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
     }
   }
 
+  // --- column compaction (Section 6: "split a row among multiple blocks ... loading activations" dominates for
+  // very large, very sparse layers): a workgroup only copies the 16-byte chunks of h that its rows read, into
+  // consecutive LDS positions.  Used when the whole of h does not fit in LDS, or when every workgroup needs
+  // clearly less than all of it; otherwise LDS mirrors the ring slot.
+  const int cpc = batch >= 4 ? 1 : 4 / batch;                 // columns per 16-byte chunk
+  const int planes = batch == 8 ? 2 : 1;
+  const int chunks_per_plane = ceil_div(hidden, cpc);
+  std::vector<std::vector<int32_t>> wg_chunks(m.grid);         // sorted needed chunks (of one plane) per workgroup
+  {
+    std::vector<char> mark(chunks_per_plane);
+    for (int wg = 0; wg < m.grid; ++wg) {
+      std::fill(mark.begin(), mark.end(), 0);
+      for (int wave = 0; wave < m.waves; ++wave)
+        for (int s = 0; s < upw; ++s) {
+          const int u = wave_units[((size_t)wg * m.waves + wave) * upw + s];
+          if (u < 0) continue;
+          for (int g = 0; g < gpu_; ++g) {
+            const int r = unit_row(u, g);
+            for (int32_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) mark[col_idx[k] / cpc] = 1;
+          }
+        }
+      for (int c = 0; c < chunks_per_plane; ++c) if (mark[c]) wg_chunks[wg].push_back(c);
+      if (wg_chunks[wg].empty()) wg_chunks[wg].push_back(0);   // keeps every table non-empty
+    }
+  }
+  size_t need_max = 1;
+  for (auto& v : wg_chunks) need_max = std::max(need_max, v.size());
+  const int copies = m.grid == 1 ? 2 : 1;   // a single workgroup double-buffers h in LDS, several exchange it through the ring
+  const bool identity_fits = (int64_t)copies * m.h_bytes + 256 + m.stage_bytes <= kLdsLimit;
+  bool compact = m.compact == 1 || (m.compact == 0 && (!identity_fits || need_max * 10 < (size_t)chunks_per_plane * 6));
+  if (m.grid == 1) compact = false;          // a single workgroup produces all of h itself
+  if (!compact && !identity_fits) return SPRNN_ERR_CAPACITY;
+  m.compact = compact ? 1 : 0;
+  int64_t lds_plane;                          // bytes of one plane of the LDS copy (bounds the packed offsets)
+  if (compact) {
+    const int rounds = ceil_div((int64_t)planes * (int64_t)need_max, m.block);
+    m.fill_rows = rounds <= 4 ? 4 : (rounds + 7) / 8 * 8;
+    m.lds_bytes = rounds * m.block * 16;
+    lds_plane = (int64_t)need_max * 16;
+    if ((int64_t)m.lds_bytes + 256 + m.stage_bytes > kLdsLimit) return SPRNN_ERR_CAPACITY;
+  } else {
+    m.fill_rows = 0;
+    m.lds_bytes = copies * m.h_bytes;
+    lds_plane = (int64_t)hidden * m.col_stride;
+  }
+  m.index_shift = 0;
+  if (lds_plane > 65536) { while ((1 << m.index_shift) < m.col_stride) ++m.index_shift; }
+  // LDS column position of a column for a workgroup
+  std::vector<int32_t> chunk_pos(compact ? (size_t)chunks_per_plane : 0);
+  auto lds_col = [&](int col) { return compact ? chunk_pos[col / cpc] * cpc + col % cpc : col; };
+
   Packed& P = *out;
   P.map = m;
   const int NW = m.template_words;
+  if (compact) {
+    // copy list: entry e = c * block + tid of a workgroup is the ring byte offset of the chunk that thread tid
+    // copies in round c to LDS position e * 16; bit 0 marks an entry past the end (the thread then repeats its
+    // round-0 copy).  Both planes of a batch-8 layout follow each other, so plane 1 starts at (chunks) * 16.
+    P.fill_src.assign((size_t)m.grid * m.fill_rows * m.block, 0u);
+    P.wg_plane.assign(m.grid, 0);
+    for (int wg = 0; wg < m.grid; ++wg) {
+      const auto& ch = wg_chunks[wg];
+      const size_t n = ch.size();
+      P.wg_plane[wg] = (int32_t)(n * 16);
+      for (int c = 0; c < m.fill_rows; ++c)
+        for (int t = 0; t < m.block; ++t) {
+          const size_t e = (size_t)c * m.block + t;
+          auto src_of = [&](size_t i) { return (uint32_t)((i / n) * ((size_t)hidden * 16) + (size_t)ch[i % n] * 16); };
+          // past the end: repeat the thread's round-0 copy (same source, same LDS position t * 16); a thread whose
+          // round-0 entry is itself past the end copies chunk 0 into its own, otherwise unused, position
+          const uint32_t v = e < n * planes ? src_of(e) : (src_of((size_t)t < n * planes ? (size_t)t : 0) | 1u);
+          P.fill_src[((size_t)wg * m.fill_rows + c) * m.block + t] = v;
+        }
+    }
+  }
   const size_t lanes = (size_t)m.grid * m.block;
   P.words.assign(lanes * NW, 0u);
   P.lane_row.assign(lanes, -1);
@@ -299,10 +369,10 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   P.wave_words.assign(total_waves, 0);
 
   const int groups = pass_lanes(batch);
-  auto pad_word = [&](int lane_in_wave, int k) -> uint32_t {
+  auto pad_word = [&](int lane_in_wave, int k, int ncols) -> uint32_t {
     // zero-valued filler that reads the bank group this lane would ideally hit
     int col = (lane_in_wave + k * L) % groups;
-    if (col >= hidden) col = 0;
+    if (col >= ncols) col = 0;
     return (uint32_t)(((uint32_t)col * (uint32_t)m.col_stride) >> m.index_shift) << 16;
   };
 
@@ -310,8 +380,16 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   int words_max = 0;
   int64_t padded = 0;
   std::vector<RowGroup> rg;
+  int pos_wg = -1;
+  std::vector<int> wg_cols(m.grid, hidden);   // LDS column positions a workgroup may address
   for (int gw = 0; gw < total_waves; ++gw) {
     const int wg = gw / m.waves, wave = gw % m.waves;
+    if (compact && wg != pos_wg) {
+      pos_wg = wg;
+      for (size_t i = 0; i < wg_chunks[wg].size(); ++i) chunk_pos[wg_chunks[wg][i]] = (int32_t)i;
+      wg_cols[wg] = std::min<int64_t>((int64_t)wg_chunks[wg].size() * cpc, hidden);
+    }
+    const int ncols = wg_cols[wg];
     int trip = 0;
     for (int s = 0; s < upw; ++s) {
       const int u = wave_units[(size_t)gw * upw + s];
@@ -328,7 +406,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
         q.lane0 = (s * gpu_ + g) * L;
         if (u >= 0) {
           q.row = unit_row(u, g);
-          for (int32_t k = row_ptr[q.row]; k < row_ptr[q.row + 1]; ++k) q.items.push_back({col_idx[k], val_bits[k]});
+          for (int32_t k = row_ptr[q.row]; k < row_ptr[q.row + 1]; ++k) q.items.push_back({lds_col(col_idx[k]), val_bits[k]});   // bank classes follow LDS positions
         }
         rg.push_back(std::move(q));
       }
@@ -341,7 +419,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
         for (int l = 0; l < L; ++l) {
           const size_t at = ((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + q.lane0 + l;
           const int i = q.pos[(size_t)k * L + l];
-          if (i < 0) { P.words[at] = pad_word(q.lane0 + l, k); continue; }
+          if (i < 0) { P.words[at] = pad_word(q.lane0 + l, k, ncols); continue; }
           const uint32_t idx = ((uint32_t)q.items[i].col * (uint32_t)m.col_stride) >> m.index_shift;
           P.words[at] = (idx << 16) | q.items[i].bits;
           if ((q.items[i].bits & 0x7FFFu) == 0) is_real_zero[at] = 1;
@@ -372,7 +450,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
               used[((wp[l] >> 16) << m.index_shift) / m.col_stride % groups] = 1;
               continue;
             }
-            while (g < groups && (used[g] || g >= hidden)) ++g;
+            while (g < groups && (used[g] || g >= wg_cols[wg])) ++g;
             if (g < groups) {
               wp[l] = (uint32_t)(((uint32_t)g * (uint32_t)m.col_stride) >> m.index_shift) << 16;
               used[g] = 1;

@@ -35,7 +35,9 @@ struct Mapping {
   int col_stride = 0;        // bytes between consecutive columns of h in LDS (4 * min(B, 4))
   int index_shift = 0;       // packed index = (col * col_stride) >> index_shift
   int h_bytes = 0;           // bytes of one copy of h in LDS / one ring slot (multiple of 16)
-  int lds_bytes = 0;         // LDS taken by h: h_bytes, or 2 * h_bytes for a single workgroup
+  int lds_bytes = 0;         // LDS taken by h: h_bytes, 2 * h_bytes for a single workgroup, less with column compaction
+  int compact = 0;           // 1: a workgroup copies only the chunks of h that its rows read (see pack())
+  int fill_rows = 0;         // compaction: rounds in the per-workgroup copy list (4, or a multiple of 8)
   int stage_bytes = 0;       // LSTM: per-workgroup LDS area through which gate sums reach the cell lanes
   int64_t nnz = 0, padded_words = 0;
 };
@@ -46,6 +48,8 @@ struct Packed {
   std::vector<int32_t> lane_row;    // [grid][block]  row of W served by the lane, -1 if idle
   std::vector<int32_t> lane_words;  // [grid][block]  real (non-padding) words of the lane
   std::vector<int32_t> wave_words;  // [grid][waves]  loop trip count of each wavefront
+  std::vector<uint32_t> fill_src;   // compaction: [grid][fill_rows][block] ring byte offset of each copied chunk (bit 0: repeat)
+  std::vector<int32_t> wg_plane;    // compaction: [grid] bytes of one plane of the workgroup's LDS copy
 };
 
 // Returns SPRNN_OK or an error code; on success `out` holds the mapping and the image.

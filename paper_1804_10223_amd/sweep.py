@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,batch,steps] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps] [--reps 8]
 
 Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
 closed libraries on other hardware and are not reproduced):
@@ -11,6 +11,7 @@ closed libraries on other hardware and are not reproduced):
              ordering -> tagged hand-off, with the packer's LDS pass model as the bank-conflict figure.
   density / size / batch / steps
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
+  constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
 
 Prints markdown tables on stdout.  Needs a GPU; every number comes from the HIP library.
 """
@@ -84,24 +85,25 @@ def ablation(torch, wl, reps):
 
 def axis(torch, wl, reps, title, cases):
     print("## %s\n" % title)
-    print("| hidden | batch | density | T | nonzeros | persistent us/step | per-timestep launches us/step | ratio | grid x block | lanes/row | back-off |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    print("| hidden | batch | density | T | nonzeros | persistent us/step | per-timestep launches us/step | ratio | grid x block | lanes/row | back-off | LDS for h |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
     for (H, B, dens, T) in cases:
         w = wl.make_workload("sweep", "relu", H, B, T, dens, seed=0)
         try:
             us, info = measure(torch, w, reps)
         except Exception as e:  # a shape that does not fit on chip is part of the picture
-            print("| %d | %d | %.0f %% | %d | %d | does not fit: %s | | | | | |" % (H, B, 100 * dens, T, w.nnz, e), flush=True)
+            print("| %d | %d | %.1f %% | %d | %d | does not fit: %s | | | | | | |" % (H, B, 100 * dens, T, w.nnz, e), flush=True)
             continue
         st, _ = measure(torch, w, reps, stepwise=True)
-        print("| %d | %d | %.0f %% | %d | %d | %.2f | %.2f | %.1fx | %d x %d | %d | %d |" % (
-            H, B, 100 * dens, T, w.nnz, us, st, st / us, info["grid"], info["block"], info["lanes_per_row"], info["poll_delay"]), flush=True)
+        print("| %d | %d | %.1f %% | %d | %d | %.2f | %.2f | %.1fx | %d x %d | %d | %d | %d KB%s |" % (
+            H, B, 100 * dens, T, w.nnz, us, st, st / us, info["grid"], info["block"], info["lanes_per_row"], info["poll_delay"],
+            info["lds_bytes"] // 1024, " (compacted)" if info["compact"] else ""), flush=True)
     print()
 
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,batch,steps")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps")
     ap.add_argument("--reps", type=int, default=8)
     args = ap.parse_args()
     import torch
@@ -118,6 +120,10 @@ def main():
     if "size" in what:
         axis(torch, wl, args.reps, "Layer size (cf. Sections 5.2 and 5.3): density 10 %, batch 4, T 256",
              [(H, 4, 0.10, 256) for H in (1024, 1792, 2304, 3072, 4096, 5120)] + [(5760, 2, 0.10, 256), (11520, 1, 0.01, 256)])
+    if "constnnz" in what:
+        axis(torch, wl, args.reps, "Constant number of nonzeros (cf. Section 5.3): about 1.32 M, batch 4, T 256",
+             [(2304, 4, 0.25, 256), (3072, 4, 0.14, 256), (4096, 4, 0.079, 256), (5760, 4, 0.04, 256), (7168, 4, 0.026, 256),
+              (11520, 4, 0.01, 256)])
     if "batch" in what:
         axis(torch, wl, args.reps, "Batch size: hidden 1792, density 10 %, T 256", [(1792, B, 0.10, 256) for B in (1, 2, 4, 8)])
     if "steps" in what:

@@ -135,11 +135,46 @@ def test_unsupported_and_capacity_errors():
     with pytest.raises(binding.SprnnError) as e:
         binding.pack_host(4096, 1, "relu", big.row_ptr, big.col_idx, big.val_bits, grid=1, lanes_per_row=64)
     assert e.value.code == binding.SPRNN_ERR_CAPACITY
-    # h does not fit twice into LDS
-    row_ptr = np.zeros(60001, dtype=np.int32)
+    # h does not fit into LDS and every workgroup needs all of it (47 consecutive rows with 256 columns at stride 47)
+    H = 12000
+    cols = np.sort((np.arange(H)[:, None] + 47 * np.arange(256)[None, :]) % H, axis=1).astype(np.int32).ravel()
+    row_ptr = (256 * np.arange(H + 1)).astype(np.int32)
     with pytest.raises(binding.SprnnError) as e:
-        binding.pack_host(60000, 4, "relu", row_ptr, np.zeros(0, np.int32), np.zeros(0, np.uint16))
+        binding.pack_host(H, 4, "relu", row_ptr, cols, np.full(cols.size, 0x3C00, np.uint16))
     assert e.value.code == binding.SPRNN_ERR_CAPACITY
+    # an all-zero matrix of any size needs no column of h at all
+    row_ptr = np.zeros(60001, dtype=np.int32)
+    info = binding.pack_host(60000, 4, "relu", row_ptr, np.zeros(0, np.int32), np.zeros(0, np.uint16))[3]
+    assert info["compact"] == 1
+
+
+def test_column_compaction_is_chosen_for_very_sparse_large_layers():
+    w = wl.make_workload("p", "relu", 11520, 4, 1, 0.01, seed=2)
+    info = binding.pack_host(w.hidden, 4, "relu", w.row_ptr, w.col_idx, w.val_bits)[3]
+    assert info["compact"] == 1 and info["lds_bytes"] < 100 * 1024     # all of h would be 184 KB
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(w.hidden, 4, "relu", w.row_ptr, w.col_idx, w.val_bits, compact=2)
+    assert e.value.code == binding.SPRNN_ERR_CAPACITY
+    dense = wl.make_config("cfg3", steps=1)
+    info = binding.pack_host(dense.hidden, 4, "relu", dense.row_ptr, dense.col_idx, dense.val_bits)[3]
+    assert info["compact"] == 0 and info["lds_bytes"] == 2304 * 16     # every workgroup reads every column
+    # the packed rows survive compaction: same multiset of values per row (columns are renumbered per workgroup)
+    small = wl.make_workload("p", "relu", 600, 4, 1, 0.01, seed=3)
+    words, lane_row, lane_words, info = binding.pack_host(600, 4, "relu", small.row_ptr, small.col_idx, small.val_bits,
+                                                          compact=1, grid=10)
+    assert info["compact"] == 1 and int(lane_words.sum()) == small.nnz
+    got = {}
+    g, nw, blk = words.shape
+    for wg in range(g):
+        for t in range(blk):
+            r = int(lane_row[wg, t])
+            for k in range(nw):
+                bits = int(words[wg, k, t]) & 0xFFFF
+                if r >= 0 and (bits & 0x7FFF):
+                    got.setdefault(r, []).append(bits)
+    for r in range(600):
+        want = sorted(int(b) for b in small.val_bits[small.row_ptr[r]:small.row_ptr[r + 1]] if int(b) & 0x7FFF)
+        assert sorted(got.get(r, [])) == want
 
 
 def test_empty_matrix_and_empty_rows_pack():

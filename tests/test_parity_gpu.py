@@ -84,6 +84,16 @@ SMALL = [
     ("relu", 500, 1, 10, 0.2, "fixed", {"sync": "barrier", "grid": 6}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"poll_delay": -1}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"plain_launch": 1}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"compact": 1}),
+    ("relu", 2000, 4, 8, 0.01, "poisson", {"compact": 1, "grid": 50}),
+    ("tanh", 1500, 2, 8, 0.01, "fixed", {"compact": 1, "grid": 40}),
+    ("identity", 3000, 1, 8, 0.005, "poisson", {"compact": 1, "grid": 30}),
+    ("relu", 1200, 8, 8, 0.02, "fixed", {"compact": 1, "grid": 64}),
+    ("relu", 1200, 8, 8, 0.02, "fixed", {"compact": 1, "grid": 64, "sync": "barrier"}),
+    ("relu", 2000, 4, 6, 0.02, "fixed", {"compact": 1, "waves": 2}),
+    ("relu", 4000, 4, 5, 0.02, "fixed", {"compact": 1, "waves": 2}),
+    ("lstm", 600, 8, 7, 0.02, "fixed", {"compact": 1}),
+    ("lstm", 700, 2, 7, 0.01, "poisson", {"compact": 1, "grid": 20}),
     ("lstm", 64, 8, 9, 0.3, "fixed", {}),
     ("lstm", 40, 2, 9, 0.3, "fixed", {"grid": 1, "sync": "barrier"}),
     ("tanh", 88, 4, 9, 0.3, "poisson", {"grid": 1}),
@@ -101,6 +111,36 @@ def test_small_shapes_match_oracle(cell, H, B, T, dens, rownnz, opts):
     if cell == "lstm":
         w.c0 = (np.random.default_rng(1).standard_normal((B, H)) * 0.5).astype(np.float32)
     check_workload(w, **opts)
+
+
+def test_very_large_sparse_layer_fits_through_column_compaction():
+    # hidden 11520 at batch 4 (the largest layer of Section 5.3): h is 184 KB, more than a CU's LDS; every
+    # workgroup copies only the columns its rows read
+    w = wl.make_workload("huge", "relu", 11520, 4, 5, 0.01, seed=14, h0_std=0.5)
+    info = check_workload(w, stepwise_too=False)
+    assert info["compact"] == 1 and info["lds_bytes"] < 11520 * 16
+    with pytest.raises(binding.SprnnError) as e:
+        binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, compact=2)
+    assert e.value.code == binding.SPRNN_ERR_CAPACITY
+
+
+@pytest.mark.parametrize("H,B", [(4099, 2), (20000, 1), (9000, 4)])
+def test_permutation_matrix_bit_exact_with_column_compaction(H, B):
+    rng = np.random.default_rng(H)
+    perm = rng.permutation(H).astype(np.int32)
+    row_ptr = np.arange(H + 1, dtype=np.int32)
+    ones = np.full(H, 0x3C00, dtype=np.uint16)
+    T = 4
+    x = np.zeros((T, B, H), dtype=np.float32)
+    h0 = np.abs(rng.standard_normal((B, H))).astype(np.float32) + np.float32(0.01)
+    with binding.SparseRNN(H, B, "relu", row_ptr, perm, ones, compact=1) as rnn:
+        assert rnn.info()["compact"] == 1
+        h = rnn.forward(_dev(x), _dev(h0)).cpu().numpy()
+        assert rnn.check() == binding.SPRNN_OK
+    cur = h0
+    for t in range(T):
+        cur = cur[:, perm]
+        assert np.array_equal(h[t].view(np.uint32), cur.view(np.uint32)), t
 
 
 def test_large_layer_whose_columns_need_scaled_indices():
