@@ -71,7 +71,7 @@ typedef struct sprnn_options_s {
                         results must not change                                                   */
   int compact;       /* column compaction: a workgroup copies only the 16-byte pieces of h that its rows
                         read, into consecutive LDS positions.  0 auto (when all of h does not fit in
-                        LDS, or every workgroup needs less than 60 % of it), 1 on, 2 off            */
+                        LDS, or every workgroup needs less than half of it), 1 on, 2 off            */
   int reserved[3];
 } sprnn_options_t;
 

@@ -229,10 +229,11 @@ __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)
 }
 
 // Copy D 16-byte chunks per lane from a ring slot (byte offsets `off`) into LDS (byte offsets `to`), all D loads in
-// flight at once.  A chunk that still
-// holds the "not written" mark makes the whole wavefront poll again (bounded by spin_limit; a tripped watchdog
-// anywhere ends the wait).  Returns false when the wait was given up.
-template <int D>
+// flight at once.  With MAYSKIP an entry with to[c] < 0 is empty: its source offset lies out of range, so the load
+// costs no memory traffic and returns zeros, and nothing is written.  A chunk that still holds the "not written" mark makes
+// the whole wavefront poll again (bounded by spin_limit; a tripped watchdog anywhere ends the wait).  Returns false
+// when the wait was given up.
+template <int D, bool MAYSKIP>
 __device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slot_byte, const int (&off)[D], const int (&to)[D],
                                             unsigned char* dst, int spin_limit, const uint32_t* status_word, unsigned long long& repolls) {
   i32x4 v[D];
@@ -254,7 +255,8 @@ __device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slo
     }
   }
 #pragma unroll
-  for (int c = 0; c < D; ++c) *reinterpret_cast<i32x4*>(dst + to[c]) = v[c];
+  for (int c = 0; c < D; ++c)
+    if (!MAYSKIP || to[c] >= 0) *reinterpret_cast<i32x4*>(dst + to[c]) = v[c];
   return ok;
 }
 
@@ -336,26 +338,24 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * R * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
 
-  // ---- the copy of h into LDS: 16-byte chunks; chunk c of a lane comes from ring offset fsrc[c] and goes to LDS
-  // offset fdst[c].  Without compaction LDS mirrors the ring slot: chunk tid + c * block, indices past the end
-  // clamped to the last chunk (a few lanes then copy it twice), which keeps the copy free of per-lane branches.
-  // With compaction the sources come from the workgroup's copy list and the destinations are consecutive.
-  // Up to four chunks per lane have their offsets in registers (the common case: one round of four loads).
+  // ---- the copy of h into LDS: 16-byte chunks.  In round c a lane copies the chunk at ring offset src to LDS
+  // offset dst.  Without compaction LDS mirrors the ring slot: chunk tid + c * block goes to the same offset, and
+  // indices past the end are clamped to the last chunk (a few lanes then copy it twice), which keeps that path free
+  // of per-lane branches.  With compaction the sources come from the workgroup's copy list, the destinations are
+  // consecutive, and an entry past the end of the list is empty (src out of range, dst < 0).
+  // The first four rounds have their sources in registers.
   const int n4 = p.h_bytes >> 4;               // 16-byte chunks in a ring slot
   const int last_chunk = n4 - 1;
   const int chunk_rounds = compacted ? p.fill_rows : (n4 + block - 1) / block;
   const uint32_t* const my_list = compacted ? p.fill_src + (size_t)wg * p.fill_rows * block + tid : nullptr;
-  auto list_entry = [&](int c, int& src, int& dst) {   // entry c of this lane in the copy list
-    const uint32_t e = my_list[(size_t)c * block];
-    src = (int)(e & ~15u);
-    dst = (e & 1u) ? tid * 16 : (tid + c * block) * 16;
+  auto copy_src = [&](int c) -> int {          // source of round c
+    if (compacted) return c < chunk_rounds ? (int)my_list[(size_t)c * block] : kOutOfRange;
+    return min(tid + c * block, last_chunk) * 16;
   };
-  int fsrc[4], fdst[4];
+  auto copy_dst = [&](int c, int src) -> int { return compacted ? (src == kOutOfRange ? -1 : (tid + c * block) * 16) : src; };
+  int fsrc[4];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    if (compacted) list_entry(c, fsrc[c], fdst[c]);
-    else fsrc[c] = fdst[c] = min(tid + c * block, last_chunk) * 16;
-  }
+  for (int c = 0; c < 4; ++c) fsrc[c] = copy_src(c);
 
   // ---- h_0 into LDS copy 0, cell state into registers
   if (tid < 2) s_abort[tid] = 0;
@@ -369,8 +369,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   } else {
     // the same chunks the step loop will copy, taken from the caller's [B][H] array
     for (int c = 0; c < chunk_rounds; ++c) {
-      int src, dst;
-      list_entry(c, src, dst);
+      const int src = copy_src(c), dst = copy_dst(c, src);
+      if (dst < 0) continue;
       f32x4 v;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -459,18 +459,37 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       ts4 = tick<TL>(tl_on);
       if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
         if (chunk_rounds <= 4) {
-          failed = !copy_chunks<4>(ring, slot_byte, fsrc, fdst, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
-        } else {
-          // a large h or a small workgroup: eight loads per lane in flight, as many rounds as it takes
-          // (a copy list has a multiple of eight rounds)
-          for (int r0 = 0; r0 < chunk_rounds && !failed; r0 += 8) {
-            int off[8], to[8];
+          if (!compacted) {
+            failed = !copy_chunks<4, false>(ring, slot_byte, fsrc, fsrc, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+          } else {
+            int to[4];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-              if (compacted) list_entry(r0 + c, off[c], to[c]);
-              else off[c] = to[c] = min(tid + (r0 + c) * block, last_chunk) * 16;
-            }
-            failed = !copy_chunks<8>(ring, slot_byte, off, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            for (int c = 0; c < 4; ++c) to[c] = copy_dst(c, fsrc[c]);
+            failed = !copy_chunks<4, true>(ring, slot_byte, fsrc, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+          }
+        } else if (!compacted) {
+          // a large h or a small workgroup: eight loads per lane in flight, as many rounds as it takes
+          for (int r0 = 0; r0 < chunk_rounds && !failed; r0 += 8) {
+            int off[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) off[c] = copy_src(r0 + c);
+            failed = !copy_chunks<8, false>(ring, slot_byte, off, off, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+          }
+        } else {
+          // the same with a copy list: the sources of the next eight rounds are fetched while this round's data is
+          // on its way
+          int off[8];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) off[c] = copy_src(c);
+          for (int r0 = 0; r0 < chunk_rounds && !failed; r0 += 8) {
+            int to[8], next[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) to[c] = copy_dst(r0 + c, off[c]);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) next[c] = (r0 + 8 < chunk_rounds) ? copy_src(r0 + 8 + c) : kOutOfRange;
+            failed = !copy_chunks<8, true>(ring, slot_byte, off, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) off[c] = next[c];
           }
         }
         ts5 = ts4;

@@ -290,7 +290,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   // --- column compaction (Section 6: "split a row among multiple blocks ... loading activations" dominates for
   // very large, very sparse layers): a workgroup only copies the 16-byte chunks of h that its rows read, into
   // consecutive LDS positions.  Used when the whole of h does not fit in LDS, or when every workgroup needs
-  // clearly less than all of it; otherwise LDS mirrors the ring slot.
+  // less than half of it; otherwise LDS mirrors the ring slot.
   const int cpc = batch >= 4 ? 1 : 4 / batch;                 // columns per 16-byte chunk
   const int planes = batch == 8 ? 2 : 1;
   const int chunks_per_plane = ceil_div(hidden, cpc);
@@ -316,14 +316,15 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   for (auto& v : wg_chunks) need_max = std::max(need_max, v.size());
   const int copies = m.grid == 1 ? 2 : 1;   // a single workgroup double-buffers h in LDS, several exchange it through the ring
   const bool identity_fits = (int64_t)copies * m.h_bytes + 256 + m.stage_bytes <= kLdsLimit;
-  bool compact = m.compact == 1 || (m.compact == 0 && (!identity_fits || need_max * 10 < (size_t)chunks_per_plane * 6));
+  // (scattered 16-byte reads cost more per byte than the contiguous copy: measured break-even near one half)
+  bool compact = m.compact == 1 || (m.compact == 0 && (!identity_fits || need_max * 2 < (size_t)chunks_per_plane));
   if (m.grid == 1) compact = false;          // a single workgroup produces all of h itself
   if (!compact && !identity_fits) return SPRNN_ERR_CAPACITY;
   m.compact = compact ? 1 : 0;
   int64_t lds_plane;                          // bytes of one plane of the LDS copy (bounds the packed offsets)
   if (compact) {
     const int rounds = ceil_div((int64_t)planes * (int64_t)need_max, m.block);
-    m.fill_rows = rounds <= 4 ? 4 : (rounds + 7) / 8 * 8;
+    m.fill_rows = rounds;
     m.lds_bytes = rounds * m.block * 16;
     lds_plane = (int64_t)need_max * 16;
     if ((int64_t)m.lds_bytes + 256 + m.stage_bytes > kLdsLimit) return SPRNN_ERR_CAPACITY;
@@ -343,25 +344,20 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   const int NW = m.template_words;
   if (compact) {
     // copy list: entry e = c * block + tid of a workgroup is the ring byte offset of the chunk that thread tid
-    // copies in round c to LDS position e * 16; bit 0 marks an entry past the end (the thread then repeats its
-    // round-0 copy).  Both planes of a batch-8 layout follow each other, so plane 1 starts at (chunks) * 16.
-    P.fill_src.assign((size_t)m.grid * m.fill_rows * m.block, 0u);
+    // copies in round c to LDS position e * 16, or an out-of-range offset past the end of the list.  Both planes
+    // of a batch-8 layout follow each other, so plane 1 starts at (chunks) * 16 in LDS.
+    constexpr uint32_t kEmptyEntry = 0x7ffffff0u;
+    P.fill_src.assign((size_t)m.grid * m.fill_rows * m.block, kEmptyEntry);
     P.wg_plane.assign(m.grid, 0);
     for (int wg = 0; wg < m.grid; ++wg) {
       const auto& ch = wg_chunks[wg];
       const size_t n = ch.size();
       P.wg_plane[wg] = (int32_t)(n * 16);
-      for (int c = 0; c < m.fill_rows; ++c)
-        for (int t = 0; t < m.block; ++t) {
-          const size_t e = (size_t)c * m.block + t;
-          auto src_of = [&](size_t i) { return (uint32_t)((i / n) * ((size_t)hidden * 16) + (size_t)ch[i % n] * 16); };
-          // past the end: repeat the thread's round-0 copy (same source, same LDS position t * 16); a thread whose
-          // round-0 entry is itself past the end copies chunk 0 into its own, otherwise unused, position
-          const uint32_t v = e < n * planes ? src_of(e) : (src_of((size_t)t < n * planes ? (size_t)t : 0) | 1u);
-          P.fill_src[((size_t)wg * m.fill_rows + c) * m.block + t] = v;
-        }
+      for (size_t e = 0; e < n * planes; ++e)
+        P.fill_src[(size_t)wg * m.fill_rows * m.block + e] = (uint32_t)((e / n) * ((size_t)hidden * 16) + (size_t)ch[e % n] * 16);
     }
   }
+
   const size_t lanes = (size_t)m.grid * m.block;
   P.words.assign(lanes * NW, 0u);
   P.lane_row.assign(lanes, -1);

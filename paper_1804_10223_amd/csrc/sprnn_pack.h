@@ -37,7 +37,7 @@ struct Mapping {
   int h_bytes = 0;           // bytes of one copy of h in LDS / one ring slot (multiple of 16)
   int lds_bytes = 0;         // LDS taken by h: h_bytes, 2 * h_bytes for a single workgroup, less with column compaction
   int compact = 0;           // 1: a workgroup copies only the chunks of h that its rows read (see pack())
-  int fill_rows = 0;         // compaction: rounds in the per-workgroup copy list (4, or a multiple of 8)
+  int fill_rows = 0;         // compaction: rounds in the per-workgroup copy list
   int stage_bytes = 0;       // LSTM: per-workgroup LDS area through which gate sums reach the cell lanes
   int64_t nnz = 0, padded_words = 0;
 };
@@ -48,7 +48,7 @@ struct Packed {
   std::vector<int32_t> lane_row;    // [grid][block]  row of W served by the lane, -1 if idle
   std::vector<int32_t> lane_words;  // [grid][block]  real (non-padding) words of the lane
   std::vector<int32_t> wave_words;  // [grid][waves]  loop trip count of each wavefront
-  std::vector<uint32_t> fill_src;   // compaction: [grid][fill_rows][block] ring byte offset of each copied chunk (bit 0: repeat)
+  std::vector<uint32_t> fill_src;   // compaction: [grid][fill_rows][block] ring byte offset of each copied chunk (out of range: none)
   std::vector<int32_t> wg_plane;    // compaction: [grid] bytes of one plane of the workgroup's LDS copy
 };
 
