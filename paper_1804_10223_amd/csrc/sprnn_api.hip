@@ -34,7 +34,7 @@ struct sprnn_handle_s {
   int32_t* d_col = nullptr;
   uint16_t* d_val = nullptr;
   uint32_t step_base = 0;        // global step index at which the next forward starts
-  uint32_t barrier_base = 0;     // barrier arrivals so far (grid-barrier mode)
+  uint32_t barrier_base = 0;     // grid barriers completed so far (grid-barrier mode)
   bool poisoned = false;         // a watchdog trip was observed: the ring no longer holds a consistent state
 };
 
@@ -264,12 +264,13 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
     a.step_base = h->step_base; a.barrier_base = h->barrier_base;
     void* args[] = {&a};
-    const bool plain = m.plain_launch != 0;
+    // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
+    const bool plain = m.plain_launch != 0 || m.grid == 1;
     hipError_t e = plain ? hipLaunchKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
                          : hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
     h->step_base += (uint32_t)tn;
-    h->barrier_base += (uint32_t)(tn - 1) * (uint32_t)m.grid;   // one barrier before every step but the first
+    h->barrier_base += (uint32_t)(tn - 1);   // one barrier before every step but the first
   }
   return SPRNN_OK;
 }

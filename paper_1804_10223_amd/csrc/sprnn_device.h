@@ -13,8 +13,8 @@ namespace sprnn {
 constexpr int kRingSlotsDev = 4;                  // exchange ring depth (power of two)
 constexpr uint32_t kSentinelBits = 0x80000000u;   // -0.0f marks a ring element that is not written yet
 constexpr int kCtrlStatus = 0;                    // ctrl[0]: non-zero once a spin watchdog tripped
-constexpr int kCtrlBarrier = 32;                  // ctrl[32]: arrival counter of the grid-barrier mode (own cache line)
-constexpr int kCtrlWords = 64;
+constexpr int kCtrlBarrier = 32;                  // grid-barrier mode: ctrl[32] top counter, ctrl[32 + 16 (1 + g)] counter of group g (64 bytes apart)
+constexpr int kCtrlWords = kCtrlBarrier + 16 * 9;
 constexpr int kTimelineSlots = 16;                // 64-bit accumulators per workgroup in the phase timeline
 constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after h: abort flags, timeline sums
 
@@ -38,7 +38,7 @@ struct KernelArgs {
   int jitter;                 // test aid: seed of pseudo-random pauses (0 = none)
   int index_shift;            // LDS byte offset of a packed word = (word >> 16) << index_shift
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
-  uint32_t barrier_base;      // barrier arrivals before this call
+  uint32_t barrier_base;      // grid barriers completed before this call (step t waits at barrier number barrier_base + t)
 };
 
 struct StepArgs {

@@ -432,8 +432,21 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
-          __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          const uint32_t target = p.barrier_base + (uint32_t)t * (uint32_t)gridDim.x;
+          // Counters only grow: barrier number n (counted since the handle was created) is complete when its counter
+          // reaches n * arrivals.  A small grid arrives at and waits on one counter.  A large one uses two levels, so
+          // that no counter sees more than 32 arrivals: workgroup w belongs to group w % 8 (the XCD it is normally
+          // dispatched to), the last arrival of a group reports to the top counter, and everybody waits for that.
+          const uint32_t n = p.barrier_base + (uint32_t)t;
+          uint32_t target;
+          if (gridDim.x < 64u) {
+            __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            target = n * gridDim.x;
+          } else {
+            const uint32_t grp = (uint32_t)wg % 8u, members = gridDim.x / 8u + (grp < gridDim.x % 8u ? 1u : 0u);
+            const uint32_t before = __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier + 16 * (1 + grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (before + 1 == n * members) __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            target = n * 8u;
+          }
           int spins = 0;
           for (;;) {
             const uint32_t seen = __hip_atomic_load(p.ctrl + kCtrlBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
