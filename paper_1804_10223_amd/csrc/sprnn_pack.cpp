@@ -294,11 +294,22 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   const int cpc = batch >= 4 ? 1 : 4 / batch;                 // columns per 16-byte chunk
   const int planes = batch == 8 ? 2 : 1;
   const int chunks_per_plane = ceil_div(hidden, cpc);
+  // Flow control: the exchange ring is only safe because a workgroup cannot start step t before it has seen
+  // something of step t-1 from EVERY workgroup (that is what keeps all of them within one step of each other and
+  // lets a producer re-arm a slot two steps ahead).  Copying all of h gives that for free; a compacted copy must
+  // keep it, so every workgroup's list also contains the chunk of the first unit of every workgroup.
+  std::vector<int32_t> first_chunk_of_wg;
+  for (int wg = 0; wg < m.grid; ++wg)
+    for (int i = 0; i < m.waves * upw; ++i) {
+      const int u = wave_units[(size_t)wg * m.waves * upw + i];
+      if (u >= 0) { first_chunk_of_wg.push_back(u / cpc); break; }
+    }
   std::vector<std::vector<int32_t>> wg_chunks(m.grid);         // sorted needed chunks (of one plane) per workgroup
   {
     std::vector<char> mark(chunks_per_plane);
     for (int wg = 0; wg < m.grid; ++wg) {
       std::fill(mark.begin(), mark.end(), 0);
+      for (int32_t c : first_chunk_of_wg) mark[c] = 1;
       for (int wave = 0; wave < m.waves; ++wave)
         for (int s = 0; s < upw; ++s) {
           const int u = wave_units[((size_t)wg * m.waves + wave) * upw + s];
@@ -309,7 +320,6 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
           }
         }
       for (int c = 0; c < chunks_per_plane; ++c) if (mark[c]) wg_chunks[wg].push_back(c);
-      if (wg_chunks[wg].empty()) wg_chunks[wg].push_back(0);   // keeps every table non-empty
     }
   }
   size_t need_max = 1;

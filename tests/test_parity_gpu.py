@@ -173,6 +173,33 @@ def test_zero_weights_bit_exact(cell):
     assert np.array_equal(h, want + np.float32(0))       # +0: a -0.0 result is written as +0.0
 
 
+def test_workgroups_that_read_nothing_of_each_other_stay_in_step():
+    # zero weights with column compaction: no workgroup needs any column of h, so only the flow-control entries of
+    # the copy lists keep the workgroups within one step of each other (without them a fast workgroup would
+    # overwrite ring slots that a slow one has not read); pauses widen the window, many steps give it room
+    H, B, T = 3000, 2, 400
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((T, B, H)).astype(np.float32)
+    row_ptr = np.zeros(H + 1, dtype=np.int32)
+    for seed in (0, 7):
+        with binding.SparseRNN(H, B, "relu", row_ptr, np.zeros(0, np.int32), np.zeros(0, np.uint16), compact=1, jitter=seed, grid=60) as rnn:
+            assert rnn.info()["compact"] == 1
+            h = rnn.forward(_dev(x), None).cpu().numpy()
+            assert rnn.check() == binding.SPRNN_OK
+        assert np.array_equal(h, np.maximum(x, np.float32(0)) + np.float32(0))
+    # block-diagonal weights: every workgroup reads only its own rows' columns
+    w = wl.make_workload("blk", "relu", 1920, 4, 300, 0.02, seed=15, h0_std=0.4)
+    keep = (w.col_idx // 64) == (np.repeat(np.arange(1920), np.diff(w.row_ptr)) // 64)
+    counts = np.add.reduceat(keep.astype(np.int64), w.row_ptr[:-1])
+    w.col_idx, w.val_bits = w.col_idx[keep], w.val_bits[keep]
+    w.row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    want, _ = oracle_run(w)
+    for seed in (0, 3):
+        with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, compact=1, jitter=seed, grid=30) as rnn:
+            got, _ = gpu_run(rnn, w)
+        assert_parity(got, want, "block diagonal, jitter %d" % seed)
+
+
 def test_empty_rows_and_stored_zeros():
     H, B, T = 90, 2, 6
     w = wl.make_workload("e", "relu", H, B, T, 0.2, seed=2, h0_std=0.5)
@@ -249,6 +276,8 @@ def test_consecutive_forwards_and_time_composition():
 
 @pytest.mark.parametrize("cell,H,B,opts", [
     ("relu", 1152, 4, {}),
+    ("relu", 3000, 4, {"compact": 1, "grid": 150}),
+    ("lstm", 800, 4, {"compact": 1}),
     ("relu", 1152, 4, {"sync": "barrier"}),
     ("relu", 2000, 2, {"grid": 250, "poll_delay": 2}),
     ("lstm", 512, 8, {}),
