@@ -6,7 +6,8 @@ import this module; only ``tests/``, the smoke check and the benchmark's
 CPU-baseline leg do.  It imports nothing from the product package.
 
 Cells and equations: see the header of ``sprnn_oracle.c`` (Eq. 2 of the paper
-for the vanilla cell; Appendix B's four-gate LSTM).
+for the vanilla cell; Appendix B's four-gate LSTM; Section 3.1's input
+projection b' = W x + b).
 """
 from __future__ import annotations
 
@@ -54,6 +55,8 @@ def _load():
         lib.oracle_lstm_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f32p, ci]
         lib.oracle_lstm_forward_f64.restype = ci
         lib.oracle_lstm_forward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, f64p, ci]
+        lib.oracle_input_projection_f64.restype = ci
+        lib.oracle_input_projection_f64.argtypes = [ci, ci, ci, u16p, f32p, f32p, f64p, ci]
         _lib = lib
     return _lib
 
@@ -140,3 +143,28 @@ def lstm_forward(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, h0=None
     if rc != 0:
         raise RuntimeError("oracle_lstm_forward failed")
     return h, c
+
+
+def input_projection(w_bits, x, bias=None, threads: int = 1) -> np.ndarray:
+    """b' = W x + b of Section 3.1 for every input vector: w_bits [R, I] binary16 bits, x [..., I] float32,
+    bias [R] float32 or None; returns float64 [..., R]."""
+    lib = _load()
+    w_bits = np.ascontiguousarray(w_bits, dtype=np.uint16)
+    if w_bits.ndim != 2:
+        raise ValueError("w_bits must be [R, I]")
+    R, I = w_bits.shape
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.shape[-1] != I:
+        raise ValueError("last axis of x must be I")
+    lead = x.shape[:-1]
+    M = int(np.prod(lead, dtype=np.int64))
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if bias.shape != (R,):
+            raise ValueError("bias must be [R]")
+    out = np.empty((M, R), dtype=np.float64)
+    rc = lib.oracle_input_projection_f64(R, I, M, _ptr(w_bits, ctypes.c_uint16), _ptr(x.reshape(M, I), ctypes.c_float),
+                                         _ptr(bias, ctypes.c_float), _ptr(out, ctypes.c_double), int(threads))
+    if rc != 0:
+        raise RuntimeError("oracle_input_projection_f64 failed")
+    return out.reshape(*lead, R)

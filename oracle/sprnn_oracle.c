@@ -13,6 +13,9 @@
  *   - The method of Sections 3.3 / 4 only re-orders a sparse dot product and
  *     pads it with zeros, so its result is the plain CSR row dot product; this
  *     file therefore evaluates each row in CSR order, left to right.
+ *   - Input projection: Section 3.1 rewrites Eq. 1 as Eq. 2 by computing b' = W x_t + b for all
+ *     timesteps ahead of the recurrence; oracle_input_projection_f64 is that dense product, one
+ *     row of W against one input vector at a time, summed left to right in binary64.
  *   - LSTM cell: Appendix B says only that every hidden unit has four gate rows
  *     with different activations; the standard cell without peepholes is used
  *     (gate row blocks i | f | g | o):
@@ -33,7 +36,10 @@
  * torch.nn.RNNCell / LSTMCell, identity and permutation closed forms (bit
  * exact), all-zero weights, exact rational brute force on tiny sizes,
  * homogeneity / batch-independence / time-composition invariants, and a
- * hand-worked integer example under tests/golden/.
+ * hand-worked integer example under tests/golden/.  Input projection: float64 matrix product of
+ * numpy, identity and single-entry closed forms (bit exact), exact rational brute force, a
+ * hand-worked non-square example with a bias under tests/golden/, and sensitivity checks against a
+ * transposed operand and a dropped bias.
  */
 #include <math.h>
 #include <stdint.h>
@@ -219,5 +225,29 @@ int oracle_lstm_forward_f64(int H, int B, int T, const int32_t* row_ptr, const i
   }
   free(hfirst);
   free(cfirst);
+  return 0;
+}
+
+/*
+ * Input projection b' = W x + b of Section 3.1 (Eq. 1 folded into Eq. 2) for M = T*B input vectors.
+ * w_bits is the dense [R][I] input weight matrix as binary16 bit patterns (row r holds the weights of
+ * output r), x is [M][I] float32, bias is [R] float32 or NULL (zeros), out is [M][R] binary64.
+ * Products of a binary16 and a binary32 number are exact in binary64; the sum runs over k = 0..I-1 in
+ * that order and the bias is added last.
+ */
+int oracle_input_projection_f64(int R, int I, int M, const uint16_t* w_bits, const float* x, const float* bias,
+                                double* out, int threads) {
+  if (R <= 0 || I <= 0 || M < 0 || !w_bits || !x || !out) return -1;
+#pragma omp parallel for num_threads(threads) if (threads > 1) schedule(static)
+  for (int m = 0; m < M; ++m) {
+    for (int r = 0; r < R; ++r) {
+      double acc = 0.0;
+      for (int k = 0; k < I; ++k) {
+        const double w = (double)oracle_half_bits_to_float(w_bits[(size_t)r * I + k]);
+        acc += w * (double)x[(size_t)m * I + k];
+      }
+      out[(size_t)m * R + r] = acc + (bias ? (double)bias[r] : 0.0);
+    }
+  }
   return 0;
 }

@@ -7,6 +7,9 @@ The paper prints no worked numeric example for the recurrent step (Eq. 2), so th
   * exact rational brute force on tiny sizes,
   * invariants: positive homogeneity, batch independence, time composition, fp64 twin bound,
   * exhaustive binary16 decode against numpy.
+The input projection b' = W x + b (Section 3.1) is pinned by a hand-evaluated non-square example with a
+bias (tests/golden/eq1_hand_example.json), numpy's float64 matrix product, identity / single-entry closed
+forms (bit exact), exact rational brute force, and checks that a transposed operand or a dropped bias fails.
 """
 import json
 import os
@@ -331,3 +334,67 @@ def test_generator_shapes_and_determinism():
     l = wl.make_workload("l", "lstm", 16, 2, 3, 0.25, seed=1)
     assert l.x.shape == (3, 2, 64) and l.row_ptr.shape == (65,)
     assert abs(float(l.x[:, :, 16:32].mean()) - 1.0) < 0.5      # forget-gate bias folded into b'
+
+
+# ----------------------------------------------------------------------------- input projection (Section 3.1)
+def test_golden_hand_example_input_projection():
+    with open(os.path.join(HERE, "golden", "eq1_hand_example.json")) as f:
+        g = json.load(f)
+    W = f16bits(np.array(g["W"], dtype=np.float16))
+    x = np.array(g["x"], dtype=np.float32)
+    b = np.array(g["b"], dtype=np.float32)
+    got = oracle.input_projection(W, x, b)
+    assert got.shape == (2, 2, g["rows"])
+    assert np.array_equal(got, np.array(g["b_prime"], dtype=np.float64))
+    # without the bias the hand values are missed by exactly b
+    assert np.array_equal(oracle.input_projection(W, x, None), np.array(g["b_prime"], dtype=np.float64) - b.astype(np.float64))
+
+
+def test_input_projection_matches_float64_matmul_and_is_not_its_transpose():
+    rng = np.random.default_rng(5)
+    R, I, T, B = 29, 41, 4, 3
+    w16 = (rng.standard_normal((R, I)) / np.sqrt(I)).astype(np.float16)
+    x = rng.standard_normal((T, B, I)).astype(np.float32)
+    b = rng.standard_normal(R).astype(np.float32)
+    got = oracle.input_projection(f16bits(w16), x, b)
+    want = x.astype(np.float64) @ w16.astype(np.float64).T + b.astype(np.float64)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-13)
+    assert np.array_equal(got, oracle.input_projection(f16bits(w16), x, b, threads=3))
+    # square case: the transposed operand is far away
+    ws = (rng.standard_normal((I, I)) / np.sqrt(I)).astype(np.float16)
+    g2 = oracle.input_projection(f16bits(ws), x, None)
+    assert np.abs(g2 - x.astype(np.float64) @ ws.astype(np.float64)).max() > 1e-2
+    np.testing.assert_allclose(g2, x.astype(np.float64) @ ws.astype(np.float64).T, rtol=0, atol=1e-13)
+
+
+def test_input_projection_closed_forms_bit_exact():
+    rng = np.random.default_rng(6)
+    I = 17
+    x = rng.standard_normal((5, 2, I)).astype(np.float32)
+    b = rng.standard_normal(I).astype(np.float32)
+    eye = np.eye(I, dtype=np.float16)
+    assert np.array_equal(oracle.input_projection(f16bits(eye), x, b), x.astype(np.float64) + b.astype(np.float64))
+    # one entry W[r, k] = 0.5 picks half of input k into output r and nothing else
+    W = np.zeros((3, I), dtype=np.float16)
+    W[2, 11] = 0.5
+    got = oracle.input_projection(f16bits(W), x, None)
+    want = np.zeros((5, 2, 3))
+    want[..., 2] = 0.5 * x[..., 11].astype(np.float64)
+    assert np.array_equal(got, want)
+    # zero weights leave the bias
+    assert np.array_equal(oracle.input_projection(f16bits(np.zeros((3, I), dtype=np.float16)), x, b[:3]),
+                          np.broadcast_to(b[:3].astype(np.float64), (5, 2, 3)))
+
+
+def test_input_projection_exact_rational_brute_force():
+    rng = np.random.default_rng(7)
+    R, I, M = 4, 6, 3
+    w16 = rng.standard_normal((R, I)).astype(np.float16)
+    x = rng.standard_normal((M, I)).astype(np.float32)
+    b = rng.standard_normal(R).astype(np.float32)
+    got = oracle.input_projection(f16bits(w16), x, b)
+    for m in range(M):
+        for r in range(R):
+            exact = sum((Fraction(float(w16[r, k])) * Fraction(float(x[m, k])) for k in range(I)), Fraction(0)) + Fraction(float(b[r]))
+            scale = sum(abs(float(w16[r, k]) * float(x[m, k])) for k in range(I)) + abs(float(b[r]))
+            assert abs(Fraction(float(got[m, r])) - exact) <= Fraction(scale) * Fraction(I + 1, 2 ** 52)
