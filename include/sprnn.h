@@ -141,6 +141,29 @@ int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0,
                        float* h_out, float* c_out, void* stream);
 
 /*
+ * The step before the recurrence (Section 3.1: Eq. 1's input term is computed for all timesteps ahead of
+ * time and enters Eq. 2 as b'):  b'[t][b][r] = sum_k W[r][k] x_in[t][b][k] + bias[r]  as one dense product on
+ * the matrix cores.  Its output is laid out as the `x` argument of the forward calls of the same handle, so a
+ * whole layer runs as sprnn_project followed by sprnn_forward / sprnn_forward_lstm on one stream.
+ *
+ *   input_size      I >= 1, length of one input vector.
+ *   x_in            device, float32 [T][B][I], I fastest; every |x| below 65504 (it is split into two
+ *                   binary16 numbers that together carry 22 significant bits).
+ *   w_in_fp16_bits  device, [R][I] IEEE binary16 bit patterns, row r = weights of output r (R = H, or 4H with
+ *                   gate blocks i|f|g|o for the LSTM cell).  Read, never written; the caller keeps ownership.
+ *   bias            device, float32 [R], or NULL for zeros.
+ *   b_prime         device, float32 [T][B][R]; must not overlap the inputs.
+ *   stream          hipStream_t cast to void* (NULL = default stream).
+ *
+ * Products are exact and sums are binary32; the result is within
+ *   (I + 8) * 2^-24 * (sum_k |W[r][k] x[k]| + |bias[r]|) + 2^-26 * sum_k |W[r][k]|
+ * of the exact value (the second term is the floor for inputs below 2^-14, the smallest normal binary16
+ * number).  Only enqueues work and returns; allocates nothing.  T = 0 is a no-op.
+ */
+int sprnn_project(sprnn_handle_t h, int T, int input_size, const float* x_in, const uint16_t* w_in_fp16_bits,
+                  const float* bias, float* b_prime, void* stream);
+
+/*
  * Non-persistent comparison path: one kernel launch per timestep that re-reads the CSR weights
  * from device memory every step (the per-timestep sparse product the paper compares against in
  * Section 5.2).  Same arguments and results as the persistent calls; c0 / c_out are ignored for

@@ -25,7 +25,7 @@ SPRNN_ERR_STATE = -5
 CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
-EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_stepwise",
+EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_stepwise", "sprnn_project",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
 
@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_forward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_stepwise.restype = ci
     lib.sprnn_forward_stepwise.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_project.restype = ci
+    lib.sprnn_project.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp]
     lib.sprnn_get_info.restype = ci
     lib.sprnn_get_info.argtypes = [vp, ctypes.POINTER(Info)]
     lib.sprnn_check.restype = ci
@@ -262,6 +264,23 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_forward_lstm")
         return h_out, c_out
+
+    def project(self, x_in, w_in_bits, bias=None, b_prime=None):
+        """sprnn_project: x_in [T, B, I] float32, w_in_bits [R, I] binary16 (float16 tensor, or its bits as int16/uint16),
+        bias [R] or None -> b' [T, B, R], the ``x`` argument of the forward calls."""
+        import torch
+        T, I = int(x_in.shape[0]), int(x_in.shape[-1])
+        if not (isinstance(w_in_bits, torch.Tensor) and w_in_bits.is_cuda and w_in_bits.is_contiguous()
+                and w_in_bits.element_size() == 2 and tuple(w_in_bits.shape) == (self.rows, I)):
+            raise TypeError("w_in_bits must be a contiguous 16-bit CUDA tensor of shape %s" % ((self.rows, I),))
+        if b_prime is None:
+            b_prime = torch.empty((T, self.batch, self.rows), dtype=torch.float32, device="cuda:%d" % self.device)
+        rc = self._lib.sprnn_project(self._h, T, I, _dev_ptr(x_in, (T, self.batch, I), "x_in"),
+                                     ctypes.c_void_p(w_in_bits.data_ptr()), _dev_ptr(bias, (self.rows,), "bias"),
+                                     _dev_ptr(b_prime, (T, self.batch, self.rows), "b_prime"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_project")
+        return b_prime
 
     def forward_stepwise(self, x, h0=None, c0=None, h_out=None, c_out=None):
         """sprnn_forward_stepwise: the one-launch-per-timestep comparison path; returns (h_out, c_out or None)."""

@@ -353,6 +353,20 @@ int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float*
   return SPRNN_OK;
 }
 
+int sprnn_project(sprnn_handle_t h, int T, int input_size, const float* x_in, const uint16_t* w_in_fp16_bits,
+                  const float* bias, float* b_prime, void* stream) {
+  if (!h || T < 0 || input_size <= 0) return SPRNN_ERR_INVALID;
+  if (T > 0 && (!x_in || !w_in_fp16_bits || !b_prime)) return SPRNN_ERR_INVALID;
+  if ((long long)T * h->map.batch > 0x7fffffffLL) return SPRNN_ERR_INVALID;
+  if (T == 0) return SPRNN_OK;
+  DeviceGuard guard(h->device);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  const hipError_t e = launch_project(x_in, w_in_fp16_bits, bias, b_prime, T * h->map.batch, h->map.rows, input_size,
+                                      static_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue) return SPRNN_ERR_INVALID;
+  return SPRNN_HIP(e) ? SPRNN_OK : SPRNN_ERR_HIP;
+}
+
 int sprnn_read_timeline(sprnn_handle_t h, uint64_t* out, int capacity_words, double* ticks_per_second) {
   if (!h || !out) return SPRNN_ERR_INVALID;
   if (!h->d_timeline) return SPRNN_ERR_UNSUPPORTED;

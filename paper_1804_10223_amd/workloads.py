@@ -121,6 +121,30 @@ def make_config(name: str, seed: int = 0, steps: Optional[int] = None) -> Worklo
     return make_workload(name, seed=seed, **kw)
 
 
+@dataclass
+class Projection:
+    """Inputs of the step before the recurrence (Section 3.1): b' = W_in x + b for all timesteps."""
+    rows: int                 # R: H, or 4H for an LSTM (gate blocks i | f | g | o)
+    input_size: int           # I
+    w_bits: np.ndarray        # uint16 [R, I], dense IEEE binary16 bit patterns
+    bias: np.ndarray          # float32 [R]
+    x_in: np.ndarray          # float32 [T, B, I]
+
+
+def make_projection(rows: int, input_size: int, steps: int, batch: int, seed: int = 0, x_scale: float = 1.0,
+                    forget_block: Optional[tuple] = None, forget_bias: float = 1.0) -> Projection:
+    """Dense input weights N(0, 1/I) rounded once to binary16, bias N(0, 0.1^2) (+forget_bias on rows
+    forget_block = (first, last)), inputs N(0, x_scale^2); drawn in that order from PCG64(seed)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    w = rng.standard_normal((rows, input_size), dtype=np.float32) / np.float32(np.sqrt(input_size))
+    w_bits = w.astype(np.float16).view(np.uint16).copy()
+    bias = (rng.standard_normal(rows, dtype=np.float32) * np.float32(0.1)).astype(np.float32)
+    if forget_block is not None:
+        bias[forget_block[0]:forget_block[1]] += np.float32(forget_bias)
+    x_in = (rng.standard_normal((steps, batch, input_size), dtype=np.float32) * np.float32(x_scale)).astype(np.float32)
+    return Projection(rows=rows, input_size=input_size, w_bits=w_bits, bias=bias, x_in=x_in)
+
+
 def csr_from_dense(dense_fp16: np.ndarray):
     """CSR (row_ptr, col_idx, val_bits) of the nonzero pattern of a float16 matrix; stored zeros are dropped."""
     dense_fp16 = np.asarray(dense_fp16, dtype=np.float16)
