@@ -14,6 +14,8 @@ Reported beside the throughput:
                 latency + time to bring h into one CU), its three device constants measured live by
                 libsprnn_probe, and achieved/peak in microseconds per timestep.
   stepwise      the non-persistent comparison path (one launch per timestep) on the same inputs.
+  projection    the step before the path (sprnn_project: b' = W x + b for all timesteps, input size = hidden size)
+                against the dense fp16 MFMA peak, and the whole layer (projection + recurrence) per call.
   cpu_baseline  the CPU oracle as it stands, timed on the host cores of this machine.
 """
 from __future__ import annotations
@@ -79,6 +81,38 @@ def measure_config(name, steps, warmup, torch, with_stepwise=True, options=None)
         res["stepwise_ms"] = float(np.median(sper))
     rnn.close()
     return res
+
+
+def measure_projection(w, steps, warmup, torch):
+    """The step before the path (Section 3.1's b' = W x + b for all timesteps, sprnn_project) on the same shape with
+    input size = hidden size, and the whole layer (projection then recurrence on one stream)."""
+    from paper_1804_10223_amd import binding, workloads as wl
+    p = wl.make_projection(w.rows, w.hidden, w.steps, w.batch, seed=1,
+                           forget_block=(w.hidden, 2 * w.hidden) if w.cell == "lstm" else None)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        x_in = torch.from_numpy(p.x_in).cuda()
+        w_in = torch.from_numpy(p.w_bits.view(np.int16)).cuda()
+        bias = torch.from_numpy(p.bias).cuda()
+        bp = torch.empty((w.steps, w.batch, w.rows), dtype=torch.float32, device="cuda")
+        h_out = torch.empty((w.steps, w.batch, w.hidden), dtype=torch.float32, device="cuda")
+        c_out = torch.empty_like(h_out) if w.cell == "lstm" else None
+        _, per_call = time_forward(lambda: rnn.project(x_in, w_in, bias, bp), steps, warmup, torch)
+
+        def layer():
+            rnn.project(x_in, w_in, bias, bp)
+            if w.cell == "lstm":
+                rnn.forward_lstm(bp, None, None, h_out, c_out)
+            else:
+                rnn.forward(bp, None, h_out)
+        _, per_layer = time_forward(layer, steps, warmup, torch)
+        if rnn.check() != 0:
+            raise RuntimeError("spin watchdog tripped during the layer benchmark")
+    us = float(np.median(per_call)) * 1e3
+    flops = 2.0 * w.steps * w.batch * w.rows * w.hidden
+    return {"kernel": "project_kernel (v_mfma_f32_32x32x16_f16, x split into two fp16 halves)", "input_size": w.hidden,
+            "us_per_launch": us, "bound": "mfma", "achieved": flops / us * 1e-6, "peak": 2500.0, "unit": "TFLOP/s",
+            "frac": flops / us * 1e-6 / 2500.0, "flops_algorithmic": flops, "mfma_flops_executed": 2.0 * flops,
+            "layer_ms": float(np.median(per_layer))}
 
 
 def roofline_for(w, info, probe_vals):
@@ -184,6 +218,10 @@ def main():
         args.config, us_per_ts, res["kernel_ms"], T, value, roof["t_roof_us"], 100 * roof["t_roof_us"] / us_per_ts))
     log("  mapping: " + json.dumps({k: info[k] for k in ("grid", "block", "lanes_per_row", "template_words", "words_per_lane_max", "lds_bytes", "sync", "bank_aware", "balance", "poll_delay", "lds_pass_factor", "padded_words", "nnz")}))
 
+    proj = measure_projection(w, args.steps, args.warmup, torch)
+    log("  input projection (input size %d): %.1f us per launch, %.1f TFLOP/s algorithmic; whole layer %.3f ms" % (
+        proj["input_size"], proj["us_per_launch"], proj["achieved"], proj["layer_ms"]))
+
     table = []
     if args.all_configs:
         for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
@@ -249,6 +287,7 @@ def main():
             "kernel_ms_per_launch": res["kernel_ms"],
         },
         "stepwise": {"us_per_timestep": res["stepwise_ms"] * 1e3 / T, "speedup_of_persistent": res["stepwise_ms"] / res["kernel_ms"]},
+        "projection": proj,
         "cpu_baseline": cpu,
     }
     if table:

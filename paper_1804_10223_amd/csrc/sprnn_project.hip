@@ -4,106 +4,121 @@
 // ahead of the recurrence.  That term is one dense product over M = T * B input vectors; both operands are
 // contiguous along k, so a wavefront's MFMA fragments (8 consecutive k of one row per lane) are 16-byte reads.
 //
-// Precision: W is binary16 (exact in the MFMA), x is binary32.  Each x is split once, while it is staged into
-// LDS, into hi = fp16(x) and lo = fp16((x - hi) * 2^11); hi + lo / 2^11 carries 22 significant bits of x.  The
-// two halves go through v_mfma_f32_32x32x16_f16 with separate binary32 accumulators that are combined in the
-// epilogue, so products are exact and every sum is binary32.  The scale keeps lo a normal binary16 number
-// whenever x is, and hi is forced to zero where it would be subnormal, so the result does not depend on how
-// the matrix cores treat subnormal inputs.  |x| must stay below the binary16 maximum (65504).
+// Precision: W is binary16 (exact in the MFMA, subnormals included), x is binary32.  Each x is split once,
+// while it is staged into LDS, into hi = fp16(x) (rounded toward zero) and lo = fp16((x - hi) * 2^11) (rounded to
+// nearest); hi + lo / 2^11 reproduces x to 2^-21 relative.  The two halves go through v_mfma_f32_32x32x16_f16 with
+// separate binary32 accumulators that are combined in the epilogue, so products are exact and every sum is
+// binary32.  The scale keeps lo in the normal binary16 range whenever x is.  |x| must stay below the binary16
+// maximum (65504).
 //
-// Tiling: a workgroup of four wavefronts owns a 64 (m) x 128 (n) tile of b' and walks k in slabs of 64; each
-// wavefront owns 32 x 64 of it (two 32x32 MFMA tiles, hi and lo accumulators each).  The next slab is fetched
-// into registers while the current one is multiplied out of LDS.  LDS rows are padded by 16 bytes so that the
-// eight lanes served in one LDS pass touch all banks.  Consecutive tiles of one n block (the same rows of W)
-// are dealt to workgroups that share an XCD, hence an L2.
+// Tiling: a workgroup of four wavefronts owns a 64 (m) x 64 NJ (n) tile of b' and walks k in slabs of 64; each
+// wavefront owns 32 x 32 NJ of it (NJ 32x32 MFMA tiles, hi and lo accumulators each).  Two LDS stages: while slab
+// s is multiplied out of one, slab s + 1 is converted and written into the other between the MFMAs, and slabs
+// s + 2 and s + 3 are in flight from memory in two register sets; one workgroup barrier per slab.  LDS rows are
+// padded by 16 bytes so that the eight lanes served in one LDS pass touch all banks.  Consecutive tiles of one n
+// block (the same rows of W) are dealt to workgroups that share an XCD, hence an L2.
+#include <cstdlib>
+
 #include "sprnn_device.h"
 
 namespace sprnn {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBM = 64;                 // rows of x (time x batch) per workgroup tile
-constexpr int kBN = 128;                // rows of W (outputs) per workgroup tile
 constexpr int kBK = 64;                 // k per slab
-constexpr int kRowHalfs = kBK + 8;      // LDS row pitch: 144 bytes
+constexpr int kPitch = (kBK + 8) * 2;   // LDS row pitch in bytes: 144
 constexpr int kThreads = 256;
 constexpr float kLoScale = 2048.0f;
-constexpr float kMinNormalHalf = 6.103515625e-05f;
+constexpr int kAPlane = kBM * kPitch;   // bytes of the hi (or lo) plane of one stage
+constexpr int stage_bytes(int nj) { return 2 * kAPlane + 64 * nj * kPitch; }
 
+// NJ = 32-wide MFMA tiles per wavefront along n.
+template <int NJ>
 struct SlabRegs {
-  float4 a[4];   // 4 x (4 consecutive k of one x row)
-  uint4 b[4];    // 4 x (8 consecutive k of one W row, binary16 bits)
+  float4 a[4];        // 4 x (4 consecutive k of one x row)
+  uint4 b[2 * NJ];    // 2 NJ x (8 consecutive k of one W row, binary16 bits)
 };
 
-__device__ __forceinline__ void load_slab(SlabRegs& r, const float* __restrict__ X, const uint16_t* __restrict__ W, int tid,
-                                          int m0, int n0, int k0, int M, int N, int K, bool a_vec, bool b_vec) {
+// Per-thread constants of the staging copies: chunk i of a thread is x row (tid / 16 + 16 i), k (tid % 16) * 4 and
+// W row (tid / 8 + 32 i), k (tid % 8) * 8 of the slab.
+template <int NJ>
+struct Staging {
+  uint32_t a_off[4];        // byte offset of the chunk from x + m0 * K + k0 (row clamped to M - 1)
+  uint32_t b_off[2 * NJ];   // byte offset from W + n0 * K + k0 (row clamped to N - 1)
+};
+
+// Full slab, rows 16-byte aligned: plain vector loads at precomputed offsets.
+template <int NJ>
+__device__ __forceinline__ void load_slab_fast(SlabRegs<NJ>& r, const Staging<NJ>& st, const char* xs, const char* ws) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.a[i] = *reinterpret_cast<const float4*>(xs + st.a_off[i]);
+#pragma unroll
+  for (int i = 0; i < 2 * NJ; ++i) r.b[i] = *reinterpret_cast<const uint4*>(ws + st.b_off[i]);
+}
+
+// Any slab: element-wise loads with zeros beyond K.
+template <int NJ>
+__device__ __forceinline__ void load_slab_any(SlabRegs<NJ>& r, const float* __restrict__ X, const uint16_t* __restrict__ W,
+                                              int tid, int m0, int n0, int k0, int M, int N, int K) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int c = tid + kThreads * i;
     const int row = min(m0 + (c >> 4), M - 1);
     const int k = k0 + (c & 15) * 4;
     const float* src = X + (size_t)row * K + k;
-    if (a_vec && k + 4 <= K) {
-      r.a[i] = *reinterpret_cast<const float4*>(src);
-    } else {
-      r.a[i].x = (k + 0 < K) ? src[0] : 0.0f;
-      r.a[i].y = (k + 1 < K) ? src[1] : 0.0f;
-      r.a[i].z = (k + 2 < K) ? src[2] : 0.0f;
-      r.a[i].w = (k + 3 < K) ? src[3] : 0.0f;
-    }
+    r.a[i].x = (k + 0 < K) ? src[0] : 0.0f;
+    r.a[i].y = (k + 1 < K) ? src[1] : 0.0f;
+    r.a[i].z = (k + 2 < K) ? src[2] : 0.0f;
+    r.a[i].w = (k + 3 < K) ? src[3] : 0.0f;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2 * NJ; ++i) {
     const int c = tid + kThreads * i;
     const int row = min(n0 + (c >> 3), N - 1);
     const int k = k0 + (c & 7) * 8;
     const uint16_t* src = W + (size_t)row * K + k;
-    if (b_vec && k + 8 <= K) {
-      r.b[i] = *reinterpret_cast<const uint4*>(src);
-    } else {
-      uint32_t h[8];
+    uint32_t h[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) h[e] = (k + e < K) ? (uint32_t)src[e] : 0u;
-      r.b[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    }
+    for (int e = 0; e < 8; ++e) h[e] = (k + e < K) ? (uint32_t)src[e] : 0u;
+    r.b[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
   }
 }
 
-__device__ __forceinline__ void split(float x, _Float16& hi, _Float16& lo) {
-  hi = (fabsf(x) >= kMinNormalHalf) ? (_Float16)x : (_Float16)0.0f;
-  lo = (_Float16)((x - (float)hi) * kLoScale);
+// (x0, x1) -> packed hi halves and packed scaled lo halves.
+__device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  const auto h = __builtin_amdgcn_cvt_pkrtz(x0, x1);
+  hi = __builtin_bit_cast(uint32_t, h);
+  typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+  half2v l;
+  l[0] = (_Float16)((x0 - (float)h[0]) * kLoScale);
+  l[1] = (_Float16)((x1 - (float)h[1]) * kLoScale);
+  lo = __builtin_bit_cast(uint32_t, l);
 }
 
-__device__ __forceinline__ void store_slab(const SlabRegs& r, _Float16* a_hi, _Float16* a_lo, _Float16* b_s, int tid) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = tid + kThreads * i;
-    const int at = (c >> 4) * kRowHalfs + (c & 15) * 4;
-    half4 hi, lo;
-    _Float16 h, l;
-    split(r.a[i].x, h, l); hi[0] = h; lo[0] = l;
-    split(r.a[i].y, h, l); hi[1] = h; lo[1] = l;
-    split(r.a[i].z, h, l); hi[2] = h; lo[2] = l;
-    split(r.a[i].w, h, l); hi[3] = h; lo[3] = l;
-    *reinterpret_cast<half4*>(a_hi + at) = hi;
-    *reinterpret_cast<half4*>(a_lo + at) = lo;
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = tid + kThreads * i;
-    *reinterpret_cast<uint4*>(b_s + (c >> 3) * kRowHalfs + (c & 7) * 8) = r.b[i];
-  }
+// Convert and write chunk i of x and chunks of W of a slab into one LDS stage.
+template <int NJ>
+__device__ __forceinline__ void store_a_chunk(const SlabRegs<NJ>& r, int i, char* stage, int a_at) {
+  uint2 hi, lo;
+  split2(r.a[i].x, r.a[i].y, hi.x, lo.x);
+  split2(r.a[i].z, r.a[i].w, hi.y, lo.y);
+  *reinterpret_cast<uint2*>(stage + a_at + i * 16 * kPitch) = hi;
+  *reinterpret_cast<uint2*>(stage + kAPlane + a_at + i * 16 * kPitch) = lo;
+}
+template <int NJ>
+__device__ __forceinline__ void store_b_chunk(const SlabRegs<NJ>& r, int i, char* stage, int b_at) {
+  *reinterpret_cast<uint4*>(stage + 2 * kAPlane + b_at + i * 32 * kPitch) = r.b[i];
 }
 
+template <int NJ>
 __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restrict__ X, const uint16_t* __restrict__ W,
                                                            const float* __restrict__ bias, float* __restrict__ out,
-                                                           int M, int N, int K, int tiles_m, int a_vec, int b_vec) {
-  __shared__ __attribute__((aligned(16))) _Float16 a_hi[kBM * kRowHalfs];
-  __shared__ __attribute__((aligned(16))) _Float16 a_lo[kBM * kRowHalfs];
-  __shared__ __attribute__((aligned(16))) _Float16 b_s[kBN * kRowHalfs];
+                                                           int M, int N, int K, int tiles_m, int vec) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int kBN = 64 * NJ;
+  constexpr int kStage = stage_bytes(NJ);
 
   // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles.
   const int nb = gridDim.x, bid = blockIdx.x;
@@ -113,41 +128,106 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int r = lane & 31, kh = lane >> 5;
-  const _Float16* a_hi_row = a_hi + (wm * 32 + r) * kRowHalfs + kh * 8;
-  const _Float16* a_lo_row = a_lo + (wm * 32 + r) * kRowHalfs + kh * 8;
-  const _Float16* b_row = b_s + (wn * 64 + r) * kRowHalfs + kh * 8;
+  const int a_frag = (wm * 32 + r) * kPitch + kh * 16;                       // within the hi plane
+  const int b_frag = 2 * kAPlane + (wn * 32 * NJ + r) * kPitch + kh * 16;
+  const int a_at = (tid >> 4) * kPitch + (tid & 15) * 8;
+  const int b_at = (tid >> 3) * kPitch + (tid & 7) * 16;
 
-  floatx16 acc_hi[2], acc_lo[2];
+  Staging<NJ> st;
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int i = 0; i < 4; ++i)
+    st.a_off[i] = (uint32_t)(min(m0 + (tid >> 4) + 16 * i, M - 1) - m0) * (uint32_t)K * 4u + (uint32_t)(tid & 15) * 16u;
+#pragma unroll
+  for (int i = 0; i < 2 * NJ; ++i)
+    st.b_off[i] = (uint32_t)(min(n0 + (tid >> 3) + 32 * i, N - 1) - n0) * (uint32_t)K * 2u + (uint32_t)(tid & 7) * 16u;
+  const char* x_tile = reinterpret_cast<const char*>(X + (size_t)m0 * K);
+  const char* w_tile = reinterpret_cast<const char*>(W + (size_t)n0 * K);
+
+  floatx16 acc_hi[NJ], acc_lo[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
 #pragma unroll
     for (int v = 0; v < 16; ++v) { acc_hi[j][v] = 0.0f; acc_lo[j][v] = 0.0f; }
 
-  SlabRegs regs;
-  const int slabs = (K + kBK - 1) / kBK;
-  load_slab(regs, X, W, tid, m0, n0, 0, M, N, K, a_vec != 0, b_vec != 0);
-  for (int s = 0; s < slabs; ++s) {
-    __syncthreads();   // every wavefront is done with the previous slab
-    store_slab(regs, a_hi, a_lo, b_s, tid);
-    __syncthreads();
-    if (s + 1 < slabs) load_slab(regs, X, W, tid, m0, n0, (s + 1) * kBK, M, N, K, a_vec != 0, b_vec != 0);
+  // Fragments of 16 k of a slab: this lane's 8 k of one x row (hi and lo) and of NJ rows of W.
+  struct Frags { half8 ah, al, b[NJ]; };
+  auto read_frags = [&](Frags& f, const char* cur, int q) {
+    f.ah = *reinterpret_cast<const half8*>(cur + a_frag + q * 32);
+    f.al = *reinterpret_cast<const half8*>(cur + kAPlane + a_frag + q * 32);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) f.b[j] = *reinterpret_cast<const half8*>(cur + b_frag + j * 32 * kPitch + q * 32);
+  };
+  auto mfmas = [&](const Frags& f) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      acc_hi[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.ah, f.b[j], acc_hi[j], 0, 0, 0);
+      acc_lo[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.al, f.b[j], acc_lo[j], 0, 0, 0);
+    }
+  };
+  auto multiply = [&](const char* cur, int q) {
+    Frags f;
+    read_frags(f, cur, q);
+    mfmas(f);
+  };
+
+  // Pipelined part: the full slabs of a problem whose rows are 16-byte aligned.
+  const int nfast = vec ? K / kBK : 0;
+  auto load = [&](SlabRegs<NJ>& regs, int s) {
+    load_slab_fast<NJ>(regs, st, x_tile + (size_t)s * kBK * 4, w_tile + (size_t)s * kBK * 2);
+  };
+  // One slab: multiply slab s out of `cur` while `regs` (slab s + 1) is converted into `nxt` in the shadow of the
+  // MFMAs (harmless when there is no slab s + 1), then refill `regs` with slab s + 3 (the last slab again near the end).  After the closing barrier
+  // every wavefront is done with `cur` and `nxt` is complete.
+  auto step = [&](char* cur, char* nxt, SlabRegs<NJ>& regs, int s) {
+    Frags f[2];
+    read_frags(f[0], cur, 0);
 #pragma unroll
     for (int q = 0; q < kBK / 16; ++q) {
-      const half8 ah = *reinterpret_cast<const half8*>(a_hi_row + q * 16);
-      const half8 al = *reinterpret_cast<const half8*>(a_lo_row + q * 16);
-      const half8 b0 = *reinterpret_cast<const half8*>(b_row + q * 16);
-      const half8 b1 = *reinterpret_cast<const half8*>(b_row + 32 * kRowHalfs + q * 16);
-      acc_hi[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, b0, acc_hi[0], 0, 0, 0);
-      acc_hi[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, b1, acc_hi[1], 0, 0, 0);
-      acc_lo[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b0, acc_lo[0], 0, 0, 0);
-      acc_lo[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b1, acc_lo[1], 0, 0, 0);
+      if (q + 1 < kBK / 16) read_frags(f[(q + 1) & 1], cur, q + 1);   // the next fragments arrive under these MFMAs
+      mfmas(f[q & 1]);
+      store_a_chunk<NJ>(regs, q, nxt, a_at);
+      if (q < 2 * NJ) store_b_chunk<NJ>(regs, q < 2 * NJ ? q : 0, nxt, b_at);
     }
+    load(regs, min(s + 3, nfast - 1));   // unconditional, so that the count of loads in flight is the same on every path
+    __syncthreads();
+  };
+  if (nfast > 0) {
+    SlabRegs<NJ> r0, r1;
+    load(r0, 0);
+    load(r1, nfast > 1 ? 1 : 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) store_a_chunk<NJ>(r0, i, lds, a_at);
+#pragma unroll
+    for (int i = 0; i < 2 * NJ; ++i) store_b_chunk<NJ>(r0, i, lds, b_at);
+    load(r0, min(2, nfast - 1));
+    __syncthreads();
+    int s = 0;
+    for (; s + 2 <= nfast; s += 2) {
+      step(lds, lds + kStage, r1, s);          // stage 0 holds slab s; r1 holds slab s + 1
+      step(lds + kStage, lds, r0, s + 1);      // stage 1 holds slab s + 1; r0 holds slab s + 2
+    }
+    if (s < nfast) step(lds, lds + kStage, r1, s);
+  }
+
+  // The rest (a ragged last slab, or every slab of an unaligned problem): one slab at a time, guarded loads.
+  const int slabs = (K + kBK - 1) / kBK;
+  for (int s = nfast; s < slabs; ++s) {
+    SlabRegs<NJ> regs;
+    load_slab_any<NJ>(regs, X, W, tid, m0, n0, s * kBK, M, N, K);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) store_a_chunk<NJ>(regs, i, lds, a_at);
+#pragma unroll
+    for (int i = 0; i < 2 * NJ; ++i) store_b_chunk<NJ>(regs, i, lds, b_at);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kBK / 16; ++q) multiply(lds, q);
   }
 
   // Accumulator element v of lane (r, kh) is row 8 (v / 4) + 4 kh + v % 4, column r of its 32 x 32 tile.
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + j * 32 + r;
+  for (int j = 0; j < NJ; ++j) {
+    const int n = n0 + wn * 32 * NJ + j * 32 + r;
     if (n >= N) continue;
     const float bn = bias ? bias[n] : 0.0f;
 #pragma unroll
@@ -163,13 +243,33 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
 hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, float* out, int M, int N, int K,
                           hipStream_t stream) {
   if (M <= 0 || N <= 0 || K <= 0) return hipSuccess;
-  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
-  const long long tiles = (long long)tiles_m * tiles_n;
-  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-  const int a_vec = (K % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
-  const int b_vec = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(w) % 16 == 0);
-  hipLaunchKernelGGL(project_kernel, dim3((unsigned)tiles), dim3(kThreads), 0, stream, x, w, bias, out, M, N, K, tiles_m,
-                     a_vec, b_vec);
+  if (K > (1 << 23)) return hipErrorInvalidValue;   // 32-bit byte offsets inside a tile
+  const int vec = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(w) % 16 == 0);
+  const int tiles_m = (M + kBM - 1) / kBM;
+  // Wide tiles re-read less of x and W; narrow ones keep several workgroups per CU busy on small problems.
+  const long long wide = (long long)tiles_m * ((N + 127) / 128), narrow = (long long)tiles_m * ((N + 63) / 64);
+  if (narrow > 0x7fffffffLL) return hipErrorInvalidValue;
+  // (measured: 64 x 128 tiles win as soon as they occupy most CUs; SPRNN_PROJECT_TILE=64|128 overrides for experiments)
+  static const int force = std::getenv("SPRNN_PROJECT_TILE") ? std::atoi(std::getenv("SPRNN_PROJECT_TILE")) : 0;
+  const bool use_wide = force ? force == 128 : wide >= 200;
+  // The wide kernel's two LDS stages exceed the 64 KB a launch may ask for by default: raise the limit once per device.
+  static bool raised[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (use_wide && dev >= 0 && dev < 64 && !raised[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(project_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * stage_bytes(2));
+    if (e != hipSuccess) return e;
+    raised[dev] = true;
+  }
+  if (use_wide) {
+    hipLaunchKernelGGL(project_kernel<2>, dim3((unsigned)wide), dim3(kThreads), 2 * stage_bytes(2), stream, x, w, bias, out, M,
+                       N, K, tiles_m, vec);
+  } else {
+    hipLaunchKernelGGL(project_kernel<1>, dim3((unsigned)narrow), dim3(kThreads), 2 * stage_bytes(1), stream, x, w, bias, out,
+                       M, N, K, tiles_m, vec);
+  }
   return hipGetLastError();
 }
 

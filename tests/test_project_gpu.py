@@ -136,3 +136,22 @@ def test_whole_layer_from_raw_inputs(name):
         ref = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, bp_ref, f64=True, threads=8)
     for t in range(w.steps):
         assert np.abs(h[t] - ref[t]).max() <= 1e-3 * np.abs(ref[t]).max(), t
+
+
+def test_projection_keeps_subnormal_weights_and_tiny_inputs():
+    """Binary16 subnormal weights (multiples of 2^-24) and inputs below the binary16 normal range contribute exactly."""
+    rng = np.random.default_rng(4)
+    H, B, T = 96, 2, 5
+    w_bits = rng.integers(1, 1024, size=(H, H)).astype(np.uint16)        # exponent field 0: all subnormal, positive
+    w_bits[::2] |= 0x8000                                                # every other row negative
+    x = rng.integers(-8, 9, size=(T, B, H)).astype(np.float32)
+    p = wl.Projection(rows=H, input_size=H, w_bits=w_bits, bias=np.zeros(H, np.float32), x_in=x)
+    got = run_project(H, B, "relu", p)
+    want = oracle.input_projection(w_bits, x, None)                      # integers times 2^-24: exact in binary32 too
+    assert np.array_equal(got.astype(np.float64), want)
+    # inputs of magnitude 2^-20 .. 2^-17 with 6 significant bits against weights that are small integers
+    x_tiny = (rng.integers(-63, 64, size=(T, B, H)).astype(np.float32) * np.float32(2.0 ** -23))
+    w_int = rng.integers(-4, 5, size=(H, H)).astype(np.float16)
+    p = wl.Projection(rows=H, input_size=H, w_bits=w_int.view(np.uint16).copy(), bias=np.zeros(H, np.float32), x_in=x_tiny)
+    got = run_project(H, B, "relu", p)
+    assert np.array_equal(got.astype(np.float64), oracle.input_projection(p.w_bits, x_tiny, None))
