@@ -83,13 +83,13 @@ def measure_config(name, steps, warmup, torch, with_stepwise=True, options=None)
     return res
 
 
-def measure_projection(w, steps, warmup, torch):
+def measure_projection(w, steps, warmup, torch, options=None):
     """The step before the path (Section 3.1's b' = W x + b for all timesteps, sprnn_project) on the same shape with
     input size = hidden size, and the whole layer (projection then recurrence on one stream)."""
     from paper_1804_10223_amd import binding, workloads as wl
     p = wl.make_projection(w.rows, w.hidden, w.steps, w.batch, seed=1,
                            forget_block=(w.hidden, 2 * w.hidden) if w.cell == "lstm" else None)
-    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, **(options or {})) as rnn:
         x_in = torch.from_numpy(p.x_in).cuda()
         w_in = torch.from_numpy(p.w_bits.view(np.int16)).cuda()
         bias = torch.from_numpy(p.bias).cuda()
@@ -209,7 +209,8 @@ def main():
     log("  hand-off one way: same XCD %.0f ns %s, cross XCD %.0f ns %s; fill %.1f GB/s per CU (36 KB copy %.2f us)" % (
         pv["handoff_same_ns"], pv["xcc_same"], pv["handoff_cross_ns"], pv["xcc_cross"], pv["fill_Bps"] / 1e9, pv["fill_36k_s"] * 1e6))
 
-    res = measure_config(args.config, args.steps, args.warmup, torch, options=({"poll_delay": args.poll_delay} if args.poll_delay else None))
+    options = {"poll_delay": args.poll_delay} if args.poll_delay else None
+    res = measure_config(args.config, args.steps, args.warmup, torch, options=options)
     w, info, T = res["workload"], res["info"], res["T"]
     us_per_ts = res["kernel_ms"] * 1e3 / T
     roof = roofline_for(w, info, pv)
@@ -218,7 +219,7 @@ def main():
         args.config, us_per_ts, res["kernel_ms"], T, value, roof["t_roof_us"], 100 * roof["t_roof_us"] / us_per_ts))
     log("  mapping: " + json.dumps({k: info[k] for k in ("grid", "block", "lanes_per_row", "template_words", "words_per_lane_max", "lds_bytes", "sync", "bank_aware", "balance", "poll_delay", "lds_pass_factor", "padded_words", "nnz")}))
 
-    proj = measure_projection(w, args.steps, args.warmup, torch)
+    proj = measure_projection(w, args.steps, args.warmup, torch, options=options)
     log("  input projection (input size %d): %.1f us per launch, %.1f TFLOP/s algorithmic; whole layer %.3f ms" % (
         proj["input_size"], proj["us_per_launch"], proj["achieved"], proj["layer_ms"]))
 
