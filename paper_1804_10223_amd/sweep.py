@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,casestudy] [--reps 8]
 
 Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
 closed libraries on other hardware and are not reproduced):
@@ -12,6 +12,9 @@ closed libraries on other hardware and are not reproduced):
   density / size / batch / steps
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
   constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
+  casestudy  the layer shapes of Appendix B's two tables (machine translation LSTMs at 4-12.5 % density, speech
+             recognition layers at 12 %) with random unstructured patterns, as the paper itself does for the speech
+             layers; milliseconds per 256-timestep sequence beside the paper's own figure (another GPU: context).
 
 Prints markdown tables on stdout.  Needs a GPU; every number comes from the HIP library.
 """
@@ -101,9 +104,26 @@ def axis(torch, wl, reps, title, cases):
     print()
 
 
+def casestudy(torch, wl, reps):
+    print("## Case-study layer shapes (cf. Appendix B, both tables): random unstructured pattern, T 256\n")
+    print("| layer | cell | hidden | density | batch | persistent us/step | ms per 256 steps | per-timestep launches ms | paper's sparse persistent ms (V100, its batch) | grid x block | lanes/row |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    nmt = [(256, 0.125, 0.33), (512, 0.0625, 0.37), (768, 0.0417, 0.48), (1024, 0.047, 0.55), (1024, 0.125, 0.63), (1448, 0.047, 0.78)]
+    ds2 = [(1760, 0.12, 0.72), (2560, 0.12, 0.89), (3072, 0.12, 0.94)]
+    cases = [("translation", "lstm", H, d, B, ms) for (H, d, ms) in nmt for B in (1, 4)] + \
+            [("speech", "relu", H, d, B, ms) for (H, d, ms) in ds2 for B in (1, 8)]
+    for (what, cell, H, dens, B, paper_ms) in cases:
+        w = wl.make_workload("case", cell, H, B, 256, dens, seed=0, gain=1.0 if cell == "lstm" else 0.9)
+        us, info = measure(torch, w, reps)
+        st, _ = measure(torch, w, reps, stepwise=True)
+        print("| %s | %s | %d | %.2f %% | %d | %.2f | %.3f | %.2f | %.2f | %d x %d | %d |" % (
+            what, cell, H, 100 * dens, B, us, us * 256e-3, st * 256e-3, paper_ms, info["grid"], info["block"], info["lanes_per_row"]), flush=True)
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,casestudy")
     ap.add_argument("--reps", type=int, default=8)
     args = ap.parse_args()
     import torch
@@ -124,6 +144,8 @@ def main():
         axis(torch, wl, args.reps, "Constant number of nonzeros (cf. Section 5.3): about 1.32 M, batch 4, T 256",
              [(2304, 4, 0.25, 256), (3072, 4, 0.14, 256), (4096, 4, 0.079, 256), (5760, 4, 0.04, 256), (7168, 4, 0.026, 256),
               (11520, 4, 0.01, 256)])
+    if "casestudy" in what:
+        casestudy(torch, wl, args.reps)
     if "batch" in what:
         axis(torch, wl, args.reps, "Batch size: hidden 1792, density 10 %, T 256", [(1792, B, 0.10, 256) for B in (1, 2, 4, 8)])
     if "steps" in what:
