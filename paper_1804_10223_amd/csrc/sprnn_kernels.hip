@@ -161,22 +161,32 @@ struct Column {
   f32x4 lo, hi;
 };
 
+// `addr` is an absolute LDS address (32 bits), so the read needs no address arithmetic.  (The host pass of the
+// compiler sees a 32-bit integer turned into one of its 64-bit pointers here and would warn; it never runs this.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wint-to-pointer-cast"
+#define SPRNN_LDS_PTR(T, addr) ((const __attribute__((address_space(3))) T*)(uint32_t)(addr))
+__device__ __forceinline__ uint32_t lds_address(const void* generic) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)generic;
+}
+
 template <int B>
-__device__ __forceinline__ Column<B> gather_column(const unsigned char* hb, uint32_t off, int plane_bytes) {
+__device__ __forceinline__ Column<B> gather_column(uint32_t addr, int plane_bytes) {
   Column<B> c;
   if constexpr (B == 1) {
-    c.lo.x = *reinterpret_cast<const float*>(hb + off);
+    c.lo.x = *SPRNN_LDS_PTR(float, addr);
   } else if constexpr (B == 2) {
-    const f32x2 v = *reinterpret_cast<const f32x2*>(hb + off);
+    const f32x2 v = *SPRNN_LDS_PTR(f32x2, addr);
     c.lo.x = v.x; c.lo.y = v.y;
   } else if constexpr (B == 4) {
-    c.lo = *reinterpret_cast<const f32x4*>(hb + off);
+    c.lo = *SPRNN_LDS_PTR(f32x4, addr);
   } else {
-    c.lo = *reinterpret_cast<const f32x4*>(hb + off);
-    c.hi = *reinterpret_cast<const f32x4*>(hb + plane_bytes + off);
+    c.lo = *SPRNN_LDS_PTR(f32x4, addr);
+    c.hi = *SPRNN_LDS_PTR(f32x4, addr + (uint32_t)plane_bytes);
   }
   return c;
 }
+#pragma clang diagnostic pop
 
 template <int B>
 __device__ __forceinline__ void mac_column(float (&acc)[B], float wv, const Column<B>& c) {
@@ -198,11 +208,10 @@ __device__ __forceinline__ void mac_column(float (&acc)[B], float wv, const Colu
 // The scheduling barrier keeps the compiler from sinking a gather below the arithmetic of an earlier one,
 // so a wavefront has N wide LDS reads in flight instead of one.
 template <int B, int N>
-__device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, const float* wv, const unsigned char* hb,
-                                          int plane_bytes) {
+__device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, const float* wv, int plane_bytes) {
   Column<B> c[N];
 #pragma unroll
-  for (int j = 0; j < N; ++j) c[j] = gather_column<B>(hb, off[j], plane_bytes);
+  for (int j = 0; j < N; ++j) c[j] = gather_column<B>(off[j], plane_bytes);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int j = 0; j < N; ++j) mac_column<B>(acc, wv[j], c[j]);
@@ -210,20 +219,20 @@ __device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, 
 
 constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer this kernel addresses
 
-// The n_w (wavefront-uniform) packed words of a lane against one copy of h: gathers in groups of four so the
-// LDS reads are issued back to back; no early exit, so every register index stays static.
+// The n_w (wavefront-uniform) packed words of a lane (w_off: absolute LDS addresses of their columns): gathers in
+// groups of four so the LDS reads are issued back to back; no early exit, so every register index stays static.
 template <int B, int NW>
 __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w,
-                                        const unsigned char* hb, int plane_bytes) {
+                                        int plane_bytes) {
 #pragma unroll
   for (int k = 0; k < NW; k += 4) {
     if (k + 4 <= n_w) {
-      mac_words<B, 4>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+      mac_words<B, 4>(acc, &w_off[k], &w_val[k], plane_bytes);
     } else if (k < n_w) {   // ragged tail of 1..3 words
       const int rem = n_w - k;
-      if (rem == 3) mac_words<B, 3>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
-      else if (rem == 2) mac_words<B, 2>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
-      else mac_words<B, 1>(acc, &w_off[k], &w_val[k], hb, plane_bytes);
+      if (rem == 3) mac_words<B, 3>(acc, &w_off[k], &w_val[k], plane_bytes);
+      else if (rem == 2) mac_words<B, 2>(acc, &w_off[k], &w_val[k], plane_bytes);
+      else mac_words<B, 1>(acc, &w_off[k], &w_val[k], plane_bytes);
     }
   }
 }
@@ -306,7 +315,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
 #pragma unroll
   for (int k = 0; k < NW; ++k) {
     const uint32_t word = (k < n_w) ? p.words[((size_t)wg * NW + k) * block + tid] : 0u;
-    w_off[k] = (word >> 16) << p.index_shift;   // (the 16-bit index counts columns when byte offsets would not fit)
+    w_off[k] = lds_address(lds) + ((word >> 16) << p.index_shift);   // (the 16-bit index counts columns when byte offsets would not fit)
     w_val[k] = half_bits_to_float(word);
   }
   // After the reduction (reduce_scatter) the first B lanes of a row group each own one sample of the row: they
@@ -422,6 +431,10 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       if (t > 0) {
         __syncthreads();
         cur ^= 1;
+        // the gather offsets follow the copy (only this mapping has two), so the hot loop adds no base
+        const uint32_t delta = cur ? (uint32_t)p.lds_h_bytes : 0u - (uint32_t)p.lds_h_bytes;
+#pragma unroll
+        for (int k = 0; k < NW; ++k) w_off[k] += delta;
       }
     } else if (t > 0) {
       const int slot_byte = (int)((g - 1) & (kRingSlotsDev - 1)) * p.h_bytes;
@@ -525,7 +538,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     float acc[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) acc[b] = 0.0f;
-    operate<B, NW>(acc, w_off, w_val, n_w, lds + cur * p.lds_h_bytes, plane_bytes);
+    operate<B, NW>(acc, w_off, w_val, n_w, plane_bytes);
     ts1 = tick<TL>(tl_on);
 
     // ---- reduce over the lanes of the row: every lane ends up with the sum of its own sample
