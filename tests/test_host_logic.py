@@ -195,3 +195,13 @@ def test_auto_mapping_of_the_five_configs():
             assert info[k] == v, (name, k, info)
         assert info["grid"] <= 256 and info["waves"] <= 12 and info["lds_bytes"] <= 160 * 1024
         assert info["words_per_lane_max"] <= info["template_words"]
+
+
+def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
+    lib = binding.load_library()
+    none = ctypes.c_void_p()
+    assert lib.sprnn_forward(none, 1, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_forward_lstm(none, 1, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_forward_stepwise(none, 1, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_project(none, 1, 8, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_destroy(none) == binding.SPRNN_OK
