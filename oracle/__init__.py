@@ -6,8 +6,8 @@ import this module; only ``tests/``, the smoke check and the benchmark's
 CPU-baseline leg do.  It imports nothing from the product package.
 
 Cells and equations: see the header of ``sprnn_oracle.c`` (Eq. 2 of the paper
-for the vanilla cell; Appendix B's four-gate LSTM; Section 3.1's input
-projection b' = W x + b).
+for the vanilla cell; Appendix B's four-gate LSTM; a three-gate GRU; Section
+3.1's input projection b' = W x + b).
 """
 from __future__ import annotations
 
@@ -55,6 +55,10 @@ def _load():
         lib.oracle_lstm_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f32p, ci]
         lib.oracle_lstm_forward_f64.restype = ci
         lib.oracle_lstm_forward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, f64p, ci]
+        lib.oracle_gru_forward.restype = ci
+        lib.oracle_gru_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, ci]
+        lib.oracle_gru_forward_f64.restype = ci
+        lib.oracle_gru_forward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, ci]
         lib.oracle_input_projection_f64.restype = ci
         lib.oracle_input_projection_f64.argtypes = [ci, ci, ci, u16p, f32p, f32p, f64p, ci]
         _lib = lib
@@ -143,6 +147,33 @@ def lstm_forward(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, h0=None
     if rc != 0:
         raise RuntimeError("oracle_lstm_forward failed")
     return h, c
+
+
+def gru_forward(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, b_hn=None, h0=None,
+                f64: bool = False, threads: int = 1) -> np.ndarray:
+    """h [T, B, H] of the GRU cell; gate row blocks r | z | n; b_hn [H] is the candidate's recurrent bias."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, 3 * hidden, hidden)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T = x.shape[0]
+    if x.shape != (T, batch, 3 * hidden):
+        raise ValueError("x must be [T, B, 3H]")
+    if b_hn is not None:
+        b_hn = np.ascontiguousarray(b_hn, dtype=np.float32)
+        if b_hn.shape != (hidden,):
+            raise ValueError("b_hn must be [H]")
+    if h0 is not None:
+        h0 = np.ascontiguousarray(h0, dtype=np.float32)
+        if h0.shape != (batch, hidden):
+            raise ValueError("h0 must be [B, H]")
+    out = np.empty((T, batch, hidden), dtype=np.float64 if f64 else np.float32)
+    fn = lib.oracle_gru_forward_f64 if f64 else lib.oracle_gru_forward
+    rc = fn(hidden, batch, T, _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+            _ptr(val_bits, ctypes.c_uint16), _ptr(x, ctypes.c_float), _ptr(b_hn, ctypes.c_float),
+            _ptr(h0, ctypes.c_float), _ptr(out, ctypes.c_double if f64 else ctypes.c_float), int(threads))
+    if rc != 0:
+        raise RuntimeError("oracle_gru_forward failed")
+    return out
 
 
 def input_projection(w_bits, x, bias=None, threads: int = 1) -> np.ndarray:

@@ -23,6 +23,14 @@
  *         h_t = sigmoid(p_o) * tanh(c_t)
  *     with p_* = W_* h_{t-1} + x_*[t].
  *
+ *   - GRU cell: the paper names gated recurrent units as a cell its approach extends to and gives no
+ *     equations; the formulation of the libraries it compares with is used (three gate rows per hidden
+ *     unit, row blocks r | z | n, the recurrent bias of the candidate inside the reset product):
+ *         r = sigmoid(p_r),  z = sigmoid(p_z),  n = tanh(x_n[t] + r * (U_n h_{t-1} + b_hn))
+ *         h_t = (1 - z) * n + z * h_{t-1}
+ *     with p_r = U_r h_{t-1} + x_r[t], p_z = U_z h_{t-1} + x_z[t]; x carries the input projection and
+ *     every bias except b_hn.
+ *
  * Precision: weights are IEEE binary16 bit patterns decoded exactly to binary32
  * (Section 6 names 16-bit weights as the compressed format); activations, the
  * products and the running sums are binary32 (one rounding per multiply and per
@@ -39,7 +47,8 @@
  * hand-worked integer example under tests/golden/.  Input projection: float64 matrix product of
  * numpy, identity and single-entry closed forms (bit exact), exact rational brute force, a
  * hand-worked non-square example with a bias under tests/golden/, and sensitivity checks against a
- * transposed operand and a dropped bias.
+ * transposed operand and a dropped bias.  GRU: torch.nn.GRUCell on dense weights, closed forms (update
+ * gate saturated either way, zero weights), batch independence and time composition.
  */
 #include <math.h>
 #include <stdint.h>
@@ -249,5 +258,83 @@ int oracle_input_projection_f64(int R, int I, int M, const uint16_t* w_bits, con
       out[(size_t)m * R + r] = acc + (bias ? (double)bias[r] : 0.0);
     }
   }
+  return 0;
+}
+
+/*
+ * GRU cell.  U is [3H][H] in CSR with row blocks r | z | n; x is [T][B][3H] in the same block order;
+ * b_hn is [H] or NULL (zeros); h0 is [B][H] or NULL (zeros); h_out is [T][B][H].
+ */
+int oracle_gru_forward(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                       const uint16_t* val_bits, const float* x, const float* b_hn, const float* h0,
+                       float* h_out, int threads) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out) return -1;
+  float* zeros = (float*)calloc((size_t)B * H, sizeof(float));
+  if (!zeros) return -1;
+  for (int t = 0; t < T; ++t) {
+    const float* h_prev = (t == 0) ? (h0 ? h0 : zeros) : h_out + (size_t)(t - 1) * B * H;
+    float* h_cur = h_out + (size_t)t * B * H;
+    const float* x_t = x + (size_t)t * B * 3 * H;
+#pragma omp parallel for num_threads(threads) if (threads > 1) schedule(static)
+    for (int j = 0; j < H; ++j) {
+      for (int b = 0; b < B; ++b) {
+        float s[3];
+        for (int g = 0; g < 3; ++g) {
+          const int row = g * H + j;
+          float acc = 0.0f;
+          for (int32_t k = row_ptr[row]; k < row_ptr[row + 1]; ++k) {
+            const float w = oracle_half_bits_to_float(val_bits[k]);
+            const float prod = w * h_prev[(size_t)b * H + col_idx[k]];
+            acc = acc + prod;
+          }
+          s[g] = acc;
+        }
+        const float r = sigmoid_f32(s[0] + x_t[(size_t)b * 3 * H + j]);
+        const float z = sigmoid_f32(s[1] + x_t[(size_t)b * 3 * H + H + j]);
+        const float q = s[2] + (b_hn ? b_hn[j] : 0.0f);
+        const float rq = r * q;
+        const float n = tanhf(x_t[(size_t)b * 3 * H + 2 * H + j] + rq);
+        const float keep = z * h_prev[(size_t)b * H + j];
+        const float fresh = (1.0f - z) * n;
+        h_cur[(size_t)b * H + j] = fresh + keep;
+      }
+    }
+  }
+  free(zeros);
+  return 0;
+}
+
+/* Binary64 twin of oracle_gru_forward. */
+int oracle_gru_forward_f64(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                           const uint16_t* val_bits, const float* x, const float* b_hn, const float* h0,
+                           double* h_out, int threads) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out) return -1;
+  double* first = (double*)calloc((size_t)B * H, sizeof(double));
+  if (!first) return -1;
+  if (h0) for (size_t j = 0; j < (size_t)B * H; ++j) first[j] = (double)h0[j];
+  for (int t = 0; t < T; ++t) {
+    const double* h_prev = (t == 0) ? first : h_out + (size_t)(t - 1) * B * H;
+    double* h_cur = h_out + (size_t)t * B * H;
+    const float* x_t = x + (size_t)t * B * 3 * H;
+#pragma omp parallel for num_threads(threads) if (threads > 1) schedule(static)
+    for (int j = 0; j < H; ++j) {
+      for (int b = 0; b < B; ++b) {
+        double s[3];
+        for (int g = 0; g < 3; ++g) {
+          const int row = g * H + j;
+          double acc = 0.0;
+          for (int32_t k = row_ptr[row]; k < row_ptr[row + 1]; ++k) {
+            acc += (double)oracle_half_bits_to_float(val_bits[k]) * h_prev[(size_t)b * H + col_idx[k]];
+          }
+          s[g] = acc;
+        }
+        const double r = sigmoid_f64(s[0] + (double)x_t[(size_t)b * 3 * H + j]);
+        const double z = sigmoid_f64(s[1] + (double)x_t[(size_t)b * 3 * H + H + j]);
+        const double n = tanh((double)x_t[(size_t)b * 3 * H + 2 * H + j] + r * (s[2] + (b_hn ? (double)b_hn[j] : 0.0)));
+        h_cur[(size_t)b * H + j] = (1.0 - z) * n + z * h_prev[(size_t)b * H + j];
+      }
+    }
+  }
+  free(first);
   return 0;
 }

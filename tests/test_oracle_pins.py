@@ -10,6 +10,8 @@ The paper prints no worked numeric example for the recurrent step (Eq. 2), so th
 The input projection b' = W x + b (Section 3.1) is pinned by a hand-evaluated non-square example with a
 bias (tests/golden/eq1_hand_example.json), numpy's float64 matrix product, identity / single-entry closed
 forms (bit exact), exact rational brute force, and checks that a transposed operand or a dropped bias fails.
+The GRU cell (three gates; the paper gives no equations) is pinned against torch.nn.GRUCell, which fixes the gate
+order r, z, n and the place of the candidate's recurrent bias, and by closed forms and invariants.
 """
 import json
 import os
@@ -398,3 +400,86 @@ def test_input_projection_exact_rational_brute_force():
             exact = sum((Fraction(float(w16[r, k])) * Fraction(float(x[m, k])) for k in range(I)), Fraction(0)) + Fraction(float(b[r]))
             scale = sum(abs(float(w16[r, k]) * float(x[m, k])) for k in range(I)) + abs(float(b[r]))
             assert abs(Fraction(float(got[m, r])) - exact) <= Fraction(scale) * Fraction(I + 1, 2 ** 52)
+
+
+# ----------------------------------------------------------------------------- GRU cell
+def test_dense_gru_matches_torch_grucell_gate_order_and_bias_placement():
+    rng = np.random.default_rng(21)
+    H, B, T = 19, 3, 6
+    w16 = (rng.standard_normal((3 * H, H)) / np.sqrt(H)).astype(np.float16)
+    row_ptr, col_idx, vals = dense_csr(w16)
+    x = rng.standard_normal((T, B, 3 * H)).astype(np.float32)
+    b_hh = rng.standard_normal(3 * H).astype(np.float32)
+    h0 = rng.standard_normal((B, H)).astype(np.float32)
+    # b_hr and b_hz are additive and travel inside x; b_hn must stay inside the reset product
+    xb = x.copy()
+    xb[:, :, :2 * H] += b_hh[:2 * H]
+    got = oracle.gru_forward(H, B, row_ptr, col_idx, vals, xb, b_hh[2 * H:], h0)
+    cell = torch.nn.GRUCell(3 * H, H, bias=True).double()   # gate order r, z, n
+    with torch.no_grad():
+        cell.weight_hh.copy_(torch.from_numpy(w16.astype(np.float64)))
+        cell.weight_ih.copy_(torch.eye(3 * H, dtype=torch.float64))
+        cell.bias_ih.zero_()
+        cell.bias_hh.copy_(torch.from_numpy(b_hh.astype(np.float64)))
+        h = torch.from_numpy(h0.astype(np.float64))
+        for t in range(T):
+            h = cell(torch.from_numpy(x[t].astype(np.float64)), h)
+            np.testing.assert_allclose(got[t], h.numpy(), rtol=0, atol=2e-5)
+    g64 = oracle.gru_forward(H, B, row_ptr, col_idx, vals, xb, b_hh[2 * H:], h0, f64=True)
+    np.testing.assert_allclose(g64[-1], h.numpy(), rtol=0, atol=1e-6)   # x + b_hr, x + b_hz were rounded to binary32
+    # the candidate's recurrent bias outside the reset product, or two gate blocks swapped, must be visible
+    xo = xb.copy()
+    xo[:, :, 2 * H:] += b_hh[2 * H:]
+    assert np.abs(oracle.gru_forward(H, B, row_ptr, col_idx, vals, xo, None, h0) - got).max() > 1e-2
+    xs = xb.copy()
+    xs[:, :, 0:H], xs[:, :, H:2 * H] = xb[:, :, H:2 * H], xb[:, :, 0:H]
+    assert np.abs(oracle.gru_forward(H, B, row_ptr, col_idx, vals, xs, b_hh[2 * H:], h0) - got).max() > 1e-2
+
+
+def test_gru_closed_forms():
+    rng = np.random.default_rng(22)
+    H, B, T = 11, 2, 4
+    zero = np.zeros(3 * H + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16)
+    h0 = rng.standard_normal((B, H)).astype(np.float32)
+    b_hn = rng.standard_normal(H).astype(np.float32)
+    x = rng.standard_normal((T, B, 3 * H)).astype(np.float32)
+    # update gate saturated at 1 (sigmoid(40) == 1 in binary32): the state never changes
+    xk = x.copy()
+    xk[:, :, H:2 * H] = 40.0
+    got = oracle.gru_forward(H, B, *zero, xk, b_hn, h0)
+    assert np.array_equal(got, np.broadcast_to(h0, (T, B, H)))
+    # update gate saturated at 0, reset gate at 1, zero weights: h_t = tanh(x_n + b_hn) whatever came before
+    xf = x.copy()
+    xf[:, :, H:2 * H] = -120.0
+    xf[:, :, 0:H] = 40.0
+    got = oracle.gru_forward(H, B, *zero, xf, b_hn, h0, f64=True)
+    np.testing.assert_allclose(got, np.tanh(xf[:, :, 2 * H:].astype(np.float64) + b_hn.astype(np.float64)), rtol=0, atol=1e-15)
+    # reset gate at 0: the candidate ignores the recurrent term (a one-entry weight in the n block has no effect)
+    xr = x.copy()
+    xr[:, :, 0:H] = -120.0
+    rp = np.zeros(3 * H + 1, dtype=np.int32)
+    rp[2 * H + 1:] = 1                       # row 2H (candidate of unit 0) reads column 3
+    a = oracle.gru_forward(H, B, rp, np.array([3], np.int32), f16bits([1.5]), xr, None, h0, f64=True)
+    b = oracle.gru_forward(H, B, *zero, xr, None, h0, f64=True)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-30)
+
+
+def test_gru_time_composition_batch_independence_and_twin():
+    rng = np.random.default_rng(23)
+    H, B, T = 40, 2, 9
+    parts = [wl.make_workload("g", "relu", H, B, 1, 0.3, seed=s) for s in (1, 2, 3)]
+    row_ptr = np.concatenate([[0], np.cumsum(np.concatenate([np.diff(p.row_ptr) for p in parts]))]).astype(np.int32)
+    col_idx = np.concatenate([p.col_idx for p in parts])
+    vals = np.concatenate([p.val_bits for p in parts])
+    x = rng.standard_normal((T, B, 3 * H)).astype(np.float32)
+    b_hn = rng.standard_normal(H).astype(np.float32)
+    h0 = rng.standard_normal((B, H)).astype(np.float32)
+    full = oracle.gru_forward(H, B, row_ptr, col_idx, vals, x, b_hn, h0)
+    first = oracle.gru_forward(H, B, row_ptr, col_idx, vals, x[:4], b_hn, h0)
+    rest = oracle.gru_forward(H, B, row_ptr, col_idx, vals, x[4:], b_hn, first[-1])
+    assert np.array_equal(full, np.concatenate([first, rest]))
+    one = oracle.gru_forward(H, 1, row_ptr, col_idx, vals, x[:, 1:2], b_hn, h0[1:2])
+    assert np.array_equal(one[:, 0], full[:, 1])
+    twin = oracle.gru_forward(H, B, row_ptr, col_idx, vals, x, b_hn, h0, f64=True)
+    assert np.abs(full - twin).max() < 2e-5
+    assert np.array_equal(full, oracle.gru_forward(H, B, row_ptr, col_idx, vals, x, b_hn, h0, threads=3))
