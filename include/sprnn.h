@@ -32,8 +32,9 @@ enum {
   SPRNN_ERR_STATE = -5        /* a previous forward tripped the spin watchdog; handle unusable    */
 };
 
-/* Cell / activation g of Eq. 2.  SPRNN_CELL_LSTM selects the four-gate cell of Appendix B. */
-enum { SPRNN_ACT_RELU = 0, SPRNN_ACT_TANH = 1, SPRNN_ACT_IDENTITY = 2, SPRNN_CELL_LSTM = 3 };
+/* Cell / activation g of Eq. 2.  SPRNN_CELL_LSTM selects the four-gate cell of Appendix B, SPRNN_CELL_GRU a
+ * three-gate gated recurrent unit (Section 2 names it as a cell the approach extends to). */
+enum { SPRNN_ACT_RELU = 0, SPRNN_ACT_TANH = 1, SPRNN_ACT_IDENTITY = 2, SPRNN_CELL_LSTM = 3, SPRNN_CELL_GRU = 4 };
 
 /* Cross-workgroup hand-off of h_t (Section 4.2 discusses a global barrier versus Lamport timestamps). */
 enum {
@@ -50,7 +51,7 @@ enum {
 typedef struct sprnn_options_s {
   int grid;          /* number of persistent workgroups (<= co-resident capacity)                  */
   int waves;         /* wavefronts (64 lanes) per workgroup, 1..12                                 */
-  int lanes_per_row; /* lanes that share one weight row: batch,...,32,64 (<= 16 for the LSTM cell) */
+  int lanes_per_row; /* lanes that share one weight row: batch,...,32,64 (<= 16 for the gated cells) */
   int sync;          /* SPRNN_SYNC_*                                                               */
   int bank_aware;    /* 0 auto, 1 = bank-aware ordering of a row's nonzeros (Section 4.1, App. A),
                         2 = keep CSR order ("naive")                                               */
@@ -100,7 +101,8 @@ typedef struct sprnn_info_s {
  *
  *   hidden      H, 1..65535.
  *   batch       B in {1,2,4,8}: sequences advanced together (wide loads of Section 4.1).
- *   activation  SPRNN_ACT_* (R = H rows) or SPRNN_CELL_LSTM (R = 4H rows, row blocks i|f|g|o).
+ *   activation  SPRNN_ACT_* (R = H rows), SPRNN_CELL_LSTM (R = 4H rows, row blocks i|f|g|o) or
+ *               SPRNN_CELL_GRU (R = 3H rows, row blocks r|z|n).
  *   row_ptr     host, R+1 entries, row_ptr[0] = 0, non-decreasing.
  *   col_idx     host, nnz = row_ptr[R] entries, 0 <= col < H, strictly increasing inside a row.
  *   val_fp16_bits host, nnz IEEE binary16 bit patterns (finite).  The library rounds nothing.
@@ -141,6 +143,16 @@ int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0,
                        float* h_out, float* c_out, void* stream);
 
 /*
+ * GRU cell: x is float32 [T][B][3H] with gate blocks r|z|n (input projection and every bias except b_hn folded in),
+ * b_hn is device float32 [H] or NULL (zeros): the recurrent bias of the candidate, which sits inside the reset
+ * product; h0 is [B][H] or NULL, h_out is [T][B][H].
+ *   r = sigmoid(p_r), z = sigmoid(p_z), n = tanh(x_n + r (U_n h_{t-1} + b_hn)),  h_t = (1 - z) n + z h_{t-1}.
+ * Internally the unit keeps the four-row layout of the LSTM with the fourth row empty.
+ */
+int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn, const float* h0, float* h_out,
+                      void* stream);
+
+/*
  * The step before the recurrence (Section 3.1: Eq. 1's input term is computed for all timesteps ahead of
  * time and enters Eq. 2 as b'):  b'[t][b][r] = sum_k W[r][k] x_in[t][b][k] + bias[r]  as one dense product on
  * the matrix cores.  Its output is laid out as the `x` argument of the forward calls of the same handle, so a
@@ -167,7 +179,7 @@ int sprnn_project(sprnn_handle_t h, int T, int input_size, const float* x_in, co
  * Non-persistent comparison path: one kernel launch per timestep that re-reads the CSR weights
  * from device memory every step (the per-timestep sparse product the paper compares against in
  * Section 5.2).  Same arguments and results as the persistent calls; c0 / c_out are ignored for
- * vanilla cells.
+ * vanilla cells.  Not offered for the GRU cell (SPRNN_ERR_UNSUPPORTED).
  */
 int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                            float* h_out, float* c_out, void* stream);

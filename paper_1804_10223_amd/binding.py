@@ -22,10 +22,12 @@ SPRNN_ERR_HIP = -3
 SPRNN_ERR_UNSUPPORTED = -4
 SPRNN_ERR_STATE = -5
 
-CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3}
+CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4}
+GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
-EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_stepwise", "sprnn_project",
+EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_gru", "sprnn_forward_stepwise",
+           "sprnn_project",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
 
@@ -81,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_forward.argtypes = [vp, ci, vp, vp, vp, vp]
     lib.sprnn_forward_lstm.restype = ci
     lib.sprnn_forward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_forward_gru.restype = ci
+    lib.sprnn_forward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_forward_stepwise.restype = ci
     lib.sprnn_forward_stepwise.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sprnn_project.restype = ci
@@ -177,7 +181,7 @@ class SparseRNN:
         self._lib = load_library()
         self._h = ctypes.c_void_p()
         self.hidden, self.batch, self.cell = int(hidden), int(batch), cell
-        self.rows = self.hidden * (4 if cell == "lstm" else 1)
+        self.rows = self.hidden * GATES.get(cell, 1)
         self.device = int(device)
         keep, rp, cp, vp = _csr_args(row_ptr, col_idx, val_bits)
         opt = make_options(**options)
@@ -264,6 +268,19 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_forward_lstm")
         return h_out, c_out
+
+    def forward_gru(self, x, b_hn=None, h0=None, h_out=None):
+        """sprnn_forward_gru: x [T, B, 3H] (blocks r|z|n), b_hn [H] or None -> h_out [T, B, H]."""
+        T = int(x.shape[0])
+        if h_out is None:
+            h_out = self._alloc(T)
+        rc = self._lib.sprnn_forward_gru(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
+                                         _dev_ptr(b_hn, (self.hidden,), "b_hn"),
+                                         _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                         _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_forward_gru")
+        return h_out
 
     def project(self, x_in, w_in_bits, bias=None, b_prime=None):
         """sprnn_project: x_in [T, B, I] float32, w_in_bits [R, I] binary16 (float16 tensor, or its bits as int16/uint16),

@@ -100,7 +100,7 @@ int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 6 : 0; }
 }  // namespace
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
-                              float* h_out, float* c_out, void* stream);
+                              float* h_out, float* c_out, void* stream, const float* b_hn = nullptr);
 static int calibrate_poll_delay(sprnn_handle_s* h);
 
 extern "C" {
@@ -182,7 +182,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   h->num_cus = prop.multiProcessorCount;
   h->pass_factor = lds_pass_factor(P);
   const Mapping& m = h->map;
-  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell == SPRNN_CELL_LSTM, m.timeline != 0);
+  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU, m.timeline != 0);
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
@@ -236,7 +236,7 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 }
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
-                              float* h_out, float* c_out, void* stream) {
+                              float* h_out, float* c_out, void* stream, const float* b_hn) {
   if (h->poisoned) return SPRNN_ERR_STATE;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
@@ -259,6 +259,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.c0 = t0 ? (c_out ? c_out + (size_t)(t0 - 1) * hb : nullptr) : c0;
     a.h_out = h_out + (size_t)t0 * hb;
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
+    a.b_hn = b_hn;
     a.timeline = h->d_timeline;
     a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
@@ -317,7 +318,7 @@ static int calibrate_poll_delay(sprnn_handle_s* h) {
 
 int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream) {
   if (!h || T < 0) return SPRNN_ERR_INVALID;
-  if (h->map.cell == SPRNN_CELL_LSTM) return SPRNN_ERR_UNSUPPORTED;
+  if (h->map.cell == SPRNN_CELL_LSTM || h->map.cell == SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
   return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream);
 }
@@ -330,9 +331,18 @@ int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0,
   return forward_persistent(h, T, x, h0, c0, h_out, c_out, stream);
 }
 
+int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn, const float* h0, float* h_out,
+                      void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
+  return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream, b_hn);
+}
+
 int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                            float* h_out, float* c_out, void* stream) {
   if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell == SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
   const Mapping& m = h->map;
   const bool lstm = m.cell == SPRNN_CELL_LSTM;
   if (T > 0 && (!x || !h_out || (lstm && !c_out))) return SPRNN_ERR_INVALID;

@@ -29,6 +29,7 @@ struct KernelArgs {
   const float* x;             // [T][B][R]
   const float* h0;            // [B][H] or null
   const float* c0;            // [B][H] or null (LSTM)
+  const float* b_hn;          // [H] or null (GRU: recurrent bias of the candidate)
   float* h_out;               // [T][B][H]
   float* c_out;               // [T][B][H] (LSTM)
   unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)

@@ -324,10 +324,17 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   // pre-activation to "cell lanes" through a small per-wavefront LDS area, so that lane u * B + b owns sample b
   // of the wavefront's unit slot u: one cell update per lane.
   // Lanes that load or store nothing point out of range, where loads return zero and stores are dropped.
+  // The GRU uses the same four-row layout with an empty fourth row: its b' has three blocks per sample, its
+  // candidate row hands over the recurrent sum (+ b_hn) and b'_n separately (the reset gate multiplies only the
+  // former), the latter in the fourth row's slot, and the cell lanes keep h_{t-1} where the LSTM keeps c.
+  const bool gru = LSTM && p.act == SPRNN_CELL_GRU;
+  const int Rx = gru ? 3 * H : R;              // rows of b' per sample
   const int row = p.lane_row[(size_t)wg * block + tid];
   const int sample = sample_of_lane<B>(lane);
   const bool owner = row >= 0 && (lane & (L - 1)) < B;
-  const int x_voff = owner ? (sample * R + row) * 4 : kOutOfRange;
+  const int x_voff = (owner && row < Rx) ? (sample * Rx + row) * 4 : kOutOfRange;
+  const int gate = LSTM ? (lane / L) & 3 : 0;
+  const float bhn = (gru && owner && gate == 2 && p.b_hn) ? p.b_hn[row - 2 * H] : 0.0f;
   int out_voff, ring_voff;
   int cell_unit = -1;
   if constexpr (LSTM) {
@@ -344,7 +351,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     ring_voff = owner ? lds_offset<B>(row, sample, H) : kOutOfRange;
   }
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
-  const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * R * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * Rx * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
 
   // ---- the copy of h into LDS: 16-byte chunks.  In round c a lane copies the chunk at ring offset src to LDS
@@ -391,7 +398,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       *reinterpret_cast<f32x4*>(lds + dst) = v;
     }
   }
-  float c_state = (LSTM && cell_unit >= 0 && p.c0) ? p.c0[(size_t)(lane % B) * H + cell_unit] : 0.0f;
+  const float* const state0 = gru ? p.h0 : p.c0;
+  float c_state = (LSTM && cell_unit >= 0 && state0) ? state0[(size_t)(lane % B) * H + cell_unit] : 0.0f;
   // hand-over area of this wavefront: [unit slot][sample][gate] floats, after the flags and the timeline sums
   float* const stage = reinterpret_cast<float*>(lds_tail + kLdsTailBytes) + (LSTM ? wave * (64 / (4 * L)) * B * 4 : 0);
   const int stage_write = ((lane / (4 * L)) * B + sample) * 4 + ((lane / L) & 3);   // [unit slot][sample][gate]
@@ -542,7 +550,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     ts1 = tick<TL>(tl_on);
 
     // ---- reduce over the lanes of the row: every lane ends up with the sum of its own sample
-    const float pre = reduce_rows<B>(acc, L, lane) + xn;
+    const float red = reduce_rows<B>(acc, L, lane);
+    const float pre = red + xn;
 
     // ---- epilogue and hand-off: publish h_t, write the outputs (only the owners' stores land).
     // The re-arm stores issued one step ago must be performed before this step's data can be seen, hence the wait.
@@ -551,17 +560,29 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     const int out_soff = t * B * H * 4;
     float hval;
     if constexpr (LSTM) {
-      if (owner) stage[stage_write] = pre;
+      if (gru) {
+        if (owner && gate < 2) stage[stage_write] = pre;
+        if (owner && gate == 2) { stage[stage_write] = red + bhn; stage[stage_write + 1] = xn; }
+      } else if (owner) {
+        stage[stage_write] = pre;
+      }
       // LDS serves the operations of one wavefront in order: no hardware barrier between these writes and the
       // read, only a fence that keeps the compiler from moving one across the other
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
       const f32x4 gates = *reinterpret_cast<const f32x4*>(stage + stage_read);   // i, f, g, o of this lane's sample
-      const float c = sigmoidf_(gates.y) * c_state + sigmoidf_(gates.x) * tanhf_(gates.z);
-      c_state = c;
-      hval = sigmoidf_(gates.w) * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
-      const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c), cbuf, out_voff, out_soff, 0);
+      if (gru) {                                                                 // GRU: p_r, p_z, U_n h + b_hn, b'_n
+        const float r = sigmoidf_(gates.x), z = sigmoidf_(gates.y);
+        const float n = tanhf_(fmaf(r, gates.z, gates.w));
+        hval = fmaf(z, c_state - n, n) + 0.0f;                                   // (1 - z) n + z h_{t-1}
+        c_state = hval;
+      } else {
+        const float c = sigmoidf_(gates.y) * c_state + sigmoidf_(gates.x) * tanhf_(gates.z);
+        c_state = c;
+        hval = sigmoidf_(gates.w) * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
+        const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c), cbuf, out_voff, out_soff, 0);
+      }
     } else {
       hval = activate(p.act, pre);
     }
@@ -576,7 +597,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     }
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
     if (t + 1 < p.T) {
-      xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, (t + 1) * B * R * 4, 0));
+      xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, (t + 1) * B * Rx * 4, 0));
     }
     ts3 = tick<TL>(tl_on);
 

@@ -10,14 +10,19 @@ namespace sprnn {
 static inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 static inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
+// Gate rows per hidden unit in the caller's matrix; the gated cells are laid out with four row groups per unit
+// (the GRU leaves the fourth one empty).
+static int visible_gates(int cell) { return cell == SPRNN_CELL_LSTM ? 4 : (cell == SPRNN_CELL_GRU ? 3 : 1); }
+static bool gated(int cell) { return cell == SPRNN_CELL_LSTM || cell == SPRNN_CELL_GRU; }
+
 int validate_csr(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
                  const uint16_t* val_bits) {
   if (hidden < 1) return SPRNN_ERR_INVALID;
   if (hidden > 65535) return SPRNN_ERR_UNSUPPORTED;
   if (!(batch == 1 || batch == 2 || batch == 4 || batch == 8)) return SPRNN_ERR_UNSUPPORTED;
-  if (cell < SPRNN_ACT_RELU || cell > SPRNN_CELL_LSTM) return SPRNN_ERR_INVALID;
+  if (cell < SPRNN_ACT_RELU || cell > SPRNN_CELL_GRU) return SPRNN_ERR_INVALID;
   if (!row_ptr) return SPRNN_ERR_INVALID;
-  const int rows = hidden * (cell == SPRNN_CELL_LSTM ? 4 : 1);
+  const int rows = hidden * visible_gates(cell);
   if (row_ptr[0] != 0) return SPRNN_ERR_INVALID;
   for (int r = 0; r < rows; ++r) {
     if (row_ptr[r + 1] < row_ptr[r]) return SPRNN_ERR_INVALID;
@@ -44,8 +49,8 @@ static int pass_lanes(int batch) { return batch >= 4 ? 16 : (batch == 2 ? 32 : 6
 
 static int choose_mapping(int hidden, int batch, int cell, const std::vector<int>& row_nnz, const sprnn_options_t* opt,
                           int num_cus, Mapping* m) {
-  const bool lstm = cell == SPRNN_CELL_LSTM;
-  const int rows = hidden * (lstm ? 4 : 1);
+  const bool lstm = gated(cell);                 // four row groups per unit
+  const int rows = hidden * (lstm ? 4 : 1);      // rows of the layout (row_nnz has this many entries)
   const int lmax = lstm ? 16 : kWave;
   int maxnnz = 1;
   int64_t nnz = 0;
@@ -95,7 +100,7 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   if (!grid) grid = ceil_div(wt, waves);
   if ((int64_t)grid * waves < wt) return SPRNN_ERR_CAPACITY;
 
-  m->hidden = hidden; m->rows = rows; m->batch = batch; m->cell = cell;
+  m->hidden = hidden; m->rows = hidden * visible_gates(cell); m->batch = batch; m->cell = cell;
   // Wavefronts beyond the ones that own rows only help with copying h into LDS (more loads in flight).
   int total = waves;
   if (opt && opt->fill_waves > 0) {
@@ -123,7 +128,8 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   // Contiguous rows publish whole cache lines per workgroup; dealing rows by nonzero count scatters a workgroup's
   // rows over the exchange ring.  On the measured shapes the scatter costs more than about 15 % of zero padding
   // saves, so rows are only dealt by count when the longest row exceeds the mean by more than a quarter.
-  if (balance == 0) balance = ((int64_t)maxnnz * rows > nnz + nnz / 4 + rows) ? 1 : 2;
+  const int64_t real_rows = (int64_t)hidden * visible_gates(cell);   // the GRU's empty fourth rows do not count
+  if (balance == 0) balance = ((int64_t)maxnnz * real_rows > nnz + nnz / 4 + real_rows) ? 1 : 2;
   m->balance = balance;
   m->poll_delay = opt ? opt->poll_delay : 0;
   m->spin_limit = (opt && opt->spin_limit > 0) ? opt->spin_limit : (1 << 22);
@@ -240,8 +246,15 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
          const uint16_t* val_bits, const sprnn_options_t* opt, int num_cus, Packed* out) {
   int rc = validate_csr(hidden, batch, cell, row_ptr, col_idx, val_bits);
   if (rc != SPRNN_OK) return rc;
-  const bool lstm = cell == SPRNN_CELL_LSTM;
+  const bool lstm = gated(cell);
   const int rows = hidden * (lstm ? 4 : 1);
+  // the GRU's three row blocks become four with an empty last one
+  std::vector<int32_t> padded_row_ptr;
+  if (cell == SPRNN_CELL_GRU) {
+    padded_row_ptr.assign(row_ptr, row_ptr + 3 * hidden + 1);
+    padded_row_ptr.resize((size_t)rows + 1, row_ptr[3 * hidden]);
+    row_ptr = padded_row_ptr.data();
+  }
   std::vector<int> row_nnz(rows);
   for (int r = 0; r < rows; ++r) row_nnz[r] = row_ptr[r + 1] - row_ptr[r];
   Mapping m;
@@ -420,7 +433,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
     order_wave(rg, L, trip, groups, m.bank_aware == 1);
     for (const RowGroup& q : rg) {
       const size_t tid0 = (size_t)wg * m.block + (size_t)wave * kWave + q.lane0;
-      for (int l = 0; l < L; ++l) P.lane_row[tid0 + l] = q.row;
+      for (int l = 0; l < L; ++l) P.lane_row[tid0 + l] = q.row < m.rows ? q.row : -1;   // the GRU's empty fourth row owns nothing
       for (int k = 0; k < trip; ++k)
         for (int l = 0; l < L; ++l) {
           const size_t at = ((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + q.lane0 + l;

@@ -19,7 +19,8 @@ Draw order per workload (one ``numpy.random.Generator(PCG64(seed))``):
      rounded once to binary16 (round-to-nearest-even, subnormals kept),
   4. ``x``: ``standard_normal((T, B, R), float32)`` (+1.0 on the forget block
      of an LSTM: the forget-gate bias folded into b' of Eq. 2),
-  5. ``h0``: ``normal(0, h0_std)`` if ``h0_std > 0`` else absent (zeros).
+  5. ``h0``: ``normal(0, h0_std)`` if ``h0_std > 0`` else absent (zeros),
+  6. GRU only: ``b_hn``: ``normal(0, 0.5)`` of length H.
 """
 from __future__ import annotations
 
@@ -32,26 +33,29 @@ CELL_RNN_RELU = "relu"
 CELL_RNN_TANH = "tanh"
 CELL_RNN_IDENTITY = "identity"
 CELL_LSTM = "lstm"
+CELL_GRU = "gru"
+GATES = {CELL_LSTM: 4, CELL_GRU: 3}   # gate rows per hidden unit
 
 
 @dataclass
 class Workload:
     name: str
-    cell: str                 # "relu" | "tanh" | "identity" | "lstm"
+    cell: str                 # "relu" | "tanh" | "identity" | "lstm" | "gru"
     hidden: int               # H
     batch: int                # B
     steps: int                # T
-    row_ptr: np.ndarray       # int32 [R+1], R = H (RNN) or 4H (LSTM)
+    row_ptr: np.ndarray       # int32 [R+1], R = H (RNN), 4H (LSTM) or 3H (GRU)
     col_idx: np.ndarray       # int32 [nnz], strictly increasing inside a row
     val_bits: np.ndarray      # uint16 [nnz], IEEE binary16 bit patterns
     x: np.ndarray             # float32 [T, B, R]
     h0: Optional[np.ndarray]  # float32 [B, H] or None (zeros)
     c0: Optional[np.ndarray] = None  # float32 [B, H] or None (zeros); LSTM only
+    b_hn: Optional[np.ndarray] = None  # float32 [H]; GRU only: recurrent bias of the candidate gate
     meta: dict = field(default_factory=dict)
 
     @property
     def rows(self) -> int:
-        return self.hidden * (4 if self.cell == CELL_LSTM else 1)
+        return self.hidden * GATES.get(self.cell, 1)
 
     @property
     def nnz(self) -> int:
@@ -79,7 +83,7 @@ def make_workload(name: str, cell: str, hidden: int, batch: int, steps: int, den
                   seed: int = 0, gain: float = 0.9, row_nnz: str = "fixed",
                   h0_std: float = 0.0, forget_bias: float = 1.0) -> Workload:
     rng = np.random.Generator(np.random.PCG64(seed))
-    rows = hidden * (4 if cell == CELL_LSTM else 1)
+    rows = hidden * GATES.get(cell, 1)
     k_mean = density * hidden
     if row_nnz == "fixed":
         counts = np.full(rows, int(round(k_mean)), dtype=np.int64)
@@ -98,8 +102,11 @@ def make_workload(name: str, cell: str, hidden: int, batch: int, steps: int, den
     h0 = None
     if h0_std > 0.0:
         h0 = (rng.standard_normal((batch, hidden), dtype=np.float32) * np.float32(h0_std)).astype(np.float32)
+    b_hn = None
+    if cell == CELL_GRU:
+        b_hn = (rng.standard_normal(hidden, dtype=np.float32) * np.float32(0.5)).astype(np.float32)
     return Workload(name=name, cell=cell, hidden=hidden, batch=batch, steps=steps,
-                    row_ptr=row_ptr, col_idx=col_idx, val_bits=val_bits, x=x, h0=h0, c0=None,
+                    row_ptr=row_ptr, col_idx=col_idx, val_bits=val_bits, x=x, h0=h0, c0=None, b_hn=b_hn,
                     meta=dict(density=density, seed=seed, gain=gain, row_nnz=row_nnz, h0_std=h0_std))
 
 

@@ -59,6 +59,8 @@ def _unpack(words, lane_row, lane_words, info, hidden, batch):
     ("lstm", 48, 8, 0.25, "fixed", {}),
     ("lstm", 33, 4, 0.4, "poisson", {"lanes_per_row": 4}),
     ("relu", 300, 4, 0.1, "fixed", {"grid": 7}),
+    ("gru", 40, 4, 0.3, "fixed", {}),
+    ("gru", 77, 2, 0.2, "poisson", {"lanes_per_row": 8}),
 ])
 def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
     w = wl.make_workload("p", cell, H, B, 1, dens, seed=3, row_nnz=rownnz)
@@ -78,12 +80,15 @@ def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
     served = lane_row[lane_row >= 0]
     assert sorted(set(served.tolist())) == list(range(w.rows))
     assert np.all(np.bincount(served, minlength=w.rows) == L)   # every row served by exactly one group
-    if cell == "lstm":
-        # the four gate rows of a unit sit in four consecutive groups of one wavefront, order i f g o
+    if cell in ("lstm", "gru"):
+        # the gate rows of a unit sit in four consecutive groups of one wavefront, order i f g o (r z n and an
+        # idle group for the GRU)
         units = lane_row.reshape(info["grid"], -1, 4, L)[:, :, :, 0]
         ok = units[:, :, 0] >= 0
-        for q in range(4):
+        for q in range(4 if cell == "lstm" else 3):
             assert np.all(units[:, :, q][ok] == units[:, :, 0][ok] + q * H)
+        if cell == "gru":
+            assert np.all(units[:, :, 3] == -1) and info["rows"] == 3 * H
 
 
 def test_bank_aware_order_reduces_modelled_lds_passes():

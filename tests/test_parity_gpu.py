@@ -22,6 +22,8 @@ def _dev(a):
 def oracle_run(w, threads=8):
     if w.cell == "lstm":
         return oracle.lstm_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, w.c0, threads=threads)
+    if w.cell == "gru":
+        return oracle.gru_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x, w.b_hn, w.h0, threads=threads), None
     return oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=threads), None
 
 
@@ -31,6 +33,8 @@ def gpu_run(rnn, w, stepwise=False):
         h, c = rnn.forward_stepwise(x, h0, c0)
     elif w.cell == "lstm":
         h, c = rnn.forward_lstm(x, h0, c0)
+    elif w.cell == "gru":
+        h, c = rnn.forward_gru(x, _dev(w.b_hn), h0), None
     else:
         h, c = rnn.forward(x, h0), None
     assert rnn.check() == binding.SPRNN_OK
@@ -55,7 +59,7 @@ def check_workload(w, stepwise_too=True, **options):
         assert_parity(got_h, want_h, "h persistent")
         if want_c is not None:
             assert_parity(got_c, want_c, "c persistent")
-        if stepwise_too:
+        if stepwise_too and w.cell != "gru":      # the per-timestep comparison path is not offered for the GRU
             s_h, s_c = gpu_run(rnn, w, stepwise=True)
             assert_parity(s_h, want_h, "h stepwise")
             if want_c is not None:
@@ -384,3 +388,54 @@ def test_full_configs_match_oracle(name):
     w = wl.make_config(name)
     info = check_workload(w, stepwise_too=(name in ("cfg1", "cfg2", "cfg5")))
     assert info["grid"] <= info["resident_capacity"]
+
+
+# ------------------------------------------------------------------ GRU cell
+@pytest.mark.parametrize("H,B,T,dens,rownnz,opts", [
+    (48, 4, 9, 0.3, "fixed", {}),
+    (100, 1, 7, 0.2, "poisson", {}),
+    (130, 2, 6, 0.25, "poisson", {"lanes_per_row": 16}),
+    (64, 8, 5, 0.5, "fixed", {}),
+    (300, 4, 8, 0.1, "poisson", {"balance": 1}),
+    (40, 4, 6, 0.4, "fixed", {"grid": 1}),
+    (512, 4, 12, 0.1, "fixed", {"sync": "barrier"}),
+    (600, 2, 10, 0.02, "poisson", {"compact": 1}),
+    (1024, 8, 16, 0.2, "fixed", {}),
+])
+def test_gru_matches_oracle(H, B, T, dens, rownnz, opts):
+    w = wl.make_workload("gru", "gru", H, B, T, dens, seed=H + B, gain=1.0, row_nnz=rownnz, h0_std=0.5)
+    check_workload(w, **opts)
+
+
+def test_gru_time_composition_null_arguments_and_wrong_calls():
+    w = wl.make_workload("gru", "gru", 256, 4, 20, 0.2, seed=9, gain=1.0, h0_std=0.3)
+    with binding.SparseRNN(w.hidden, w.batch, "gru", w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        x, h0, bhn = _dev(w.x), _dev(w.h0), _dev(w.b_hn)
+        full = rnn.forward_gru(x, bhn, h0)
+        first = rnn.forward_gru(x[:7].contiguous(), bhn, h0)
+        rest = rnn.forward_gru(x[7:].contiguous(), bhn, first[-1].contiguous())
+        torch.cuda.synchronize()
+        assert torch.equal(full, torch.cat([first, rest]))
+        # no b_hn, no h0: zeros
+        got = rnn.forward_gru(x).cpu().numpy()
+        want = oracle.gru_forward(w.hidden, w.batch, w.row_ptr, w.col_idx, w.val_bits, w.x, None, None, threads=8)
+        assert_parity(got, want, "gru without b_hn / h0")
+        with pytest.raises(binding.SprnnError):
+            rnn.forward(x)
+        with pytest.raises(binding.SprnnError):
+            rnn.forward_stepwise(x)
+        assert rnn.check() == binding.SPRNN_OK
+    v = wl.make_workload("v", "relu", 64, 4, 1, 0.2)
+    with binding.SparseRNN(64, 4, "relu", v.row_ptr, v.col_idx, v.val_bits) as rnn:
+        with pytest.raises(binding.SprnnError):
+            rnn.forward_gru(torch.zeros((1, 4, 64), device="cuda"))
+
+
+def test_gru_with_random_pauses_is_unchanged():
+    w = wl.make_workload("gru", "gru", 768, 4, 40, 0.1, seed=3, gain=1.0, h0_std=0.3)
+    outs = []
+    for jitter in (0, 5, 11):
+        with binding.SparseRNN(w.hidden, w.batch, "gru", w.row_ptr, w.col_idx, w.val_bits, jitter=jitter) as rnn:
+            outs.append(rnn.forward_gru(_dev(w.x), _dev(w.b_hn), _dev(w.h0)).cpu().numpy())
+            assert rnn.check() == binding.SPRNN_OK
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
