@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,casestudy] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,cells,casestudy] [--reps 8]
 
 Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
 closed libraries on other hardware and are not reproduced):
@@ -12,6 +12,7 @@ closed libraries on other hardware and are not reproduced):
   density / size / batch / steps
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
   constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
+  cells      the four cells (ReLU, tanh, LSTM, GRU) on one layer shape: hidden 1024, density 20 %, T 256, batch 4 and 8.
   casestudy  the layer shapes of Appendix B's two tables (machine translation LSTMs at 4-12.5 % density, speech
              recognition layers at 12 %) with random unstructured patterns, as the paper itself does for the speech
              layers; milliseconds per 256-timestep sequence beside the paper's own figure (another GPU: context).
@@ -55,6 +56,9 @@ def measure(torch, w, reps, stepwise=False, **options):
             run = lambda: rnn.forward_stepwise(x, h0, c0, h_out, c_out)
         elif w.cell == "lstm":
             run = lambda: rnn.forward_lstm(x, h0, c0, h_out, c_out)
+        elif w.cell == "gru":
+            b_hn = dev(w.b_hn)
+            run = lambda: rnn.forward_gru(x, b_hn, h0, h_out)
         else:
             run = lambda: rnn.forward(x, h0, h_out)
         us = _time_us_per_step(torch, run, T, max(3, reps // 2) if stepwise else reps)
@@ -104,6 +108,19 @@ def axis(torch, wl, reps, title, cases):
     print()
 
 
+def cells(torch, wl, reps):
+    print("## Cells: hidden 1024, density 20 %, T 256\n")
+    print("| cell | gate rows | batch | nonzeros | persistent us/step | grid x block | lanes/row | back-off |")
+    print("|---|---|---|---|---|---|---|---|")
+    for B in (4, 8):
+        for cell in ("relu", "tanh", "lstm", "gru"):
+            w = wl.make_workload("cells", cell, 1024, B, 256, 0.20, seed=0, gain=1.0 if cell in ("lstm", "gru") else 0.9)
+            us, info = measure(torch, w, reps)
+            print("| %s | %d | %d | %d | %.2f | %d x %d | %d | %d |" % (
+                cell, w.rows // w.hidden, B, w.nnz, us, info["grid"], info["block"], info["lanes_per_row"], info["poll_delay"]), flush=True)
+    print()
+
+
 def casestudy(torch, wl, reps):
     print("## Case-study layer shapes (cf. Appendix B, both tables): random unstructured pattern, T 256\n")
     print("| layer | cell | hidden | density | batch | persistent us/step | ms per 256 steps | per-timestep launches ms | paper's sparse persistent ms (V100, its batch) | grid x block | lanes/row |")
@@ -123,7 +140,7 @@ def casestudy(torch, wl, reps):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,casestudy")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,cells,casestudy")
     ap.add_argument("--reps", type=int, default=8)
     args = ap.parse_args()
     import torch
@@ -144,6 +161,8 @@ def main():
         axis(torch, wl, args.reps, "Constant number of nonzeros (cf. Section 5.3): about 1.32 M, batch 4, T 256",
              [(2304, 4, 0.25, 256), (3072, 4, 0.14, 256), (4096, 4, 0.079, 256), (5760, 4, 0.04, 256), (7168, 4, 0.026, 256),
               (11520, 4, 0.01, 256)])
+    if "cells" in what:
+        cells(torch, wl, args.reps)
     if "casestudy" in what:
         casestudy(torch, wl, args.reps)
     if "batch" in what:
