@@ -182,7 +182,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   h->num_cus = prop.multiProcessorCount;
   h->pass_factor = lds_pass_factor(P);
   const Mapping& m = h->map;
-  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU, m.timeline != 0);
+  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0);
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.

@@ -54,7 +54,7 @@ struct StepArgs {
   int hidden, act;
 };
 
-const void* persistent_kernel_for(int batch, int template_words, bool lstm, bool timeline);
+const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline);   // cell: SPRNN_ACT_* / SPRNN_CELL_*
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream);
 // b'[m][n] = sum_k x[m][k] W[n][k] + bias[n] (bias may be null); x [M][K] float32, w [N][K] binary16 bits, out [M][N] float32.
 hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, float* out, int M, int N, int K,

@@ -285,8 +285,11 @@ __device__ __forceinline__ long long tick(bool on) {
   return 0;
 }
 
-template <int B, int NW, bool LSTM, bool TL>
+// CELL: 0 = vanilla cell (one row per unit), 1 = LSTM (four gate rows per unit), 2 = GRU (the LSTM's layout with an
+// idle fourth row; a template value of its own so that the LSTM instantiations carry none of its code).
+template <int B, int NW, int CELL, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const KernelArgs p) {
+  constexpr bool LSTM = CELL != 0;   // gated cell: four row groups per unit, cell lanes
   // LDS: [h][abort flags][timeline sums][LSTM hand-over area].  A single workgroup (no exchange) keeps two copies of
   // h and writes h_t straight into the other one; otherwise one copy is enough, because the workgroup barrier
   // before a step's first poll also separates the last gather of step t from the first write of h_t.
@@ -327,7 +330,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   // The GRU uses the same four-row layout with an empty fourth row: its b' has three blocks per sample, its
   // candidate row hands over the recurrent sum (+ b_hn) and b'_n separately (the reset gate multiplies only the
   // former), the latter in the fourth row's slot, and the cell lanes keep h_{t-1} where the LSTM keeps c.
-  const bool gru = LSTM && p.act == SPRNN_CELL_GRU;
+  constexpr bool gru = CELL == 2;
   const int Rx = gru ? 3 * H : R;              // rows of b' per sample
   const int row = p.lane_row[(size_t)wg * block + tid];
   const int sample = sample_of_lane<B>(lane);
@@ -688,33 +691,38 @@ __global__ void fill_kernel(uint32_t* dst, uint32_t value, size_t n) {
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int B, bool LSTM, bool TL>
+template <int B, int CELL, bool TL>
 static const void* pick_nw(int nw) {
   switch (nw) {
-    case 8: return (const void*)persistent_kernel<B, 8, LSTM, TL>;
-    case 16: return (const void*)persistent_kernel<B, 16, LSTM, TL>;
-    case 24: return (const void*)persistent_kernel<B, 24, LSTM, TL>;
-    case 32: return (const void*)persistent_kernel<B, 32, LSTM, TL>;
-    case 48: return (const void*)persistent_kernel<B, 48, LSTM, TL>;
-    case 64: return (const void*)persistent_kernel<B, 64, LSTM, TL>;
+    case 8: return (const void*)persistent_kernel<B, 8, CELL, TL>;
+    case 16: return (const void*)persistent_kernel<B, 16, CELL, TL>;
+    case 24: return (const void*)persistent_kernel<B, 24, CELL, TL>;
+    case 32: return (const void*)persistent_kernel<B, 32, CELL, TL>;
+    case 48: return (const void*)persistent_kernel<B, 48, CELL, TL>;
+    case 64: return (const void*)persistent_kernel<B, 64, CELL, TL>;
     default: return nullptr;
   }
 }
 
-template <bool LSTM, bool TL>
+template <int CELL, bool TL>
 static const void* pick_b(int batch, int nw) {
   switch (batch) {
-    case 1: return pick_nw<1, LSTM, TL>(nw);
-    case 2: return pick_nw<2, LSTM, TL>(nw);
-    case 4: return pick_nw<4, LSTM, TL>(nw);
-    case 8: return pick_nw<8, LSTM, TL>(nw);
+    case 1: return pick_nw<1, CELL, TL>(nw);
+    case 2: return pick_nw<2, CELL, TL>(nw);
+    case 4: return pick_nw<4, CELL, TL>(nw);
+    case 8: return pick_nw<8, CELL, TL>(nw);
     default: return nullptr;
   }
 }
 
-const void* persistent_kernel_for(int batch, int template_words, bool lstm, bool timeline) {
-  if (timeline) return lstm ? pick_b<true, true>(batch, template_words) : pick_b<false, true>(batch, template_words);
-  return lstm ? pick_b<true, false>(batch, template_words) : pick_b<false, false>(batch, template_words);
+const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline) {
+  const int kind = cell == SPRNN_CELL_LSTM ? 1 : (cell == SPRNN_CELL_GRU ? 2 : 0);
+  if (timeline) {   // the phase timeline is built for the vanilla and LSTM cells only
+    if (kind == 2) return nullptr;
+    return kind == 1 ? pick_b<1, true>(batch, template_words) : pick_b<0, true>(batch, template_words);
+  }
+  if (kind == 2) return pick_b<2, false>(batch, template_words);
+  return kind == 1 ? pick_b<1, false>(batch, template_words) : pick_b<0, false>(batch, template_words);
 }
 
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream) {
