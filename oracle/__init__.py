@@ -6,8 +6,8 @@ import this module; only ``tests/``, the smoke check and the benchmark's
 CPU-baseline leg do.  It imports nothing from the product package.
 
 Cells and equations: see the header of ``sprnn_oracle.c`` (Eq. 2 of the paper
-for the vanilla cell; Appendix B's four-gate LSTM; a three-gate GRU; Section
-3.1's input projection b' = W x + b).
+for the vanilla cell; Appendix B's four-gate LSTM; a three-gate GRU; the backward pass
+through time of the vanilla cell; Section 3.1's input projection b' = W x + b).
 """
 from __future__ import annotations
 
@@ -59,6 +59,8 @@ def _load():
         lib.oracle_gru_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, ci]
         lib.oracle_gru_forward_f64.restype = ci
         lib.oracle_gru_forward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, ci]
+        lib.oracle_rnn_backward_f64.restype = ci
+        lib.oracle_rnn_backward_f64.argtypes = [ci, ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, f64p, f64p]
         lib.oracle_input_projection_f64.restype = ci
         lib.oracle_input_projection_f64.argtypes = [ci, ci, ci, u16p, f32p, f32p, f64p, ci]
         _lib = lib
@@ -174,6 +176,33 @@ def gru_forward(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, b_hn=Non
     if rc != 0:
         raise RuntimeError("oracle_gru_forward failed")
     return out
+
+
+def rnn_backward(hidden: int, batch: int, act: str, row_ptr, col_idx, val_bits, h_fwd, dh_ext, h0=None):
+    """Backward pass through time of the vanilla cell for L = sum_t <dh_ext[t], h_t>, binary64.
+    Returns (d_bprime [T, B, H], dh0 [B, H], dU [nnz] in CSR order)."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, hidden, hidden)
+    h_fwd = np.ascontiguousarray(h_fwd, dtype=np.float32)
+    dh_ext = np.ascontiguousarray(dh_ext, dtype=np.float32)
+    T = h_fwd.shape[0]
+    if h_fwd.shape != (T, batch, hidden) or dh_ext.shape != (T, batch, hidden):
+        raise ValueError("h_fwd and dh_ext must be [T, B, H]")
+    if h0 is not None:
+        h0 = np.ascontiguousarray(h0, dtype=np.float32)
+        if h0.shape != (batch, hidden):
+            raise ValueError("h0 must be [B, H]")
+    nnz = int(row_ptr[-1])
+    d_bprime = np.empty((T, batch, hidden), dtype=np.float64)
+    dh0 = np.empty((batch, hidden), dtype=np.float64)
+    dU = np.empty(max(nnz, 1), dtype=np.float64)
+    rc = lib.oracle_rnn_backward_f64(hidden, batch, T, ACT[act], _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+                                     _ptr(val_bits, ctypes.c_uint16), _ptr(h_fwd, ctypes.c_float), _ptr(h0, ctypes.c_float),
+                                     _ptr(dh_ext, ctypes.c_float), _ptr(d_bprime, ctypes.c_double), _ptr(dh0, ctypes.c_double),
+                                     _ptr(dU, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError("oracle_rnn_backward_f64 failed")
+    return d_bprime, dh0, dU[:nnz]
 
 
 def input_projection(w_bits, x, bias=None, threads: int = 1) -> np.ndarray:

@@ -31,6 +31,12 @@
  *     with p_r = U_r h_{t-1} + x_r[t], p_z = U_z h_{t-1} + x_z[t]; x carries the input projection and
  *     every bias except b_hn.
  *
+ *   - Backward pass through time of the vanilla cell (Appendix B.1 trains with the pruned weights in both
+ *     passes): for L = sum_t <e_t, h_t> with e_t = dL/dh_t from outside,
+ *         d_t = e_t + U_r^T delta_{t+1},  delta_t = g'(a_t) * d_t  (= dL/db'_t),  delta_{T+1} = 0,
+ *         dL/dh_0 = U_r^T delta_1,  dL/dU_r[i][j] = sum_t sum_b delta_t[b][i] h_{t-1}[b][j]  on the pattern,
+ *     with g' taken from the forward output (ReLU: h_t > 0; tanh: 1 - h_t^2; identity: 1).  Binary64.
+ *
  * Precision: weights are IEEE binary16 bit patterns decoded exactly to binary32
  * (Section 6 names 16-bit weights as the compressed format); activations, the
  * products and the running sums are binary32 (one rounding per multiply and per
@@ -48,7 +54,9 @@
  * numpy, identity and single-entry closed forms (bit exact), exact rational brute force, a
  * hand-worked non-square example with a bias under tests/golden/, and sensitivity checks against a
  * transposed operand and a dropped bias.  GRU: torch.nn.GRUCell on dense weights, closed forms (update
- * gate saturated either way, zero weights), batch independence and time composition.
+ * gate saturated either way, zero weights), batch independence and time composition.  Backward pass:
+ * torch autograd on the dense cell (dL/db', dL/dh_0, dL/dU on and off the pattern), finite differences, T = 1
+ * closed form.
  */
 #include <math.h>
 #include <stdint.h>
@@ -336,5 +344,50 @@ int oracle_gru_forward_f64(int H, int B, int T, const int32_t* row_ptr, const in
     }
   }
   free(first);
+  return 0;
+}
+
+/*
+ * Backward pass through time of the vanilla cell, binary64.  U is [H][H] in CSR (the forward matrix, not its
+ * transpose); h_fwd is [T][B][H] (forward outputs h_1..h_T), h0 is [B][H] or NULL (zeros), dh_ext is
+ * [T][B][H] (e_t).  Outputs: d_bprime [T][B][H] (delta_t), dh0 [B][H] (may be NULL), dU [nnz] in CSR order
+ * (may be NULL).
+ */
+int oracle_rnn_backward_f64(int H, int B, int T, int act, const int32_t* row_ptr, const int32_t* col_idx,
+                            const uint16_t* val_bits, const float* h_fwd, const float* h0, const float* dh_ext,
+                            double* d_bprime, double* dh0, double* dU) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !d_bprime || (T > 0 && (!h_fwd || !dh_ext))) return -1;
+  const int64_t nnz = row_ptr[H];
+  double* back = (double*)calloc((size_t)B * H, sizeof(double)); /* U^T delta_{t+1}, per sample */
+  if (!back) return -1;
+  if (dU) for (int64_t k = 0; k < nnz; ++k) dU[k] = 0.0;
+  for (int t = T - 1; t >= 0; --t) {
+    const float* h_t = h_fwd + (size_t)t * B * H;
+    const float* h_prev = (t == 0) ? h0 : h_fwd + (size_t)(t - 1) * B * H;
+    double* delta = d_bprime + (size_t)t * B * H;
+    for (int b = 0; b < B; ++b) {
+      for (int i = 0; i < H; ++i) {
+        const double h = (double)h_t[(size_t)b * H + i];
+        double slope;
+        if (act == ORACLE_ACT_RELU) slope = (h > 0.0) ? 1.0 : 0.0;
+        else if (act == ORACLE_ACT_TANH) slope = 1.0 - h * h;
+        else slope = 1.0;
+        delta[(size_t)b * H + i] = slope * ((double)dh_ext[((size_t)t * B + b) * H + i] + back[(size_t)b * H + i]);
+      }
+    }
+    for (size_t j = 0; j < (size_t)B * H; ++j) back[j] = 0.0;
+    for (int i = 0; i < H; ++i) {
+      for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) {
+        const double w = (double)oracle_half_bits_to_float(val_bits[k]);
+        const int j = col_idx[k];
+        for (int b = 0; b < B; ++b) {
+          back[(size_t)b * H + j] += w * delta[(size_t)b * H + i];
+          if (dU) dU[k] += delta[(size_t)b * H + i] * (h_prev ? (double)h_prev[(size_t)b * H + j] : 0.0);
+        }
+      }
+    }
+  }
+  if (dh0) for (size_t j = 0; j < (size_t)B * H; ++j) dh0[j] = back[j];
+  free(back);
   return 0;
 }

@@ -483,3 +483,89 @@ def test_gru_time_composition_batch_independence_and_twin():
     twin = oracle.gru_forward(H, B, row_ptr, col_idx, vals, x, b_hn, h0, f64=True)
     assert np.abs(full - twin).max() < 2e-5
     assert np.array_equal(full, oracle.gru_forward(H, B, row_ptr, col_idx, vals, x, b_hn, h0, threads=3))
+
+
+# ----------------------------------------------------------------------------- backward pass through time
+@pytest.mark.parametrize("act", ["relu", "tanh", "identity"])
+def test_backward_matches_torch_autograd(act):
+    rng = np.random.default_rng(31)
+    H, B, T = 23, 3, 6
+    w = wl.make_workload("b", act, H, B, T, 0.4, seed=5, row_nnz="poisson", h0_std=0.5)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    h_fwd = oracle.rnn_forward(H, B, act, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, f64=True).astype(np.float32)
+    d_b, dh0, dU = oracle.rnn_backward(H, B, act, w.row_ptr, w.col_idx, w.val_bits, h_fwd, e, w.h0)
+    # the same cell, dense, in torch float64 with autograd
+    U = np.zeros((H, H))
+    for i in range(H):
+        for k in range(w.row_ptr[i], w.row_ptr[i + 1]):
+            U[i, w.col_idx[k]] = float(np.array(w.val_bits[k], dtype=np.uint16).view(np.float16))
+    Ut = torch.tensor(U, dtype=torch.float64, requires_grad=True)
+    xt = torch.tensor(w.x.astype(np.float64), requires_grad=True)
+    h0t = torch.tensor(w.h0.astype(np.float64), requires_grad=True)
+    f = {"relu": torch.relu, "tanh": torch.tanh, "identity": lambda z: z}[act]
+    h, loss = h0t, 0.0
+    for t in range(T):
+        h = f(h @ Ut.T + xt[t])
+        loss = loss + (torch.tensor(e[t].astype(np.float64)) * h).sum()
+    loss.backward()
+    # the oracle takes g' from the binary32 forward outputs, torch from its own binary64 ones
+    np.testing.assert_allclose(d_b, xt.grad.numpy(), rtol=0, atol=2e-6 * np.abs(xt.grad.numpy()).max())
+    np.testing.assert_allclose(dh0, h0t.grad.numpy(), rtol=0, atol=2e-6 * np.abs(h0t.grad.numpy()).max())
+    dense = Ut.grad.numpy()
+    want = np.array([dense[i, w.col_idx[k]] for i in range(H) for k in range(w.row_ptr[i], w.row_ptr[i + 1])])
+    np.testing.assert_allclose(dU, want, rtol=0, atol=2e-6 * np.abs(want).max())
+    # a transposed matrix in the recurrence is far away
+    bad = oracle.rnn_backward(H, B, act, *wl.csr_from_dense(U.T.astype(np.float16)), h_fwd, e, w.h0)[0]
+    assert np.abs(bad - d_b).max() > 1e-2
+
+
+def test_backward_single_step_closed_form_and_zero_weights():
+    rng = np.random.default_rng(32)
+    H, B = 9, 2
+    w = wl.make_workload("b", "tanh", H, B, 1, 0.5, seed=6, h0_std=1.0)
+    e = rng.standard_normal((1, B, H)).astype(np.float32)
+    h1 = oracle.rnn_forward(H, B, "tanh", w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0)
+    d_b, dh0, dU = oracle.rnn_backward(H, B, "tanh", w.row_ptr, w.col_idx, w.val_bits, h1, e, w.h0)
+    delta = (1.0 - h1[0].astype(np.float64) ** 2) * e[0]
+    assert np.array_equal(d_b[0], delta)
+    U = np.zeros((H, H))
+    for i in range(H):
+        for k in range(w.row_ptr[i], w.row_ptr[i + 1]):
+            U[i, w.col_idx[k]] = float(np.array(w.val_bits[k], dtype=np.uint16).view(np.float16))
+    np.testing.assert_allclose(dh0, delta @ U, rtol=0, atol=1e-14)
+    k = 0
+    for i in range(H):
+        for kk in range(w.row_ptr[i], w.row_ptr[i + 1]):
+            np.testing.assert_allclose(dU[k], (delta[:, i] * w.h0[:, w.col_idx[kk]].astype(np.float64)).sum(), rtol=0, atol=1e-14)
+            k += 1
+    # zero weights: nothing flows back through time
+    zero = np.zeros(H + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16)
+    T = 4
+    hf = rng.standard_normal((T, B, H)).astype(np.float32)
+    ee = rng.standard_normal((T, B, H)).astype(np.float32)
+    d_b, dh0, dU = oracle.rnn_backward(H, B, "relu", *zero, hf, ee, None)
+    assert np.array_equal(d_b, np.where(hf > 0, ee.astype(np.float64), 0.0))
+    assert not dh0.any() and dU.size == 0
+
+
+def test_backward_agrees_with_finite_differences_of_the_forward_oracle():
+    rng = np.random.default_rng(33)
+    H, B, T = 7, 1, 4
+    w = wl.make_workload("b", "tanh", H, B, T, 0.6, seed=7, h0_std=0.5)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    fwd = lambda x, h0: oracle.rnn_forward(H, B, "tanh", w.row_ptr, w.col_idx, w.val_bits, x, h0, f64=True)
+    h_fwd = fwd(w.x, w.h0).astype(np.float32)
+    d_b, dh0, _ = oracle.rnn_backward(H, B, "tanh", w.row_ptr, w.col_idx, w.val_bits, h_fwd, e, w.h0)
+    loss = lambda x, h0: float((fwd(x, h0) * e).sum())
+    eps = 2.0 ** -7                             # exactly representable steps of binary32 inputs
+    for (t, j) in ((0, 1), (2, 4), (3, 6)):
+        xp, xm = w.x.copy(), w.x.copy()
+        xp[t, 0, j] += eps
+        xm[t, 0, j] -= eps
+        fd = (loss(xp, w.h0) - loss(xm, w.h0)) / (float(xp[t, 0, j]) - float(xm[t, 0, j]))
+        assert abs(fd - d_b[t, 0, j]) < 2e-3 * max(1.0, abs(fd))
+    hp, hm = w.h0.copy(), w.h0.copy()
+    hp[0, 3] += eps
+    hm[0, 3] -= eps
+    fd = (loss(w.x, hp) - loss(w.x, hm)) / (float(hp[0, 3]) - float(hm[0, 3]))
+    assert abs(fd - dh0[0, 3]) < 2e-3 * max(1.0, abs(fd))
