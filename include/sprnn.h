@@ -153,6 +153,32 @@ int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn
                       void* stream);
 
 /*
+ * Backward pass through time of a vanilla cell with the pruned weights resident on chip (Appendix B.1: the pruned
+ * weights are used for the computation of both passes).  For a loss L with e_t = dL/dh_t from outside the layer,
+ *   delta_t = g'(a_t) (e_t + U_r^T delta_{t+1}),  delta_{T+1} = 0,   dL/db'_t = delta_t,   dL/dh_0 = U_r^T delta_1,
+ * which is the forward recurrence on the transposed matrix with time reversed and g' (taken from the forward
+ * output: ReLU h_t > 0, tanh 1 - h_t^2, identity 1) in place of g.  The handle must therefore have been created
+ * from the TRANSPOSE of the forward matrix (sprnn_transpose_csr) with the forward pass's activation and batch.
+ *
+ *   dh_ext    device, float32 [T][B][H]: e_t.
+ *   h_fwd     device, float32 [T][B][H]: the forward outputs h_1..h_T.
+ *   d_bprime  device, float32 [T][B][H]: delta_t (the gradient of the input projection's output; the gradient of
+ *             the weights is the sum over t and b of delta_t[b][i] h_{t-1}[b][j], a non-recurrent product that
+ *             this library leaves to the caller).
+ *   dh0       device, float32 [B][H], or NULL if not wanted.
+ * One launch; T is limited to 2^30 / (4 B H) timesteps per call.  Same stream, state and error rules as sprnn_forward.
+ */
+int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, float* d_bprime,
+                   float* dh0, void* stream);
+
+/*
+ * Host helper: transpose a CSR matrix (rows x cols) of binary16 values.  t_row_ptr has cols + 1 entries, t_col_idx
+ * and t_val_fp16_bits have row_ptr[rows] entries; the columns inside a transposed row come out ascending.
+ */
+int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* val_fp16_bits,
+                        int32_t* t_row_ptr, int32_t* t_col_idx, uint16_t* t_val_fp16_bits);
+
+/*
  * The step before the recurrence (Section 3.1: Eq. 1's input term is computed for all timesteps ahead of
  * time and enters Eq. 2 as b'):  b'[t][b][r] = sum_k W[r][k] x_in[t][b][k] + bias[r]  as one dense product on
  * the matrix cores.  Its output is laid out as the `x` argument of the forward calls of the same handle, so a

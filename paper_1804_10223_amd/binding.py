@@ -27,7 +27,7 @@ GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_gru", "sprnn_forward_stepwise",
-           "sprnn_project",
+           "sprnn_project", "sprnn_backward", "sprnn_transpose_csr",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
 
@@ -85,6 +85,10 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_forward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_gru.restype = ci
     lib.sprnn_forward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp]
+    lib.sprnn_backward.restype = ci
+    lib.sprnn_backward.argtypes = [vp, ci, vp, vp, vp, vp, vp]
+    lib.sprnn_transpose_csr.restype = ci
+    lib.sprnn_transpose_csr.argtypes = [ci, ci, i32p, i32p, u16p, i32p, i32p, u16p]
     lib.sprnn_forward_stepwise.restype = ci
     lib.sprnn_forward_stepwise.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sprnn_project.restype = ci
@@ -282,6 +286,21 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_forward_gru")
         return h_out
 
+    def backward(self, dh_ext, h_fwd, d_bprime=None, want_dh0=True):
+        """sprnn_backward on a handle that holds the TRANSPOSED matrix: (delta [T, B, H], dh0 [B, H] or None)."""
+        import torch
+        T = int(dh_ext.shape[0])
+        if d_bprime is None:
+            d_bprime = self._alloc(T)
+        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device="cuda:%d" % self.device) if want_dh0 else None
+        rc = self._lib.sprnn_backward(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
+                                      _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
+                                      _dev_ptr(d_bprime, (T, self.batch, self.hidden), "d_bprime"),
+                                      _dev_ptr(dh0, (self.batch, self.hidden), "dh0"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_backward")
+        return d_bprime, dh0
+
     def project(self, x_in, w_in_bits, bias=None, b_prime=None):
         """sprnn_project: x_in [T, B, I] float32, w_in_bits [R, I] binary16 (float16 tensor, or its bits as int16/uint16),
         bias [R] or None -> b' [T, B, R], the ``x`` argument of the forward calls."""
@@ -316,3 +335,19 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_forward_stepwise")
         return h_out, c_out
+
+
+def transpose_csr(rows: int, cols: int, row_ptr, col_idx, val_bits):
+    """sprnn_transpose_csr on numpy arrays: (t_row_ptr [cols + 1], t_col_idx, t_val_bits)."""
+    lib = load_library()
+    keep, rp, cp, vp = _csr_args(row_ptr, col_idx, val_bits)
+    nnz = int(np.asarray(row_ptr)[rows])
+    t_rp = np.zeros(cols + 1, dtype=np.int32)
+    t_ci = np.zeros(max(nnz, 1), dtype=np.int32)
+    t_vb = np.zeros(max(nnz, 1), dtype=np.uint16)
+    rc = lib.sprnn_transpose_csr(rows, cols, rp, cp, vp, t_rp.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                 t_ci.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                 t_vb.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+    if rc != SPRNN_OK:
+        raise SprnnError(rc, "sprnn_transpose_csr")
+    return t_rp, t_ci[:nnz], t_vb[:nnz]

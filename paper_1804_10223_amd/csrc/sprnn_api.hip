@@ -22,6 +22,7 @@ struct sprnn_handle_s {
   int launch_lds = 0;            // dynamic LDS requested at launch (>= map.lds_bytes; large enough for one workgroup per CU)
   double pass_factor = 1.0;
   const void* kernel = nullptr;
+  const void* kernel_bwd = nullptr;   // backward pass of a vanilla cell (same launch shape and LDS)
   uint32_t* d_words = nullptr;
   int32_t* d_lane_row = nullptr;
   int32_t* d_wave_words = nullptr;
@@ -100,7 +101,8 @@ int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 6 : 0; }
 }  // namespace
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
-                              float* h_out, float* c_out, void* stream, const float* b_hn = nullptr);
+                              float* h_out, float* c_out, void* stream, const float* b_hn = nullptr,
+                              const float* bwd_h_fwd = nullptr, float* bwd_dh0 = nullptr, bool backward = false);
 static int calibrate_poll_delay(sprnn_handle_s* h);
 
 extern "C" {
@@ -192,6 +194,11 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   h->launch_lds = std::max(lds_need, lds_cu / 2 + 1024);
   if (h->launch_lds > lds_cu) { release(h); return SPRNN_ERR_CAPACITY; }
   if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
+  if (m.cell <= SPRNN_ACT_IDENTITY && !m.timeline) {
+    // the backward pass of a vanilla cell runs on a handle that holds the transposed matrix: same shape, same LDS
+    h->kernel_bwd = persistent_kernel_for(m.batch, m.template_words, kCellBackward, false);
+    if (h->kernel_bwd && !SPRNN_HIP(hipFuncSetAttribute(h->kernel_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
+  }
   int per_cu = 0;
   if (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, h->kernel, m.block, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
   h->capacity = per_cu * h->num_cus;
@@ -236,7 +243,8 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 }
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
-                              float* h_out, float* c_out, void* stream, const float* b_hn) {
+                              float* h_out, float* c_out, void* stream, const float* b_hn, const float* bwd_h_fwd,
+                              float* bwd_dh0, bool backward) {
   if (h->poisoned) return SPRNN_ERR_STATE;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
@@ -247,6 +255,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
   const size_t step_bytes = (size_t)m.batch * m.rows * 4;
   const int t_max = (int)std::max<size_t>(1, ((size_t)1 << 30) / step_bytes);
   const size_t hb = (size_t)m.batch * m.hidden;
+  if (backward && T > t_max) return SPRNN_ERR_UNSUPPORTED;   // time runs backwards: one launch only
   for (int t0 = 0; t0 < T; t0 += t_max) {
     const int tn = std::min(t_max, T - t0);
     KernelArgs a;
@@ -260,6 +269,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.h_out = h_out + (size_t)t0 * hb;
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
     a.b_hn = b_hn;
+    a.aux = bwd_h_fwd; a.dh0 = bwd_dh0;
     a.timeline = h->d_timeline;
     a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
@@ -267,11 +277,13 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     void* args[] = {&a};
     // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
     const bool plain = m.plain_launch != 0 || m.grid == 1;
-    hipError_t e = plain ? hipLaunchKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
-                         : hipLaunchCooperativeKernel(h->kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+    const void* kernel = backward ? h->kernel_bwd : h->kernel;
+    hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
+                         : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
-    h->step_base += (uint32_t)tn;
-    h->barrier_base += (uint32_t)(tn - 1);   // one barrier before every step but the first
+    const int ran = tn + ((backward && bwd_dh0) ? 1 : 0);   // the backward pass adds the step that yields dL/dh_0
+    h->step_base += (uint32_t)ran;
+    h->barrier_base += (uint32_t)(ran - 1);   // one barrier before every step but the first
   }
   return SPRNN_OK;
 }
@@ -337,6 +349,44 @@ int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn
   if (h->map.cell != SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
   return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream, b_hn);
+}
+
+int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, float* d_bprime,
+                   float* dh0, void* stream) {
+  sprnn_handle_t h = h_transposed;
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell > SPRNN_ACT_IDENTITY || !h->kernel_bwd) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!dh_ext || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
+  // the occupancy of the backward kernel is checked like the forward one's before it may spin on its neighbours
+  int per_cu = 0;
+  {
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return SPRNN_ERR_HIP;
+    if (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, h->kernel_bwd, h->map.block, h->launch_lds))) return SPRNN_ERR_HIP;
+  }
+  if (h->map.grid > per_cu * h->num_cus) return SPRNN_ERR_CAPACITY;
+  return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, nullptr, h_fwd, dh0, true);
+}
+
+int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* val_fp16_bits,
+                        int32_t* t_row_ptr, int32_t* t_col_idx, uint16_t* t_val_fp16_bits) {
+  if (rows < 0 || cols < 0 || !row_ptr || !t_row_ptr) return SPRNN_ERR_INVALID;
+  const int64_t nnz = row_ptr[rows];
+  if (nnz < 0 || (nnz > 0 && (!col_idx || !val_fp16_bits || !t_col_idx || !t_val_fp16_bits))) return SPRNN_ERR_INVALID;
+  for (int c = 0; c <= cols; ++c) t_row_ptr[c] = 0;
+  for (int64_t k = 0; k < nnz; ++k) {
+    if (col_idx[k] < 0 || col_idx[k] >= cols) return SPRNN_ERR_INVALID;
+    ++t_row_ptr[col_idx[k] + 1];
+  }
+  for (int c = 0; c < cols; ++c) t_row_ptr[c + 1] += t_row_ptr[c];
+  std::vector<int32_t> next(t_row_ptr, t_row_ptr + cols);
+  for (int r = 0; r < rows; ++r)   // rows in ascending order, so the columns of a transposed row come out ascending
+    for (int32_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {
+      const int32_t at = next[col_idx[k]]++;
+      t_col_idx[at] = r;
+      t_val_fp16_bits[at] = val_fp16_bits[k];
+    }
+  return SPRNN_OK;
 }
 
 int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,

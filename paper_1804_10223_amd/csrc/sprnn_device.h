@@ -15,6 +15,7 @@ constexpr uint32_t kSentinelBits = 0x80000000u;   // -0.0f marks a ring element 
 constexpr int kCtrlStatus = 0;                    // ctrl[0]: non-zero once a spin watchdog tripped
 constexpr int kCtrlBarrier = 32;                  // grid-barrier mode: ctrl[32] top counter, ctrl[32 + 16 (1 + g)] counter of group g (64 bytes apart)
 constexpr int kCtrlWords = kCtrlBarrier + 16 * 9;
+constexpr int kCellBackward = 100;                // persistent_kernel_for: backward pass of a vanilla cell
 constexpr int kTimelineSlots = 16;                // 64-bit accumulators per workgroup in the phase timeline
 constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after h: abort flags, timeline sums
 
@@ -30,6 +31,8 @@ struct KernelArgs {
   const float* h0;            // [B][H] or null
   const float* c0;            // [B][H] or null (LSTM)
   const float* b_hn;          // [H] or null (GRU: recurrent bias of the candidate)
+  const float* aux;           // backward pass: forward outputs h_t, [T][B][H]
+  float* dh0;                 // backward pass: dL/dh_0, [B][H], or null
   float* h_out;               // [T][B][H]
   float* c_out;               // [T][B][H] (LSTM)
   unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)

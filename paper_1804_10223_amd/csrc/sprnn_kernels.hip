@@ -286,10 +286,16 @@ __device__ __forceinline__ long long tick(bool on) {
 }
 
 // CELL: 0 = vanilla cell (one row per unit), 1 = LSTM (four gate rows per unit), 2 = GRU (the LSTM's layout with an
-// idle fourth row; a template value of its own so that the LSTM instantiations carry none of its code).
+// idle fourth row; a template value of its own so that the LSTM instantiations carry none of its code),
+// 3 = backward pass through time of the vanilla cell: the handle holds the transposed matrix, time runs from T
+// down to 1, the state that is exchanged is delta_t = g'(a_t) (e_t + U^T delta_{t+1}), with g' taken from the forward
+// output h_t (p.aux) and e_t = p.x; one more step without g' and e gives dL/dh_0 = U^T delta_1 (p.dh0).
 template <int B, int NW, int CELL, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const KernelArgs p) {
-  constexpr bool LSTM = CELL != 0;   // gated cell: four row groups per unit, cell lanes
+  constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
+  constexpr bool BWD = CELL == 3;
+  const int steps = BWD ? p.T + (p.dh0 ? 1 : 0) : p.T;
+  auto time_of = [&](int s) { return BWD ? p.T - 1 - s : s; };   // index into x / aux / outputs of step s
   // LDS: [h][abort flags][timeline sums][LSTM hand-over area].  A single workgroup (no exchange) keeps two copies of
   // h and writes h_t straight into the other one; otherwise one copy is enough, because the workgroup barrier
   // before a step's first poll also separates the last gather of step t from the first write of h_t.
@@ -356,6 +362,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * Rx * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t abuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(BWD ? p.aux : p.x), 0, p.T * B * H * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t dbuf = __builtin_amdgcn_make_buffer_rsrc(BWD && p.dh0 ? p.dh0 : p.h_out, 0, B * H * 4, kBufWord3);
 
   // ---- the copy of h into LDS: 16-byte chunks.  In round c a lane copies the chunk at ring offset src to LDS
   // offset dst.  Without compaction LDS mirrors the ring slot: chunk tid + c * block goes to the same offset, and
@@ -412,7 +420,9 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   // whole timestep, so the load for step t+1 is issued before step t's wait for h_t.
   // (scalar offsets select the timestep and the sample; the host keeps one launch below 1 GiB of x, so an
   // out-of-range lane offset stays out of range whatever scalar offset is added to it)
-  float xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, 0, 0));
+  float xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(0) * B * Rx * 4, 0));
+  float an = 0.0f;   // backward pass: forward output h_t of the same element
+  if constexpr (BWD) an = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, x_voff, time_of(0) * B * H * 4, 0));
 
   __syncthreads();
 
@@ -431,7 +441,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   const uint32_t wave_id = (uint32_t)(wg * (block >> 6) + wave);
   int cur = 0;   // LDS copy that holds h_{t-1}; stays 0 unless solo
   long long tl_prev = 0;
-  for (int t = 0; t < p.T; ++t) {
+  for (int t = 0; t < steps; ++t) {
     const uint32_t g = p.step_base + (uint32_t)t;         // global step index: the slot number is the timestep tag
     long long ts0 = 0, ts1 = 0, ts2 = 0, ts3 = 0, ts4 = 0, ts5 = 0, ts6 = 0, ts7 = 0;
     unsigned long long repolls = 0;
@@ -560,7 +570,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     // The re-arm stores issued one step ago must be performed before this step's data can be seen, hence the wait.
     const int slot_byte = (int)(g & (kRingSlotsDev - 1)) * p.h_bytes;
     const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
-    const int out_soff = t * B * H * 4;
+    const int out_soff = time_of(t) * B * H * 4;
     float hval;
     if constexpr (LSTM) {
       if (gru) {
@@ -586,6 +596,13 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c), cbuf, out_voff, out_soff, 0);
       }
+    } else if constexpr (BWD) {
+      if (t < p.T) {
+        const float slope = p.act == SPRNN_ACT_RELU ? (an > 0.0f ? 1.0f : 0.0f) : (p.act == SPRNN_ACT_TANH ? fmaf(-an, an, 1.0f) : 1.0f);
+        hval = slope * pre + 0.0f;   // + 0.0f: 0 * negative is -0.0, the "not written" mark
+      } else {
+        hval = red + 0.0f;           // the extra step: U^T delta_1, no e, no g'
+      }
     } else {
       hval = activate(p.act, pre);
     }
@@ -598,9 +615,14 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
       if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
     }
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
+    if (BWD && t == p.T) {
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, out_voff, 0, 0);
+    } else {
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
+    }
     if (t + 1 < p.T) {
-      xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, (t + 1) * B * Rx * 4, 0));
+      xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(t + 1) * B * Rx * 4, 0));
+      if constexpr (BWD) an = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, x_voff, time_of(t + 1) * B * H * 4, 0));
     }
     ts3 = tick<TL>(tl_on);
 
@@ -717,11 +739,12 @@ static const void* pick_b(int batch, int nw) {
 
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline) {
   const int kind = cell == SPRNN_CELL_LSTM ? 1 : (cell == SPRNN_CELL_GRU ? 2 : 0);
-  if (timeline) {   // the phase timeline is built for the vanilla and LSTM cells only
-    if (kind == 2) return nullptr;
+  if (timeline) {   // the phase timeline is built for the forward pass of the vanilla and LSTM cells only
+    if (kind == 2 || cell == kCellBackward) return nullptr;
     return kind == 1 ? pick_b<1, true>(batch, template_words) : pick_b<0, true>(batch, template_words);
   }
   if (kind == 2) return pick_b<2, false>(batch, template_words);
+  if (cell == kCellBackward) return pick_b<3, false>(batch, template_words);
   return kind == 1 ? pick_b<1, false>(batch, template_words) : pick_b<0, false>(batch, template_words);
 }
 

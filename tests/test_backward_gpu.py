@@ -1,0 +1,83 @@
+"""Parity of the backward pass through time (sprnn_backward) against the CPU oracle, through the C ABI.
+
+Both sides get the same inputs: the oracle's own forward outputs h_t (binary32) and seeded e_t = dL/dh_t.
+Bar, as for the forward pass: per timestep  max|delta_gpu - delta_oracle| <= 1e-3 * max|delta_oracle|, same for dL/dh_0.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1804_10223_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-3
+
+
+def _dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_case(w, e, **options):
+    h_fwd = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=8)
+    want_d, want_dh0, _ = oracle.rnn_backward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, h_fwd, e, w.h0)
+    t_rp, t_ci, t_vb = binding.transpose_csr(w.hidden, w.hidden, w.row_ptr, w.col_idx, w.val_bits)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, t_rp, t_ci, t_vb, **options) as rnn:
+        info = rnn.info()
+        print("case", w.cell, "H", w.hidden, "B", w.batch, "T", w.steps, options, {k: info[k] for k in ("grid", "block", "lanes_per_row", "sync")}, flush=True)
+        got_d, got_dh0 = rnn.backward(_dev(e), _dev(h_fwd))
+        assert rnn.check() == binding.SPRNN_OK
+        got_d, got_dh0 = got_d.cpu().numpy(), got_dh0.cpu().numpy()
+        again, none = rnn.backward(_dev(e), _dev(h_fwd), want_dh0=False)     # second call on the same handle, no dh0
+        assert none is None and np.array_equal(again.cpu().numpy(), got_d)
+        assert rnn.check() == binding.SPRNN_OK
+    assert np.all(np.isfinite(got_d)) and np.all(np.isfinite(got_dh0))
+    for t in range(w.steps):
+        scale = np.abs(want_d[t]).max()
+        assert np.abs(got_d[t] - want_d[t]).max() <= REL_TOL * scale + 1e-30, t
+    assert np.abs(got_dh0 - want_dh0).max() <= REL_TOL * np.abs(want_dh0).max() + 1e-30
+    return got_d
+
+
+@pytest.mark.parametrize("cell,H,B,T,dens,rownnz,opts", [
+    ("relu", 96, 4, 9, 0.3, "fixed", {}),
+    ("tanh", 257, 1, 7, 0.2, "poisson", {}),
+    ("identity", 130, 8, 5, 0.1, "poisson", {}),
+    ("relu", 333, 2, 6, 0.15, "poisson", {"balance": 1}),
+    ("tanh", 64, 4, 8, 0.4, "fixed", {"grid": 1}),
+    ("relu", 640, 4, 10, 0.3, "fixed", {"sync": "barrier"}),
+    ("relu", 2000, 4, 6, 0.01, "poisson", {"compact": 1}),
+    ("tanh", 1152, 4, 32, 0.1, "fixed", {}),
+])
+def test_backward_matches_oracle(cell, H, B, T, dens, rownnz, opts):
+    w = wl.make_workload("bwd", cell, H, B, T, dens, seed=H + T, row_nnz=rownnz, h0_std=0.5)
+    e = np.random.default_rng(H).standard_normal((T, B, H)).astype(np.float32)
+    run_case(w, e, **opts)
+
+
+def test_backward_relu_mask_and_zero_weights_bit_exact():
+    # zero weights: delta_t = [h_t > 0] e_t exactly, dL/dh_0 = 0
+    H, B, T = 300, 4, 5
+    rng = np.random.default_rng(1)
+    hf = rng.standard_normal((T, B, H)).astype(np.float32)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    with binding.SparseRNN(H, B, "relu", np.zeros(H + 1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.uint16)) as rnn:
+        d, dh0 = rnn.backward(_dev(e), _dev(hf))
+        assert rnn.check() == binding.SPRNN_OK
+        assert np.array_equal(d.cpu().numpy(), np.where(hf > 0, e, np.float32(0)))
+        assert not dh0.cpu().numpy().any()
+
+
+def test_backward_at_the_headline_shape():
+    w = wl.make_config("cfg3", steps=64)
+    e = np.random.default_rng(3).standard_normal((w.steps, w.batch, w.hidden)).astype(np.float32)
+    run_case(w, e)
+
+
+def test_backward_is_refused_for_gated_cells_and_bad_arguments():
+    w = wl.make_config("cfg5", steps=2)
+    with binding.SparseRNN(w.hidden, w.batch, "lstm", w.row_ptr, w.col_idx, w.val_bits, poll_delay=-1) as rnn:
+        z = torch.zeros((2, w.batch, w.hidden), device="cuda")
+        with pytest.raises(binding.SprnnError):
+            rnn.backward(z, z)

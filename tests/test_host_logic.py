@@ -209,4 +209,26 @@ def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
     assert lib.sprnn_forward_lstm(none, 1, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_forward_stepwise(none, 1, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_project(none, 1, 8, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_forward_gru(none, 1, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_backward(none, 1, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_destroy(none) == binding.SPRNN_OK
+
+
+def test_transpose_csr_matches_a_dense_transpose():
+    w = wl.make_workload("t", "relu", 57, 1, 1, 0.3, seed=2, row_nnz="poisson")
+    t_rp, t_ci, t_vb = binding.transpose_csr(57, 57, w.row_ptr, w.col_idx, w.val_bits)
+    dense = np.zeros((57, 57), dtype=np.uint16)
+    for r in range(57):
+        dense[r, w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]]] = w.val_bits[w.row_ptr[r]:w.row_ptr[r + 1]]
+    back = np.zeros((57, 57), dtype=np.uint16)
+    for r in range(57):
+        cols = t_ci[t_rp[r]:t_rp[r + 1]]
+        assert np.all(np.diff(cols) > 0)                       # ascending, as sprnn_create requires
+        back[r, cols] = t_vb[t_rp[r]:t_rp[r + 1]]
+    assert np.array_equal(back, dense.T)
+    # a non-square matrix and an empty one
+    rp = np.array([0, 2, 3], dtype=np.int32)
+    t_rp, t_ci, t_vb = binding.transpose_csr(2, 4, rp, np.array([1, 3, 3], np.int32), np.array([7, 8, 9], np.uint16))
+    assert t_rp.tolist() == [0, 0, 1, 1, 3] and t_ci.tolist() == [0, 0, 1] and t_vb.tolist() == [7, 8, 9]
+    t_rp, t_ci, t_vb = binding.transpose_csr(3, 3, np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.uint16))
+    assert t_rp.tolist() == [0, 0, 0, 0] and t_ci.size == 0
