@@ -14,6 +14,7 @@ Reported beside the throughput:
                 latency + time to bring h into one CU), its three device constants measured live by
                 libsprnn_probe, and achieved/peak in microseconds per timestep.
   stepwise      the non-persistent comparison path (one launch per timestep) on the same inputs.
+  backward      the backward pass through time of the same layer (sprnn_backward on the transposed matrix).
   projection    the step before the path (sprnn_project: b' = W x + b for all timesteps, input size = hidden size)
                 against the dense fp16 MFMA peak, and the whole layer (projection + recurrence) per call.
   cpu_baseline  the CPU oracle as it stands, timed on the host cores of this machine.
@@ -113,6 +114,26 @@ def measure_projection(w, steps, warmup, torch, options=None):
             "us_per_launch": us, "bound": "mfma", "achieved": flops / us * 1e-6, "peak": 2500.0, "unit": "TFLOP/s",
             "frac": flops / us * 1e-6 / 2500.0, "flops_algorithmic": flops, "mfma_flops_executed": 2.0 * flops,
             "layer_ms": float(np.median(per_layer))}
+
+
+def measure_backward(w, steps, warmup, torch, options=None):
+    """Backward pass through time (sprnn_backward) of the same layer: the transposed matrix resident, T + 1 steps."""
+    from paper_1804_10223_amd import binding
+    if w.cell not in ("relu", "tanh", "identity"):
+        return None
+    t_rp, t_ci, t_vb = binding.transpose_csr(w.hidden, w.hidden, w.row_ptr, w.col_idx, w.val_bits)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, t_rp, t_ci, t_vb, **(options or {})) as rnn:
+        info = rnn.info()
+        gen = torch.Generator(device="cuda").manual_seed(1)
+        e = torch.randn((w.steps, w.batch, w.hidden), device="cuda", generator=gen)
+        h_fwd = torch.randn((w.steps, w.batch, w.hidden), device="cuda", generator=gen)
+        d = torch.empty_like(e)
+        _, per_call = time_forward(lambda: rnn.backward(e, h_fwd, d), steps, warmup, torch)
+        if rnn.check() != 0:
+            raise RuntimeError("spin watchdog tripped during the backward benchmark")
+    ms = float(np.median(per_call))
+    return {"kernel": "persistent_kernel<B=%d,NW=%d,backward>" % (w.batch, info["template_words"]), "ms_per_launch": ms,
+            "us_per_timestep": ms * 1e3 / w.steps, "grid": info["grid"], "block": info["block"], "poll_delay": info["poll_delay"]}
 
 
 def roofline_for(w, info, probe_vals):
@@ -223,6 +244,10 @@ def main():
     log("  input projection (input size %d): %.1f us per launch, %.1f TFLOP/s algorithmic; whole layer %.3f ms" % (
         proj["input_size"], proj["us_per_launch"], proj["achieved"], proj["layer_ms"]))
 
+    bwd = measure_backward(w, args.steps, args.warmup, torch, options=options)
+    if bwd:
+        log("  backward pass through time: %.3f us/timestep (%.3f ms per launch)" % (bwd["us_per_timestep"], bwd["ms_per_launch"]))
+
     table = []
     if args.all_configs:
         for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
@@ -289,6 +314,7 @@ def main():
         },
         "stepwise": {"us_per_timestep": res["stepwise_ms"] * 1e3 / T, "speedup_of_persistent": res["stepwise_ms"] / res["kernel_ms"]},
         "projection": proj,
+        "backward": bwd,
         "cpu_baseline": cpu,
     }
     if table:
