@@ -132,8 +132,14 @@ def measure_backward(w, steps, warmup, torch, options=None):
         if rnn.check() != 0:
             raise RuntimeError("spin watchdog tripped during the backward benchmark")
     ms = float(np.median(per_call))
+    # the non-recurrent half: gradient of the recurrent weights on the forward handle
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, poll_delay=-1) as fwd:
+        dU = torch.empty((w.nnz,), dtype=torch.float32, device="cuda")
+        _, per_wg = time_forward(lambda: fwd.weight_gradient(d, h_fwd, None, dU), steps, warmup, torch)
+    wg_ms = float(np.median(per_wg))
     return {"kernel": "persistent_kernel<B=%d,NW=%d,backward>" % (w.batch, info["template_words"]), "ms_per_launch": ms,
-            "us_per_timestep": ms * 1e3 / w.steps, "grid": info["grid"], "block": info["block"], "poll_delay": info["poll_delay"]}
+            "us_per_timestep": ms * 1e3 / w.steps, "grid": info["grid"], "block": info["block"], "poll_delay": info["poll_delay"],
+            "weight_gradient_ms_per_launch": wg_ms, "weight_gradient_us_per_timestep": wg_ms * 1e3 / w.steps}
 
 
 def roofline_for(w, info, probe_vals):
@@ -246,7 +252,8 @@ def main():
 
     bwd = measure_backward(w, args.steps, args.warmup, torch, options=options)
     if bwd:
-        log("  backward pass through time: %.3f us/timestep (%.3f ms per launch)" % (bwd["us_per_timestep"], bwd["ms_per_launch"]))
+        log("  backward pass through time: %.3f us/timestep (%.3f ms per launch); weight gradient %.3f us/timestep (%.3f ms per launch)" % (
+            bwd["us_per_timestep"], bwd["ms_per_launch"], bwd["weight_gradient_us_per_timestep"], bwd["weight_gradient_ms_per_launch"]))
 
     table = []
     if args.all_configs:

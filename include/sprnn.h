@@ -163,13 +163,25 @@ int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn
  *   dh_ext    device, float32 [T][B][H]: e_t.
  *   h_fwd     device, float32 [T][B][H]: the forward outputs h_1..h_T.
  *   d_bprime  device, float32 [T][B][H]: delta_t (the gradient of the input projection's output; the gradient of
- *             the weights is the sum over t and b of delta_t[b][i] h_{t-1}[b][j], a non-recurrent product that
- *             this library leaves to the caller).
+ *             the recurrent weights follows from it without a recurrence: sprnn_weight_gradient).
  *   dh0       device, float32 [B][H], or NULL if not wanted.
  * One launch; T is limited to 2^30 / (4 B H) timesteps per call.  Same stream, state and error rules as sprnn_forward.
  */
 int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, float* d_bprime,
                    float* dh0, void* stream);
+
+/*
+ * Gradient of the recurrent weights on their sparsity pattern, the non-recurrent half of the backward pass:
+ *   dU[k] = sum_t sum_b delta_t[b][row(k)] * h_{t-1}[b][col(k)]      for every stored nonzero k, in CSR order.
+ * Runs on the FORWARD handle (vanilla cells whose h fits in LDS whole: no column compaction) and re-uses its
+ * mapping: every lane keeps one accumulator per nonzero it holds in the forward pass, in registers, for all T steps.
+ *   d_bprime  device, float32 [T][B][H]: delta_t from sprnn_backward.
+ *   h_fwd     device, float32 [T][B][H]: forward outputs h_1..h_T;  h0: device [B][H] or NULL (zeros).
+ *   dU        device, float32 [nnz]: overwritten (T = 0 writes zeros).
+ * Sums are binary32, in time order.  Only enqueues work; allocates nothing.
+ */
+int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const float* h_fwd, const float* h0, float* dU,
+                          void* stream);
 
 /*
  * Host helper: transpose a CSR matrix (rows x cols) of binary16 values.  t_row_ptr has cols + 1 entries, t_col_idx

@@ -27,7 +27,7 @@ GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_gru", "sprnn_forward_stepwise",
-           "sprnn_project", "sprnn_backward", "sprnn_transpose_csr",
+           "sprnn_project", "sprnn_backward", "sprnn_weight_gradient", "sprnn_transpose_csr",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
 
@@ -87,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_forward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_backward.restype = ci
     lib.sprnn_backward.argtypes = [vp, ci, vp, vp, vp, vp, vp]
+    lib.sprnn_weight_gradient.restype = ci
+    lib.sprnn_weight_gradient.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_transpose_csr.restype = ci
     lib.sprnn_transpose_csr.argtypes = [ci, ci, i32p, i32p, u16p, i32p, i32p, u16p]
     lib.sprnn_forward_stepwise.restype = ci
@@ -300,6 +302,21 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_backward")
         return d_bprime, dh0
+
+    def weight_gradient(self, d_bprime, h_fwd, h0=None, dU=None):
+        """sprnn_weight_gradient on the FORWARD handle: dU [nnz] float32 in CSR order."""
+        import torch
+        T = int(d_bprime.shape[0])
+        nnz = self.info()["nnz"]
+        if dU is None:
+            dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device="cuda:%d" % self.device)
+        rc = self._lib.sprnn_weight_gradient(self._h, T, _dev_ptr(d_bprime, (T, self.batch, self.hidden), "d_bprime"),
+                                             _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
+                                             _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                             ctypes.c_void_p(dU.data_ptr()), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_weight_gradient")
+        return dU[:nnz]
 
     def project(self, x_in, w_in_bits, bias=None, b_prime=None):
         """sprnn_project: x_in [T, B, I] float32, w_in_bits [R, I] binary16 (float16 tensor, or its bits as int16/uint16),

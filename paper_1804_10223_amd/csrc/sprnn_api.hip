@@ -28,6 +28,8 @@ struct sprnn_handle_s {
   int32_t* d_wave_words = nullptr;
   uint32_t* d_fill_src = nullptr;    // column compaction only
   int32_t* d_wg_plane = nullptr;
+  int32_t* d_word_src = nullptr;     // vanilla cells without compaction: packed word -> CSR position (weight gradient)
+  const void* kernel_wgrad = nullptr;
   uint32_t* d_ring = nullptr;
   uint32_t* d_ctrl = nullptr;
   unsigned long long* d_timeline = nullptr;   // [grid][16], only with options.timeline
@@ -87,7 +89,7 @@ hipError_t upload(T** dst, const T* src, size_t n) {
 void release(sprnn_handle_s* h) {
   if (!h) return;
   (void)hipFree(h->d_words); (void)hipFree(h->d_lane_row); (void)hipFree(h->d_wave_words);
-  (void)hipFree(h->d_fill_src); (void)hipFree(h->d_wg_plane);
+  (void)hipFree(h->d_fill_src); (void)hipFree(h->d_wg_plane); (void)hipFree(h->d_word_src);
   (void)hipFree(h->d_ring); (void)hipFree(h->d_ctrl); (void)hipFree(h->d_timeline);
   (void)hipFree(h->d_row_ptr); (void)hipFree(h->d_col); (void)hipFree(h->d_val);
   delete h;
@@ -224,6 +226,12 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
             SPRNN_HIP(upload(&h->d_col, col_idx, (size_t)m.nnz)) &&
             SPRNN_HIP(upload(&h->d_val, val_fp16_bits, (size_t)m.nnz));
+  if (ok && m.cell <= SPRNN_ACT_IDENTITY && !m.compact) {
+    // the weight gradient re-uses the forward mapping: one accumulator per packed word, left through this map
+    h->kernel_wgrad = weight_grad_kernel_for(m.batch, m.template_words);
+    ok = h->kernel_wgrad != nullptr && SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size())) &&
+         SPRNN_HIP(hipFuncSetAttribute(h->kernel_wgrad, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds));
+  }
   if (ok && m.timeline) {
     std::vector<unsigned long long> zeros((size_t)m.grid * kTimelineSlots, 0ull);
     ok = SPRNN_HIP(upload(&h->d_timeline, zeros.data(), zeros.size()));
@@ -366,6 +374,26 @@ int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, cons
   }
   if (h->map.grid > per_cu * h->num_cus) return SPRNN_ERR_CAPACITY;
   return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, nullptr, h_fwd, dh0, true);
+}
+
+int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const float* h_fwd, const float* h0, float* dU,
+                          void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (!h->kernel_wgrad || !h->d_word_src) return SPRNN_ERR_UNSUPPORTED;   // gated cell, or column compaction in use
+  if (!dU && h->map.nnz > 0) return SPRNN_ERR_INVALID;
+  if (T > 0 && (!d_bprime || !h_fwd)) return SPRNN_ERR_INVALID;
+  if (h->map.nnz == 0) return SPRNN_OK;
+  DeviceGuard guard(h->device);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  const Mapping& m = h->map;
+  WGradArgs a;
+  a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words; a.word_src = h->d_word_src;
+  a.delta = d_bprime; a.h_fwd = h_fwd; a.h0 = h0; a.dU = dU;
+  a.hidden = m.hidden; a.T = T; a.index_shift = m.index_shift;
+  void* args[] = {&a};
+  // workgroups are independent here: an ordinary launch, one workgroup per CU by the same LDS request
+  const hipError_t e = hipLaunchKernel(h->kernel_wgrad, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+  return hip_ok(e, "hipLaunchKernel(weight gradient)") ? SPRNN_OK : SPRNN_ERR_HIP;
 }
 
 int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* val_fp16_bits,

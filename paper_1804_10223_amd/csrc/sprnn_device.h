@@ -45,6 +45,19 @@ struct KernelArgs {
   uint32_t barrier_base;      // grid barriers completed before this call (step t waits at barrier number barrier_base + t)
 };
 
+// Weight gradient of a vanilla cell on the sparsity pattern: dU[k] = sum_t sum_b delta_t[b][row(k)] h_{t-1}[b][col(k)].
+struct WGradArgs {
+  const uint32_t* words;      // the handle's packed words (only the column offsets are used)
+  const int32_t* lane_row;    // [grid][block]
+  const int32_t* wave_words;  // [grid][waves]
+  const int32_t* word_src;    // [grid][NW][block] CSR position of each packed word, -1 for padding
+  const float* delta;         // [T][B][H]
+  const float* h_fwd;         // [T][B][H] forward outputs h_1..h_T
+  const float* h0;            // [B][H] or null (zeros)
+  float* dU;                  // [nnz] CSR order
+  int hidden, T, index_shift;
+};
+
 struct StepArgs {
   const int32_t* row_ptr;
   const int32_t* col;
@@ -62,6 +75,7 @@ hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t 
 // b'[m][n] = sum_k x[m][k] W[n][k] + bias[n] (bias may be null); x [M][K] float32, w [N][K] binary16 bits, out [M][N] float32.
 hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, float* out, int M, int N, int K,
                           hipStream_t stream);
+const void* weight_grad_kernel_for(int batch, int template_words);
 hipError_t launch_fill(uint32_t* dst, uint32_t value, size_t n, hipStream_t stream);
 
 }  // namespace sprnn

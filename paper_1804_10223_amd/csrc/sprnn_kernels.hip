@@ -663,6 +663,113 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
 }
 
 // ------------------------------------------------------------------------------------------------
+// Weight gradient on the sparsity pattern (the non-recurrent half of the backward pass): the forward mapping
+// turned around.  A lane keeps one ACCUMULATOR per nonzero it holds in the forward pass, resident in registers for
+// all T steps; per step every workgroup brings h_{t-1} into LDS in the forward layout, a lane gathers the column of
+// each of its nonzeros (the same wide reads, the same bank-aware order) and adds delta_t[b][row] * h_{t-1}[b][col].
+// Workgroups do not talk to each other; the sums leave through the packer's word -> CSR position map.
+template <int B, int NW>
+__global__ __launch_bounds__(NW >= 48 ? 256 : 768) void weight_grad_kernel(const WGradArgs p) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int block = blockDim.x, wg = blockIdx.x, H = p.hidden;
+  const int n_w = __builtin_amdgcn_readfirstlane(p.wave_words[wg * (block >> 6) + wave]);
+  const int plane_bytes = H * 16;
+  uint32_t w_off[NW];
+  float acc[NW];
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {
+    const uint32_t word = (k < n_w) ? p.words[((size_t)wg * NW + k) * block + tid] : 0u;
+    w_off[k] = lds_address(lds) + ((word >> 16) << p.index_shift);
+    acc[k] = 0.0f;
+  }
+  const int row = p.lane_row[(size_t)wg * block + tid];
+  (void)lane;
+  // [B][H] in memory -> [H][B] in LDS (two planes of four samples for B = 8): a lane assembles whole 16-byte LDS
+  // chunks from four coalesced 4-byte loads each, sixteen loads in flight, and writes them as consecutive b128.
+  // The first four chunks of a lane (all of them up to 16 KB x waves of h) and its delta values are fetched one step
+  // ahead, while the gathers of the current step run.
+  constexpr int bb = B < 4 ? B : 4, cpc = 4 / bb;
+  const int per_plane = (H + cpc - 1) / cpc, chunks = (B == 8 ? 2 : 1) * per_plane;
+  auto h_before = [&](int t) { return t ? p.h_fwd + (size_t)(t - 1) * B * H : p.h0; };
+  auto load_chunks = [&](f32x4 (&v)[4], const float* hp, int c0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = min(c0 + i * block, chunks - 1);   // clamped: the last chunk may be copied twice
+      const int pl = c / per_plane, cc = c % per_plane;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int col = cc * cpc + e / bb, smp = pl * 4 + e % bb;
+        v[i][e] = (hp && col < H) ? hp[(size_t)smp * H + col] : 0.0f;
+      }
+    }
+  };
+  auto store_chunks = [&](const f32x4 (&v)[4], int c0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = min(c0 + i * block, chunks - 1);
+      *reinterpret_cast<f32x4*>(lds + (c / per_plane) * plane_bytes + (c % per_plane) * 16) = v[i];
+    }
+  };
+  auto load_delta = [&](float (&d)[B], int t) {
+#pragma unroll
+    for (int b = 0; b < B; ++b) d[b] = row >= 0 ? p.delta[((size_t)t * B + b) * H + row] : 0.0f;
+  };
+  f32x4 ahead[4];
+  float d_ahead[B];
+  if (p.T > 0) {
+    load_chunks(ahead, h_before(0), tid);
+    load_delta(d_ahead, 0);
+  }
+  for (int t = 0; t < p.T; ++t) {
+    const float* hp = h_before(t);
+    __syncthreads();   // the gathers of the previous step are done
+    store_chunks(ahead, tid);
+    for (int c0 = tid + 4 * block; c0 < chunks; c0 += 4 * block) {   // long h: the rest, not fetched ahead
+      f32x4 v[4];
+      load_chunks(v, hp, c0);
+      store_chunks(v, c0);
+    }
+    float d[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) d[b] = d_ahead[b];
+    __syncthreads();
+    if (t + 1 < p.T) {
+      load_chunks(ahead, h_before(t + 1), tid);
+      load_delta(d_ahead, t + 1);
+    }
+#pragma unroll
+    for (int k0 = 0; k0 < NW; k0 += 4) {
+      if (k0 < n_w) {   // a group of four slots: slots past n_w read the first column and feed sums that are never stored
+        Column<B> c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = gather_column<B>(w_off[k0 + j], plane_bytes);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float s = acc[k0 + j];
+          s = fmaf(d[0], c[j].lo.x, s);
+          if constexpr (B >= 2) s = fmaf(d[1], c[j].lo.y, s);
+          if constexpr (B >= 4) { s = fmaf(d[2], c[j].lo.z, s); s = fmaf(d[3], c[j].lo.w, s); }
+          if constexpr (B == 8) {
+            s = fmaf(d[4], c[j].hi.x, s); s = fmaf(d[5], c[j].hi.y, s);
+            s = fmaf(d[6], c[j].hi.z, s); s = fmaf(d[7], c[j].hi.w, s);
+          }
+          acc[k0 + j] = s;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {
+    if (k < n_w) {
+      const int src = p.word_src[((size_t)wg * NW + k) * block + tid];
+      if (src >= 0) p.dU[src] = acc[k];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Per-timestep comparison kernel: one launch per step, CSR weights re-read from device memory,
 // one wavefront per weight row (vanilla) or per hidden unit (LSTM: its four gate rows in turn).
 template <int B, bool LSTM>
@@ -746,6 +853,29 @@ const void* persistent_kernel_for(int batch, int template_words, int cell, bool 
   if (kind == 2) return pick_b<2, false>(batch, template_words);
   if (cell == kCellBackward) return pick_b<3, false>(batch, template_words);
   return kind == 1 ? pick_b<1, false>(batch, template_words) : pick_b<0, false>(batch, template_words);
+}
+
+template <int B>
+static const void* pick_wgrad(int nw) {
+  switch (nw) {
+    case 8: return (const void*)weight_grad_kernel<B, 8>;
+    case 16: return (const void*)weight_grad_kernel<B, 16>;
+    case 24: return (const void*)weight_grad_kernel<B, 24>;
+    case 32: return (const void*)weight_grad_kernel<B, 32>;
+    case 48: return (const void*)weight_grad_kernel<B, 48>;
+    case 64: return (const void*)weight_grad_kernel<B, 64>;
+    default: return nullptr;
+  }
+}
+
+const void* weight_grad_kernel_for(int batch, int template_words) {
+  switch (batch) {
+    case 1: return pick_wgrad<1>(template_words);
+    case 2: return pick_wgrad<2>(template_words);
+    case 4: return pick_wgrad<4>(template_words);
+    case 8: return pick_wgrad<8>(template_words);
+    default: return nullptr;
+  }
 }
 
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream) {

@@ -383,6 +383,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
 
   const size_t lanes = (size_t)m.grid * m.block;
   P.words.assign(lanes * NW, 0u);
+  P.word_src.assign(lanes * NW, -1);
   P.lane_row.assign(lanes, -1);
   P.lane_words.assign(lanes, 0);
   P.wave_words.assign(total_waves, 0);
@@ -441,6 +442,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
           if (i < 0) { P.words[at] = pad_word(q.lane0 + l, k, ncols); continue; }
           const uint32_t idx = ((uint32_t)q.items[i].col * (uint32_t)m.col_stride) >> m.index_shift;
           P.words[at] = (idx << 16) | q.items[i].bits;
+          P.word_src[at] = row_ptr[q.row] + i;   // items are the row's nonzeros in CSR order
           if ((q.items[i].bits & 0x7FFFu) == 0) is_real_zero[at] = 1;
           P.lane_words[tid0 + l] += 1;
         }

@@ -50,6 +50,7 @@ struct Packed {
   std::vector<int32_t> wave_words;  // [grid][waves]  loop trip count of each wavefront
   std::vector<uint32_t> fill_src;   // compaction: [grid][fill_rows][block] ring byte offset of each copied chunk (out of range: none)
   std::vector<int32_t> wg_plane;    // compaction: [grid] bytes of one plane of the workgroup's LDS copy
+  std::vector<int32_t> word_src;    // [grid][template_words][block] CSR position of the nonzero a packed word holds, -1 for padding
 };
 
 // Returns SPRNN_OK or an error code; on success `out` holds the mapping and the image.

@@ -73,6 +73,12 @@ def test_backward_at_the_headline_shape():
     w = wl.make_config("cfg3", steps=64)
     e = np.random.default_rng(3).standard_normal((w.steps, w.batch, w.hidden)).astype(np.float32)
     run_case(w, e)
+    # and the gradient of its 1.6 M weights
+    h_fwd = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=8)
+    delta, _, want = oracle.rnn_backward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, h_fwd, e, w.h0)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, poll_delay=-1) as rnn:
+        got = rnn.weight_gradient(_dev(delta.astype(np.float32)), _dev(h_fwd), _dev(w.h0)).cpu().numpy()
+    assert np.abs(got - want).max() <= REL_TOL * np.abs(want).max()
 
 
 def test_backward_is_refused_for_gated_cells_and_bad_arguments():
@@ -81,3 +87,56 @@ def test_backward_is_refused_for_gated_cells_and_bad_arguments():
         z = torch.zeros((2, w.batch, w.hidden), device="cuda")
         with pytest.raises(binding.SprnnError):
             rnn.backward(z, z)
+
+
+# ------------------------------------------------------------------ gradient of the recurrent weights
+@pytest.mark.parametrize("cell,H,B,T,dens,rownnz,opts", [
+    ("relu", 96, 4, 9, 0.3, "fixed", {}),
+    ("tanh", 257, 1, 7, 0.2, "poisson", {}),
+    ("identity", 130, 8, 5, 0.1, "poisson", {}),
+    ("relu", 333, 2, 6, 0.15, "poisson", {"balance": 1}),
+    ("tanh", 64, 4, 8, 0.4, "fixed", {"grid": 1}),
+    ("relu", 640, 4, 10, 0.5, "fixed", {"lanes_per_row": 8}),
+    ("tanh", 1152, 4, 32, 0.1, "fixed", {}),
+])
+def test_weight_gradient_matches_oracle(cell, H, B, T, dens, rownnz, opts):
+    w = wl.make_workload("wg", cell, H, B, T, dens, seed=H + T, row_nnz=rownnz, h0_std=0.5)
+    e = np.random.default_rng(H).standard_normal((T, B, H)).astype(np.float32)
+    h_fwd = oracle.rnn_forward(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=8)
+    delta, _, want = oracle.rnn_backward(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, h_fwd, e, w.h0)
+    delta32 = delta.astype(np.float32)
+    # cross-check that rounding delta to binary32 for the call does not matter at this bar
+    hp = np.concatenate([w.h0[None].astype(np.float64), h_fwd[:-1].astype(np.float64)])
+    rows = np.repeat(np.arange(H), np.diff(w.row_ptr))
+    want32 = np.einsum("tbk,tbk->k", delta32.astype(np.float64)[:, :, rows], hp[:, :, w.col_idx])
+    assert np.abs(want32 - want).max() <= 1e-5 * np.abs(want).max()
+    with binding.SparseRNN(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, poll_delay=-1, **opts) as rnn:
+        got = rnn.weight_gradient(_dev(delta32), _dev(h_fwd), _dev(w.h0)).cpu().numpy()
+        assert rnn.check() == binding.SPRNN_OK
+    assert got.shape == want.shape
+    assert np.abs(got - want).max() <= REL_TOL * np.abs(want).max()
+
+
+def test_weight_gradient_closed_forms_bit_exact():
+    # one timestep, small integers: every product and sum is exact, each nonzero gets exactly its own pair
+    H, B = 200, 4
+    rng = np.random.default_rng(8)
+    w = wl.make_workload("wg", "identity", H, B, 1, 0.1, seed=1, row_nnz="poisson")
+    delta = rng.integers(-4, 5, size=(1, B, H)).astype(np.float32)
+    h0 = rng.integers(-4, 5, size=(B, H)).astype(np.float32)
+    hf = np.zeros((1, B, H), dtype=np.float32)
+    rows = np.repeat(np.arange(H), np.diff(w.row_ptr))
+    want = (delta[0][:, rows] * h0[:, w.col_idx]).sum(axis=0)
+    with binding.SparseRNN(H, B, "identity", w.row_ptr, w.col_idx, w.val_bits, poll_delay=-1) as rnn:
+        got = rnn.weight_gradient(_dev(delta), _dev(hf), _dev(h0)).cpu().numpy()
+        assert np.array_equal(got, want)
+        # without h0 the first step contributes nothing
+        assert not rnn.weight_gradient(_dev(delta), _dev(hf), None).cpu().numpy().any()
+
+
+def test_weight_gradient_is_refused_where_the_forward_mapping_cannot_serve():
+    w = wl.make_workload("wg", "relu", 2000, 4, 2, 0.01, seed=2, row_nnz="poisson")
+    z = torch.zeros((2, 4, 2000), device="cuda")
+    with binding.SparseRNN(2000, 4, "relu", w.row_ptr, w.col_idx, w.val_bits, poll_delay=-1, compact=1) as rnn:
+        with pytest.raises(binding.SprnnError):
+            rnn.weight_gradient(z, z)
