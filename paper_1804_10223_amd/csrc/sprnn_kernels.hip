@@ -692,50 +692,74 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void weight_grad_kernel(const
   constexpr int bb = B < 4 ? B : 4, cpc = 4 / bb;
   const int per_plane = (H + cpc - 1) / cpc, chunks = (B == 8 ? 2 : 1) * per_plane;
   auto h_before = [&](int t) { return t ? p.h_fwd + (size_t)(t - 1) * B * H : p.h0; };
-  auto load_chunks = [&](f32x4 (&v)[4], const float* hp, int c0) {
+  // Element offsets of a lane's chunks are fixed for the whole launch: chunk c holds columns cc * cpc .. of samples
+  // pl * 4 ..; element e of it sits (e % bb) rows of H and e / bb columns further.  When H is not a multiple of the
+  // columns per chunk (batch 1 or 2 only) the last chunk is ragged and every element is checked instead.
+  const bool whole_chunks = H % cpc == 0;
+  auto chunk_offsets = [&](uint32_t (&goff)[4], uint32_t (&loff)[4], int c0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int c = min(c0 + i * block, chunks - 1);   // clamped: the last chunk may be copied twice
       const int pl = c / per_plane, cc = c % per_plane;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int col = cc * cpc + e / bb, smp = pl * 4 + e % bb;
-        v[i][e] = (hp && col < H) ? hp[(size_t)smp * H + col] : 0.0f;
-      }
+      goff[i] = (uint32_t)(pl * 4 * H + cc * cpc);
+      loff[i] = (uint32_t)(pl * plane_bytes + cc * 16);
     }
   };
-  auto store_chunks = [&](const f32x4 (&v)[4], int c0) {
+  auto load_chunks = [&](f32x4 (&v)[4], const float* hp, const uint32_t (&goff)[4]) {
+    if (hp && !whole_chunks) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = min(c0 + i * block, chunks - 1);
-      *reinterpret_cast<f32x4*>(lds + (c / per_plane) * plane_bytes + (c % per_plane) * 16) = v[i];
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t at = goff[i] + (uint32_t)((e % bb) * H + e / bb);
+          const int col = (int)(goff[i] % (uint32_t)H) + e / bb;     // goff = sample row * H + first column
+          v[i][e] = col < H ? hp[at] : 0.0f;
+        }
+    } else if (hp) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float* he = hp + (size_t)(e % bb) * H + e / bb;   // wavefront-uniform base, per-lane 32-bit offset
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i][e] = he[goff[i]];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
+  };
+  auto store_chunks = [&](const f32x4 (&v)[4], const uint32_t (&loff)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<f32x4*>(lds + loff[i]) = v[i];
   };
   auto load_delta = [&](float (&d)[B], int t) {
 #pragma unroll
     for (int b = 0; b < B; ++b) d[b] = row >= 0 ? p.delta[((size_t)t * B + b) * H + row] : 0.0f;
   };
+  uint32_t goff0[4], loff0[4];
+  chunk_offsets(goff0, loff0, tid);
   f32x4 ahead[4];
   float d_ahead[B];
   if (p.T > 0) {
-    load_chunks(ahead, h_before(0), tid);
+    load_chunks(ahead, h_before(0), goff0);
     load_delta(d_ahead, 0);
   }
   for (int t = 0; t < p.T; ++t) {
     const float* hp = h_before(t);
     __syncthreads();   // the gathers of the previous step are done
-    store_chunks(ahead, tid);
+    store_chunks(ahead, loff0);
     for (int c0 = tid + 4 * block; c0 < chunks; c0 += 4 * block) {   // long h: the rest, not fetched ahead
+      uint32_t goff[4], loff[4];
       f32x4 v[4];
-      load_chunks(v, hp, c0);
-      store_chunks(v, c0);
+      chunk_offsets(goff, loff, c0);
+      load_chunks(v, hp, goff);
+      store_chunks(v, loff);
     }
     float d[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) d[b] = d_ahead[b];
     __syncthreads();
     if (t + 1 < p.T) {
-      load_chunks(ahead, h_before(t + 1), tid);
+      load_chunks(ahead, h_before(t + 1), goff0);
       load_delta(d_ahead, t + 1);
     }
 #pragma unroll
