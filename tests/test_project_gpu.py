@@ -155,3 +155,28 @@ def test_projection_keeps_subnormal_weights_and_tiny_inputs():
     p = wl.Projection(rows=H, input_size=H, w_bits=w_int.view(np.uint16).copy(), bias=np.zeros(H, np.float32), x_in=x_tiny)
     got = run_project(H, B, "relu", p)
     assert np.array_equal(got.astype(np.float64), oracle.input_projection(p.w_bits, x_tiny, None))
+
+
+def test_two_stacked_layers_from_raw_inputs():
+    """Layer 2 takes layer 1's h_t as its input: project -> recurrence -> project -> recurrence, all enqueued on one
+    stream without a host synchronisation in between, against the same chain of oracle calls."""
+    H, B, T, I = 384, 4, 20, 200
+    w1 = wl.make_workload("l1", "tanh", H, B, T, 0.2, seed=11)
+    w2 = wl.make_workload("l2", "relu", H, B, T, 0.1, seed=12, row_nnz="poisson")
+    p1 = wl.make_projection(H, I, T, B, seed=13)
+    p2 = wl.make_projection(H, H, T, B, seed=14)
+    with binding.SparseRNN(H, B, "tanh", w1.row_ptr, w1.col_idx, w1.val_bits) as l1, \
+            binding.SparseRNN(H, B, "relu", w2.row_ptr, w2.col_idx, w2.val_bits) as l2:
+        dev = lambda a, view=None: torch.from_numpy(a if view is None else a.view(view)).cuda()
+        h1 = l1.forward(l1.project(dev(p1.x_in), dev(p1.w_bits, np.int16), dev(p1.bias)))
+        h2 = l2.forward(l2.project(h1, dev(p2.w_bits, np.int16), dev(p2.bias)))
+        torch.cuda.synchronize()
+        assert l1.check() == 0 and l2.check() == 0
+        h1, h2 = h1.cpu().numpy(), h2.cpu().numpy()
+    b1 = oracle.input_projection(p1.w_bits, p1.x_in, p1.bias, threads=8).astype(np.float32)
+    r1 = oracle.rnn_forward(H, B, "tanh", w1.row_ptr, w1.col_idx, w1.val_bits, b1, f64=True, threads=8)
+    b2 = oracle.input_projection(p2.w_bits, r1.astype(np.float32), p2.bias, threads=8).astype(np.float32)
+    r2 = oracle.rnn_forward(H, B, "relu", w2.row_ptr, w2.col_idx, w2.val_bits, b2, f64=True, threads=8)
+    for t in range(T):
+        assert np.abs(h1[t] - r1[t]).max() <= 1e-3 * np.abs(r1[t]).max(), t
+        assert np.abs(h2[t] - r2[t]).max() <= 1e-3 * np.abs(r2[t]).max(), t
