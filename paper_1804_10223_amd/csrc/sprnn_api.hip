@@ -200,6 +200,10 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     // the backward pass of a vanilla cell runs on a handle that holds the transposed matrix: same shape, same LDS
     h->kernel_bwd = persistent_kernel_for(m.batch, m.template_words, kCellBackward, false);
     if (h->kernel_bwd && !SPRNN_HIP(hipFuncSetAttribute(h->kernel_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
+    // it spins on its neighbours like the forward kernel: usable only if the same grid is co-resident with it
+    int per_cu_bwd = 0;
+    if (h->kernel_bwd && (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_bwd, h->kernel_bwd, m.block, h->launch_lds)) ||
+                          m.grid > per_cu_bwd * prop.multiProcessorCount)) h->kernel_bwd = nullptr;
   }
   int per_cu = 0;
   if (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, h->kernel, m.block, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
@@ -365,14 +369,6 @@ int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, cons
   if (!h || T < 0) return SPRNN_ERR_INVALID;
   if (h->map.cell > SPRNN_ACT_IDENTITY || !h->kernel_bwd) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!dh_ext || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
-  // the occupancy of the backward kernel is checked like the forward one's before it may spin on its neighbours
-  int per_cu = 0;
-  {
-    DeviceGuard guard(h->device);
-    if (!guard.ok) return SPRNN_ERR_HIP;
-    if (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, h->kernel_bwd, h->map.block, h->launch_lds))) return SPRNN_ERR_HIP;
-  }
-  if (h->map.grid > per_cu * h->num_cus) return SPRNN_ERR_CAPACITY;
   return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, nullptr, h_fwd, dh0, true);
 }
 
