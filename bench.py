@@ -129,6 +129,12 @@ def measure_backward(w, steps, warmup, torch, options=None):
         h_fwd = torch.randn((w.steps, w.batch, w.hidden), device="cuda", generator=gen)
         d = torch.empty_like(e)
         _, per_call = time_forward(lambda: rnn.backward(e, h_fwd, d), steps, warmup, torch)
+        fused_ms = None
+        try:   # the same pass with the weight gradient fused in (not built for every mapping)
+            _, per_fused = time_forward(lambda: rnn.backward_with_weights(e, h_fwd, None, d), steps, warmup, torch)
+            fused_ms = float(np.median(per_fused))
+        except binding.SprnnError:
+            pass
         if rnn.check() != 0:
             raise RuntimeError("spin watchdog tripped during the backward benchmark")
     ms = float(np.median(per_call))
@@ -139,7 +145,9 @@ def measure_backward(w, steps, warmup, torch, options=None):
     wg_ms = float(np.median(per_wg))
     return {"kernel": "persistent_kernel<B=%d,NW=%d,backward>" % (w.batch, info["template_words"]), "ms_per_launch": ms,
             "us_per_timestep": ms * 1e3 / w.steps, "grid": info["grid"], "block": info["block"], "poll_delay": info["poll_delay"],
-            "weight_gradient_ms_per_launch": wg_ms, "weight_gradient_us_per_timestep": wg_ms * 1e3 / w.steps}
+            "weight_gradient_ms_per_launch": wg_ms, "weight_gradient_us_per_timestep": wg_ms * 1e3 / w.steps,
+            "fused_with_weight_gradient_ms_per_launch": fused_ms,
+            "fused_with_weight_gradient_us_per_timestep": None if fused_ms is None else fused_ms * 1e3 / w.steps}
 
 
 def roofline_for(w, info, probe_vals):
@@ -252,8 +260,9 @@ def main():
 
     bwd = measure_backward(w, args.steps, args.warmup, torch, options=options)
     if bwd:
-        log("  backward pass through time: %.3f us/timestep (%.3f ms per launch); weight gradient %.3f us/timestep (%.3f ms per launch)" % (
-            bwd["us_per_timestep"], bwd["ms_per_launch"], bwd["weight_gradient_us_per_timestep"], bwd["weight_gradient_ms_per_launch"]))
+        log("  backward pass through time: %.3f us/timestep (%.3f ms per launch); weight gradient alone %.3f us/timestep (%.3f ms per launch); "
+            "both fused: %s us/timestep" % (bwd["us_per_timestep"], bwd["ms_per_launch"], bwd["weight_gradient_us_per_timestep"],
+                                           bwd["weight_gradient_ms_per_launch"], bwd["fused_with_weight_gradient_us_per_timestep"]))
 
     table = []
     if args.all_configs:

@@ -171,6 +171,19 @@ int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, cons
                    float* dh0, void* stream);
 
 /*
+ * sprnn_backward with the gradient of the recurrent weights fused in.  The column of delta_{t+1} that a lane gathers
+ * for a nonzero (j, i) of the transposed matrix is exactly the factor that dL/dU[i][j] pairs with the forward output
+ * h_t[.][j] of the lane's own row, so every gather of the recurrence also feeds one accumulator per nonzero that
+ * stays in a register for the whole sequence; the sums cost no extra pass over h.
+ *   h0             device, float32 [B][H] or NULL (zeros): h_0 of the forward pass (pairs with delta_1).
+ *   dU_transposed  device, float32 [nnz]: dL/dU in the order of the TRANSPOSED matrix's CSR arrays (entry p belongs to
+ *                  the forward nonzero t_source[p] of sprnn_transpose_csr); overwritten.
+ * Other arguments as sprnn_backward.  Not available with column compaction (SPRNN_ERR_UNSUPPORTED).
+ */
+int sprnn_backward_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, const float* h0,
+                                float* d_bprime, float* dh0, float* dU_transposed, void* stream);
+
+/*
  * Gradient of the recurrent weights on their sparsity pattern, the non-recurrent half of the backward pass:
  *   dU[k] = sum_t sum_b delta_t[b][row(k)] * h_{t-1}[b][col(k)]      for every stored nonzero k, in CSR order.
  * Runs on the FORWARD handle (vanilla cells whose h fits in LDS whole: no column compaction) and re-uses its
@@ -186,9 +199,11 @@ int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const 
 /*
  * Host helper: transpose a CSR matrix (rows x cols) of binary16 values.  t_row_ptr has cols + 1 entries, t_col_idx
  * and t_val_fp16_bits have row_ptr[rows] entries; the columns inside a transposed row come out ascending.
+ * t_source (row_ptr[rows] entries, or NULL) receives, for every entry of the transpose, the position of the same
+ * nonzero in the input arrays.
  */
 int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* val_fp16_bits,
-                        int32_t* t_row_ptr, int32_t* t_col_idx, uint16_t* t_val_fp16_bits);
+                        int32_t* t_row_ptr, int32_t* t_col_idx, uint16_t* t_val_fp16_bits, int32_t* t_source);
 
 /*
  * The step before the recurrence (Section 3.1: Eq. 1's input term is computed for all timesteps ahead of

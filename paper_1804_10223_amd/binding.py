@@ -27,7 +27,7 @@ GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_gru", "sprnn_forward_stepwise",
-           "sprnn_project", "sprnn_backward", "sprnn_weight_gradient", "sprnn_transpose_csr",
+           "sprnn_project", "sprnn_backward", "sprnn_backward_with_weights", "sprnn_weight_gradient", "sprnn_transpose_csr",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
 
@@ -90,7 +90,9 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_weight_gradient.restype = ci
     lib.sprnn_weight_gradient.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_transpose_csr.restype = ci
-    lib.sprnn_transpose_csr.argtypes = [ci, ci, i32p, i32p, u16p, i32p, i32p, u16p]
+    lib.sprnn_transpose_csr.argtypes = [ci, ci, i32p, i32p, u16p, i32p, i32p, u16p, i32p]
+    lib.sprnn_backward_with_weights.restype = ci
+    lib.sprnn_backward_with_weights.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_stepwise.restype = ci
     lib.sprnn_forward_stepwise.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sprnn_project.restype = ci
@@ -303,6 +305,27 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_backward")
         return d_bprime, dh0
 
+    def backward_with_weights(self, dh_ext, h_fwd, h0=None, d_bprime=None, want_dh0=True):
+        """sprnn_backward_with_weights on a handle that holds the TRANSPOSED matrix:
+        (delta [T, B, H], dh0 [B, H] or None, dU [nnz] in the transposed matrix's CSR order)."""
+        import torch
+        T = int(dh_ext.shape[0])
+        nnz = self.info()["nnz"]
+        if d_bprime is None:
+            d_bprime = self._alloc(T)
+        dev = "cuda:%d" % self.device
+        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
+        dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
+        rc = self._lib.sprnn_backward_with_weights(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
+                                                   _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
+                                                   _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                                   _dev_ptr(d_bprime, (T, self.batch, self.hidden), "d_bprime"),
+                                                   _dev_ptr(dh0, (self.batch, self.hidden), "dh0"),
+                                                   ctypes.c_void_p(dU.data_ptr()), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_backward_with_weights")
+        return d_bprime, dh0, dU[:nnz]
+
     def weight_gradient(self, d_bprime, h_fwd, h0=None, dU=None):
         """sprnn_weight_gradient on the FORWARD handle: dU [nnz] float32 in CSR order."""
         import torch
@@ -354,17 +377,21 @@ class SparseRNN:
         return h_out, c_out
 
 
-def transpose_csr(rows: int, cols: int, row_ptr, col_idx, val_bits):
-    """sprnn_transpose_csr on numpy arrays: (t_row_ptr [cols + 1], t_col_idx, t_val_bits)."""
+def transpose_csr(rows: int, cols: int, row_ptr, col_idx, val_bits, with_source: bool = False):
+    """sprnn_transpose_csr on numpy arrays: (t_row_ptr [cols + 1], t_col_idx, t_val_bits[, t_source])."""
     lib = load_library()
     keep, rp, cp, vp = _csr_args(row_ptr, col_idx, val_bits)
     nnz = int(np.asarray(row_ptr)[rows])
     t_rp = np.zeros(cols + 1, dtype=np.int32)
     t_ci = np.zeros(max(nnz, 1), dtype=np.int32)
     t_vb = np.zeros(max(nnz, 1), dtype=np.uint16)
+    t_src = np.zeros(max(nnz, 1), dtype=np.int32)
     rc = lib.sprnn_transpose_csr(rows, cols, rp, cp, vp, t_rp.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
                                  t_ci.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                                 t_vb.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+                                 t_vb.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)),
+                                 t_src.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
     if rc != SPRNN_OK:
         raise SprnnError(rc, "sprnn_transpose_csr")
+    if with_source:
+        return t_rp, t_ci[:nnz], t_vb[:nnz], t_src[:nnz]
     return t_rp, t_ci[:nnz], t_vb[:nnz]

@@ -23,6 +23,7 @@ struct sprnn_handle_s {
   double pass_factor = 1.0;
   const void* kernel = nullptr;
   const void* kernel_bwd = nullptr;   // backward pass of a vanilla cell (same launch shape and LDS)
+  const void* kernel_bwd_grad = nullptr;   // the same with the weight gradient fused in
   uint32_t* d_words = nullptr;
   int32_t* d_lane_row = nullptr;
   int32_t* d_wave_words = nullptr;
@@ -104,7 +105,8 @@ int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 6 : 0; }
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const float* b_hn = nullptr,
-                              const float* bwd_h_fwd = nullptr, float* bwd_dh0 = nullptr, bool backward = false);
+                              const float* bwd_h_fwd = nullptr, float* bwd_dh0 = nullptr, bool backward = false,
+                              const float* bwd_h0 = nullptr, float* bwd_dU = nullptr);
 static int calibrate_poll_delay(sprnn_handle_s* h);
 
 extern "C" {
@@ -235,6 +237,17 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     h->kernel_wgrad = weight_grad_kernel_for(m.batch, m.template_words);
     ok = h->kernel_wgrad != nullptr && SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size())) &&
          SPRNN_HIP(hipFuncSetAttribute(h->kernel_wgrad, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds));
+    if (ok && h->kernel_bwd && !m.timeline) {
+      // backward pass with the weight gradient fused in: same co-residency requirement as the plain one
+      const void* k = persistent_kernel_for(m.batch, m.template_words, kCellBackwardGrad, false);
+      int per_cu_g = 0;
+      hipFuncAttributes fa;
+      if (k && SPRNN_HIP(hipFuncGetAttributes(&fa, k)) && fa.maxThreadsPerBlock >= m.block &&
+          SPRNN_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds)) &&
+          SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_g, k, m.block, h->launch_lds)) &&
+          m.grid <= per_cu_g * prop.multiProcessorCount)
+        h->kernel_bwd_grad = k;
+    }
   }
   if (ok && m.timeline) {
     std::vector<unsigned long long> zeros((size_t)m.grid * kTimelineSlots, 0ull);
@@ -256,7 +269,7 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const float* b_hn, const float* bwd_h_fwd,
-                              float* bwd_dh0, bool backward) {
+                              float* bwd_dh0, bool backward, const float* bwd_h0, float* bwd_dU) {
   if (h->poisoned) return SPRNN_ERR_STATE;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
@@ -281,7 +294,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.h_out = h_out + (size_t)t0 * hb;
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
     a.b_hn = b_hn;
-    a.aux = bwd_h_fwd; a.dh0 = bwd_dh0;
+    a.aux = bwd_h_fwd; a.dh0 = bwd_dh0; a.bwd_h0 = bwd_h0; a.word_src = h->d_word_src; a.dU = bwd_dU;
     a.timeline = h->d_timeline;
     a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
@@ -289,11 +302,11 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     void* args[] = {&a};
     // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
     const bool plain = m.plain_launch != 0 || m.grid == 1;
-    const void* kernel = backward ? h->kernel_bwd : h->kernel;
+    const void* kernel = backward ? (bwd_dU ? h->kernel_bwd_grad : h->kernel_bwd) : h->kernel;
     hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
                          : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
-    const int ran = tn + ((backward && bwd_dh0) ? 1 : 0);   // the backward pass adds the step that yields dL/dh_0
+    const int ran = tn + ((backward && (bwd_dh0 || bwd_dU)) ? 1 : 0);   // the backward pass adds the step that pairs delta_1 with h_0
     h->step_base += (uint32_t)ran;
     h->barrier_base += (uint32_t)(ran - 1);   // one barrier before every step but the first
   }
@@ -372,6 +385,22 @@ int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, cons
   return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, nullptr, h_fwd, dh0, true);
 }
 
+int sprnn_backward_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, const float* h0,
+                                float* d_bprime, float* dh0, float* dU_transposed, void* stream) {
+  sprnn_handle_t h = h_transposed;
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell > SPRNN_ACT_IDENTITY || !h->kernel_bwd_grad || !h->d_word_src) return SPRNN_ERR_UNSUPPORTED;
+  if (!dU_transposed && h->map.nnz > 0) return SPRNN_ERR_INVALID;
+  if (T > 0 && (!dh_ext || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
+  if (T == 0) {   // nothing to sum
+    if (h->map.nnz == 0) return SPRNN_OK;
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return SPRNN_ERR_HIP;
+    return SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dU_transposed), 0u, (size_t)h->map.nnz, (hipStream_t)stream)) ? SPRNN_OK : SPRNN_ERR_HIP;
+  }
+  return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, nullptr, h_fwd, dh0, true, h0, dU_transposed);
+}
+
 int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const float* h_fwd, const float* h0, float* dU,
                           void* stream) {
   if (!h || T < 0) return SPRNN_ERR_INVALID;
@@ -393,7 +422,7 @@ int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const 
 }
 
 int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_t* col_idx, const uint16_t* val_fp16_bits,
-                        int32_t* t_row_ptr, int32_t* t_col_idx, uint16_t* t_val_fp16_bits) {
+                        int32_t* t_row_ptr, int32_t* t_col_idx, uint16_t* t_val_fp16_bits, int32_t* t_source) {
   if (rows < 0 || cols < 0 || !row_ptr || !t_row_ptr) return SPRNN_ERR_INVALID;
   const int64_t nnz = row_ptr[rows];
   if (nnz < 0 || (nnz > 0 && (!col_idx || !val_fp16_bits || !t_col_idx || !t_val_fp16_bits))) return SPRNN_ERR_INVALID;
@@ -409,6 +438,7 @@ int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_
       const int32_t at = next[col_idx[k]]++;
       t_col_idx[at] = r;
       t_val_fp16_bits[at] = val_fp16_bits[k];
+      if (t_source) t_source[at] = k;
     }
   return SPRNN_OK;
 }

@@ -16,6 +16,7 @@ constexpr int kCtrlStatus = 0;                    // ctrl[0]: non-zero once a sp
 constexpr int kCtrlBarrier = 32;                  // grid-barrier mode: ctrl[32] top counter, ctrl[32 + 16 (1 + g)] counter of group g (64 bytes apart)
 constexpr int kCtrlWords = kCtrlBarrier + 16 * 9;
 constexpr int kCellBackward = 100;                // persistent_kernel_for: backward pass of a vanilla cell
+constexpr int kCellBackwardGrad = 101;            // the same with the weight gradient fused in
 constexpr int kTimelineSlots = 16;                // 64-bit accumulators per workgroup in the phase timeline
 constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after h: abort flags, timeline sums
 
@@ -33,6 +34,9 @@ struct KernelArgs {
   const float* b_hn;          // [H] or null (GRU: recurrent bias of the candidate)
   const float* aux;           // backward pass: forward outputs h_t, [T][B][H]
   float* dh0;                 // backward pass: dL/dh_0, [B][H], or null
+  const float* bwd_h0;        // backward pass with weight gradient: h_0, [B][H], or null (zeros)
+  const int32_t* word_src;    // backward pass with weight gradient: packed word -> CSR position (of the handle's matrix)
+  float* dU;                  // backward pass with weight gradient: [nnz] sums, in the handle's CSR order
   float* h_out;               // [T][B][H]
   float* c_out;               // [T][B][H] (LSTM)
   unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)

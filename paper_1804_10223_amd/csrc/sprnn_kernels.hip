@@ -207,32 +207,51 @@ __device__ __forceinline__ void mac_column(float (&acc)[B], float wv, const Colu
 // N (1..4) words of one lane: all N gathers are issued back to back, then the multiply-adds follow.
 // The scheduling barrier keeps the compiler from sinking a gather below the arithmetic of an earlier one,
 // so a wavefront has N wide LDS reads in flight instead of one.
-template <int B, int N>
-__device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, const float* wv, int plane_bytes) {
+template <int B>
+__device__ __forceinline__ float dot_column(const float (&s)[B], const Column<B>& c, float sum) {
+  sum = fmaf(s[0], c.lo.x, sum);
+  if constexpr (B >= 2) sum = fmaf(s[1], c.lo.y, sum);
+  if constexpr (B >= 4) { sum = fmaf(s[2], c.lo.z, sum); sum = fmaf(s[3], c.lo.w, sum); }
+  if constexpr (B == 8) {
+    sum = fmaf(s[4], c.hi.x, sum); sum = fmaf(s[5], c.hi.y, sum);
+    sum = fmaf(s[6], c.hi.z, sum); sum = fmaf(s[7], c.hi.w, sum);
+  }
+  return sum;
+}
+
+// With GRAD, the gathered column also feeds the weight gradient of its nonzero: g[j] += sum_b side[b] * column[b]
+// (backward pass: the column is delta_{t+1} of the nonzero's column, side is the forward output of the lane's row).
+template <int B, int N, bool GRAD = false>
+__device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, const float* wv, int plane_bytes,
+                                          float* g = nullptr, const float (*side)[B] = nullptr) {
   Column<B> c[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) c[j] = gather_column<B>(off[j], plane_bytes);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int j = 0; j < N; ++j) mac_column<B>(acc, wv[j], c[j]);
+  for (int j = 0; j < N; ++j) {
+    mac_column<B>(acc, wv[j], c[j]);
+    if constexpr (GRAD) g[j] = dot_column<B>(*side, c[j], g[j]);
+  }
 }
 
 constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer this kernel addresses
 
 // The n_w (wavefront-uniform) packed words of a lane (w_off: absolute LDS addresses of their columns): gathers in
 // groups of four so the LDS reads are issued back to back; no early exit, so every register index stays static.
-template <int B, int NW>
+template <int B, int NW, bool GRAD = false>
 __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w,
-                                        int plane_bytes) {
+                                        int plane_bytes, float* g = nullptr, const float (*side)[B] = nullptr) {
 #pragma unroll
   for (int k = 0; k < NW; k += 4) {
+    float* gk = GRAD ? g + k : nullptr;
     if (k + 4 <= n_w) {
-      mac_words<B, 4>(acc, &w_off[k], &w_val[k], plane_bytes);
+      mac_words<B, 4, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
     } else if (k < n_w) {   // ragged tail of 1..3 words
       const int rem = n_w - k;
-      if (rem == 3) mac_words<B, 3>(acc, &w_off[k], &w_val[k], plane_bytes);
-      else if (rem == 2) mac_words<B, 2>(acc, &w_off[k], &w_val[k], plane_bytes);
-      else mac_words<B, 1>(acc, &w_off[k], &w_val[k], plane_bytes);
+      if (rem == 3) mac_words<B, 3, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
+      else if (rem == 2) mac_words<B, 2, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
+      else mac_words<B, 1, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
     }
   }
 }
@@ -289,12 +308,17 @@ __device__ __forceinline__ long long tick(bool on) {
 // idle fourth row; a template value of its own so that the LSTM instantiations carry none of its code),
 // 3 = backward pass through time of the vanilla cell: the handle holds the transposed matrix, time runs from T
 // down to 1, the state that is exchanged is delta_t = g'(a_t) (e_t + U^T delta_{t+1}), with g' taken from the forward
-// output h_t (p.aux) and e_t = p.x; one more step without g' and e gives dL/dh_0 = U^T delta_1 (p.dh0).
+// output h_t (p.aux) and e_t = p.x; one more step without g' and e gives dL/dh_0 = U^T delta_1 (p.dh0),
+// 4 = the same with the weight gradient fused in (one more register per packed word, so the instantiations with 24
+// and 32 words per lane are built for at most 512 threads): the column a lane gathers for a nonzero (i, j) of the transposed
+// matrix is delta_{t+1}[.][i], exactly the factor that dL/dU[i][j] = sum_t sum_b delta_{t+1}[b][i] h_t[b][j] pairs with
+// the forward output of the lane's own row j, so every gather also feeds one resident accumulator per nonzero.
 template <int B, int NW, int CELL, bool TL>
-__global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const KernelArgs p) {
+__global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
-  constexpr bool BWD = CELL == 3;
-  const int steps = BWD ? p.T + (p.dh0 ? 1 : 0) : p.T;
+  constexpr bool BWD = CELL == 3 || CELL == 4;
+  constexpr bool WGRAD = CELL == 4;
+  const int steps = BWD ? p.T + ((p.dh0 || WGRAD) ? 1 : 0) : p.T;   // the last one pairs delta_1 with h_0
   auto time_of = [&](int s) { return BWD ? p.T - 1 - s : s; };   // index into x / aux / outputs of step s
   // LDS: [h][abort flags][timeline sums][LSTM hand-over area].  A single workgroup (no exchange) keeps two copies of
   // h and writes h_t straight into the other one; otherwise one copy is enough, because the workgroup barrier
@@ -423,6 +447,22 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
   float xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(0) * B * Rx * 4, 0));
   float an = 0.0f;   // backward pass: forward output h_t of the same element
   if constexpr (BWD) an = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, x_voff, time_of(0) * B * H * 4, 0));
+  // weight gradient: forward output of this lane's row for every sample (h_0 in the extra step), one accumulator per word
+  float side[B], gacc[WGRAD ? NW : 1];
+  const int row_voff = row >= 0 ? row * 4 : kOutOfRange;
+  const __amdgpu_buffer_rsrc_t h0buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(WGRAD && p.bwd_h0 ? p.bwd_h0 : p.x), 0,
+                                                                         (WGRAD && p.bwd_h0) ? B * H * 4 : 0, kBufWord3);
+  auto load_side = [&](int s) {   // s: step index; rows of step T come from h_0 (an empty buffer returns zeros)
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+      side[b] = __builtin_bit_cast(float, s < p.T ? __builtin_amdgcn_raw_buffer_load_b32(abuf, row_voff, (time_of(s) * B + b) * H * 4, 0)
+                                                  : __builtin_amdgcn_raw_buffer_load_b32(h0buf, row_voff, b * H * 4, 0));
+  };
+  if constexpr (WGRAD) {
+#pragma unroll
+    for (int k = 0; k < NW; ++k) gacc[k] = 0.0f;
+    load_side(0);
+  }
 
   __syncthreads();
 
@@ -559,7 +599,11 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
     float acc[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) acc[b] = 0.0f;
-    operate<B, NW>(acc, w_off, w_val, n_w, plane_bytes);
+    if constexpr (WGRAD) {
+      operate<B, NW, true>(acc, w_off, w_val, n_w, plane_bytes, gacc, &side);
+    } else {
+      operate<B, NW>(acc, w_off, w_val, n_w, plane_bytes);
+    }
     ts1 = tick<TL>(tl_on);
 
     // ---- reduce over the lanes of the row: every lane ends up with the sum of its own sample
@@ -616,13 +660,16 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
       if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
     }
     if (BWD && t == p.T) {
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, out_voff, 0, 0);
+      if (p.dh0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, out_voff, 0, 0);
     } else {
       __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
     }
     if (t + 1 < p.T) {
       xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(t + 1) * B * Rx * 4, 0));
       if constexpr (BWD) an = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, x_voff, time_of(t + 1) * B * H * 4, 0));
+    }
+    if constexpr (WGRAD) {
+      if (t + 1 < steps) load_side(t + 1);
     }
     ts3 = tick<TL>(tl_on);
 
@@ -646,6 +693,15 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void persistent_kernel(const 
         s_tl[9] += 1ull;                                    // steps counted
       }
       tl_prev = ts3;
+    }
+  }
+  if constexpr (WGRAD) {   // the sums leave through the packer's word -> CSR position map (of the transposed matrix)
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+      if (k < n_w) {
+        const int src = p.word_src[((size_t)wg * NW + k) * block + tid];
+        if (src >= 0) p.dU[src] = gacc[k];
+      }
     }
   }
   if constexpr (TL) {
@@ -871,11 +927,12 @@ static const void* pick_b(int batch, int nw) {
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline) {
   const int kind = cell == SPRNN_CELL_LSTM ? 1 : (cell == SPRNN_CELL_GRU ? 2 : 0);
   if (timeline) {   // the phase timeline is built for the forward pass of the vanilla and LSTM cells only
-    if (kind == 2 || cell == kCellBackward) return nullptr;
+    if (kind == 2 || cell == kCellBackward || cell == kCellBackwardGrad) return nullptr;
     return kind == 1 ? pick_b<1, true>(batch, template_words) : pick_b<0, true>(batch, template_words);
   }
   if (kind == 2) return pick_b<2, false>(batch, template_words);
   if (cell == kCellBackward) return pick_b<3, false>(batch, template_words);
+  if (cell == kCellBackwardGrad) return pick_b<4, false>(batch, template_words);
   return kind == 1 ? pick_b<1, false>(batch, template_words) : pick_b<0, false>(batch, template_words);
 }
 

@@ -140,3 +140,59 @@ def test_weight_gradient_is_refused_where_the_forward_mapping_cannot_serve():
     with binding.SparseRNN(2000, 4, "relu", w.row_ptr, w.col_idx, w.val_bits, poll_delay=-1, compact=1) as rnn:
         with pytest.raises(binding.SprnnError):
             rnn.weight_gradient(z, z)
+
+
+# ------------------------------------------------------------------ backward pass with the weight gradient fused in
+@pytest.mark.parametrize("cell,H,B,T,dens,rownnz,opts", [
+    ("relu", 96, 4, 9, 0.3, "fixed", {}),
+    ("tanh", 257, 1, 7, 0.2, "poisson", {}),
+    ("identity", 130, 8, 5, 0.1, "poisson", {}),
+    ("relu", 333, 2, 6, 0.15, "poisson", {"balance": 1}),
+    ("tanh", 64, 4, 8, 0.4, "fixed", {"grid": 1}),
+    ("relu", 640, 4, 10, 0.3, "fixed", {"sync": "barrier"}),
+    ("relu", 640, 4, 10, 0.5, "fixed", {"lanes_per_row": 8}),      # 40 words per lane: the 512-thread instantiation
+    ("tanh", 1152, 4, 32, 0.1, "fixed", {}),
+])
+def test_backward_with_weights_matches_oracle(cell, H, B, T, dens, rownnz, opts):
+    w = wl.make_workload("bw", cell, H, B, T, dens, seed=H + T, row_nnz=rownnz, h0_std=0.5)
+    e = np.random.default_rng(H).standard_normal((T, B, H)).astype(np.float32)
+    h_fwd = oracle.rnn_forward(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=8)
+    want_d, want_dh0, want_dU = oracle.rnn_backward(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, h_fwd, e, w.h0)
+    t_rp, t_ci, t_vb, t_src = binding.transpose_csr(H, H, w.row_ptr, w.col_idx, w.val_bits, with_source=True)
+    with binding.SparseRNN(H, B, cell, t_rp, t_ci, t_vb, **opts) as rnn:
+        info = rnn.info()
+        print("case", cell, H, B, T, opts, {k: info[k] for k in ("grid", "block", "lanes_per_row", "template_words")}, flush=True)
+        try:
+            d, dh0, dU_t = rnn.backward_with_weights(_dev(e), _dev(h_fwd), _dev(w.h0))
+        except binding.SprnnError as err:
+            if err.code == binding.SPRNN_ERR_UNSUPPORTED:
+                pytest.skip("mapping too wide for the fused instantiation: %s" % err)
+            raise
+        assert rnn.check() == binding.SPRNN_OK
+        d, dh0, dU_t = d.cpu().numpy(), dh0.cpu().numpy(), dU_t.cpu().numpy()
+        # the plain backward pass on the same handle gives the same delta, bit for bit
+        d2, _ = rnn.backward(_dev(e), _dev(h_fwd))
+        assert np.array_equal(d2.cpu().numpy(), d)
+    for t in range(T):
+        assert np.abs(d[t] - want_d[t]).max() <= REL_TOL * np.abs(want_d[t]).max() + 1e-30, t
+    assert np.abs(dh0 - want_dh0).max() <= REL_TOL * np.abs(want_dh0).max() + 1e-30
+    dU = np.empty_like(dU_t)
+    dU[t_src] = dU_t                       # back to the forward matrix's CSR order
+    assert np.abs(dU - want_dU).max() <= REL_TOL * np.abs(want_dU).max()
+
+
+def test_backward_with_weights_at_the_headline_shape_and_without_h0():
+    w = wl.make_config("cfg3", steps=48)
+    e = np.random.default_rng(5).standard_normal((w.steps, w.batch, w.hidden)).astype(np.float32)
+    h_fwd = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, w.x, None, threads=8)
+    want_d, want_dh0, want_dU = oracle.rnn_backward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, h_fwd, e, None)
+    t_rp, t_ci, t_vb, t_src = binding.transpose_csr(w.hidden, w.hidden, w.row_ptr, w.col_idx, w.val_bits, with_source=True)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, t_rp, t_ci, t_vb) as rnn:
+        d, dh0, dU_t = rnn.backward_with_weights(_dev(e), _dev(h_fwd), None, want_dh0=False)
+        assert rnn.check() == binding.SPRNN_OK and dh0 is None
+        d, dU_t = d.cpu().numpy(), dU_t.cpu().numpy()
+    for t in range(w.steps):
+        assert np.abs(d[t] - want_d[t]).max() <= REL_TOL * np.abs(want_d[t]).max() + 1e-30, t
+    dU = np.empty_like(dU_t)
+    dU[t_src] = dU_t
+    assert np.abs(dU - want_dU).max() <= REL_TOL * np.abs(want_dU).max()

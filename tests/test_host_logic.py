@@ -216,7 +216,8 @@ def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
 
 def test_transpose_csr_matches_a_dense_transpose():
     w = wl.make_workload("t", "relu", 57, 1, 1, 0.3, seed=2, row_nnz="poisson")
-    t_rp, t_ci, t_vb = binding.transpose_csr(57, 57, w.row_ptr, w.col_idx, w.val_bits)
+    t_rp, t_ci, t_vb, t_src = binding.transpose_csr(57, 57, w.row_ptr, w.col_idx, w.val_bits, with_source=True)
+    assert sorted(t_src.tolist()) == list(range(w.nnz)) and np.array_equal(w.val_bits[t_src], t_vb)
     dense = np.zeros((57, 57), dtype=np.uint16)
     for r in range(57):
         dense[r, w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]]] = w.val_bits[w.row_ptr[r]:w.row_ptr[r + 1]]
