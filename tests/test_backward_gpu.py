@@ -196,3 +196,20 @@ def test_backward_with_weights_at_the_headline_shape_and_without_h0():
     dU = np.empty_like(dU_t)
     dU[t_src] = dU_t
     assert np.abs(dU - want_dU).max() <= REL_TOL * np.abs(want_dU).max()
+
+
+def test_backward_with_random_pauses_in_the_hand_off_is_unchanged():
+    w = wl.make_workload("bj", "tanh", 768, 4, 40, 0.1, seed=4, h0_std=0.3)
+    rng = np.random.default_rng(6)
+    e = rng.standard_normal((w.steps, w.batch, w.hidden)).astype(np.float32)
+    hf = rng.standard_normal((w.steps, w.batch, w.hidden)).astype(np.float32) * np.float32(0.5)
+    t_rp, t_ci, t_vb = binding.transpose_csr(w.hidden, w.hidden, w.row_ptr, w.col_idx, w.val_bits)
+    outs = []
+    for jitter in (0, 5, 11):
+        with binding.SparseRNN(w.hidden, w.batch, "tanh", t_rp, t_ci, t_vb, jitter=jitter) as rnn:
+            d, dh0, dU = rnn.backward_with_weights(_dev(e), _dev(hf), _dev(w.h0))
+            assert rnn.check() == binding.SPRNN_OK
+            outs.append((d.cpu().numpy(), dh0.cpu().numpy(), dU.cpu().numpy()))
+    for a in outs[1:]:
+        for x, y in zip(outs[0], a):
+            assert np.array_equal(x, y)
