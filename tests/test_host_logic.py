@@ -233,3 +233,47 @@ def test_transpose_csr_matches_a_dense_transpose():
     assert t_rp.tolist() == [0, 0, 1, 1, 3] and t_ci.tolist() == [0, 0, 1] and t_vb.tolist() == [7, 8, 9]
     t_rp, t_ci, t_vb = binding.transpose_csr(3, 3, np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.uint16))
     assert t_rp.tolist() == [0, 0, 0, 0] and t_ci.size == 0
+
+
+# ----------------------------------------------------------------------------- hand-off protocol on host threads
+def _build_handoff_model(tmp_path_factory):
+    import shutil
+    import subprocess
+    src = os.path.join(ROOT, "tests", "handoff_model.cpp")
+    out = str(tmp_path_factory.mktemp("handoff") / "handoff_model")
+    base = ["g++", "-O1", "-g", "-std=c++17", "-pthread", src, "-o", out]
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    r = subprocess.run(base[:4] + ["-fsanitize=thread"] + base[4:], capture_output=True, text=True)
+    if r.returncode != 0:       # no ThreadSanitizer runtime here: the model still checks the protocol's logic
+        subprocess.run(base, check=True)
+    return out
+
+
+@pytest.fixture(scope="module")
+def handoff_model(tmp_path_factory):
+    return _build_handoff_model(tmp_path_factory)
+
+
+@pytest.mark.parametrize("G,E,T,pattern,slow", [
+    (6, 3, 150, 0, -1),      # everyone reads everyone
+    (6, 3, 150, 0, 2),       # ... with one workgroup that pauses in every step
+    (7, 2, 150, 1, 6),       # one-directional needs: workgroup 0 needs nobody, the slow last one needs everybody
+    (7, 2, 150, 1, 0),
+    (8, 1, 150, 2, 3),       # neighbours only
+])
+def test_handoff_protocol_model_with_flow_control(handoff_model, G, E, T, pattern, slow):
+    import subprocess
+    for seed in (1, 2):
+        r = subprocess.run([handoff_model, str(G), str(E), str(T), str(pattern), "1", str(slow), str(seed)],
+                           capture_output=True, text=True, timeout=300)
+        assert r.returncode == 0 and "OK" in r.stdout, (r.returncode, r.stdout[-300:], r.stderr[-2000:])
+        assert "ThreadSanitizer" not in r.stderr, r.stderr[-2000:]
+
+
+def test_handoff_protocol_model_needs_its_flow_control(handoff_model):
+    """The mistake is planted in the CPU model: without the flow-control words a workgroup that needs nobody runs ahead
+    of a slow reader and destroys slots the reader has not seen, which shows as wrong values or as a wait that never ends."""
+    import subprocess
+    r = subprocess.run([handoff_model, "7", "2", "60", "1", "0", "6", "1", "300000"], capture_output=True, text=True, timeout=300)
+    assert r.returncode in (1, 2), (r.returncode, r.stdout[-300:])
