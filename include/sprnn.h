@@ -213,7 +213,7 @@ int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_
  *
  *   input_size      I >= 1, length of one input vector.
  *   x_in            device, float32 [T][B][I], I fastest; every |x| below 65504 (it is split into two
- *                   binary16 numbers that together carry 22 significant bits).
+ *                   binary16 numbers that together reproduce it to 2^-21).
  *   w_in_fp16_bits  device, [R][I] IEEE binary16 bit patterns, row r = weights of output r (R = H, or 4H with
  *                   gate blocks i|f|g|o for the LSTM cell).  Read, never written; the caller keeps ownership.
  *   bias            device, float32 [R], or NULL for zeros.
