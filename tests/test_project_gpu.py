@@ -2,7 +2,7 @@
 
 Tolerance, written out: products are exact in the matrix cores and the sums are binary32, so with K = input size
     |b'_gpu - b'_exact| <= (K + 8) * 2^-24 * (sum_k |W[r][k] x[k]| + |bias[r]|) + 2^-26 * sum_k |W[r][k]|
-(the first term is the worst case of K binary32 additions plus the 22-bit split of x; the second is the absolute
+(the first term is the worst case of K binary32 additions plus the split of x into two binary16 halves, exact to 2^-21 = 8 * 2^-24; the second is the absolute
 floor of the split for inputs below the smallest normal binary16 number).  Typical errors are ~sqrt(K) smaller.
 """
 import numpy as np
