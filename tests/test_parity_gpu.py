@@ -439,3 +439,43 @@ def test_gru_with_random_pauses_is_unchanged():
             outs.append(rnn.forward_gru(_dev(w.x), _dev(w.b_hn), _dev(w.h0)).cpu().numpy())
             assert rnn.check() == binding.SPRNN_OK
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+# ------------------------------------------------------------------ a fixed draw of odd shapes and forced mappings
+def _drawn_cases(n=36, seed=2024):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        cell = ["relu", "tanh", "identity", "lstm", "gru"][int(rng.integers(0, 5))]
+        B = [1, 2, 4, 8][int(rng.integers(0, 4))]
+        H = int(rng.integers(3, 700))
+        T = int(rng.integers(1, 12))
+        dens = float(rng.choice([0.02, 0.1, 0.3, 0.7, 1.0]))
+        rownnz = ["fixed", "poisson"][int(rng.integers(0, 2))]
+        opts = {}
+        pick = int(rng.integers(0, 6))
+        if pick == 0:
+            opts["sync"] = "barrier"
+        elif pick == 1:
+            opts["balance"] = int(rng.integers(1, 3))
+        elif pick == 2:
+            opts["compact"] = 1
+        elif pick == 3:
+            opts["bank_aware"] = 2
+        elif pick == 4:
+            lmax = 16 if cell in ("lstm", "gru") else 64
+            opts["lanes_per_row"] = int(min(lmax, max(B, 2 ** int(rng.integers(0, 7)))))
+        cases.append((cell, H, B, T, dens, rownnz, opts))
+    return cases
+
+
+@pytest.mark.parametrize("cell,H,B,T,dens,rownnz,opts", _drawn_cases())
+def test_drawn_shapes_match_oracle(cell, H, B, T, dens, rownnz, opts):
+    w = wl.make_workload("drawn", cell, H, B, T, dens, seed=H * 7 + T, gain=1.0 if cell in ("lstm", "gru") else 0.9,
+                         row_nnz=rownnz, h0_std=0.4)
+    try:
+        check_workload(w, **opts)
+    except binding.SprnnError as err:
+        # a forced mapping may not fit (too many words per lane for the lanes asked for): that must be a clean refusal
+        assert err.code in (binding.SPRNN_ERR_CAPACITY, binding.SPRNN_ERR_INVALID), err
+        assert opts, "the library's own choice of mapping must always fit these sizes"
