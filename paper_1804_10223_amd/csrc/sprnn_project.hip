@@ -11,8 +11,8 @@
 // binary32.  The scale keeps lo in the normal binary16 range whenever x is.  |x| must stay below the binary16
 // maximum (65504).
 //
-// Tiling: a workgroup of four wavefronts owns a 64 (m) x 64 NJ (n) tile of b' and walks k in slabs of 64; each
-// wavefront owns 32 x 32 NJ of it (NJ 32x32 MFMA tiles, hi and lo accumulators each).  Two LDS stages: while slab
+// Tiling: a workgroup of four wavefronts owns a 64 (m) x 64 NJ (n) tile of b' (NJ = 1, 2, 3) and walks k in slabs of
+// 64; each wavefront owns 32 x 32 NJ of it (NJ 32x32 MFMA tiles, hi and lo accumulators each).  Two LDS stages: while slab
 // s is multiplied out of one, slab s + 1 is converted and written into the other between the MFMAs, and slabs
 // s + 2 and s + 3 are in flight from memory in two register sets; one workgroup barrier per slab.  LDS rows are
 // padded by 16 bytes so that the eight lanes served in one LDS pass touch all banks.  Consecutive tiles of one n
@@ -186,7 +186,8 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
       if (q + 1 < kBK / 16) read_frags(f[(q + 1) & 1], cur, q + 1);   // the next fragments arrive under these MFMAs
       mfmas(f[q & 1]);
       store_a_chunk<NJ>(regs, q, nxt, a_at);
-      if (q < 2 * NJ) store_b_chunk<NJ>(regs, q < 2 * NJ ? q : 0, nxt, b_at);
+#pragma unroll
+      for (int i = q; i < 2 * NJ; i += kBK / 16) store_b_chunk<NJ>(regs, i, nxt, b_at);   // the W chunks, dealt over the four rounds
     }
     load(regs, min(s + 3, nfast - 1));   // unconditional, so that the count of loads in flight is the same on every path
     __syncthreads();
@@ -246,30 +247,47 @@ hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, 
   if (K > (1 << 23)) return hipErrorInvalidValue;   // 32-bit byte offsets inside a tile
   const int vec = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(w) % 16 == 0);
   const int tiles_m = (M + kBM - 1) / kBM;
-  // Wide tiles re-read less of x and W; narrow ones keep several workgroups per CU busy on small problems.
-  const long long wide = (long long)tiles_m * ((N + 127) / 128), narrow = (long long)tiles_m * ((N + 63) / 64);
-  if (narrow > 0x7fffffffLL) return hipErrorInvalidValue;
-  // (measured: 64 x 128 tiles win as soon as they occupy most CUs; SPRNN_PROJECT_TILE=64|128 overrides for experiments)
+  // Tile width 64 NJ (SPRNN_PROJECT_TILE=64|128|192 overrides the choice for experiments).
   static const int force = std::getenv("SPRNN_PROJECT_TILE") ? std::atoi(std::getenv("SPRNN_PROJECT_TILE")) : 0;
-  const bool use_wide = force ? force == 128 : wide >= 200;
-  // The wide kernel's two LDS stages exceed the 64 KB a launch may ask for by default: raise the limit once per device.
-  static bool raised[64] = {};
+  int cus = 256;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (use_wide && dev >= 0 && dev < 64 && !raised[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(project_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * stage_bytes(2));
-    if (e != hipSuccess) return e;
-    raised[dev] = true;
+  static int cu_count[64] = {};
+  if (dev >= 0 && dev < 64) {
+    if (!cu_count[dev]) {
+      hipDeviceProp_t prop;
+      if (hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0) cu_count[dev] = prop.multiProcessorCount;
+      else cu_count[dev] = 256;
+    }
+    cus = cu_count[dev];
   }
-  if (use_wide) {
-    hipLaunchKernelGGL(project_kernel<2>, dim3((unsigned)wide), dim3(kThreads), 2 * stage_bytes(2), stream, x, w, bias, out, M,
-                       N, K, tiles_m, vec);
+  int nj = 2;
+  if (force) {
+    nj = force / 64;
   } else {
-    hipLaunchKernelGGL(project_kernel<1>, dim3((unsigned)narrow), dim3(kThreads), 2 * stage_bytes(1), stream, x, w, bias, out,
-                       M, N, K, tiles_m, vec);
+    // Measured on four layer shapes: 128-wide tiles are the best all-rounder; 192-wide ones win when the 128-wide
+    // tiles are a little more than one per CU (every CU would otherwise wait for the few that carry two) and the
+    // wider ones fit one per CU; 64-wide ones only serve outputs that are no wider.
+    const long long t2 = (long long)tiles_m * ((N + 127) / 128), t3 = (long long)tiles_m * ((N + 191) / 192);
+    if (N <= 64) nj = 1;
+    else if (t2 > cus && 2 * t2 <= 3LL * cus && t3 <= cus) nj = 3;
   }
+  if (nj < 1 || nj > 3) return hipErrorInvalidValue;
+  const long long tiles = (long long)tiles_m * ((N + 64 * nj - 1) / (64 * nj));
+  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+  // Two LDS stages of the wider kernels exceed the 64 KB a launch may ask for by default: raise the limit once per device.
+  static bool raised[64][4] = {};
+  const void* kernels[4] = {nullptr, (const void*)project_kernel<1>, (const void*)project_kernel<2>, (const void*)project_kernel<3>};
+  const int lds = 2 * stage_bytes(nj);
+  if (lds > 65536 && dev >= 0 && dev < 64 && !raised[dev][nj]) {
+    e = hipFuncSetAttribute(kernels[nj], hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    raised[dev][nj] = true;
+  }
+  void* args[] = {(void*)&x, (void*)&w, (void*)&bias, (void*)&out, (void*)&M, (void*)&N, (void*)&K, (void*)&tiles_m, (void*)&vec};
+  e = hipLaunchKernel(kernels[nj], dim3((unsigned)tiles), dim3(kThreads), args, (size_t)lds, stream);
+  if (e != hipSuccess) return e;
   return hipGetLastError();
 }
 
