@@ -11,8 +11,10 @@
 // binary32.  The scale keeps lo in the normal binary16 range whenever x is.  |x| must stay below the binary16
 // maximum (65504).
 //
-// Tiling: a workgroup of four wavefronts owns a 64 (m) x 64 NJ (n) tile of b' (NJ = 1, 2, 3) and walks k in slabs of
-// 64; each wavefront owns 32 x 32 NJ of it (NJ 32x32 MFMA tiles, hi and lo accumulators each).  Two LDS stages: while slab
+// Tiling: a workgroup of eight wavefronts owns a 64 (m) x 64 NJ (n) tile of b' (NJ = 1, 2, 3) and walks k in slabs of
+// 64; four wavefronts (2 x 2 over the tile, 32 x 32 NJ each: NJ 32x32 MFMA tiles, hi and lo accumulators each) multiply
+// the lower 32 k of every slab, the other four the upper 32 k, and the two sets of sums meet through LDS at the end:
+// two wavefronts per SIMD cover each other's LDS and issue latencies.  Two LDS stages: while slab
 // s is multiplied out of one, slab s + 1 is converted and written into the other between the MFMAs, and slabs
 // s + 2 and s + 3 are in flight from memory in two register sets; one workgroup barrier per slab.  LDS rows are
 // padded by 16 bytes so that the eight lanes served in one LDS pass touch all banks.  Consecutive tiles of one n
@@ -30,7 +32,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kBM = 64;                 // rows of x (time x batch) per workgroup tile
 constexpr int kBK = 64;                 // k per slab
 constexpr int kPitch = (kBK + 8) * 2;   // LDS row pitch in bytes: 144
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;           // eight wavefronts: 2 (m) x 2 (n) x 2 (halves of a slab's k)
 constexpr float kLoScale = 2048.0f;
 constexpr int kAPlane = kBM * kPitch;   // bytes of the hi (or lo) plane of one stage
 constexpr int stage_bytes(int nj) { return 2 * kAPlane + 64 * nj * kPitch; }
@@ -38,25 +40,25 @@ constexpr int stage_bytes(int nj) { return 2 * kAPlane + 64 * nj * kPitch; }
 // NJ = 32-wide MFMA tiles per wavefront along n.
 template <int NJ>
 struct SlabRegs {
-  float4 a[4];        // 4 x (4 consecutive k of one x row)
-  uint4 b[2 * NJ];    // 2 NJ x (8 consecutive k of one W row, binary16 bits)
+  float4 a[2];        // 2 x (4 consecutive k of one x row)
+  uint4 b[NJ];        // NJ x (8 consecutive k of one W row, binary16 bits)
 };
 
-// Per-thread constants of the staging copies: chunk i of a thread is x row (tid / 16 + 16 i), k (tid % 16) * 4 and
-// W row (tid / 8 + 32 i), k (tid % 8) * 8 of the slab.
+// Per-thread constants of the staging copies: chunk i of a thread is x row (tid / 16 + 32 i), k (tid % 16) * 4 and
+// W row (tid / 8 + 64 i), k (tid % 8) * 8 of the slab.
 template <int NJ>
 struct Staging {
-  uint32_t a_off[4];        // byte offset of the chunk from x + m0 * K + k0 (row clamped to M - 1)
-  uint32_t b_off[2 * NJ];   // byte offset from W + n0 * K + k0 (row clamped to N - 1)
+  uint32_t a_off[2];        // byte offset of the chunk from x + m0 * K + k0 (row clamped to M - 1)
+  uint32_t b_off[NJ];       // byte offset from W + n0 * K + k0 (row clamped to N - 1)
 };
 
 // Full slab, rows 16-byte aligned: plain vector loads at precomputed offsets.
 template <int NJ>
 __device__ __forceinline__ void load_slab_fast(SlabRegs<NJ>& r, const Staging<NJ>& st, const char* xs, const char* ws) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) r.a[i] = *reinterpret_cast<const float4*>(xs + st.a_off[i]);
+  for (int i = 0; i < 2; ++i) r.a[i] = *reinterpret_cast<const float4*>(xs + st.a_off[i]);
 #pragma unroll
-  for (int i = 0; i < 2 * NJ; ++i) r.b[i] = *reinterpret_cast<const uint4*>(ws + st.b_off[i]);
+  for (int i = 0; i < NJ; ++i) r.b[i] = *reinterpret_cast<const uint4*>(ws + st.b_off[i]);
 }
 
 // Any slab: element-wise loads with zeros beyond K.
@@ -64,7 +66,7 @@ template <int NJ>
 __device__ __forceinline__ void load_slab_any(SlabRegs<NJ>& r, const float* __restrict__ X, const uint16_t* __restrict__ W,
                                               int tid, int m0, int n0, int k0, int M, int N, int K) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2; ++i) {
     const int c = tid + kThreads * i;
     const int row = min(m0 + (c >> 4), M - 1);
     const int k = k0 + (c & 15) * 4;
@@ -75,7 +77,7 @@ __device__ __forceinline__ void load_slab_any(SlabRegs<NJ>& r, const float* __re
     r.a[i].w = (k + 3 < K) ? src[3] : 0.0f;
   }
 #pragma unroll
-  for (int i = 0; i < 2 * NJ; ++i) {
+  for (int i = 0; i < NJ; ++i) {
     const int c = tid + kThreads * i;
     const int row = min(n0 + (c >> 3), N - 1);
     const int k = k0 + (c & 7) * 8;
@@ -104,12 +106,12 @@ __device__ __forceinline__ void store_a_chunk(const SlabRegs<NJ>& r, int i, char
   uint2 hi, lo;
   split2(r.a[i].x, r.a[i].y, hi.x, lo.x);
   split2(r.a[i].z, r.a[i].w, hi.y, lo.y);
-  *reinterpret_cast<uint2*>(stage + a_at + i * 16 * kPitch) = hi;
-  *reinterpret_cast<uint2*>(stage + kAPlane + a_at + i * 16 * kPitch) = lo;
+  *reinterpret_cast<uint2*>(stage + a_at + i * 32 * kPitch) = hi;
+  *reinterpret_cast<uint2*>(stage + kAPlane + a_at + i * 32 * kPitch) = lo;
 }
 template <int NJ>
 __device__ __forceinline__ void store_b_chunk(const SlabRegs<NJ>& r, int i, char* stage, int b_at) {
-  *reinterpret_cast<uint4*>(stage + 2 * kAPlane + b_at + i * 32 * kPitch) = r.b[i];
+  *reinterpret_cast<uint4*>(stage + 2 * kAPlane + b_at + i * 64 * kPitch) = r.b[i];
 }
 
 template <int NJ>
@@ -126,7 +128,8 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
   const int m0 = (id % tiles_m) * kBM, n0 = (id / tiles_m) * kBN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
+  const int kg = wave >> 2;                       // which half of a slab's k this wavefront multiplies
+  const int wm = wave & 1, wn = (wave >> 1) & 1;
   const int r = lane & 31, kh = lane >> 5;
   const int a_frag = (wm * 32 + r) * kPitch + kh * 16;                       // within the hi plane
   const int b_frag = 2 * kAPlane + (wn * 32 * NJ + r) * kPitch + kh * 16;
@@ -135,11 +138,11 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
 
   Staging<NJ> st;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    st.a_off[i] = (uint32_t)(min(m0 + (tid >> 4) + 16 * i, M - 1) - m0) * (uint32_t)K * 4u + (uint32_t)(tid & 15) * 16u;
+  for (int i = 0; i < 2; ++i)
+    st.a_off[i] = (uint32_t)(min(m0 + (tid >> 4) + 32 * i, M - 1) - m0) * (uint32_t)K * 4u + (uint32_t)(tid & 15) * 16u;
 #pragma unroll
-  for (int i = 0; i < 2 * NJ; ++i)
-    st.b_off[i] = (uint32_t)(min(n0 + (tid >> 3) + 32 * i, N - 1) - n0) * (uint32_t)K * 2u + (uint32_t)(tid & 7) * 16u;
+  for (int i = 0; i < NJ; ++i)
+    st.b_off[i] = (uint32_t)(min(n0 + (tid >> 3) + 64 * i, N - 1) - n0) * (uint32_t)K * 2u + (uint32_t)(tid & 7) * 16u;
   const char* x_tile = reinterpret_cast<const char*>(X + (size_t)m0 * K);
   const char* w_tile = reinterpret_cast<const char*>(W + (size_t)n0 * K);
 
@@ -180,15 +183,16 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
   // every wavefront is done with `cur` and `nxt` is complete.
   auto step = [&](char* cur, char* nxt, SlabRegs<NJ>& regs, int s) {
     Frags f[2];
-    read_frags(f[0], cur, 0);
+    read_frags(f[0], cur, 2 * kg);
+    read_frags(f[1], cur, 2 * kg + 1);
+    mfmas(f[0]);
+    store_a_chunk<NJ>(regs, 0, nxt, a_at);
 #pragma unroll
-    for (int q = 0; q < kBK / 16; ++q) {
-      if (q + 1 < kBK / 16) read_frags(f[(q + 1) & 1], cur, q + 1);   // the next fragments arrive under these MFMAs
-      mfmas(f[q & 1]);
-      store_a_chunk<NJ>(regs, q, nxt, a_at);
+    for (int i = 0; i < NJ; i += 2) store_b_chunk<NJ>(regs, i, nxt, b_at);
+    mfmas(f[1]);
+    store_a_chunk<NJ>(regs, 1, nxt, a_at);
 #pragma unroll
-      for (int i = q; i < 2 * NJ; i += kBK / 16) store_b_chunk<NJ>(regs, i, nxt, b_at);   // the W chunks, dealt over the four rounds
-    }
+    for (int i = 1; i < NJ; i += 2) store_b_chunk<NJ>(regs, i, nxt, b_at);
     load(regs, min(s + 3, nfast - 1));   // unconditional, so that the count of loads in flight is the same on every path
     __syncthreads();
   };
@@ -197,9 +201,9 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
     load(r0, 0);
     load(r1, nfast > 1 ? 1 : 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) store_a_chunk<NJ>(r0, i, lds, a_at);
+    for (int i = 0; i < 2; ++i) store_a_chunk<NJ>(r0, i, lds, a_at);
 #pragma unroll
-    for (int i = 0; i < 2 * NJ; ++i) store_b_chunk<NJ>(r0, i, lds, b_at);
+    for (int i = 0; i < NJ; ++i) store_b_chunk<NJ>(r0, i, lds, b_at);
     load(r0, min(2, nfast - 1));
     __syncthreads();
     int s = 0;
@@ -217,13 +221,25 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
     load_slab_any<NJ>(regs, X, W, tid, m0, n0, s * kBK, M, N, K);
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) store_a_chunk<NJ>(regs, i, lds, a_at);
+    for (int i = 0; i < 2; ++i) store_a_chunk<NJ>(regs, i, lds, a_at);
 #pragma unroll
-    for (int i = 0; i < 2 * NJ; ++i) store_b_chunk<NJ>(regs, i, lds, b_at);
+    for (int i = 0; i < NJ; ++i) store_b_chunk<NJ>(regs, i, lds, b_at);
     __syncthreads();
-#pragma unroll
-    for (int q = 0; q < kBK / 16; ++q) multiply(lds, q);
+    multiply(lds, 2 * kg);
+    multiply(lds, 2 * kg + 1);
   }
+
+  // The two halves of k meet: the wavefronts of the upper half hand their sums over through LDS.
+  __syncthreads();
+  float* const handover = reinterpret_cast<float*>(lds) + (size_t)(wave & 3) * NJ * 16 * 64;
+  if (kg == 1) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) handover[(j * 16 + v) * 64 + lane] = acc_hi[j][v] + acc_lo[j][v] * (1.0f / kLoScale);
+  }
+  __syncthreads();
+  if (kg == 1) return;
 
   // Accumulator element v of lane (r, kh) is row 8 (v / 4) + 4 kh + v % 4, column r of its 32 x 32 tile.
 #pragma unroll
@@ -234,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const float* __restri
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int m = m0 + wm * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
-      if (m < M) out[(size_t)m * N + n] = (acc_hi[j][v] + acc_lo[j][v] * (1.0f / kLoScale)) + bn;
+      if (m < M) out[(size_t)m * N + n] = ((acc_hi[j][v] + acc_lo[j][v] * (1.0f / kLoScale)) + handover[(j * 16 + v) * 64 + lane]) + bn;
     }
   }
 }
