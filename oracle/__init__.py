@@ -55,6 +55,11 @@ def _load():
         lib.oracle_lstm_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f32p, ci]
         lib.oracle_lstm_forward_f64.restype = ci
         lib.oracle_lstm_forward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, f64p, ci]
+        lib.oracle_lstm_forward_saved.restype = ci
+        lib.oracle_lstm_forward_saved.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f32p, f32p, ci]
+        lib.oracle_lstm_backward_f64.restype = ci
+        lib.oracle_lstm_backward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f32p, f32p,
+                                                 f64p, f64p, f64p, f64p]
         lib.oracle_gru_forward.restype = ci
         lib.oracle_gru_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, ci]
         lib.oracle_gru_forward_f64.restype = ci
@@ -203,6 +208,63 @@ def rnn_backward(hidden: int, batch: int, act: str, row_ptr, col_idx, val_bits, 
     if rc != 0:
         raise RuntimeError("oracle_rnn_backward_f64 failed")
     return d_bprime, dh0, dU[:nnz]
+
+
+def lstm_forward_saved(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, h0=None, c0=None, threads: int = 1):
+    """The binary32 LSTM forward pass, also returning what a backward pass needs:
+    (h [T, B, H], c [T, B, H], gates [T, B, 4H] after their activations, blocks i | f | g | o)."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, 4 * hidden, hidden)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T = x.shape[0]
+    if x.shape != (T, batch, 4 * hidden):
+        raise ValueError("x must be [T, B, 4H]")
+    if h0 is not None:
+        h0 = np.ascontiguousarray(h0, dtype=np.float32)
+    if c0 is not None:
+        c0 = np.ascontiguousarray(c0, dtype=np.float32)
+    h = np.empty((T, batch, hidden), dtype=np.float32)
+    c = np.empty((T, batch, hidden), dtype=np.float32)
+    gates = np.empty((T, batch, 4 * hidden), dtype=np.float32)
+    f = ctypes.c_float
+    rc = lib.oracle_lstm_forward_saved(hidden, batch, T, _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+                                       _ptr(val_bits, ctypes.c_uint16), _ptr(x, f), _ptr(h0, f), _ptr(c0, f),
+                                       _ptr(h, f), _ptr(c, f), _ptr(gates, f), int(threads))
+    if rc != 0:
+        raise RuntimeError("oracle_lstm_forward_saved failed")
+    return h, c, gates
+
+
+def lstm_backward(hidden: int, batch: int, row_ptr, col_idx, val_bits, gates, c_fwd, h_fwd, dh_ext, h0=None, c0=None):
+    """Backward pass through time of the LSTM cell for L = sum_t <dh_ext[t], h_t>, binary64, from the gate values,
+    cell states and outputs kept by the forward pass.
+    Returns (d_bprime [T, B, 4H], dh0 [B, H], dc0 [B, H], dU [nnz] in CSR order of the [4H][H] matrix)."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, 4 * hidden, hidden)
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+    gates, c_fwd, h_fwd, dh_ext, h0, c0 = map(f32, (gates, c_fwd, h_fwd, dh_ext, h0, c0))
+    T = h_fwd.shape[0]
+    if gates.shape != (T, batch, 4 * hidden):
+        raise ValueError("gates must be [T, B, 4H]")
+    for a in (c_fwd, h_fwd, dh_ext):
+        if a.shape != (T, batch, hidden):
+            raise ValueError("c_fwd, h_fwd and dh_ext must be [T, B, H]")
+    for a in (h0, c0):
+        if a is not None and a.shape != (batch, hidden):
+            raise ValueError("h0 and c0 must be [B, H]")
+    nnz = int(row_ptr[-1])
+    d_bprime = np.empty((T, batch, 4 * hidden), dtype=np.float64)
+    dh0 = np.empty((batch, hidden), dtype=np.float64)
+    dc0 = np.empty((batch, hidden), dtype=np.float64)
+    dU = np.empty(max(nnz, 1), dtype=np.float64)
+    f, d = ctypes.c_float, ctypes.c_double
+    rc = lib.oracle_lstm_backward_f64(hidden, batch, T, _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+                                      _ptr(val_bits, ctypes.c_uint16), _ptr(gates, f), _ptr(c_fwd, f), _ptr(c0, f),
+                                      _ptr(h_fwd, f), _ptr(h0, f), _ptr(dh_ext, f), _ptr(d_bprime, d), _ptr(dh0, d),
+                                      _ptr(dc0, d), _ptr(dU, d))
+    if rc != 0:
+        raise RuntimeError("oracle_lstm_backward_f64 failed")
+    return d_bprime, dh0, dc0, dU[:nnz]
 
 
 def input_projection(w_bits, x, bias=None, threads: int = 1) -> np.ndarray:

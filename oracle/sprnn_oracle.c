@@ -37,6 +37,15 @@
  *         dL/dh_0 = U_r^T delta_1,  dL/dU_r[i][j] = sum_t sum_b delta_t[b][i] h_{t-1}[b][j]  on the pattern,
  *     with g' taken from the forward output (ReLU: h_t > 0; tanh: 1 - h_t^2; identity: 1).  Binary64.
  *
+ *   - Backward pass through time of the LSTM cell above, for L = sum_t <e_t, h_t>: the chain rule applied to the
+ *     two cell equations, with the gate values i, f, g, o (after their activations), c_t and h_t kept from the
+ *     forward pass.  Going from t = T down to 1, with dc_{T+1} f_{T+1} = 0 and U^T dp_{T+1} = 0:
+ *         dh_t = e_t + U^T dp_{t+1}                      (U is [4H][H]; dp are the gradients of the four p blocks)
+ *         dc_t = dc_{t+1} f_{t+1} + dh_t o_t (1 - tanh(c_t)^2)
+ *         dp_i = dc_t g_t i_t (1 - i_t),   dp_f = dc_t c_{t-1} f_t (1 - f_t),
+ *         dp_g = dc_t i_t (1 - g_t^2),     dp_o = dh_t tanh(c_t) o_t (1 - o_t)
+ *     dp_t = dL/db'_t; dL/dh_0 = U^T dp_1; dL/dc_0 = dc_1 f_1; dL/dU[r][k] = sum_t sum_b dp_t[b][r] h_{t-1}[b][k].
+ *
  * Precision: weights are IEEE binary16 bit patterns decoded exactly to binary32
  * (Section 6 names 16-bit weights as the compressed format); activations, the
  * products and the running sums are binary32 (one rounding per multiply and per
@@ -164,9 +173,9 @@ int oracle_rnn_forward_f64(int H, int B, int T, int act, const int32_t* row_ptr,
  * LSTM cell.  W is [4H][H] in CSR with row blocks i | f | g | o; x is [T][B][4H] in the same block
  * order; h0, c0 are [B][H] or NULL (zeros); h_out, c_out are [T][B][H].
  */
-int oracle_lstm_forward(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
-                        const uint16_t* val_bits, const float* x, const float* h0, const float* c0,
-                        float* h_out, float* c_out, int threads) {
+static int lstm_forward_f32(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                            const uint16_t* val_bits, const float* x, const float* h0, const float* c0,
+                            float* h_out, float* c_out, float* gates_out, int threads) {
   if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out || !c_out) return -1;
   float* zeros = (float*)calloc((size_t)B * H, sizeof(float));
   if (!zeros) return -1;
@@ -197,6 +206,10 @@ int oracle_lstm_forward(int H, int B, int T, const int32_t* row_ptr, const int32
         const float keep = gf * c_prev[(size_t)b * H + j];
         const float add = gi * gg;
         const float c = keep + add;
+        if (gates_out) {
+          float* q = gates_out + ((size_t)t * B + b) * 4 * H + j;
+          q[0] = gi; q[(size_t)H] = gf; q[(size_t)2 * H] = gg; q[(size_t)3 * H] = go;
+        }
         c_cur[(size_t)b * H + j] = c;
         h_cur[(size_t)b * H + j] = go * tanhf(c);
       }
@@ -204,6 +217,21 @@ int oracle_lstm_forward(int H, int B, int T, const int32_t* row_ptr, const int32
   }
   free(zeros);
   return 0;
+}
+
+int oracle_lstm_forward(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                        const uint16_t* val_bits, const float* x, const float* h0, const float* c0,
+                        float* h_out, float* c_out, int threads) {
+  return lstm_forward_f32(H, B, T, row_ptr, col_idx, val_bits, x, h0, c0, h_out, c_out, NULL, threads);
+}
+
+/* The same forward pass, also keeping what a backward pass needs: gates_out is [T][B][4H], the gate values after
+ * their activations (blocks sigmoid(p_i) | sigmoid(p_f) | tanh(p_g) | sigmoid(p_o)). */
+int oracle_lstm_forward_saved(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                              const uint16_t* val_bits, const float* x, const float* h0, const float* c0,
+                              float* h_out, float* c_out, float* gates_out, int threads) {
+  if (!gates_out) return -1;
+  return lstm_forward_f32(H, B, T, row_ptr, col_idx, val_bits, x, h0, c0, h_out, c_out, gates_out, threads);
 }
 
 /* Binary64 twin of oracle_lstm_forward. */
@@ -389,5 +417,59 @@ int oracle_rnn_backward_f64(int H, int B, int T, int act, const int32_t* row_ptr
   }
   if (dh0) for (size_t j = 0; j < (size_t)B * H; ++j) dh0[j] = back[j];
   free(back);
+  return 0;
+}
+
+/*
+ * Backward pass through time of the LSTM cell, binary64.  U is [4H][H] in CSR (the forward matrix, row blocks
+ * i | f | g | o).  Kept from the forward pass: gates [T][B][4H] (after their activations, same blocks), c_fwd and
+ * h_fwd [T][B][H]; c0, h0 [B][H] or NULL (zeros).  dh_ext is [T][B][H] (e_t).  Outputs: d_bprime [T][B][4H] (dp_t),
+ * dh0, dc0 [B][H] (may be NULL), dU [nnz] in CSR order (may be NULL).
+ */
+int oracle_lstm_backward_f64(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                             const uint16_t* val_bits, const float* gates, const float* c_fwd, const float* c0,
+                             const float* h_fwd, const float* h0, const float* dh_ext,
+                             double* d_bprime, double* dh0, double* dc0, double* dU) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !d_bprime || (T > 0 && (!gates || !c_fwd || !h_fwd || !dh_ext))) return -1;
+  const int64_t nnz = row_ptr[4 * H];
+  double* back = (double*)calloc((size_t)B * H, sizeof(double));  /* U^T dp_{t+1} */
+  double* carry = (double*)calloc((size_t)B * H, sizeof(double)); /* dc_{t+1} f_{t+1} */
+  if (!back || !carry) { free(back); free(carry); return -1; }
+  if (dU) for (int64_t k = 0; k < nnz; ++k) dU[k] = 0.0;
+  for (int t = T - 1; t >= 0; --t) {
+    const float* h_prev = (t == 0) ? h0 : h_fwd + (size_t)(t - 1) * B * H;
+    const float* c_prev = (t == 0) ? c0 : c_fwd + (size_t)(t - 1) * B * H;
+    double* dp = d_bprime + (size_t)t * B * 4 * H;
+    for (int b = 0; b < B; ++b) {
+      const float* q = gates + ((size_t)t * B + b) * 4 * H;
+      for (int j = 0; j < H; ++j) {
+        const double gi = q[j], gf = q[H + j], gg = q[2 * H + j], go = q[3 * H + j];
+        const double tc = tanh((double)c_fwd[((size_t)t * B + b) * H + j]);
+        const double cp = c_prev ? (double)c_prev[(size_t)b * H + j] : 0.0;
+        const double dh = (double)dh_ext[((size_t)t * B + b) * H + j] + back[(size_t)b * H + j];
+        const double dc = carry[(size_t)b * H + j] + dh * go * (1.0 - tc * tc);
+        dp[(size_t)b * 4 * H + j] = dc * gg * gi * (1.0 - gi);
+        dp[(size_t)b * 4 * H + H + j] = dc * cp * gf * (1.0 - gf);
+        dp[(size_t)b * 4 * H + 2 * H + j] = dc * gi * (1.0 - gg * gg);
+        dp[(size_t)b * 4 * H + 3 * H + j] = dh * tc * go * (1.0 - go);
+        carry[(size_t)b * H + j] = dc * gf;
+      }
+    }
+    for (size_t j = 0; j < (size_t)B * H; ++j) back[j] = 0.0;
+    for (int r = 0; r < 4 * H; ++r) {
+      for (int32_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {
+        const double w = (double)oracle_half_bits_to_float(val_bits[k]);
+        const int j = col_idx[k];
+        for (int b = 0; b < B; ++b) {
+          back[(size_t)b * H + j] += w * dp[(size_t)b * 4 * H + r];
+          if (dU) dU[k] += dp[(size_t)b * 4 * H + r] * (h_prev ? (double)h_prev[(size_t)b * H + j] : 0.0);
+        }
+      }
+    }
+  }
+  if (dh0) for (size_t j = 0; j < (size_t)B * H; ++j) dh0[j] = back[j];
+  if (dc0) for (size_t j = 0; j < (size_t)B * H; ++j) dc0[j] = carry[j];
+  free(back);
+  free(carry);
   return 0;
 }

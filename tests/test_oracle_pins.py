@@ -12,6 +12,8 @@ bias (tests/golden/eq1_hand_example.json), numpy's float64 matrix product, ident
 forms (bit exact), exact rational brute force, and checks that a transposed operand or a dropped bias fails.
 The GRU cell (three gates; the paper gives no equations) is pinned against torch.nn.GRUCell, which fixes the gate
 order r, z, n and the place of the candidate's recurrent bias, and by closed forms and invariants.
+The backward passes (vanilla cell, LSTM) are pinned against torch autograd of the same dense cell in float64
+(torch.nn.LSTMCell for the LSTM), single-step closed forms, zero weights, and finite differences of the forward oracle.
 """
 import json
 import os
@@ -569,3 +571,131 @@ def test_backward_agrees_with_finite_differences_of_the_forward_oracle():
     hm[0, 3] -= eps
     fd = (loss(w.x, hp) - loss(w.x, hm)) / (float(hp[0, 3]) - float(hm[0, 3]))
     assert abs(fd - dh0[0, 3]) < 2e-3 * max(1.0, abs(fd))
+
+
+# ----------------------------------------------------------------------------- backward pass through time, LSTM
+def _dense_from_csr(rows, cols, row_ptr, col_idx, val_bits):
+    U = np.zeros((rows, cols))
+    for i in range(rows):
+        for k in range(row_ptr[i], row_ptr[i + 1]):
+            U[i, col_idx[k]] = float(np.array(val_bits[k], dtype=np.uint16).view(np.float16))
+    return U
+
+
+def test_lstm_saved_forward_is_the_forward_and_its_gates_reproduce_the_states():
+    H, B, T = 19, 2, 5
+    w = wl.make_workload("l", "lstm", H, B, T, 0.4, seed=8, h0_std=0.5)
+    c0 = np.random.default_rng(40).standard_normal((B, H)).astype(np.float32)
+    h, c = oracle.lstm_forward(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, c0)
+    hs, cs, gates = oracle.lstm_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, c0)
+    assert np.array_equal(h, hs) and np.array_equal(c, cs)
+    i, f, g, o = (gates[:, :, k * H:(k + 1) * H].astype(np.float64) for k in range(4))
+    c_prev = np.concatenate([c0[None], c[:-1]]).astype(np.float64)
+    np.testing.assert_allclose(f * c_prev + i * g, c, rtol=0, atol=1e-6)
+    np.testing.assert_allclose(o * np.tanh(c.astype(np.float64)), h, rtol=0, atol=1e-6)
+    assert (i > 0).all() and (i < 1).all() and (np.abs(g) < 1).all()          # sigmoid and tanh ranges
+
+
+def test_lstm_backward_matches_torch_autograd_of_lstmcell():
+    rng = np.random.default_rng(41)
+    H, B, T = 17, 3, 6
+    w = wl.make_workload("l", "lstm", H, B, T, 0.4, seed=9, row_nnz="poisson", h0_std=0.5)
+    c0 = rng.standard_normal((B, H)).astype(np.float32)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    h, c, gates = oracle.lstm_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, c0)
+    d_b, dh0, dc0, dU = oracle.lstm_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, c, h, e, w.h0, c0)
+    U = _dense_from_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    cell = torch.nn.LSTMCell(4 * H, H, bias=False).double()                   # gate order i, f, g, o
+    with torch.no_grad():
+        cell.weight_hh.copy_(torch.from_numpy(U))
+        cell.weight_ih.copy_(torch.eye(4 * H, dtype=torch.float64))
+    cell.weight_ih.requires_grad_(False)
+    xt = torch.tensor(w.x.astype(np.float64), requires_grad=True)
+    h0t = torch.tensor(w.h0.astype(np.float64), requires_grad=True)
+    c0t = torch.tensor(c0.astype(np.float64), requires_grad=True)
+    ht, ct, loss = h0t, c0t, 0.0
+    for t in range(T):
+        ht, ct = cell(xt[t], (ht, ct))
+        loss = loss + (torch.tensor(e[t].astype(np.float64)) * ht).sum()
+    loss.backward()
+    # the oracle starts from the binary32 forward quantities, torch from its own binary64 ones
+    tol = lambda a: 5e-6 * np.abs(a).max()
+    np.testing.assert_allclose(d_b, xt.grad.numpy(), rtol=0, atol=tol(xt.grad.numpy()))
+    np.testing.assert_allclose(dh0, h0t.grad.numpy(), rtol=0, atol=tol(h0t.grad.numpy()))
+    np.testing.assert_allclose(dc0, c0t.grad.numpy(), rtol=0, atol=tol(c0t.grad.numpy()))
+    dense = cell.weight_hh.grad.numpy()
+    want = np.array([dense[i, w.col_idx[k]] for i in range(4 * H) for k in range(w.row_ptr[i], w.row_ptr[i + 1])])
+    np.testing.assert_allclose(dU, want, rtol=0, atol=tol(want))
+    # every block of d_bprime carries signal, and two swapped gate blocks are far away
+    for k in range(4):
+        assert np.abs(d_b[:, :, k * H:(k + 1) * H]).max() > 1e-3
+    sw = gates.copy()
+    sw[:, :, 0:H], sw[:, :, 3 * H:4 * H] = gates[:, :, 3 * H:4 * H], gates[:, :, 0:H]
+    bad = oracle.lstm_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, sw, c, h, e, w.h0, c0)[0]
+    assert np.abs(bad - d_b).max() > 1e-2
+
+
+def test_lstm_backward_single_step_closed_form_and_zero_weights():
+    rng = np.random.default_rng(42)
+    H, B = 6, 2
+    w = wl.make_workload("l", "lstm", H, B, 1, 0.5, seed=10, h0_std=1.0)
+    c0 = rng.standard_normal((B, H)).astype(np.float32)
+    e = rng.standard_normal((1, B, H)).astype(np.float32)
+    h, c, gates = oracle.lstm_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, c0)
+    d_b, dh0, dc0, dU = oracle.lstm_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, c, h, e, w.h0, c0)
+    i, f, g, o = (gates[0][:, k * H:(k + 1) * H].astype(np.float64) for k in range(4))
+    tc = np.tanh(c[0].astype(np.float64))
+    dc = e[0] * o * (1 - tc * tc)
+    want = np.concatenate([dc * g * i * (1 - i), dc * c0 * f * (1 - f), dc * i * (1 - g * g), e[0] * tc * o * (1 - o)], axis=1)
+    np.testing.assert_allclose(d_b[0], want, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(dc0, dc * f, rtol=0, atol=1e-15)
+    U = _dense_from_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    np.testing.assert_allclose(dh0, want @ U, rtol=0, atol=1e-14)
+    k = 0
+    for r in range(4 * H):
+        for kk in range(w.row_ptr[r], w.row_ptr[r + 1]):
+            np.testing.assert_allclose(dU[k], (want[:, r] * w.h0[:, w.col_idx[kk]].astype(np.float64)).sum(), rtol=0, atol=1e-14)
+            k += 1
+    # zero weights: only the cell state carries gradient through time
+    zero = np.zeros(4 * H + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16)
+    T = 3
+    x = rng.standard_normal((T, B, 4 * H)).astype(np.float32)
+    ee = rng.standard_normal((T, B, H)).astype(np.float32)
+    hz, cz, gz = oracle.lstm_forward_saved(H, B, *zero, x, None, c0)
+    d_b, dh0, dc0, dU = oracle.lstm_backward(H, B, *zero, gz, cz, hz, ee, None, c0)
+    assert not dh0.any() and dU.size == 0
+    fz, oz = gz[:, :, H:2 * H].astype(np.float64), gz[:, :, 3 * H:].astype(np.float64)
+    tz = np.tanh(cz.astype(np.float64))
+    run = np.zeros((B, H))
+    for t in range(T - 1, -1, -1):
+        dct = run + ee[t] * oz[t] * (1 - tz[t] ** 2)
+        np.testing.assert_allclose(d_b[t][:, 3 * H:], ee[t] * tz[t] * oz[t] * (1 - oz[t]), rtol=0, atol=1e-15)
+        run = dct * fz[t]
+    np.testing.assert_allclose(dc0, run, rtol=0, atol=1e-15)
+
+
+def test_lstm_backward_agrees_with_finite_differences_of_the_forward_oracle():
+    rng = np.random.default_rng(43)
+    H, B, T = 5, 1, 4
+    w = wl.make_workload("l", "lstm", H, B, T, 0.6, seed=11, h0_std=0.5)
+    c0 = rng.standard_normal((B, H)).astype(np.float32)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    fwd = lambda x, h0, cc: oracle.lstm_forward(H, B, w.row_ptr, w.col_idx, w.val_bits, x, h0, cc, f64=True)[0]
+    h, c, gates = oracle.lstm_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, c0)
+    d_b, dh0, dc0, _ = oracle.lstm_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, c, h, e, w.h0, c0)
+    loss = lambda x, h0, cc: float((fwd(x, h0, cc) * e).sum())
+    eps = 2.0 ** -7
+    for (t, r) in ((0, 1), (1, H + 2), (2, 2 * H + 4), (3, 3 * H)):
+        xp, xm = w.x.copy(), w.x.copy()
+        xp[t, 0, r] += eps
+        xm[t, 0, r] -= eps
+        fd = (loss(xp, w.h0, c0) - loss(xm, w.h0, c0)) / (float(xp[t, 0, r]) - float(xm[t, 0, r]))
+        assert abs(fd - d_b[t, 0, r]) < 2e-3 * max(1.0, abs(fd))
+    for (arr, grad, which) in ((w.h0, dh0, 0), (c0, dc0, 1)):
+        ap, am = arr.copy(), arr.copy()
+        ap[0, 3] += eps
+        am[0, 3] -= eps
+        args_p = (w.x, ap, c0) if which == 0 else (w.x, w.h0, ap)
+        args_m = (w.x, am, c0) if which == 0 else (w.x, w.h0, am)
+        fd = (loss(*args_p) - loss(*args_m)) / (float(ap[0, 3]) - float(am[0, 3]))
+        assert abs(fd - grad[0, 3]) < 2e-3 * max(1.0, abs(fd))
