@@ -33,8 +33,11 @@ enum {
 };
 
 /* Cell / activation g of Eq. 2.  SPRNN_CELL_LSTM selects the four-gate cell of Appendix B, SPRNN_CELL_GRU a
- * three-gate gated recurrent unit (Section 2 names it as a cell the approach extends to). */
-enum { SPRNN_ACT_RELU = 0, SPRNN_ACT_TANH = 1, SPRNN_ACT_IDENTITY = 2, SPRNN_CELL_LSTM = 3, SPRNN_CELL_GRU = 4 };
+ * three-gate gated recurrent unit (Section 2 names it as a cell the approach extends to).
+ * SPRNN_CELL_LSTM_BACKWARD makes a handle for the backward pass of an LSTM layer (sprnn_backward_lstm): it holds the
+ * TRANSPOSE of the LSTM's [4H][H] matrix, H rows whose columns index the 4H gate rows. */
+enum { SPRNN_ACT_RELU = 0, SPRNN_ACT_TANH = 1, SPRNN_ACT_IDENTITY = 2, SPRNN_CELL_LSTM = 3, SPRNN_CELL_GRU = 4,
+       SPRNN_CELL_LSTM_BACKWARD = 5 };
 
 /* Cross-workgroup hand-off of h_t (Section 4.2 discusses a global barrier versus Lamport timestamps). */
 enum {
@@ -101,10 +104,12 @@ typedef struct sprnn_info_s {
  *
  *   hidden      H, 1..65535.
  *   batch       B in {1,2,4,8}: sequences advanced together (wide loads of Section 4.1).
- *   activation  SPRNN_ACT_* (R = H rows), SPRNN_CELL_LSTM (R = 4H rows, row blocks i|f|g|o) or
- *               SPRNN_CELL_GRU (R = 3H rows, row blocks r|z|n).
+ *   activation  SPRNN_ACT_* (R = H rows), SPRNN_CELL_LSTM (R = 4H rows, row blocks i|f|g|o),
+ *               SPRNN_CELL_GRU (R = 3H rows, row blocks r|z|n) or SPRNN_CELL_LSTM_BACKWARD (R = H rows with
+ *               columns below 4H, H <= 16383: the transpose of an LSTM's matrix).
  *   row_ptr     host, R+1 entries, row_ptr[0] = 0, non-decreasing.
- *   col_idx     host, nnz = row_ptr[R] entries, 0 <= col < H, strictly increasing inside a row.
+ *   col_idx     host, nnz = row_ptr[R] entries, 0 <= col < H (< 4H for SPRNN_CELL_LSTM_BACKWARD), strictly
+ *               increasing inside a row.
  *   val_fp16_bits host, nnz IEEE binary16 bit patterns (finite).  The library rounds nothing.
  *   device_id   HIP device ordinal.
  *
@@ -141,6 +146,13 @@ int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, floa
  */
 int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                        float* h_out, float* c_out, void* stream);
+
+/*
+ * sprnn_forward_lstm that also keeps what the backward pass needs: gates_out, device float32 [T][B][4H], receives the
+ * gate values after their activations, blocks sigmoid(p_i) | sigmoid(p_f) | tanh(p_g) | sigmoid(p_o).
+ */
+int sprnn_forward_lstm_train(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                             float* h_out, float* c_out, float* gates_out, void* stream);
 
 /*
  * GRU cell: x is float32 [T][B][3H] with gate blocks r|z|n (input projection and every bias except b_hn folded in),
@@ -186,15 +198,39 @@ int sprnn_backward_with_weights(sprnn_handle_t h_transposed, int T, const float*
 /*
  * Gradient of the recurrent weights on their sparsity pattern, the non-recurrent half of the backward pass:
  *   dU[k] = sum_t sum_b delta_t[b][row(k)] * h_{t-1}[b][col(k)]      for every stored nonzero k, in CSR order.
- * Runs on the FORWARD handle (vanilla cells whose h fits in LDS whole: no column compaction) and re-uses its
- * mapping: every lane keeps one accumulator per nonzero it holds in the forward pass, in registers, for all T steps.
- *   d_bprime  device, float32 [T][B][H]: delta_t from sprnn_backward.
+ * Runs on the FORWARD handle (vanilla cells and the LSTM, where h fits in LDS whole: no column compaction) and
+ * re-uses its mapping: every lane keeps one accumulator per nonzero it holds in the forward pass, in registers, for
+ * all T steps.
+ *   d_bprime  device, float32 [T][B][R]: delta_t from sprnn_backward (R = H), dp_t from sprnn_backward_lstm (R = 4H).
  *   h_fwd     device, float32 [T][B][H]: forward outputs h_1..h_T;  h0: device [B][H] or NULL (zeros).
  *   dU        device, float32 [nnz]: overwritten (T = 0 writes zeros).
  * Sums are binary32, in time order.  Only enqueues work; allocates nothing.
  */
 int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const float* h_fwd, const float* h0, float* dU,
                           void* stream);
+
+/*
+ * Backward pass through time of the LSTM cell (Appendix B: four gate rows per hidden unit; B.1: the pruned weights
+ * serve both passes), weights resident on chip.  For a loss with e_t = dL/dh_t from outside the layer, going from
+ * t = T down to 1 with everything beyond T zero:
+ *   dh_t = e_t + U^T dp_{t+1},     dc_t = dc_{t+1} f_{t+1} + dh_t o_t (1 - tanh(c_t)^2),
+ *   dp_i = dc_t g_t i_t (1 - i_t),  dp_f = dc_t c_{t-1} f_t (1 - f_t),  dp_g = dc_t i_t (1 - g_t^2),
+ *   dp_o = dh_t tanh(c_t) o_t (1 - o_t);        dL/db'_t = dp_t,  dL/dh_0 = U^T dp_1,  dL/dc_0 = dc_1 f_1.
+ * The recurrent product runs over the 4H gate gradients, so the handle holds the TRANSPOSE of the forward matrix
+ * (sprnn_transpose_csr with rows = 4H, cols = H; created with SPRNN_CELL_LSTM_BACKWARD and the forward pass's batch):
+ * one row per hidden unit, whose lanes gather from the exchanged vector dp_{t+1} of length 4H; the lane that owns
+ * (unit, sample) keeps dc in a register and publishes the unit's four gate gradients.
+ *
+ *   dh_ext    device, float32 [T][B][H]: e_t.
+ *   gates     device, float32 [T][B][4H]: gate values kept by sprnn_forward_lstm_train.
+ *   c_fwd     device, float32 [T][B][H]: cell states c_1..c_T of the forward pass;  c0: [B][H] or NULL (zeros).
+ *   d_bprime  device, float32 [T][B][4H]: dp_t (the gradient of the recurrent weights follows from it and the
+ *             forward outputs without a recurrence: sprnn_weight_gradient on the forward LSTM handle).
+ *   dh0, dc0  device, float32 [B][H], or NULL if not wanted.
+ * One launch; T is limited to 2^30 / (16 B H) timesteps per call.  Same stream, state and error rules as sprnn_forward.
+ */
+int sprnn_backward_lstm(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates, const float* c_fwd,
+                        const float* c0, float* d_bprime, float* dh0, float* dc0, void* stream);
 
 /*
  * Host helper: transpose a CSR matrix (rows x cols) of binary16 values.  t_row_ptr has cols + 1 entries, t_col_idx

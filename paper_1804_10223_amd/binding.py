@@ -22,11 +22,12 @@ SPRNN_ERR_HIP = -3
 SPRNN_ERR_UNSUPPORTED = -4
 SPRNN_ERR_STATE = -5
 
-CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4}
+CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4, "lstm_backward": 5}
 GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
-EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_gru", "sprnn_forward_stepwise",
+EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
+           "sprnn_forward_stepwise", "sprnn_backward_lstm",
            "sprnn_project", "sprnn_backward", "sprnn_backward_with_weights", "sprnn_weight_gradient", "sprnn_transpose_csr",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
@@ -83,6 +84,10 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_forward.argtypes = [vp, ci, vp, vp, vp, vp]
     lib.sprnn_forward_lstm.restype = ci
     lib.sprnn_forward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_forward_lstm_train.restype = ci
+    lib.sprnn_forward_lstm_train.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_backward_lstm.restype = ci
+    lib.sprnn_backward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_gru.restype = ci
     lib.sprnn_forward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_backward.restype = ci
@@ -277,6 +282,42 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_forward_lstm")
         return h_out, c_out
 
+    def forward_lstm_train(self, x, h0=None, c0=None):
+        """sprnn_forward_lstm_train: x [T, B, 4H] -> (h_out, c_out [T, B, H], gates [T, B, 4H] after their activations)."""
+        import torch
+        T = int(x.shape[0])
+        h_out, c_out = self._alloc(T), self._alloc(T)
+        gates = torch.empty((T, self.batch, self.rows), dtype=torch.float32, device="cuda:%d" % self.device)
+        rc = self._lib.sprnn_forward_lstm_train(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
+                                                _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                                _dev_ptr(c0, (self.batch, self.hidden), "c0"),
+                                                _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"),
+                                                _dev_ptr(c_out, (T, self.batch, self.hidden), "c_out"),
+                                                _dev_ptr(gates, (T, self.batch, self.rows), "gates_out"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_forward_lstm_train")
+        return h_out, c_out, gates
+
+    def backward_lstm(self, dh_ext, gates, c_fwd, c0=None, want_dh0=True, want_dc0=True):
+        """sprnn_backward_lstm on a "lstm_backward" handle (the TRANSPOSED [H][4H] matrix):
+        (d_bprime [T, B, 4H], dh0 [B, H] or None, dc0 [B, H] or None)."""
+        import torch
+        T = int(dh_ext.shape[0])
+        dev = "cuda:%d" % self.device
+        d_bprime = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device=dev)
+        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
+        dc0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dc0 else None
+        rc = self._lib.sprnn_backward_lstm(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
+                                           _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"),
+                                           _dev_ptr(c_fwd, (T, self.batch, self.hidden), "c_fwd"),
+                                           _dev_ptr(c0, (self.batch, self.hidden), "c0"),
+                                           _dev_ptr(d_bprime, (T, self.batch, 4 * self.hidden), "d_bprime"),
+                                           _dev_ptr(dh0, (self.batch, self.hidden), "dh0"),
+                                           _dev_ptr(dc0, (self.batch, self.hidden), "dc0"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_backward_lstm")
+        return d_bprime, dh0, dc0
+
     def forward_gru(self, x, b_hn=None, h0=None, h_out=None):
         """sprnn_forward_gru: x [T, B, 3H] (blocks r|z|n), b_hn [H] or None -> h_out [T, B, H]."""
         T = int(x.shape[0])
@@ -333,7 +374,7 @@ class SparseRNN:
         nnz = self.info()["nnz"]
         if dU is None:
             dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device="cuda:%d" % self.device)
-        rc = self._lib.sprnn_weight_gradient(self._h, T, _dev_ptr(d_bprime, (T, self.batch, self.hidden), "d_bprime"),
+        rc = self._lib.sprnn_weight_gradient(self._h, T, _dev_ptr(d_bprime, (T, self.batch, self.rows), "d_bprime"),
                                              _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
                                              _dev_ptr(h0, (self.batch, self.hidden), "h0"),
                                              ctypes.c_void_p(dU.data_ptr()), self._stream())

@@ -106,7 +106,8 @@ int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 6 : 0; }
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const float* b_hn = nullptr,
                               const float* bwd_h_fwd = nullptr, float* bwd_dh0 = nullptr, bool backward = false,
-                              const float* bwd_h0 = nullptr, float* bwd_dU = nullptr);
+                              const float* bwd_h0 = nullptr, float* bwd_dU = nullptr, float* gates_out = nullptr,
+                              float* bwd_dc0 = nullptr);
 static int calibrate_poll_delay(sprnn_handle_s* h);
 
 extern "C" {
@@ -216,7 +217,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   std::vector<uint32_t> ring(ring_words, kSentinel);
   {
     // bytes of a slot beyond the last element of h are never written by a producer: mark them as present
-    const size_t used = (size_t)m.hidden * m.batch;   // 32-bit elements (both planes for batch 8)
+    const size_t used = (size_t)m.cols * m.batch;     // 32-bit elements (both planes for batch 8)
     for (int s = 0; s < kRingSlots; ++s)
       for (size_t i = used; i < (size_t)m.h_bytes / 4; ++i) ring[(size_t)s * m.h_bytes / 4 + i] = 0u;
   }
@@ -232,12 +233,12 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
             SPRNN_HIP(upload(&h->d_col, col_idx, (size_t)m.nnz)) &&
             SPRNN_HIP(upload(&h->d_val, val_fp16_bits, (size_t)m.nnz));
-  if (ok && m.cell <= SPRNN_ACT_IDENTITY && !m.compact) {
+  if (ok && (m.cell <= SPRNN_ACT_IDENTITY || m.cell == SPRNN_CELL_LSTM) && !m.compact) {
     // the weight gradient re-uses the forward mapping: one accumulator per packed word, left through this map
     h->kernel_wgrad = weight_grad_kernel_for(m.batch, m.template_words);
     ok = h->kernel_wgrad != nullptr && SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size())) &&
          SPRNN_HIP(hipFuncSetAttribute(h->kernel_wgrad, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds));
-    if (ok && h->kernel_bwd && !m.timeline) {
+    if (ok && h->kernel_bwd && !m.timeline && m.cell <= SPRNN_ACT_IDENTITY) {
       // backward pass with the weight gradient fused in: same co-residency requirement as the plain one
       const void* k = persistent_kernel_for(m.batch, m.template_words, kCellBackwardGrad, false);
       int per_cu_g = 0;
@@ -269,7 +270,8 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const float* b_hn, const float* bwd_h_fwd,
-                              float* bwd_dh0, bool backward, const float* bwd_h0, float* bwd_dU) {
+                              float* bwd_dh0, bool backward, const float* bwd_h0, float* bwd_dU, float* gates_out,
+                              float* bwd_dc0) {
   if (h->poisoned) return SPRNN_ERR_STATE;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
@@ -277,7 +279,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
   const Mapping& m = h->map;
   // The kernel addresses x and the outputs with 32-bit byte offsets from the start of the call, so a very
   // long sequence is run as several launches, each continuing from the last state of the one before.
-  const size_t step_bytes = (size_t)m.batch * m.rows * 4;
+  const size_t step_bytes = (size_t)m.batch * std::max(m.rows, m.cols) * 4;
   const int t_max = (int)std::max<size_t>(1, ((size_t)1 << 30) / step_bytes);
   const size_t hb = (size_t)m.batch * m.hidden;
   if (backward && T > t_max) return SPRNN_ERR_UNSUPPORTED;   // time runs backwards: one launch only
@@ -293,16 +295,19 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.c0 = t0 ? (c_out ? c_out + (size_t)(t0 - 1) * hb : nullptr) : c0;
     a.h_out = h_out + (size_t)t0 * hb;
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
+    a.gates_out = gates_out ? gates_out + (size_t)t0 * m.batch * m.rows : nullptr;
+    a.dc0 = bwd_dc0;
     a.b_hn = b_hn;
     a.aux = bwd_h_fwd; a.dh0 = bwd_dh0; a.bwd_h0 = bwd_h0; a.word_src = h->d_word_src; a.dU = bwd_dU;
     a.timeline = h->d_timeline;
-    a.hidden = m.hidden; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
+    a.hidden = m.cols; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
     a.step_base = h->step_base; a.barrier_base = h->barrier_base;
     void* args[] = {&a};
     // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
     const bool plain = m.plain_launch != 0 || m.grid == 1;
-    const void* kernel = backward ? (bwd_dU ? h->kernel_bwd_grad : h->kernel_bwd) : h->kernel;
+    const bool lstm_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD;
+    const void* kernel = (backward && !lstm_bwd) ? (bwd_dU ? h->kernel_bwd_grad : h->kernel_bwd) : h->kernel;
     hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
                          : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
@@ -320,7 +325,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
 static int calibrate_poll_delay(sprnn_handle_s* h) {
   const Mapping& m = h->map;
   const int T = 48;
-  const size_t xn = (size_t)T * m.batch * m.rows, hn = (size_t)T * m.batch * m.hidden;
+  const size_t xn = (size_t)T * m.batch * std::max(m.rows, m.cols), hn = (size_t)T * m.batch * m.cols;
   float *d_x = nullptr, *d_h = nullptr, *d_c = nullptr;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   const bool lstm = m.cell == SPRNN_CELL_LSTM;
@@ -337,7 +342,10 @@ static int calibrate_poll_delay(sprnn_handle_s* h) {
       float ms = 0.0f;
       for (int rep = 0; rep < 2 && rc == SPRNN_OK; ++rep) {   // the first run of a setting warms up, the second is timed
         if (!SPRNN_HIP(hipEventRecord(e0, nullptr))) { ok = false; break; }
-        rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, d_c, nullptr);
+        // (the LSTM's backward pass reads e_t, the gate values and the cell states: all from the zero buffer)
+        rc = m.cell == SPRNN_CELL_LSTM_BACKWARD
+                 ? forward_persistent(h, T, d_x, nullptr, nullptr, d_h, d_x, nullptr, nullptr, d_x, nullptr, true)
+                 : forward_persistent(h, T, d_x, nullptr, nullptr, d_h, d_c, nullptr);
         if (rc != SPRNN_OK) break;
         if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
       }
@@ -355,7 +363,7 @@ static int calibrate_poll_delay(sprnn_handle_s* h) {
 
 int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream) {
   if (!h || T < 0) return SPRNN_ERR_INVALID;
-  if (h->map.cell == SPRNN_CELL_LSTM || h->map.cell == SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
+  if (h->map.cell > SPRNN_ACT_IDENTITY) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
   return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream);
 }
@@ -366,6 +374,33 @@ int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0,
   if (h->map.cell != SPRNN_CELL_LSTM) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!x || !h_out || !c_out)) return SPRNN_ERR_INVALID;
   return forward_persistent(h, T, x, h0, c0, h_out, c_out, stream);
+}
+
+int sprnn_forward_lstm_train(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
+                             float* h_out, float* c_out, float* gates_out, void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_LSTM) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!x || !h_out || !c_out || !gates_out)) return SPRNN_ERR_INVALID;
+  return forward_persistent(h, T, x, h0, c0, h_out, c_out, stream, nullptr, nullptr, nullptr, false, nullptr, nullptr, gates_out);
+}
+
+int sprnn_backward_lstm(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates, const float* c_fwd,
+                        const float* c0, float* d_bprime, float* dh0, float* dc0, void* stream) {
+  sprnn_handle_t h = h_transposed;
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!dh_ext || !gates || !c_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
+  if (T == 0) {   // nothing flows back: both initial-state gradients are zero
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return SPRNN_ERR_HIP;
+    const size_t n = (size_t)h->map.batch * h->map.hidden;
+    for (float* out : {dh0, dc0})
+      if (out && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(out), 0u, n, (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    return SPRNN_OK;
+  }
+  // (the kernel only reads the cell states; they travel in the forward pass's output slot of the argument block)
+  return forward_persistent(h, T, dh_ext, nullptr, c0, d_bprime, const_cast<float*>(c_fwd), stream, nullptr, gates, dh0, true,
+                            nullptr, nullptr, nullptr, dc0);
 }
 
 int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn, const float* h0, float* h_out,
@@ -414,7 +449,7 @@ int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const 
   WGradArgs a;
   a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words; a.word_src = h->d_word_src;
   a.delta = d_bprime; a.h_fwd = h_fwd; a.h0 = h0; a.dU = dU;
-  a.hidden = m.hidden; a.T = T; a.index_shift = m.index_shift;
+  a.hidden = m.hidden; a.T = T; a.index_shift = m.index_shift; a.rows = m.rows;
   void* args[] = {&a};
   // workgroups are independent here: an ordinary launch, one workgroup per CU by the same LDS request
   const hipError_t e = hipLaunchKernel(h->kernel_wgrad, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
@@ -446,7 +481,7 @@ int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_
 int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                            float* h_out, float* c_out, void* stream) {
   if (!h || T < 0) return SPRNN_ERR_INVALID;
-  if (h->map.cell == SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
+  if (h->map.cell == SPRNN_CELL_GRU || h->map.cell == SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
   const Mapping& m = h->map;
   const bool lstm = m.cell == SPRNN_CELL_LSTM;
   if (T > 0 && (!x || !h_out || (lstm && !c_out))) return SPRNN_ERR_INVALID;
@@ -472,6 +507,7 @@ int sprnn_project(sprnn_handle_t h, int T, int input_size, const float* x_in, co
   if (!h || T < 0 || input_size <= 0) return SPRNN_ERR_INVALID;
   if (T > 0 && (!x_in || !w_in_fp16_bits || !b_prime)) return SPRNN_ERR_INVALID;
   if ((long long)T * h->map.batch > 0x7fffffffLL) return SPRNN_ERR_INVALID;
+  if (h->map.cell == SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
   if (!guard.ok) return SPRNN_ERR_HIP;

@@ -32,13 +32,15 @@ struct KernelArgs {
   const float* h0;            // [B][H] or null
   const float* c0;            // [B][H] or null (LSTM)
   const float* b_hn;          // [H] or null (GRU: recurrent bias of the candidate)
-  const float* aux;           // backward pass: forward outputs h_t, [T][B][H]
+  const float* aux;           // backward pass: forward outputs h_t, [T][B][H]; LSTM backward: gate values, [T][B][4H]
   float* dh0;                 // backward pass: dL/dh_0, [B][H], or null
   const float* bwd_h0;        // backward pass with weight gradient: h_0, [B][H], or null (zeros)
   const int32_t* word_src;    // backward pass with weight gradient: packed word -> CSR position (of the handle's matrix)
   float* dU;                  // backward pass with weight gradient: [nnz] sums, in the handle's CSR order
   float* h_out;               // [T][B][H]
-  float* c_out;               // [T][B][H] (LSTM)
+  float* c_out;               // [T][B][H] (LSTM; its backward pass reads the forward cell states from here)
+  float* gates_out;           // LSTM forward: [T][B][4H] gate values after their activations, or null (not kept)
+  float* dc0;                 // LSTM backward: dL/dc_0, [B][H], or null
   unsigned long long* timeline;  // [grid][16] phase accumulators in wall-clock ticks, or null (off)
   int hidden, T, lanes_per_row, act, h_bytes, poll_delay, spin_limit, sync;
   int fill_rows;              // rounds in the copy list (column compaction)
@@ -55,11 +57,12 @@ struct WGradArgs {
   const int32_t* lane_row;    // [grid][block]
   const int32_t* wave_words;  // [grid][waves]
   const int32_t* word_src;    // [grid][NW][block] CSR position of each packed word, -1 for padding
-  const float* delta;         // [T][B][H]
+  const float* delta;         // [T][B][rows]
   const float* h_fwd;         // [T][B][H] forward outputs h_1..h_T
   const float* h0;            // [B][H] or null (zeros)
   float* dU;                  // [nnz] CSR order
   int hidden, T, index_shift;
+  int rows;                   // rows of the matrix: hidden, or 4 * hidden for the LSTM
 };
 
 struct StepArgs {

@@ -321,13 +321,19 @@ __device__ __forceinline__ long long tick(bool on) {
 // and 32 words per lane are built for at most 512 threads): the column a lane gathers for a nonzero (i, j) of the transposed
 // matrix is delta_{t+1}[.][i], exactly the factor that dL/dU[i][j] = sum_t sum_b delta_{t+1}[b][i] h_t[b][j] pairs with
 // the forward output of the lane's own row j, so every gather also feeds one resident accumulator per nonzero.
+// 5 = backward pass through time of the LSTM: the handle holds the transposed matrix, one row per hidden unit over
+// the 4H gate gradients, so p.hidden (the length of the exchanged vector) is 4 * units and the vanilla layout applies.
+// The owner lane of (unit, sample) turns dh_t = e_t + U^T dp_{t+1} into the unit's four gate gradients with the gate
+// values (p.aux) and cell states (p.c_out, p.c0) of the forward pass, keeps dc_{t+1} f_{t+1} in a register, and
+// publishes four elements of the exchanged vector instead of one; one more step gives dL/dh_0 (p.dh0).
 template <int B, int NW, int CELL, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
+  constexpr bool LBWD = CELL == 5;
   constexpr bool BWD = CELL == 3 || CELL == 4;
   constexpr bool WGRAD = CELL == 4;
-  const int steps = BWD ? p.T + ((p.dh0 || WGRAD) ? 1 : 0) : p.T;   // the last one pairs delta_1 with h_0
-  auto time_of = [&](int s) { return BWD ? p.T - 1 - s : s; };   // index into x / aux / outputs of step s
+  const int steps = BWD ? p.T + ((p.dh0 || WGRAD) ? 1 : 0) : (LBWD ? p.T + (p.dh0 ? 1 : 0) : p.T);   // the last one pairs delta_1 with h_0
+  auto time_of = [&](int s) { return (BWD || LBWD) ? p.T - 1 - s : s; };   // index into x / aux / outputs of step s
   // LDS: [h][abort flags][timeline sums][LSTM hand-over area].  A single workgroup (no exchange) keeps two copies of
   // h and writes h_t straight into the other one; otherwise one copy is enough, because the workgroup barrier
   // before a step's first poll also separates the last gather of step t from the first write of h_t.
@@ -369,7 +375,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
   // candidate row hands over the recurrent sum (+ b_hn) and b'_n separately (the reset gate multiplies only the
   // former), the latter in the fourth row's slot, and the cell lanes keep h_{t-1} where the LSTM keeps c.
   constexpr bool gru = CELL == 2;
-  const int Rx = gru ? 3 * H : R;              // rows of b' per sample
+  const int Hu = LBWD ? H >> 2 : H;            // hidden units (H is the length of the exchanged vector)
+  const int Rx = gru ? 3 * H : (LBWD ? Hu : R);   // rows of b' (backward: of e) per sample
   const int row = p.lane_row[(size_t)wg * block + tid];
   const int sample = sample_of_lane<B>(lane);
   const bool owner = row >= 0 && (lane & (L - 1)) < B;
@@ -394,8 +401,15 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * Rx * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
-  const __amdgpu_buffer_rsrc_t abuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(BWD ? p.aux : p.x), 0, p.T * B * H * 4, kBufWord3);
-  const __amdgpu_buffer_rsrc_t dbuf = __builtin_amdgcn_make_buffer_rsrc(BWD && p.dh0 ? p.dh0 : p.h_out, 0, B * H * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t abuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>((BWD || LBWD) ? p.aux : p.x), 0, p.T * B * H * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t dbuf = __builtin_amdgcn_make_buffer_rsrc((BWD || LBWD) && p.dh0 ? p.dh0 : p.h_out, 0, B * Hu * 4, kBufWord3);
+  // LSTM backward: forward cell states [T][B][Hu], c_0 and dL/dc_0 [B][Hu] (an absent one is an empty buffer: loads
+  // give zero, stores are dropped); this lane's element of them, and the distance of two gate blocks in the ring
+  const __amdgpu_buffer_rsrc_t cfbuf = __builtin_amdgcn_make_buffer_rsrc(LBWD ? p.c_out : p.h_out, 0, LBWD ? p.T * B * Hu * 4 : 0, kBufWord3);
+  const __amdgpu_buffer_rsrc_t c0buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(LBWD && p.c0 ? p.c0 : p.x), 0, (LBWD && p.c0) ? B * Hu * 4 : 0, kBufWord3);
+  const __amdgpu_buffer_rsrc_t dc0buf = __builtin_amdgcn_make_buffer_rsrc(LBWD && p.dc0 ? p.dc0 : p.h_out, 0, (LBWD && p.dc0) ? B * Hu * 4 : 0, kBufWord3);
+  const int unit_voff = (LBWD && owner) ? (sample * Hu + row) * 4 : kOutOfRange;
+  const int gate_ring_bytes = Hu * (B < 4 ? B : 4) * 4;
 
   // ---- the copy of h into LDS: 16-byte chunks.  In round c a lane copies the chunk at ring offset src to LDS
   // offset dst.  Without compaction LDS mirrors the ring slot: chunk tid + c * block goes to the same offset, and
@@ -455,6 +469,22 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
   float xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(0) * B * Rx * 4, 0));
   float an = 0.0f;   // backward pass: forward output h_t of the same element
   if constexpr (BWD) an = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, x_voff, time_of(0) * B * H * 4, 0));
+  // LSTM backward: gate values i, f, g, o and the cell states c_t, c_{t-1} of this lane's (unit, sample), fetched one
+  // step ahead like e_t; carry = dc_{t+1} f_{t+1}
+  float gn[4] = {0.0f, 0.0f, 0.0f, 0.0f}, c_cur = 0.0f, c_prev = 0.0f, carry = 0.0f;
+  auto load_saved = [&](int time) {   // c_cur of this time is the c_prev of the step before
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      gn[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, out_voff, (time * B * 4 + q) * Hu * 4, 0));
+    c_prev = __builtin_bit_cast(float, time > 0 ? __builtin_amdgcn_raw_buffer_load_b32(cfbuf, unit_voff, (time - 1) * B * Hu * 4, 0)
+                                                : __builtin_amdgcn_raw_buffer_load_b32(c0buf, unit_voff, 0, 0));
+  };
+  if constexpr (LBWD) {
+    if (p.T > 0) {
+      c_cur = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(cfbuf, unit_voff, time_of(0) * B * Hu * 4, 0));
+      load_saved(time_of(0));
+    }
+  }
   // weight gradient: forward output of this lane's row for every sample (h_0 in the extra step), one accumulator per word
   float side[B], gacc[WGRAD ? NW : 1];
   const int row_voff = row >= 0 ? row * 4 : kOutOfRange;
@@ -642,11 +672,63 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
         hval = fmaf(z, c_state - n, n) + 0.0f;                                   // (1 - z) n + z h_{t-1}
         c_state = hval;
       } else {
-        const float c = sigmoidf_(gates.y) * c_state + sigmoidf_(gates.x) * tanhf_(gates.z);
+        const float gi = sigmoidf_(gates.x), gf = sigmoidf_(gates.y), gg = tanhf_(gates.z), go = sigmoidf_(gates.w);
+        const float c = gf * c_state + gi * gg;
         c_state = c;
-        hval = sigmoidf_(gates.w) * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
+        hval = go * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
         const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c), cbuf, out_voff, out_soff, 0);
+        if (p.gates_out) {   // training: the gate values the backward pass needs, [T][B][4H]
+          const __amdgpu_buffer_rsrc_t gbuf = __builtin_amdgcn_make_buffer_rsrc(p.gates_out, 0, p.T * B * H * 16, kBufWord3);
+          const int gate_voff = cell_unit >= 0 ? ((lane % B) * 4 * H + cell_unit) * 4 : kOutOfRange;
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, gi), gbuf, gate_voff, out_soff * 4, 0);
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, gf), gbuf, gate_voff, out_soff * 4 + H * 4, 0);
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, gg), gbuf, gate_voff, out_soff * 4 + H * 8, 0);
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, go), gbuf, gate_voff, out_soff * 4 + H * 12, 0);
+        }
+      }
+    } else if constexpr (LBWD) {
+      float dp[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      hval = red + 0.0f;               // the extra step: U^T dp_1 = dL/dh_0
+      if (t < p.T) {
+        const float gi = gn[0], gf = gn[1], gg = gn[2], go = gn[3];
+        const float tc = tanhf_(c_cur);
+        const float dc = fmaf(pre * go, fmaf(-tc, tc, 1.0f), carry);   // pre = dh_t
+        dp[0] = dc * gg * gi * (1.0f - gi) + 0.0f;                     // + 0.0f: never the "not written" mark
+        dp[1] = dc * c_prev * gf * (1.0f - gf) + 0.0f;
+        dp[2] = dc * gi * fmaf(-gg, gg, 1.0f) + 0.0f;
+        dp[3] = pre * tc * go * (1.0f - go) + 0.0f;
+        carry = dc * gf;
+        c_cur = c_prev;
+      }
+      jitter_pause(p.jitter, wave_id, g, 3);
+      if (solo) {
+        if (ring_voff != kOutOfRange) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff + q * gate_ring_bytes) = dp[q];
+        }
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, dp[q]), ring, ring_voff, slot_byte + q * gate_ring_bytes, kAuxCoherent);
+        if (p.sync == SPRNN_SYNC_TAGGED) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte + q * gate_ring_bytes, kAuxCoherent);
+        }
+      }
+      if (t < p.T) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, dp[q]), hbuf, out_voff, out_soff + q * Hu * 4, 0);
+        if (t == p.T - 1) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, carry), dc0buf, unit_voff, 0, 0);   // dL/dc_0 = dc_1 f_1
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, unit_voff, 0, 0);
+      }
+      if (t + 1 < p.T) {
+        xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(t + 1) * B * Rx * 4, 0));
+        load_saved(time_of(t + 1));
       }
     } else if constexpr (BWD) {
       if (t < p.T) {
@@ -659,6 +741,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
       hval = activate(p.act, pre);
     }
     ts2 = tick<TL>(tl_on);
+    if constexpr (!LBWD) {   // (the LSTM's backward pass has published its four elements above)
     jitter_pause(p.jitter, wave_id, g, 3);
     if (solo) {
       if (ring_voff != kOutOfRange) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = hval;
@@ -678,6 +761,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
     }
     if constexpr (WGRAD) {
       if (t + 1 < steps) load_side(t + 1);
+    }
     }
     ts3 = tick<TL>(tl_on);
 
@@ -797,7 +881,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : 768) void weight_grad_kernel(const
   };
   auto load_delta = [&](float (&d)[B], int t) {
 #pragma unroll
-    for (int b = 0; b < B; ++b) d[b] = row >= 0 ? p.delta[((size_t)t * B + b) * H + row] : 0.0f;
+    for (int b = 0; b < B; ++b) d[b] = row >= 0 ? p.delta[((size_t)t * B + b) * p.rows + row] : 0.0f;
   };
   uint32_t goff0[4], loff0[4];
   chunk_offsets(goff0, loff0, tid);
@@ -935,12 +1019,13 @@ static const void* pick_b(int batch, int nw) {
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline) {
   const int kind = cell == SPRNN_CELL_LSTM ? 1 : (cell == SPRNN_CELL_GRU ? 2 : 0);
   if (timeline) {   // the phase timeline is built for the forward pass of the vanilla and LSTM cells only
-    if (kind == 2 || cell == kCellBackward || cell == kCellBackwardGrad) return nullptr;
+    if (kind == 2 || cell == kCellBackward || cell == kCellBackwardGrad || cell == SPRNN_CELL_LSTM_BACKWARD) return nullptr;
     return kind == 1 ? pick_b<1, true>(batch, template_words) : pick_b<0, true>(batch, template_words);
   }
   if (kind == 2) return pick_b<2, false>(batch, template_words);
   if (cell == kCellBackward) return pick_b<3, false>(batch, template_words);
   if (cell == kCellBackwardGrad) return pick_b<4, false>(batch, template_words);
+  if (cell == SPRNN_CELL_LSTM_BACKWARD) return pick_b<5, false>(batch, template_words);
   return kind == 1 ? pick_b<1, false>(batch, template_words) : pick_b<0, false>(batch, template_words);
 }
 

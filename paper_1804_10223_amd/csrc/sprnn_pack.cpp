@@ -14,19 +14,23 @@ static inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 // (the GRU leaves the fourth one empty).
 static int visible_gates(int cell) { return cell == SPRNN_CELL_LSTM ? 4 : (cell == SPRNN_CELL_GRU ? 3 : 1); }
 static bool gated(int cell) { return cell == SPRNN_CELL_LSTM || cell == SPRNN_CELL_GRU; }
+// Columns of the matrix = length of the vector the workgroups exchange.  The backward pass of the LSTM holds the
+// transposed matrix: one row per hidden unit over the 4H gate gradients.
+static int exchange_cols(int cell, int hidden) { return cell == SPRNN_CELL_LSTM_BACKWARD ? 4 * hidden : hidden; }
 
 int validate_csr(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
                  const uint16_t* val_bits) {
   if (hidden < 1) return SPRNN_ERR_INVALID;
   if (hidden > 65535) return SPRNN_ERR_UNSUPPORTED;
+  if (cell == SPRNN_CELL_LSTM_BACKWARD && hidden > 16383) return SPRNN_ERR_UNSUPPORTED;   // 16-bit column indices
   if (!(batch == 1 || batch == 2 || batch == 4 || batch == 8)) return SPRNN_ERR_UNSUPPORTED;
-  if (cell < SPRNN_ACT_RELU || cell > SPRNN_CELL_GRU) return SPRNN_ERR_INVALID;
+  if (cell < SPRNN_ACT_RELU || cell > SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_INVALID;
   if (!row_ptr) return SPRNN_ERR_INVALID;
-  const int rows = hidden * visible_gates(cell);
+  const int rows = hidden * visible_gates(cell), cols = exchange_cols(cell, hidden);
   if (row_ptr[0] != 0) return SPRNN_ERR_INVALID;
   for (int r = 0; r < rows; ++r) {
     if (row_ptr[r + 1] < row_ptr[r]) return SPRNN_ERR_INVALID;
-    if (row_ptr[r + 1] - row_ptr[r] > hidden) return SPRNN_ERR_INVALID;
+    if (row_ptr[r + 1] - row_ptr[r] > cols) return SPRNN_ERR_INVALID;
   }
   const int64_t nnz = row_ptr[rows];
   if (nnz > 0 && (!col_idx || !val_bits)) return SPRNN_ERR_INVALID;
@@ -34,7 +38,7 @@ int validate_csr(int hidden, int batch, int cell, const int32_t* row_ptr, const 
     int32_t prev = -1;
     for (int32_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {
       const int32_t c = col_idx[k];
-      if (c <= prev || c >= hidden) return SPRNN_ERR_INVALID;  // in range, strictly increasing, no duplicates
+      if (c <= prev || c >= cols) return SPRNN_ERR_INVALID;  // in range, strictly increasing, no duplicates
       prev = c;
       if ((val_bits[k] & 0x7C00u) == 0x7C00u) return SPRNN_ERR_INVALID;  // inf / NaN weight
     }
@@ -101,17 +105,23 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   if ((int64_t)grid * waves < wt) return SPRNN_ERR_CAPACITY;
 
   m->hidden = hidden; m->rows = hidden * visible_gates(cell); m->batch = batch; m->cell = cell;
-  // Wavefronts beyond the ones that own rows only help with copying h into LDS (more loads in flight).
+  m->cols = exchange_cols(cell, hidden);
+  m->col_stride = 4 * std::min(batch, 4);
+  const int64_t plane = (int64_t)m->cols * m->col_stride;         // batch 8 keeps two planes of 4 samples
+  const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
+  // Wavefronts beyond the ones that own rows only help with copying h into LDS (more loads in flight).  Where the
+  // row owners alone would need more than four rounds of 16-byte loads for it, the workgroup is filled up to eight
+  // wavefronts (measured on the LSTM shapes: 2.51 -> 2.37 us per step forward, 4.4 -> 3.5 backward; more than eight
+  // lose again to the workgroup barriers).
   int total = waves;
   if (opt && opt->fill_waves > 0) {
     if (opt->fill_waves > wave_cap) return SPRNN_ERR_INVALID;
     total = std::max(waves, opt->fill_waves);
+  } else if ((!opt || opt->waves == 0) && grid > 1 && waves < 8 && wave_cap >= 8 && hb / 16 > (int64_t)waves * kWave * 4) {
+    total = 8;
   }
   m->grid = grid; m->row_waves = waves; m->waves = total; m->block = total * kWave; m->lanes_per_row = L;
   m->template_words = tw;
-  m->col_stride = 4 * std::min(batch, 4);
-  const int64_t plane = (int64_t)hidden * m->col_stride;          // batch 8 keeps two planes of 4 samples
-  const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
   m->stage_bytes = lstm ? total * (kWave / (4 * L)) * batch * 16 : 0;   // [wave][unit slot][sample][4 gates] floats
   if (hb * kRingSlots > ((int64_t)1 << 30)) return SPRNN_ERR_CAPACITY;
   m->h_bytes = (int)hb;       // the LDS footprint of h and the index scaling are settled by pack() (column compaction)
@@ -266,6 +276,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   const int upw = lstm ? gpw / 4 : gpw;           // units per wavefront
   const int gpu_ = lstm ? 4 : 1;                  // row groups per unit
   const int units = hidden;
+  const int cols = m.cols;
   auto unit_row = [&](int u, int g) { return lstm ? g * hidden + u : u; };
   auto unit_cost = [&](int u) {
     int c = 0;
@@ -306,7 +317,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   // less than half of it; otherwise LDS mirrors the ring slot.
   const int cpc = batch >= 4 ? 1 : 4 / batch;                 // columns per 16-byte chunk
   const int planes = batch == 8 ? 2 : 1;
-  const int chunks_per_plane = ceil_div(hidden, cpc);
+  const int chunks_per_plane = ceil_div(cols, cpc);
   // Flow control: the exchange ring is only safe because a workgroup cannot start step t before it has seen
   // something of step t-1 from EVERY workgroup (that is what keeps all of them within one step of each other and
   // lets a producer re-arm a slot two steps ahead).  Copying all of h gives that for free; a compacted copy must
@@ -354,7 +365,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   } else {
     m.fill_rows = 0;
     m.lds_bytes = copies * m.h_bytes;
-    lds_plane = (int64_t)hidden * m.col_stride;
+    lds_plane = (int64_t)cols * m.col_stride;
   }
   m.index_shift = 0;
   if (lds_plane > 65536) { while ((1 << m.index_shift) < m.col_stride) ++m.index_shift; }
@@ -377,7 +388,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
       const size_t n = ch.size();
       P.wg_plane[wg] = (int32_t)(n * 16);
       for (size_t e = 0; e < n * planes; ++e)
-        P.fill_src[(size_t)wg * m.fill_rows * m.block + e] = (uint32_t)((e / n) * ((size_t)hidden * 16) + (size_t)ch[e % n] * 16);
+        P.fill_src[(size_t)wg * m.fill_rows * m.block + e] = (uint32_t)((e / n) * ((size_t)cols * 16) + (size_t)ch[e % n] * 16);
     }
   }
 
@@ -401,13 +412,13 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   int64_t padded = 0;
   std::vector<RowGroup> rg;
   int pos_wg = -1;
-  std::vector<int> wg_cols(m.grid, hidden);   // LDS column positions a workgroup may address
+  std::vector<int> wg_cols(m.grid, cols);     // LDS column positions a workgroup may address
   for (int gw = 0; gw < total_waves; ++gw) {
     const int wg = gw / m.waves, wave = gw % m.waves;
     if (compact && wg != pos_wg) {
       pos_wg = wg;
       for (size_t i = 0; i < wg_chunks[wg].size(); ++i) chunk_pos[wg_chunks[wg][i]] = (int32_t)i;
-      wg_cols[wg] = std::min<int64_t>((int64_t)wg_chunks[wg].size() * cpc, hidden);
+      wg_cols[wg] = std::min<int64_t>((int64_t)wg_chunks[wg].size() * cpc, cols);
     }
     const int ncols = wg_cols[wg];
     int trip = 0;

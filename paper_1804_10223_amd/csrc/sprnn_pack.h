@@ -26,6 +26,7 @@ constexpr int kNumTemplateWords = 6;
 
 struct Mapping {
   int hidden = 0, rows = 0, batch = 0, cell = 0;
+  int cols = 0;              // columns of the matrix = length of the exchanged vector (4 * hidden for the LSTM's backward pass, else hidden)
   int grid = 0, waves = 0, row_waves = 0, block = 0, lanes_per_row = 0;   // waves = all, row_waves = those owning rows
   int sync = SPRNN_SYNC_TAGGED, bank_aware = 1, balance = 2, poll_delay = 0, spin_limit = 0, timeline = 0;
   int plain_launch = 0;      // 1: ordinary kernel launch instead of a cooperative one

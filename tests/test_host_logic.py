@@ -202,6 +202,41 @@ def test_auto_mapping_of_the_five_configs():
         assert info["words_per_lane_max"] <= info["template_words"]
 
 
+@pytest.mark.parametrize("H,B,dens,rownnz,opts", [
+    (48, 4, 0.3, "fixed", {}),
+    (40, 8, 0.25, "poisson", {}),
+    (33, 1, 0.4, "poisson", {"lanes_per_row": 16}),
+    (64, 2, 0.2, "fixed", {"grid": 5}),
+    (1500, 4, 0.004, "poisson", {"compact": 1}),
+])
+def test_packer_takes_the_transposed_lstm_matrix_of_the_backward_pass(H, B, dens, rownnz, opts):
+    w = wl.make_workload("p", "lstm", H, B, 1, dens, seed=4, row_nnz=rownnz)
+    t_row_ptr, t_col, t_val = binding.transpose_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    words, lane_row, lane_words, info = binding.pack_host(H, B, "lstm_backward", t_row_ptr, t_col, t_val, **opts)
+    assert info["rows"] == H and info["hidden"] == H and info["nnz"] == w.nnz
+    if not info["compact"]:
+        # H rows whose columns run over the 4H gate rows: LDS and the ring slot hold 4H columns
+        assert info["lds_bytes"] % (4 * H * 4 * B) == 0 and info["ring_bytes"] >= 4 * (4 * H * 4 * B)
+        got = _unpack(words, lane_row, lane_words, info, H, B)
+        for r in range(H):
+            cols = t_col[t_row_ptr[r]:t_row_ptr[r + 1]]
+            bits = t_val[t_row_ptr[r]:t_row_ptr[r + 1]]
+            want = sorted((int(c), int(b)) for c, b in zip(cols, bits) if (int(b) & 0x7FFF) != 0)
+            assert got.get(r, []) == want, r
+    assert int(lane_words.sum()) == w.nnz
+    served = lane_row[lane_row >= 0]
+    assert sorted(set(served.tolist())) == list(range(H))
+    # a column index of 4H or more is refused, and so is a layer whose 4H columns do not fit 16-bit indices
+    bad = t_col.copy()
+    bad[-1] = 4 * H
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(H, B, "lstm_backward", t_row_ptr, bad, t_val)
+    assert e.value.code == binding.SPRNN_ERR_INVALID
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(16384, B, "lstm_backward", np.zeros(16385, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16))
+    assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
+
+
 def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
     lib = binding.load_library()
     none = ctypes.c_void_p()
@@ -211,6 +246,8 @@ def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
     assert lib.sprnn_project(none, 1, 8, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_forward_gru(none, 1, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_backward(none, 1, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_forward_lstm_train(none, 1, None, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_backward_lstm(none, 1, None, None, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_destroy(none) == binding.SPRNN_OK
 
 
