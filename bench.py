@@ -150,6 +150,34 @@ def measure_backward(w, steps, warmup, torch, options=None):
             "fused_with_weight_gradient_us_per_timestep": None if fused_ms is None else fused_ms * 1e3 / w.steps}
 
 
+def measure_lstm_training(steps, warmup, torch):
+    """One training step of the LSTM layer of cfg5, all three launches: forward keeping the gate values, backward pass
+    through time on the transposed matrix (sprnn_backward_lstm), weight gradient on the forward handle."""
+    from paper_1804_10223_amd import binding, workloads
+    w = workloads.make_config("cfg5")
+    H, B, T = w.hidden, w.batch, w.steps
+    gen = torch.Generator(device="cuda").manual_seed(2)
+    x = torch.from_numpy(w.x).cuda()
+    e = torch.randn((T, B, H), device="cuda", generator=gen)
+    t_rp, t_ci, t_vb = binding.transpose_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    with binding.SparseRNN(H, B, "lstm", w.row_ptr, w.col_idx, w.val_bits) as fwd, \
+            binding.SparseRNN(H, B, "lstm_backward", t_rp, t_ci, t_vb) as bwd:
+        _, per_f = time_forward(lambda: fwd.forward_lstm_train(x), steps, warmup, torch)
+        h, c, g = fwd.forward_lstm_train(x)
+        _, per_b = time_forward(lambda: bwd.backward_lstm(e, g, c), steps, warmup, torch)
+        d, _, _ = bwd.backward_lstm(e, g, c)
+        dU = torch.empty((w.nnz,), dtype=torch.float32, device="cuda")
+        _, per_w = time_forward(lambda: fwd.weight_gradient(d, h, None, dU), steps, warmup, torch)
+        if fwd.check() != 0 or bwd.check() != 0:
+            raise RuntimeError("spin watchdog tripped during the LSTM training benchmark")
+        bi = bwd.info()
+    f_ms, b_ms, w_ms = (float(np.median(v)) for v in (per_f, per_b, per_w))
+    return {"workload": "cfg5: sparse LSTM, hidden %d, batch %d, T %d, density %.0f%%" % (H, B, T, 100 * w.meta["density"]),
+            "forward_keeping_gates_us_per_timestep": f_ms * 1e3 / T, "backward_us_per_timestep": b_ms * 1e3 / T,
+            "weight_gradient_us_per_timestep": w_ms * 1e3 / T, "backward_grid": bi["grid"], "backward_block": bi["block"],
+            "backward_exchange_bytes_per_timestep": 4 * H * B * 4}
+
+
 def roofline_for(w, info, probe_vals):
     """Stated per-timestep bound for one configuration from the measured device constants."""
     gather = 4 * w.batch                                   # fp32 activations of one column, all samples
@@ -264,6 +292,10 @@ def main():
             "both fused: %s us/timestep" % (bwd["us_per_timestep"], bwd["ms_per_launch"], bwd["weight_gradient_us_per_timestep"],
                                            bwd["weight_gradient_ms_per_launch"], bwd["fused_with_weight_gradient_us_per_timestep"]))
 
+    lstm = measure_lstm_training(max(5, args.steps // 2), 2, torch)
+    log("  LSTM training step at cfg5: forward keeping gates %.3f, backward %.3f, weight gradient %.3f us/timestep" % (
+        lstm["forward_keeping_gates_us_per_timestep"], lstm["backward_us_per_timestep"], lstm["weight_gradient_us_per_timestep"]))
+
     table = []
     if args.all_configs:
         for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
@@ -331,6 +363,7 @@ def main():
         "stepwise": {"us_per_timestep": res["stepwise_ms"] * 1e3 / T, "speedup_of_persistent": res["stepwise_ms"] / res["kernel_ms"]},
         "projection": proj,
         "backward": bwd,
+        "lstm_training": lstm,
         "cpu_baseline": cpu,
     }
     if table:

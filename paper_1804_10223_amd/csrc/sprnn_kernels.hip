@@ -239,12 +239,10 @@ constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer t
 
 // The n_w (wavefront-uniform) packed words of a lane (w_off: absolute LDS addresses of their columns): gathers in
 // groups of four so the LDS reads are issued back to back; no early exit, so every register index stays static.
-template <int B, int NW, bool GRAD = false>
+// GS: words per group, 4 or 8 (see the kernel's choice).
+template <int B, int NW, bool GRAD = false, int GS = 4>
 __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w,
                                         int plane_bytes, float* g = nullptr, const float (*side)[B] = nullptr) {
-  // A group is eight words for batch 1 and 4 (eight gathers in flight, half as many waits for the LDS: measured
-  // 2.7 % on the headline shape), four otherwise (batch 8 would spill, batch 2 measured no better).
-  constexpr int GS = ((B == 1 || B == 4) && !GRAD) ? 8 : 4;
 #pragma unroll
   for (int k = 0; k < NW; k += GS) {
     float* gk = GRAD ? g + k : nullptr;
@@ -640,7 +638,11 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
     if constexpr (WGRAD) {
       operate<B, NW, true>(acc, w_off, w_val, n_w, plane_bytes, gacc, &side);
     } else {
-      operate<B, NW>(acc, w_off, w_val, n_w, plane_bytes);
+      // Groups of eight words for batch 4 in the one-row-per-unit layouts (eight gathers in flight, half as many
+      // waits for the LDS: 2.5 % on the headline shape); four otherwise: eight would spill at batch 8, measured no
+      // better at batch 2 and for vanilla cells at batch 1, 15-20 % slower for the gated cells at batch 1, and at
+      // batch 4 a few per cent either way for them depending on the words per lane.
+      operate<B, NW, false, (B == 4 && !LSTM) ? 8 : 4>(acc, w_off, w_val, n_w, plane_bytes);
     }
     ts1 = tick<TL>(tl_on);
 

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,cells,casestudy] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,cells,training,casestudy] [--reps 8]
 
 Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
 closed libraries on other hardware and are not reproduced):
@@ -13,6 +13,8 @@ closed libraries on other hardware and are not reproduced):
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
   constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
   cells      the four cells (ReLU, tanh, LSTM, GRU) on one layer shape: hidden 1024, density 20 %, T 256, batch 4 and 8.
+  training   the launches of one training step (forward, backward pass through time, weight gradient) of a ReLU cell
+             and of the LSTM on the same layer shape.
   casestudy  the layer shapes of Appendix B's two tables (machine translation LSTMs at 4-12.5 % density, speech
              recognition layers at 12 %) with random unstructured patterns, as the paper itself does for the speech
              layers; milliseconds per 256-timestep sequence beside the paper's own figure (another GPU: context).
@@ -121,6 +123,46 @@ def cells(torch, wl, reps):
     print()
 
 
+def training(torch, wl, reps):
+    from . import binding
+    print("## Training step: hidden 1024, density 20 %, T 256 (microseconds per timestep of each launch)\n")
+    print("| cell | batch | forward | backward through time | weight gradient | backward with weight gradient fused in | backward grid x block |")
+    print("|---|---|---|---|---|---|---|")
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    for B in (4, 8):
+        for cell in ("relu", "lstm"):
+            w = wl.make_workload("train", cell, 1024, B, 256, 0.20, seed=0, gain=1.0 if cell == "lstm" else 0.9)
+            H, T = w.hidden, w.steps
+            x = dev(w.x)
+            e = torch.randn((T, B, H), device="cuda")
+            rows = 4 * H if cell == "lstm" else H
+            t_csr = binding.transpose_csr(rows, H, w.row_ptr, w.col_idx, w.val_bits)
+            fused = None
+            with binding.SparseRNN(H, B, cell, w.row_ptr, w.col_idx, w.val_bits) as fwd, \
+                    binding.SparseRNN(H, B, "lstm_backward" if cell == "lstm" else cell, *t_csr) as bwd:
+                if cell == "lstm":
+                    f_us = _time_us_per_step(torch, lambda: fwd.forward_lstm_train(x), T, reps)
+                    h, c, g = fwd.forward_lstm_train(x)
+                    b_us = _time_us_per_step(torch, lambda: bwd.backward_lstm(e, g, c), T, reps)
+                    d = bwd.backward_lstm(e, g, c)[0]
+                else:
+                    h = fwd.forward(x)
+                    f_us = _time_us_per_step(torch, lambda: fwd.forward(x, None, h), T, reps)
+                    b_us = _time_us_per_step(torch, lambda: bwd.backward(e, h), T, reps)
+                    d = bwd.backward(e, h)[0]
+                    try:
+                        fused = _time_us_per_step(torch, lambda: bwd.backward_with_weights(e, h), T, reps)
+                    except binding.SprnnError:
+                        pass
+                w_us = _time_us_per_step(torch, lambda: fwd.weight_gradient(d, h), T, reps)
+                if fwd.check() != 0 or bwd.check() != 0:
+                    raise RuntimeError("spin watchdog tripped")
+                bi = bwd.info()
+            print("| %s | %d | %.2f | %.2f | %.2f | %s | %d x %d |" % (
+                cell, B, f_us, b_us, w_us, "-" if fused is None else "%.2f" % fused, bi["grid"], bi["block"]), flush=True)
+    print()
+
+
 def casestudy(torch, wl, reps):
     print("## Case-study layer shapes (cf. Appendix B, both tables): random unstructured pattern, T 256\n")
     print("| layer | cell | hidden | density | batch | persistent us/step | ms per 256 steps | per-timestep launches ms | paper's sparse persistent ms (V100, its batch) | grid x block | lanes/row |")
@@ -140,7 +182,7 @@ def casestudy(torch, wl, reps):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,cells,casestudy")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
     args = ap.parse_args()
     import torch
@@ -163,6 +205,8 @@ def main():
               (11520, 4, 0.01, 256)])
     if "cells" in what:
         cells(torch, wl, args.reps)
+    if "training" in what:
+        training(torch, wl, args.reps)
     if "casestudy" in what:
         casestudy(torch, wl, args.reps)
     if "batch" in what:
