@@ -168,13 +168,21 @@ def measure_lstm_training(steps, warmup, torch):
         d, _, _ = bwd.backward_lstm(e, g, c)
         dU = torch.empty((w.nnz,), dtype=torch.float32, device="cuda")
         _, per_w = time_forward(lambda: fwd.weight_gradient(d, h, None, dU), steps, warmup, torch)
+        fused_ms = None
+        try:   # backward and weight gradient in one kernel (not built for every mapping)
+            _, per_fused = time_forward(lambda: bwd.backward_lstm_with_weights(e, g, c, h), steps, warmup, torch)
+            fused_ms = float(np.median(per_fused))
+        except binding.SprnnError:
+            pass
         if fwd.check() != 0 or bwd.check() != 0:
             raise RuntimeError("spin watchdog tripped during the LSTM training benchmark")
         bi = bwd.info()
     f_ms, b_ms, w_ms = (float(np.median(v)) for v in (per_f, per_b, per_w))
     return {"workload": "cfg5: sparse LSTM, hidden %d, batch %d, T %d, density %.0f%%" % (H, B, T, 100 * w.meta["density"]),
             "forward_keeping_gates_us_per_timestep": f_ms * 1e3 / T, "backward_us_per_timestep": b_ms * 1e3 / T,
-            "weight_gradient_us_per_timestep": w_ms * 1e3 / T, "backward_grid": bi["grid"], "backward_block": bi["block"],
+            "weight_gradient_us_per_timestep": w_ms * 1e3 / T,
+            "backward_fused_with_weight_gradient_us_per_timestep": None if fused_ms is None else fused_ms * 1e3 / T,
+            "backward_grid": bi["grid"], "backward_block": bi["block"],
             "backward_exchange_bytes_per_timestep": 4 * H * B * 4}
 
 
@@ -293,8 +301,9 @@ def main():
                                            bwd["weight_gradient_ms_per_launch"], bwd["fused_with_weight_gradient_us_per_timestep"]))
 
     lstm = measure_lstm_training(max(5, args.steps // 2), 2, torch)
-    log("  LSTM training step at cfg5: forward keeping gates %.3f, backward %.3f, weight gradient %.3f us/timestep" % (
-        lstm["forward_keeping_gates_us_per_timestep"], lstm["backward_us_per_timestep"], lstm["weight_gradient_us_per_timestep"]))
+    log("  LSTM training step at cfg5: forward keeping gates %.3f, backward %.3f, weight gradient %.3f, both fused %s us/timestep" % (
+        lstm["forward_keeping_gates_us_per_timestep"], lstm["backward_us_per_timestep"], lstm["weight_gradient_us_per_timestep"],
+        lstm["backward_fused_with_weight_gradient_us_per_timestep"]))
 
     table = []
     if args.all_configs:

@@ -233,6 +233,20 @@ int sprnn_backward_lstm(sprnn_handle_t h_transposed, int T, const float* dh_ext,
                         const float* c0, float* d_bprime, float* dh0, float* dc0, void* stream);
 
 /*
+ * sprnn_backward_lstm with the gradient of the recurrent weights fused in, as in sprnn_backward_with_weights: the
+ * column of dp_{t+1} that a lane gathers for a nonzero (j, r) of the transposed matrix is the factor that dL/dU[r][j]
+ * pairs with the forward output h_t[.][j] of the lane's own row.
+ *   h_fwd          device, float32 [T][B][H]: forward outputs h_1..h_T;  h0: [B][H] or NULL (zeros).
+ *   dU_transposed  device, float32 [nnz]: dL/dU in the order of the TRANSPOSED matrix's CSR arrays (entry p belongs to
+ *                  the forward nonzero t_source[p] of sprnn_transpose_csr); overwritten.
+ * Other arguments as sprnn_backward_lstm.  Always runs T + 1 steps.  Not available with column compaction or where
+ * the mapping needs more threads than the instantiation is built for (SPRNN_ERR_UNSUPPORTED: use the two separate calls).
+ */
+int sprnn_backward_lstm_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates,
+                                     const float* c_fwd, const float* c0, const float* h_fwd, const float* h0, float* d_bprime,
+                                     float* dh0, float* dc0, float* dU_transposed, void* stream);
+
+/*
  * Host helper: transpose a CSR matrix (rows x cols) of binary16 values.  t_row_ptr has cols + 1 entries, t_col_idx
  * and t_val_fp16_bits have row_ptr[rows] entries; the columns inside a transposed row come out ascending.
  * t_source (row_ptr[rows] entries, or NULL) receives, for every entry of the transpose, the position of the same

@@ -27,7 +27,7 @@ GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
-           "sprnn_forward_stepwise", "sprnn_backward_lstm",
+           "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights",
            "sprnn_project", "sprnn_backward", "sprnn_backward_with_weights", "sprnn_weight_gradient", "sprnn_transpose_csr",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
@@ -88,6 +88,8 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_forward_lstm_train.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.sprnn_backward_lstm.restype = ci
     lib.sprnn_backward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_backward_lstm_with_weights.restype = ci
+    lib.sprnn_backward_lstm_with_weights.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_gru.restype = ci
     lib.sprnn_forward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_backward.restype = ci
@@ -317,6 +319,28 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_backward_lstm")
         return d_bprime, dh0, dc0
+
+    def backward_lstm_with_weights(self, dh_ext, gates, c_fwd, h_fwd, c0=None, h0=None, want_dh0=True, want_dc0=True):
+        """sprnn_backward_lstm_with_weights on a "lstm_backward" handle:
+        (d_bprime [T, B, 4H], dh0, dc0 [B, H] or None, dU [nnz] in the transposed matrix's CSR order)."""
+        import torch
+        T = int(dh_ext.shape[0])
+        dev = "cuda:%d" % self.device
+        nnz = self.info()["nnz"]
+        d_bprime = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device=dev)
+        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
+        dc0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dc0 else None
+        dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
+        rc = self._lib.sprnn_backward_lstm_with_weights(
+            self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
+            _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"), _dev_ptr(c_fwd, (T, self.batch, self.hidden), "c_fwd"),
+            _dev_ptr(c0, (self.batch, self.hidden), "c0"), _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
+            _dev_ptr(h0, (self.batch, self.hidden), "h0"), _dev_ptr(d_bprime, (T, self.batch, 4 * self.hidden), "d_bprime"),
+            _dev_ptr(dh0, (self.batch, self.hidden), "dh0"), _dev_ptr(dc0, (self.batch, self.hidden), "dc0"),
+            ctypes.c_void_p(dU.data_ptr()), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_backward_lstm_with_weights")
+        return d_bprime, dh0, dc0, dU[:nnz]
 
     def forward_gru(self, x, b_hn=None, h0=None, h_out=None):
         """sprnn_forward_gru: x [T, B, 3H] (blocks r|z|n), b_hn [H] or None -> h_out [T, B, H]."""

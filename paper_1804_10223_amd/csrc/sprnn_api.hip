@@ -107,7 +107,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
                               float* h_out, float* c_out, void* stream, const float* b_hn = nullptr,
                               const float* bwd_h_fwd = nullptr, float* bwd_dh0 = nullptr, bool backward = false,
                               const float* bwd_h0 = nullptr, float* bwd_dU = nullptr, float* gates_out = nullptr,
-                              float* bwd_dc0 = nullptr);
+                              float* bwd_dc0 = nullptr, const float* bwd_side = nullptr);
 static int calibrate_poll_delay(sprnn_handle_s* h);
 
 extern "C" {
@@ -233,6 +233,20 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
             SPRNN_HIP(upload(&h->d_col, col_idx, (size_t)m.nnz)) &&
             SPRNN_HIP(upload(&h->d_val, val_fp16_bits, (size_t)m.nnz));
+  if (ok && m.cell == SPRNN_CELL_LSTM_BACKWARD && !m.compact) {
+    // backward pass of the LSTM with the weight gradient fused in: needs the word -> CSR position map, co-residency of
+    // the same grid with that kernel, and a kernel built for this many threads
+    const void* k = persistent_kernel_for(m.batch, m.template_words, kCellLstmBackwardGrad, false);
+    int per_cu_g = 0;
+    hipFuncAttributes fa;
+    if (k && SPRNN_HIP(hipFuncGetAttributes(&fa, k)) && fa.maxThreadsPerBlock >= m.block &&
+        SPRNN_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds)) &&
+        SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_g, k, m.block, h->launch_lds)) &&
+        m.grid <= per_cu_g * prop.multiProcessorCount) {
+      ok = SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size()));
+      if (ok) h->kernel_bwd_grad = k;
+    }
+  }
   if (ok && (m.cell <= SPRNN_ACT_IDENTITY || m.cell == SPRNN_CELL_LSTM) && !m.compact) {
     // the weight gradient re-uses the forward mapping: one accumulator per packed word, left through this map
     h->kernel_wgrad = weight_grad_kernel_for(m.batch, m.template_words);
@@ -271,7 +285,7 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const float* b_hn, const float* bwd_h_fwd,
                               float* bwd_dh0, bool backward, const float* bwd_h0, float* bwd_dU, float* gates_out,
-                              float* bwd_dc0) {
+                              float* bwd_dc0, const float* bwd_side) {
   if (h->poisoned) return SPRNN_ERR_STATE;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
@@ -299,6 +313,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.dc0 = bwd_dc0;
     a.b_hn = b_hn;
     a.aux = bwd_h_fwd; a.dh0 = bwd_dh0; a.bwd_h0 = bwd_h0; a.word_src = h->d_word_src; a.dU = bwd_dU;
+    a.side_src = bwd_side ? bwd_side : bwd_h_fwd;   // (vanilla cells: g' and the weight gradient both use h_t)
     a.timeline = h->d_timeline;
     a.hidden = m.cols; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
@@ -307,7 +322,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
     const bool plain = m.plain_launch != 0 || m.grid == 1;
     const bool lstm_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD;
-    const void* kernel = (backward && !lstm_bwd) ? (bwd_dU ? h->kernel_bwd_grad : h->kernel_bwd) : h->kernel;
+    const void* kernel = backward ? (bwd_dU ? h->kernel_bwd_grad : (lstm_bwd ? h->kernel : h->kernel_bwd)) : h->kernel;
     hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
                          : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
@@ -403,6 +418,27 @@ int sprnn_backward_lstm(sprnn_handle_t h_transposed, int T, const float* dh_ext,
   // (the kernel only reads the cell states; they travel in the forward pass's output slot of the argument block)
   return forward_persistent(h, T, dh_ext, nullptr, c0, d_bprime, const_cast<float*>(c_fwd), stream, nullptr, gates, dh0, true,
                             nullptr, nullptr, nullptr, dc0);
+}
+
+int sprnn_backward_lstm_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates,
+                                     const float* c_fwd, const float* c0, const float* h_fwd, const float* h0, float* d_bprime,
+                                     float* dh0, float* dc0, float* dU_transposed, void* stream) {
+  sprnn_handle_t h = h_transposed;
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_LSTM_BACKWARD || !h->kernel_bwd_grad || !h->d_word_src) return SPRNN_ERR_UNSUPPORTED;
+  if (!dU_transposed && h->map.nnz > 0) return SPRNN_ERR_INVALID;
+  if (T > 0 && (!dh_ext || !gates || !c_fwd || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
+  if (T == 0) {   // nothing to sum, nothing flows back
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return SPRNN_ERR_HIP;
+    const size_t n = (size_t)h->map.batch * h->map.hidden;
+    for (float* out : {dh0, dc0})
+      if (out && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(out), 0u, n, (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    if (h->map.nnz > 0 && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dU_transposed), 0u, (size_t)h->map.nnz, (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    return SPRNN_OK;
+  }
+  return forward_persistent(h, T, dh_ext, nullptr, c0, d_bprime, const_cast<float*>(c_fwd), stream, nullptr, gates, dh0, true,
+                            h0, dU_transposed, nullptr, dc0, h_fwd);
 }
 
 int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn, const float* h0, float* h_out,

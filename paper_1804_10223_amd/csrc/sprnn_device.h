@@ -17,6 +17,7 @@ constexpr int kCtrlBarrier = 32;                  // grid-barrier mode: ctrl[32]
 constexpr int kCtrlWords = kCtrlBarrier + 16 * 9;
 constexpr int kCellBackward = 100;                // persistent_kernel_for: backward pass of a vanilla cell
 constexpr int kCellBackwardGrad = 101;            // the same with the weight gradient fused in
+constexpr int kCellLstmBackwardGrad = 102;        // backward pass of the LSTM with the weight gradient fused in
 constexpr int kTimelineSlots = 16;                // 64-bit accumulators per workgroup in the phase timeline
 constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after h: abort flags, timeline sums
 
@@ -35,6 +36,7 @@ struct KernelArgs {
   const float* aux;           // backward pass: forward outputs h_t, [T][B][H]; LSTM backward: gate values, [T][B][4H]
   float* dh0;                 // backward pass: dL/dh_0, [B][H], or null
   const float* bwd_h0;        // backward pass with weight gradient: h_0, [B][H], or null (zeros)
+  const float* side_src;      // backward pass with weight gradient: forward outputs h_t, [T][B][H]
   const int32_t* word_src;    // backward pass with weight gradient: packed word -> CSR position (of the handle's matrix)
   float* dU;                  // backward pass with weight gradient: [nnz] sums, in the handle's CSR order
   float* h_out;               // [T][B][H]

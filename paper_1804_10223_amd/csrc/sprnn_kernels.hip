@@ -323,14 +323,16 @@ __device__ __forceinline__ long long tick(bool on) {
 // the 4H gate gradients, so p.hidden (the length of the exchanged vector) is 4 * units and the vanilla layout applies.
 // The owner lane of (unit, sample) turns dh_t = e_t + U^T dp_{t+1} into the unit's four gate gradients with the gate
 // values (p.aux) and cell states (p.c_out, p.c0) of the forward pass, keeps dc_{t+1} f_{t+1} in a register, and
-// publishes four elements of the exchanged vector instead of one; one more step gives dL/dh_0 (p.dh0).
+// publishes four elements of the exchanged vector instead of one; one more step gives dL/dh_0 (p.dh0),
+// 6 = the same with the weight gradient fused in as in 4: the column gathered for a nonzero (j, g H + i) of the transposed
+// matrix is dp_{t+1}[.][g H + i], the factor that dL/dU[g H + i][j] pairs with the forward output h_t[.][j] of the lane's row.
 template <int B, int NW, int CELL, bool TL>
-__global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
+__global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
-  constexpr bool LBWD = CELL == 5;
+  constexpr bool LBWD = CELL == 5 || CELL == 6;
   constexpr bool BWD = CELL == 3 || CELL == 4;
-  constexpr bool WGRAD = CELL == 4;
-  const int steps = BWD ? p.T + ((p.dh0 || WGRAD) ? 1 : 0) : (LBWD ? p.T + (p.dh0 ? 1 : 0) : p.T);   // the last one pairs delta_1 with h_0
+  constexpr bool WGRAD = CELL == 4 || CELL == 6;
+  const int steps = (BWD || LBWD) ? p.T + ((p.dh0 || WGRAD) ? 1 : 0) : p.T;   // the last one pairs delta_1 (dp_1) with h_0
   auto time_of = [&](int s) { return (BWD || LBWD) ? p.T - 1 - s : s; };   // index into x / aux / outputs of step s
   // LDS: [h][abort flags][timeline sums][LSTM hand-over area].  A single workgroup (no exchange) keeps two copies of
   // h and writes h_t straight into the other one; otherwise one copy is enough, because the workgroup barrier
@@ -487,12 +489,14 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
   float side[B], gacc[WGRAD ? NW : 1];
   const int row_voff = row >= 0 ? row * 4 : kOutOfRange;
   const __amdgpu_buffer_rsrc_t h0buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(WGRAD && p.bwd_h0 ? p.bwd_h0 : p.x), 0,
-                                                                         (WGRAD && p.bwd_h0) ? B * H * 4 : 0, kBufWord3);
+                                                                         (WGRAD && p.bwd_h0) ? B * Hu * 4 : 0, kBufWord3);
+  const __amdgpu_buffer_rsrc_t sbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(WGRAD ? p.side_src : p.x), 0,
+                                                                        WGRAD ? p.T * B * Hu * 4 : 0, kBufWord3);
   auto load_side = [&](int s) {   // s: step index; rows of step T come from h_0 (an empty buffer returns zeros)
 #pragma unroll
     for (int b = 0; b < B; ++b)
-      side[b] = __builtin_bit_cast(float, s < p.T ? __builtin_amdgcn_raw_buffer_load_b32(abuf, row_voff, (time_of(s) * B + b) * H * 4, 0)
-                                                  : __builtin_amdgcn_raw_buffer_load_b32(h0buf, row_voff, b * H * 4, 0));
+      side[b] = __builtin_bit_cast(float, s < p.T ? __builtin_amdgcn_raw_buffer_load_b32(sbuf, row_voff, (time_of(s) * B + b) * Hu * 4, 0)
+                                                  : __builtin_amdgcn_raw_buffer_load_b32(h0buf, row_voff, b * Hu * 4, 0));
   };
   if constexpr (WGRAD) {
 #pragma unroll
@@ -725,7 +729,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
         for (int q = 0; q < 4; ++q)
           __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, dp[q]), hbuf, out_voff, out_soff + q * Hu * 4, 0);
         if (t == p.T - 1) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, carry), dc0buf, unit_voff, 0, 0);   // dL/dc_0 = dc_1 f_1
-      } else {
+      } else if (p.dh0) {
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, unit_voff, 0, 0);
       }
       if (t + 1 < p.T) {
@@ -761,9 +765,9 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : (CELL == 4 && NW >= 24 ? 512 : 768
       xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(t + 1) * B * Rx * 4, 0));
       if constexpr (BWD) an = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, x_voff, time_of(t + 1) * B * H * 4, 0));
     }
+    }
     if constexpr (WGRAD) {
       if (t + 1 < steps) load_side(t + 1);
-    }
     }
     ts3 = tick<TL>(tl_on);
 
@@ -1021,13 +1025,14 @@ static const void* pick_b(int batch, int nw) {
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline) {
   const int kind = cell == SPRNN_CELL_LSTM ? 1 : (cell == SPRNN_CELL_GRU ? 2 : 0);
   if (timeline) {   // the phase timeline is built for the forward pass of the vanilla and LSTM cells only
-    if (kind == 2 || cell == kCellBackward || cell == kCellBackwardGrad || cell == SPRNN_CELL_LSTM_BACKWARD) return nullptr;
+    if (kind == 2 || cell == kCellBackward || cell == kCellBackwardGrad || cell == SPRNN_CELL_LSTM_BACKWARD || cell == kCellLstmBackwardGrad) return nullptr;
     return kind == 1 ? pick_b<1, true>(batch, template_words) : pick_b<0, true>(batch, template_words);
   }
   if (kind == 2) return pick_b<2, false>(batch, template_words);
   if (cell == kCellBackward) return pick_b<3, false>(batch, template_words);
   if (cell == kCellBackwardGrad) return pick_b<4, false>(batch, template_words);
   if (cell == SPRNN_CELL_LSTM_BACKWARD) return pick_b<5, false>(batch, template_words);
+  if (cell == kCellLstmBackwardGrad) return pick_b<6, false>(batch, template_words);
   return kind == 1 ? pick_b<1, false>(batch, template_words) : pick_b<0, false>(batch, template_words);
 }
 

@@ -145,6 +145,10 @@ def training(torch, wl, reps):
                     h, c, g = fwd.forward_lstm_train(x)
                     b_us = _time_us_per_step(torch, lambda: bwd.backward_lstm(e, g, c), T, reps)
                     d = bwd.backward_lstm(e, g, c)[0]
+                    try:
+                        fused = _time_us_per_step(torch, lambda: bwd.backward_lstm_with_weights(e, g, c, h), T, reps)
+                    except binding.SprnnError:
+                        pass
                 else:
                     h = fwd.forward(x)
                     f_us = _time_us_per_step(torch, lambda: fwd.forward(x, None, h), T, reps)

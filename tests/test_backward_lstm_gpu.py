@@ -74,6 +74,28 @@ def test_lstm_backward_matches_oracle(H, B, T, dens, rownnz, opts):
     run_backward(w, c0, e, **opts)
 
 
+def test_lstm_backward_single_timestep_and_one_wanted_initial_gradient():
+    H, B, T = 150, 2, 1
+    w, c0, e = _workload(H, B, T, 0.3, "poisson", seed=21)
+    run_backward(w, c0, e)
+    # only one of the two initial-state gradients asked for: the other costs nothing and is not written
+    H, B, T = 210, 4, 7
+    w, c0, e = _workload(H, B, T, 0.2, "fixed", seed=22)
+    h, c, gates = oracle.lstm_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, c0)
+    want_d, want_dh0, want_dc0, _ = oracle.lstm_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, c, h, e, w.h0, c0)
+    t_csr = binding.transpose_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    with binding.SparseRNN(H, B, "lstm_backward", *t_csr) as rnn:
+        d1, dh0, none = rnn.backward_lstm(_dev(e), _dev(gates), _dev(c), _dev(c0), want_dc0=False)
+        d2, none2, dc0 = rnn.backward_lstm(_dev(e), _dev(gates), _dev(c), _dev(c0), want_dh0=False)
+        d3, _, dc0_zero = rnn.backward_lstm(_dev(e), _dev(gates), _dev(c), None)          # c_0 = 0: dp_f of the first step is 0
+        assert rnn.check() == binding.SPRNN_OK
+    assert none is None and none2 is None and np.array_equal(d1.cpu().numpy(), d2.cpu().numpy())
+    _close(dh0.cpu().numpy(), want_dh0, "dh0 alone")
+    _close(dc0.cpu().numpy(), want_dc0, "dc0 alone")
+    assert not d3.cpu().numpy()[0][:, H:2 * H].any()
+    _close(dc0_zero.cpu().numpy(), want_dc0, "dc0 with c0 = 0")      # dc_1 f_1 does not depend on c_0
+
+
 def test_lstm_backward_zero_weights_closed_form():
     # nothing flows through h: dp_o = e tanh(c) o (1 - o) exactly as binary32 products, dL/dh_0 = 0
     H, B, T = 200, 4, 5
@@ -168,3 +190,69 @@ def test_lstm_backward_wrong_handles_are_refused():
         # T = 0: nothing flows back
         d, dh0, dc0 = bwd.backward_lstm(z[:0], z4[:0], z[:0])
         assert d.shape[0] == 0 and not dh0.cpu().numpy().any() and not dc0.cpu().numpy().any()
+
+
+@pytest.mark.parametrize("H,B,T,dens,rownnz,opts", [
+    (96, 4, 9, 0.3, "fixed", {}),
+    (257, 1, 7, 0.2, "poisson", {}),
+    (130, 8, 5, 0.1, "poisson", {}),
+    (333, 2, 6, 0.15, "poisson", {"balance": 1}),
+    (32, 4, 8, 0.4, "fixed", {"grid": 1}),
+    (320, 4, 10, 0.3, "fixed", {"sync": "barrier"}),
+    (576, 4, 32, 0.1, "fixed", {"jitter": 7}),
+])
+def test_lstm_backward_with_weights_matches_oracle(H, B, T, dens, rownnz, opts):
+    w, c0, e = _workload(H, B, T, dens, rownnz, seed=H + T + 1)
+    h, c, gates = oracle.lstm_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, c0, threads=8)
+    want_d, want_dh0, want_dc0, want_dU = oracle.lstm_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, c, h, e, w.h0, c0)
+    t_rp, t_ci, t_vb, t_src = binding.transpose_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits, with_source=True)
+    with binding.SparseRNN(H, B, "lstm_backward", t_rp, t_ci, t_vb, **opts) as rnn:
+        info = rnn.info()
+        print("case fused lstm_backward H", H, "B", B, "T", T, opts,
+              {k: info[k] for k in ("grid", "block", "lanes_per_row", "template_words")}, flush=True)
+        try:
+            d, dh0, dc0, dU_t = rnn.backward_lstm_with_weights(_dev(e), _dev(gates), _dev(c), _dev(h), _dev(c0), _dev(w.h0))
+        except binding.SprnnError as err:
+            if err.code == binding.SPRNN_ERR_UNSUPPORTED:
+                pytest.skip("mapping too wide for the fused instantiation: %s" % err)
+            raise
+        assert rnn.check() == binding.SPRNN_OK
+        # the plain backward pass on the same handle gives the same gradients, bit for bit
+        d2, dh02, dc02 = rnn.backward_lstm(_dev(e), _dev(gates), _dev(c), _dev(c0))
+        assert np.array_equal(d2.cpu().numpy(), d.cpu().numpy()) and np.array_equal(dh02.cpu().numpy(), dh0.cpu().numpy())
+        assert np.array_equal(dc02.cpu().numpy(), dc0.cpu().numpy())
+        # without the initial-state gradients the extra step still runs (it pairs dp_1 with h_0)
+        d3, n1, n2, dU_t3 = rnn.backward_lstm_with_weights(_dev(e), _dev(gates), _dev(c), _dev(h), _dev(c0), _dev(w.h0),
+                                                          want_dh0=False, want_dc0=False)
+        assert n1 is None and n2 is None and np.array_equal(dU_t3.cpu().numpy(), dU_t.cpu().numpy())
+        assert np.array_equal(d3.cpu().numpy(), d.cpu().numpy())
+        assert rnn.check() == binding.SPRNN_OK
+    d, dU_t = d.cpu().numpy(), dU_t.cpu().numpy()
+    for t in range(T):
+        _close(d[t], want_d[t], "d_bprime[%d]" % t)
+    _close(dh0.cpu().numpy(), want_dh0, "dh0")
+    _close(dc0.cpu().numpy(), want_dc0, "dc0")
+    dU = np.empty_like(dU_t)
+    dU[t_src] = dU_t                       # back to the forward matrix's CSR order
+    _close(dU, want_dU, "dU")
+
+
+def test_lstm_backward_with_weights_at_the_lstm_config_shape():
+    w = wl.make_config("cfg5", steps=20)
+    H, B, T = w.hidden, w.batch, w.steps
+    rng = np.random.default_rng(6)
+    c0 = (rng.standard_normal((B, H)) * 0.5).astype(np.float32)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    h, c, gates = oracle.lstm_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, None, c0, threads=8)
+    want_d, want_dh0, _, want_dU = oracle.lstm_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, c, h, e, None, c0)
+    t_rp, t_ci, t_vb, t_src = binding.transpose_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits, with_source=True)
+    with binding.SparseRNN(H, B, "lstm_backward", t_rp, t_ci, t_vb) as rnn:
+        d, dh0, _, dU_t = rnn.backward_lstm_with_weights(_dev(e), _dev(gates), _dev(c), _dev(h), _dev(c0), None)
+        assert rnn.check() == binding.SPRNN_OK
+    d, dU_t = d.cpu().numpy(), dU_t.cpu().numpy()
+    for t in range(T):
+        _close(d[t], want_d[t], "d_bprime[%d]" % t)
+    _close(dh0.cpu().numpy(), want_dh0, "dh0")
+    dU = np.empty_like(dU_t)
+    dU[t_src] = dU_t
+    _close(dU, want_dU, "dU")
