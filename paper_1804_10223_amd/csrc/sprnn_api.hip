@@ -103,11 +103,20 @@ int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 6 : 0; }
 
 }  // namespace
 
+// What a launch of the persistent kernel takes beyond the forward pass's five buffers.
+struct LaunchExtras {
+  const float* b_hn = nullptr;       // GRU: recurrent bias of the candidate
+  float* gates_out = nullptr;        // LSTM forward: gate values kept for the backward pass
+  bool backward = false;             // time runs from T down to 1; one launch only
+  const float* saved = nullptr;      // backward: forward outputs h_t (vanilla cells) or gate values (LSTM)
+  float* dh0 = nullptr;              // backward: dL/dh_0 (adds one step)
+  float* dc0 = nullptr;              // LSTM backward: dL/dc_0
+  const float* wgrad_h_fwd = nullptr;   // backward with the weight gradient fused in: forward outputs h_t ...
+  const float* wgrad_h0 = nullptr;      // ... h_0 ...
+  float* dU = nullptr;                  // ... and the sums (selects the fused kernel; adds one step)
+};
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
-                              float* h_out, float* c_out, void* stream, const float* b_hn = nullptr,
-                              const float* bwd_h_fwd = nullptr, float* bwd_dh0 = nullptr, bool backward = false,
-                              const float* bwd_h0 = nullptr, float* bwd_dU = nullptr, float* gates_out = nullptr,
-                              float* bwd_dc0 = nullptr, const float* bwd_side = nullptr);
+                              float* h_out, float* c_out, void* stream, const LaunchExtras& ex = LaunchExtras());
 static int calibrate_poll_delay(sprnn_handle_s* h);
 
 extern "C" {
@@ -283,9 +292,7 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 }
 
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
-                              float* h_out, float* c_out, void* stream, const float* b_hn, const float* bwd_h_fwd,
-                              float* bwd_dh0, bool backward, const float* bwd_h0, float* bwd_dU, float* gates_out,
-                              float* bwd_dc0, const float* bwd_side) {
+                              float* h_out, float* c_out, void* stream, const LaunchExtras& ex) {
   if (h->poisoned) return SPRNN_ERR_STATE;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
@@ -296,7 +303,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
   const size_t step_bytes = (size_t)m.batch * std::max(m.rows, m.cols) * 4;
   const int t_max = (int)std::max<size_t>(1, ((size_t)1 << 30) / step_bytes);
   const size_t hb = (size_t)m.batch * m.hidden;
-  if (backward && T > t_max) return SPRNN_ERR_UNSUPPORTED;   // time runs backwards: one launch only
+  if (ex.backward && T > t_max) return SPRNN_ERR_UNSUPPORTED;   // time runs backwards: one launch only
   for (int t0 = 0; t0 < T; t0 += t_max) {
     const int tn = std::min(t_max, T - t0);
     KernelArgs a;
@@ -309,11 +316,11 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.c0 = t0 ? (c_out ? c_out + (size_t)(t0 - 1) * hb : nullptr) : c0;
     a.h_out = h_out + (size_t)t0 * hb;
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
-    a.gates_out = gates_out ? gates_out + (size_t)t0 * m.batch * m.rows : nullptr;
-    a.dc0 = bwd_dc0;
-    a.b_hn = b_hn;
-    a.aux = bwd_h_fwd; a.dh0 = bwd_dh0; a.bwd_h0 = bwd_h0; a.word_src = h->d_word_src; a.dU = bwd_dU;
-    a.side_src = bwd_side ? bwd_side : bwd_h_fwd;   // (vanilla cells: g' and the weight gradient both use h_t)
+    a.gates_out = ex.gates_out ? ex.gates_out + (size_t)t0 * m.batch * m.rows : nullptr;
+    a.dc0 = ex.dc0;
+    a.b_hn = ex.b_hn;
+    a.aux = ex.saved; a.dh0 = ex.dh0; a.bwd_h0 = ex.wgrad_h0; a.word_src = h->d_word_src; a.dU = ex.dU;
+    a.side_src = ex.wgrad_h_fwd;
     a.timeline = h->d_timeline;
     a.hidden = m.cols; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
@@ -322,11 +329,11 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
     const bool plain = m.plain_launch != 0 || m.grid == 1;
     const bool lstm_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD;
-    const void* kernel = backward ? (bwd_dU ? h->kernel_bwd_grad : (lstm_bwd ? h->kernel : h->kernel_bwd)) : h->kernel;
+    const void* kernel = ex.backward ? (ex.dU ? h->kernel_bwd_grad : (lstm_bwd ? h->kernel : h->kernel_bwd)) : h->kernel;
     hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
                          : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
-    const int ran = tn + ((backward && (bwd_dh0 || bwd_dU)) ? 1 : 0);   // the backward pass adds the step that pairs delta_1 with h_0
+    const int ran = tn + ((ex.backward && (ex.dh0 || ex.dU)) ? 1 : 0);   // the backward pass adds the step that pairs delta_1 with h_0
     h->step_base += (uint32_t)ran;
     h->barrier_base += (uint32_t)(ran - 1);   // one barrier before every step but the first
   }
@@ -358,9 +365,9 @@ static int calibrate_poll_delay(sprnn_handle_s* h) {
       for (int rep = 0; rep < 4 && rc == SPRNN_OK; ++rep) {   // the first run of a setting warms up, the fastest of three counts
         if (!SPRNN_HIP(hipEventRecord(e0, nullptr))) { ok = false; break; }
         // (the LSTM's backward pass reads e_t, the gate values and the cell states: all from the zero buffer)
-        rc = m.cell == SPRNN_CELL_LSTM_BACKWARD
-                 ? forward_persistent(h, T, d_x, nullptr, nullptr, d_h, d_x, nullptr, nullptr, d_x, nullptr, true)
-                 : forward_persistent(h, T, d_x, nullptr, nullptr, d_h, d_c, nullptr);
+        LaunchExtras ex;
+        if (m.cell == SPRNN_CELL_LSTM_BACKWARD) { ex.backward = true; ex.saved = d_x; }
+        rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, m.cell == SPRNN_CELL_LSTM_BACKWARD ? d_x : d_c, nullptr, ex);
         if (rc != SPRNN_OK) break;
         if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
         if (rep > 0 && (best_of == 0.0f || ms < best_of)) best_of = ms;
@@ -398,7 +405,9 @@ int sprnn_forward_lstm_train(sprnn_handle_t h, int T, const float* x, const floa
   if (!h || T < 0) return SPRNN_ERR_INVALID;
   if (h->map.cell != SPRNN_CELL_LSTM) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!x || !h_out || !c_out || !gates_out)) return SPRNN_ERR_INVALID;
-  return forward_persistent(h, T, x, h0, c0, h_out, c_out, stream, nullptr, nullptr, nullptr, false, nullptr, nullptr, gates_out);
+  LaunchExtras ex;
+  ex.gates_out = gates_out;
+  return forward_persistent(h, T, x, h0, c0, h_out, c_out, stream, ex);
 }
 
 int sprnn_backward_lstm(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates, const float* c_fwd,
@@ -416,8 +425,9 @@ int sprnn_backward_lstm(sprnn_handle_t h_transposed, int T, const float* dh_ext,
     return SPRNN_OK;
   }
   // (the kernel only reads the cell states; they travel in the forward pass's output slot of the argument block)
-  return forward_persistent(h, T, dh_ext, nullptr, c0, d_bprime, const_cast<float*>(c_fwd), stream, nullptr, gates, dh0, true,
-                            nullptr, nullptr, nullptr, dc0);
+  LaunchExtras ex;
+  ex.backward = true; ex.saved = gates; ex.dh0 = dh0; ex.dc0 = dc0;
+  return forward_persistent(h, T, dh_ext, nullptr, c0, d_bprime, const_cast<float*>(c_fwd), stream, ex);
 }
 
 int sprnn_backward_lstm_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates,
@@ -437,8 +447,10 @@ int sprnn_backward_lstm_with_weights(sprnn_handle_t h_transposed, int T, const f
     if (h->map.nnz > 0 && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dU_transposed), 0u, (size_t)h->map.nnz, (hipStream_t)stream))) return SPRNN_ERR_HIP;
     return SPRNN_OK;
   }
-  return forward_persistent(h, T, dh_ext, nullptr, c0, d_bprime, const_cast<float*>(c_fwd), stream, nullptr, gates, dh0, true,
-                            h0, dU_transposed, nullptr, dc0, h_fwd);
+  LaunchExtras ex;
+  ex.backward = true; ex.saved = gates; ex.dh0 = dh0; ex.dc0 = dc0;
+  ex.wgrad_h_fwd = h_fwd; ex.wgrad_h0 = h0; ex.dU = dU_transposed;
+  return forward_persistent(h, T, dh_ext, nullptr, c0, d_bprime, const_cast<float*>(c_fwd), stream, ex);
 }
 
 int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn, const float* h0, float* h_out,
@@ -446,7 +458,9 @@ int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn
   if (!h || T < 0) return SPRNN_ERR_INVALID;
   if (h->map.cell != SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
-  return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream, b_hn);
+  LaunchExtras ex;
+  ex.b_hn = b_hn;
+  return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream, ex);
 }
 
 int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, float* d_bprime,
@@ -455,7 +469,9 @@ int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, cons
   if (!h || T < 0) return SPRNN_ERR_INVALID;
   if (h->map.cell > SPRNN_ACT_IDENTITY || !h->kernel_bwd) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!dh_ext || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
-  return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, nullptr, h_fwd, dh0, true);
+  LaunchExtras ex;
+  ex.backward = true; ex.saved = h_fwd; ex.dh0 = dh0;
+  return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, ex);
 }
 
 int sprnn_backward_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, const float* h0,
@@ -471,7 +487,10 @@ int sprnn_backward_with_weights(sprnn_handle_t h_transposed, int T, const float*
     if (!guard.ok) return SPRNN_ERR_HIP;
     return SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dU_transposed), 0u, (size_t)h->map.nnz, (hipStream_t)stream)) ? SPRNN_OK : SPRNN_ERR_HIP;
   }
-  return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, nullptr, h_fwd, dh0, true, h0, dU_transposed);
+  LaunchExtras ex;
+  ex.backward = true; ex.saved = h_fwd; ex.dh0 = dh0;   // (vanilla cells: g' and the weight gradient both use h_t)
+  ex.wgrad_h_fwd = h_fwd; ex.wgrad_h0 = h0; ex.dU = dU_transposed;
+  return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, ex);
 }
 
 int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const float* h_fwd, const float* h0, float* dU,
