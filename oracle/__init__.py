@@ -62,6 +62,10 @@ def _load():
                                                  f64p, f64p, f64p, f64p]
         lib.oracle_gru_forward.restype = ci
         lib.oracle_gru_forward.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, ci]
+        lib.oracle_gru_forward_saved.restype = ci
+        lib.oracle_gru_forward_saved.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f32p, ci]
+        lib.oracle_gru_backward_f64.restype = ci
+        lib.oracle_gru_backward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f32p, f64p, f64p, f64p, f64p, f64p]
         lib.oracle_gru_forward_f64.restype = ci
         lib.oracle_gru_forward_f64.argtypes = [ci, ci, ci, i32p, i32p, u16p, f32p, f32p, f32p, f64p, ci]
         lib.oracle_rnn_backward_f64.restype = ci
@@ -181,6 +185,58 @@ def gru_forward(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, b_hn=Non
     if rc != 0:
         raise RuntimeError("oracle_gru_forward failed")
     return out
+
+
+def gru_forward_saved(hidden: int, batch: int, row_ptr, col_idx, val_bits, x, b_hn=None, h0=None, threads: int = 1):
+    """The binary32 GRU forward pass, also returning what a backward pass needs:
+    (h [T, B, H], gates [T, B, 4H] with blocks r | z | n | q, q = U_n h_{t-1} + b_hn)."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, 3 * hidden, hidden)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    T = x.shape[0]
+    if x.shape != (T, batch, 3 * hidden):
+        raise ValueError("x must be [T, B, 3H]")
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+    b_hn, h0 = f32(b_hn), f32(h0)
+    h = np.empty((T, batch, hidden), dtype=np.float32)
+    gates = np.empty((T, batch, 4 * hidden), dtype=np.float32)
+    f = ctypes.c_float
+    rc = lib.oracle_gru_forward_saved(hidden, batch, T, _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+                                      _ptr(val_bits, ctypes.c_uint16), _ptr(x, f), _ptr(b_hn, f), _ptr(h0, f),
+                                      _ptr(h, f), _ptr(gates, f), int(threads))
+    if rc != 0:
+        raise RuntimeError("oracle_gru_forward_saved failed")
+    return h, gates
+
+
+def gru_backward(hidden: int, batch: int, row_ptr, col_idx, val_bits, gates, h_fwd, dh_ext, h0=None):
+    """Backward pass through time of the GRU cell for L = sum_t <dh_ext[t], h_t>, binary64, from the quantities kept
+    by the forward pass.  Returns (d_bprime [T, B, 3H] = dp_r | dp_z | da, d_rec [T, B, 3H] = dp_r | dp_z | dq,
+    dh0 [B, H], dU [nnz] in CSR order of the [3H][H] matrix, db_hn [H])."""
+    lib = _load()
+    row_ptr, col_idx, val_bits = _csr(row_ptr, col_idx, val_bits, 3 * hidden, hidden)
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+    gates, h_fwd, dh_ext, h0 = map(f32, (gates, h_fwd, dh_ext, h0))
+    T = h_fwd.shape[0]
+    if gates.shape != (T, batch, 4 * hidden):
+        raise ValueError("gates must be [T, B, 4H]")
+    if h_fwd.shape != (T, batch, hidden) or dh_ext.shape != (T, batch, hidden):
+        raise ValueError("h_fwd and dh_ext must be [T, B, H]")
+    if h0 is not None and h0.shape != (batch, hidden):
+        raise ValueError("h0 must be [B, H]")
+    nnz = int(row_ptr[-1])
+    d_bprime = np.empty((T, batch, 3 * hidden), dtype=np.float64)
+    d_rec = np.empty((T, batch, 3 * hidden), dtype=np.float64)
+    dh0 = np.empty((batch, hidden), dtype=np.float64)
+    dU = np.empty(max(nnz, 1), dtype=np.float64)
+    db_hn = np.empty(hidden, dtype=np.float64)
+    f, d = ctypes.c_float, ctypes.c_double
+    rc = lib.oracle_gru_backward_f64(hidden, batch, T, _ptr(row_ptr, ctypes.c_int32), _ptr(col_idx, ctypes.c_int32),
+                                     _ptr(val_bits, ctypes.c_uint16), _ptr(gates, f), _ptr(h_fwd, f), _ptr(h0, f),
+                                     _ptr(dh_ext, f), _ptr(d_bprime, d), _ptr(d_rec, d), _ptr(dh0, d), _ptr(dU, d), _ptr(db_hn, d))
+    if rc != 0:
+        raise RuntimeError("oracle_gru_backward_f64 failed")
+    return d_bprime, d_rec, dh0, dU[:nnz], db_hn
 
 
 def rnn_backward(hidden: int, batch: int, act: str, row_ptr, col_idx, val_bits, h_fwd, dh_ext, h0=None):

@@ -46,6 +46,15 @@
  *         dp_g = dc_t i_t (1 - g_t^2),     dp_o = dh_t tanh(c_t) o_t (1 - o_t)
  *     dp_t = dL/db'_t; dL/dh_0 = U^T dp_1; dL/dc_0 = dc_1 f_1; dL/dU[r][k] = sum_t sum_b dp_t[b][r] h_{t-1}[b][k].
  *
+ *   - Backward pass through time of the GRU cell above, for L = sum_t <e_t, h_t>: the chain rule on its equations, with
+ *     r, z, n and q = U_n h_{t-1} + b_hn kept from the forward pass.  Going from t = T down to 1, with everything
+ *     beyond T zero and v_t = (dp_r | dp_z | dq) the gradient of the three recurrent sums:
+ *         dh_t = e_t + dh_{t+1} z_{t+1} + U^T v_{t+1}            (U is [3H][H])
+ *         da = dh_t (1 - z_t) (1 - n_t^2)        (gradient of the candidate's pre-activation = dL/dx_n)
+ *         dp_r = da q_t r_t (1 - r_t),   dp_z = dh_t (h_{t-1} - n_t) z_t (1 - z_t),   dq = da r_t
+ *     dL/db'_t = (dp_r | dp_z | da); dL/dh_0 = dh_1 z_1 + U^T v_1; dL/dU[r][k] = sum_t sum_b v_t[b][r] h_{t-1}[b][k];
+ *     dL/db_hn[j] = sum_t sum_b dq_t[b][j].
+ *
  * Precision: weights are IEEE binary16 bit patterns decoded exactly to binary32
  * (Section 6 names 16-bit weights as the compressed format); activations, the
  * products and the running sums are binary32 (one rounding per multiply and per
@@ -301,9 +310,9 @@ int oracle_input_projection_f64(int R, int I, int M, const uint16_t* w_bits, con
  * GRU cell.  U is [3H][H] in CSR with row blocks r | z | n; x is [T][B][3H] in the same block order;
  * b_hn is [H] or NULL (zeros); h0 is [B][H] or NULL (zeros); h_out is [T][B][H].
  */
-int oracle_gru_forward(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
-                       const uint16_t* val_bits, const float* x, const float* b_hn, const float* h0,
-                       float* h_out, int threads) {
+static int gru_forward_f32(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                           const uint16_t* val_bits, const float* x, const float* b_hn, const float* h0,
+                           float* h_out, float* gates_out, int threads) {
   if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !x || !h_out) return -1;
   float* zeros = (float*)calloc((size_t)B * H, sizeof(float));
   if (!zeros) return -1;
@@ -332,12 +341,31 @@ int oracle_gru_forward(int H, int B, int T, const int32_t* row_ptr, const int32_
         const float n = tanhf(x_t[(size_t)b * 3 * H + 2 * H + j] + rq);
         const float keep = z * h_prev[(size_t)b * H + j];
         const float fresh = (1.0f - z) * n;
+        if (gates_out) {
+          float* o = gates_out + ((size_t)t * B + b) * 4 * H + j;
+          o[0] = r; o[(size_t)H] = z; o[(size_t)2 * H] = n; o[(size_t)3 * H] = q;
+        }
         h_cur[(size_t)b * H + j] = fresh + keep;
       }
     }
   }
   free(zeros);
   return 0;
+}
+
+int oracle_gru_forward(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                       const uint16_t* val_bits, const float* x, const float* b_hn, const float* h0,
+                       float* h_out, int threads) {
+  return gru_forward_f32(H, B, T, row_ptr, col_idx, val_bits, x, b_hn, h0, h_out, NULL, threads);
+}
+
+/* The same forward pass, also keeping what a backward pass needs: gates_out is [T][B][4H], blocks r | z | n | q with
+ * q = U_n h_{t-1} + b_hn (the factor the reset gate multiplies). */
+int oracle_gru_forward_saved(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                             const uint16_t* val_bits, const float* x, const float* b_hn, const float* h0,
+                             float* h_out, float* gates_out, int threads) {
+  if (!gates_out) return -1;
+  return gru_forward_f32(H, B, T, row_ptr, col_idx, val_bits, x, b_hn, h0, h_out, gates_out, threads);
 }
 
 /* Binary64 twin of oracle_gru_forward. */
@@ -471,5 +499,60 @@ int oracle_lstm_backward_f64(int H, int B, int T, const int32_t* row_ptr, const 
   if (dc0) for (size_t j = 0; j < (size_t)B * H; ++j) dc0[j] = carry[j];
   free(back);
   free(carry);
+  return 0;
+}
+
+/*
+ * Backward pass through time of the GRU cell, binary64.  U is [3H][H] in CSR (the forward matrix, row blocks
+ * r | z | n).  Kept from the forward pass: gates [T][B][4H] (blocks r | z | n | q), h_fwd [T][B][H]; h0 [B][H] or NULL
+ * (zeros).  dh_ext is [T][B][H] (e_t).  Outputs: d_bprime [T][B][3H] (dp_r | dp_z | da), d_rec [T][B][3H]
+ * (dp_r | dp_z | dq: what the recurrent product and the weight gradient use), dh0 [B][H] (may be NULL), dU [nnz] in CSR
+ * order (may be NULL), db_hn [H] (may be NULL).
+ */
+int oracle_gru_backward_f64(int H, int B, int T, const int32_t* row_ptr, const int32_t* col_idx,
+                            const uint16_t* val_bits, const float* gates, const float* h_fwd, const float* h0,
+                            const float* dh_ext, double* d_bprime, double* d_rec, double* dh0, double* dU, double* db_hn) {
+  if (H <= 0 || B <= 0 || T < 0 || !row_ptr || !d_bprime || !d_rec || (T > 0 && (!gates || !h_fwd || !dh_ext))) return -1;
+  const int64_t nnz = row_ptr[3 * H];
+  double* back = (double*)calloc((size_t)B * H, sizeof(double));   /* U^T v_{t+1} */
+  double* direct = (double*)calloc((size_t)B * H, sizeof(double)); /* dh_{t+1} z_{t+1} */
+  if (!back || !direct) { free(back); free(direct); return -1; }
+  if (dU) for (int64_t k = 0; k < nnz; ++k) dU[k] = 0.0;
+  if (db_hn) for (int j = 0; j < H; ++j) db_hn[j] = 0.0;
+  for (int t = T - 1; t >= 0; --t) {
+    const float* h_prev = (t == 0) ? h0 : h_fwd + (size_t)(t - 1) * B * H;
+    double* dx = d_bprime + (size_t)t * B * 3 * H;
+    double* v = d_rec + (size_t)t * B * 3 * H;
+    for (int b = 0; b < B; ++b) {
+      const float* g = gates + ((size_t)t * B + b) * 4 * H;
+      for (int j = 0; j < H; ++j) {
+        const double r = g[j], z = g[H + j], n = g[2 * H + j], q = g[3 * H + j];
+        const double hp = h_prev ? (double)h_prev[(size_t)b * H + j] : 0.0;
+        const double dh = (double)dh_ext[((size_t)t * B + b) * H + j] + direct[(size_t)b * H + j] + back[(size_t)b * H + j];
+        const double da = dh * (1.0 - z) * (1.0 - n * n);
+        const double dpr = da * q * r * (1.0 - r);
+        const double dpz = dh * (hp - n) * z * (1.0 - z);
+        const double dq = da * r;
+        dx[(size_t)b * 3 * H + j] = dpr;  dx[(size_t)b * 3 * H + H + j] = dpz;  dx[(size_t)b * 3 * H + 2 * H + j] = da;
+        v[(size_t)b * 3 * H + j] = dpr;   v[(size_t)b * 3 * H + H + j] = dpz;   v[(size_t)b * 3 * H + 2 * H + j] = dq;
+        direct[(size_t)b * H + j] = dh * z;
+        if (db_hn) db_hn[j] += dq;
+      }
+    }
+    for (size_t j = 0; j < (size_t)B * H; ++j) back[j] = 0.0;
+    for (int row = 0; row < 3 * H; ++row) {
+      for (int32_t k = row_ptr[row]; k < row_ptr[row + 1]; ++k) {
+        const double w = (double)oracle_half_bits_to_float(val_bits[k]);
+        const int j = col_idx[k];
+        for (int b = 0; b < B; ++b) {
+          back[(size_t)b * H + j] += w * v[(size_t)b * 3 * H + row];
+          if (dU) dU[k] += v[(size_t)b * 3 * H + row] * (h_prev ? (double)h_prev[(size_t)b * H + j] : 0.0);
+        }
+      }
+    }
+  }
+  if (dh0) for (size_t j = 0; j < (size_t)B * H; ++j) dh0[j] = back[j] + direct[j];
+  free(back);
+  free(direct);
   return 0;
 }

@@ -12,8 +12,8 @@ bias (tests/golden/eq1_hand_example.json), numpy's float64 matrix product, ident
 forms (bit exact), exact rational brute force, and checks that a transposed operand or a dropped bias fails.
 The GRU cell (three gates; the paper gives no equations) is pinned against torch.nn.GRUCell, which fixes the gate
 order r, z, n and the place of the candidate's recurrent bias, and by closed forms and invariants.
-The backward passes (vanilla cell, LSTM) are pinned against torch autograd of the same dense cell in float64
-(torch.nn.LSTMCell for the LSTM), single-step closed forms, zero weights, and finite differences of the forward oracle.
+The backward passes (vanilla cell, LSTM, GRU) are pinned against torch autograd of the same dense cell in float64
+(torch.nn.LSTMCell and torch.nn.GRUCell for the gated cells), single-step closed forms, zero weights, and finite differences of the forward oracle.
 """
 import json
 import os
@@ -699,3 +699,127 @@ def test_lstm_backward_agrees_with_finite_differences_of_the_forward_oracle():
         args_m = (w.x, am, c0) if which == 0 else (w.x, w.h0, am)
         fd = (loss(*args_p) - loss(*args_m)) / (float(ap[0, 3]) - float(am[0, 3]))
         assert abs(fd - grad[0, 3]) < 2e-3 * max(1.0, abs(fd))
+
+
+# ----------------------------------------------------------------------------- backward pass through time, GRU
+def test_gru_saved_forward_is_the_forward_and_its_gates_reproduce_the_outputs():
+    H, B, T = 19, 2, 5
+    w = wl.make_workload("g", "gru", H, B, T, 0.4, seed=12, h0_std=0.5)
+    h = oracle.gru_forward(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.b_hn, w.h0)
+    hs, gates = oracle.gru_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.b_hn, w.h0)
+    assert np.array_equal(h, hs)
+    r, z, n, q = (gates[:, :, k * H:(k + 1) * H].astype(np.float64) for k in range(4))
+    h_prev = np.concatenate([w.h0[None], h[:-1]]).astype(np.float64)
+    np.testing.assert_allclose((1 - z) * n + z * h_prev, h, rtol=0, atol=1e-6)
+    np.testing.assert_allclose(np.tanh(w.x[:, :, 2 * H:] + r * q), n, rtol=0, atol=1e-6)
+    U = _dense_from_csr(3 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    np.testing.assert_allclose(h_prev @ U[2 * H:].T + w.b_hn, q, rtol=0, atol=1e-5)
+
+
+def test_gru_backward_matches_torch_autograd_of_grucell():
+    rng = np.random.default_rng(51)
+    H, B, T = 17, 3, 6
+    w = wl.make_workload("g", "gru", H, B, T, 0.4, seed=13, row_nnz="poisson", h0_std=0.5)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    h, gates = oracle.gru_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.b_hn, w.h0)
+    d_b, d_rec, dh0, dU, db_hn = oracle.gru_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, h, e, w.h0)
+    U = _dense_from_csr(3 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    cell = torch.nn.GRUCell(3 * H, H, bias=True).double()                     # gate order r, z, n
+    with torch.no_grad():
+        cell.weight_hh.copy_(torch.from_numpy(U))
+        cell.weight_ih.copy_(torch.eye(3 * H, dtype=torch.float64))
+        cell.bias_ih.zero_()
+        cell.bias_hh.zero_()
+        cell.bias_hh[2 * H:].copy_(torch.from_numpy(w.b_hn.astype(np.float64)))
+    cell.weight_ih.requires_grad_(False)
+    xt = torch.tensor(w.x.astype(np.float64), requires_grad=True)
+    h0t = torch.tensor(w.h0.astype(np.float64), requires_grad=True)
+    ht, loss = h0t, 0.0
+    for t in range(T):
+        ht = cell(xt[t], ht)
+        loss = loss + (torch.tensor(e[t].astype(np.float64)) * ht).sum()
+    loss.backward()
+    tol = lambda a: 5e-6 * np.abs(a).max()
+    np.testing.assert_allclose(d_b, xt.grad.numpy(), rtol=0, atol=tol(xt.grad.numpy()))
+    np.testing.assert_allclose(dh0, h0t.grad.numpy(), rtol=0, atol=tol(h0t.grad.numpy()))
+    dense = cell.weight_hh.grad.numpy()
+    want = np.array([dense[i, w.col_idx[k]] for i in range(3 * H) for k in range(w.row_ptr[i], w.row_ptr[i + 1])])
+    np.testing.assert_allclose(dU, want, rtol=0, atol=tol(want))
+    want_b = cell.bias_hh.grad.numpy()
+    np.testing.assert_allclose(db_hn, want_b[2 * H:], rtol=0, atol=tol(want_b))
+    # the r and z blocks of the two outputs agree and the bias gradients of b_hr, b_hz are their sums; the candidate
+    # blocks differ by the reset gate
+    assert np.array_equal(d_b[:, :, :2 * H], d_rec[:, :, :2 * H])
+    np.testing.assert_allclose(d_rec[:, :, :2 * H].sum(axis=(0, 1)), want_b[:2 * H], rtol=0, atol=tol(want_b))
+    np.testing.assert_allclose(d_rec[:, :, 2 * H:], d_b[:, :, 2 * H:] * gates[:, :, :H], rtol=0, atol=1e-15)
+    # two swapped gate blocks are far away
+    sw = gates.copy()
+    sw[:, :, 0:H], sw[:, :, H:2 * H] = gates[:, :, H:2 * H], gates[:, :, 0:H]
+    bad = oracle.gru_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, sw, h, e, w.h0)[0]
+    assert np.abs(bad - d_b).max() > 1e-2
+
+
+def test_gru_backward_single_step_closed_form_and_zero_weights():
+    rng = np.random.default_rng(52)
+    H, B = 6, 2
+    w = wl.make_workload("g", "gru", H, B, 1, 0.5, seed=14, h0_std=1.0)
+    e = rng.standard_normal((1, B, H)).astype(np.float32)
+    h, gates = oracle.gru_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.b_hn, w.h0)
+    d_b, d_rec, dh0, dU, db_hn = oracle.gru_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, h, e, w.h0)
+    r, z, n, q = (gates[0][:, k * H:(k + 1) * H].astype(np.float64) for k in range(4))
+    da = e[0] * (1 - z) * (1 - n * n)
+    want = np.concatenate([da * q * r * (1 - r), e[0] * (w.h0 - n) * z * (1 - z), da], axis=1)
+    np.testing.assert_allclose(d_b[0], want, rtol=0, atol=1e-15)
+    v = np.concatenate([want[:, :2 * H], da * r], axis=1)
+    np.testing.assert_allclose(d_rec[0], v, rtol=0, atol=1e-15)
+    U = _dense_from_csr(3 * H, H, w.row_ptr, w.col_idx, w.val_bits)
+    np.testing.assert_allclose(dh0, e[0] * z + v @ U, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(db_hn, (da * r).sum(axis=0), rtol=0, atol=1e-14)
+    k = 0
+    for row in range(3 * H):
+        for kk in range(w.row_ptr[row], w.row_ptr[row + 1]):
+            np.testing.assert_allclose(dU[k], (v[:, row] * w.h0[:, w.col_idx[kk]].astype(np.float64)).sum(), rtol=0, atol=1e-14)
+            k += 1
+    # zero weights: only the update gate's direct path carries gradient through time
+    zero = np.zeros(3 * H + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16)
+    T = 3
+    x = rng.standard_normal((T, B, 3 * H)).astype(np.float32)
+    ee = rng.standard_normal((T, B, H)).astype(np.float32)
+    hz, gz = oracle.gru_forward_saved(H, B, *zero, x, None, w.h0)
+    d_b, d_rec, dh0, dU, db_hn = oracle.gru_backward(H, B, *zero, gz, hz, ee, w.h0)
+    zz = gz[:, :, H:2 * H].astype(np.float64)
+    run = np.zeros((B, H))
+    for t in range(T - 1, -1, -1):
+        dh = ee[t] + run
+        np.testing.assert_allclose(d_b[t][:, 2 * H:], dh * (1 - zz[t]) * (1 - gz[t][:, 2 * H:3 * H].astype(np.float64) ** 2), rtol=0, atol=1e-15)
+        run = dh * zz[t]
+    np.testing.assert_allclose(dh0, run, rtol=0, atol=1e-15)
+    assert dU.size == 0 and not d_b[:, :, :H].any()      # q = 0: the reset gate gets no gradient
+
+
+def test_gru_backward_agrees_with_finite_differences_of_the_forward_oracle():
+    rng = np.random.default_rng(53)
+    H, B, T = 5, 1, 4
+    w = wl.make_workload("g", "gru", H, B, T, 0.6, seed=15, h0_std=0.5)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    fwd = lambda x, h0, b: oracle.gru_forward(H, B, w.row_ptr, w.col_idx, w.val_bits, x, b, h0, f64=True)
+    h, gates = oracle.gru_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.b_hn, w.h0)
+    d_b, _, dh0, _, db_hn = oracle.gru_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, h, e, w.h0)
+    loss = lambda x, h0, b: float((fwd(x, h0, b) * e).sum())
+    eps = 2.0 ** -7
+    for (t, r) in ((0, 1), (1, H + 2), (3, 2 * H + 4)):
+        xp, xm = w.x.copy(), w.x.copy()
+        xp[t, 0, r] += eps
+        xm[t, 0, r] -= eps
+        fd = (loss(xp, w.h0, w.b_hn) - loss(xm, w.h0, w.b_hn)) / (float(xp[t, 0, r]) - float(xm[t, 0, r]))
+        assert abs(fd - d_b[t, 0, r]) < 2e-3 * max(1.0, abs(fd))
+    hp, hm = w.h0.copy(), w.h0.copy()
+    hp[0, 3] += eps
+    hm[0, 3] -= eps
+    fd = (loss(w.x, hp, w.b_hn) - loss(w.x, hm, w.b_hn)) / (float(hp[0, 3]) - float(hm[0, 3]))
+    assert abs(fd - dh0[0, 3]) < 2e-3 * max(1.0, abs(fd))
+    bp, bm = w.b_hn.copy(), w.b_hn.copy()
+    bp[2] += eps
+    bm[2] -= eps
+    fd = (loss(w.x, w.h0, bp) - loss(w.x, w.h0, bm)) / (float(bp[2]) - float(bm[2]))
+    assert abs(fd - db_hn[2]) < 2e-3 * max(1.0, abs(fd))
