@@ -35,9 +35,10 @@ enum {
 /* Cell / activation g of Eq. 2.  SPRNN_CELL_LSTM selects the four-gate cell of Appendix B, SPRNN_CELL_GRU a
  * three-gate gated recurrent unit (Section 2 names it as a cell the approach extends to).
  * SPRNN_CELL_LSTM_BACKWARD makes a handle for the backward pass of an LSTM layer (sprnn_backward_lstm): it holds the
- * TRANSPOSE of the LSTM's [4H][H] matrix, H rows whose columns index the 4H gate rows. */
+ * TRANSPOSE of the LSTM's [4H][H] matrix, H rows whose columns index the 4H gate rows; SPRNN_CELL_GRU_BACKWARD the
+ * same for the GRU (sprnn_backward_gru, the transpose of its [3H][H] matrix). */
 enum { SPRNN_ACT_RELU = 0, SPRNN_ACT_TANH = 1, SPRNN_ACT_IDENTITY = 2, SPRNN_CELL_LSTM = 3, SPRNN_CELL_GRU = 4,
-       SPRNN_CELL_LSTM_BACKWARD = 5 };
+       SPRNN_CELL_LSTM_BACKWARD = 5, SPRNN_CELL_GRU_BACKWARD = 6 };
 
 /* Cross-workgroup hand-off of h_t (Section 4.2 discusses a global barrier versus Lamport timestamps). */
 enum {
@@ -105,10 +106,11 @@ typedef struct sprnn_info_s {
  *   hidden      H, 1..65535.
  *   batch       B in {1,2,4,8}: sequences advanced together (wide loads of Section 4.1).
  *   activation  SPRNN_ACT_* (R = H rows), SPRNN_CELL_LSTM (R = 4H rows, row blocks i|f|g|o),
- *               SPRNN_CELL_GRU (R = 3H rows, row blocks r|z|n) or SPRNN_CELL_LSTM_BACKWARD (R = H rows with
- *               columns below 4H, H <= 16383: the transpose of an LSTM's matrix).
+ *               SPRNN_CELL_GRU (R = 3H rows, row blocks r|z|n), SPRNN_CELL_LSTM_BACKWARD (R = H rows with
+ *               columns below 4H, H <= 16383: the transpose of an LSTM's matrix) or SPRNN_CELL_GRU_BACKWARD (R = H rows
+ *               with columns below 3H, H <= 21845).
  *   row_ptr     host, R+1 entries, row_ptr[0] = 0, non-decreasing.
- *   col_idx     host, nnz = row_ptr[R] entries, 0 <= col < H (< 4H for SPRNN_CELL_LSTM_BACKWARD), strictly
+ *   col_idx     host, nnz = row_ptr[R] entries, 0 <= col < H (< 4H, < 3H for the two backward cells), strictly
  *               increasing inside a row.
  *   val_fp16_bits host, nnz IEEE binary16 bit patterns (finite).  The library rounds nothing.
  *   device_id   HIP device ordinal.
@@ -198,10 +200,11 @@ int sprnn_backward_with_weights(sprnn_handle_t h_transposed, int T, const float*
 /*
  * Gradient of the recurrent weights on their sparsity pattern, the non-recurrent half of the backward pass:
  *   dU[k] = sum_t sum_b delta_t[b][row(k)] * h_{t-1}[b][col(k)]      for every stored nonzero k, in CSR order.
- * Runs on the FORWARD handle (vanilla cells and the LSTM, where h fits in LDS whole: no column compaction) and
+ * Runs on the FORWARD handle (vanilla cells, the LSTM and the GRU, where h fits in LDS whole: no column compaction) and
  * re-uses its mapping: every lane keeps one accumulator per nonzero it holds in the forward pass, in registers, for
  * all T steps.
- *   d_bprime  device, float32 [T][B][R]: delta_t from sprnn_backward (R = H), dp_t from sprnn_backward_lstm (R = 4H).
+ *   d_bprime  device, float32 [T][B][R]: delta_t from sprnn_backward (R = H), dp_t from sprnn_backward_lstm (R = 4H),
+ *             d_recurrent from sprnn_backward_gru (R = 3H).
  *   h_fwd     device, float32 [T][B][H]: forward outputs h_1..h_T;  h0: device [B][H] or NULL (zeros).
  *   dU        device, float32 [nnz]: overwritten (T = 0 writes zeros).
  * Sums are binary32, in time order.  Only enqueues work; allocates nothing.
@@ -231,6 +234,37 @@ int sprnn_weight_gradient(sprnn_handle_t h, int T, const float* d_bprime, const 
  */
 int sprnn_backward_lstm(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates, const float* c_fwd,
                         const float* c0, float* d_bprime, float* dh0, float* dc0, void* stream);
+
+/*
+ * sprnn_forward_gru that also keeps what the backward pass needs: gates_out, device float32 [T][B][4H], receives the
+ * blocks r | z | n | q with q = U_n h_{t-1} + b_hn, the factor the reset gate multiplies.
+ */
+int sprnn_forward_gru_train(sprnn_handle_t h, int T, const float* x, const float* b_hn, const float* h0, float* h_out,
+                            float* gates_out, void* stream);
+
+/*
+ * Backward pass through time of the GRU cell of sprnn_forward_gru, weights resident on chip.  With e_t = dL/dh_t from
+ * outside the layer, going from t = T down to 1 with everything beyond T zero:
+ *   dh_t = e_t + dh_{t+1} z_{t+1} + U^T v_{t+1},      da = dh_t (1 - z_t) (1 - n_t^2),
+ *   dp_r = da q_t r_t (1 - r_t),   dp_z = dh_t (h_{t-1} - n_t) z_t (1 - z_t),   dq = da r_t,   v_t = (dp_r | dp_z | dq);
+ *   dL/db'_t = (dp_r | dp_z | da),   dL/dh_0 = dh_1 z_1 + U^T v_1.
+ * The handle holds the TRANSPOSE of the forward matrix (sprnn_transpose_csr with rows = 3H, cols = H; created with
+ * SPRNN_CELL_GRU_BACKWARD and the forward pass's batch): one row per hidden unit, whose lanes gather from the exchanged
+ * vector v_{t+1} of length 3H; the lane that owns (unit, sample) keeps dh_{t+1} z_{t+1} in a register and publishes
+ * the unit's three elements.
+ *
+ *   dh_ext       device, float32 [T][B][H]: e_t.
+ *   gates        device, float32 [T][B][4H]: r | z | n | q kept by sprnn_forward_gru_train.
+ *   h_fwd        device, float32 [T][B][H]: forward outputs h_1..h_T;  h0: [B][H] or NULL (zeros).
+ *   d_bprime     device, float32 [T][B][3H]: dL/db'_t.
+ *   d_recurrent  device, float32 [T][B][3H], or NULL if not wanted: v_t, the gradient of the three recurrent sums.  It
+ *                is what sprnn_weight_gradient on the forward GRU handle takes as d_bprime (dL/dU[r][k] = sum_t sum_b
+ *                v_t[b][r] h_{t-1}[b][k]), and the sum of its third block over t and b is dL/db_hn.
+ *   dh0          device, float32 [B][H], or NULL if not wanted.
+ * One launch; T is limited to 2^30 / (16 B H) timesteps per call.  Same stream, state and error rules as sprnn_forward.
+ */
+int sprnn_backward_gru(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates, const float* h_fwd,
+                       const float* h0, float* d_bprime, float* d_recurrent, float* dh0, void* stream);
 
 /*
  * sprnn_backward_lstm with the gradient of the recurrent weights fused in, as in sprnn_backward_with_weights: the

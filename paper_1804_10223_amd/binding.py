@@ -22,12 +22,13 @@ SPRNN_ERR_HIP = -3
 SPRNN_ERR_UNSUPPORTED = -4
 SPRNN_ERR_STATE = -5
 
-CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4, "lstm_backward": 5}
+CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4, "lstm_backward": 5, "gru_backward": 6}
 GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
-           "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights",
+           "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights", "sprnn_forward_gru_train",
+           "sprnn_backward_gru",
            "sprnn_project", "sprnn_backward", "sprnn_backward_with_weights", "sprnn_weight_gradient", "sprnn_transpose_csr",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
@@ -90,6 +91,10 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_backward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.sprnn_backward_lstm_with_weights.restype = ci
     lib.sprnn_backward_lstm_with_weights.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_forward_gru_train.restype = ci
+    lib.sprnn_forward_gru_train.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_backward_gru.restype = ci
+    lib.sprnn_backward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_gru.restype = ci
     lib.sprnn_forward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_backward.restype = ci
@@ -354,6 +359,40 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_forward_gru")
         return h_out
+
+    def forward_gru_train(self, x, b_hn=None, h0=None):
+        """sprnn_forward_gru_train: x [T, B, 3H] -> (h_out [T, B, H], gates [T, B, 4H] = r | z | n | q)."""
+        import torch
+        T = int(x.shape[0])
+        h_out = self._alloc(T)
+        gates = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device="cuda:%d" % self.device)
+        rc = self._lib.sprnn_forward_gru_train(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
+                                               _dev_ptr(b_hn, (self.hidden,), "b_hn"), _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                               _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"),
+                                               _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates_out"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_forward_gru_train")
+        return h_out, gates
+
+    def backward_gru(self, dh_ext, gates, h_fwd, h0=None, want_dh0=True, want_recurrent=True):
+        """sprnn_backward_gru on a "gru_backward" handle (the TRANSPOSED [H][3H] matrix):
+        (d_bprime [T, B, 3H], d_recurrent [T, B, 3H] or None, dh0 [B, H] or None)."""
+        import torch
+        T = int(dh_ext.shape[0])
+        dev = "cuda:%d" % self.device
+        d_bprime = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
+        d_rec = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev) if want_recurrent else None
+        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
+        rc = self._lib.sprnn_backward_gru(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
+                                          _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"),
+                                          _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
+                                          _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                          _dev_ptr(d_bprime, (T, self.batch, 3 * self.hidden), "d_bprime"),
+                                          _dev_ptr(d_rec, (T, self.batch, 3 * self.hidden), "d_recurrent"),
+                                          _dev_ptr(dh0, (self.batch, self.hidden), "dh0"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_backward_gru")
+        return d_bprime, d_rec, dh0
 
     def backward(self, dh_ext, h_fwd, d_bprime=None, want_dh0=True):
         """sprnn_backward on a handle that holds the TRANSPOSED matrix: (delta [T, B, H], dh0 [B, H] or None)."""

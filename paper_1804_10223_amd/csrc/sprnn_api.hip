@@ -256,7 +256,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
       if (ok) h->kernel_bwd_grad = k;
     }
   }
-  if (ok && (m.cell <= SPRNN_ACT_IDENTITY || m.cell == SPRNN_CELL_LSTM) && !m.compact) {
+  if (ok && (m.cell <= SPRNN_ACT_IDENTITY || m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU) && !m.compact) {
     // the weight gradient re-uses the forward mapping: one accumulator per packed word, left through this map
     h->kernel_wgrad = weight_grad_kernel_for(m.batch, m.template_words);
     ok = h->kernel_wgrad != nullptr && SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size())) &&
@@ -328,7 +328,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     void* args[] = {&a};
     // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
     const bool plain = m.plain_launch != 0 || m.grid == 1;
-    const bool lstm_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD;
+    const bool lstm_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;   // the handle's own kernel is the backward pass
     const void* kernel = ex.backward ? (ex.dU ? h->kernel_bwd_grad : (lstm_bwd ? h->kernel : h->kernel_bwd)) : h->kernel;
     hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
                          : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
@@ -347,7 +347,8 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
 static int calibrate_poll_delay(sprnn_handle_s* h) {
   const Mapping& m = h->map;
   const int T = 48;
-  const size_t xn = (size_t)T * m.batch * std::max(m.rows, m.cols), hn = (size_t)T * m.batch * m.cols;
+  // (the gated cells' backward passes read [T][B][4H] kept gate values from the zero buffer)
+  const size_t xn = (size_t)T * m.batch * std::max(std::max(m.rows, m.cols), 4 * m.hidden), hn = (size_t)T * m.batch * m.cols;
   float *d_x = nullptr, *d_h = nullptr, *d_c = nullptr;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   const bool lstm = m.cell == SPRNN_CELL_LSTM;
@@ -366,8 +367,9 @@ static int calibrate_poll_delay(sprnn_handle_s* h) {
         if (!SPRNN_HIP(hipEventRecord(e0, nullptr))) { ok = false; break; }
         // (the LSTM's backward pass reads e_t, the gate values and the cell states: all from the zero buffer)
         LaunchExtras ex;
-        if (m.cell == SPRNN_CELL_LSTM_BACKWARD) { ex.backward = true; ex.saved = d_x; }
-        rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, m.cell == SPRNN_CELL_LSTM_BACKWARD ? d_x : d_c, nullptr, ex);
+        const bool gated_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;
+        if (gated_bwd) { ex.backward = true; ex.saved = d_x; }
+        rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, gated_bwd ? d_x : d_c, nullptr, ex);
         if (rc != SPRNN_OK) break;
         if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
         if (rep > 0 && (best_of == 0.0f || ms < best_of)) best_of = ms;
@@ -463,6 +465,35 @@ int sprnn_forward_gru(sprnn_handle_t h, int T, const float* x, const float* b_hn
   return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream, ex);
 }
 
+int sprnn_forward_gru_train(sprnn_handle_t h, int T, const float* x, const float* b_hn, const float* h0, float* h_out,
+                            float* gates_out, void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_GRU) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!x || !h_out || !gates_out)) return SPRNN_ERR_INVALID;
+  LaunchExtras ex;
+  ex.b_hn = b_hn; ex.gates_out = gates_out;
+  return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream, ex);
+}
+
+int sprnn_backward_gru(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates, const float* h_fwd,
+                       const float* h0, float* d_bprime, float* d_recurrent, float* dh0, void* stream) {
+  sprnn_handle_t h = h_transposed;
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_GRU_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!dh_ext || !gates || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
+  if (T == 0) {   // nothing flows back
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return SPRNN_ERR_HIP;
+    if (dh0 && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dh0), 0u, (size_t)h->map.batch * h->map.hidden, (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    return SPRNN_OK;
+  }
+  // (h_{t-1} travels where the LSTM's backward pass has its cell states, the second output where the forward pass
+  // keeps gate values)
+  LaunchExtras ex;
+  ex.backward = true; ex.saved = gates; ex.dh0 = dh0; ex.gates_out = d_recurrent;
+  return forward_persistent(h, T, dh_ext, nullptr, h0, d_bprime, const_cast<float*>(h_fwd), stream, ex);
+}
+
 int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* h_fwd, float* d_bprime,
                    float* dh0, void* stream) {
   sprnn_handle_t h = h_transposed;
@@ -538,7 +569,7 @@ int sprnn_transpose_csr(int rows, int cols, const int32_t* row_ptr, const int32_
 int sprnn_forward_stepwise(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                            float* h_out, float* c_out, void* stream) {
   if (!h || T < 0) return SPRNN_ERR_INVALID;
-  if (h->map.cell == SPRNN_CELL_GRU || h->map.cell == SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
+  if (h->map.cell == SPRNN_CELL_GRU || h->map.cell >= SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
   const Mapping& m = h->map;
   const bool lstm = m.cell == SPRNN_CELL_LSTM;
   if (T > 0 && (!x || !h_out || (lstm && !c_out))) return SPRNN_ERR_INVALID;
@@ -564,7 +595,7 @@ int sprnn_project(sprnn_handle_t h, int T, int input_size, const float* x_in, co
   if (!h || T < 0 || input_size <= 0) return SPRNN_ERR_INVALID;
   if (T > 0 && (!x_in || !w_in_fp16_bits || !b_prime)) return SPRNN_ERR_INVALID;
   if ((long long)T * h->map.batch > 0x7fffffffLL) return SPRNN_ERR_INVALID;
-  if (h->map.cell == SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
+  if (h->map.cell >= SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_UNSUPPORTED;
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
   if (!guard.ok) return SPRNN_ERR_HIP;

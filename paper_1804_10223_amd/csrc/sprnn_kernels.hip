@@ -325,11 +325,16 @@ __device__ __forceinline__ long long tick(bool on) {
 // values (p.aux) and cell states (p.c_out, p.c0) of the forward pass, keeps dc_{t+1} f_{t+1} in a register, and
 // publishes four elements of the exchanged vector instead of one; one more step gives dL/dh_0 (p.dh0),
 // 6 = the same with the weight gradient fused in as in 4: the column gathered for a nonzero (j, g H + i) of the transposed
-// matrix is dp_{t+1}[.][g H + i], the factor that dL/dU[g H + i][j] pairs with the forward output h_t[.][j] of the lane's row.
+// matrix is dp_{t+1}[.][g H + i], the factor that dL/dU[g H + i][j] pairs with the forward output h_t[.][j] of the lane's row,
+// 7 = backward pass through time of the GRU: as 5 with three elements per unit, v = (dp_r | dp_z | dq) over the transposed
+// [H][3H] matrix; kept from the forward pass are r, z, n, q (p.aux, [T][B][4H]) and h_{t-1} (p.c_out, p.c0); the lane carries
+// dh_{t+1} z_{t+1}; outputs dL/db' = (dp_r | dp_z | da) in p.h_out and v itself in p.gates_out (the weight gradient's factor).
 template <int B, int NW, int CELL, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
-  constexpr bool LBWD = CELL == 5 || CELL == 6;
+  constexpr bool LBWD = CELL == 5 || CELL == 6 || CELL == 7;   // backward pass of a gated cell
+  constexpr bool GBWD = CELL == 7;                             // ... of the GRU
+  constexpr int NG = GBWD ? 3 : 4;                             // elements of the exchanged vector per hidden unit
   constexpr bool BWD = CELL == 3 || CELL == 4;
   constexpr bool WGRAD = CELL == 4 || CELL == 6;
   const int steps = (BWD || LBWD) ? p.T + ((p.dh0 || WGRAD) ? 1 : 0) : p.T;   // the last one pairs delta_1 (dp_1) with h_0
@@ -375,7 +380,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >=
   // candidate row hands over the recurrent sum (+ b_hn) and b'_n separately (the reset gate multiplies only the
   // former), the latter in the fourth row's slot, and the cell lanes keep h_{t-1} where the LSTM keeps c.
   constexpr bool gru = CELL == 2;
-  const int Hu = LBWD ? H >> 2 : H;            // hidden units (H is the length of the exchanged vector)
+  const int Hu = LBWD ? H / NG : H;            // hidden units (H is the length of the exchanged vector)
   const int Rx = gru ? 3 * H : (LBWD ? Hu : R);   // rows of b' (backward: of e) per sample
   const int row = p.lane_row[(size_t)wg * block + tid];
   const int sample = sample_of_lane<B>(lane);
@@ -401,7 +406,9 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >=
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * Rx * 4, kBufWord3);
   const __amdgpu_buffer_rsrc_t hbuf = __builtin_amdgcn_make_buffer_rsrc(p.h_out, 0, p.T * B * H * 4, kBufWord3);
-  const __amdgpu_buffer_rsrc_t abuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>((BWD || LBWD) ? p.aux : p.x), 0, p.T * B * H * 4, kBufWord3);
+  const __amdgpu_buffer_rsrc_t abuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>((BWD || LBWD) ? p.aux : p.x), 0,
+                                                                        p.T * B * (LBWD ? 4 * Hu : H) * 4, kBufWord3);
+  const int gates_voff = (LBWD && owner) ? (sample * 4 * Hu + row) * 4 : kOutOfRange;   // this lane's first kept gate value
   const __amdgpu_buffer_rsrc_t dbuf = __builtin_amdgcn_make_buffer_rsrc((BWD || LBWD) && p.dh0 ? p.dh0 : p.h_out, 0, B * Hu * 4, kBufWord3);
   // LSTM backward: forward cell states [T][B][Hu], c_0 and dL/dc_0 [B][Hu] (an absent one is an empty buffer: loads
   // give zero, stores are dropped); this lane's element of them, and the distance of two gate blocks in the ring
@@ -475,13 +482,13 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >=
   auto load_saved = [&](int time) {   // c_cur of this time is the c_prev of the step before
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      gn[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, out_voff, (time * B * 4 + q) * Hu * 4, 0));
+      gn[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(abuf, gates_voff, (time * B * 4 + q) * Hu * 4, 0));
     c_prev = __builtin_bit_cast(float, time > 0 ? __builtin_amdgcn_raw_buffer_load_b32(cfbuf, unit_voff, (time - 1) * B * Hu * 4, 0)
                                                 : __builtin_amdgcn_raw_buffer_load_b32(c0buf, unit_voff, 0, 0));
   };
   if constexpr (LBWD) {
     if (p.T > 0) {
-      c_cur = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(cfbuf, unit_voff, time_of(0) * B * Hu * 4, 0));
+      if constexpr (!GBWD) c_cur = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(cfbuf, unit_voff, time_of(0) * B * Hu * 4, 0));
       load_saved(time_of(0));
     }
   }
@@ -660,6 +667,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >=
     const int rearm_byte = (int)((g + 2) & (kRingSlotsDev - 1)) * p.h_bytes;
     const int out_soff = time_of(t) * B * H * 4;
     float hval;
+    float kept[4] = {0.0f, 0.0f, 0.0f, 0.0f}, c_new = 0.0f;   // gated cells: values stored after the publish
     if constexpr (LSTM) {
       if (gru) {
         if (owner && gate < 2) stage[stage_write] = pre;
@@ -677,58 +685,70 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >=
         const float n = tanhf_(fmaf(r, gates.z, gates.w));
         hval = fmaf(z, c_state - n, n) + 0.0f;                                   // (1 - z) n + z h_{t-1}
         c_state = hval;
+        kept[0] = r; kept[1] = z; kept[2] = n; kept[3] = gates.z;               // r, z, n and q = U_n h + b_hn
       } else {
         const float gi = sigmoidf_(gates.x), gf = sigmoidf_(gates.y), gg = tanhf_(gates.z), go = sigmoidf_(gates.w);
         const float c = gf * c_state + gi * gg;
         c_state = c;
         hval = go * tanhf_(c) + 0.0f;   // + 0.0f: -0.0 -> +0.0 (-0.0 is the "not written" mark)
-        const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c), cbuf, out_voff, out_soff, 0);
-        if (p.gates_out) {   // training: the gate values the backward pass needs, [T][B][4H]
-          const __amdgpu_buffer_rsrc_t gbuf = __builtin_amdgcn_make_buffer_rsrc(p.gates_out, 0, p.T * B * H * 16, kBufWord3);
-          const int gate_voff = cell_unit >= 0 ? ((lane % B) * 4 * H + cell_unit) * 4 : kOutOfRange;
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, gi), gbuf, gate_voff, out_soff * 4, 0);
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, gf), gbuf, gate_voff, out_soff * 4 + H * 4, 0);
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, gg), gbuf, gate_voff, out_soff * 4 + H * 8, 0);
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, go), gbuf, gate_voff, out_soff * 4 + H * 12, 0);
-        }
+        c_new = c;
+        kept[0] = gi; kept[1] = gf; kept[2] = gg; kept[3] = go;
       }
     } else if constexpr (LBWD) {
-      float dp[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      hval = red + 0.0f;               // the extra step: U^T dp_1 = dL/dh_0
+      float dp[NG], dx_n = 0.0f;       // dx_n: GRU, gradient of the candidate's pre-activation
+#pragma unroll
+      for (int q = 0; q < NG; ++q) dp[q] = 0.0f;
+      hval = (GBWD ? red + carry : red) + 0.0f;   // the extra step: dL/dh_0 (the GRU adds the update gate's direct path)
       if (t < p.T) {
-        const float gi = gn[0], gf = gn[1], gg = gn[2], go = gn[3];
-        const float tc = tanhf_(c_cur);
-        const float dc = fmaf(pre * go, fmaf(-tc, tc, 1.0f), carry);   // pre = dh_t
-        dp[0] = dc * gg * gi * (1.0f - gi) + 0.0f;                     // + 0.0f: never the "not written" mark
-        dp[1] = dc * c_prev * gf * (1.0f - gf) + 0.0f;
-        dp[2] = dc * gi * fmaf(-gg, gg, 1.0f) + 0.0f;
-        dp[3] = pre * tc * go * (1.0f - go) + 0.0f;
-        carry = dc * gf;
-        c_cur = c_prev;
+        if constexpr (GBWD) {
+          const float gr = gn[0], gz = gn[1], gc = gn[2], gq = gn[3];
+          const float dh = pre + carry;                                  // pre = e_t + U^T v_{t+1}
+          dx_n = dh * (1.0f - gz) * fmaf(-gc, gc, 1.0f) + 0.0f;
+          dp[0] = dx_n * gq * gr * (1.0f - gr) + 0.0f;                   // + 0.0f: never the "not written" mark
+          dp[1] = dh * (c_prev - gc) * gz * (1.0f - gz) + 0.0f;          // c_prev holds h_{t-1}
+          dp[2] = dx_n * gr + 0.0f;
+          carry = dh * gz;
+        } else {
+          const float gi = gn[0], gf = gn[1], gg = gn[2], go = gn[3];
+          const float tc = tanhf_(c_cur);
+          const float dc = fmaf(pre * go, fmaf(-tc, tc, 1.0f), carry);   // pre = dh_t
+          dp[0] = dc * gg * gi * (1.0f - gi) + 0.0f;
+          dp[1] = dc * c_prev * gf * (1.0f - gf) + 0.0f;
+          dp[2] = dc * gi * fmaf(-gg, gg, 1.0f) + 0.0f;
+          dp[3] = pre * tc * go * (1.0f - go) + 0.0f;
+          carry = dc * gf;
+          c_cur = c_prev;
+        }
       }
       jitter_pause(p.jitter, wave_id, g, 3);
       if (solo) {
         if (ring_voff != kOutOfRange) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff + q * gate_ring_bytes) = dp[q];
+          for (int q = 0; q < NG; ++q) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff + q * gate_ring_bytes) = dp[q];
         }
       } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < NG; ++q)
           __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, dp[q]), ring, ring_voff, slot_byte + q * gate_ring_bytes, kAuxCoherent);
         if (p.sync == SPRNN_SYNC_TAGGED) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q)
+          for (int q = 0; q < NG; ++q)
             __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte + q * gate_ring_bytes, kAuxCoherent);
         }
       }
       if (t < p.T) {
+        if constexpr (GBWD) {   // the recurrent sums' gradient for the weight gradient, then dL/db' with da in the third block
+          const __amdgpu_buffer_rsrc_t vbuf = __builtin_amdgcn_make_buffer_rsrc(p.gates_out, 0, p.gates_out ? p.T * B * H * 4 : 0, kBufWord3);
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+          for (int q = 0; q < NG; ++q)
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, dp[q]), vbuf, out_voff, out_soff + q * Hu * 4, 0);
+          dp[2] = dx_n;
+        }
+#pragma unroll
+        for (int q = 0; q < NG; ++q)
           __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, dp[q]), hbuf, out_voff, out_soff + q * Hu * 4, 0);
-        if (t == p.T - 1) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, carry), dc0buf, unit_voff, 0, 0);   // dL/dc_0 = dc_1 f_1
+        if (!GBWD && t == p.T - 1) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, carry), dc0buf, unit_voff, 0, 0);   // dL/dc_0 = dc_1 f_1
       } else if (p.dh0) {
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, unit_voff, 0, 0);
       }
@@ -760,6 +780,21 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >=
       if (p.dh0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, out_voff, 0, 0);
     } else {
       __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), hbuf, out_voff, out_soff, 0);
+    }
+    if constexpr (LSTM) {
+      // The cell state and (training) the kept gate values leave after the publish: the publish waits for every
+      // earlier store of the wavefront, and these would sit in front of it.
+      if (!gru) {
+        const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(p.c_out, 0, p.T * B * H * 4, kBufWord3);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, c_new), cbuf, out_voff, out_soff, 0);
+      }
+      if (p.gates_out) {   // [T][B][4H]: i | f | g | o after their activations, or r | z | n | q for the GRU
+        const __amdgpu_buffer_rsrc_t gbuf = __builtin_amdgcn_make_buffer_rsrc(p.gates_out, 0, p.T * B * H * 16, kBufWord3);
+        const int gate_voff = cell_unit >= 0 ? ((lane % B) * 4 * H + cell_unit) * 4 : kOutOfRange;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, kept[q]), gbuf, gate_voff, out_soff * 4 + q * H * 4, 0);
+      }
     }
     if (t + 1 < p.T) {
       xn = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, x_voff, time_of(t + 1) * B * Rx * 4, 0));
@@ -1025,7 +1060,8 @@ static const void* pick_b(int batch, int nw) {
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline) {
   const int kind = cell == SPRNN_CELL_LSTM ? 1 : (cell == SPRNN_CELL_GRU ? 2 : 0);
   if (timeline) {   // the phase timeline is built for the forward pass of the vanilla and LSTM cells only
-    if (kind == 2 || cell == kCellBackward || cell == kCellBackwardGrad || cell == SPRNN_CELL_LSTM_BACKWARD || cell == kCellLstmBackwardGrad) return nullptr;
+    if (kind == 2 || cell == kCellBackward || cell == kCellBackwardGrad || cell == SPRNN_CELL_LSTM_BACKWARD || cell == kCellLstmBackwardGrad ||
+        cell == SPRNN_CELL_GRU_BACKWARD) return nullptr;
     return kind == 1 ? pick_b<1, true>(batch, template_words) : pick_b<0, true>(batch, template_words);
   }
   if (kind == 2) return pick_b<2, false>(batch, template_words);
@@ -1033,6 +1069,7 @@ const void* persistent_kernel_for(int batch, int template_words, int cell, bool 
   if (cell == kCellBackwardGrad) return pick_b<4, false>(batch, template_words);
   if (cell == SPRNN_CELL_LSTM_BACKWARD) return pick_b<5, false>(batch, template_words);
   if (cell == kCellLstmBackwardGrad) return pick_b<6, false>(batch, template_words);
+  if (cell == SPRNN_CELL_GRU_BACKWARD) return pick_b<7, false>(batch, template_words);
   return kind == 1 ? pick_b<1, false>(batch, template_words) : pick_b<0, false>(batch, template_words);
 }
 

@@ -15,16 +15,18 @@ static inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 static int visible_gates(int cell) { return cell == SPRNN_CELL_LSTM ? 4 : (cell == SPRNN_CELL_GRU ? 3 : 1); }
 static bool gated(int cell) { return cell == SPRNN_CELL_LSTM || cell == SPRNN_CELL_GRU; }
 // Columns of the matrix = length of the vector the workgroups exchange.  The backward pass of the LSTM holds the
-// transposed matrix: one row per hidden unit over the 4H gate gradients.
-static int exchange_cols(int cell, int hidden) { return cell == SPRNN_CELL_LSTM_BACKWARD ? 4 * hidden : hidden; }
+// transposed matrix: one row per hidden unit over the 4H gate gradients (3H for the GRU).
+static int exchange_cols(int cell, int hidden) {
+  return cell == SPRNN_CELL_LSTM_BACKWARD ? 4 * hidden : (cell == SPRNN_CELL_GRU_BACKWARD ? 3 * hidden : hidden);
+}
 
 int validate_csr(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
                  const uint16_t* val_bits) {
   if (hidden < 1) return SPRNN_ERR_INVALID;
   if (hidden > 65535) return SPRNN_ERR_UNSUPPORTED;
-  if (cell == SPRNN_CELL_LSTM_BACKWARD && hidden > 16383) return SPRNN_ERR_UNSUPPORTED;   // 16-bit column indices
+  if (exchange_cols(cell, hidden) > 65535) return SPRNN_ERR_UNSUPPORTED;   // 16-bit column indices
   if (!(batch == 1 || batch == 2 || batch == 4 || batch == 8)) return SPRNN_ERR_UNSUPPORTED;
-  if (cell < SPRNN_ACT_RELU || cell > SPRNN_CELL_LSTM_BACKWARD) return SPRNN_ERR_INVALID;
+  if (cell < SPRNN_ACT_RELU || cell > SPRNN_CELL_GRU_BACKWARD) return SPRNN_ERR_INVALID;
   if (!row_ptr) return SPRNN_ERR_INVALID;
   const int rows = hidden * visible_gates(cell), cols = exchange_cols(cell, hidden);
   if (row_ptr[0] != 0) return SPRNN_ERR_INVALID;

@@ -13,8 +13,8 @@ closed libraries on other hardware and are not reproduced):
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
   constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
   cells      the four cells (ReLU, tanh, LSTM, GRU) on one layer shape: hidden 1024, density 20 %, T 256, batch 4 and 8.
-  training   the launches of one training step (forward, backward pass through time, weight gradient) of a ReLU cell
-             and of the LSTM on the same layer shape.
+  training   the launches of one training step (forward, backward pass through time, weight gradient) of a ReLU cell,
+             the LSTM and the GRU on the same layer shape.
   casestudy  the layer shapes of Appendix B's two tables (machine translation LSTMs at 4-12.5 % density, speech
              recognition layers at 12 %) with random unstructured patterns, as the paper itself does for the speech
              layers; milliseconds per 256-timestep sequence beside the paper's own figure (another GPU: context).
@@ -130,16 +130,15 @@ def training(torch, wl, reps):
     print("|---|---|---|---|---|---|---|")
     dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
     for B in (4, 8):
-        for cell in ("relu", "lstm"):
-            w = wl.make_workload("train", cell, 1024, B, 256, 0.20, seed=0, gain=1.0 if cell == "lstm" else 0.9)
+        for cell in ("relu", "lstm", "gru"):
+            w = wl.make_workload("train", cell, 1024, B, 256, 0.20, seed=0, gain=0.9 if cell == "relu" else 1.0)
             H, T = w.hidden, w.steps
             x = dev(w.x)
             e = torch.randn((T, B, H), device="cuda")
-            rows = 4 * H if cell == "lstm" else H
-            t_csr = binding.transpose_csr(rows, H, w.row_ptr, w.col_idx, w.val_bits)
+            t_csr = binding.transpose_csr(w.rows, H, w.row_ptr, w.col_idx, w.val_bits)
             fused = None
             with binding.SparseRNN(H, B, cell, w.row_ptr, w.col_idx, w.val_bits) as fwd, \
-                    binding.SparseRNN(H, B, "lstm_backward" if cell == "lstm" else cell, *t_csr) as bwd:
+                    binding.SparseRNN(H, B, {"lstm": "lstm_backward", "gru": "gru_backward"}.get(cell, cell), *t_csr) as bwd:
                 if cell == "lstm":
                     f_us = _time_us_per_step(torch, lambda: fwd.forward_lstm_train(x), T, reps)
                     h, c, g = fwd.forward_lstm_train(x)
@@ -149,6 +148,12 @@ def training(torch, wl, reps):
                         fused = _time_us_per_step(torch, lambda: bwd.backward_lstm_with_weights(e, g, c, h), T, reps)
                     except binding.SprnnError:
                         pass
+                elif cell == "gru":
+                    b_hn = dev(w.b_hn)
+                    f_us = _time_us_per_step(torch, lambda: fwd.forward_gru_train(x, b_hn), T, reps)
+                    h, g = fwd.forward_gru_train(x, b_hn)
+                    b_us = _time_us_per_step(torch, lambda: bwd.backward_gru(e, g, h), T, reps)
+                    d = bwd.backward_gru(e, g, h)[1]          # the recurrent sums' gradient feeds the weight gradient
                 else:
                     h = fwd.forward(x)
                     f_us = _time_us_per_step(torch, lambda: fwd.forward(x, None, h), T, reps)

@@ -235,6 +235,16 @@ def test_packer_takes_the_transposed_lstm_matrix_of_the_backward_pass(H, B, dens
     with pytest.raises(binding.SprnnError) as e:
         binding.pack_host(16384, B, "lstm_backward", np.zeros(16385, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16))
     assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
+    # the GRU's transposed matrix: H rows over 3H columns
+    g = wl.make_workload("p", "gru", H, B, 1, dens, seed=5, row_nnz=rownnz)
+    g_row_ptr, g_col, g_val = binding.transpose_csr(3 * H, H, g.row_ptr, g.col_idx, g.val_bits)
+    _, g_lane_row, g_lane_words, g_info = binding.pack_host(H, B, "gru_backward", g_row_ptr, g_col, g_val, **opts)
+    assert g_info["rows"] == H and g_info["nnz"] == g.nnz and int(g_lane_words.sum()) == g.nnz
+    if not g_info["compact"]:
+        assert g_info["lds_bytes"] >= 3 * H * 4 * B and g_info["lds_bytes"] < 2 * (3 * H * 4 * B) + 32
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(21846, B, "gru_backward", np.zeros(21847, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.uint16))
+    assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
 
 
 def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
@@ -249,6 +259,8 @@ def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
     assert lib.sprnn_forward_lstm_train(none, 1, None, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_backward_lstm(none, 1, None, None, None, None, None, None, None, None) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_backward_lstm_with_weights(none, 1, *([None] * 11)) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_forward_gru_train(none, 1, *([None] * 6)) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_backward_gru(none, 1, *([None] * 8)) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_destroy(none) == binding.SPRNN_OK
 
 
