@@ -497,8 +497,10 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >=
   const int row_voff = row >= 0 ? row * 4 : kOutOfRange;
   const __amdgpu_buffer_rsrc_t h0buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(WGRAD && p.bwd_h0 ? p.bwd_h0 : p.x), 0,
                                                                          (WGRAD && p.bwd_h0) ? B * Hu * 4 : 0, kBufWord3);
-  const __amdgpu_buffer_rsrc_t sbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(WGRAD ? p.side_src : p.x), 0,
-                                                                        WGRAD ? p.T * B * Hu * 4 : 0, kBufWord3);
+  // (the vanilla cell's g' and its weight gradient both read the forward outputs: one descriptor serves both)
+  const __amdgpu_buffer_rsrc_t sbuf = CELL == 4 ? abuf
+                                                : __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(WGRAD ? p.side_src : p.x), 0,
+                                                                                    WGRAD ? p.T * B * Hu * 4 : 0, kBufWord3);
   auto load_side = [&](int s) {   // s: step index; rows of step T come from h_0 (an empty buffer returns zeros)
 #pragma unroll
     for (int b = 0; b < B; ++b)
