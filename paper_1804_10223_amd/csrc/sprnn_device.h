@@ -80,6 +80,10 @@ struct StepArgs {
 };
 
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline);   // cell: SPRNN_ACT_* / SPRNN_CELL_*
+// (the instantiations live in four translation units; persistent_kernel_for forwards to these three)
+const void* persistent_timeline_kernel_for(int batch, int template_words, bool lstm);        // forward pass with the phase timeline
+const void* persistent_backward_kernel_for(int batch, int template_words, int cell);         // kCellBackward, kCellBackwardGrad
+const void* persistent_gated_backward_kernel_for(int batch, int template_words, int cell);   // SPRNN_CELL_*_BACKWARD, kCellLstmBackwardGrad
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream);
 // b'[m][n] = sum_k x[m][k] W[n][k] + bias[n] (bias may be null); x [M][K] float32, w [N][K] binary16 bits, out [M][N] float32.
 hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, float* out, int M, int N, int K,

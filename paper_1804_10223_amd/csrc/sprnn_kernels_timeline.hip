@@ -1,0 +1,11 @@
+// Device code of libsprnn: the persistent kernel's instantiations with the phase timeline (options.timeline), forward
+// pass of the vanilla cells and the LSTM.
+#include "sprnn_persistent.h"
+
+namespace sprnn {
+
+const void* persistent_timeline_kernel_for(int batch, int template_words, bool lstm) {
+  return lstm ? pick_b<1, true>(batch, template_words) : pick_b<0, true>(batch, template_words);
+}
+
+}  // namespace sprnn
