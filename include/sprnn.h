@@ -267,6 +267,19 @@ int sprnn_backward_gru(sprnn_handle_t h_transposed, int T, const float* dh_ext, 
                        const float* h0, float* d_bprime, float* d_recurrent, float* dh0, void* stream);
 
 /*
+ * sprnn_backward_gru with the gradient of the recurrent weights fused in, as in sprnn_backward_with_weights: the column
+ * of v_{t+1} that a lane gathers for a nonzero (j, r) of the transposed matrix is the factor that dL/dU[r][j] pairs with
+ * the forward output h_t[.][j] of the lane's own row.
+ *   dU_transposed  device, float32 [nnz]: dL/dU in the order of the TRANSPOSED matrix's CSR arrays (entry p belongs to
+ *                  the forward nonzero t_source[p] of sprnn_transpose_csr); overwritten.
+ * Other arguments as sprnn_backward_gru.  Always runs T + 1 steps.  Not available with column compaction or where the
+ * mapping needs more threads than the instantiation is built for (SPRNN_ERR_UNSUPPORTED: use the two separate calls).
+ */
+int sprnn_backward_gru_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates,
+                                    const float* h_fwd, const float* h0, float* d_bprime, float* d_recurrent, float* dh0,
+                                    float* dU_transposed, void* stream);
+
+/*
  * sprnn_backward_lstm with the gradient of the recurrent weights fused in, as in sprnn_backward_with_weights: the
  * column of dp_{t+1} that a lane gathers for a nonzero (j, r) of the transposed matrix is the factor that dL/dU[r][j]
  * pairs with the forward output h_t[.][j] of the lane's own row.

@@ -28,7 +28,7 @@ SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
            "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights", "sprnn_forward_gru_train",
-           "sprnn_backward_gru",
+           "sprnn_backward_gru", "sprnn_backward_gru_with_weights",
            "sprnn_project", "sprnn_backward", "sprnn_backward_with_weights", "sprnn_weight_gradient", "sprnn_transpose_csr",
            "sprnn_get_info", "sprnn_read_timeline", "sprnn_check", "sprnn_pack_host", "sprnn_free_host", "sprnn_status_string",
            "sprnn_destroy"]
@@ -95,6 +95,8 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_forward_gru_train.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sprnn_backward_gru.restype = ci
     lib.sprnn_backward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.sprnn_backward_gru_with_weights.restype = ci
+    lib.sprnn_backward_gru_with_weights.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_gru.restype = ci
     lib.sprnn_forward_gru.argtypes = [vp, ci, vp, vp, vp, vp, vp]
     lib.sprnn_backward.restype = ci
@@ -393,6 +395,27 @@ class SparseRNN:
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_backward_gru")
         return d_bprime, d_rec, dh0
+
+    def backward_gru_with_weights(self, dh_ext, gates, h_fwd, h0=None, want_dh0=True, want_recurrent=True):
+        """sprnn_backward_gru_with_weights on a "gru_backward" handle:
+        (d_bprime [T, B, 3H], d_recurrent or None, dh0 or None, dU [nnz] in the transposed matrix's CSR order)."""
+        import torch
+        T = int(dh_ext.shape[0])
+        dev = "cuda:%d" % self.device
+        nnz = self.info()["nnz"]
+        d_bprime = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
+        d_rec = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev) if want_recurrent else None
+        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
+        dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
+        rc = self._lib.sprnn_backward_gru_with_weights(
+            self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
+            _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"), _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
+            _dev_ptr(h0, (self.batch, self.hidden), "h0"), _dev_ptr(d_bprime, (T, self.batch, 3 * self.hidden), "d_bprime"),
+            _dev_ptr(d_rec, (T, self.batch, 3 * self.hidden), "d_recurrent"), _dev_ptr(dh0, (self.batch, self.hidden), "dh0"),
+            ctypes.c_void_p(dU.data_ptr()), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_backward_gru_with_weights")
+        return d_bprime, d_rec, dh0, dU[:nnz]
 
     def backward(self, dh_ext, h_fwd, d_bprime=None, want_dh0=True):
         """sprnn_backward on a handle that holds the TRANSPOSED matrix: (delta [T, B, H], dh0 [B, H] or None)."""

@@ -242,10 +242,11 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
             SPRNN_HIP(upload(&h->d_col, col_idx, (size_t)m.nnz)) &&
             SPRNN_HIP(upload(&h->d_val, val_fp16_bits, (size_t)m.nnz));
-  if (ok && m.cell == SPRNN_CELL_LSTM_BACKWARD && !m.compact) {
-    // backward pass of the LSTM with the weight gradient fused in: needs the word -> CSR position map, co-residency of
-    // the same grid with that kernel, and a kernel built for this many threads
-    const void* k = persistent_kernel_for(m.batch, m.template_words, kCellLstmBackwardGrad, false);
+  if (ok && (m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD) && !m.compact) {
+    // backward pass of a gated cell with the weight gradient fused in: needs the word -> CSR position map, co-residency
+    // of the same grid with that kernel, and a kernel built for this many threads
+    const void* k = persistent_kernel_for(m.batch, m.template_words,
+                                          m.cell == SPRNN_CELL_LSTM_BACKWARD ? kCellLstmBackwardGrad : kCellGruBackwardGrad, false);
     int per_cu_g = 0;
     hipFuncAttributes fa;
     if (k && SPRNN_HIP(hipFuncGetAttributes(&fa, k)) && fa.maxThreadsPerBlock >= m.block &&
@@ -491,6 +492,27 @@ int sprnn_backward_gru(sprnn_handle_t h_transposed, int T, const float* dh_ext, 
   // keeps gate values)
   LaunchExtras ex;
   ex.backward = true; ex.saved = gates; ex.dh0 = dh0; ex.gates_out = d_recurrent;
+  return forward_persistent(h, T, dh_ext, nullptr, h0, d_bprime, const_cast<float*>(h_fwd), stream, ex);
+}
+
+int sprnn_backward_gru_with_weights(sprnn_handle_t h_transposed, int T, const float* dh_ext, const float* gates,
+                                    const float* h_fwd, const float* h0, float* d_bprime, float* d_recurrent, float* dh0,
+                                    float* dU_transposed, void* stream) {
+  sprnn_handle_t h = h_transposed;
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell != SPRNN_CELL_GRU_BACKWARD || !h->kernel_bwd_grad || !h->d_word_src) return SPRNN_ERR_UNSUPPORTED;
+  if (!dU_transposed && h->map.nnz > 0) return SPRNN_ERR_INVALID;
+  if (T > 0 && (!dh_ext || !gates || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
+  if (T == 0) {   // nothing to sum, nothing flows back
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return SPRNN_ERR_HIP;
+    if (dh0 && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dh0), 0u, (size_t)h->map.batch * h->map.hidden, (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    if (h->map.nnz > 0 && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dU_transposed), 0u, (size_t)h->map.nnz, (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    return SPRNN_OK;
+  }
+  LaunchExtras ex;
+  ex.backward = true; ex.saved = gates; ex.dh0 = dh0; ex.gates_out = d_recurrent;
+  ex.wgrad_h_fwd = h_fwd; ex.wgrad_h0 = h0; ex.dU = dU_transposed;
   return forward_persistent(h, T, dh_ext, nullptr, h0, d_bprime, const_cast<float*>(h_fwd), stream, ex);
 }
 

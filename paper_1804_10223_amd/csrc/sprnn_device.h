@@ -18,6 +18,7 @@ constexpr int kCtrlWords = kCtrlBarrier + 16 * 9;
 constexpr int kCellBackward = 100;                // persistent_kernel_for: backward pass of a vanilla cell
 constexpr int kCellBackwardGrad = 101;            // the same with the weight gradient fused in
 constexpr int kCellLstmBackwardGrad = 102;        // backward pass of the LSTM with the weight gradient fused in
+constexpr int kCellGruBackwardGrad = 103;         // backward pass of the GRU with the weight gradient fused in
 constexpr int kTimelineSlots = 16;                // 64-bit accumulators per workgroup in the phase timeline
 constexpr int kLdsTailBytes = 16 + 8 * kTimelineSlots;   // LDS after h: abort flags, timeline sums
 
@@ -83,7 +84,7 @@ const void* persistent_kernel_for(int batch, int template_words, int cell, bool 
 // (the instantiations live in four translation units; persistent_kernel_for forwards to these three)
 const void* persistent_timeline_kernel_for(int batch, int template_words, bool lstm);        // forward pass with the phase timeline
 const void* persistent_backward_kernel_for(int batch, int template_words, int cell);         // kCellBackward, kCellBackwardGrad
-const void* persistent_gated_backward_kernel_for(int batch, int template_words, int cell);   // SPRNN_CELL_*_BACKWARD, kCellLstmBackwardGrad
+const void* persistent_gated_backward_kernel_for(int batch, int template_words, int cell);   // SPRNN_CELL_*_BACKWARD, kCell{Lstm,Gru}BackwardGrad
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream);
 // b'[m][n] = sum_k x[m][k] W[n][k] + bias[n] (bias may be null); x [M][K] float32, w [N][K] binary16 bits, out [M][N] float32.
 hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, float* out, int M, int N, int K,

@@ -333,15 +333,16 @@ __device__ __forceinline__ long long tick(bool on) {
 // matrix is dp_{t+1}[.][g H + i], the factor that dL/dU[g H + i][j] pairs with the forward output h_t[.][j] of the lane's row,
 // 7 = backward pass through time of the GRU: as 5 with three elements per unit, v = (dp_r | dp_z | dq) over the transposed
 // [H][3H] matrix; kept from the forward pass are r, z, n, q (p.aux, [T][B][4H]) and h_{t-1} (p.c_out, p.c0); the lane carries
-// dh_{t+1} z_{t+1}; outputs dL/db' = (dp_r | dp_z | da) in p.h_out and v itself in p.gates_out (the weight gradient's factor).
+// dh_{t+1} z_{t+1}; outputs dL/db' = (dp_r | dp_z | da) in p.h_out and v itself in p.gates_out (the weight gradient's factor),
+// 8 = the same with the weight gradient fused in as in 4 and 6.
 template <int B, int NW, int CELL, bool TL>
-__global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
+__global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL == 8) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
-  constexpr bool LBWD = CELL == 5 || CELL == 6 || CELL == 7;   // backward pass of a gated cell
-  constexpr bool GBWD = CELL == 7;                             // ... of the GRU
+  constexpr bool LBWD = CELL >= 5 && CELL <= 8;                // backward pass of a gated cell
+  constexpr bool GBWD = CELL == 7 || CELL == 8;                // ... of the GRU
   constexpr int NG = GBWD ? 3 : 4;                             // elements of the exchanged vector per hidden unit
   constexpr bool BWD = CELL == 3 || CELL == 4;
-  constexpr bool WGRAD = CELL == 4 || CELL == 6;
+  constexpr bool WGRAD = CELL == 4 || CELL == 6 || CELL == 8;
   const int steps = (BWD || LBWD) ? p.T + ((p.dh0 || WGRAD) ? 1 : 0) : p.T;   // the last one pairs delta_1 (dp_1) with h_0
   auto time_of = [&](int s) { return (BWD || LBWD) ? p.T - 1 - s : s; };   // index into x / aux / outputs of step s
   // LDS: [h][abort flags][timeline sums][LSTM hand-over area].  A single workgroup (no exchange) keeps two copies of

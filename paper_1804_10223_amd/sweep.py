@@ -154,6 +154,10 @@ def training(torch, wl, reps):
                     h, g = fwd.forward_gru_train(x, b_hn)
                     b_us = _time_us_per_step(torch, lambda: bwd.backward_gru(e, g, h), T, reps)
                     d = bwd.backward_gru(e, g, h)[1]          # the recurrent sums' gradient feeds the weight gradient
+                    try:
+                        fused = _time_us_per_step(torch, lambda: bwd.backward_gru_with_weights(e, g, h), T, reps)
+                    except binding.SprnnError:
+                        pass
                 else:
                     h = fwd.forward(x)
                     f_us = _time_us_per_step(torch, lambda: fwd.forward(x, None, h), T, reps)

@@ -150,3 +150,47 @@ def test_gru_backward_zero_weights_and_wrong_handles():
         with pytest.raises(binding.SprnnError) as err:
             fwd.backward_gru(z, z4, z)
         assert err.value.code == binding.SPRNN_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("H,B,T,dens,rownnz,opts", [
+    (96, 4, 9, 0.3, "fixed", {}),
+    (257, 1, 7, 0.2, "poisson", {}),
+    (130, 8, 5, 0.1, "poisson", {}),
+    (333, 2, 6, 0.15, "poisson", {"balance": 1}),
+    (32, 4, 8, 0.4, "fixed", {"grid": 1}),
+    (320, 4, 10, 0.3, "fixed", {"sync": "barrier"}),
+    (576, 4, 32, 0.1, "fixed", {"jitter": 7}),
+    (1024, 8, 16, 0.2, "fixed", {}),
+])
+def test_gru_backward_with_weights_matches_oracle(H, B, T, dens, rownnz, opts):
+    w = wl.make_workload("gbw", "gru", H, B, T, dens, seed=H + T + 1, gain=1.0, row_nnz=rownnz, h0_std=0.5)
+    e = np.random.default_rng(H + 1).standard_normal((T, B, H)).astype(np.float32)
+    h, gates = oracle.gru_forward_saved(H, B, w.row_ptr, w.col_idx, w.val_bits, w.x, w.b_hn, w.h0, threads=8)
+    want_d, want_v, want_dh0, want_dU, _ = oracle.gru_backward(H, B, w.row_ptr, w.col_idx, w.val_bits, gates, h, e, w.h0)
+    t_rp, t_ci, t_vb, t_src = binding.transpose_csr(3 * H, H, w.row_ptr, w.col_idx, w.val_bits, with_source=True)
+    with binding.SparseRNN(H, B, "gru_backward", t_rp, t_ci, t_vb, **opts) as rnn:
+        info = rnn.info()
+        print("case fused gru_backward H", H, "B", B, "T", T, opts,
+              {k: info[k] for k in ("grid", "block", "lanes_per_row", "template_words")}, flush=True)
+        try:
+            d, v, dh0, dU_t = rnn.backward_gru_with_weights(_dev(e), _dev(gates), _dev(h), _dev(w.h0))
+        except binding.SprnnError as err:
+            if err.code == binding.SPRNN_ERR_UNSUPPORTED:
+                pytest.skip("mapping too wide for the fused instantiation: %s" % err)
+            raise
+        assert rnn.check() == binding.SPRNN_OK
+        # the plain backward pass on the same handle gives the same gradients, bit for bit
+        d2, v2, dh02 = rnn.backward_gru(_dev(e), _dev(gates), _dev(h), _dev(w.h0))
+        assert np.array_equal(d2.cpu().numpy(), d.cpu().numpy()) and np.array_equal(v2.cpu().numpy(), v.cpu().numpy())
+        assert np.array_equal(dh02.cpu().numpy(), dh0.cpu().numpy())
+        d3, n1, n2, dU_t3 = rnn.backward_gru_with_weights(_dev(e), _dev(gates), _dev(h), _dev(w.h0), want_dh0=False, want_recurrent=False)
+        assert n1 is None and n2 is None and np.array_equal(dU_t3.cpu().numpy(), dU_t.cpu().numpy())
+        assert rnn.check() == binding.SPRNN_OK
+    d, v, dU_t = d.cpu().numpy(), v.cpu().numpy(), dU_t.cpu().numpy()
+    for t in range(T):
+        _close(d[t], want_d[t], "d_bprime[%d]" % t)
+        _close(v[t], want_v[t], "d_recurrent[%d]" % t)
+    _close(dh0.cpu().numpy(), want_dh0, "dh0")
+    dU = np.empty_like(dU_t)
+    dU[t_src] = dU_t                       # back to the forward matrix's CSR order
+    _close(dU, want_dU, "dU")

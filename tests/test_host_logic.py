@@ -261,6 +261,7 @@ def test_calls_on_a_null_handle_are_refused_without_touching_a_device():
     assert lib.sprnn_backward_lstm_with_weights(none, 1, *([None] * 11)) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_forward_gru_train(none, 1, *([None] * 6)) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_backward_gru(none, 1, *([None] * 8)) == binding.SPRNN_ERR_INVALID
+    assert lib.sprnn_backward_gru_with_weights(none, 1, *([None] * 9)) == binding.SPRNN_ERR_INVALID
     assert lib.sprnn_destroy(none) == binding.SPRNN_OK
 
 
