@@ -301,7 +301,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
   const Mapping& m = h->map;
   // The kernel addresses x and the outputs with 32-bit byte offsets from the start of the call, so a very
   // long sequence is run as several launches, each continuing from the last state of the one before.
-  const size_t step_bytes = (size_t)m.batch * std::max(m.rows, m.cols) * 4;
+  const size_t step_bytes = (size_t)m.batch * std::max(std::max(m.rows, m.cols), m.cell > SPRNN_ACT_IDENTITY ? 4 * m.hidden : 0) * 4;
   const int t_max = (int)std::max<size_t>(1, ((size_t)1 << 30) / step_bytes);
   const size_t hb = (size_t)m.batch * m.hidden;
   if (ex.backward && T > t_max) return SPRNN_ERR_UNSUPPORTED;   // time runs backwards: one launch only
@@ -317,7 +317,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.c0 = t0 ? (c_out ? c_out + (size_t)(t0 - 1) * hb : nullptr) : c0;
     a.h_out = h_out + (size_t)t0 * hb;
     a.c_out = c_out ? c_out + (size_t)t0 * hb : nullptr;
-    a.gates_out = ex.gates_out ? ex.gates_out + (size_t)t0 * m.batch * m.rows : nullptr;
+    a.gates_out = ex.gates_out ? ex.gates_out + (size_t)t0 * m.batch * 4 * m.hidden : nullptr;   // [T][B][4H] for both gated cells
     a.dc0 = ex.dc0;
     a.b_hn = ex.b_hn;
     a.aux = ex.saved; a.dh0 = ex.dh0; a.bwd_h0 = ex.wgrad_h0; a.word_src = h->d_word_src; a.dU = ex.dU;
