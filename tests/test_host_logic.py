@@ -23,6 +23,21 @@ def test_library_exports_every_declared_symbol():
     assert "CSR" in binding.status_string(-1)
 
 
+def test_public_headers_are_plain_c(tmp_path):
+    # the boundary is a C ABI: both headers must compile as C99 (and as C++) without any HIP or torch header
+    import shutil
+    import subprocess
+    src = tmp_path / "use_headers.c"
+    src.write_text('#include "sprnn.h"\n#include "sprnn_probe.h"\nint main(void) { return sprnn_status_string(0) == 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cc, flags in (("gcc", ["-std=c99"]), ("g++", ["-std=c++17", "-x", "c++"])):
+        if shutil.which(cc) is None:
+            pytest.skip("no %s here" % cc)
+        r = subprocess.run([cc, *flags, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I" + inc, str(src)],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+
+
 def test_struct_layouts_match_header_sizes():
     # 8 ints + 8 reserved; 16 ints + 3 int64 + double + 8 reserved ints
     assert ctypes.sizeof(binding.Options) == 16 * 4
