@@ -69,7 +69,10 @@ typedef struct sprnn_options_s {
   int plain_launch;  /* 1 = ordinary kernel launch instead of a cooperative one: about 10 us less per
                         forward call, but the caller must then guarantee that nothing else runs on the
                         device meanwhile (the workgroups spin on each other and must all be resident;
-                        the spin watchdog still bounds every wait)                                 */
+                        the spin watchdog still bounds every wait).  Also the way to run in a second
+                        process on one device: the HIP runtime grants cooperative launches to one
+                        process per device at a time, and refuses the others' (then sprnn_create
+                        returns SPRNN_ERR_HIP from its first launch)                               */
   int jitter;        /* test aid: non-zero seeds pseudo-random pauses (0..15 x 64 clocks) of every
                         wavefront before it publishes, before it polls and after it has copied h,
                         different in every step, to widen the windows of any race in the hand-off;

@@ -21,7 +21,7 @@ def test_plain_c_program_rotates_a_permutation_bit_exactly(tmp_path):
            "-Wl,-rpath," + PKG, "-Wl,-rpath,/opt/rocm/lib"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
-    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100, env=dict(os.environ, SPRNN_DEBUG="1"))
     print(r.stdout, r.stderr, flush=True)
     assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
     assert "0 mismatches" in r.stdout
