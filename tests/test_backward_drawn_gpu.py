@@ -103,3 +103,35 @@ def test_drawn_backward_shapes_match_oracle(cell, H, B, T, dens, rownnz, opts, f
         dU = np.empty_like(got["dU_t"])
         dU[t_src] = got["dU_t"]
         _close(dU, want["dU"], "dU")
+
+
+@pytest.mark.parametrize("cell,H,B,T,dens", [
+    ("lstm", 2560, 4, 4, 0.004),      # 4H x B x 4 bytes = 160 KB of gate gradients: only the chunks a workgroup reads fit in LDS
+    ("gru", 5000, 2, 3, 0.004),
+    ("lstm", 3000, 8, 3, 0.01),
+])
+def test_large_gated_backward_layers_run_through_column_compaction(cell, H, B, T, dens):
+    w = wl.make_workload("big", cell, H, B, T, dens, seed=1, gain=1.0, row_nnz="poisson", h0_std=0.3)
+    e = np.random.default_rng(1).standard_normal((T, B, H)).astype(np.float32)
+    csr = (w.row_ptr, w.col_idx, w.val_bits)
+    t_csr = binding.transpose_csr(w.rows, H, *csr)
+    with binding.SparseRNN(H, B, cell + "_backward", *t_csr) as rnn:
+        info = rnn.info()
+        print("case", cell, H, B, {k: info[k] for k in ("grid", "block", "lds_bytes", "compact", "template_words")}, flush=True)
+        assert info["compact"] == 1
+        if cell == "lstm":
+            h, c, g = oracle.lstm_forward_saved(H, B, *csr, w.x, w.h0, None, threads=8)
+            want = oracle.lstm_backward(H, B, *csr, g, c, h, e, w.h0, None)[:3]
+            got = rnn.backward_lstm(_dev(e), _dev(g), _dev(c))
+        else:
+            h, g = oracle.gru_forward_saved(H, B, *csr, w.x, w.b_hn, w.h0, threads=8)
+            want = oracle.gru_backward(H, B, *csr, g, h, e, w.h0)[:3]
+            got = rnn.backward_gru(_dev(e), _dev(g), _dev(h), _dev(w.h0))
+        assert rnn.check() == binding.SPRNN_OK
+    for a, b, what in zip(got, want, ("first output", "second output", "third output")):
+        a = a.cpu().numpy()
+        if a.ndim == 3:
+            for t in range(T):
+                _close(a[t], b[t], "%s[%d]" % (what, t))
+        else:
+            _close(a, b, what)
