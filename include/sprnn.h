@@ -145,6 +145,21 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
 int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream);
 
 /*
+ * sprnn_forward for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernels and results, but the exchange ring and the control words live in
+ * one array of 1 MiB that the library holds in static device memory on every GPU it runs on (until the process ends)
+ * instead of the handle's own allocations.  Calls no hipMalloc, hipFree or other allocating routine; enqueues one
+ * small fill kernel (the array keeps the last call's contents, so ring marks and control words are set afresh) and the
+ * persistent kernel.  Vanilla cells only; arguments as sprnn_forward.
+ *   Limit: 4 ring slots of the layer (4 * 4 * B * H bytes, rounded up to 16 per slot) plus 1 KiB must fit in the
+ *   array, i.e. B * H <= 65 472; larger layers get SPRNN_ERR_CAPACITY and nothing is enqueued.
+ *   All calls on one GPU share that GPU's array: two such calls that overlap in time on one GPU (different streams,
+ *   different handles) race and are not allowed; calls in stream order are fine.  sprnn_check on the handle also
+ *   reports a watchdog trip of its most recent call here.
+ */
+int sprnn_forward_noalloc(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream);
+
+/*
  * LSTM cell (Appendix B): x is float32 [T][B][4H] with gate blocks i|f|g|o (biases folded in),
  * c0 / h0 are [B][H] or NULL, h_out and c_out are [T][B][H].
  *   c_t = sigmoid(p_f) c_{t-1} + sigmoid(p_i) tanh(p_g),  h_t = sigmoid(p_o) tanh(c_t).

@@ -26,7 +26,7 @@ CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4, "lstm_backwar
 GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 
-EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
+EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_noalloc", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
            "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights", "sprnn_forward_gru_train",
            "sprnn_backward_gru", "sprnn_backward_gru_with_weights",
            "sprnn_project", "sprnn_backward", "sprnn_backward_with_weights", "sprnn_weight_gradient", "sprnn_transpose_csr",
@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.sprnn_create_ex.argtypes = [ctypes.POINTER(vp), ci, ci, ci, i32p, i32p, u16p, ci, ctypes.POINTER(Options)]
     lib.sprnn_forward.restype = ci
     lib.sprnn_forward.argtypes = [vp, ci, vp, vp, vp, vp]
+    lib.sprnn_forward_noalloc.restype = ci
+    lib.sprnn_forward_noalloc.argtypes = [vp, ci, vp, vp, vp, vp]
     lib.sprnn_forward_lstm.restype = ci
     lib.sprnn_forward_lstm.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp]
     lib.sprnn_forward_lstm_train.restype = ci
@@ -273,6 +275,16 @@ class SparseRNN:
                                      _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"), self._stream())
         if rc != SPRNN_OK:
             raise SprnnError(rc, "sprnn_forward")
+        return h_out
+
+    def forward_noalloc(self, x, h0, h_out):
+        """sprnn_forward_noalloc: as forward, exchange ring in the library's static device array; h_out is the caller's."""
+        T = int(x.shape[0])
+        rc = self._lib.sprnn_forward_noalloc(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
+                                             _dev_ptr(h0, (self.batch, self.hidden), "h0"),
+                                             _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"), self._stream())
+        if rc != SPRNN_OK:
+            raise SprnnError(rc, "sprnn_forward_noalloc")
         return h_out
 
     def forward_lstm(self, x, h0=None, c0=None, h_out=None, c_out=None):

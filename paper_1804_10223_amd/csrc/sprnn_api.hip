@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -40,7 +41,19 @@ struct sprnn_handle_s {
   uint32_t step_base = 0;        // global step index at which the next forward starts
   uint32_t barrier_base = 0;     // grid barriers completed so far (grid-barrier mode)
   bool poisoned = false;         // a watchdog trip was observed: the ring no longer holds a consistent state
+  bool used_shared_exchange = false;   // sprnn_forward_noalloc ran on this handle: sprnn_check also reads its status word
 };
+
+// ---- storage of sprnn_forward_noalloc: one array per device, alive as long as the library is loaded.
+// Layout: [control words, kScratchCtrlBytes][exchange ring, 4 slots].  On the host the array's name is only a
+// stand-in for the symbol; the address on each device comes from hipGetSymbolAddress and is kept in g_scratch.
+constexpr size_t kScratchBytes = (size_t)1 << 20;
+constexpr size_t kScratchCtrlBytes = 1024;
+static_assert(kScratchCtrlBytes >= kCtrlWords * 4 && kScratchCtrlBytes % 256 == 0, "control words must fit in front of the ring");
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxScratchDevices = 64;
+static unsigned char* g_scratch[kMaxScratchDevices];   // per device, null until looked up
+static std::mutex g_scratch_mutex;
 
 namespace {
 
@@ -101,6 +114,18 @@ void release(sprnn_handle_s* h) {
 // side, as measured on MI355X.
 int default_poll_delay(const Mapping& m) { return m.grid > 1 ? 6 : 0; }
 
+// Address of this device's copy of `scratch`; the device must be current.  Looked up once per device.
+unsigned char* scratch_on_device(int device) {
+  if (device < 0 || device >= kMaxScratchDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch[device]) {
+    void* ptr = nullptr;
+    if (!SPRNN_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)))) return nullptr;
+    g_scratch[device] = static_cast<unsigned char*>(ptr);
+  }
+  return g_scratch[device];
+}
+
 }  // namespace
 
 // What a launch of the persistent kernel takes beyond the forward pass's five buffers.
@@ -114,6 +139,7 @@ struct LaunchExtras {
   const float* wgrad_h_fwd = nullptr;   // backward with the weight gradient fused in: forward outputs h_t ...
   const float* wgrad_h0 = nullptr;      // ... h_0 ...
   float* dU = nullptr;                  // ... and the sums (selects the fused kernel; adds one step)
+  bool shared_exchange = false;      // ring and control words in the device's static array instead of the handle's own
 };
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const LaunchExtras& ex = LaunchExtras());
@@ -188,6 +214,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   }
   if (rc != SPRNN_OK) return rc;
 
+  (void)scratch_on_device(device_id);   // sprnn_forward_noalloc's array: address looked up once per device, here at set-up
   sprnn_handle_s* h = new (std::nothrow) sprnn_handle_s;
   if (!h) return SPRNN_ERR_CAPACITY;
   h->map = P.map;
@@ -305,13 +332,28 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
   const int t_max = (int)std::max<size_t>(1, ((size_t)1 << 30) / step_bytes);
   const size_t hb = (size_t)m.batch * m.hidden;
   if (ex.backward && T > t_max) return SPRNN_ERR_UNSUPPORTED;   // time runs backwards: one launch only
+  uint32_t* ring = h->d_ring;
+  uint32_t* ctrl = h->d_ctrl;
+  if (ex.shared_exchange) {
+    unsigned char* const base = scratch_on_device(h->device);
+    if (!base) return SPRNN_ERR_HIP;
+    ctrl = reinterpret_cast<uint32_t*>(base);
+    ring = reinterpret_cast<uint32_t*>(base + kScratchCtrlBytes);
+    h->used_shared_exchange = true;
+  }
   for (int t0 = 0; t0 < T; t0 += t_max) {
     const int tn = std::min(t_max, T - t0);
+    if (ex.shared_exchange) {
+      // the array keeps whatever the last call on this device left: every launch starts from a freshly marked ring and
+      // cleared control words, as a new handle would (a fill kernel, so that the call can be captured in a graph)
+      if (!SPRNN_HIP(launch_exchange_reset(ring, (size_t)m.h_bytes / 4, (size_t)m.cols * m.batch, kRingSlots, ctrl, kCtrlWords,
+                                           (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    }
     KernelArgs a;
     a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
     a.fill_src = h->d_fill_src; a.wg_plane = h->d_wg_plane; a.fill_rows = m.fill_rows;
     a.lds_h_bytes = m.grid == 1 ? m.lds_bytes / 2 : m.lds_bytes;
-    a.ring = h->d_ring; a.ctrl = h->d_ctrl;
+    a.ring = ring; a.ctrl = ctrl;
     a.x = x + (size_t)t0 * m.batch * m.rows;
     a.h0 = t0 ? h_out + (size_t)(t0 - 1) * hb : h0;
     a.c0 = t0 ? (c_out ? c_out + (size_t)(t0 - 1) * hb : nullptr) : c0;
@@ -325,7 +367,8 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.timeline = h->d_timeline;
     a.hidden = m.cols; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
-    a.step_base = h->step_base; a.barrier_base = h->barrier_base;
+    a.step_base = ex.shared_exchange ? 0u : h->step_base;
+    a.barrier_base = ex.shared_exchange ? 0u : h->barrier_base;
     void* args[] = {&a};
     // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
     const bool plain = m.plain_launch != 0 || m.grid == 1;
@@ -334,6 +377,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
                          : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
+    if (ex.shared_exchange) continue;   // (the handle's own ring did not move)
     const int ran = tn + ((ex.backward && (ex.dh0 || ex.dU)) ? 1 : 0);   // the backward pass adds the step that pairs delta_1 with h_0
     h->step_base += (uint32_t)ran;
     h->barrier_base += (uint32_t)(ran - 1);   // one barrier before every step but the first
@@ -393,6 +437,22 @@ int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, floa
   if (h->map.cell > SPRNN_ACT_IDENTITY) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
   return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream);
+}
+
+int sprnn_forward_noalloc(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream) {
+  if (!h || T < 0) return SPRNN_ERR_INVALID;
+  if (h->map.cell > SPRNN_ACT_IDENTITY) return SPRNN_ERR_UNSUPPORTED;
+  if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
+  // the ring of this layer must fit behind the control words of the static array
+  if ((size_t)kRingSlots * (size_t)h->map.h_bytes + kScratchCtrlBytes > kScratchBytes) {
+    static const bool verbose = std::getenv("SPRNN_DEBUG") != nullptr;
+    if (verbose) std::fprintf(stderr, "sprnn_forward_noalloc: exchange ring of %zu bytes exceeds the static limit of %zu bytes\n",
+                              (size_t)kRingSlots * (size_t)h->map.h_bytes, kScratchBytes - kScratchCtrlBytes);
+    return SPRNN_ERR_CAPACITY;
+  }
+  LaunchExtras ex;
+  ex.shared_exchange = true;
+  return forward_persistent(h, T, x, h0, nullptr, h_out, nullptr, stream, ex);
 }
 
 int sprnn_forward_lstm(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
@@ -658,6 +718,11 @@ int sprnn_check(sprnn_handle_t h) {
   if (hipDeviceSynchronize() != hipSuccess) return SPRNN_ERR_HIP;
   uint32_t status = 0;
   if (hipMemcpy(&status, h->d_ctrl + kCtrlStatus, 4, hipMemcpyDeviceToHost) != hipSuccess) return SPRNN_ERR_HIP;
+  if (!status && h->used_shared_exchange) {
+    // sprnn_forward_noalloc keeps its status word in the device's static array (cleared by every such call)
+    unsigned char* const base = scratch_on_device(h->device);
+    if (!base || hipMemcpy(&status, reinterpret_cast<uint32_t*>(base) + kCtrlStatus, 4, hipMemcpyDeviceToHost) != hipSuccess) return SPRNN_ERR_HIP;
+  }
   if (status) h->poisoned = true;
   return status ? SPRNN_ERR_STATE : SPRNN_OK;
 }

@@ -91,6 +91,11 @@ hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, 
                           hipStream_t stream);
 const void* weight_grad_kernel_for(int batch, int template_words);
 hipError_t launch_fill(uint32_t* dst, uint32_t value, size_t n, hipStream_t stream);
+// Put an exchange ring and its control words into the state a new handle starts from: the first `used_words` 32-bit
+// elements of each of the `slots` slots (of `slot_words` each) carry the "not written" mark, the rest of a slot is
+// zero, the control words are zero.
+hipError_t launch_exchange_reset(uint32_t* ring, size_t slot_words, size_t used_words, int slots, uint32_t* ctrl, int ctrl_words,
+                                 hipStream_t stream);
 
 }  // namespace sprnn
 #endif

@@ -1,5 +1,7 @@
 // Device code of libsprnn: the forward instantiations of the persistent kernel (sprnn_persistent.h), the weight
 // gradient kernel, the per-timestep comparison kernel and small helpers.
+#include <algorithm>
+
 #include "sprnn_persistent.h"
 
 namespace sprnn {
@@ -185,6 +187,12 @@ __global__ void fill_kernel(uint32_t* dst, uint32_t value, size_t n) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = value;
 }
 
+__global__ void exchange_reset_kernel(uint32_t* ring, size_t slot_words, size_t used_words, int slots, uint32_t* ctrl, int ctrl_words) {
+  const size_t first = blockIdx.x * (size_t)blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = first; i < slot_words * (size_t)slots; i += stride) ring[i] = (i % slot_words) < used_words ? kSentinelBits : 0u;
+  for (size_t i = first; i < (size_t)ctrl_words; i += stride) ctrl[i] = 0u;
+}
+
 // ------------------------------------------------------------------------------------------------
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline) {
   const int kind = cell == SPRNN_CELL_LSTM ? 1 : (cell == SPRNN_CELL_GRU ? 2 : 0);
@@ -244,6 +252,15 @@ hipError_t launch_fill(uint32_t* dst, uint32_t value, size_t n, hipStream_t stre
   const int block = 256;
   const int grid = (int)((n + block - 1) / block < 1024 ? (n + block - 1) / block : 1024);
   hipLaunchKernelGGL(fill_kernel, dim3(grid), dim3(block), 0, stream, dst, value, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_exchange_reset(uint32_t* ring, size_t slot_words, size_t used_words, int slots, uint32_t* ctrl, int ctrl_words,
+                                 hipStream_t stream) {
+  const size_t n = std::max(slot_words * (size_t)slots, (size_t)ctrl_words);
+  const int block = 256;
+  const int grid = (int)std::min<size_t>((n + block - 1) / block, 256);
+  hipLaunchKernelGGL(exchange_reset_kernel, dim3(std::max(grid, 1)), dim3(block), 0, stream, ring, slot_words, used_words, slots, ctrl, ctrl_words);
   return hipGetLastError();
 }
 
