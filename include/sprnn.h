@@ -7,6 +7,12 @@
  * allocates inside a forward call: all device storage it needs (packed weights, exchange ring,
  * status word) is allocated by sprnn_create and released by sprnn_destroy.
  *
+ * One HIP runtime per process: libsprnn.so links against libamdhip64.so.7 and uses whichever copy the process
+ * has already mapped.  A process that also uses another HIP client that ships its own runtime (PyTorch does)
+ * must load that client FIRST, so that the dynamic linker resolves libsprnn's dependency to the copy already
+ * in the process; streams and device pointers of one runtime are invalid in another.  The Python binding
+ * enforces this (it imports torch before loading the library and refuses to run with two runtimes mapped).
+ *
  * What is computed (paper, Section 3.1, Eq. 2):  h_t = g(U_r h_{t-1} + b'_t)  for t = 1..T, with
  * U_r the pruned recurrent weight matrix held in on-chip storage for the whole sequence
  * (Section 3.3) and b'_t = W x_t + b computed by the caller ahead of time (Eq. 1 -> Eq. 2).

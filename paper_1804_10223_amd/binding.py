@@ -64,15 +64,46 @@ class SprnnError(RuntimeError):
 _lib = None
 
 
+def hip_runtimes_mapped() -> set:
+    """Paths of the HIP runtime libraries (libamdhip64) mapped into this process."""
+    found = set()
+    try:
+        with open("/proc/self/maps") as f:
+            for line in f:
+                if "libamdhip64" in line:
+                    found.add(line.split()[-1])
+    except OSError:
+        pass
+    return found
+
+
+def load_with_one_runtime(path: str) -> ctypes.CDLL:
+    """dlopen a HIP library of this package so that the process keeps ONE HIP runtime (see load_library)."""
+    if not hip_runtimes_mapped():
+        import torch  # noqa: F401  (maps torch's bundled HIP runtime before the library asks for one)
+    lib = ctypes.CDLL(path)
+    runtimes = hip_runtimes_mapped()
+    if len(runtimes) > 1:
+        raise ImportError("two HIP runtimes are mapped into this process (%s): load %s after the runtime the "
+                          "application uses, e.g. import torch first" % (", ".join(sorted(runtimes)), os.path.basename(path)))
+    return lib
+
+
 def load_library() -> ctypes.CDLL:
-    """Load libsprnn.so from the package directory; fails loudly when it has not been built."""
+    """Load libsprnn.so from the package directory; fails loudly when it has not been built.
+
+    One HIP runtime per process: libsprnn.so depends on libamdhip64.so.7 and the dynamic linker gives it the copy the
+    process already holds.  PyTorch ships its own copy, and this binding hands torch's streams and device pointers to
+    the library, so torch has to be in the process first; with no runtime mapped yet it is imported here, and a process
+    that ends up with two different runtimes is refused.
+    """
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError("libsprnn.so is missing: build it with `python -m paper_1804_10223_amd.build` "
                           "(there is no fallback path)")
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = load_with_one_runtime(LIB_PATH)
     vp, ci = ctypes.c_void_p, ctypes.c_int
     i32p, u16p, u32pp, i32pp = (ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint16),
                                 ctypes.POINTER(ctypes.POINTER(ctypes.c_uint32)),

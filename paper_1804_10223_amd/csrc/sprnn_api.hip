@@ -234,11 +234,13 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   const int lds_need = m.lds_bytes + kLdsTailBytes + m.stage_bytes;      // h + the abort flags (+ the LSTM hand-over area)
   h->launch_lds = std::max(lds_need, lds_cu / 2 + 1024);
   if (h->launch_lds > lds_cu) { release(h); return SPRNN_ERR_CAPACITY; }
-  if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
+  // (the per-kernel limit on dynamic LDS is state shared by every handle that uses the same instantiation: it is
+  // always raised to the device's maximum, never set to one handle's own request)
+  if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
   if (m.cell <= SPRNN_ACT_IDENTITY && !m.timeline) {
     // the backward pass of a vanilla cell runs on a handle that holds the transposed matrix: same shape, same LDS
     h->kernel_bwd = persistent_kernel_for(m.batch, m.template_words, kCellBackward, false);
-    if (h->kernel_bwd && !SPRNN_HIP(hipFuncSetAttribute(h->kernel_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
+    if (h->kernel_bwd && !SPRNN_HIP(hipFuncSetAttribute(h->kernel_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
     // it spins on its neighbours like the forward kernel: usable only if the same grid is co-resident with it
     int per_cu_bwd = 0;
     if (h->kernel_bwd && (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_bwd, h->kernel_bwd, m.block, h->launch_lds)) ||
@@ -277,7 +279,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     int per_cu_g = 0;
     hipFuncAttributes fa;
     if (k && SPRNN_HIP(hipFuncGetAttributes(&fa, k)) && fa.maxThreadsPerBlock >= m.block &&
-        SPRNN_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds)) &&
+        SPRNN_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu)) &&
         SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_g, k, m.block, h->launch_lds)) &&
         m.grid <= per_cu_g * prop.multiProcessorCount) {
       ok = SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size()));
@@ -288,14 +290,14 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     // the weight gradient re-uses the forward mapping: one accumulator per packed word, left through this map
     h->kernel_wgrad = weight_grad_kernel_for(m.batch, m.template_words);
     ok = h->kernel_wgrad != nullptr && SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size())) &&
-         SPRNN_HIP(hipFuncSetAttribute(h->kernel_wgrad, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds));
+         SPRNN_HIP(hipFuncSetAttribute(h->kernel_wgrad, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu));
     if (ok && h->kernel_bwd && !m.timeline && m.cell <= SPRNN_ACT_IDENTITY) {
       // backward pass with the weight gradient fused in: same co-residency requirement as the plain one
       const void* k = persistent_kernel_for(m.batch, m.template_words, kCellBackwardGrad, false);
       int per_cu_g = 0;
       hipFuncAttributes fa;
       if (k && SPRNN_HIP(hipFuncGetAttributes(&fa, k)) && fa.maxThreadsPerBlock >= m.block &&
-          SPRNN_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, h->launch_lds)) &&
+          SPRNN_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu)) &&
           SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_g, k, m.block, h->launch_lds)) &&
           m.grid <= per_cu_g * prop.multiProcessorCount)
         h->kernel_bwd_grad = k;
@@ -582,6 +584,12 @@ int sprnn_backward(sprnn_handle_t h_transposed, int T, const float* dh_ext, cons
   if (!h || T < 0) return SPRNN_ERR_INVALID;
   if (h->map.cell > SPRNN_ACT_IDENTITY || !h->kernel_bwd) return SPRNN_ERR_UNSUPPORTED;
   if (T > 0 && (!dh_ext || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
+  if (T == 0) {   // nothing flows back
+    if (!dh0) return SPRNN_OK;
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return SPRNN_ERR_HIP;
+    return SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dh0), 0u, (size_t)h->map.batch * h->map.hidden, (hipStream_t)stream)) ? SPRNN_OK : SPRNN_ERR_HIP;
+  }
   LaunchExtras ex;
   ex.backward = true; ex.saved = h_fwd; ex.dh0 = dh0;
   return forward_persistent(h, T, dh_ext, nullptr, nullptr, d_bprime, nullptr, stream, ex);
@@ -594,10 +602,11 @@ int sprnn_backward_with_weights(sprnn_handle_t h_transposed, int T, const float*
   if (h->map.cell > SPRNN_ACT_IDENTITY || !h->kernel_bwd_grad || !h->d_word_src) return SPRNN_ERR_UNSUPPORTED;
   if (!dU_transposed && h->map.nnz > 0) return SPRNN_ERR_INVALID;
   if (T > 0 && (!dh_ext || !h_fwd || !d_bprime)) return SPRNN_ERR_INVALID;
-  if (T == 0) {   // nothing to sum
-    if (h->map.nnz == 0) return SPRNN_OK;
+  if (T == 0) {   // nothing to sum, nothing flows back
     DeviceGuard guard(h->device);
     if (!guard.ok) return SPRNN_ERR_HIP;
+    if (dh0 && !SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dh0), 0u, (size_t)h->map.batch * h->map.hidden, (hipStream_t)stream))) return SPRNN_ERR_HIP;
+    if (h->map.nnz == 0) return SPRNN_OK;
     return SPRNN_HIP(launch_fill(reinterpret_cast<uint32_t*>(dU_transposed), 0u, (size_t)h->map.nnz, (hipStream_t)stream)) ? SPRNN_OK : SPRNN_ERR_HIP;
   }
   LaunchExtras ex;

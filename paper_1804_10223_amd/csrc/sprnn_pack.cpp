@@ -313,8 +313,8 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
     }
   }
 
-  // --- column compaction (Section 6: "split a row among multiple blocks ... loading activations" dominates for
-  // very large, very sparse layers): a workgroup only copies the 16-byte chunks of h that its rows read, into
+  // --- column compaction (Section 6 names the loading of activations as what dominates for very large, very
+  // sparse layers, and proposes to give a block less than whole rows' worth of it): a workgroup only copies the 16-byte chunks of h that its rows read, into
   // consecutive LDS positions.  Used when the whole of h does not fit in LDS, or when every workgroup needs
   // less than half of it; otherwise LDS mirrors the ring slot.
   const int cpc = batch >= 4 ? 1 : 4 / batch;                 // columns per 16-byte chunk

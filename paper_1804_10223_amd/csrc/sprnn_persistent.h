@@ -257,9 +257,10 @@ __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)
       const int rem = n_w - k;
       if (GS == 8 && rem >= 4) {
         mac_words<B, 4, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
-        if (rem == 7) mac_words<B, 3, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk, side);
-        else if (rem == 6) mac_words<B, 2, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk, side);
-        else if (rem == 5) mac_words<B, 1, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk, side);
+        float* gk4 = GRAD ? gk + 4 : nullptr;   // the second half's sums belong to words k + 4 ..
+        if (rem == 7) mac_words<B, 3, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
+        else if (rem == 6) mac_words<B, 2, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
+        else if (rem == 5) mac_words<B, 1, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
       } else if (rem == 3) mac_words<B, 3, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
       else if (rem == 2) mac_words<B, 2, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
       else mac_words<B, 1, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);

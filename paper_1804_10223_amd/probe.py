@@ -16,7 +16,8 @@ def load_library() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError("libsprnn_probe.so is missing: build it with `python -m paper_1804_10223_amd.build`")
-        lib = ctypes.CDLL(LIB_PATH)
+        from .binding import load_with_one_runtime
+        lib = load_with_one_runtime(LIB_PATH)   # one HIP runtime per process
         ci, dp = ctypes.c_int, ctypes.POINTER(ctypes.c_double)
         lib.sprnn_probe_lds_gather.restype = ci
         lib.sprnn_probe_lds_gather.argtypes = [ci, ci, ci, ci, ci, dp]

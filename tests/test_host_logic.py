@@ -23,6 +23,21 @@ def test_library_exports_every_declared_symbol():
     assert "CSR" in binding.status_string(-1)
 
 
+def test_binding_keeps_one_hip_runtime_whatever_the_import_order():
+    # libsprnn.so depends on libamdhip64.so.7, PyTorch ships a copy of its own: a process must end up with exactly one,
+    # also when the binding is loaded (and even a handle-less library call made) before anybody imported torch
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_1804_10223_amd import binding, probe\n"
+            "assert 'torch' not in sys.modules\n"
+            "binding.load_library(); probe.load_library()\n"
+            "print(len(binding.hip_runtimes_mapped()))\n") % ROOT
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr
+    assert r.stdout.strip().splitlines()[-1] == "1", r.stdout + r.stderr
+
+
 def test_public_headers_are_plain_c(tmp_path):
     # the boundary is a C ABI: both headers must compile as C99 (and as C++) without any HIP or torch header
     import shutil
