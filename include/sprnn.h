@@ -86,7 +86,11 @@ typedef struct sprnn_options_s {
   int compact;       /* column compaction: a workgroup copies only the 16-byte pieces of h that its rows
                         read, into consecutive LDS positions.  0 auto (when all of h does not fit in
                         LDS, or every workgroup needs less than half of it), 1 on, 2 off            */
-  int reserved[3];
+  int layout;        /* how the lanes of a workgroup are given to rows (vanilla cells, more than one workgroup):
+                        0 auto, 1 = one power-of-two lane group per row, every wavefront does every stage,
+                        2 = lane pool: a row takes as many groups of `batch` lanes as its nonzeros need out of a
+                        pool of 4 or 7 gathering wavefronts, and separate wavefronts own b', g and the stores  */
+  int reserved[2];
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */
@@ -104,7 +108,9 @@ typedef struct sprnn_info_s {
   double lds_pass_factor;   /* LDS passes the packed gathers need / passes of a conflict-free layout
                                (1.0 = no bank conflicts), from the 64-bank, 256 B-per-pass model     */
   int compact;              /* 1 if column compaction is in use                                      */
-  int reserved[7];
+  int layout;               /* 1 = one lane group per row, 2 = lane pool (see sprnn_options_t.layout)   */
+  int gather_waves;         /* wavefronts per workgroup that hold weights (all of them for layout 1)    */
+  int reserved[5];
 } sprnn_info_t;
 
 /*

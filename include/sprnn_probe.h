@@ -28,6 +28,17 @@ int sprnn_probe_lds_gather(int device, int workgroups, int threads, int width_by
                            double* bytes_per_second);
 
 /*
+ * The same measurement with the caller's own read pattern: offsets (host) holds 16 x `threads` byte offsets into a 64 KB
+ * LDS array, offsets[k * threads + t] = address of thread t's k-th read (multiples of width_bytes, below 65536).  Every
+ * thread issues its 16 reads over and over; *bytes_per_second counts width_bytes per read.  bare = 1
+ * leaves everything but the reads out of the loop, so that the LDS alone bounds it (the default loop also adds the
+ * values up, which costs about as many issue cycles as conflict-free reads take).  Used to check the model of which lanes
+ * the LDS serves together (and hence which column orders collide) against packed weight images.
+ */
+int sprnn_probe_lds_gather_offsets(int device, int workgroups, int threads, int width_bytes, int bare, const uint32_t* offsets,
+                                   double* bytes_per_second);
+
+/*
  * One-way producer-store -> consumer-observes latency between two workgroups, by ping-pong on two
  * agent-coherent flags.  `same_xcd` = 1 picks two workgroups on one XCD, 0 two on different XCDs
  * (workgroups are dealt round-robin over the XCDs).  *nanoseconds = round trip / 2;

@@ -25,6 +25,7 @@ SPRNN_ERR_STATE = -5
 CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4, "lstm_backward": 5, "gru_backward": 6}
 GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
+LAYOUT = {"auto": 0, "row_groups": 1, "lane_pool": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_noalloc", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
            "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights", "sprnn_forward_gru_train",
@@ -38,7 +39,8 @@ class Options(ctypes.Structure):
     _fields_ = [("grid", ctypes.c_int), ("waves", ctypes.c_int), ("lanes_per_row", ctypes.c_int),
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
-                ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+                ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
+                ("reserved", ctypes.c_int * 2)]
 
 
 class Info(ctypes.Structure):
@@ -49,7 +51,8 @@ class Info(ctypes.Structure):
                 ("words_per_lane_max", ctypes.c_int), ("template_words", ctypes.c_int),
                 ("lds_bytes", ctypes.c_int), ("resident_capacity", ctypes.c_int),
                 ("nnz", ctypes.c_int64), ("padded_words", ctypes.c_int64), ("ring_bytes", ctypes.c_int64),
-                ("lds_pass_factor", ctypes.c_double), ("compact", ctypes.c_int), ("reserved", ctypes.c_int * 7)]
+                ("lds_pass_factor", ctypes.c_double), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
+                ("gather_waves", ctypes.c_int), ("reserved", ctypes.c_int * 5)]
 
     def as_dict(self) -> dict:
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
@@ -172,6 +175,8 @@ def make_options(**kw) -> Options:
     for k, v in kw.items():
         if k == "sync" and isinstance(v, str):
             v = SYNC[v]
+        if k == "layout" and isinstance(v, str):
+            v = LAYOUT[v]
         if not hasattr(o, k):
             raise TypeError("unknown option %r" % k)
         setattr(o, k, int(v))

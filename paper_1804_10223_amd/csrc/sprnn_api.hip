@@ -30,6 +30,7 @@ struct sprnn_handle_s {
   int32_t* d_wave_words = nullptr;
   uint32_t* d_fill_src = nullptr;    // column compaction only
   int32_t* d_wg_plane = nullptr;
+  int32_t* d_lane_sum = nullptr;     // lane-pool layout only
   int32_t* d_word_src = nullptr;     // vanilla cells without compaction: packed word -> CSR position (weight gradient)
   const void* kernel_wgrad = nullptr;
   uint32_t* d_ring = nullptr;
@@ -89,6 +90,8 @@ void fill_info(const Mapping& m, int capacity, double pass_factor, sprnn_info_t*
   info->ring_bytes = (int64_t)kRingSlots * m.h_bytes;
   info->lds_pass_factor = pass_factor;
   info->compact = m.compact;
+  info->layout = m.layout ? 2 : 1;
+  info->gather_waves = m.row_waves;
 }
 
 template <typename T>
@@ -103,7 +106,7 @@ hipError_t upload(T** dst, const T* src, size_t n) {
 void release(sprnn_handle_s* h) {
   if (!h) return;
   (void)hipFree(h->d_words); (void)hipFree(h->d_lane_row); (void)hipFree(h->d_wave_words);
-  (void)hipFree(h->d_fill_src); (void)hipFree(h->d_wg_plane); (void)hipFree(h->d_word_src);
+  (void)hipFree(h->d_fill_src); (void)hipFree(h->d_wg_plane); (void)hipFree(h->d_word_src); (void)hipFree(h->d_lane_sum);
   (void)hipFree(h->d_ring); (void)hipFree(h->d_ctrl); (void)hipFree(h->d_timeline);
   (void)hipFree(h->d_row_ptr); (void)hipFree(h->d_col); (void)hipFree(h->d_val);
   delete h;
@@ -213,6 +216,19 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     return SPRNN_ERR_CAPACITY;
   }
   if (rc != SPRNN_OK) return rc;
+  if (P.map.layout == 1 && !pool_kernel_for(P.map.batch, P.map.template_words, P.map.cell, P.map.timeline != 0)) {
+    // no lane-pool kernel is built for this many words per lane: the automatic choice takes the other layout
+    if (opt && opt->layout == 2) return SPRNN_ERR_UNSUPPORTED;
+    sprnn_options_t other = opt ? *opt : sprnn_options_t();
+    if (!opt) std::memset(&other, 0, sizeof(other));
+    other.layout = 1;
+    try {
+      rc = pack(hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, &other, prop.multiProcessorCount, &P);
+    } catch (const std::bad_alloc&) {
+      return SPRNN_ERR_CAPACITY;
+    }
+    if (rc != SPRNN_OK) return rc;
+  }
 
   (void)scratch_on_device(device_id);   // sprnn_forward_noalloc's array: address looked up once per device, here at set-up
   sprnn_handle_s* h = new (std::nothrow) sprnn_handle_s;
@@ -225,7 +241,8 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   h->num_cus = prop.multiProcessorCount;
   h->pass_factor = lds_pass_factor(P);
   const Mapping& m = h->map;
-  h->kernel = persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0);
+  const bool pool = m.layout == 1;
+  h->kernel = pool ? pool_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0) : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0);
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
@@ -239,7 +256,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
   if (m.cell <= SPRNN_ACT_IDENTITY && !m.timeline) {
     // the backward pass of a vanilla cell runs on a handle that holds the transposed matrix: same shape, same LDS
-    h->kernel_bwd = persistent_kernel_for(m.batch, m.template_words, kCellBackward, false);
+    h->kernel_bwd = pool ? pool_kernel_for(m.batch, m.template_words, kCellBackward) : persistent_kernel_for(m.batch, m.template_words, kCellBackward, false);
     if (h->kernel_bwd && !SPRNN_HIP(hipFuncSetAttribute(h->kernel_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
     // it spins on its neighbours like the forward kernel: usable only if the same grid is co-resident with it
     int per_cu_bwd = 0;
@@ -266,6 +283,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
             SPRNN_HIP(upload(&h->d_wave_words, P.wave_words.data(), P.wave_words.size())) &&
             (!m.compact || (SPRNN_HIP(upload(&h->d_fill_src, P.fill_src.data(), P.fill_src.size())) &&
                             SPRNN_HIP(upload(&h->d_wg_plane, P.wg_plane.data(), P.wg_plane.size())))) &&
+            (!pool || SPRNN_HIP(upload(&h->d_lane_sum, P.lane_sum.data(), P.lane_sum.size()))) &&
             SPRNN_HIP(upload(&h->d_ring, ring.data(), ring.size())) &&
             SPRNN_HIP(upload(&h->d_ctrl, ctrl.data(), ctrl.size())) &&
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
@@ -288,12 +306,16 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   }
   if (ok && (m.cell <= SPRNN_ACT_IDENTITY || m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU) && !m.compact) {
     // the weight gradient re-uses the forward mapping: one accumulator per packed word, left through this map
+    // (built for the word counts of the one-group-per-row layout; a lane-pool mapping with another count has none:
+    // sprnn_weight_gradient is then unsupported on this handle, the fused backward pass is the way)
     h->kernel_wgrad = weight_grad_kernel_for(m.batch, m.template_words);
-    ok = h->kernel_wgrad != nullptr && SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size())) &&
-         SPRNN_HIP(hipFuncSetAttribute(h->kernel_wgrad, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu));
+    ok = SPRNN_HIP(upload(&h->d_word_src, P.word_src.data(), P.word_src.size())) &&
+         (!h->kernel_wgrad || SPRNN_HIP(hipFuncSetAttribute(h->kernel_wgrad, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu)));
+    hipFuncAttributes wfa;   // (the instantiations with many words per lane are built for fewer threads than a lane-pool workgroup may have)
+    if (ok && h->kernel_wgrad && (!SPRNN_HIP(hipFuncGetAttributes(&wfa, h->kernel_wgrad)) || wfa.maxThreadsPerBlock < m.block)) h->kernel_wgrad = nullptr;
     if (ok && h->kernel_bwd && !m.timeline && m.cell <= SPRNN_ACT_IDENTITY) {
       // backward pass with the weight gradient fused in: same co-residency requirement as the plain one
-      const void* k = persistent_kernel_for(m.batch, m.template_words, kCellBackwardGrad, false);
+      const void* k = pool ? pool_kernel_for(m.batch, m.template_words, kCellBackwardGrad) : persistent_kernel_for(m.batch, m.template_words, kCellBackwardGrad, false);
       int per_cu_g = 0;
       hipFuncAttributes fa;
       if (k && SPRNN_HIP(hipFuncGetAttributes(&fa, k)) && fa.maxThreadsPerBlock >= m.block &&
@@ -354,6 +376,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     KernelArgs a;
     a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
     a.fill_src = h->d_fill_src; a.wg_plane = h->d_wg_plane; a.fill_rows = m.fill_rows;
+    a.lane_sum = h->d_lane_sum; a.gather_waves = m.row_waves;
     a.lds_h_bytes = m.grid == 1 ? m.lds_bytes / 2 : m.lds_bytes;
     a.ring = ring; a.ctrl = ctrl;
     a.x = x + (size_t)t0 * m.batch * m.rows;
@@ -367,6 +390,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.aux = ex.saved; a.dh0 = ex.dh0; a.bwd_h0 = ex.wgrad_h0; a.word_src = h->d_word_src; a.dU = ex.dU;
     a.side_src = ex.wgrad_h_fwd;
     a.timeline = h->d_timeline;
+    { const char* tw = std::getenv("SPRNN_TIMELINE_WAVE"); a.tl_wave = tw ? std::atoi(tw) : 0; }
     a.hidden = m.cols; a.T = tn; a.lanes_per_row = m.lanes_per_row; a.act = m.cell; a.h_bytes = m.h_bytes;
     a.index_shift = m.index_shift; a.jitter = m.jitter; a.poll_delay = m.poll_delay; a.spin_limit = m.spin_limit; a.sync = m.sync;
     a.step_base = ex.shared_exchange ? 0u : h->step_base;

@@ -28,6 +28,7 @@ struct KernelArgs {
   const int32_t* wave_words;  // [grid][waves]
   const uint32_t* fill_src;   // column compaction: [grid][fill_rows][block] copy list, or null
   const int32_t* wg_plane;    // column compaction: [grid] bytes of one plane of the workgroup's LDS copy
+  const int32_t* lane_sum;    // lane-pool layout: [grid][block] for an output lane: first group of its row | groups << 16
   uint32_t* ring;             // [4][h_bytes / 4]
   uint32_t* ctrl;             // [kCtrlWords]
   const float* x;             // [T][B][R]
@@ -49,6 +50,8 @@ struct KernelArgs {
   int fill_rows;              // rounds in the copy list (column compaction)
   int lds_h_bytes;            // bytes of one LDS copy of h (= h_bytes without column compaction)
   int jitter;                 // test aid: seed of pseudo-random pauses (0 = none)
+  int tl_wave;                // phase timeline: the wavefront of every workgroup that records it
+  int gather_waves;           // lane-pool layout: wavefronts of a workgroup that hold weights (the others own the outputs)
   int index_shift;            // LDS byte offset of a packed word = (word >> 16) << index_shift
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
   uint32_t barrier_base;      // grid barriers completed before this call (step t waits at barrier number barrier_base + t)
@@ -89,6 +92,7 @@ hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t 
 // b'[m][n] = sum_k x[m][k] W[n][k] + bias[n] (bias may be null); x [M][K] float32, w [N][K] binary16 bits, out [M][N] float32.
 hipError_t launch_project(const float* x, const uint16_t* w, const float* bias, float* out, int M, int N, int K,
                           hipStream_t stream);
+const void* pool_kernel_for(int batch, int template_words, int cell, bool timeline = false);                         // lane-pool layout: SPRNN_ACT_*, kCellBackward, kCellBackwardGrad
 const void* weight_grad_kernel_for(int batch, int template_words);
 hipError_t launch_fill(uint32_t* dst, uint32_t value, size_t n, hipStream_t stream);
 // Put an exchange ring and its control words into the state a new handle starts from: the first `used_words` 32-bit

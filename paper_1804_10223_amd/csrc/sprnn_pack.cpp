@@ -48,10 +48,36 @@ int validate_csr(int hidden, int batch, int cell, const int32_t* row_ptr, const 
   return SPRNN_OK;
 }
 
-// Lanes that one LDS pass serves together, and the number of bank groups a gather of this width can
-// hit, on gfx950: 64 banks x 4 B = 256 B per pass, so a 16-byte gather serves 16 lanes per pass over 16
-// groups, an 8-byte gather 32 over 32, a 4-byte gather 64 over 64.
-static int pass_lanes(int batch) { return batch >= 4 ? 16 : (batch == 2 ? 32 : 64); }
+// Which lanes of a wavefront the LDS of gfx950 serves together in one pass of a gather, and how many bank classes a
+// gather of that width can fall into (64 banks x 4 bytes = 256 bytes per pass), as measured with pairs of lanes that
+// read different addresses of one class (sprnn_probe_lds_gather_offsets):
+//   16-byte reads: four passes of 16 lanes.  A half of the wavefront (32 lanes = 8 groups of four lanes) is served as the
+//                  groups {0, 3, 5, 6} and then {1, 2, 4, 7}: the order in which 64 consecutive 16-byte pieces fall into
+//                  all 64 banks twice over.  16 classes (column mod 16).
+//   8-byte reads:  two passes, the lower and the upper 32 lanes; 32 classes.
+//   4-byte reads:  the same two passes; 64 classes (a 4-byte gather runs at half the bytes per clock of the wider ones).
+// Lanes of a pass that read different addresses of one class serialise; the same address is served once.
+struct PassModel {
+  int npass = 0, classes = 0;
+  int pass_of[kWave];
+  std::vector<int> lanes[4];
+};
+static PassModel make_pass_model(int batch) {
+  PassModel pm;
+  pm.npass = batch >= 4 ? 4 : 2;
+  pm.classes = batch >= 4 ? 16 : (batch == 2 ? 32 : 64);
+  for (int lane = 0; lane < kWave; ++lane) {
+    int p = lane / 32;
+    if (batch >= 4) {
+      const int quad = (lane % 32) / 4;
+      const bool first = quad == 0 || quad == 3 || quad == 5 || quad == 6;
+      p = (lane / 32) * 2 + (first ? 0 : 1);
+    }
+    pm.pass_of[lane] = p;
+    pm.lanes[p].push_back(lane);
+  }
+  return pm;
+}
 
 static int choose_mapping(int hidden, int batch, int cell, const std::vector<int>& row_nnz, const sprnn_options_t* opt,
                           int num_cus, Mapping* m) {
@@ -166,26 +192,37 @@ struct RowGroup {
 //
 // Bank-aware ordering (Section 4.1; Appendix A gives one greedy way for 32 banks, this is another for the
 // same goal on this LDS).  All the hardware cares about is which columns are read together in one LDS pass:
-// a pass serves `groups` consecutive lanes of one gather instruction (= one slot k) and takes as many
-// cycles as the largest number of different addresses that fall into one bank group (class = column mod
-// groups).  A nonzero may sit in any slot and any lane of its own row, so the nonzeros are dealt class by
+// a pass serves a fixed set of lanes of one gather instruction (= one slot k; see PassModel) and takes as many
+// cycles as the largest number of different addresses that fall into one bank class (column mod classes).
+// A nonzero may sit in any slot and any lane of its own row, so the nonzeros are dealt class by
 // class (largest class first) to the pass, among those that contain lanes of the row and still have room,
 // where they add no cycle, else to the emptiest one.  Surplus nonzeros of over-full classes thereby pile
 // into the same few passes, and a row that owns whole passes reaches max(largest class, passes) cycles,
-// the lower bound.  Rows that share a pass (L < groups) are scheduled against the same pass state.
-// LDS cycles one wavefront needs for its `trip` gathers under the pass model above.
-static int64_t wave_cycles(const std::vector<RowGroup>& rg, int L, int trip, int groups) {
+// the lower bound.  Rows that share a pass are scheduled against the same pass state.
+// A run of lanes of one wavefront that holds (part of) one row.
+namespace {
+struct Seg {
+  int lane0 = 0, n = 0;       // lanes [lane0, lane0 + n) of the wavefront
+  int row = -1;
+  int first = 0;              // CSR position of items[0]
+  std::vector<Nz> items;      // the part of the row held by these lanes, in CSR order
+  std::vector<int> pos;       // [trip * n] slot k, lane j -> index into items, -1 = filler
+};
+}  // namespace
+
+// LDS cycles one wavefront needs for its `trip` gathers under the pass model.
+static int64_t segs_cycles(const std::vector<Seg>& segs, int trip, const PassModel& pm) {
   int64_t total = 0;
-  std::vector<std::vector<int32_t>> seen(groups);
+  std::vector<std::vector<int32_t>> seen(pm.classes);
   for (int k = 0; k < trip; ++k)
-    for (int base = 0; base < kWave; base += groups) {
+    for (int p = 0; p < pm.npass; ++p) {
       for (auto& v : seen) v.clear();
-      for (const RowGroup& q : rg)
-        for (int l = 0; l < L; ++l) {
-          if (q.lane0 + l < base || q.lane0 + l >= base + groups) continue;
-          const int i = q.pos[(size_t)k * L + l];
-          if (i < 0) continue;   // fillers are given a free bank group afterwards
-          auto& v = seen[q.items[i].col % groups];
+      for (const Seg& q : segs)
+        for (int j = 0; j < q.n; ++j) {
+          if (pm.pass_of[q.lane0 + j] != p) continue;
+          const int i = q.pos[(size_t)k * q.n + j];
+          if (i < 0) continue;   // fillers are given a free bank class afterwards
+          auto& v = seen[q.items[i].col % pm.classes];
           if (std::find(v.begin(), v.end(), q.items[i].col) == v.end()) v.push_back(q.items[i].col);
         }
       size_t worst = 1;
@@ -195,69 +232,308 @@ static int64_t wave_cycles(const std::vector<RowGroup>& rg, int L, int trip, int
   return total;
 }
 
-static void order_wave(std::vector<RowGroup>& rg, int L, int trip, int groups, bool bank_aware) {
-  for (auto& g : rg) g.pos.assign((size_t)trip * L, -1);
-  if (trip == 0) return;
-  // CSR order: nonzero i -> lane i % L, slot i / L
-  for (auto& g : rg)
-    for (int i = 0; i < (int)g.items.size(); ++i) g.pos[i] = i;
-  if (!bank_aware) return;
-  const int64_t csr_cycles = wave_cycles(rg, L, trip, groups);
-  std::vector<std::vector<int>> csr_pos(rg.size());
-  for (size_t q = 0; q < rg.size(); ++q) { csr_pos[q] = rg[q].pos; rg[q].pos.assign((size_t)trip * L, -1); }
-  const int pgs = kWave / groups;                  // pass groups per gather instruction
-  const int P = trip * pgs;                        // passes of this wavefront: p = k * pgs + pg
-  std::vector<int> pass_cycles(P, 0), pass_load(P, 0);
-  std::vector<int> mult((size_t)P * groups, 0);
-  const int sub = std::max(1, L / groups);         // pass groups one row spans
-  const int cap = std::min(L, groups);             // lanes of one row inside one pass
-  // per row and pass: how many of the row's lanes are already taken
-  std::vector<std::vector<int>> taken(rg.size(), std::vector<int>((size_t)trip * sub, 0));
-  std::vector<std::vector<std::vector<int>>> bucket(rg.size(), std::vector<std::vector<int>>(groups));
-  std::vector<int64_t> class_total(groups, 0);
-  for (size_t q = 0; q < rg.size(); ++q)
-    for (int i = (int)rg[q].items.size() - 1; i >= 0; --i) {
-      bucket[q][rg[q].items[i].col % groups].push_back(i);
-      class_total[rg[q].items[i].col % groups] += 1;
+static void order_segments(std::vector<Seg>& segs, int trip, const PassModel& pm, bool bank_aware) {
+  for (auto& q : segs) {
+    q.pos.assign((size_t)trip * q.n, -1);
+    for (int i = 0; i < (int)q.items.size(); ++i) q.pos[i] = i;   // CSR order: item i -> lane i % n, slot i / n
+  }
+  if (!bank_aware || trip == 0) return;
+  const int64_t csr_cycles = segs_cycles(segs, trip, pm);
+  std::vector<std::vector<int>> csr_pos(segs.size());
+  for (size_t q = 0; q < segs.size(); ++q) { csr_pos[q] = segs[q].pos; segs[q].pos.assign((size_t)trip * segs[q].n, -1); }
+  const int classes = pm.classes, np = pm.npass;
+  const int P = trip * np;                         // passes of this wavefront: index k * np + p
+  std::vector<int> pass_cycles(P, 0), pass_load(P, 0), mult((size_t)P * classes, 0);
+  std::vector<int64_t> class_total(classes, 0);
+  std::vector<std::vector<std::vector<int>>> bucket(segs.size(), std::vector<std::vector<int>>(classes));
+  std::vector<std::vector<int>> taken(segs.size());
+  std::vector<std::vector<std::vector<int>>> mine(segs.size(), std::vector<std::vector<int>>(np));   // lanes of a segment (as offsets into it) per pass
+  for (size_t q = 0; q < segs.size(); ++q) {
+    taken[q].assign((size_t)trip * np, 0);
+    for (int j = 0; j < segs[q].n; ++j) mine[q][pm.pass_of[segs[q].lane0 + j]].push_back(j);
+    for (int i = (int)segs[q].items.size() - 1; i >= 0; --i) {
+      bucket[q][segs[q].items[i].col % classes].push_back(i);
+      class_total[segs[q].items[i].col % classes] += 1;
     }
-  std::vector<int> order(groups);
+  }
+  std::vector<int> order(classes);
   std::iota(order.begin(), order.end(), 0);
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return class_total[a] > class_total[b]; });
   for (int g : order)
-    for (size_t q = 0; q < rg.size(); ++q) {
-      const int pg0 = rg[q].lane0 / groups;
+    for (size_t q = 0; q < segs.size(); ++q) {
+      const Seg& sg = segs[q];
       while (!bucket[q][g].empty()) {
-        int best_k = -1, best_s = 0, best_cost = 0, best_load = 0;
+        int best_k = -1, best_p = 0, best_cost = 0, best_load = 0;
         for (int k = 0; k < trip; ++k)
-          for (int sidx = 0; sidx < sub; ++sidx) {
-            if (taken[q][(size_t)k * sub + sidx] >= cap) continue;
-            const int p = k * pgs + pg0 + sidx;
-            const int cost = (mult[(size_t)p * groups + g] + 1 > pass_cycles[p]) ? 1 : 0;
-            if (best_k < 0 || cost < best_cost || (cost == best_cost && pass_load[p] < best_load)) {
-              best_k = k; best_s = sidx; best_cost = cost; best_load = pass_load[p];
+          for (int p = 0; p < np; ++p) {
+            if (taken[q][(size_t)k * np + p] >= (int)mine[q][p].size()) continue;
+            const int at = k * np + p;
+            const int cost = (mult[(size_t)at * classes + g] + 1 > pass_cycles[at]) ? 1 : 0;
+            if (best_k < 0 || cost < best_cost || (cost == best_cost && pass_load[at] < best_load)) {
+              best_k = k; best_p = p; best_cost = cost; best_load = pass_load[at];
             }
           }
-        // the row has at most trip * L nonzeros, so a free lane always exists
-        const int i = bucket[q][g].back();
+        const int i = bucket[q][g].back();   // (a segment never holds more than trip * n nonzeros: a free lane exists)
         bucket[q][g].pop_back();
-        const int p = best_k * pgs + pg0 + best_s;
-        int& used = taken[q][(size_t)best_k * sub + best_s];
-        rg[q].pos[(size_t)best_k * L + best_s * groups + used] = i;
+        const int at = best_k * np + best_p;
+        int& used = taken[q][(size_t)best_k * np + best_p];
+        segs[q].pos[(size_t)best_k * sg.n + mine[q][best_p][used]] = i;
         used += 1;
-        pass_load[p] += 1;
-        const int mcount = ++mult[(size_t)p * groups + g];
-        pass_cycles[p] = std::max(pass_cycles[p], mcount);
+        pass_load[at] += 1;
+        const int mcount = ++mult[(size_t)at * classes + g];
+        pass_cycles[at] = std::max(pass_cycles[at], mcount);
       }
     }
   // the greedy deal is not optimal when many short rows share a pass: never do worse than CSR order
-  if (wave_cycles(rg, L, trip, groups) > csr_cycles)
-    for (size_t q = 0; q < rg.size(); ++q) rg[q].pos = csr_pos[q];
+  if (segs_cycles(segs, trip, pm) > csr_cycles)
+    for (size_t q = 0; q < segs.size(); ++q) segs[q].pos = csr_pos[q];
+}
+
+// Place the nonzeros of all rows of one wavefront of the one-group-per-row layout: every row group is one segment.
+static void order_wave(std::vector<RowGroup>& rg, int L, int trip, const PassModel& pm, bool bank_aware) {
+  std::vector<Seg> segs(rg.size());
+  for (size_t q = 0; q < rg.size(); ++q) { segs[q].lane0 = rg[q].lane0; segs[q].n = L; segs[q].row = rg[q].row; segs[q].items = rg[q].items; }
+  order_segments(segs, trip, pm, bank_aware);
+  for (size_t q = 0; q < rg.size(); ++q) rg[q].pos = std::move(segs[q].pos);
+}
+
+// Filler words should not add bank conflicts: give each one a column whose bank group is still free in
+// its pass (or, failing that, an address that another lane of the pass already reads: a broadcast).
+static void place_fillers(Packed& P, const std::vector<int>& wg_cols, const std::vector<char>& is_real_zero) {
+  const Mapping& m = P.map;
+  const int NW = m.template_words;
+  const PassModel pm = make_pass_model(m.batch);
+  const int classes = pm.classes;
+  for (int wg = 0; wg < m.grid; ++wg)
+    for (int wave = 0; wave < m.waves; ++wave) {
+      const int trip = P.wave_words[(size_t)wg * m.waves + wave];
+      for (int k = 0; k < trip; ++k)
+        for (int p = 0; p < pm.npass; ++p) {
+          std::vector<char> used(classes, 0);
+          const size_t base = ((size_t)wg * NW + k) * m.block + (size_t)wave * kWave;
+          std::vector<int> fillers;
+          uint32_t some_addr = 0; bool have_addr = false;
+          for (int l : pm.lanes[p]) {
+            const uint32_t w = P.words[base + l];
+            if ((w & 0x7FFFu) == 0) { fillers.push_back(l); continue; }   // zero value: a filler, or a stored zero (kept below)
+            used[((w >> 16) << m.index_shift) / m.col_stride % classes] = 1;
+            some_addr = w >> 16; have_addr = true;
+          }
+          int g = 0;
+          for (int l : fillers) {
+            if (is_real_zero[base + l]) {
+              used[((P.words[base + l] >> 16) << m.index_shift) / m.col_stride % classes] = 1;
+              continue;
+            }
+            while (g < classes && (used[g] || g >= wg_cols[wg])) ++g;
+            if (g < classes) {
+              P.words[base + l] = (uint32_t)(((uint32_t)g * (uint32_t)m.col_stride) >> m.index_shift) << 16;
+              used[g] = 1;
+            } else {
+              P.words[base + l] = have_addr ? (some_addr << 16) : 0u;
+            }
+          }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Lane-pool layout (vanilla cells, more than one workgroup).
+//
+// The gathering wavefronts of a workgroup form one pool of lanes.  A row takes as many GROUPS of `batch` lanes as its
+// nonzeros need at NW words per lane, anywhere in the pool (groups of one row are consecutive and may straddle
+// wavefronts); all words of a lane still belong to one row (Section 3.3), and a ragged matrix balances by itself
+// because a longer row simply takes more groups (Section 6's load balancing by nonzero count, without sorting rows).
+// The lanes of a group reduce among themselves (one sample per lane), the group sums meet in LDS, and OUTPUT lanes in
+// separate wavefronts (lane e -> row e / batch of the workgroup, sample e % batch) add them up, add b', apply g and do
+// every store.  The gathering wavefronts therefore issue no global memory operation but the polls of the exchange
+// ring, so that no poll ever queues behind a store or a b' fetch of its own wavefront.
+// Returns SPRNN_OK, or SPRNN_ERR_CAPACITY when the matrix does not suit this layout (the caller then uses the other one).
+static int pack_pool(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
+                     const uint16_t* val_bits, const sprnn_options_t* opt, int num_cus, Packed* out) {
+  const int rows = hidden, cols = hidden, G = batch;
+  const int64_t nnz = row_ptr[rows];
+  if (num_cus < 1) return SPRNN_ERR_INVALID;
+  if (opt && (opt->compact == 1 || opt->lanes_per_row || opt->fill_waves || opt->balance == 1)) return SPRNN_ERR_CAPACITY;
+  constexpr int kMaxWavesPool = 8;      // gathering + output wavefronts of one workgroup (512 threads: 256 registers per lane)
+  constexpr int64_t kRowCost = 8;       // what an (even empty) row adds to a workgroup's share besides its nonzeros
+  const int max_rows_wg = (kMaxWavesPool - 4) * kWave / batch;   // output lanes for them must fit beside four gathering wavefronts
+
+  // --- workgroups: enough of them that the gathers of a step are short, few enough that every one has work
+  int grid = opt ? opt->grid : 0;
+  if (grid < 0) return SPRNN_ERR_INVALID;
+  if (!grid) {
+    const int64_t by_work = (nnz + 2047) / 2048;
+    const int64_t by_rows = ((int64_t)rows + max_rows_wg / 2 - 1) / (max_rows_wg / 2);
+    grid = (int)std::max<int64_t>(2, std::min<int64_t>(num_cus, std::max(by_work, by_rows)));
+  }
+  if (grid < 2 || grid > rows) return SPRNN_ERR_CAPACITY;
+  // contiguous rows per workgroup (whole cache lines of the ring per producer), shares balanced by nonzero count
+  std::vector<int> first_row(grid + 1, rows);
+  {
+    std::vector<int64_t> cum((size_t)rows + 1, 0);
+    for (int r = 0; r < rows; ++r) cum[r + 1] = cum[r] + (row_ptr[r + 1] - row_ptr[r]) + kRowCost;
+    first_row[0] = 0;
+    for (int i = 1; i < grid; ++i) {
+      const int64_t target = cum[rows] * i / grid;
+      int r = (int)(std::lower_bound(cum.begin(), cum.end(), target) - cum.begin());   // smallest r with cum[r] >= target
+      if (r > 0 && target - cum[r - 1] < cum[r] - target) --r;                          // ... or the boundary just below, if nearer
+      r = std::max(r, first_row[i - 1] + 1);                                            // every workgroup owns a row
+      r = std::min(r, rows - (grid - i));
+      first_row[i] = r;
+    }
+  }
+  int rows_wg_max = 0;
+  for (int wg = 0; wg < grid; ++wg) rows_wg_max = std::max(rows_wg_max, first_row[wg + 1] - first_row[wg]);
+  const int epi_waves = std::max(1, ceil_div((int64_t)rows_wg_max * batch, kWave));
+
+  // --- gathering wavefronts and words per lane: the smallest NW per workgroup for which its rows' groups fit in the pool
+  auto words_needed = [&](int wg, int W) -> int {   // 0 = does not fit at any NW
+    const int pool_groups = W * kWave / G;
+    int64_t wg_nnz = row_ptr[first_row[wg + 1]] - row_ptr[first_row[wg]];
+    for (int nw = std::max<int64_t>(1, ceil_div(wg_nnz, (int64_t)W * kWave)); nw <= kTemplateWords[kNumTemplateWords - 1]; ++nw) {
+      int64_t need = 0;
+      for (int r = first_row[wg]; r < first_row[wg + 1] && need <= pool_groups; ++r) need += ceil_div(row_ptr[r + 1] - row_ptr[r], (int64_t)nw * G);
+      if (need <= pool_groups) return nw;
+    }
+    return 0;
+  };
+  int W = 0, words_max = 0;
+  std::vector<int> nw_wg(grid, 1);
+  {
+    int64_t best_cost = 0;
+    const int forced = opt ? opt->waves : 0;
+    for (int cand : {4, 7}) {
+      if (forced && forced != cand) continue;
+      if (cand + epi_waves > kMaxWavesPool) continue;
+      int worst = 0;
+      bool fits = true;
+      std::vector<int> nws(grid);
+      for (int wg = 0; wg < grid && fits; ++wg) { nws[wg] = words_needed(wg, cand); fits = nws[wg] > 0; worst = std::max(worst, nws[wg]); }
+      if (!fits) continue;
+      // multiply-add issue slots per SIMD and step ~ (wavefronts per SIMD) x words, plus what every wavefront spends around them
+      const int64_t cost = (int64_t)(cand == 4 ? 1 : 2) * (4 * worst + 12);
+      if (!W || cost < best_cost) { W = cand; best_cost = cost; nw_wg = nws; words_max = worst; }
+    }
+    if (forced && forced != 4 && forced != 7) return SPRNN_ERR_INVALID;
+  }
+  if (!W) return SPRNN_ERR_CAPACITY;
+  const int tw = std::max(4, (words_max + 3) / 4 * 4);   // the lane-pool kernels are built for every multiple of four up to 64
+  if (tw > 64) return SPRNN_ERR_CAPACITY;
+
+  Mapping m;
+  m.hidden = hidden; m.rows = rows; m.batch = batch; m.cell = cell; m.cols = cols;
+  m.col_stride = 4 * std::min(batch, 4);
+  const int64_t plane = (int64_t)cols * m.col_stride;
+  const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
+  m.grid = grid; m.row_waves = W; m.waves = W + epi_waves; m.block = m.waves * kWave; m.lanes_per_row = G; m.group = G;
+  m.layout = 1;
+  m.template_words = tw;
+  m.stage_bytes = batch * (W * kWave / G) * 4 + 64;   // group sums [sample][group] (+ room for reads past a short row)
+  if (hb * kRingSlots > ((int64_t)1 << 30)) return SPRNN_ERR_CAPACITY;
+  m.h_bytes = (int)hb;
+  if (hb + 256 + m.stage_bytes > kLdsLimit) return SPRNN_ERR_CAPACITY;   // h has to fit in LDS whole (no column compaction here)
+  m.lds_bytes = (int)hb;
+  m.compact = 0; m.fill_rows = 0;
+  m.index_shift = 0;
+  if (plane > 65536) { while ((1 << m.index_shift) < m.col_stride) ++m.index_shift; }
+  m.nnz = nnz;
+  m.sync = (opt && opt->sync) ? opt->sync : SPRNN_SYNC_TAGGED;
+  if (m.sync != SPRNN_SYNC_TAGGED && m.sync != SPRNN_SYNC_BARRIER) return SPRNN_ERR_INVALID;
+  m.bank_aware = (opt && opt->bank_aware) ? opt->bank_aware : 1;
+  if (m.bank_aware != 1 && m.bank_aware != 2) return SPRNN_ERR_INVALID;
+  m.balance = 2;
+  m.poll_delay = opt ? opt->poll_delay : 0;
+  m.spin_limit = (opt && opt->spin_limit > 0) ? opt->spin_limit : (1 << 22);
+  m.timeline = (opt && opt->timeline) ? 1 : 0;
+  m.plain_launch = (opt && opt->plain_launch) ? 1 : 0;
+  m.jitter = opt ? opt->jitter : 0;
+
+  Packed& P = *out;
+  P = Packed();
+  P.map = m;
+  const int NW = tw;
+  const size_t lanes = (size_t)grid * m.block;
+  P.words.assign(lanes * NW, 0u);
+  P.word_src.assign(lanes * NW, -1);
+  P.lane_row.assign(lanes, -1);
+  P.lane_words.assign(lanes, 0);
+  P.lane_sum.assign(lanes, 0);
+  P.wave_words.assign((size_t)grid * m.waves, 0);
+  std::vector<char> is_real_zero(P.words.size(), 0);
+  const PassModel pm = make_pass_model(batch);
+  int64_t padded = 0;
+  int used_words_max = 0;
+  std::vector<std::vector<Seg>> wave_segs(W);
+  for (int wg = 0; wg < grid; ++wg) {
+    for (auto& v : wave_segs) v.clear();
+    int lane = 0;                                   // next free lane of the pool
+    for (int r = first_row[wg]; r < first_row[wg + 1]; ++r) {
+      const int n = row_ptr[r + 1] - row_ptr[r];
+      const int ng = ceil_div(n, (int64_t)nw_wg[wg] * G), nl = ng * G;
+      const int e = (r - first_row[wg]) * batch;    // first output lane of the row
+      for (int b = 0; b < batch; ++b) {
+        const size_t at = (size_t)wg * m.block + (size_t)W * kWave + e + b;
+        P.lane_row[at] = r;
+        P.lane_sum[at] = (lane / G) | (ng << 16);
+      }
+      if (!nl) continue;
+      const int wpl = ceil_div(n, nl);              // words per lane of this row (<= the workgroup's NW)
+      int given = 0;
+      for (int l0 = lane; l0 < lane + nl;) {        // one segment per wavefront the row touches
+        const int wave = l0 / kWave, l1 = std::min(lane + nl, (wave + 1) * kWave);
+        Seg q;
+        q.lane0 = l0 % kWave; q.n = l1 - l0; q.row = r;
+        const int take = std::min(n - given, q.n * wpl);
+        q.first = row_ptr[r] + given;
+        for (int i = 0; i < take; ++i) q.items.push_back({col_idx[q.first + i], val_bits[q.first + i]});
+        given += take;
+        wave_segs[wave].push_back(std::move(q));
+        P.wave_words[(size_t)wg * m.waves + wave] = std::max(P.wave_words[(size_t)wg * m.waves + wave], wpl);
+        l0 = l1;
+      }
+      lane += nl;
+    }
+    for (int wave = 0; wave < W; ++wave) {
+      const int trip = P.wave_words[(size_t)wg * m.waves + wave];
+      used_words_max = std::max(used_words_max, trip);
+      padded += (int64_t)trip * kWave;
+      order_segments(wave_segs[wave], trip, pm, m.bank_aware == 1);
+      for (const Seg& q : wave_segs[wave]) {
+        const size_t tid0 = (size_t)wg * m.block + (size_t)wave * kWave + q.lane0;
+        for (int j = 0; j < q.n; ++j) P.lane_row[tid0 + j] = q.row;
+        for (int k = 0; k < trip; ++k)
+          for (int j = 0; j < q.n; ++j) {
+            const size_t at = ((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + q.lane0 + j;
+            const int i = q.pos[(size_t)k * q.n + j];
+            if (i < 0) continue;                   // stays a zero word; place_fillers gives it a harmless column
+            const uint32_t idx = ((uint32_t)q.items[i].col * (uint32_t)m.col_stride) >> m.index_shift;
+            P.words[at] = (idx << 16) | q.items[i].bits;
+            P.word_src[at] = q.first + i;
+            if ((q.items[i].bits & 0x7FFFu) == 0) is_real_zero[at] = 1;
+            P.lane_words[tid0 + j] += 1;
+          }
+      }
+    }
+  }
+  std::vector<int> wg_cols(grid, cols);
+  place_fillers(P, wg_cols, is_real_zero);
+  P.map.words_max = used_words_max;
+  P.map.padded_words = padded;
+  return SPRNN_OK;
 }
 
 int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t* col_idx,
          const uint16_t* val_bits, const sprnn_options_t* opt, int num_cus, Packed* out) {
   int rc = validate_csr(hidden, batch, cell, row_ptr, col_idx, val_bits);
   if (rc != SPRNN_OK) return rc;
+  const int layout = opt ? opt->layout : 0;
+  if (layout < 0 || layout > 2) return SPRNN_ERR_INVALID;
+  if (layout == 2 && cell > SPRNN_ACT_IDENTITY) return SPRNN_ERR_UNSUPPORTED;
+  if (cell <= SPRNN_ACT_IDENTITY && layout == 2) {
+    rc = pack_pool(hidden, batch, cell, row_ptr, col_idx, val_bits, opt, num_cus, out);
+    if (rc != SPRNN_ERR_CAPACITY || layout == 2) return rc;   // (auto: a matrix that does not suit the pool takes the other layout)
+  }
   const bool lstm = gated(cell);
   const int rows = hidden * (lstm ? 4 : 1);
   // the GRU's three row blocks become four with an empty last one
@@ -401,10 +677,10 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   P.lane_words.assign(lanes, 0);
   P.wave_words.assign(total_waves, 0);
 
-  const int groups = pass_lanes(batch);
+  const PassModel pm = make_pass_model(batch);
   auto pad_word = [&](int lane_in_wave, int k, int ncols) -> uint32_t {
-    // zero-valued filler that reads the bank group this lane would ideally hit
-    int col = (lane_in_wave + k * L) % groups;
+    // zero-valued filler (place_fillers gives it a bank class that is free in its pass afterwards)
+    int col = (lane_in_wave + k * L) % pm.classes;
     if (col >= ncols) col = 0;
     return (uint32_t)(((uint32_t)col * (uint32_t)m.col_stride) >> m.index_shift) << 16;
   };
@@ -444,7 +720,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
         rg.push_back(std::move(q));
       }
     }
-    order_wave(rg, L, trip, groups, m.bank_aware == 1);
+    order_wave(rg, L, trip, pm, m.bank_aware == 1);
     for (const RowGroup& q : rg) {
       const size_t tid0 = (size_t)wg * m.block + (size_t)wave * kWave + q.lane0;
       for (int l = 0; l < L; ++l) P.lane_row[tid0 + l] = q.row < m.rows ? q.row : -1;   // the GRU's empty fourth row owns nothing
@@ -461,63 +737,31 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
         }
     }
   }
-  // Filler words should not add bank conflicts: give each one a column whose bank group is still free in
-  // its pass (or, failing that, an address that another lane of the pass already reads: a broadcast).
-  for (int wg = 0; wg < m.grid; ++wg)
-    for (int wave = 0; wave < m.waves; ++wave) {
-      const int trip = P.wave_words[(size_t)wg * m.waves + wave];
-      for (int k = 0; k < trip; ++k)
-        for (int base = 0; base < kWave; base += groups) {
-          std::vector<char> used(groups, 0);
-          uint32_t* wp = &P.words[((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + base];
-          std::vector<int> fillers;
-          uint32_t some_addr = 0; bool have_addr = false;
-          for (int l = 0; l < groups; ++l) {
-            const uint32_t w = wp[l];
-            if ((w & 0x7FFFu) == 0) { fillers.push_back(l); continue; }   // zero value: a filler, or a stored zero (kept below)
-            used[((w >> 16) << m.index_shift) / m.col_stride % groups] = 1;
-            some_addr = w >> 16; have_addr = true;
-          }
-          int g = 0;
-          for (int l : fillers) {
-            if (is_real_zero[((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + base + l]) {
-              used[((wp[l] >> 16) << m.index_shift) / m.col_stride % groups] = 1;
-              continue;
-            }
-            while (g < groups && (used[g] || g >= wg_cols[wg])) ++g;
-            if (g < groups) {
-              wp[l] = (uint32_t)(((uint32_t)g * (uint32_t)m.col_stride) >> m.index_shift) << 16;
-              used[g] = 1;
-            } else {
-              wp[l] = have_addr ? (some_addr << 16) : 0u;
-            }
-          }
-        }
-    }
+  place_fillers(P, wg_cols, is_real_zero);
   P.map.words_max = words_max;
   P.map.padded_words = padded;
   return SPRNN_OK;
 }
 
-// LDS passes needed by the packed gathers relative to a conflict-free layout, under the measured gfx950
-// model: a pass serves `groups` consecutive lanes; lanes that read different addresses in the same bank
-// group serialise, lanes that read the same address are served together.
+// LDS cycles needed by the packed gathers relative to a conflict-free layout, under the measured gfx950 model (see
+// PassModel): lanes of a pass that read different addresses in the same bank class serialise, lanes that read the same
+// address are served together.
 double lds_pass_factor(const Packed& P) {
   const Mapping& m = P.map;
-  const int groups = pass_lanes(m.batch);
+  const PassModel pm = make_pass_model(m.batch);
   const int width = m.col_stride;
   int64_t passes = 0, ideal = 0;
-  std::vector<std::vector<uint32_t>> seen(groups);
+  std::vector<std::vector<uint32_t>> seen(pm.classes);
   for (int wg = 0; wg < m.grid; ++wg)
     for (int wave = 0; wave < m.waves; ++wave) {
       const int trip = P.wave_words[(size_t)wg * m.waves + wave];
       for (int k = 0; k < trip; ++k)
-        for (int base = 0; base < kWave; base += groups) {
+        for (int p = 0; p < pm.npass; ++p) {
           for (auto& v : seen) v.clear();
-          for (int l = base; l < base + groups; ++l) {
+          for (int l : pm.lanes[p]) {
             const uint32_t w = P.words[((size_t)wg * m.template_words + k) * m.block + (size_t)wave * kWave + l];
             const uint32_t byte = (w >> 16) << m.index_shift;
-            auto& v = seen[(byte / width) % groups];
+            auto& v = seen[(byte / width) % pm.classes];
             if (std::find(v.begin(), v.end(), byte) == v.end()) v.push_back(byte);
           }
           size_t worst = 1;

@@ -39,7 +39,9 @@ struct Mapping {
   int lds_bytes = 0;         // LDS taken by h: h_bytes, 2 * h_bytes for a single workgroup, less with column compaction
   int compact = 0;           // 1: a workgroup copies only the chunks of h that its rows read (see pack())
   int fill_rows = 0;         // compaction: rounds in the per-workgroup copy list
-  int stage_bytes = 0;       // LSTM: per-workgroup LDS area through which gate sums reach the cell lanes
+  int stage_bytes = 0;       // LSTM: per-workgroup LDS area through which gate sums reach the cell lanes; lane-pool layout: the group sums
+  int layout = 0;            // 0: one power-of-two lane group per row; 1: lane pool (see pack_pool): row_waves gather, the others own the outputs
+  int group = 0;             // lane pool: lanes per group (= batch); a row takes whole groups
   int64_t nnz = 0, padded_words = 0;
 };
 
@@ -52,6 +54,7 @@ struct Packed {
   std::vector<uint32_t> fill_src;   // compaction: [grid][fill_rows][block] ring byte offset of each copied chunk (out of range: none)
   std::vector<int32_t> wg_plane;    // compaction: [grid] bytes of one plane of the workgroup's LDS copy
   std::vector<int32_t> word_src;    // [grid][template_words][block] CSR position of the nonzero a packed word holds, -1 for padding
+  std::vector<int32_t> lane_sum;    // lane pool: [grid][block] for an output lane: first group of its row | groups of the row << 16
 };
 
 // Returns SPRNN_OK or an error code; on success `out` holds the mapping and the image.

@@ -175,6 +175,22 @@ __device__ __forceinline__ uint32_t lds_address(const void* generic) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)generic;
 }
 
+// Workgroup barrier that orders LDS traffic only: global loads and stores of the wavefront stay in flight across it.
+// (__syncthreads() also waits for every outstanding global memory operation of the wavefront.)
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// The abort flags live in LDS and are read by every wavefront in every step: explicit LDS accesses.  (Through a
+// generic volatile pointer the compiler emits system-scope flat instructions, which take the long way through the
+// vector memory pipeline and make every wavefront drain its global loads and stores first.)
+__device__ __forceinline__ void lds_store_int(uint32_t addr, int v) {
+  *((volatile __attribute__((address_space(3))) int*)(uint32_t)addr) = v;
+}
+__device__ __forceinline__ int lds_load_int(uint32_t addr) {
+  return *((volatile __attribute__((address_space(3))) int*)(uint32_t)addr);
+}
+
 template <int B>
 __device__ __forceinline__ Column<B> gather_column(uint32_t addr, int plane_bytes) {
   Column<B> c;
@@ -353,7 +369,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
   const bool solo = gridDim.x == 1;   // no other workgroup to exchange with
   unsigned char* const lds_tail = lds + (solo ? 2 : 1) * p.lds_h_bytes;
   // abort flags, indexed by step parity so that a fast wave's next-step flag cannot be read one step early
-  volatile int* s_abort = reinterpret_cast<volatile int*>(lds_tail);
+  const uint32_t s_abort = lds_address(lds_tail);   // LDS address of the two flags
   unsigned long long* s_tl = reinterpret_cast<unsigned long long*>(lds_tail + 16);
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -445,7 +461,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
   for (int c = 0; c < 4; ++c) fsrc[c] = copy_src(c);
 
   // ---- h_0 into LDS copy 0, cell state into registers
-  if (tid < 2) s_abort[tid] = 0;
+  if (tid < 2) lds_store_int(s_abort + 4 * tid, 0);
   if (TL && tid < kTimelineSlots) s_tl[tid] = 0ull;
   if (!compacted) {
     for (int e = tid; e < H * B; e += block) {
@@ -522,7 +538,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
 
   __syncthreads();
 
-  const bool tl_on = TL && p.timeline != nullptr && wave == 0;
+  const bool tl_on = TL && p.timeline != nullptr && wave == p.tl_wave;
   long long tl_launch_core = 0, tl_launch_wall = 0, tl_clock_cost = 0;
   if (TL && tl_on) {   // cost of reading the clock itself: 16 back-to-back reads
     const long long c0 = wall_clock64();
@@ -582,13 +598,13 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
             const uint32_t seen = __hip_atomic_load(p.ctrl + kCtrlBarrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((int)(seen - target) >= 0) break;
             if (++spins > p.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(p.ctrl + kCtrlStatus, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-              s_abort[t & 1] = 1;
+              lds_store_int(s_abort + 4 * (t & 1), 1);
               break;
             }
           }
         }
         __syncthreads();
-        failed = __builtin_amdgcn_readfirstlane(s_abort[t & 1]) != 0;   // the same for every lane of the workgroup
+        failed = __builtin_amdgcn_readfirstlane(lds_load_int(s_abort + 4 * (t & 1))) != 0;   // the same for every lane of the workgroup
       } else {
         // Polling a line before its producer wrote it installs a stale copy in this XCD's L2 that has to be
         // invalidated and fetched again, which costs more than waiting a little too long: back off first.
@@ -640,13 +656,13 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
       jitter_pause(p.jitter, wave_id, g, 2);
       ts6 = tick<TL>(tl_on);
       if (failed) {
-        s_abort[t & 1] = 1;
+        lds_store_int(s_abort + 4 * (t & 1), 1);
         __hip_atomic_store(p.ctrl + kCtrlStatus, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
       __syncthreads();
       // every wave of the workgroup leaves together; other workgroups see the status word
       // (readfirstlane: the flag is the same for every lane, and a scalar exit keeps the loop counter scalar)
-      if (__builtin_amdgcn_readfirstlane(s_abort[t & 1])) break;
+      if (__builtin_amdgcn_readfirstlane(lds_load_int(s_abort + 4 * (t & 1)))) break;
       ts7 = tick<TL>(tl_on);
     }
     ts0 = tick<TL>(tl_on);

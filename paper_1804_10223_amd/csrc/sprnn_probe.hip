@@ -46,6 +46,36 @@ __global__ __launch_bounds__(1024) void gather_kernel(const uint32_t* __restrict
   out[blockIdx.x * blockDim.x + threadIdx.x] = a0 + a1 + a2 + a3;
 }
 
+// The same 16-byte reads with nothing else in the loop (the results are only kept alive, not added up), so that the
+// loop is bound by the LDS alone and not by the additions of gather_kernel.
+template <int WIDTH>
+__global__ __launch_bounds__(1024) void gather_raw_kernel(const uint32_t* __restrict__ offs, int iters, int lds_bytes, float* out) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  for (int i = threadIdx.x * 4; i < lds_bytes; i += blockDim.x * 4) *reinterpret_cast<float*>(lds + i) = 1.0f;
+  uint32_t o[kGatherWords];
+  const uint32_t base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds;
+#pragma unroll
+  for (int k = 0; k < kGatherWords; ++k) o[k] = base + offs[k * blockDim.x + threadIdx.x];
+  __syncthreads();
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  f32x4 v[kGatherWords];
+#pragma unroll
+  for (int k = 0; k < kGatherWords; ++k) v[k] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int k = 0; k < kGatherWords; ++k) {
+      if constexpr (WIDTH == 16) asm volatile("ds_read_b128 %0, %1" : "=v"(v[k]) : "v"(o[k]));
+      else if constexpr (WIDTH == 8) asm volatile("ds_read_b64 %0, %1" : "=v"(*reinterpret_cast<double*>(&v[k])) : "v"(o[k]));
+      else asm volatile("ds_read_b32 %0, %1" : "=v"(v[k].x) : "v"(o[k]));
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
+  float a = 0.0f;
+#pragma unroll
+  for (int k = 0; k < kGatherWords; ++k) a += v[k].x + v[k].y + v[k].z + v[k].w;
+  out[blockIdx.x * blockDim.x + threadIdx.x] = a;
+}
+
 __global__ void where_kernel(uint32_t* xcc) {
   if (threadIdx.x == 0) xcc[blockIdx.x] = xcc_id();
 }
@@ -109,24 +139,16 @@ double wall_clock_hz(int device) {
 
 extern "C" {
 
-int sprnn_probe_lds_gather(int device, int workgroups, int threads, int width_bytes, int pattern, double* bytes_per_second) {
-  if (!bytes_per_second || workgroups < 1 || threads < 64 || threads > 1024 || threads % 64) return -1;
-  if (width_bytes != 4 && width_bytes != 8 && width_bytes != 16) return -1;
+static int run_gather(int device, int workgroups, int threads, int width_bytes, const std::vector<uint32_t>& offs, double* bytes_per_second,
+                      bool raw = false) {
   PROBE_CHECK(hipSetDevice(device));
   const int lds_bytes = 64 * 1024;
-  const int ncol = lds_bytes / width_bytes;
-  std::vector<uint32_t> offs((size_t)kGatherWords * threads);
-  std::mt19937 rng(1);
-  for (int k = 0; k < kGatherWords; ++k)
-    for (int t = 0; t < threads; ++t) {
-      const uint32_t col = pattern == 1 ? (uint32_t)(rng() % ncol) : (uint32_t)(((t % 64) + 64 * k + 7 * (t / 64)) % ncol);
-      offs[(size_t)k * threads + t] = col * width_bytes;
-    }
   DevBuf d_offs, d_out;
   PROBE_CHECK(hipMalloc(&d_offs.p, offs.size() * 4));
   PROBE_CHECK(hipMalloc(&d_out.p, (size_t)workgroups * threads * 4));
   PROBE_CHECK(hipMemcpy(d_offs.p, offs.data(), offs.size() * 4, hipMemcpyHostToDevice));
   const void* fn = width_bytes == 16 ? (const void*)gather_kernel<16> : width_bytes == 8 ? (const void*)gather_kernel<8> : (const void*)gather_kernel<4>;
+  if (raw) fn = width_bytes == 16 ? (const void*)gather_raw_kernel<16> : width_bytes == 8 ? (const void*)gather_raw_kernel<8> : (const void*)gather_raw_kernel<4>;
   PROBE_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));   // > half a CU: one workgroup per CU
   hipEvent_t e0, e1;
   PROBE_CHECK(hipEventCreate(&e0));
@@ -147,6 +169,30 @@ int sprnn_probe_lds_gather(int device, int workgroups, int threads, int width_by
   (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
   *bytes_per_second = best;
   return 0;
+}
+
+int sprnn_probe_lds_gather(int device, int workgroups, int threads, int width_bytes, int pattern, double* bytes_per_second) {
+  if (!bytes_per_second || workgroups < 1 || threads < 64 || threads > 1024 || threads % 64) return -1;
+  if (width_bytes != 4 && width_bytes != 8 && width_bytes != 16) return -1;
+  const int ncol = 64 * 1024 / width_bytes;
+  std::vector<uint32_t> offs((size_t)kGatherWords * threads);
+  std::mt19937 rng(1);
+  for (int k = 0; k < kGatherWords; ++k)
+    for (int t = 0; t < threads; ++t) {
+      const uint32_t col = pattern == 1 ? (uint32_t)(rng() % ncol) : (uint32_t)(((t % 64) + 64 * k + 7 * (t / 64)) % ncol);
+      offs[(size_t)k * threads + t] = col * width_bytes;
+    }
+  return run_gather(device, workgroups, threads, width_bytes, offs, bytes_per_second);
+}
+
+int sprnn_probe_lds_gather_offsets(int device, int workgroups, int threads, int width_bytes, int bare, const uint32_t* offsets,
+                                   double* bytes_per_second) {
+  if (!bytes_per_second || !offsets || workgroups < 1 || threads < 64 || threads > 1024 || threads % 64) return -1;
+  if (width_bytes != 4 && width_bytes != 8 && width_bytes != 16) return -1;
+  std::vector<uint32_t> offs(offsets, offsets + (size_t)kGatherWords * threads);
+  for (uint32_t o : offs)
+    if (o % width_bytes || o + width_bytes > 64u * 1024u) return -1;   // every read inside the 64 KB the kernel fills
+  return run_gather(device, workgroups, threads, width_bytes, offs, bytes_per_second, bare != 0);
 }
 
 int sprnn_probe_handoff(int device, int same_xcd, int rounds, double* nanoseconds, int xcc[2]) {

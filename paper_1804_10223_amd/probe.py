@@ -7,7 +7,7 @@ import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsprnn_probe.so")
-EXPORTS = ["sprnn_probe_lds_gather", "sprnn_probe_handoff", "sprnn_probe_fill"]
+EXPORTS = ["sprnn_probe_lds_gather", "sprnn_probe_lds_gather_offsets", "sprnn_probe_handoff", "sprnn_probe_fill"]
 _lib = None
 
 
@@ -21,6 +21,8 @@ def load_library() -> ctypes.CDLL:
         ci, dp = ctypes.c_int, ctypes.POINTER(ctypes.c_double)
         lib.sprnn_probe_lds_gather.restype = ci
         lib.sprnn_probe_lds_gather.argtypes = [ci, ci, ci, ci, ci, dp]
+        lib.sprnn_probe_lds_gather_offsets.restype = ci
+        lib.sprnn_probe_lds_gather_offsets.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ctypes.c_uint32), dp]
         lib.sprnn_probe_handoff.restype = ci
         lib.sprnn_probe_handoff.argtypes = [ci, ci, ci, dp, ctypes.POINTER(ci * 2)]
         lib.sprnn_probe_fill.restype = ci
@@ -35,6 +37,20 @@ def lds_gather(workgroups: int, threads: int, width_bytes: int, pattern: int = 0
     rc = load_library().sprnn_probe_lds_gather(device, workgroups, threads, width_bytes, pattern, ctypes.byref(out))
     if rc:
         raise RuntimeError("sprnn_probe_lds_gather failed (%d)" % rc)
+    return out.value
+
+
+def lds_gather_offsets(offsets, width_bytes: int, workgroups: int = 256, device: int = 0, bare: bool = False) -> float:
+    """Aggregate LDS gather rate in bytes/s for the caller's pattern: offsets is uint32 [16, threads] (byte offsets);
+    bare leaves only the reads in the timed loop."""
+    import numpy as np
+    offsets = np.ascontiguousarray(offsets, dtype=np.uint32)
+    assert offsets.ndim == 2 and offsets.shape[0] == 16
+    out = ctypes.c_double()
+    rc = load_library().sprnn_probe_lds_gather_offsets(device, workgroups, int(offsets.shape[1]), width_bytes, 1 if bare else 0,
+                                                       offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), ctypes.byref(out))
+    if rc:
+        raise RuntimeError("sprnn_probe_lds_gather_offsets failed (%d)" % rc)
     return out.value
 
 

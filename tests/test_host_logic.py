@@ -121,6 +121,40 @@ def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
             assert np.all(units[:, :, 3] == -1) and info["rows"] == 3 * H
 
 
+@pytest.mark.parametrize("cell,H,B,dens,rownnz,opts", [
+    ("relu", 300, 4, 0.3, "poisson", {}),
+    ("tanh", 257, 1, 0.2, "poisson", {"grid": 5}),
+    ("relu", 640, 2, 0.5, "fixed", {"waves": 7}),
+    ("identity", 130, 8, 0.1, "poisson", {"bank_aware": 2}),
+    ("relu", 2304, 4, 0.3, "fixed", {}),
+])
+def test_lane_pool_packer_preserves_every_row_and_keeps_its_structure(cell, H, B, dens, rownnz, opts):
+    w = wl.make_workload("p", cell, H, B, 1, dens, seed=5, row_nnz=rownnz)
+    words, lane_row, lane_words, info = binding.pack_host(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, layout=2, **opts)
+    assert info["layout"] == 2 and info["template_words"] % 4 == 0
+    got = _unpack(words, lane_row, lane_words, info, H, B)
+    for r in range(H):
+        cols = w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]]
+        bits = w.val_bits[w.row_ptr[r]:w.row_ptr[r + 1]]
+        want = sorted((int(c), int(b)) for c, b in zip(cols, bits) if (int(b) & 0x7FFF) != 0)
+        assert got.get(r, []) == want, r
+    assert int(lane_words.sum()) == w.nnz
+    pool = 64 * info["gather_waves"]
+    gather, output = lane_row[:, :pool], lane_row[:, pool:]
+    assert not lane_words[:, pool:].any()                       # the output wavefronts hold no weights
+    # gathering lanes: whole groups of `batch` lanes per row, the groups of one row next to each other, rows in order
+    g = gather.reshape(info["grid"], -1, B)
+    assert np.all(g == g[:, :, :1])
+    for wg in range(info["grid"]):
+        rows = [r for r in g[wg, :, 0].tolist() if r >= 0]
+        assert rows == sorted(rows)
+    # output lanes: lane e owns sample e % batch of the workgroup's row e / batch; every row exactly once per sample
+    o = output.reshape(info["grid"], -1, B)
+    assert np.all(o == o[:, :, :1])
+    owned = o[:, :, 0][o[:, :, 0] >= 0]
+    assert sorted(owned.tolist()) == list(range(H))
+
+
 def test_bank_aware_order_reduces_modelled_lds_passes():
     w = wl.make_workload("p", "relu", 1152, 4, 1, 0.1, seed=0)
     naive = binding.pack_host(1152, 4, "relu", w.row_ptr, w.col_idx, w.val_bits, bank_aware=2)[3]
