@@ -9,10 +9,13 @@ T = 256, the shape the metric is quoted on).  Inputs are resident in device memo
 region.  Prints ONE JSON line on stdout; everything else goes to stderr.
 
 Reported beside the throughput:
-  roofline      the stated per-timestep bound  T_roof = nnz*gather_bytes/BW_lds + L_handoff + |h|/BW_fill
-                (LDS operand bandwidth for the nonzero stream + measured cross-workgroup store->observe
-                latency + time to bring h into one CU), its three device constants measured live by
-                libsprnn_probe, and achieved/peak in microseconds per timestep.
+  roofline      the stated per-timestep bound  T_roof = max(nnz*gather_bytes/BW_lds, nnz*B/R_valu) + L_handoff + |h|/BW_fill
+                (on-chip operand bandwidth or multiply-add issue rate for the nonzero stream + cross-workgroup
+                store->observe latency + marginal time to bring h into one CU), its device constants measured live
+                by libsprnn_probe (LDS rate with nothing but the reads in the loop; hand-off as the minimum over
+                several probe launches; fill rate as the SLOPE of copy time over three sizes, its intercept being
+                latency that the hand-off term already holds), and achieved/peak in microseconds per timestep.
+                HBM traffic per launch comes from a counter summary file (--traffic-file), never from a constant.
   stepwise      the non-persistent comparison path (one launch per timestep) on the same inputs.
   backward      the backward pass through time of the same layer (sprnn_backward on the transposed matrix).
   projection    the step before the path (sprnn_project: b' = W x + b for all timesteps, input size = hidden size)
@@ -128,10 +131,13 @@ def measure_backward(w, steps, warmup, torch, options=None):
         e = torch.randn((w.steps, w.batch, w.hidden), device="cuda", generator=gen)
         h_fwd = torch.randn((w.steps, w.batch, w.hidden), device="cuda", generator=gen)
         d = torch.empty_like(e)
-        _, per_call = time_forward(lambda: rnn.backward(e, h_fwd, d), steps, warmup, torch)
+        dh0 = torch.empty((w.batch, w.hidden), dtype=torch.float32, device="cuda")
+        dU_t = torch.empty((max(w.nnz, 1),), dtype=torch.float32, device="cuda")
+        # (every output is allocated here, outside the timed region: the binding allocates nothing when given them)
+        _, per_call = time_forward(lambda: rnn.backward(e, h_fwd, d, dh0=dh0), steps, warmup, torch)
         fused_ms = None
         try:   # the same pass with the weight gradient fused in (not built for every mapping)
-            _, per_fused = time_forward(lambda: rnn.backward_with_weights(e, h_fwd, None, d), steps, warmup, torch)
+            _, per_fused = time_forward(lambda: rnn.backward_with_weights(e, h_fwd, None, d, dh0=dh0, dU=dU_t), steps, warmup, torch)
             fused_ms = float(np.median(per_fused))
         except binding.SprnnError:
             pass
@@ -162,15 +168,17 @@ def measure_lstm_training(steps, warmup, torch):
     t_rp, t_ci, t_vb = binding.transpose_csr(4 * H, H, w.row_ptr, w.col_idx, w.val_bits)
     with binding.SparseRNN(H, B, "lstm", w.row_ptr, w.col_idx, w.val_bits) as fwd, \
             binding.SparseRNN(H, B, "lstm_backward", t_rp, t_ci, t_vb) as bwd:
-        _, per_f = time_forward(lambda: fwd.forward_lstm_train(x), steps, warmup, torch)
-        h, c, g = fwd.forward_lstm_train(x)
-        _, per_b = time_forward(lambda: bwd.backward_lstm(e, g, c), steps, warmup, torch)
-        d, _, _ = bwd.backward_lstm(e, g, c)
-        dU = torch.empty((w.nnz,), dtype=torch.float32, device="cuda")
+        # every output is allocated here, outside the timed regions: the binding allocates nothing when given them
+        mk = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+        h, c, g = mk(T, B, H), mk(T, B, H), mk(T, B, 4 * H)
+        d, dh0, dc0, dU, dU_t = mk(T, B, 4 * H), mk(B, H), mk(B, H), mk(w.nnz), mk(w.nnz)
+        _, per_f = time_forward(lambda: fwd.forward_lstm_train(x, None, None, h, c, g), steps, warmup, torch)
+        _, per_b = time_forward(lambda: bwd.backward_lstm(e, g, c, d_bprime=d, dh0=dh0, dc0=dc0), steps, warmup, torch)
         _, per_w = time_forward(lambda: fwd.weight_gradient(d, h, None, dU), steps, warmup, torch)
         fused_ms = None
         try:   # backward and weight gradient in one kernel (not built for every mapping)
-            _, per_fused = time_forward(lambda: bwd.backward_lstm_with_weights(e, g, c, h), steps, warmup, torch)
+            _, per_fused = time_forward(lambda: bwd.backward_lstm_with_weights(e, g, c, h, d_bprime=d, dh0=dh0, dc0=dc0, dU=dU_t),
+                                        steps, warmup, torch)
             fused_ms = float(np.median(per_fused))
         except binding.SprnnError:
             pass
@@ -186,33 +194,60 @@ def measure_lstm_training(steps, warmup, torch):
             "backward_exchange_bytes_per_timestep": 4 * H * B * 4}
 
 
+VALU_LANES_PER_CLK_PER_CU = 64      # 4 SIMDs x 16 lanes: one multiply-add per lane and clock
+
+
 def roofline_for(w, info, probe_vals):
     """Stated per-timestep bound for one configuration from the measured device constants."""
     gather = 4 * w.batch                                   # fp32 activations of one column, all samples
     lds_bytes = w.nnz * gather
     width = min(16, gather)
-    t_operate = lds_bytes / probe_vals["lds_Bps"][width]
+    t_lds = lds_bytes / probe_vals["lds_Bps"][width]
+    t_valu = w.nnz * w.batch / probe_vals["valu_lane_ops_per_s"]       # one multiply-add per nonzero and sample
+    t_operate = max(t_lds, t_valu)
     t_handoff = probe_vals["handoff_cross_ns"] * 1e-9 if info["grid"] > 32 else probe_vals["handoff_same_ns"] * 1e-9
     if info["grid"] == 1:
         t_handoff = 0.0
     h_bytes = w.hidden * w.batch * 4
-    t_fill = h_bytes / probe_vals["fill_Bps"]
-    return dict(t_operate_us=t_operate * 1e6, t_handoff_us=t_handoff * 1e6, t_fill_us=t_fill * 1e6,
-                t_roof_us=(t_operate + t_handoff + t_fill) * 1e6, lds_bytes_per_step=lds_bytes, h_bytes=h_bytes)
+    t_fill = 0.0 if info["grid"] == 1 else h_bytes * probe_vals["fill_s_per_byte"]
+    return dict(t_operate_us=t_operate * 1e6, t_lds_us=t_lds * 1e6, t_valu_us=t_valu * 1e6, t_handoff_us=t_handoff * 1e6,
+                t_fill_us=t_fill * 1e6, t_roof_us=(t_operate + t_handoff + t_fill) * 1e6, lds_bytes_per_step=lds_bytes, h_bytes=h_bytes)
 
 
-def measure_probes(probe):
+def measure_probes(probe, torch):
     vals = {"lds_Bps": {}}
     for width in (4, 8, 16):
-        vals["lds_Bps"][width] = probe.lds_gather(256, 1024, width, 0)
+        vals["lds_Bps"][width] = probe.lds_peak(width)
+    vals["lds_with_adds_Bps_16"] = probe.lds_gather(256, 1024, 16, 0)
     vals["lds_random_Bps_16"] = probe.lds_gather(256, 1024, 16, 1)
-    vals["handoff_same_ns"], vals["xcc_same"] = probe.handoff_ns(True)
-    vals["handoff_cross_ns"], vals["xcc_cross"] = probe.handoff_ns(False)
-    # asymptotic per-CU fill rate: a large copy (64 KB), all 256 CUs at once
-    big = 64 * 1024
-    vals["fill_Bps"] = big / probe.fill_seconds(256, 1024, big)
-    vals["fill_36k_s"] = probe.fill_seconds(256, 1024, 36864)
+    vals["handoff_same_ns"], vals["xcc_same"] = probe.handoff_ns_best(True, launches=6)
+    vals["handoff_cross_ns"], vals["xcc_cross"] = probe.handoff_ns_best(False, launches=6)
+    slope, intercept, times = probe.fill_fit()
+    vals["fill_s_per_byte"], vals["fill_intercept_s"], vals["fill_times_s"] = slope, intercept, times
+    prop = torch.cuda.get_device_properties(0)
+    vals["cus"] = int(prop.multi_processor_count)
+    vals["clock_hz"] = float(getattr(prop, "clock_rate", 2400000)) * 1e3
+    vals["valu_lane_ops_per_s"] = vals["cus"] * VALU_LANES_PER_CLK_PER_CU * vals["clock_hz"]
     return vals
+
+
+def read_traffic_file(path, workload_name):
+    """HBM bytes per launch of the persistent kernel from a counter summary: text lines `key = value` written from
+    rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE, each scaled by the same run's reference copy).  None when the
+    file is missing or describes another workload."""
+    try:
+        kv = {}
+        with open(path) as f:
+            for line in f:
+                if "=" in line and not line.lstrip().startswith("#"):
+                    k, v = line.split("=", 1)
+                    kv[k.strip()] = v.strip()
+        if kv.get("workload") != workload_name:
+            return None
+        return {"fetch_bytes_per_launch": float(kv["fetch_bytes_per_launch"]), "write_bytes_per_launch": float(kv["write_bytes_per_launch"]),
+                "source": os.path.relpath(path, ROOT)}
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(w, budget_s=20.0):
@@ -257,6 +292,8 @@ def main():
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--all-configs", action="store_true", help="also time cfg1..cfg5 and write a table to stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "persistent_kernel_cfg3_traffic.txt"),
+                    help="counter summary (key = value lines) that holds the measured HBM bytes per launch of the timed kernel")
     ap.add_argument("--poll-delay", type=int, default=0,
                     help="fix the back-off before a step's first poll (units of 64 clocks) instead of letting "
                          "sprnn_create measure it: profiler runs then see only the timed launches")
@@ -274,11 +311,14 @@ def main():
     binding.load_library()
 
     log("measuring device constants (LDS gather rate, hand-off latency, fill rate) ...")
-    pv = measure_probes(probe)
-    log("  LDS conflict-free: b128 %.1f TB/s, b64 %.1f TB/s, b32 %.1f TB/s; random b128 %.1f TB/s" % (
-        pv["lds_Bps"][16] / 1e12, pv["lds_Bps"][8] / 1e12, pv["lds_Bps"][4] / 1e12, pv["lds_random_Bps_16"] / 1e12))
-    log("  hand-off one way: same XCD %.0f ns %s, cross XCD %.0f ns %s; fill %.1f GB/s per CU (36 KB copy %.2f us)" % (
-        pv["handoff_same_ns"], pv["xcc_same"], pv["handoff_cross_ns"], pv["xcc_cross"], pv["fill_Bps"] / 1e9, pv["fill_36k_s"] * 1e6))
+    pv = measure_probes(probe, torch)
+    log("  LDS conflict-free, reads only: b128 %.1f TB/s, b64 %.1f TB/s, b32 %.1f TB/s (with the values added up: b128 %.1f TB/s; random columns %.1f TB/s)" % (
+        pv["lds_Bps"][16] / 1e12, pv["lds_Bps"][8] / 1e12, pv["lds_Bps"][4] / 1e12, pv["lds_with_adds_Bps_16"] / 1e12, pv["lds_random_Bps_16"] / 1e12))
+    log("  hand-off one way (minimum of 6 launches): same XCD %.0f ns %s, cross XCD %.0f ns %s" % (
+        pv["handoff_same_ns"], pv["xcc_same"], pv["handoff_cross_ns"], pv["xcc_cross"]))
+    log("  fill: %s us for %s bytes -> marginal %.1f GB/s per CU, intercept %.2f us" % (
+        ["%.2f" % (t * 1e6) for t in pv["fill_times_s"].values()], list(pv["fill_times_s"].keys()),
+        1e-9 / pv["fill_s_per_byte"], pv["fill_intercept_s"] * 1e6))
 
     options = {"poll_delay": args.poll_delay} if args.poll_delay else None
     res = measure_config(args.config, args.steps, args.warmup, torch, options=options)
@@ -312,7 +352,10 @@ def main():
             rf = roofline_for(r["workload"], r["info"], pv)
             us = r["kernel_ms"] * 1e3 / r["T"]
             row = dict(config=name, us_per_timestep=us, stepwise_us_per_timestep=r["stepwise_ms"] * 1e3 / r["T"],
-                       roofline_us=rf["t_roof_us"], frac=rf["t_roof_us"] / us, grid=r["info"]["grid"], block=r["info"]["block"])
+                       roofline={"bound": "lds+exchange", "achieved": us, "peak": rf["t_roof_us"], "frac": rf["t_roof_us"] / us,
+                                 "unit": "us/timestep", "t_operate_us": rf["t_operate_us"], "t_handoff_us": rf["t_handoff_us"],
+                                 "t_fill_us": rf["t_fill_us"]},
+                       grid=r["info"]["grid"], block=r["info"]["block"])
             table.append(row)
             log("  %s" % json.dumps(row))
 
@@ -333,6 +376,7 @@ def main():
         log("  oracle: %.1f us/timestep single thread; %.1f us/timestep on %d cores" % (
             cpu["us_per_timestep"], cpu["all_cores"]["us_per_timestep"], cpu["all_cores"]["cores"]))
 
+    traffic = read_traffic_file(args.traffic_file, w.name)
     out = {
         "metric": "timesteps_per_sec (hidden %d, batch %d, density %.0f%%)" % (w.hidden, w.batch, 100 * w.meta["density"]),
         "value": value,
@@ -356,16 +400,20 @@ def main():
             "peak": roof["t_roof_us"],
             "unit": "us/timestep (lower is better; frac = peak/achieved)",
             "frac": roof["t_roof_us"] / us_per_ts,
-            # HBM bytes per launch (fetch + write) from the committed rocprofv3 --pmc passes of this command,
-            # scaled by the 256 MiB calibration copy (profiles/persistent_kernel_cfg3.md); cfg3 only
-            "traffic": (125.0e6 + 54.5e6) if args.config == "cfg3" else None,
+            # HBM bytes per launch (fetch + write) of the timed kernel, read from the counter summary of this command
+            # (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes scaled by the run's reference copy); null without one
+            "traffic": None if traffic is None else traffic["fetch_bytes_per_launch"] + traffic["write_bytes_per_launch"],
+            "traffic_source": None if traffic is None else traffic["source"],
             "traffic_algorithmic": 4.0 * info["padded_words"] + 4.0 * w.x.size + 4.0 * T * w.batch * w.hidden,
-            "t_operate_us": roof["t_operate_us"], "t_handoff_us": roof["t_handoff_us"], "t_fill_us": roof["t_fill_us"],
+            "t_operate_us": roof["t_operate_us"], "t_lds_us": roof["t_lds_us"], "t_valu_us": roof["t_valu_us"],
+            "t_handoff_us": roof["t_handoff_us"], "t_fill_us": roof["t_fill_us"],
             "lds_bytes_per_timestep": roof["lds_bytes_per_step"],
             "lds_achieved_TBps": roof["lds_bytes_per_step"] / (us_per_ts * 1e-6) / 1e12,
             "lds_peak_measured_TBps": pv["lds_Bps"][min(16, 4 * w.batch)] / 1e12,
+            "valu_peak_lane_ops_per_s": pv["valu_lane_ops_per_s"],
             "handoff_same_xcd_ns": pv["handoff_same_ns"], "handoff_cross_xcd_ns": pv["handoff_cross_ns"],
-            "fill_GBps_per_cu": pv["fill_Bps"] / 1e9,
+            "fill_marginal_GBps_per_cu": 1e-9 / pv["fill_s_per_byte"], "fill_intercept_us": pv["fill_intercept_s"] * 1e6,
+            "fill_times_us": {str(k): v * 1e6 for k, v in pv["fill_times_s"].items()},
             "kernel": "persistent_kernel<B=%d,NW=%d>" % (w.batch, info["template_words"]),
             "kernel_ms_per_launch": res["kernel_ms"],
         },

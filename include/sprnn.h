@@ -90,7 +90,14 @@ typedef struct sprnn_options_s {
                         0 auto, 1 = one power-of-two lane group per row, every wavefront does every stage,
                         2 = lane pool: a row takes as many groups of `batch` lanes as its nonzeros need out of a
                         pool of 4 or 7 gathering wavefronts, and separate wavefronts own b', g and the stores  */
-  int reserved[2];
+  int gather;        /* 0 auto, 1 = one wide LDS read per nonzero fetches all samples of its column (Section 4.1's wide
+                        loads), 2 = one 4-byte read per sample (the rung below it in the ablation; batch 4, vanilla
+                        cells, layout 1, forward pass only)                                            */
+  int xcd;           /* small layers (at most 32 workgroups; not the gated cells' backward passes): 0 auto = measured at
+                        create time together with the back-off, 1 = workgroups spread over all XCDs, 2 = one XCD:
+                        the launch holds eight times the workgroups, those that the dispatcher put on one XCD take
+                        the work and exchange h through that XCD's L2 alone (if it put too few there, the launch
+                        leaves without results and sprnn_check reports SPRNN_ERR_STATE)                       */
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */
@@ -110,7 +117,8 @@ typedef struct sprnn_info_s {
   int compact;              /* 1 if column compaction is in use                                      */
   int layout;               /* 1 = one lane group per row, 2 = lane pool (see sprnn_options_t.layout)   */
   int gather_waves;         /* wavefronts per workgroup that hold weights (all of them for layout 1)    */
-  int reserved[5];
+  int one_xcd;              /* 1 if the workgroups are confined to one XCD (see sprnn_options_t.xcd)     */
+  int reserved[4];
 } sprnn_info_t;
 
 /*

@@ -26,6 +26,8 @@ CELLS = {"relu": 0, "tanh": 1, "identity": 2, "lstm": 3, "gru": 4, "lstm_backwar
 GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 LAYOUT = {"auto": 0, "row_groups": 1, "lane_pool": 2}
+GATHER = {"auto": 0, "wide": 1, "narrow": 2}
+XCD = {"auto": 0, "spread": 1, "one": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_noalloc", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
            "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights", "sprnn_forward_gru_train",
@@ -40,7 +42,7 @@ class Options(ctypes.Structure):
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
                 ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
-                ("reserved", ctypes.c_int * 2)]
+                ("gather", ctypes.c_int), ("xcd", ctypes.c_int)]
 
 
 class Info(ctypes.Structure):
@@ -52,7 +54,7 @@ class Info(ctypes.Structure):
                 ("lds_bytes", ctypes.c_int), ("resident_capacity", ctypes.c_int),
                 ("nnz", ctypes.c_int64), ("padded_words", ctypes.c_int64), ("ring_bytes", ctypes.c_int64),
                 ("lds_pass_factor", ctypes.c_double), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
-                ("gather_waves", ctypes.c_int), ("reserved", ctypes.c_int * 5)]
+                ("gather_waves", ctypes.c_int), ("one_xcd", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
 
     def as_dict(self) -> dict:
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
@@ -177,6 +179,10 @@ def make_options(**kw) -> Options:
             v = SYNC[v]
         if k == "layout" and isinstance(v, str):
             v = LAYOUT[v]
+        if k == "gather" and isinstance(v, str):
+            v = GATHER[v]
+        if k == "xcd" and isinstance(v, str):
+            v = XCD[v]
         if not hasattr(o, k):
             raise TypeError("unknown option %r" % k)
         setattr(o, k, int(v))
@@ -288,6 +294,11 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_read_timeline")
         return buf, hz.value
 
+    def _nnz(self) -> int:
+        if getattr(self, "_nnz_cached", None) is None:
+            self._nnz_cached = int(self.info()["nnz"])
+        return self._nnz_cached
+
     def check(self) -> int:
         """sprnn_check: synchronise and return the status code (SPRNN_OK or SPRNN_ERR_STATE)."""
         return int(self._lib.sprnn_check(self._h))
@@ -339,12 +350,15 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_forward_lstm")
         return h_out, c_out
 
-    def forward_lstm_train(self, x, h0=None, c0=None):
-        """sprnn_forward_lstm_train: x [T, B, 4H] -> (h_out, c_out [T, B, H], gates [T, B, 4H] after their activations)."""
+    def forward_lstm_train(self, x, h0=None, c0=None, h_out=None, c_out=None, gates=None):
+        """sprnn_forward_lstm_train: x [T, B, 4H] -> (h_out, c_out [T, B, H], gates [T, B, 4H] after their activations).
+        Outputs the caller does not pass are allocated here."""
         import torch
         T = int(x.shape[0])
-        h_out, c_out = self._alloc(T), self._alloc(T)
-        gates = torch.empty((T, self.batch, self.rows), dtype=torch.float32, device="cuda:%d" % self.device)
+        h_out = self._alloc(T) if h_out is None else h_out
+        c_out = self._alloc(T) if c_out is None else c_out
+        if gates is None:
+            gates = torch.empty((T, self.batch, self.rows), dtype=torch.float32, device="cuda:%d" % self.device)
         rc = self._lib.sprnn_forward_lstm_train(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
                                                 _dev_ptr(h0, (self.batch, self.hidden), "h0"),
                                                 _dev_ptr(c0, (self.batch, self.hidden), "c0"),
@@ -355,15 +369,18 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_forward_lstm_train")
         return h_out, c_out, gates
 
-    def backward_lstm(self, dh_ext, gates, c_fwd, c0=None, want_dh0=True, want_dc0=True):
+    def backward_lstm(self, dh_ext, gates, c_fwd, c0=None, want_dh0=True, want_dc0=True, d_bprime=None, dh0=None, dc0=None):
         """sprnn_backward_lstm on a "lstm_backward" handle (the TRANSPOSED [H][4H] matrix):
-        (d_bprime [T, B, 4H], dh0 [B, H] or None, dc0 [B, H] or None)."""
+        (d_bprime [T, B, 4H], dh0 [B, H] or None, dc0 [B, H] or None).  Outputs the caller does not pass are allocated here."""
         import torch
         T = int(dh_ext.shape[0])
         dev = "cuda:%d" % self.device
-        d_bprime = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device=dev)
-        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
-        dc0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dc0 else None
+        if d_bprime is None:
+            d_bprime = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device=dev)
+        if dh0 is None and want_dh0:
+            dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev)
+        if dc0 is None and want_dc0:
+            dc0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev)
         rc = self._lib.sprnn_backward_lstm(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
                                            _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"),
                                            _dev_ptr(c_fwd, (T, self.batch, self.hidden), "c_fwd"),
@@ -375,17 +392,23 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_backward_lstm")
         return d_bprime, dh0, dc0
 
-    def backward_lstm_with_weights(self, dh_ext, gates, c_fwd, h_fwd, c0=None, h0=None, want_dh0=True, want_dc0=True):
+    def backward_lstm_with_weights(self, dh_ext, gates, c_fwd, h_fwd, c0=None, h0=None, want_dh0=True, want_dc0=True,
+                                   d_bprime=None, dh0=None, dc0=None, dU=None):
         """sprnn_backward_lstm_with_weights on a "lstm_backward" handle:
-        (d_bprime [T, B, 4H], dh0, dc0 [B, H] or None, dU [nnz] in the transposed matrix's CSR order)."""
+        (d_bprime [T, B, 4H], dh0, dc0 [B, H] or None, dU [nnz] in the transposed matrix's CSR order).
+        Outputs the caller does not pass are allocated here (dU: at least max(nnz, 1) elements)."""
         import torch
         T = int(dh_ext.shape[0])
         dev = "cuda:%d" % self.device
-        nnz = self.info()["nnz"]
-        d_bprime = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device=dev)
-        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
-        dc0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dc0 else None
-        dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
+        nnz = self._nnz()
+        if d_bprime is None:
+            d_bprime = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device=dev)
+        if dh0 is None and want_dh0:
+            dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev)
+        if dc0 is None and want_dc0:
+            dc0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev)
+        if dU is None:
+            dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
         rc = self._lib.sprnn_backward_lstm_with_weights(
             self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
             _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"), _dev_ptr(c_fwd, (T, self.batch, self.hidden), "c_fwd"),
@@ -465,13 +488,14 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_backward_gru_with_weights")
         return d_bprime, d_rec, dh0, dU[:nnz]
 
-    def backward(self, dh_ext, h_fwd, d_bprime=None, want_dh0=True):
+    def backward(self, dh_ext, h_fwd, d_bprime=None, want_dh0=True, dh0=None):
         """sprnn_backward on a handle that holds the TRANSPOSED matrix: (delta [T, B, H], dh0 [B, H] or None)."""
         import torch
         T = int(dh_ext.shape[0])
         if d_bprime is None:
             d_bprime = self._alloc(T)
-        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device="cuda:%d" % self.device) if want_dh0 else None
+        if dh0 is None and want_dh0:
+            dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device="cuda:%d" % self.device)
         rc = self._lib.sprnn_backward(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
                                       _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
                                       _dev_ptr(d_bprime, (T, self.batch, self.hidden), "d_bprime"),
@@ -480,17 +504,19 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_backward")
         return d_bprime, dh0
 
-    def backward_with_weights(self, dh_ext, h_fwd, h0=None, d_bprime=None, want_dh0=True):
+    def backward_with_weights(self, dh_ext, h_fwd, h0=None, d_bprime=None, want_dh0=True, dh0=None, dU=None):
         """sprnn_backward_with_weights on a handle that holds the TRANSPOSED matrix:
         (delta [T, B, H], dh0 [B, H] or None, dU [nnz] in the transposed matrix's CSR order)."""
         import torch
         T = int(dh_ext.shape[0])
-        nnz = self.info()["nnz"]
+        nnz = self._nnz()
         if d_bprime is None:
             d_bprime = self._alloc(T)
         dev = "cuda:%d" % self.device
-        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
-        dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
+        if dh0 is None and want_dh0:
+            dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev)
+        if dU is None:
+            dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
         rc = self._lib.sprnn_backward_with_weights(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
                                                    _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
                                                    _dev_ptr(h0, (self.batch, self.hidden), "h0"),
@@ -505,7 +531,7 @@ class SparseRNN:
         """sprnn_weight_gradient on the FORWARD handle: dU [nnz] float32 in CSR order."""
         import torch
         T = int(d_bprime.shape[0])
-        nnz = self.info()["nnz"]
+        nnz = self._nnz()
         if dU is None:
             dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device="cuda:%d" % self.device)
         rc = self._lib.sprnn_weight_gradient(self._h, T, _dev_ptr(d_bprime, (T, self.batch, self.rows), "d_bprime"),

@@ -41,6 +41,8 @@ struct sprnn_handle_s {
   uint16_t* d_val = nullptr;
   uint32_t step_base = 0;        // global step index at which the next forward starts
   uint32_t barrier_base = 0;     // grid barriers completed so far (grid-barrier mode)
+  uint32_t launch_epoch = 0;     // persistent launches so far (parity selects the placement counters of the one-XCD mode)
+  bool one_xcd = false;          // launches hold 8 x grid workgroups and those of one XCD take the work
   bool poisoned = false;         // a watchdog trip was observed: the ring no longer holds a consistent state
   bool used_shared_exchange = false;   // sprnn_forward_noalloc ran on this handle: sprnn_check also reads its status word
 };
@@ -93,6 +95,7 @@ void fill_info(const Mapping& m, int capacity, double pass_factor, sprnn_info_t*
   info->layout = m.layout ? 2 : 1;
   info->gather_waves = m.row_waves;
 }
+// (fill_info has no handle: the one-XCD flag is added by sprnn_get_info)
 
 template <typename T>
 hipError_t upload(T** dst, const T* src, size_t n) {
@@ -146,7 +149,7 @@ struct LaunchExtras {
 };
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const LaunchExtras& ex = LaunchExtras());
-static int calibrate_poll_delay(sprnn_handle_s* h);
+static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd);
 
 extern "C" {
 
@@ -242,7 +245,8 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   h->pass_factor = lds_pass_factor(P);
   const Mapping& m = h->map;
   const bool pool = m.layout == 1;
-  h->kernel = pool ? pool_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0) : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0);
+  h->kernel = pool ? pool_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0)
+                   : (m.narrow ? persistent_narrow_kernel_for(m.batch, m.template_words) : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0));
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
@@ -254,7 +258,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   // (the per-kernel limit on dynamic LDS is state shared by every handle that uses the same instantiation: it is
   // always raised to the device's maximum, never set to one handle's own request)
   if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
-  if (m.cell <= SPRNN_ACT_IDENTITY && !m.timeline) {
+  if (m.cell <= SPRNN_ACT_IDENTITY && !m.timeline && !m.narrow) {
     // the backward pass of a vanilla cell runs on a handle that holds the transposed matrix: same shape, same LDS
     h->kernel_bwd = pool ? pool_kernel_for(m.batch, m.template_words, kCellBackward) : persistent_kernel_for(m.batch, m.template_words, kCellBackward, false);
     if (h->kernel_bwd && !SPRNN_HIP(hipFuncSetAttribute(h->kernel_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
@@ -267,6 +271,14 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   if (!SPRNN_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, h->kernel, m.block, h->launch_lds))) { release(h); return SPRNN_ERR_HIP; }
   h->capacity = per_cu * h->num_cus;
   if (m.grid > h->capacity) { release(h); return SPRNN_ERR_CAPACITY; }   // a spinning grid that is not co-resident would deadlock
+  // One-XCD mode: small layers whose workgroups fit the CUs of one XCD (8 x grid workgroups must be co-resident)
+  const int xcd_opt = opt ? opt->xcd : 0;
+  if (xcd_opt < 0 || xcd_opt > 2) { release(h); return SPRNN_ERR_INVALID; }
+  const bool xcd_eligible = !pool && m.grid >= 2 && m.grid * 8 <= h->capacity && m.grid <= prop.multiProcessorCount / 8 &&
+                            m.cell != SPRNN_CELL_LSTM_BACKWARD && m.cell != SPRNN_CELL_GRU_BACKWARD && !m.timeline;
+  if (xcd_opt == 2 && !xcd_eligible) { release(h); return SPRNN_ERR_UNSUPPORTED; }
+  h->one_xcd = xcd_opt == 2;
+  const bool try_one_xcd = xcd_opt == 0 && xcd_eligible && calibrate;
 
   const size_t ring_words = (size_t)kRingSlots * m.h_bytes / 4;
   std::vector<uint32_t> ring(ring_words, kSentinel);
@@ -331,7 +343,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   }
   if (!ok || !SPRNN_HIP(hipDeviceSynchronize())) { release(h); return SPRNN_ERR_HIP; }
   if (calibrate) {
-    const int rc2 = calibrate_poll_delay(h);
+    const int rc2 = calibrate_poll_delay(h, try_one_xcd);
     if (rc2 != SPRNN_OK) { release(h); return rc2; }
   }
   *out = h;
@@ -377,6 +389,8 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
     a.fill_src = h->d_fill_src; a.wg_plane = h->d_wg_plane; a.fill_rows = m.fill_rows;
     a.lane_sum = h->d_lane_sum; a.gather_waves = m.row_waves;
+    a.one_xcd = h->one_xcd ? 1 : 0;
+    a.launch_epoch = ex.shared_exchange ? 0u : h->launch_epoch;
     a.lds_h_bytes = m.grid == 1 ? m.lds_bytes / 2 : m.lds_bytes;
     a.ring = ring; a.ctrl = ctrl;
     a.x = x + (size_t)t0 * m.batch * m.rows;
@@ -400,10 +414,12 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     const bool plain = m.plain_launch != 0 || m.grid == 1;
     const bool lstm_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;   // the handle's own kernel is the backward pass
     const void* kernel = ex.backward ? (ex.dU ? h->kernel_bwd_grad : (lstm_bwd ? h->kernel : h->kernel_bwd)) : h->kernel;
-    hipError_t e = plain ? hipLaunchKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
-                         : hipLaunchCooperativeKernel(kernel, dim3(m.grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+    const int launch_grid = m.grid * (h->one_xcd ? 8 : 1);
+    hipError_t e = plain ? hipLaunchKernel(kernel, dim3(launch_grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
+                         : hipLaunchCooperativeKernel(kernel, dim3(launch_grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
     if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
     if (ex.shared_exchange) continue;   // (the handle's own ring did not move)
+    h->launch_epoch += 1;
     const int ran = tn + ((ex.backward && (ex.dh0 || ex.dU)) ? 1 : 0);   // the backward pass adds the step that pairs delta_1 with h_0
     h->step_base += (uint32_t)ran;
     h->barrier_base += (uint32_t)(ran - 1);   // one barrier before every step but the first
@@ -415,7 +431,7 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
 // conflicts, cell type).  Polling too early is far more expensive than polling late, and the sweet spot moves
 // from 3 to 12 units between the measured shapes, so it is measured once per handle: a short run on zero input
 // for a handful of candidates, keeping the fastest.  Timing does not depend on the data.
-static int calibrate_poll_delay(sprnn_handle_s* h) {
+static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd) {
   const Mapping& m = h->map;
   const int T = 48;
   // (the gated cells' backward passes read [T][B][4H] kept gate values from the zero buffer)
@@ -427,32 +443,52 @@ static int calibrate_poll_delay(sprnn_handle_s* h) {
             SPRNN_HIP(hipMalloc((void**)&d_h, hn * 4)) && (!lstm || SPRNN_HIP(hipMalloc((void**)&d_c, hn * 4))) &&
             SPRNN_HIP(hipEventCreate(&e0)) && SPRNN_HIP(hipEventCreate(&e1));
   int best = h->map.poll_delay;
+  bool best_one_xcd = h->one_xcd;
   int rc = SPRNN_OK;
   if (ok) {
-    static const int candidates[] = {2, 3, 4, 6, 8, 10, 12, 16};
+    // The exchange inside one XCD is shorter, so its candidates start lower; it is tried second, and dropped for good if
+    // the dispatcher did not put enough workgroups on one XCD (the kernel flags that in the status word and leaves).
+    static const int spread[] = {2, 3, 4, 6, 8, 10, 12, 16};
+    static const int local[] = {-1, 1, 2, 3, 4, 6};
     float best_ms = 0.0f;
-    for (int c : candidates) {
-      h->map.poll_delay = c;
-      float ms = 0.0f, best_of = 0.0f;
-      for (int rep = 0; rep < 4 && rc == SPRNN_OK; ++rep) {   // the first run of a setting warms up, the fastest of three counts
-        if (!SPRNN_HIP(hipEventRecord(e0, nullptr))) { ok = false; break; }
-        // (the LSTM's backward pass reads e_t, the gate values and the cell states: all from the zero buffer)
-        LaunchExtras ex;
-        const bool gated_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;
-        if (gated_bwd) { ex.backward = true; ex.saved = d_x; }
-        rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, gated_bwd ? d_x : d_c, nullptr, ex);
-        if (rc != SPRNN_OK) break;
-        if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
-        if (rep > 0 && (best_of == 0.0f || ms < best_of)) best_of = ms;
+    for (int mode = h->one_xcd ? 1 : 0; mode < ((try_one_xcd || h->one_xcd) ? 2 : 1) && ok && rc == SPRNN_OK; ++mode) {
+      h->one_xcd = mode == 1;
+      const int* cand = mode ? local : spread;
+      const int ncand = mode ? (int)(sizeof(local) / sizeof(int)) : (int)(sizeof(spread) / sizeof(int));
+      for (int ci = 0; ci < ncand; ++ci) {
+        const int c = cand[ci];
+        h->map.poll_delay = c < 0 ? 0 : c;
+        float ms = 0.0f, best_of = 0.0f;
+        for (int rep = 0; rep < 4 && rc == SPRNN_OK; ++rep) {   // the first run of a setting warms up, the fastest of three counts
+          if (!SPRNN_HIP(hipEventRecord(e0, nullptr))) { ok = false; break; }
+          // (the LSTM's backward pass reads e_t, the gate values and the cell states: all from the zero buffer)
+          LaunchExtras ex;
+          const bool gated_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;
+          if (gated_bwd) { ex.backward = true; ex.saved = d_x; }
+          rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, gated_bwd ? d_x : d_c, nullptr, ex);
+          if (rc != SPRNN_OK) break;
+          if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
+          if (rep > 0 && (best_of == 0.0f || ms < best_of)) best_of = ms;
+        }
+        ms = best_of;
+        if (!ok || rc != SPRNN_OK) break;
+        if (mode == 1) {
+          uint32_t status = 0;
+          if (!SPRNN_HIP(hipMemcpy(&status, h->d_ctrl + kCtrlStatus, 4, hipMemcpyDeviceToHost))) { ok = false; break; }
+          if (status & kStatusPlacement) {   // not enough workgroups on any XCD: this mode is not for this device state
+            status &= ~kStatusPlacement;
+            if (!SPRNN_HIP(hipMemcpy(h->d_ctrl + kCtrlStatus, &status, 4, hipMemcpyHostToDevice))) ok = false;
+            break;
+          }
+        }
+        if (best_ms == 0.0f || ms < best_ms) { best_ms = ms; best = h->map.poll_delay; best_one_xcd = mode == 1; }
       }
-      ms = best_of;
-      if (!ok || rc != SPRNN_OK) break;
-      if (best_ms == 0.0f || ms < best_ms) { best_ms = ms; best = c; }
     }
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
   (void)hipFree(d_x); (void)hipFree(d_h); (void)hipFree(d_c);
+  h->one_xcd = (ok && rc == SPRNN_OK) ? best_one_xcd : false;
   h->map.poll_delay = (ok && rc == SPRNN_OK) ? best : default_poll_delay(h->map);
   if (rc == SPRNN_OK && sprnn_check(h) != SPRNN_OK) rc = SPRNN_ERR_STATE;
   return rc;   // allocation or timing trouble is not fatal: the fallback value is used
@@ -741,6 +777,7 @@ int sprnn_read_timeline(sprnn_handle_t h, uint64_t* out, int capacity_words, dou
 int sprnn_get_info(sprnn_handle_t h, sprnn_info_t* info) {
   if (!h || !info) return SPRNN_ERR_INVALID;
   fill_info(h->map, h->capacity, h->pass_factor, info);
+  info->one_xcd = h->one_xcd ? 1 : 0;
   return SPRNN_OK;
 }
 

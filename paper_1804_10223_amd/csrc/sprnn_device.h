@@ -14,7 +14,9 @@ constexpr int kRingSlotsDev = 4;                  // exchange ring depth (power 
 constexpr uint32_t kSentinelBits = 0x80000000u;   // -0.0f marks a ring element that is not written yet
 constexpr int kCtrlStatus = 0;                    // ctrl[0]: non-zero once a spin watchdog tripped
 constexpr int kCtrlBarrier = 32;                  // grid-barrier mode: ctrl[32] top counter, ctrl[32 + 16 (1 + g)] counter of group g (64 bytes apart)
-constexpr int kCtrlWords = kCtrlBarrier + 16 * 9;
+constexpr int kCtrlPlacement = kCtrlBarrier + 16 * 9;   // one-XCD mode: two sets (launch parity) of 16 words: workgroups seen per XCD [0..7], arrivals [8]
+constexpr int kCtrlWords = kCtrlPlacement + 32;
+constexpr uint32_t kStatusWatchdog = 1u, kStatusPlacement = 2u;   // bits of the status word
 constexpr int kCellBackward = 100;                // persistent_kernel_for: backward pass of a vanilla cell
 constexpr int kCellBackwardGrad = 101;            // the same with the weight gradient fused in
 constexpr int kCellLstmBackwardGrad = 102;        // backward pass of the LSTM with the weight gradient fused in
@@ -51,6 +53,8 @@ struct KernelArgs {
   int lds_h_bytes;            // bytes of one LDS copy of h (= h_bytes without column compaction)
   int jitter;                 // test aid: seed of pseudo-random pauses (0 = none)
   int tl_wave;                // phase timeline: the wavefront of every workgroup that records it
+  int one_xcd;                // 1: the launch has 8 x the workgroups, those of one XCD take the work (see persistent_kernel)
+  uint32_t launch_epoch;      // launches of this handle so far (parity selects the placement counters)
   int gather_waves;           // lane-pool layout: wavefronts of a workgroup that hold weights (the others own the outputs)
   int index_shift;            // LDS byte offset of a packed word = (word >> 16) << index_shift
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
@@ -86,6 +90,7 @@ struct StepArgs {
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline);   // cell: SPRNN_ACT_* / SPRNN_CELL_*
 // (the instantiations live in four translation units; persistent_kernel_for forwards to these three)
 const void* persistent_timeline_kernel_for(int batch, int template_words, bool lstm);        // forward pass with the phase timeline
+const void* persistent_narrow_kernel_for(int batch, int template_words);                     // vanilla forward, batch 4, 4-byte gathers (ablation)
 const void* persistent_backward_kernel_for(int batch, int template_words, int cell);         // kCellBackward, kCellBackwardGrad
 const void* persistent_gated_backward_kernel_for(int batch, int template_words, int cell);   // SPRNN_CELL_*_BACKWARD, kCell{Lstm,Gru}BackwardGrad
 hipError_t launch_stepwise(int batch, bool lstm, const StepArgs& a, hipStream_t stream);

@@ -174,6 +174,9 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   m->timeline = (opt && opt->timeline) ? 1 : 0;
   m->plain_launch = (opt && opt->plain_launch) ? 1 : 0;
   m->jitter = opt ? opt->jitter : 0;
+  m->narrow = (opt && opt->gather == 2) ? 1 : 0;
+  if (opt && (opt->gather < 0 || opt->gather > 2)) return SPRNN_ERR_INVALID;
+  if (m->narrow && (batch != 4 || cell > SPRNN_ACT_IDENTITY || m->timeline)) return SPRNN_ERR_UNSUPPORTED;
   return SPRNN_OK;
 }
 
@@ -354,7 +357,7 @@ static int pack_pool(int hidden, int batch, int cell, const int32_t* row_ptr, co
   const int rows = hidden, cols = hidden, G = batch;
   const int64_t nnz = row_ptr[rows];
   if (num_cus < 1) return SPRNN_ERR_INVALID;
-  if (opt && (opt->compact == 1 || opt->lanes_per_row || opt->fill_waves || opt->balance == 1)) return SPRNN_ERR_CAPACITY;
+  if (opt && (opt->compact == 1 || opt->lanes_per_row || opt->fill_waves || opt->balance == 1 || opt->gather == 2)) return SPRNN_ERR_CAPACITY;
   constexpr int kMaxWavesPool = 8;      // gathering + output wavefronts of one workgroup (512 threads: 256 registers per lane)
   constexpr int64_t kRowCost = 8;       // what an (even empty) row adds to a workgroup's share besides its nonzeros
   const int max_rows_wg = (kMaxWavesPool - 4) * kWave / batch;   // output lanes for them must fit beside four gathering wavefronts

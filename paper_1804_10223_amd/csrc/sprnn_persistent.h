@@ -191,10 +191,18 @@ __device__ __forceinline__ int lds_load_int(uint32_t addr) {
   return *((volatile __attribute__((address_space(3))) int*)(uint32_t)addr);
 }
 
-template <int B>
+// NARROW: one 4-byte read per sample instead of one wide read per column (batch 4 only): the rung below Section 4.1's
+// wide loads in the ablation.  The four reads of a lane hit four different banks, but the lanes of a pass now spread
+// over a quarter of the banks per read, and the LDS has four times the instructions to serve.
+template <int B, bool NARROW = false>
 __device__ __forceinline__ Column<B> gather_column(uint32_t addr, int plane_bytes) {
   Column<B> c;
-  if constexpr (B == 1) {
+  if constexpr (NARROW && B == 4) {
+    c.lo.x = *SPRNN_LDS_PTR(float, addr);
+    c.lo.y = *SPRNN_LDS_PTR(float, addr + 4);
+    c.lo.z = *SPRNN_LDS_PTR(float, addr + 8);
+    c.lo.w = *SPRNN_LDS_PTR(float, addr + 12);
+  } else if constexpr (B == 1) {
     c.lo.x = *SPRNN_LDS_PTR(float, addr);
   } else if constexpr (B == 2) {
     const f32x2 v = *SPRNN_LDS_PTR(f32x2, addr);
@@ -242,12 +250,12 @@ __device__ __forceinline__ float dot_column(const float (&s)[B], const Column<B>
 
 // With GRAD, the gathered column also feeds the weight gradient of its nonzero: g[j] += sum_b side[b] * column[b]
 // (backward pass: the column is delta_{t+1} of the nonzero's column, side is the forward output of the lane's row).
-template <int B, int N, bool GRAD = false>
+template <int B, int N, bool GRAD = false, bool NARROW = false>
 __device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, const float* wv, int plane_bytes,
                                           float* g = nullptr, const float (*side)[B] = nullptr) {
   Column<B> c[N];
 #pragma unroll
-  for (int j = 0; j < N; ++j) c[j] = gather_column<B>(off[j], plane_bytes);
+  for (int j = 0; j < N; ++j) c[j] = gather_column<B, NARROW>(off[j], plane_bytes);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int j = 0; j < N; ++j) {
@@ -261,25 +269,25 @@ constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer t
 // The n_w (wavefront-uniform) packed words of a lane (w_off: absolute LDS addresses of their columns): gathers in
 // groups of four so the LDS reads are issued back to back; no early exit, so every register index stays static.
 // GS: words per group, 4 or 8 (see the kernel's choice).
-template <int B, int NW, bool GRAD = false, int GS = 4>
+template <int B, int NW, bool GRAD = false, int GS = 4, bool NARROW = false>
 __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w,
                                         int plane_bytes, float* g = nullptr, const float (*side)[B] = nullptr) {
 #pragma unroll
   for (int k = 0; k < NW; k += GS) {
     float* gk = GRAD ? g + k : nullptr;
     if (k + GS <= n_w) {
-      mac_words<B, GS, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
+      mac_words<B, GS, GRAD, NARROW>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
     } else if (k < n_w) {   // ragged tail
       const int rem = n_w - k;
       if (GS == 8 && rem >= 4) {
-        mac_words<B, 4, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
+        mac_words<B, 4, GRAD, NARROW>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
         float* gk4 = GRAD ? gk + 4 : nullptr;   // the second half's sums belong to words k + 4 ..
-        if (rem == 7) mac_words<B, 3, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
-        else if (rem == 6) mac_words<B, 2, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
-        else if (rem == 5) mac_words<B, 1, GRAD>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
-      } else if (rem == 3) mac_words<B, 3, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
-      else if (rem == 2) mac_words<B, 2, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
-      else mac_words<B, 1, GRAD>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
+        if (rem == 7) mac_words<B, 3, GRAD, NARROW>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
+        else if (rem == 6) mac_words<B, 2, GRAD, NARROW>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
+        else if (rem == 5) mac_words<B, 1, GRAD, NARROW>(acc, &w_off[k + 4], &w_val[k + 4], plane_bytes, gk4, side);
+      } else if (rem == 3) mac_words<B, 3, GRAD, NARROW>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
+      else if (rem == 2) mac_words<B, 2, GRAD, NARROW>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
+      else mac_words<B, 1, GRAD, NARROW>(acc, &w_off[k], &w_val[k], plane_bytes, gk, side);
     }
   }
 }
@@ -351,7 +359,9 @@ __device__ __forceinline__ long long tick(bool on) {
 // 7 = backward pass through time of the GRU: as 5 with three elements per unit, v = (dp_r | dp_z | dq) over the transposed
 // [H][3H] matrix; kept from the forward pass are r, z, n, q (p.aux, [T][B][4H]) and h_{t-1} (p.c_out, p.c0); the lane carries
 // dh_{t+1} z_{t+1}; outputs dL/db' = (dp_r | dp_z | da) in p.h_out and v itself in p.gates_out (the weight gradient's factor),
-// 8 = the same with the weight gradient fused in as in 4 and 6.
+// 8 = the same with the weight gradient fused in as in 4 and 6,
+// 9 = the vanilla cell's forward pass with one 4-byte LDS read per sample instead of one wide read per column (batch 4
+// only): the "no wide loads" rung of the ablation (options.gather).
 template <int B, int NW, int CELL, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL == 8) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
@@ -366,14 +376,52 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
   // h and writes h_t straight into the other one; otherwise one copy is enough, because the workgroup barrier
   // before a step's first poll also separates the last gather of step t from the first write of h_t.
   extern __shared__ __align__(16) unsigned char lds[];
-  const bool solo = gridDim.x == 1;   // no other workgroup to exchange with
+  // One-XCD mode (small layers: at most 32 workgroups): the launch holds eight times the workgroups the mapping needs,
+  // dealt over the eight XCDs by the dispatcher.  Every workgroup reports the XCD it runs on, waits until all have
+  // reported, and the first XCD that received enough of them takes the work; its workgroups number themselves in the
+  // order they arrived, all others leave.  The exchange then stays inside one L2: results are published with plain
+  // stores (no write-through to the memory side) and read with loads that only miss the per-CU cache.  If no XCD got
+  // enough workgroups the launch gives up and flags it in the status word.
+  int grid_x = (int)gridDim.x, wg_index = (int)blockIdx.x;
+  if (p.one_xcd) {
+    grid_x = (int)gridDim.x / 8;
+    const uint32_t flags = lds_address(lds);          // two words at the start of LDS, before anything else uses it
+    if (threadIdx.x == 0) {
+      uint32_t* const cnt = p.ctrl + kCtrlPlacement + 16 * (p.launch_epoch & 1u);
+      const uint32_t xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u;   // XCC_ID
+      const uint32_t order = __hip_atomic_fetch_add(cnt + xcc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(cnt + 8, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int rank = -1, spins = 0;
+      bool all_here = true;
+      while (__hip_atomic_load(cnt + 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gridDim.x) {
+        if (++spins > p.spin_limit) { all_here = false; break; }
+      }
+      int chosen = -1;
+      if (all_here) {
+        for (int x = 7; x >= 0; --x)
+          if (__hip_atomic_load(cnt + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= (uint32_t)grid_x) chosen = x;
+      }
+      if (chosen == (int)xcc && order < (uint32_t)grid_x) rank = (int)order;
+      if (chosen < 0 && blockIdx.x == 0) __hip_atomic_fetch_or(p.ctrl + kCtrlStatus, kStatusPlacement, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (blockIdx.x == 0) {   // the other set of counters belongs to the launch before (done) and the one after (not begun)
+        uint32_t* const other = p.ctrl + kCtrlPlacement + 16 * ((p.launch_epoch + 1u) & 1u);
+        for (int i = 0; i < 9; ++i) __hip_atomic_store(other + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      lds_store_int(flags, rank);
+    }
+    __syncthreads();
+    wg_index = lds_load_int(flags);
+    __syncthreads();                                   // (LDS is initialised only after everyone has read the flag)
+    if (wg_index < 0) return;
+  }
+  const bool solo = grid_x == 1;   // no other workgroup to exchange with
   unsigned char* const lds_tail = lds + (solo ? 2 : 1) * p.lds_h_bytes;
   // abort flags, indexed by step parity so that a fast wave's next-step flag cannot be read one step early
   const uint32_t s_abort = lds_address(lds_tail);   // LDS address of the two flags
   unsigned long long* s_tl = reinterpret_cast<unsigned long long*>(lds_tail + 16);
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int block = blockDim.x, wg = blockIdx.x;
+  const int block = blockDim.x, wg = wg_index;
   const int wave = __builtin_amdgcn_readfirstlane(tid) >> 6;
   const int H = p.hidden, L = p.lanes_per_row;
   const int R = LSTM ? 4 * H : H;
@@ -584,11 +632,11 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
           // dispatched to), the last arrival of a group reports to the top counter, and everybody waits for that.
           const uint32_t n = p.barrier_base + (uint32_t)t;
           uint32_t target;
-          if (gridDim.x < 64u) {
+          if (grid_x < 64) {
             __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            target = n * gridDim.x;
+            target = n * (uint32_t)grid_x;
           } else {
-            const uint32_t grp = (uint32_t)wg % 8u, members = gridDim.x / 8u + (grp < gridDim.x % 8u ? 1u : 0u);
+            const uint32_t grp = (uint32_t)wg % 8u, members = (uint32_t)grid_x / 8u + (grp < (uint32_t)grid_x % 8u ? 1u : 0u);
             const uint32_t before = __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier + 16 * (1 + grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (before + 1 == n * members) __hip_atomic_fetch_add(p.ctrl + kCtrlBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             target = n * 8u;
@@ -678,7 +726,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
       // waits for the LDS: 2.5 % on the headline shape); four otherwise: eight would spill at batch 8, measured no
       // better at batch 2 and for vanilla cells at batch 1, 15-20 % slower for the gated cells at batch 1, and at
       // batch 4 a few per cent either way for them depending on the words per lane.
-      operate<B, NW, false, (B == 4 && !LSTM) ? 8 : 4>(acc, w_off, w_val, n_w, plane_bytes);
+      operate<B, NW, false, (B == 4 && !LSTM) ? 8 : 4, CELL == 9>(acc, w_off, w_val, n_w, plane_bytes);
     }
     ts1 = tick<TL>(tl_on);
 
@@ -798,8 +846,13 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
       if (ring_voff != kOutOfRange) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = hval;
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
-      if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
+      if (p.one_xcd) {   // every workgroup shares one L2: plain stores reach it and need not go further
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, 0);
+        if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, 0);
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), ring, ring_voff, slot_byte, kAuxCoherent);
+        if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b32((int)kSentinelBits, ring, ring_voff, rearm_byte, kAuxCoherent);
+      }
     }
     if (BWD && t == p.T) {
       if (p.dh0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, hval), dbuf, out_voff, 0, 0);

@@ -71,3 +71,33 @@ def fill_seconds(workgroups: int, threads: int, nbytes: int, rounds: int = 200, 
     if rc:
         raise RuntimeError("sprnn_probe_fill failed (%d)" % rc)
     return out.value
+
+
+def lds_peak(width_bytes: int, workgroups: int = 256, threads: int = 1024, device: int = 0) -> float:
+    """Conflict-free LDS read rate in bytes/s with nothing but the reads in the timed loop: every wavefront reads 64
+    consecutive pieces of ``width_bytes`` (16 different ones per thread), the pattern the banks serve at full rate."""
+    import numpy as np
+    t = np.arange(threads)
+    offs = np.stack([(((t % 64) + 64 * ((t // 64 + k) % 16)) * width_bytes) % 65536 for k in range(16)]).astype(np.uint32)
+    return lds_gather_offsets(offs, width_bytes, workgroups=workgroups, device=device, bare=True)
+
+
+def handoff_ns_best(same_xcd: bool, launches: int = 5, rounds: int = 2000, device: int = 0):
+    """Smallest one-way store->observe latency over several probe launches (a latency floor is a minimum, and single
+    launches differ by tens of per cent with where the two workgroups land)."""
+    best, where = None, None
+    for _ in range(max(1, launches)):
+        ns, xcc = handoff_ns(same_xcd, rounds, device)
+        if best is None or ns < best:
+            best, where = ns, xcc
+    return best, where
+
+
+def fill_fit(sizes=(16384, 36864, 65536), workgroups: int = 256, threads: int = 1024, device: int = 0):
+    """Least-squares line through the copy times of several sizes: (seconds per byte, seconds at zero bytes, times).
+    The slope is the marginal rate at which one CU brings coherent memory into LDS while every CU does the same; the
+    intercept is the latency of the first piece, which the hand-off latency already accounts for."""
+    import numpy as np
+    times = [fill_seconds(workgroups, threads, int(n), device=device) for n in sizes]
+    slope, intercept = np.polyfit(np.asarray(sizes, dtype=np.float64), np.asarray(times, dtype=np.float64), 1)
+    return float(slope), float(intercept), dict(zip([int(n) for n in sizes], times))

@@ -2,13 +2,15 @@
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
     python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,cells,training,casestudy] [--reps 8]
+    python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged     (one rung alone, for counter passes)
 
 Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
 closed libraries on other hardware and are not reproduced):
 
   ablation   Table 1's shape (hidden 1152, batch 4, density 10 %, T 256) and the headline shape (2304, 30 %):
-             per-timestep launches -> persistent with a grid barrier and CSR-order nonzeros -> bank-aware
-             ordering -> tagged hand-off, with the packer's LDS pass model as the bank-conflict figure.
+             per-timestep launches -> persistent with 4-byte gathers, CSR-order nonzeros and a grid barrier ->
+             wide gathers -> bank-aware ordering -> tagged hand-off (Table 1's four rungs), with the packer's LDS pass
+             model as the bank-conflict figure; then the two layouts side by side.
   density / size / batch / steps
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
   constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
@@ -69,20 +71,31 @@ def measure(torch, w, reps, stepwise=False, **options):
     return us, info
 
 
+# The rungs of Table 1, each on top of the one before: no wide loads and a grid barrier ("naive"), wide loads
+# (Section 4.1), bank-aware order of a row's nonzeros (Section 4.1, Appendix A), validity carried by the data instead
+# of a barrier (Section 4.2's Lamport timestamps).
+RUNGS = [
+    ("naive", dict(sync="barrier", bank_aware=2, gather="narrow")),
+    ("wide", dict(sync="barrier", bank_aware=2, gather="wide")),
+    ("bank_aware", dict(sync="barrier", bank_aware=1, gather="wide")),
+    ("tagged", dict(sync="tagged", bank_aware=1, gather="wide")),
+]
+
+
 def ablation(torch, wl, reps):
-    print("## Ablation (cf. Table 1): microseconds per timestep, whole launch / T\n")
-    print("| shape | per-timestep launches | persistent, grid barrier, CSR order | + bank-aware order | tagged hand-off, CSR order | + bank-aware order (default) | LDS passes per gather: CSR order / bank-aware |")
-    print("|---|---|---|---|---|---|---|")
+    print("## Ablation (cf. Table 1): microseconds per timestep, whole launch / T (layout: one lane group per row)\n")
+    print("| shape | per-timestep launches | persistent: 4-byte gathers, CSR order, grid barrier | + wide gathers | + bank-aware order | + tagged hand-off (default) | tagged hand-off with CSR order | modelled LDS cycles per gather: CSR order / bank-aware |")
+    print("|---|---|---|---|---|---|---|---|")
     for name in ("cfg2", "cfg3"):
         w = wl.make_config(name)
         step, _ = measure(torch, w, reps, stepwise=True)
-        bn, i_n = measure(torch, w, reps, sync="barrier", bank_aware=2)
-        ba, i_a = measure(torch, w, reps, sync="barrier", bank_aware=1)
-        tn, _ = measure(torch, w, reps, sync="tagged", bank_aware=2)
-        ta, _ = measure(torch, w, reps, sync="tagged", bank_aware=1)
-        print("| %s: hidden %d, batch %d, density %.0f %%, T %d | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f / %.2f |" % (
-            name, w.hidden, w.batch, 100 * w.meta["density"], w.steps, step, bn, ba, tn, ta,
-            i_n["lds_pass_factor"], i_a["lds_pass_factor"]), flush=True)
+        got = {}
+        for rung, opts in RUNGS:
+            got[rung] = measure(torch, w, reps, layout=1, **opts)
+        tn, _ = measure(torch, w, reps, layout=1, sync="tagged", bank_aware=2)
+        print("| %s: hidden %d, batch %d, density %.0f %%, T %d | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f / %.2f |" % (
+            name, w.hidden, w.batch, 100 * w.meta["density"], w.steps, step, got["naive"][0], got["wide"][0], got["bank_aware"][0],
+            got["tagged"][0], tn, got["wide"][1]["lds_pass_factor"], got["bank_aware"][1]["lds_pass_factor"]), flush=True)
     print()
     w = wl.make_config("cfg4")
     b1, i1 = measure(torch, w, reps, balance=1)
@@ -90,6 +103,28 @@ def ablation(torch, wl, reps):
     print("Load balance (cf. Section 6), cfg4 (hidden 5760, batch 2, Poisson(576) rows): rows dealt by nonzero count "
           "%.2f us/step with %.1f %% padding; contiguous rows %.2f us/step with %.1f %% padding.\n" % (
               b1, 100.0 * (i1["padded_words"] / max(i1["nnz"], 1) - 1), b2, 100.0 * (i2["padded_words"] / max(i2["nnz"], 1) - 1)), flush=True)
+    print("Layout (cf. Section 6, load balancing by nonzero count): one lane group per row against the lane pool\n")
+    print("| shape | one lane group per row us/step | lane pool us/step | lane pool grid x block, words per lane | modelled LDS cycles per gather: groups / pool |")
+    print("|---|---|---|---|---|")
+    for name in ("cfg2", "cfg3", "cfg4"):
+        w = wl.make_config(name)
+        a, ia = measure(torch, w, reps, layout=1)
+        try:
+            b, ib = measure(torch, w, reps, layout=2)
+            print("| %s | %.2f | %.2f | %d x %d, %d | %.2f / %.2f |" % (name, a, b, ib["grid"], ib["block"], ib["words_per_lane_max"],
+                                                                 ia["lds_pass_factor"], ib["lds_pass_factor"]), flush=True)
+        except Exception as e:
+            print("| %s | %.2f | refused: %s | | |" % (name, a, e), flush=True)
+    print()
+
+
+def one_rung(torch, wl, reps, config, rung):
+    """One rung of the ablation alone in this process (so that a counter pass of the profiler sees only its launches)."""
+    opts = dict(RUNGS)[rung]
+    w = wl.make_config(config)
+    us, info = measure(torch, w, reps, layout=1, poll_delay=3, **opts)
+    print("rung %s on %s: %.3f us/step, grid %d x %d, modelled LDS cycles per gather %.3f" % (
+        rung, config, us, info["grid"], info["block"], info["lds_pass_factor"]), flush=True)
 
 
 def axis(torch, wl, reps, title, cases):
@@ -197,6 +232,8 @@ def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
+    ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged")
+    ap.add_argument("--config", default="cfg2", help="with --what rung: the configuration")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -204,6 +241,8 @@ def main():
         sys.exit(3)
     from . import workloads as wl
     what = args.what.split(",")
+    if "rung" in what:
+        one_rung(torch, wl, args.reps, args.config, args.rung)
     if "ablation" in what:
         ablation(torch, wl, args.reps)
     if "density" in what:

@@ -49,6 +49,7 @@ def run_case(w, e, **options):
     ("relu", 640, 4, 10, 0.3, "fixed", {"sync": "barrier"}),
     ("relu", 2000, 4, 6, 0.01, "poisson", {"compact": 1}),
     ("tanh", 1152, 4, 32, 0.1, "fixed", {}),
+    ("tanh", 640, 4, 12, 0.2, "fixed", {"xcd": "one"}),
 ])
 def test_backward_matches_oracle(cell, H, B, T, dens, rownnz, opts):
     w = wl.make_workload("bwd", cell, H, B, T, dens, seed=H + T, row_nnz=rownnz, h0_std=0.5)

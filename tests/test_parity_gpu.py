@@ -87,6 +87,15 @@ SMALL = [
     ("relu", 500, 4, 10, 0.2, "fixed", {"sync": "barrier"}),
     ("relu", 500, 1, 10, 0.2, "fixed", {"sync": "barrier", "grid": 6}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"poll_delay": -1}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"xcd": "one"}),                                 # every workgroup on one XCD, exchange through its L2
+    ("relu", 500, 4, 10, 0.2, "fixed", {"xcd": "one", "sync": "barrier", "grid": 7}),
+    ("tanh", 1152, 4, 20, 0.1, "fixed", {"xcd": "one", "grid": 32, "jitter": 3}),
+    ("relu", 1000, 2, 12, 0.05, "poisson", {"xcd": "one", "compact": 1, "grid": 13}),
+    ("lstm", 100, 4, 7, 0.2, "poisson", {"xcd": "one"}),
+    ("lstm", 256, 8, 9, 0.125, "fixed", {"xcd": "one", "poll_delay": 1}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"xcd": "spread"}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"gather": "narrow"}),                       # one 4-byte LDS read per sample (ablation rung)
+    ("tanh", 1152, 4, 12, 0.1, "fixed", {"gather": "narrow", "sync": "barrier", "bank_aware": 2}),   # the ablation's first rung
     ("relu", 500, 4, 10, 0.2, "fixed", {"plain_launch": 1}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"compact": 1}),
     ("relu", 2000, 4, 8, 0.01, "poisson", {"compact": 1, "grid": 50}),
@@ -353,6 +362,39 @@ def test_side_stream():
 
 
 # ------------------------------------------------------------------ error paths that need a device
+def test_one_xcd_mode_repeated_calls_and_refusal():
+    # many launches on one handle (the placement counters alternate between two sets and are cleared by the launch in
+    # between), results identical to the spread mapping's bit for bit; refused where 8 x grid workgroups cannot be resident
+    w = wl.make_workload("x", "relu", 768, 4, 10, 0.1, seed=7, h0_std=0.3)
+    x, h0 = _dev(w.x), _dev(w.h0)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, xcd="spread") as rnn:
+        want = rnn.forward(x, h0).cpu().numpy()
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, xcd="one") as rnn:
+        info = rnn.info()
+        print("case one xcd", {k: info[k] for k in ("grid", "block", "one_xcd", "poll_delay")}, flush=True)
+        assert info["one_xcd"] == 1
+        for i in range(7):
+            assert np.array_equal(rnn.forward(x, h0).cpu().numpy(), want), i
+        out = torch.empty_like(x)
+        rnn.forward_noalloc(x, h0, out)
+        assert np.array_equal(out.cpu().numpy(), want)
+        assert rnn.check() == binding.SPRNN_OK
+    big = wl.make_config("cfg3", steps=2)
+    with pytest.raises(binding.SprnnError) as e:
+        binding.SparseRNN(big.hidden, big.batch, big.cell, big.row_ptr, big.col_idx, big.val_bits, xcd="one")
+    assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:   # auto: measured at create time
+        print("case auto", rnn.info()["one_xcd"], rnn.info()["poll_delay"], flush=True)
+        assert np.array_equal(rnn.forward(x, h0).cpu().numpy(), want)
+
+
+def test_narrow_gathers_are_refused_where_not_built():
+    w = wl.make_workload("n", "relu", 200, 2, 2, 0.2, seed=0)
+    with pytest.raises(binding.SprnnError) as e:
+        binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, gather="narrow")
+    assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
+
+
 def test_wrong_cell_call_and_bad_arguments():
     w = wl.make_workload("s", "relu", 64, 2, 3, 0.2, seed=8)
     with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
