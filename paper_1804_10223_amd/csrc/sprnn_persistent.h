@@ -938,7 +938,9 @@ static const void* pick_nw(int nw) {
     case 24: return (const void*)persistent_kernel<B, 24, CELL, TL>;
     case 32: return (const void*)persistent_kernel<B, 32, CELL, TL>;
     case 48: return (const void*)persistent_kernel<B, 48, CELL, TL>;
-    case 64: return (const void*)persistent_kernel<B, 64, CELL, TL>;
+    case 64:   // (with the weight gradient fused in, batch 8 and 64 words per lane no longer fit in registers: not built)
+      if constexpr (B == 8 && (CELL == 4 || CELL == 6 || CELL == 8)) return nullptr;
+      else return (const void*)persistent_kernel<B, 64, CELL, TL>;
     default: return nullptr;
   }
 }

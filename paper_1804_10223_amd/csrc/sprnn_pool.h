@@ -356,10 +356,10 @@ __global__ __launch_bounds__(512) void pool_kernel(const KernelArgs p) {
 
 // Instantiations: every multiple of four words per lane up to 64 (the arithmetic runs over all NW slots, so the menu is
 // fine-grained), as far as everything stays in the 256 registers of a lane: the kernel with the weight gradient fused in
-// keeps one more register per word and goes up to 32 words, 24 at batch 8; the others up to 64, 48 at batch 8.
+// keeps one more register per word and goes up to 32 words, 16 at batch 8; the others up to 64, 48 at batch 8.
 template <int B, int CELL, bool TL = false>
 static const void* pick_pool_nw(int nw) {
-  constexpr int most = CELL == 4 ? (B == 8 ? 24 : 32) : (B == 8 ? 48 : 64);
+  constexpr int most = CELL == 4 ? (B == 8 ? 16 : 32) : (B == 8 ? 48 : 64);
 #define SPRNN_POOL_CASE(N) case N: if constexpr (most >= N) return (const void*)pool_kernel<B, N, CELL, TL>; else return nullptr;
   switch (nw) {
     SPRNN_POOL_CASE(4) SPRNN_POOL_CASE(8) SPRNN_POOL_CASE(12) SPRNN_POOL_CASE(16) SPRNN_POOL_CASE(20) SPRNN_POOL_CASE(24)

@@ -67,31 +67,40 @@ def test_drawn_backward_shapes_match_oracle(cell, H, B, T, dens, rownnz, opts, f
         want = dict(zip(("d", "dh0", "dU"), oracle.rnn_backward(H, B, cell, *csr, h, e, w.h0)))
     t_rp, t_ci, t_vb, t_src = binding.transpose_csr(w.rows, H, *csr, with_source=True)
     kind = {"lstm": "lstm_backward", "gru": "gru_backward"}.get(cell, cell)
-    got = {}
-    try:
-        with binding.SparseRNN(H, B, kind, t_rp, t_ci, t_vb, **opts) as rnn:
+    def run(options, with_weights):
+        out = {}
+        with binding.SparseRNN(H, B, kind, t_rp, t_ci, t_vb, **options) as rnn:
             if cell == "lstm":
-                if fused:
-                    got["d"], got["dh0"], got["dc0"], got["dU_t"] = rnn.backward_lstm_with_weights(_dev(e), _dev(gates), _dev(c), _dev(h), _dev(c0), _dev(w.h0))
+                if with_weights:
+                    out["d"], out["dh0"], out["dc0"], out["dU_t"] = rnn.backward_lstm_with_weights(_dev(e), _dev(gates), _dev(c), _dev(h), _dev(c0), _dev(w.h0))
                 else:
-                    got["d"], got["dh0"], got["dc0"] = rnn.backward_lstm(_dev(e), _dev(gates), _dev(c), _dev(c0))
+                    out["d"], out["dh0"], out["dc0"] = rnn.backward_lstm(_dev(e), _dev(gates), _dev(c), _dev(c0))
             elif cell == "gru":
-                if fused:
-                    got["d"], got["v"], got["dh0"], got["dU_t"] = rnn.backward_gru_with_weights(_dev(e), _dev(gates), _dev(h), _dev(w.h0))
+                if with_weights:
+                    out["d"], out["v"], out["dh0"], out["dU_t"] = rnn.backward_gru_with_weights(_dev(e), _dev(gates), _dev(h), _dev(w.h0))
                 else:
-                    got["d"], got["v"], got["dh0"] = rnn.backward_gru(_dev(e), _dev(gates), _dev(h), _dev(w.h0))
+                    out["d"], out["v"], out["dh0"] = rnn.backward_gru(_dev(e), _dev(gates), _dev(h), _dev(w.h0))
             else:
-                if fused:
-                    got["d"], got["dh0"], got["dU_t"] = rnn.backward_with_weights(_dev(e), _dev(h), _dev(w.h0))
+                if with_weights:
+                    out["d"], out["dh0"], out["dU_t"] = rnn.backward_with_weights(_dev(e), _dev(h), _dev(w.h0))
                 else:
-                    got["d"], got["dh0"] = rnn.backward(_dev(e), _dev(h))
+                    out["d"], out["dh0"] = rnn.backward(_dev(e), _dev(h))
             assert rnn.check() == binding.SPRNN_OK
-            got = {k: v.cpu().numpy() for k, v in got.items()}
-    except binding.SprnnError as err:
-        # a forced mapping may not fit, and the fused kernels are not built for every mapping: a clean refusal
-        assert err.code in (binding.SPRNN_ERR_CAPACITY, binding.SPRNN_ERR_INVALID, binding.SPRNN_ERR_UNSUPPORTED), err
-        assert opts or fused, "the library's own choice of mapping must always fit these sizes"
-        pytest.skip("refused: %s" % err)
+            return {k: v.cpu().numpy() for k, v in out.items()}
+
+    # A forced mapping may not fit, and the fused kernels are not built for every mapping.  Such a draw must be refused
+    # cleanly, and then runs without the part that was refused (first the fusion, then the forced option), so that every
+    # draw is compared with the oracle; the library's own mapping must always work.
+    got = None
+    for options, with_weights in ((opts, fused), (opts, False), ({}, fused), ({}, False)):
+        try:
+            got = run(options, with_weights)
+            print("   ran with", options, "fused" if with_weights else "plain", flush=True)
+            break
+        except binding.SprnnError as err:
+            assert err.code in (binding.SPRNN_ERR_CAPACITY, binding.SPRNN_ERR_INVALID, binding.SPRNN_ERR_UNSUPPORTED), err
+            assert options or with_weights, "the library's own choice of mapping must always fit these sizes"
+    assert got is not None
     for t in range(T):
         _close(got["d"][t], want["d"][t], "d_bprime[%d]" % t)
         if "v" in got:
@@ -103,6 +112,23 @@ def test_drawn_backward_shapes_match_oracle(cell, H, B, T, dens, rownnz, opts, f
         dU = np.empty_like(got["dU_t"])
         dU[t_src] = got["dU_t"]
         _close(dU, want["dU"], "dU")
+
+
+@pytest.mark.parametrize("cell,H,B,opts,code", [
+    ("relu", 100, 8, {"lanes_per_row": 4}, binding.SPRNN_ERR_INVALID),            # fewer lanes per row than samples
+    ("lstm_backward", 100, 4, {"lanes_per_row": 3}, binding.SPRNN_ERR_INVALID),   # not a power of two
+    ("gru_backward", 200, 4, {"waves": 13}, binding.SPRNN_ERR_INVALID),           # more wavefronts than a workgroup may have
+    ("relu", 3000, 4, {"compact": 2, "grid": 1}, binding.SPRNN_ERR_CAPACITY),     # one workgroup cannot hold two copies of h ... and all rows
+    ("lstm_backward", 20000, 1, {}, binding.SPRNN_ERR_UNSUPPORTED),               # 4H columns exceed 16-bit indices
+])
+def test_mappings_that_cannot_be_served_are_refused_cleanly(cell, H, B, opts, code):
+    gates = {"lstm_backward": 4, "gru_backward": 3}.get(cell, 1)
+    rows = H
+    row_ptr = np.arange(rows + 1, dtype=np.int32)
+    col = (np.arange(rows, dtype=np.int64) % (gates * H)).astype(np.int32)
+    with pytest.raises(binding.SprnnError) as err:
+        binding.SparseRNN(H, B, cell, row_ptr, col, np.full(rows, 0x3C00, np.uint16), **opts)
+    assert err.value.code == code, err.value
 
 
 @pytest.mark.parametrize("cell,H,B,T,dens", [

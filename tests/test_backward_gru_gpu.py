@@ -50,6 +50,44 @@ def run_backward(w, e, **options):
     return h, want_v, want_dU
 
 
+@pytest.mark.parametrize("B", [1, 2])
+def test_gru_backward_at_the_largest_hidden_size(B):
+    # H = 21845: 3H = 65535 gate rows, the most a 16-bit column index of the transposed matrix reaches.  H of the 3H
+    # rows of U hold a single 1.0, one per column, the last row among them: a wrong index moves a whole gate gradient
+    # to the wrong place, far outside the bar.
+    H, T = 21845, 3
+    rng = np.random.default_rng(21845 + B)
+    chosen = np.sort(np.concatenate([rng.permutation(3 * H - 1)[:H - 1], [3 * H - 1]])).astype(np.int64)
+    cols = rng.permutation(H).astype(np.int32)
+    counts = np.zeros(3 * H, dtype=np.int64)
+    counts[chosen] = 1
+    row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    ones = np.full(H, 0x3C00, dtype=np.uint16)
+    x = rng.standard_normal((T, B, 3 * H)).astype(np.float32)
+    b_hn = (rng.standard_normal(H) * 0.1).astype(np.float32)
+    h0 = (rng.standard_normal((B, H)) * 0.5).astype(np.float32)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    h, gates = oracle.gru_forward_saved(H, B, row_ptr, cols, ones, x, b_hn, h0, threads=8)
+    want_d, want_v, want_dh0, _, _ = oracle.gru_backward(H, B, row_ptr, cols, ones, gates, h, e, h0)
+    t_csr = binding.transpose_csr(3 * H, H, row_ptr, cols, ones)
+    assert t_csr[1].max() == 3 * H - 1 == 65534
+    with binding.SparseRNN(H, B, "gru_backward", *t_csr) as rnn:
+        info = rnn.info()
+        print("case gru_backward at the index limit, B", B, {k: info[k] for k in ("grid", "block", "compact", "lds_bytes")}, flush=True)
+        d, v, dh0 = rnn.backward_gru(_dev(e), _dev(gates), _dev(h), _dev(h0))
+        assert rnn.check() == binding.SPRNN_OK
+        d, v, dh0 = d.cpu().numpy(), v.cpu().numpy(), dh0.cpu().numpy()
+    for t in range(T):
+        _close(d[t], want_d[t], "d_bprime[%d]" % t)
+        _close(v[t], want_v[t], "d_recurrent[%d]" % t)
+    _close(dh0, want_dh0, "dh0")
+    # element by element too: every entry of dL/dh_0 holds one moved gate gradient of size O(1)
+    assert np.abs(dh0 - want_dh0).max() <= REL_TOL * max(1.0, np.abs(want_dh0).max())
+    with pytest.raises(binding.SprnnError) as err:                      # one more and the index no longer fits
+        binding.SparseRNN(H + 1, B, "gru_backward", np.zeros(H + 2, np.int32), np.zeros(0, np.int32), np.zeros(0, np.uint16))
+    assert err.value.code == binding.SPRNN_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("H,B,T,dens,rownnz,opts", [
     (96, 4, 9, 0.3, "fixed", {}),
     (257, 1, 7, 0.2, "poisson", {}),

@@ -74,6 +74,46 @@ def test_lstm_backward_matches_oracle(H, B, T, dens, rownnz, opts):
     run_backward(w, c0, e, **opts)
 
 
+@pytest.mark.parametrize("B", [1, 4])
+def test_lstm_backward_at_the_largest_hidden_size(B):
+    # H = 16383: 4H = 65532 gate rows, the most a 16-bit column index of the transposed matrix reaches.  H of the 4H
+    # rows of U hold a single 1.0, one per column, so dL/dh_{t-1} = e_{t-1} + (one gate gradient each): parity with
+    # the oracle as everywhere, and dL/dh_0 must be the chosen entries of dL/db'_0 bit for bit.
+    H, T = 16383, 3
+    rng = np.random.default_rng(16383 + B)
+    chosen = np.sort(rng.permutation(4 * H)[:H]).astype(np.int64)      # the rows of U that are not empty
+    cols = rng.permutation(H).astype(np.int32)                         # row chosen[k] reads column cols[k]
+    counts = np.zeros(4 * H, dtype=np.int64)
+    counts[chosen] = 1
+    row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    ones = np.full(H, 0x3C00, dtype=np.uint16)
+    x = rng.standard_normal((T, B, 4 * H)).astype(np.float32)
+    h0 = (rng.standard_normal((B, H)) * 0.5).astype(np.float32)
+    c0 = (rng.standard_normal((B, H)) * 0.5).astype(np.float32)
+    e = rng.standard_normal((T, B, H)).astype(np.float32)
+    h, c, gates = oracle.lstm_forward_saved(H, B, row_ptr, cols, ones, x, h0, c0, threads=8)
+    want_d, want_dh0, want_dc0, _ = oracle.lstm_backward(H, B, row_ptr, cols, ones, gates, c, h, e, h0, c0)
+    t_rp, t_ci, t_vb = binding.transpose_csr(4 * H, H, row_ptr, cols, ones)
+    gate_row_of_column = np.empty(H, dtype=np.int64)
+    gate_row_of_column[cols] = chosen
+    assert np.array_equal(t_ci[:H], gate_row_of_column) and t_ci.max() >= 4 * H - 40
+    with binding.SparseRNN(H, B, "lstm_backward", t_rp, t_ci, t_vb) as rnn:
+        info = rnn.info()
+        print("case lstm_backward at the index limit, B", B, {k: info[k] for k in ("grid", "block", "compact", "lds_bytes")}, flush=True)
+        got_d, got_dh0, got_dc0 = rnn.backward_lstm(_dev(e), _dev(gates), _dev(c), _dev(c0))
+        assert rnn.check() == binding.SPRNN_OK
+        got_d, got_dh0, got_dc0 = got_d.cpu().numpy(), got_dh0.cpu().numpy(), got_dc0.cpu().numpy()
+    for t in range(T):
+        _close(got_d[t], want_d[t], "d_bprime[%d]" % t)
+    _close(got_dh0, want_dh0, "dh0")
+    _close(got_dc0, want_dc0, "dc0")
+    moved = got_d[0][:, gate_row_of_column] + np.float32(0)
+    assert np.array_equal(got_dh0.view(np.uint32), moved.view(np.uint32))
+    with pytest.raises(binding.SprnnError) as err:                      # one more and the index no longer fits
+        binding.SparseRNN(H + 1, B, "lstm_backward", np.zeros(H + 2, np.int32), np.zeros(0, np.int32), np.zeros(0, np.uint16))
+    assert err.value.code == binding.SPRNN_ERR_UNSUPPORTED
+
+
 def test_lstm_backward_single_timestep_and_one_wanted_initial_gradient():
     H, B, T = 150, 2, 1
     w, c0, e = _workload(H, B, T, 0.3, "poisson", seed=21)

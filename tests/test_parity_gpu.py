@@ -137,7 +137,7 @@ def test_very_large_sparse_layer_fits_through_column_compaction():
     assert e.value.code == binding.SPRNN_ERR_CAPACITY
 
 
-@pytest.mark.parametrize("H,B", [(4099, 2), (20000, 1), (9000, 4)])
+@pytest.mark.parametrize("H,B", [(4099, 2), (20000, 1), (9000, 4), (65535, 1), (65535, 2)])   # 65535: the largest hidden size a 16-bit column index reaches
 def test_permutation_matrix_bit_exact_with_column_compaction(H, B):
     rng = np.random.default_rng(H)
     perm = rng.permutation(H).astype(np.int32)
@@ -228,7 +228,7 @@ def test_empty_rows_and_stored_zeros():
     check_workload(w)
 
 
-@pytest.mark.parametrize("H,B", [(7, 4), (4099, 2), (16384, 1), (4100, 4), (9000, 2), (20000, 1), (5000, 8)])
+@pytest.mark.parametrize("H,B", [(7, 4), (4099, 2), (16384, 1), (4100, 4), (9000, 2), (20000, 1), (5000, 8), (65535, 1)])
 def test_permutation_matrix_bit_exact(H, B):
     rng = np.random.default_rng(H)
     perm = rng.permutation(H).astype(np.int32)
