@@ -98,6 +98,10 @@ typedef struct sprnn_options_s {
                         the launch holds eight times the workgroups, those that the dispatcher put on one XCD take
                         the work and exchange h through that XCD's L2 alone (if it put too few there, the launch
                         leaves without results and sprnn_check reports SPRNN_ERR_STATE)                       */
+  int overlap;       /* copy of h into LDS overlapped with the gathers (vanilla cells, forward pass, batch <= 4, no column
+                        compaction, 2..8 copy rounds): 0 auto, 1 off, 2 on = the columns of h are consumed in two
+                        parts; a row's nonzeros of the first part sit in its lanes' leading slots and are worked
+                        through while the second part is still arriving                                    */
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */
@@ -118,7 +122,10 @@ typedef struct sprnn_info_s {
   int layout;               /* 1 = one lane group per row, 2 = lane pool (see sprnn_options_t.layout)   */
   int gather_waves;         /* wavefronts per workgroup that hold weights (all of them for layout 1)    */
   int one_xcd;              /* 1 if the workgroups are confined to one XCD (see sprnn_options_t.xcd)     */
-  int reserved[4];
+  int overlap_rounds;       /* > 0: copy rounds (one 16-byte piece per lane each) that make up the first part of h when
+                               the copy is overlapped with the gathers (see sprnn_options_t.overlap)     */
+  int overlap_words;        /* leading slots per lane that read only that first part: least over the wavefronts */
+  int reserved[2];
 } sprnn_info_t;
 
 /*

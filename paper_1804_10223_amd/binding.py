@@ -42,7 +42,7 @@ class Options(ctypes.Structure):
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
                 ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
-                ("gather", ctypes.c_int), ("xcd", ctypes.c_int)]
+                ("gather", ctypes.c_int), ("xcd", ctypes.c_int), ("overlap", ctypes.c_int)]
 
 
 class Info(ctypes.Structure):
@@ -54,7 +54,8 @@ class Info(ctypes.Structure):
                 ("lds_bytes", ctypes.c_int), ("resident_capacity", ctypes.c_int),
                 ("nnz", ctypes.c_int64), ("padded_words", ctypes.c_int64), ("ring_bytes", ctypes.c_int64),
                 ("lds_pass_factor", ctypes.c_double), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
-                ("gather_waves", ctypes.c_int), ("one_xcd", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
+                ("gather_waves", ctypes.c_int), ("one_xcd", ctypes.c_int), ("overlap_rounds", ctypes.c_int),
+                ("overlap_words", ctypes.c_int), ("reserved", ctypes.c_int * 2)]
 
     def as_dict(self) -> dict:
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
@@ -433,12 +434,15 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_forward_gru")
         return h_out
 
-    def forward_gru_train(self, x, b_hn=None, h0=None):
-        """sprnn_forward_gru_train: x [T, B, 3H] -> (h_out [T, B, H], gates [T, B, 4H] = r | z | n | q)."""
+    def forward_gru_train(self, x, b_hn=None, h0=None, h_out=None, gates=None):
+        """sprnn_forward_gru_train: x [T, B, 3H] -> (h_out [T, B, H], gates [T, B, 4H] = r | z | n | q).
+        Outputs the caller does not pass are allocated here."""
         import torch
         T = int(x.shape[0])
-        h_out = self._alloc(T)
-        gates = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device="cuda:%d" % self.device)
+        if h_out is None:
+            h_out = self._alloc(T)
+        if gates is None:
+            gates = torch.empty((T, self.batch, 4 * self.hidden), dtype=torch.float32, device="cuda:%d" % self.device)
         rc = self._lib.sprnn_forward_gru_train(self._h, T, _dev_ptr(x, (T, self.batch, self.rows), "x"),
                                                _dev_ptr(b_hn, (self.hidden,), "b_hn"), _dev_ptr(h0, (self.batch, self.hidden), "h0"),
                                                _dev_ptr(h_out, (T, self.batch, self.hidden), "h_out"),
@@ -447,15 +451,20 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_forward_gru_train")
         return h_out, gates
 
-    def backward_gru(self, dh_ext, gates, h_fwd, h0=None, want_dh0=True, want_recurrent=True):
+    def backward_gru(self, dh_ext, gates, h_fwd, h0=None, want_dh0=True, want_recurrent=True, d_bprime=None, d_recurrent=None, dh0=None):
         """sprnn_backward_gru on a "gru_backward" handle (the TRANSPOSED [H][3H] matrix):
-        (d_bprime [T, B, 3H], d_recurrent [T, B, 3H] or None, dh0 [B, H] or None)."""
+        (d_bprime [T, B, 3H], d_recurrent [T, B, 3H] or None, dh0 [B, H] or None).  Outputs the caller does not pass are
+        allocated here."""
         import torch
         T = int(dh_ext.shape[0])
         dev = "cuda:%d" % self.device
-        d_bprime = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
-        d_rec = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev) if want_recurrent else None
-        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
+        if d_bprime is None:
+            d_bprime = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
+        d_rec = d_recurrent
+        if d_rec is None and want_recurrent:
+            d_rec = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
+        if dh0 is None and want_dh0:
+            dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev)
         rc = self._lib.sprnn_backward_gru(self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
                                           _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"),
                                           _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),
@@ -467,17 +476,24 @@ class SparseRNN:
             raise SprnnError(rc, "sprnn_backward_gru")
         return d_bprime, d_rec, dh0
 
-    def backward_gru_with_weights(self, dh_ext, gates, h_fwd, h0=None, want_dh0=True, want_recurrent=True):
+    def backward_gru_with_weights(self, dh_ext, gates, h_fwd, h0=None, want_dh0=True, want_recurrent=True,
+                                  d_bprime=None, d_recurrent=None, dh0=None, dU=None):
         """sprnn_backward_gru_with_weights on a "gru_backward" handle:
-        (d_bprime [T, B, 3H], d_recurrent or None, dh0 or None, dU [nnz] in the transposed matrix's CSR order)."""
+        (d_bprime [T, B, 3H], d_recurrent or None, dh0 or None, dU [nnz] in the transposed matrix's CSR order).
+        Outputs the caller does not pass are allocated here (dU: at least max(nnz, 1) elements)."""
         import torch
         T = int(dh_ext.shape[0])
         dev = "cuda:%d" % self.device
-        nnz = self.info()["nnz"]
-        d_bprime = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
-        d_rec = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev) if want_recurrent else None
-        dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev) if want_dh0 else None
-        dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
+        nnz = self._nnz()
+        if d_bprime is None:
+            d_bprime = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
+        d_rec = d_recurrent
+        if d_rec is None and want_recurrent:
+            d_rec = torch.empty((T, self.batch, 3 * self.hidden), dtype=torch.float32, device=dev)
+        if dh0 is None and want_dh0:
+            dh0 = torch.empty((self.batch, self.hidden), dtype=torch.float32, device=dev)
+        if dU is None:
+            dU = torch.empty((max(nnz, 1),), dtype=torch.float32, device=dev)
         rc = self._lib.sprnn_backward_gru_with_weights(
             self._h, T, _dev_ptr(dh_ext, (T, self.batch, self.hidden), "dh_ext"),
             _dev_ptr(gates, (T, self.batch, 4 * self.hidden), "gates"), _dev_ptr(h_fwd, (T, self.batch, self.hidden), "h_fwd"),

@@ -28,6 +28,7 @@ struct sprnn_handle_s {
   uint32_t* d_words = nullptr;
   int32_t* d_lane_row = nullptr;
   int32_t* d_wave_words = nullptr;
+  int32_t* d_wave_early = nullptr;   // two-part copy only
   uint32_t* d_fill_src = nullptr;    // column compaction only
   int32_t* d_wg_plane = nullptr;
   int32_t* d_lane_sum = nullptr;     // lane-pool layout only
@@ -94,6 +95,8 @@ void fill_info(const Mapping& m, int capacity, double pass_factor, sprnn_info_t*
   info->compact = m.compact;
   info->layout = m.layout ? 2 : 1;
   info->gather_waves = m.row_waves;
+  info->overlap_rounds = m.seg_rounds;
+  info->overlap_words = m.seg_words;
 }
 // (fill_info has no handle: the one-XCD flag is added by sprnn_get_info)
 
@@ -108,7 +111,7 @@ hipError_t upload(T** dst, const T* src, size_t n) {
 
 void release(sprnn_handle_s* h) {
   if (!h) return;
-  (void)hipFree(h->d_words); (void)hipFree(h->d_lane_row); (void)hipFree(h->d_wave_words);
+  (void)hipFree(h->d_words); (void)hipFree(h->d_lane_row); (void)hipFree(h->d_wave_words); (void)hipFree(h->d_wave_early);
   (void)hipFree(h->d_fill_src); (void)hipFree(h->d_wg_plane); (void)hipFree(h->d_word_src); (void)hipFree(h->d_lane_sum);
   (void)hipFree(h->d_ring); (void)hipFree(h->d_ctrl); (void)hipFree(h->d_timeline);
   (void)hipFree(h->d_row_ptr); (void)hipFree(h->d_col); (void)hipFree(h->d_val);
@@ -246,7 +249,9 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   const Mapping& m = h->map;
   const bool pool = m.layout == 1;
   h->kernel = pool ? pool_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0)
-                   : (m.narrow ? persistent_narrow_kernel_for(m.batch, m.template_words) : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0));
+                   : (m.narrow ? persistent_narrow_kernel_for(m.batch, m.template_words)
+                               : (m.seg_rounds ? persistent_overlap_kernel_for(m.batch, m.template_words, m.timeline != 0)
+                                               : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0)));
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
@@ -296,6 +301,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
             (!m.compact || (SPRNN_HIP(upload(&h->d_fill_src, P.fill_src.data(), P.fill_src.size())) &&
                             SPRNN_HIP(upload(&h->d_wg_plane, P.wg_plane.data(), P.wg_plane.size())))) &&
             (!pool || SPRNN_HIP(upload(&h->d_lane_sum, P.lane_sum.data(), P.lane_sum.size()))) &&
+            (!m.seg_rounds || SPRNN_HIP(upload(&h->d_wave_early, P.wave_early.data(), P.wave_early.size()))) &&
             SPRNN_HIP(upload(&h->d_ring, ring.data(), ring.size())) &&
             SPRNN_HIP(upload(&h->d_ctrl, ctrl.data(), ctrl.size())) &&
             SPRNN_HIP(upload(&h->d_row_ptr, row_ptr, (size_t)rows + 1)) &&
@@ -389,6 +395,8 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.words = h->d_words; a.lane_row = h->d_lane_row; a.wave_words = h->d_wave_words;
     a.fill_src = h->d_fill_src; a.wg_plane = h->d_wg_plane; a.fill_rows = m.fill_rows;
     a.lane_sum = h->d_lane_sum; a.gather_waves = m.row_waves;
+    a.wave_early = ex.backward ? nullptr : h->d_wave_early;   // (only the forward pass consumes h in two parts)
+    a.seg_rounds = ex.backward ? 0 : m.seg_rounds;
     a.one_xcd = h->one_xcd ? 1 : 0;
     a.launch_epoch = ex.shared_exchange ? 0u : h->launch_epoch;
     a.lds_h_bytes = m.grid == 1 ? m.lds_bytes / 2 : m.lds_bytes;

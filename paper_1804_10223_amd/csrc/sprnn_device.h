@@ -30,6 +30,7 @@ struct KernelArgs {
   const int32_t* wave_words;  // [grid][waves]
   const uint32_t* fill_src;   // column compaction: [grid][fill_rows][block] copy list, or null
   const int32_t* wg_plane;    // column compaction: [grid] bytes of one plane of the workgroup's LDS copy
+  const int32_t* wave_early;  // two-part copy: [grid][waves] leading slots of a wavefront's lanes that read only the first part, or null
   const int32_t* lane_sum;    // lane-pool layout: [grid][block] for an output lane: first group of its row | groups << 16
   uint32_t* ring;             // [4][h_bytes / 4]
   uint32_t* ctrl;             // [kCtrlWords]
@@ -55,6 +56,7 @@ struct KernelArgs {
   int tl_wave;                // phase timeline: the wavefront of every workgroup that records it
   int one_xcd;                // 1: the launch has 8 x the workgroups, those of one XCD take the work (see persistent_kernel)
   uint32_t launch_epoch;      // launches of this handle so far (parity selects the placement counters)
+  int seg_rounds;             // > 0: the copy of h is consumed in two parts, its first seg_rounds rounds first (see persistent_kernel)
   int gather_waves;           // lane-pool layout: wavefronts of a workgroup that hold weights (the others own the outputs)
   int index_shift;            // LDS byte offset of a packed word = (word >> 16) << index_shift
   uint32_t step_base;         // global index of the first step of this call (ring slot = index mod 4)
@@ -90,6 +92,7 @@ struct StepArgs {
 const void* persistent_kernel_for(int batch, int template_words, int cell, bool timeline);   // cell: SPRNN_ACT_* / SPRNN_CELL_*
 // (the instantiations live in four translation units; persistent_kernel_for forwards to these three)
 const void* persistent_timeline_kernel_for(int batch, int template_words, bool lstm);        // forward pass with the phase timeline
+const void* persistent_overlap_kernel_for(int batch, int template_words, bool timeline);     // vanilla forward with the copy of h consumed in two parts (batch <= 4; timeline: batch 4)
 const void* persistent_narrow_kernel_for(int batch, int template_words);                     // vanilla forward, batch 4, 4-byte gathers (ablation)
 const void* persistent_backward_kernel_for(int batch, int template_words, int cell);         // kCellBackward, kCellBackwardGrad
 const void* persistent_gated_backward_kernel_for(int batch, int template_words, int cell);   // SPRNN_CELL_*_BACKWARD, kCell{Lstm,Gru}BackwardGrad

@@ -300,6 +300,48 @@ static void order_wave(std::vector<RowGroup>& rg, int L, int trip, const PassMod
   for (size_t q = 0; q < rg.size(); ++q) rg[q].pos = std::move(segs[q].pos);
 }
 
+// Two-phase order for the overlap of the copy with the gathers (Section 4.2 wants useful work while the load stage is
+// still in flight): the columns below seg_col reach LDS first, and slots [0, k1) of every lane may only hold nonzeros
+// of those columns (or fillers), so that a wavefront can work through them while the rest of h is still on its way.
+// Largest k1 (a multiple of four, the gathers' group size) that needs no extra slot: what a row cannot place in the
+// first k1 slots must fit into the other trip - k1.
+static int phase_words(const std::vector<RowGroup>& rg, int L, int trip, int seg_col) {
+  int k1 = trip / 4 * 4;
+  for (const RowGroup& q : rg) {
+    if (q.row < 0) continue;
+    int n0 = 0;
+    for (const Nz& z : q.items) n0 += z.col < seg_col ? 1 : 0;
+    const int n = (int)q.items.size();
+    while (k1 > 0 && n - std::min(n0, k1 * L) > (trip - k1) * L) k1 -= 4;
+  }
+  return k1;
+}
+
+static void order_wave_phased(std::vector<RowGroup>& rg, int L, int trip, int k1, int seg_col, const PassModel& pm, bool bank_aware) {
+  std::vector<Seg> early(rg.size()), late(rg.size());
+  std::vector<std::vector<int>> early_of(rg.size()), late_of(rg.size());   // index into the row's items
+  for (size_t q = 0; q < rg.size(); ++q) {
+    early[q].lane0 = late[q].lane0 = rg[q].lane0;
+    early[q].n = late[q].n = L;
+    early[q].row = late[q].row = rg[q].row;
+    for (int i = 0; i < (int)rg[q].items.size(); ++i) {
+      const bool first = rg[q].items[i].col < seg_col && (int)early_of[q].size() < k1 * L;
+      (first ? early_of[q] : late_of[q]).push_back(i);
+      (first ? early[q] : late[q]).items.push_back(rg[q].items[i]);
+    }
+  }
+  order_segments(early, k1, pm, bank_aware);
+  order_segments(late, trip - k1, pm, bank_aware);
+  for (size_t q = 0; q < rg.size(); ++q) {
+    rg[q].pos.assign((size_t)trip * L, -1);
+    for (int k = 0; k < trip; ++k)
+      for (int l = 0; l < L; ++l) {
+        const int i = k < k1 ? early[q].pos[(size_t)k * L + l] : late[q].pos[(size_t)(k - k1) * L + l];
+        if (i >= 0) rg[q].pos[(size_t)k * L + l] = k < k1 ? early_of[q][i] : late_of[q][i];
+      }
+  }
+}
+
 // Filler words should not add bank conflicts: give each one a column whose bank group is still free in
 // its pass (or, failing that, an address that another lane of the pass already reads: a broadcast).
 static void place_fillers(Packed& P, const std::vector<int>& wg_cols, const std::vector<char>& is_real_zero) {
@@ -654,6 +696,17 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   std::vector<int32_t> chunk_pos(compact ? (size_t)chunks_per_plane : 0);
   auto lds_col = [&](int col) { return compact ? chunk_pos[col / cpc] * cpc + col % cpc : col; };
 
+  // Overlap of the copy with the gathers: the first seg_rounds of the copy's rounds (a round = one 16-byte chunk per
+  // lane of the workgroup) bring the columns below seg_col; see order_wave_phased.
+  const int overlap = opt ? opt->overlap : 0;
+  if (overlap < 0 || overlap > 2) return SPRNN_ERR_INVALID;
+  const int copy_rounds = ceil_div(m.h_bytes / 16, m.block);
+  const bool can_overlap = !compact && m.grid > 1 && planes == 1 && cell <= SPRNN_ACT_IDENTITY && m.sync == SPRNN_SYNC_TAGGED &&
+                           copy_rounds >= 2 && copy_rounds <= 8 && !m.narrow;
+  if (overlap == 2 && !can_overlap) return SPRNN_ERR_UNSUPPORTED;
+  m.seg_rounds = (overlap == 2 && can_overlap) ? copy_rounds / 2 : 0;
+  const int seg_col = m.seg_rounds * m.block * cpc;
+
   Packed& P = *out;
   P.map = m;
   const int NW = m.template_words;
@@ -679,6 +732,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   P.lane_row.assign(lanes, -1);
   P.lane_words.assign(lanes, 0);
   P.wave_words.assign(total_waves, 0);
+  if (m.seg_rounds) P.wave_early.assign(total_waves, 0);
 
   const PassModel pm = make_pass_model(batch);
   auto pad_word = [&](int lane_in_wave, int k, int ncols) -> uint32_t {
@@ -723,7 +777,13 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
         rg.push_back(std::move(q));
       }
     }
-    order_wave(rg, L, trip, pm, m.bank_aware == 1);
+    if (m.seg_rounds) {
+      const int k1 = phase_words(rg, L, trip, seg_col);
+      P.wave_early[gw] = k1;
+      order_wave_phased(rg, L, trip, k1, seg_col, pm, m.bank_aware == 1);
+    } else {
+      order_wave(rg, L, trip, pm, m.bank_aware == 1);
+    }
     for (const RowGroup& q : rg) {
       const size_t tid0 = (size_t)wg * m.block + (size_t)wave * kWave + q.lane0;
       for (int l = 0; l < L; ++l) P.lane_row[tid0 + l] = q.row < m.rows ? q.row : -1;   // the GRU's empty fourth row owns nothing
@@ -743,6 +803,12 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   place_fillers(P, wg_cols, is_real_zero);
   P.map.words_max = words_max;
   P.map.padded_words = padded;
+  if (m.seg_rounds) {
+    int least = -1;
+    for (int gw = 0; gw < total_waves; ++gw)
+      if (P.wave_words[gw] > 0 && (least < 0 || P.wave_early[gw] < least)) least = P.wave_early[gw];
+    P.map.seg_words = std::max(least, 0);
+  }
   return SPRNN_OK;
 }
 

@@ -41,6 +41,8 @@ struct Mapping {
   int compact = 0;           // 1: a workgroup copies only the chunks of h that its rows read (see pack())
   int fill_rows = 0;         // compaction: rounds in the per-workgroup copy list
   int stage_bytes = 0;       // LSTM: per-workgroup LDS area through which gate sums reach the cell lanes; lane-pool layout: the group sums
+  int seg_words = 0;         // two-part copy: least number of leading slots (over the wavefronts that hold weights) that read only the first part
+  int seg_rounds = 0;        // > 0: the copy of h is consumed in two parts, the first seg_rounds rounds of it first (see pack())
   int layout = 0;            // 0: one power-of-two lane group per row; 1: lane pool (see pack_pool): row_waves gather, the others own the outputs
   int group = 0;             // lane pool: lanes per group (= batch); a row takes whole groups
   int64_t nnz = 0, padded_words = 0;
@@ -52,6 +54,7 @@ struct Packed {
   std::vector<int32_t> lane_row;    // [grid][block]  row of W served by the lane, -1 if idle
   std::vector<int32_t> lane_words;  // [grid][block]  real (non-padding) words of the lane
   std::vector<int32_t> wave_words;  // [grid][waves]  loop trip count of each wavefront
+  std::vector<int32_t> wave_early;  // two-part copy: [grid][waves] leading slots that only read columns of the first part
   std::vector<uint32_t> fill_src;   // compaction: [grid][fill_rows][block] ring byte offset of each copied chunk (out of range: none)
   std::vector<int32_t> wg_plane;    // compaction: [grid] bytes of one plane of the workgroup's LDS copy
   std::vector<int32_t> word_src;    // [grid][template_words][block] CSR position of the nonzero a packed word holds, -1 for padding

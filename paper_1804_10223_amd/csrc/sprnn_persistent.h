@@ -292,6 +292,71 @@ __device__ __forceinline__ void operate(float (&acc)[B], const uint32_t (&w_off)
   }
 }
 
+// Words [lo, hi) of a lane (wavefront-uniform bounds, lo a multiple of four): the two-part copy works through a lane's
+// leading words while the rest of h is still arriving, and through the others afterwards.  Groups of eight gathers
+// where a whole one lies inside the span, of four otherwise.
+template <int B, int NW, int K>
+__device__ __forceinline__ void span_four(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int lo, int hi, int plane_bytes) {
+  if constexpr (K < NW) {   // (NW is a multiple of eight, so four slots from K on exist)
+    if (K >= lo && K < hi) {
+      const int rem = hi - K;
+      if (rem >= 4) mac_words<B, 4>(acc, &w_off[K], &w_val[K], plane_bytes);
+      else if (rem == 3) mac_words<B, 3>(acc, &w_off[K], &w_val[K], plane_bytes);
+      else if (rem == 2) mac_words<B, 2>(acc, &w_off[K], &w_val[K], plane_bytes);
+      else mac_words<B, 1>(acc, &w_off[K], &w_val[K], plane_bytes);
+    }
+  }
+}
+template <int B, int NW, int K = 0>
+__device__ __forceinline__ void operate_span(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int lo, int hi,
+                                             int plane_bytes) {
+  if constexpr (K < NW) {
+    if (K >= lo && K + 8 <= hi) {
+      mac_words<B, 8>(acc, &w_off[K], &w_val[K], plane_bytes);
+    } else {
+      span_four<B, NW, K>(acc, w_off, w_val, lo, hi, plane_bytes);
+      span_four<B, NW, K + 4>(acc, w_off, w_val, lo, hi, plane_bytes);
+    }
+    operate_span<B, NW, K + 8>(acc, w_off, w_val, lo, hi, plane_bytes);
+  }
+}
+
+// The chunks of rounds [LO, HI) of a copy whose loads (v, from ring offsets `off`) are already in flight: wait until
+// all of them are written (polling again where the "not written" mark is still there; bounded like copy_chunks), then
+// put them into LDS at the same offsets.  Returns false when the wait was given up.  The bounds are compile-time values so
+// that the wait for a load's data counts exactly the loads issued after it: the later rounds stay in flight.
+template <int D, int LO, int HI>
+__device__ __forceinline__ bool finish_chunks(__amdgpu_buffer_rsrc_t ring, int slot_byte, const int (&off)[D], i32x4 (&v)[D],
+                                              unsigned char* dst, int spin_limit, const uint32_t* status_word, unsigned long long& repolls) {
+  // The first check stands outside the polling loop: straight-line code after the loads were issued, where the wait
+  // for round c's data is "all but the HI - 1 - c .. loads issued after it"; inside a loop the compiler has to assume
+  // the worst of both ways into it and would wait for every load in flight.
+  auto all_written_now = [&]() {
+    int low = min_word(v[LO]);
+#pragma unroll
+    for (int c = LO + 1; c < HI; ++c) low = min(low, min_word(v[c]));
+    return __builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) == 0;
+  };
+  bool ok = true;
+  if (!all_written_now()) {
+    int spins = 0;
+    for (;;) {
+      ++spins;
+      ++repolls;
+      if (spins > spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(status_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+        ok = false;
+        break;
+      }
+#pragma unroll
+      for (int c = LO; c < HI; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
+      if (all_written_now()) break;
+    }
+  }
+#pragma unroll
+  for (int c = LO; c < HI; ++c) *reinterpret_cast<i32x4*>(dst + off[c]) = v[c];
+  return ok;
+}
+
 // Copy D 16-byte chunks per lane from a ring slot (byte offsets `off`) into LDS (byte offsets `to`), all D loads in
 // flight at once.  With MAYSKIP an entry with to[c] < 0 is empty: its source offset lies out of range, so the load
 // costs no memory traffic and returns zeros, and nothing is written.  A chunk that still holds the "not written" mark makes
@@ -340,6 +405,32 @@ __device__ __forceinline__ long long tick(bool on) {
   return 0;
 }
 
+// The load stage of the two-part copy for a copy of R rounds, the first R / 2 of them forming the first part: all R
+// loads go out at once; the first part is checked, stored and, after a barrier that orders LDS traffic only (so the
+// other loads stay in flight across it), every wavefront works through the `early` leading words of its lanes; then the
+// second part is checked and stored.  A wavefront that gave up still meets the others at the barrier.
+// (LDS mirrors the ring slot: round c of lane tid is the chunk tid + c * block, clamped to the last one.)
+template <int B, int NW, int R, bool TL>
+__device__ __forceinline__ bool copy_two_parts(__amdgpu_buffer_rsrc_t ring, int slot_byte, int tid, int block, int last_chunk, unsigned char* dst,
+                                               int spin_limit, const uint32_t* status_word, unsigned long long& repolls, int jitter,
+                                               uint32_t wave_id, uint32_t step, float (&acc)[B], const uint32_t (&w_off)[NW],
+                                               const float (&w_val)[NW], int early, int plane_bytes, bool tl_on, long long& t_first) {
+  constexpr int R0 = R / 2;
+  int off[R];
+  i32x4 v[R];
+#pragma unroll
+  for (int c = 0; c < R; ++c) off[c] = min(tid + c * block, last_chunk) * 16;
+#pragma unroll
+  for (int c = 0; c < R; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
+  bool ok = finish_chunks<R, 0, R0>(ring, slot_byte, off, v, dst, spin_limit, status_word, repolls);
+  jitter_pause(jitter, wave_id, step, 4);
+  lds_barrier();
+  t_first = tick<TL>(tl_on);
+  operate_span<B, NW>(acc, w_off, w_val, 0, early, plane_bytes);
+  if (ok) ok = finish_chunks<R, R0, R>(ring, slot_byte, off, v, dst, spin_limit, status_word, repolls);
+  return ok;
+}
+
 // CELL: 0 = vanilla cell (one row per unit), 1 = LSTM (four gate rows per unit), 2 = GRU (the LSTM's layout with an
 // idle fourth row; a template value of its own so that the LSTM instantiations carry none of its code),
 // 3 = backward pass through time of the vanilla cell: the handle holds the transposed matrix, time runs from T
@@ -361,7 +452,12 @@ __device__ __forceinline__ long long tick(bool on) {
 // dh_{t+1} z_{t+1}; outputs dL/db' = (dp_r | dp_z | da) in p.h_out and v itself in p.gates_out (the weight gradient's factor),
 // 8 = the same with the weight gradient fused in as in 4 and 6,
 // 9 = the vanilla cell's forward pass with one 4-byte LDS read per sample instead of one wide read per column (batch 4
-// only): the "no wide loads" rung of the ablation (options.gather).
+// only): the "no wide loads" rung of the ablation (options.gather),
+// 10 = the vanilla cell's forward pass with the copy of h consumed in two parts (batch <= 4, no column compaction, at
+// most eight copy rounds; options.overlap): every load of the copy goes out at once, the first p.seg_rounds rounds of
+// it (the low columns) are stored first, and while the rest is still arriving every wavefront works through the leading
+// words of its lanes, which the packer filled with nonzeros of those low columns only (Section 4.2's case for doing
+// useful work during the load stage).
 template <int B, int NW, int CELL, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL == 8) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
@@ -433,6 +529,10 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
   // Each word is unpacked once into an LDS byte offset and an fp32 value (two registers per nonzero): the
   // hot loop then spends its VALU issue slots on the multiply-adds only.
   const int n_w = __builtin_amdgcn_readfirstlane(p.wave_words[wg * (block >> 6) + wave]);
+  // Two-part copy (vanilla forward pass, one plane): the first p.seg_rounds rounds of the copy bring the low columns of
+  // h, and the first k_early words of every lane of this wavefront read only those.
+  constexpr bool kTwoPart = CELL == 10;
+  const int k_early = kTwoPart ? __builtin_amdgcn_readfirstlane(p.wave_early[wg * (block >> 6) + wave]) : 0;
   uint32_t w_off[NW];
   float w_val[NW];
 #pragma unroll
@@ -605,6 +705,10 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
     const uint32_t g = p.step_base + (uint32_t)t;         // global step index: the slot number is the timestep tag
     long long ts0 = 0, ts1 = 0, ts2 = 0, ts3 = 0, ts4 = 0, ts5 = 0, ts6 = 0, ts7 = 0;
     unsigned long long repolls = 0;
+    float acc[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) acc[b] = 0.0f;
+    int k_done = 0;   // words of this step's operate stage already worked through during the copy
 
     // ---- load: h_{t-1} (published by every workgroup in step t-1) into the other LDS copy
     if (solo) {
@@ -664,7 +768,26 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
         jitter_pause(p.jitter, wave_id, g, 1);
       }
       ts4 = tick<TL>(tl_on);
-      if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
+      if constexpr (kTwoPart) {
+        if (!failed) {
+          // (timeline: slot 5 = first part stored and seen by all, slot 6 = early words + second part)
+          const int early = min(k_early, n_w);
+#define SPRNN_TWO_PARTS(R)                                                                                                    \
+  case R:                                                                                                                     \
+    failed = !copy_two_parts<B, NW, R, TL>(ring, slot_byte, tid, block, last_chunk, dst, p.spin_limit, p.ctrl + kCtrlStatus,    \
+                                           repolls, p.jitter, wave_id, g, acc, w_off, w_val, early, plane_bytes, tl_on, ts5);   \
+    break;
+          switch (chunk_rounds) {   // (the host selects this kernel only for 2..8 rounds)
+            SPRNN_TWO_PARTS(2) SPRNN_TWO_PARTS(3) SPRNN_TWO_PARTS(4) SPRNN_TWO_PARTS(5)
+            SPRNN_TWO_PARTS(6) SPRNN_TWO_PARTS(7) SPRNN_TWO_PARTS(8)
+            default: failed = true; break;
+          }
+#undef SPRNN_TWO_PARTS
+          k_done = k_early;
+        } else {
+          ts5 = ts4;
+        }
+      } else if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
         if (chunk_rounds <= 4) {
           if (!compacted) {
             failed = !copy_chunks<4, false>(ring, slot_byte, fsrc, fsrc, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
@@ -716,11 +839,10 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
     ts0 = tick<TL>(tl_on);
 
     // ---- operate
-    float acc[B];
-#pragma unroll
-    for (int b = 0; b < B; ++b) acc[b] = 0.0f;
     if constexpr (WGRAD) {
       operate<B, NW, true>(acc, w_off, w_val, n_w, plane_bytes, gacc, &side);
+    } else if constexpr (kTwoPart) {
+      operate_span<B, NW>(acc, w_off, w_val, k_done, n_w, plane_bytes);
     } else {
       // Groups of eight words for batch 4 in the one-row-per-unit layouts (eight gathers in flight, half as many
       // waits for the LDS: 2.5 % on the headline shape); four otherwise: eight would spill at batch 8, measured no

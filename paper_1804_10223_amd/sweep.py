@@ -116,6 +116,20 @@ def ablation(torch, wl, reps):
         except Exception as e:
             print("| %s | %.2f | refused: %s | | |" % (name, a, e), flush=True)
     print()
+    print("Copy of h consumed in two parts, early words during the second (cf. Section 4.2, work during the load stage)
+")
+    print("| shape | one copy, then all words us/step | two parts us/step | copy rounds in the first part, early words of the words per lane | modelled LDS cycles per gather: one copy / two parts |")
+    print("|---|---|---|---|---|")
+    for name in ("cfg3", "cfg4"):
+        w = wl.make_config(name)
+        a, ia = measure(torch, w, reps, overlap=1)
+        try:
+            b, ib = measure(torch, w, reps, overlap=2)
+            print("| %s | %.2f | %.2f | %d, %d of %d | %.2f / %.2f |" % (name, a, b, ib["overlap_rounds"], ib["overlap_words"], ib["words_per_lane_max"],
+                                                                  ia["lds_pass_factor"], ib["lds_pass_factor"]), flush=True)
+        except Exception as e:
+            print("| %s | %.2f | refused: %s | | |" % (name, a, e), flush=True)
+    print()
 
 
 def one_rung(torch, wl, reps, config, rung):

@@ -68,6 +68,7 @@ def run_case(w, e, **options):
     ("relu", 2000, 4, 6, 0.01, "poisson", {"compact": 1}),
     ("tanh", 1152, 4, 32, 0.1, "fixed", {}),
     ("tanh", 640, 4, 12, 0.2, "fixed", {"xcd": "one"}),
+    ("tanh", 1000, 2, 6, 0.4, "fixed", {"overlap": 2, "waves": 2, "lanes_per_row": 32}),   # (a forward-only option: the backward kernels read the same words in one go)
 ])
 def test_backward_matches_oracle(cell, H, B, T, dens, rownnz, opts):
     w = wl.make_workload("bwd", cell, H, B, T, dens, seed=H + T, row_nnz=rownnz, h0_std=0.5)

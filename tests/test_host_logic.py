@@ -54,8 +54,8 @@ def test_public_headers_are_plain_c(tmp_path):
 
 
 def test_struct_layouts_match_header_sizes():
-    # 8 ints + 8 reserved; 16 ints + 3 int64 + double + 8 reserved ints
-    assert ctypes.sizeof(binding.Options) == 16 * 4
+    # 17 ints; 16 ints + 3 int64 + double + 8 more ints
+    assert ctypes.sizeof(binding.Options) == 17 * 4
     assert ctypes.sizeof(binding.Info) == 16 * 4 + 3 * 8 + 8 + 8 * 4
 
 
@@ -91,6 +91,9 @@ def _unpack(words, lane_row, lane_words, info, hidden, batch):
     ("relu", 300, 4, 0.1, "fixed", {"grid": 7}),
     ("gru", 40, 4, 0.3, "fixed", {}),
     ("gru", 77, 2, 0.2, "poisson", {"lanes_per_row": 8}),
+    ("relu", 640, 4, 0.4, "fixed", {"overlap": 2, "waves": 2}),
+    ("tanh", 1000, 2, 0.4, "poisson", {"overlap": 2, "waves": 2}),
+    ("relu", 1500, 1, 0.3, "poisson", {"overlap": 2, "waves": 1, "bank_aware": 2}),
 ])
 def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
     w = wl.make_workload("p", cell, H, B, 1, dens, seed=3, row_nnz=rownnz)
@@ -153,6 +156,53 @@ def test_lane_pool_packer_preserves_every_row_and_keeps_its_structure(cell, H, B
     assert np.all(o == o[:, :, :1])
     owned = o[:, :, 0][o[:, :, 0] >= 0]
     assert sorted(owned.tolist()) == list(range(H))
+
+
+@pytest.mark.parametrize("H,B,dens,rownnz,opts", [
+    (2304, 4, 0.3, "fixed", {}),
+    (1000, 2, 0.4, "poisson", {"waves": 2}),
+    (1000, 2, 0.4, "fixed", {"waves": 2}),
+    (2000, 1, 0.5, "poisson", {"waves": 2}),
+    (1200, 4, 0.6, "fixed", {"waves": 3, "bank_aware": 2}),
+])
+def test_two_part_order_keeps_the_leading_words_inside_the_first_part(H, B, dens, rownnz, opts):
+    # options.overlap: the leading slots of every lane (info.overlap_words is the least over the wavefronts) may only
+    # address columns that the first overlap_rounds rounds of the copy bring, fillers included; nothing else changes
+    w = wl.make_workload("ov", "relu", H, B, 1, dens, seed=5, row_nnz=rownnz)
+    words, lane_row, lane_words, info = binding.pack_host(H, B, "relu", w.row_ptr, w.col_idx, w.val_bits, overlap=2, **opts)
+    plain = binding.pack_host(H, B, "relu", w.row_ptr, w.col_idx, w.val_bits, overlap=1, **opts)[3]
+    assert plain["overlap_rounds"] == 0 and plain["overlap_words"] == 0
+    for k in ("grid", "block", "lanes_per_row", "template_words", "padded_words", "lds_bytes"):
+        assert info[k] == plain[k], k                                  # the two-part order needs no extra slot
+    rounds, early = info["overlap_rounds"], info["overlap_words"]
+    copy_rounds = -(-(H * B * 4 // 16) // info["block"])
+    assert rounds == copy_rounds // 2 and 2 <= copy_rounds <= 8
+    assert early % 4 == 0 and (early > 0 or rownnz == "poisson")       # (a ragged matrix may leave some wavefront none)
+    stride = 4 * B
+    first_part_cols = rounds * info["block"] * (16 // stride)
+    cols = (words >> 16).astype(np.int64) // stride
+    if early:
+        assert cols[:, :early, :].max() < first_part_cols
+    assert cols[:, early:, :].max() >= first_part_cols                 # (the rest of h is read by the later slots)
+    got = _unpack(words, lane_row, lane_words, info, H, B)
+    for r in range(w.rows):
+        want = sorted((int(c), int(b)) for c, b in zip(w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]], w.val_bits[w.row_ptr[r]:w.row_ptr[r + 1]])
+                      if (int(b) & 0x7FFF) != 0)
+        assert got.get(r, []) == want, r
+
+
+def test_two_part_copy_is_refused_where_it_does_not_apply():
+    w = wl.make_workload("ov", "lstm", 256, 4, 1, 0.3, seed=1)
+    for cell, H, B, opts in (("lstm", 256, 4, {}),                         # gated cell
+                             ("relu", 2304, 8, {}),                        # two planes
+                             ("relu", 100, 4, {"grid": 1}),                # a single workgroup copies nothing
+                             ("relu", 2304, 4, {"sync": "barrier"}),
+                             ("relu", 4000, 4, {"compact": 1}),
+                             ("relu", 300, 4, {"waves": 8})):              # one copy round
+        w = wl.make_workload("ov", cell, H, B, 1, 0.05 if H > 3000 else 0.3, seed=1)
+        with pytest.raises(binding.SprnnError) as e:
+            binding.pack_host(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, overlap=2, **opts)
+        assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED, (cell, H, B, opts)
 
 
 def test_bank_aware_order_reduces_modelled_lds_passes():
@@ -351,11 +401,11 @@ def test_transpose_csr_matches_a_dense_transpose():
 
 
 # ----------------------------------------------------------------------------- hand-off protocol on host threads
-def _build_handoff_model(tmp_path_factory):
+def _build_handoff_model(tmp_path_factory, name="handoff_model"):
     import shutil
     import subprocess
-    src = os.path.join(ROOT, "tests", "handoff_model.cpp")
-    out = str(tmp_path_factory.mktemp("handoff") / "handoff_model")
+    src = os.path.join(ROOT, "tests", name + ".cpp")
+    out = str(tmp_path_factory.mktemp("handoff") / name)
     base = ["g++", "-O1", "-g", "-std=c++17", "-pthread", src, "-o", out]
     if shutil.which("g++") is None:
         pytest.skip("no g++")
@@ -384,6 +434,34 @@ def test_handoff_protocol_model_with_flow_control(handoff_model, G, E, T, patter
                            capture_output=True, text=True, timeout=300)
         assert r.returncode == 0 and "OK" in r.stdout, (r.returncode, r.stdout[-300:], r.stderr[-2000:])
         assert "ThreadSanitizer" not in r.stderr, r.stderr[-2000:]
+
+
+@pytest.fixture(scope="module")
+def two_part_model(tmp_path_factory):
+    return _build_handoff_model(tmp_path_factory, "two_part_model")
+
+
+@pytest.mark.parametrize("G,W,E,T", [(3, 3, 2, 150), (2, 5, 1, 150), (4, 2, 3, 100)])
+def test_two_part_copy_model_is_race_free_and_exact(two_part_model, G, W, E, T):
+    """Wavefronts of a workgroup store the second part of h into the shared copy while others still read the first part:
+    disjoint by construction, three barriers per step.  Values must match the sequential reference and ThreadSanitizer
+    (when available) must stay silent."""
+    import subprocess
+    for seed in (1, 2):
+        r = subprocess.run([two_part_model, str(G), str(W), str(E), str(T), "0", str(seed)], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 0 and "OK" in r.stdout, (r.returncode, r.stdout[-300:], r.stderr[-2000:])
+        assert "ThreadSanitizer" not in r.stderr, r.stderr[-2000:]
+
+
+def test_two_part_copy_model_catches_early_words_that_reach_into_the_second_part(two_part_model):
+    """The mistake is planted in the CPU model: an early word that reads one element of the second part races with the
+    wavefront that stores it (a data race under ThreadSanitizer; without it, stale values show as a mismatch in most runs)."""
+    import subprocess
+    seen = False
+    for seed in (1, 2, 3):
+        r = subprocess.run([two_part_model, "3", "3", "2", "150", "1", str(seed)], capture_output=True, text=True, timeout=300)
+        seen = seen or r.returncode == 1 or "data race" in r.stderr
+    assert seen
 
 
 def test_handoff_protocol_model_needs_its_flow_control(handoff_model):

@@ -94,6 +94,12 @@ SMALL = [
     ("lstm", 100, 4, 7, 0.2, "poisson", {"xcd": "one"}),
     ("lstm", 256, 8, 9, 0.125, "fixed", {"xcd": "one", "poll_delay": 1}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"xcd": "spread"}),
+    ("relu", 640, 4, 12, 0.8, "fixed", {"overlap": 2, "waves": 2, "lanes_per_row": 32}),   # copy of h consumed in two parts, early words during the second
+    ("tanh", 1000, 2, 9, 0.4, "fixed", {"overlap": 2, "waves": 2, "jitter": 3}),
+    ("tanh", 1024, 1, 7, 0.9, "poisson", {"overlap": 2, "waves": 2, "lanes_per_row": 16, "jitter": 5}),
+    ("relu", 1200, 4, 40, 0.6, "fixed", {"overlap": 2, "waves": 4, "lanes_per_row": 32, "jitter": 7}),
+    ("relu", 1000, 2, 9, 0.4, "poisson", {"overlap": 2, "waves": 2, "lanes_per_row": 32}),
+    ("relu", 1152, 4, 20, 0.3, "fixed", {"overlap": 2, "xcd": "one", "grid": 32, "lanes_per_row": 16}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"gather": "narrow"}),                       # one 4-byte LDS read per sample (ablation rung)
     ("tanh", 1152, 4, 12, 0.1, "fixed", {"gather": "narrow", "sync": "barrier", "bank_aware": 2}),   # the ablation's first rung
     ("relu", 500, 4, 10, 0.2, "fixed", {"plain_launch": 1}),
@@ -430,6 +436,27 @@ def test_full_configs_match_oracle(name):
     w = wl.make_config(name)
     info = check_workload(w, stepwise_too=(name in ("cfg1", "cfg2", "cfg5")))
     assert info["grid"] <= info["resident_capacity"]
+
+
+def test_two_part_copy_at_the_headline_shape_and_with_random_pauses():
+    # options.overlap at full size (cfg3, cfg4), where the second part really is in flight while the early words are
+    # worked through; random pauses must not change a bit, and a backward pass on the same handle ignores the option
+    for name in ("cfg3", "cfg4"):
+        w = wl.make_config(name, steps=48)
+        info = check_workload(w, stepwise_too=False, overlap=2)
+        assert info["overlap_rounds"] == 2 and info["overlap_words"] >= 4
+    w = wl.make_config("cfg3", steps=64)
+    outs = []
+    for jitter in (0, 5, 11):
+        with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, overlap=2, jitter=jitter) as rnn:
+            outs.append(rnn.forward(_dev(w.x), _dev(w.h0)).cpu().numpy())
+            assert rnn.check() == binding.SPRNN_OK
+            if jitter == 0:
+                h = torch.from_numpy(outs[0]).cuda()
+                e = torch.ones_like(h)
+                d, dh0 = rnn.backward(e, h)        # (the matrix as it is: any square matrix serves as "the transposed one")
+                assert rnn.check() == binding.SPRNN_OK and bool(torch.isfinite(d).all()) and bool(torch.isfinite(dh0).all())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
 # ------------------------------------------------------------------ GRU cell
