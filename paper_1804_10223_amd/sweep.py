@@ -2,7 +2,8 @@
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
     python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,cells,training,casestudy] [--reps 8]
-    python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged     (one rung alone, for counter passes)
+    python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged|pool|two_part
+                                                                  (one variant alone in the process, for counter passes)
 
 Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
 closed libraries on other hardware and are not reproduced):
@@ -116,8 +117,7 @@ def ablation(torch, wl, reps):
         except Exception as e:
             print("| %s | %.2f | refused: %s | | |" % (name, a, e), flush=True)
     print()
-    print("Copy of h consumed in two parts, early words during the second (cf. Section 4.2, work during the load stage)
-")
+    print("Copy of h consumed in two parts, early words during the second (cf. Section 4.2, work during the load stage)\n")
     print("| shape | one copy, then all words us/step | two parts us/step | copy rounds in the first part, early words of the words per lane | modelled LDS cycles per gather: one copy / two parts |")
     print("|---|---|---|---|---|")
     for name in ("cfg3", "cfg4"):
@@ -132,11 +132,17 @@ def ablation(torch, wl, reps):
     print()
 
 
+# further variants that --what rung can run alone: the lane-pool layout and the two-part copy
+VARIANTS = dict(RUNGS, pool=dict(layout=2), two_part=dict(overlap=2))
+
+
 def one_rung(torch, wl, reps, config, rung):
-    """One rung of the ablation alone in this process (so that a counter pass of the profiler sees only its launches)."""
-    opts = dict(RUNGS)[rung]
+    """One rung of the ablation (or one variant) alone in this process, so that a counter pass of the profiler sees only
+    its launches; the back-off is fixed, so there are no calibration launches either."""
+    opts = dict(layout=1, poll_delay=3)
+    opts.update(VARIANTS[rung])
     w = wl.make_config(config)
-    us, info = measure(torch, w, reps, layout=1, poll_delay=3, **opts)
+    us, info = measure(torch, w, reps, **opts)
     print("rung %s on %s: %.3f us/step, grid %d x %d, modelled LDS cycles per gather %.3f" % (
         rung, config, us, info["grid"], info["block"], info["lds_pass_factor"]), flush=True)
 
@@ -246,7 +252,7 @@ def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
-    ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged")
+    ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged | pool | two_part")
     ap.add_argument("--config", default="cfg2", help="with --what rung: the configuration")
     args = ap.parse_args()
     import torch

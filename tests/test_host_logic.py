@@ -38,6 +38,15 @@ def test_binding_keeps_one_hip_runtime_whatever_the_import_order():
     assert r.stdout.strip().splitlines()[-1] == "1", r.stdout + r.stderr
 
 
+def test_every_python_file_of_the_repository_compiles():
+    import py_compile
+    files = [os.path.join(ROOT, f) for f in ("bench.py", "__graft_entry__.py")]
+    for folder in ("paper_1804_10223_amd", "oracle", "tests"):
+        files += [os.path.join(ROOT, folder, f) for f in sorted(os.listdir(os.path.join(ROOT, folder))) if f.endswith(".py")]
+    for f in files:
+        py_compile.compile(f, doraise=True)
+
+
 def test_public_headers_are_plain_c(tmp_path):
     # the boundary is a C ABI: both headers must compile as C99 (and as C++) without any HIP or torch header
     import shutil
