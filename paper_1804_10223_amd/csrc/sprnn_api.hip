@@ -441,7 +441,9 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
 // for a handful of candidates, keeping the fastest.  Timing does not depend on the data.
 static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd) {
   const Mapping& m = h->map;
-  const int T = 48;
+  // (a launch of the one-XCD mode holds eight times the workgroups and costs a few microseconds more to start: the
+  // comparison of the two placements runs long enough for the per-step time to decide, as it does at real lengths)
+  const int T = try_one_xcd ? 160 : 48;
   // (the gated cells' backward passes read [T][B][4H] kept gate values from the zero buffer)
   const size_t xn = (size_t)T * m.batch * std::max(std::max(m.rows, m.cols), 4 * m.hidden), hn = (size_t)T * m.batch * m.cols;
   float *d_x = nullptr, *d_h = nullptr, *d_c = nullptr;

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,cells,training,casestudy] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,cells,training,casestudy] [--reps 8]
     python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged|pool|two_part
                                                                   (one variant alone in the process, for counter passes)
 
@@ -15,6 +15,7 @@ closed libraries on other hardware and are not reproduced):
   density / size / batch / steps
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
   constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
+  placement  small layers with their workgroups spread over all XCDs against confined to one XCD (options.xcd).
   cells      the four cells (ReLU, tanh, LSTM, GRU) on one layer shape: hidden 1024, density 20 %, T 256, batch 4 and 8.
   training   the launches of one training step (forward, backward pass through time, weight gradient) of a ReLU cell,
              the LSTM and the GRU on the same layer shape.
@@ -149,19 +150,43 @@ def one_rung(torch, wl, reps, config, rung):
 
 def axis(torch, wl, reps, title, cases):
     print("## %s\n" % title)
-    print("| hidden | batch | density | T | nonzeros | persistent us/step | per-timestep launches us/step | ratio | grid x block | lanes/row | back-off | LDS for h |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
+    print("| hidden | batch | density | T | nonzeros | persistent us/step | per-timestep launches us/step | ratio | grid x block | lanes/row | back-off | LDS for h | one XCD |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for (H, B, dens, T) in cases:
         w = wl.make_workload("sweep", "relu", H, B, T, dens, seed=0)
         try:
             us, info = measure(torch, w, reps)
         except Exception as e:  # a shape that does not fit on chip is part of the picture
-            print("| %d | %d | %.1f %% | %d | %d | does not fit: %s | | | | | | |" % (H, B, 100 * dens, T, w.nnz, e), flush=True)
+            print("| %d | %d | %.1f %% | %d | %d | does not fit: %s | | | | | | | |" % (H, B, 100 * dens, T, w.nnz, e), flush=True)
             continue
         st, _ = measure(torch, w, reps, stepwise=True)
-        print("| %d | %d | %.1f %% | %d | %d | %.2f | %.2f | %.1fx | %d x %d | %d | %d | %d KB%s |" % (
+        print("| %d | %d | %.1f %% | %d | %d | %.2f | %.2f | %.1fx | %d x %d | %d | %d | %d KB%s | %s |" % (
             H, B, 100 * dens, T, w.nnz, us, st, st / us, info["grid"], info["block"], info["lanes_per_row"], info["poll_delay"],
-            info["lds_bytes"] // 1024, " (compacted)" if info["compact"] else ""), flush=True)
+            info["lds_bytes"] // 1024, " (compacted)" if info["compact"] else "", "yes" if info["one_xcd"] else ""), flush=True)
+    print()
+
+
+def placement(torch, wl, reps):
+    """Small layers (at most 32 workgroups): workgroups spread over all XCDs against the one-XCD mode, and what the
+    calibration at create time picks by itself."""
+    print("## XCD placement of small layers: microseconds per timestep, T 256\n")
+    print("| layer | grid x block | spread over all XCDs | one XCD | chosen at create time (one XCD?) |")
+    print("|---|---|---|---|---|")
+    cases = [("cfg2 with 32 workgroups", wl.make_config("cfg2"), dict(grid=32)),
+             ("relu 1792, 1 %, batch 4", wl.make_workload("p", "relu", 1792, 4, 256, 0.01, seed=0), {}),
+             ("relu 1792, 5 %, batch 4", wl.make_workload("p", "relu", 1792, 4, 256, 0.05, seed=0), {}),
+             ("relu 1792, 10 %, batch 4, 28 workgroups of 8 lanes per row", wl.make_workload("p", "relu", 1792, 4, 256, 0.10, seed=0), dict(grid=28, lanes_per_row=8)),
+             ("relu 1024, 10 %, batch 4", wl.make_workload("p", "relu", 1024, 4, 256, 0.10, seed=0), {}),
+             ("lstm 256, 12.5 %, batch 4", wl.make_workload("p", "lstm", 256, 4, 256, 0.125, seed=0, gain=1.0), {}),
+             ("lstm 1024, 4.7 %, batch 1", wl.make_workload("p", "lstm", 1024, 1, 256, 0.047, seed=0, gain=1.0), {})]
+    for name, w, opts in cases:
+        try:
+            a, ia = measure(torch, w, reps, xcd="spread", **opts)
+            b, _ = measure(torch, w, reps, xcd="one", **opts)
+            c, ic = measure(torch, w, reps, **opts)
+            print("| %s | %d x %d | %.2f | %.2f | %.2f (%s) |" % (name, ia["grid"], ia["block"], a, b, c, "yes" if ic["one_xcd"] else "no"), flush=True)
+        except Exception as e:
+            print("| %s | | refused: %s | | |" % (name, e), flush=True)
     print()
 
 
@@ -250,7 +275,7 @@ def casestudy(torch, wl, reps):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,cells,training,casestudy")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
     ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged | pool | two_part")
     ap.add_argument("--config", default="cfg2", help="with --what rung: the configuration")
@@ -275,6 +300,8 @@ def main():
         axis(torch, wl, args.reps, "Constant number of nonzeros (cf. Section 5.3): about 1.32 M, batch 4, T 256",
              [(2304, 4, 0.25, 256), (3072, 4, 0.14, 256), (4096, 4, 0.079, 256), (5760, 4, 0.04, 256), (7168, 4, 0.026, 256),
               (11520, 4, 0.01, 256)])
+    if "placement" in what:
+        placement(torch, wl, args.reps)
     if "cells" in what:
         cells(torch, wl, args.reps)
     if "training" in what:
