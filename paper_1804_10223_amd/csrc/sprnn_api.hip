@@ -458,7 +458,7 @@ static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd) {
   if (ok) {
     // The exchange inside one XCD is shorter, so its candidates start lower; it is tried second, and dropped for good if
     // the dispatcher did not put enough workgroups on one XCD (the kernel flags that in the status word and leaves).
-    static const int spread[] = {2, 3, 4, 6, 8, 10, 12, 16};
+    static const int spread[] = {-1, 1, 2, 3, 4, 6, 8, 10, 12, 16};   // (-1: none; a wavefront's polls queue behind its own publish anyway)
     static const int local[] = {-1, 1, 2, 3, 4, 6};
     float best_ms = 0.0f;
     for (int mode = h->one_xcd ? 1 : 0; mode < ((try_one_xcd || h->one_xcd) ? 2 : 1) && ok && rc == SPRNN_OK; ++mode) {

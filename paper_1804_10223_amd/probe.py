@@ -82,11 +82,15 @@ def lds_peak(width_bytes: int, workgroups: int = 256, threads: int = 1024, devic
     return lds_gather_offsets(offs, width_bytes, workgroups=workgroups, device=device, bare=True)
 
 
-def handoff_ns_best(same_xcd: bool, launches: int = 5, rounds: int = 2000, device: int = 0):
+def handoff_ns_best(same_xcd: bool, launches: int = 5, rounds: int = 2000, device: int = 0, warm=None):
     """Smallest one-way store->observe latency over several probe launches (a latency floor is a minimum, and single
-    launches differ by tens of per cent with where the two workgroups land)."""
+    launches differ by tens of per cent with where the two workgroups land).  `warm`, if given, is called before every
+    launch: two lone workgroups do not keep the chip's clocks up by themselves, and on an idle device the same probe
+    reads up to 1.6 times longer than right after a busy kernel."""
     best, where = None, None
     for _ in range(max(1, launches)):
+        if warm is not None:
+            warm()
         ns, xcc = handoff_ns(same_xcd, rounds, device)
         if best is None or ns < best:
             best, where = ns, xcc
