@@ -102,6 +102,13 @@ typedef struct sprnn_options_s {
                         compaction, 2..8 copy rounds): 0 auto, 1 off, 2 on = the columns of h are consumed in two
                         parts; a row's nonzeros of the first part sit in its lanes' leading slots and are worked
                         through while the second part is still arriving                                    */
+  int activations;   /* precision in which h travels between workgroups and sits in LDS (vanilla cells, forward pass, batch 4,
+                        one lane group per row, no column compaction): 0 auto = 1 = binary32 (the default everywhere);
+                        2 = binary16 (Section 6 names lower-precision activations as future work): every h_t is rounded
+                        to nearest once before it is published, sums, b' and h_out stay binary32, so h_out[t] is the
+                        unrounded value while step t + 1 reads the rounded one.  Half the exchange and LDS traffic;
+                        the error against binary32 activations is a few 1e-4 of max|h|, inside the 1e-3 bound of the
+                        tests but no longer far inside                                                        */
 } sprnn_options_t;
 
 /* Filled by sprnn_get_info: how the matrix was mapped onto the chip. */
@@ -125,7 +132,8 @@ typedef struct sprnn_info_s {
   int overlap_rounds;       /* > 0: copy rounds (one 16-byte piece per lane each) that make up the first part of h when
                                the copy is overlapped with the gathers (see sprnn_options_t.overlap)     */
   int overlap_words;        /* leading slots per lane that read only that first part: least over the wavefronts */
-  int reserved[2];
+  int activations;          /* 1 = h is exchanged as binary32, 2 = as binary16 (see sprnn_options_t.activations)   */
+  int reserved[1];
 } sprnn_info_t;
 
 /*

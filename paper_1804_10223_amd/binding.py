@@ -27,6 +27,7 @@ GATES = {"lstm": 4, "gru": 3}
 SYNC = {"auto": 0, "tagged": 1, "barrier": 2}
 LAYOUT = {"auto": 0, "row_groups": 1, "lane_pool": 2}
 GATHER = {"auto": 0, "wide": 1, "narrow": 2}
+ACTIVATIONS = {"auto": 0, "binary32": 1, "binary16": 2}
 XCD = {"auto": 0, "spread": 1, "one": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_noalloc", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
@@ -42,7 +43,7 @@ class Options(ctypes.Structure):
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
                 ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
-                ("gather", ctypes.c_int), ("xcd", ctypes.c_int), ("overlap", ctypes.c_int)]
+                ("gather", ctypes.c_int), ("xcd", ctypes.c_int), ("overlap", ctypes.c_int), ("activations", ctypes.c_int)]
 
 
 class Info(ctypes.Structure):
@@ -55,7 +56,7 @@ class Info(ctypes.Structure):
                 ("nnz", ctypes.c_int64), ("padded_words", ctypes.c_int64), ("ring_bytes", ctypes.c_int64),
                 ("lds_pass_factor", ctypes.c_double), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
                 ("gather_waves", ctypes.c_int), ("one_xcd", ctypes.c_int), ("overlap_rounds", ctypes.c_int),
-                ("overlap_words", ctypes.c_int), ("reserved", ctypes.c_int * 2)]
+                ("overlap_words", ctypes.c_int), ("activations", ctypes.c_int), ("reserved", ctypes.c_int * 1)]
 
     def as_dict(self) -> dict:
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
@@ -184,6 +185,8 @@ def make_options(**kw) -> Options:
             v = GATHER[v]
         if k == "xcd" and isinstance(v, str):
             v = XCD[v]
+        if k == "activations" and isinstance(v, str):
+            v = ACTIVATIONS[v]
         if not hasattr(o, k):
             raise TypeError("unknown option %r" % k)
         setattr(o, k, int(v))

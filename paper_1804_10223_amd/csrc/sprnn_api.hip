@@ -97,6 +97,7 @@ void fill_info(const Mapping& m, int capacity, double pass_factor, sprnn_info_t*
   info->gather_waves = m.row_waves;
   info->overlap_rounds = m.seg_rounds;
   info->overlap_words = m.seg_words;
+  info->activations = m.half ? 2 : 1;
 }
 // (fill_info has no handle: the one-XCD flag is added by sprnn_get_info)
 
@@ -251,7 +252,8 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   h->kernel = pool ? pool_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0)
                    : (m.narrow ? persistent_narrow_kernel_for(m.batch, m.template_words)
                                : (m.seg_rounds ? persistent_overlap_kernel_for(m.batch, m.template_words, m.timeline != 0)
-                                               : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0)));
+                                  : (m.half ? persistent_half_kernel_for(m.batch, m.template_words)
+                                            : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0))));
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.
@@ -263,7 +265,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   // (the per-kernel limit on dynamic LDS is state shared by every handle that uses the same instantiation: it is
   // always raised to the device's maximum, never set to one handle's own request)
   if (!SPRNN_HIP(hipFuncSetAttribute(h->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
-  if (m.cell <= SPRNN_ACT_IDENTITY && !m.timeline && !m.narrow) {
+  if (m.cell <= SPRNN_ACT_IDENTITY && !m.timeline && !m.narrow && !m.half) {
     // the backward pass of a vanilla cell runs on a handle that holds the transposed matrix: same shape, same LDS
     h->kernel_bwd = pool ? pool_kernel_for(m.batch, m.template_words, kCellBackward) : persistent_kernel_for(m.batch, m.template_words, kCellBackward, false);
     if (h->kernel_bwd && !SPRNN_HIP(hipFuncSetAttribute(h->kernel_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cu))) { release(h); return SPRNN_ERR_HIP; }
@@ -286,10 +288,11 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   const bool try_one_xcd = xcd_opt == 0 && xcd_eligible && calibrate;
 
   const size_t ring_words = (size_t)kRingSlots * m.h_bytes / 4;
-  std::vector<uint32_t> ring(ring_words, kSentinel);
+  // (binary16 activations: two elements per 32-bit word, each carrying the mark)
+  std::vector<uint32_t> ring(ring_words, m.half ? (kSentinel >> 16 | kSentinel) : kSentinel);
   {
     // bytes of a slot beyond the last element of h are never written by a producer: mark them as present
-    const size_t used = (size_t)m.cols * m.batch;     // 32-bit elements (both planes for batch 8)
+    const size_t used = (size_t)m.cols * m.batch / (m.half ? 2 : 1);     // 32-bit words (both planes for batch 8)
     for (int s = 0; s < kRingSlots; ++s)
       for (size_t i = used; i < (size_t)m.h_bytes / 4; ++i) ring[(size_t)s * m.h_bytes / 4 + i] = 0u;
   }
@@ -322,7 +325,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
       if (ok) h->kernel_bwd_grad = k;
     }
   }
-  if (ok && (m.cell <= SPRNN_ACT_IDENTITY || m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU) && !m.compact) {
+  if (ok && (m.cell <= SPRNN_ACT_IDENTITY || m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU) && !m.compact && !m.half) {
     // the weight gradient re-uses the forward mapping: one accumulator per packed word, left through this map
     // (built for the word counts of the one-group-per-row layout; a lane-pool mapping with another count has none:
     // sprnn_weight_gradient is then unsupported on this handle, the fused backward pass is the way)
@@ -514,6 +517,7 @@ int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, floa
 int sprnn_forward_noalloc(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream) {
   if (!h || T < 0) return SPRNN_ERR_INVALID;
   if (h->map.cell > SPRNN_ACT_IDENTITY) return SPRNN_ERR_UNSUPPORTED;
+  if (h->map.half) return SPRNN_ERR_UNSUPPORTED;   // (the per-launch reset marks binary32 elements)
   if (T > 0 && (!x || !h_out)) return SPRNN_ERR_INVALID;
   // the ring of this layer must fit behind the control words of the static array
   if ((size_t)kRingSlots * (size_t)h->map.h_bytes + kScratchCtrlBytes > kScratchBytes) {

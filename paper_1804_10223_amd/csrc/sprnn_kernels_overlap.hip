@@ -1,5 +1,6 @@
 // Device code of libsprnn: the persistent kernel's instantiations that consume the copy of h in two parts
-// (options.overlap): forward pass of the vanilla cells at batch 1, 2 and 4; with the phase timeline at batch 4.
+// (options.overlap): forward pass of the vanilla cells at batch 1, 2 and 4; with the phase timeline at batch 4; and
+// the instantiations with binary16 activations (options.activations): vanilla forward pass, batch 4.
 #include "sprnn_persistent.h"
 
 namespace sprnn {
@@ -12,6 +13,10 @@ const void* persistent_overlap_kernel_for(int batch, int template_words, bool ti
     case 4: return pick_nw<4, 10, false>(template_words);
     default: return nullptr;
   }
+}
+
+const void* persistent_half_kernel_for(int batch, int template_words) {
+  return batch == 4 ? pick_nw<4, 11, false>(template_words) : nullptr;
 }
 
 }  // namespace sprnn

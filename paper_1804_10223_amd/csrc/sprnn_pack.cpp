@@ -134,9 +134,16 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
 
   m->hidden = hidden; m->rows = hidden * visible_gates(cell); m->batch = batch; m->cell = cell;
   m->cols = exchange_cols(cell, hidden);
-  m->col_stride = 4 * std::min(batch, 4);
+  const int activations = opt ? opt->activations : 0;
+  if (activations < 0 || activations > 2) return SPRNN_ERR_INVALID;
+  m->half = activations == 2 ? 1 : 0;
+  if (m->half && (batch != 4 || cell > SPRNN_ACT_IDENTITY)) return SPRNN_ERR_UNSUPPORTED;
+  // binary16 activations: a column of h is batch x 2 bytes, which is the geometry of binary32 activations at half the batch
+  const int lb = m->half ? batch / 2 : batch;
+  m->layout_batch = lb;
+  m->col_stride = 4 * std::min(lb, 4);
   const int64_t plane = (int64_t)m->cols * m->col_stride;         // batch 8 keeps two planes of 4 samples
-  const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
+  const int64_t hb = ((plane * (lb == 8 ? 2 : 1)) + 15) / 16 * 16;
   // Wavefronts beyond the ones that own rows only help with copying h into LDS (more loads in flight).  Where the
   // row owners alone would need more than four rounds of 16-byte loads for it, the workgroup is filled up to eight
   // wavefronts (measured on the LSTM shapes: 2.51 -> 2.37 us per step forward, 4.4 -> 3.5 backward; more than eight
@@ -177,6 +184,7 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   m->narrow = (opt && opt->gather == 2) ? 1 : 0;
   if (opt && (opt->gather < 0 || opt->gather > 2)) return SPRNN_ERR_INVALID;
   if (m->narrow && (batch != 4 || cell > SPRNN_ACT_IDENTITY || m->timeline)) return SPRNN_ERR_UNSUPPORTED;
+  if (m->half && (m->narrow || m->timeline)) return SPRNN_ERR_UNSUPPORTED;
   return SPRNN_OK;
 }
 
@@ -347,7 +355,7 @@ static void order_wave_phased(std::vector<RowGroup>& rg, int L, int trip, int k1
 static void place_fillers(Packed& P, const std::vector<int>& wg_cols, const std::vector<char>& is_real_zero) {
   const Mapping& m = P.map;
   const int NW = m.template_words;
-  const PassModel pm = make_pass_model(m.batch);
+  const PassModel pm = make_pass_model(m.layout_batch ? m.layout_batch : m.batch);
   const int classes = pm.classes;
   for (int wg = 0; wg < m.grid; ++wg)
     for (int wave = 0; wave < m.waves; ++wave) {
@@ -468,6 +476,7 @@ static int pack_pool(int hidden, int batch, int cell, const int32_t* row_ptr, co
 
   Mapping m;
   m.hidden = hidden; m.rows = rows; m.batch = batch; m.cell = cell; m.cols = cols;
+  m.layout_batch = batch;
   m.col_stride = 4 * std::min(batch, 4);
   const int64_t plane = (int64_t)cols * m.col_stride;
   const int64_t hb = ((plane * (batch == 8 ? 2 : 1)) + 15) / 16 * 16;
@@ -575,6 +584,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   const int layout = opt ? opt->layout : 0;
   if (layout < 0 || layout > 2) return SPRNN_ERR_INVALID;
   if (layout == 2 && cell > SPRNN_ACT_IDENTITY) return SPRNN_ERR_UNSUPPORTED;
+  if (layout == 2 && opt && opt->activations == 2) return SPRNN_ERR_UNSUPPORTED;
   if (cell <= SPRNN_ACT_IDENTITY && layout == 2) {
     rc = pack_pool(hidden, batch, cell, row_ptr, col_idx, val_bits, opt, num_cus, out);
     if (rc != SPRNN_ERR_CAPACITY || layout == 2) return rc;   // (auto: a matrix that does not suit the pool takes the other layout)
@@ -638,8 +648,9 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   // sparse layers, and proposes to give a block less than whole rows' worth of it): a workgroup only copies the 16-byte chunks of h that its rows read, into
   // consecutive LDS positions.  Used when the whole of h does not fit in LDS, or when every workgroup needs
   // less than half of it; otherwise LDS mirrors the ring slot.
-  const int cpc = batch >= 4 ? 1 : 4 / batch;                 // columns per 16-byte chunk
-  const int planes = batch == 8 ? 2 : 1;
+  const int lb = m.layout_batch;                             // (batch / 2 with binary16 activations: twice the columns per chunk)
+  const int cpc = lb >= 4 ? 1 : 4 / lb;                      // columns per 16-byte chunk
+  const int planes = lb == 8 ? 2 : 1;
   const int chunks_per_plane = ceil_div(cols, cpc);
   // Flow control: the exchange ring is only safe because a workgroup cannot start step t before it has seen
   // something of step t-1 from EVERY workgroup (that is what keeps all of them within one step of each other and
@@ -676,6 +687,10 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   // (scattered 16-byte reads cost more per byte than the contiguous copy: measured break-even near one half)
   bool compact = m.compact == 1 || (m.compact == 0 && (!identity_fits || need_max * 2 < (size_t)chunks_per_plane));
   if (m.grid == 1) compact = false;          // a single workgroup produces all of h itself
+  if (m.half && compact) {                   // (the compacted copy is built for binary32 elements)
+    if (m.compact == 1 || !identity_fits) return SPRNN_ERR_UNSUPPORTED;
+    compact = false;
+  }
   if (!compact && !identity_fits) return SPRNN_ERR_CAPACITY;
   m.compact = compact ? 1 : 0;
   int64_t lds_plane;                          // bytes of one plane of the LDS copy (bounds the packed offsets)
@@ -702,7 +717,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   if (overlap < 0 || overlap > 2) return SPRNN_ERR_INVALID;
   const int copy_rounds = ceil_div(m.h_bytes / 16, m.block);
   const bool can_overlap = !compact && m.grid > 1 && planes == 1 && cell <= SPRNN_ACT_IDENTITY && m.sync == SPRNN_SYNC_TAGGED &&
-                           copy_rounds >= 2 && copy_rounds <= 8 && !m.narrow;
+                           copy_rounds >= 2 && copy_rounds <= 8 && !m.narrow && !m.half;
   if (overlap == 2 && !can_overlap) return SPRNN_ERR_UNSUPPORTED;
   m.seg_rounds = (overlap == 2 && can_overlap) ? copy_rounds / 2 : 0;
   const int seg_col = m.seg_rounds * m.block * cpc;
@@ -734,7 +749,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   P.wave_words.assign(total_waves, 0);
   if (m.seg_rounds) P.wave_early.assign(total_waves, 0);
 
-  const PassModel pm = make_pass_model(batch);
+  const PassModel pm = make_pass_model(lb);
   auto pad_word = [&](int lane_in_wave, int k, int ncols) -> uint32_t {
     // zero-valued filler (place_fillers gives it a bank class that is free in its pass afterwards)
     int col = (lane_in_wave + k * L) % pm.classes;
@@ -817,7 +832,7 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
 // address are served together.
 double lds_pass_factor(const Packed& P) {
   const Mapping& m = P.map;
-  const PassModel pm = make_pass_model(m.batch);
+  const PassModel pm = make_pass_model(m.layout_batch ? m.layout_batch : m.batch);
   const int width = m.col_stride;
   int64_t passes = 0, ideal = 0;
   std::vector<std::vector<uint32_t>> seen(pm.classes);

@@ -31,6 +31,8 @@ struct Mapping {
   int sync = SPRNN_SYNC_TAGGED, bank_aware = 1, balance = 2, poll_delay = 0, spin_limit = 0, timeline = 0;
   int plain_launch = 0;      // 1: ordinary kernel launch instead of a cooperative one
   int jitter = 0;            // test aid: seed of pseudo-random pauses in the hand-off (0 = none)
+  int half = 0;              // 1: h is exchanged and kept in LDS as binary16 (options.activations = 2)
+  int layout_batch = 0;      // samples' worth of 4-byte elements per column of the LDS copy: batch, or batch / 2 with binary16 activations
   int narrow = 0;            // 1: one 4-byte LDS read per sample instead of one wide read per column (ablation)
   int template_words = 0;    // NW of the kernel instantiation
   int words_max = 0;         // largest per-lane word count actually used

@@ -264,6 +264,55 @@ __device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, 
   }
 }
 
+// binary16 activations (batch 4): a column of h is four binary16 values, one 8-byte read; products and sums stay
+// binary32 (the conversion is exact, and the compiler folds it into a mixed-precision multiply-add).
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+template <int N>
+__device__ __forceinline__ void mac_words_half(float (&acc)[4], const uint32_t* off, const float* wv) {
+  halfx4 c[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) c[j] = *SPRNN_LDS_PTR(halfx4, off[j]);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[b] = fmaf(wv[j], (float)c[j][b], acc[b]);
+  }
+}
+template <int NW>
+__device__ __forceinline__ void operate_half(float (&acc)[4], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w) {
+#pragma unroll
+  for (int k = 0; k < NW; k += 8) {
+    if (k + 8 <= n_w) {
+      mac_words_half<8>(acc, &w_off[k], &w_val[k]);
+    } else if (k < n_w) {
+      const int rem = n_w - k;
+      if (rem >= 4) {
+        mac_words_half<4>(acc, &w_off[k], &w_val[k]);
+        if (rem == 7) mac_words_half<3>(acc, &w_off[k + 4], &w_val[k + 4]);
+        else if (rem == 6) mac_words_half<2>(acc, &w_off[k + 4], &w_val[k + 4]);
+        else if (rem == 5) mac_words_half<1>(acc, &w_off[k + 4], &w_val[k + 4]);
+      } else if (rem == 3) mac_words_half<3>(acc, &w_off[k], &w_val[k]);
+      else if (rem == 2) mac_words_half<2>(acc, &w_off[k], &w_val[k]);
+      else mac_words_half<1>(acc, &w_off[k], &w_val[k]);
+    }
+  }
+}
+// A 32-bit word of the exchange ring holds two binary16 elements; "not written" is the mark in both halves.
+constexpr uint32_t kSentinelHalfPair = 0x80008000u;
+// smallest of the chunk's words after an exclusive-or with the mark pair: zero exactly when one of them is unwritten
+__device__ __forceinline__ uint32_t unwritten_key_half(i32x4 v) {
+  const uint32_t a = (uint32_t)v.x ^ kSentinelHalfPair, b = (uint32_t)v.y ^ kSentinelHalfPair;
+  const uint32_t c = (uint32_t)v.z ^ kSentinelHalfPair, d = (uint32_t)v.w ^ kSentinelHalfPair;
+  return min(min(a, b), min(c, d));
+}
+// binary32 -> binary16 bits, round to nearest even; -0.0 (the mark) becomes +0.0
+__device__ __forceinline__ uint32_t half_bits_for_exchange(float v) {
+  const _Float16 h = (_Float16)v;
+  const uint32_t bits = (uint32_t)__builtin_bit_cast(unsigned short, h);
+  return bits == 0x8000u ? 0u : bits;
+}
+
 constexpr int kOutOfRange = 0x7ffffff0;   // a byte offset beyond every buffer this kernel addresses
 
 // The n_w (wavefront-uniform) packed words of a lane (w_off: absolute LDS addresses of their columns): gathers in
@@ -362,7 +411,7 @@ __device__ __forceinline__ bool finish_chunks(__amdgpu_buffer_rsrc_t ring, int s
 // costs no memory traffic and returns zeros, and nothing is written.  A chunk that still holds the "not written" mark makes
 // the whole wavefront poll again (bounded by spin_limit; a tripped watchdog anywhere ends the wait).  Returns false
 // when the wait was given up.
-template <int D, bool MAYSKIP>
+template <int D, bool MAYSKIP, bool HALF = false>
 __device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slot_byte, const int (&off)[D], const int (&to)[D],
                                             unsigned char* dst, int spin_limit, const uint32_t* status_word, unsigned long long& repolls) {
   i32x4 v[D];
@@ -371,10 +420,19 @@ __device__ __forceinline__ bool copy_chunks(__amdgpu_buffer_rsrc_t ring, int slo
   for (;;) {
 #pragma unroll
     for (int c = 0; c < D; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(ring, off[c], slot_byte, kAuxCoherent);
-    int low = min_word(v[0]);
+    bool pending;
+    if constexpr (HALF) {
+      uint32_t key = unwritten_key_half(v[0]);
 #pragma unroll
-    for (int c = 1; c < D; ++c) low = min(low, min_word(v[c]));
-    if (__builtin_amdgcn_ballot_w64(low == (int)kSentinelBits) == 0) break;
+      for (int c = 1; c < D; ++c) key = min(key, unwritten_key_half(v[c]));
+      pending = key == 0u;
+    } else {
+      int low = min_word(v[0]);
+#pragma unroll
+      for (int c = 1; c < D; ++c) low = min(low, min_word(v[c]));
+      pending = low == (int)kSentinelBits;
+    }
+    if (__builtin_amdgcn_ballot_w64(pending) == 0) break;
     // some producer has not published yet
     ++spins;
     ++repolls;
@@ -457,7 +515,10 @@ __device__ __forceinline__ bool copy_two_parts(__amdgpu_buffer_rsrc_t ring, int 
 // most eight copy rounds; options.overlap): every load of the copy goes out at once, the first p.seg_rounds rounds of
 // it (the low columns) are stored first, and while the rest is still arriving every wavefront works through the leading
 // words of its lanes, which the packer filled with nonzeros of those low columns only (Section 4.2's case for doing
-// useful work during the load stage).
+// useful work during the load stage),
+// 11 = the vanilla cell's forward pass with h exchanged and kept in LDS as binary16 (batch 4; options.activations;
+// Section 6 names lower-precision activations as future work): one 8-byte gather per nonzero, products and sums in
+// binary32, every h_t rounded to nearest once before it is published (h_out keeps the unrounded value).
 template <int B, int NW, int CELL, bool TL>
 __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL == 8) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
@@ -532,6 +593,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
   // Two-part copy (vanilla forward pass, one plane): the first p.seg_rounds rounds of the copy bring the low columns of
   // h, and the first k_early words of every lane of this wavefront read only those.
   constexpr bool kTwoPart = CELL == 10;
+  constexpr bool kHalf = CELL == 11;   // h travels and sits in LDS as binary16: [H][B] halves, 8 bytes per column at batch 4
+  static_assert(!kHalf || B == 4, "binary16 activations are built for batch 4");
   const int k_early = kTwoPart ? __builtin_amdgcn_readfirstlane(p.wave_early[wg * (block >> 6) + wave]) : 0;
   uint32_t w_off[NW];
   float w_val[NW];
@@ -572,7 +635,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
     ring_voff = cell_unit >= 0 ? lds_offset<B>(cell_unit, b, H) : kOutOfRange;
   } else {
     out_voff = owner ? (sample * H + row) * 4 : kOutOfRange;
-    ring_voff = owner ? lds_offset<B>(row, sample, H) : kOutOfRange;
+    // (binary16 activations: the owner of sample 0 stores the row's four elements as one 8-byte piece)
+    ring_voff = kHalf ? ((owner && sample == 0) ? row * (B * 2) : kOutOfRange) : (owner ? lds_offset<B>(row, sample, H) : kOutOfRange);
   }
   const __amdgpu_buffer_rsrc_t ring = __builtin_amdgcn_make_buffer_rsrc(p.ring, 0, kRingSlotsDev * p.h_bytes, kBufWord3);
   const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.x), 0, p.T * B * Rx * 4, kBufWord3);
@@ -615,7 +679,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
     for (int e = tid; e < H * B; e += block) {
       const int j = e / B, b = e % B;
       const float v = p.h0 ? p.h0[(size_t)b * H + j] : 0.0f;
-      *reinterpret_cast<float*>(lds + lds_offset<B>(j, b, H)) = v;
+      if constexpr (kHalf) *reinterpret_cast<_Float16*>(lds + (j * B + b) * 2) = (_Float16)v;
+      else *reinterpret_cast<float*>(lds + lds_offset<B>(j, b, H)) = v;
     }
   } else {
     // the same chunks the step loop will copy, taken from the caller's [B][H] array
@@ -790,7 +855,14 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
       } else if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
         if (chunk_rounds <= 4) {
           if (!compacted) {
-            failed = !copy_chunks<4, false>(ring, slot_byte, fsrc, fsrc, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            if (kHalf && chunk_rounds <= 2) {
+              // half the bytes, half the rounds: a copy of four would end with two rounds in which every lane fetches the
+              // clamped last chunk and writes it to one and the same LDS address (measured: 0.1 us per such round here)
+              const int two[2] = {fsrc[0], fsrc[1]};
+              failed = !copy_chunks<2, false, kHalf>(ring, slot_byte, two, two, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            } else {
+              failed = !copy_chunks<4, false, kHalf>(ring, slot_byte, fsrc, fsrc, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            }
           } else {
             int to[4];
 #pragma unroll
@@ -803,7 +875,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
             int off[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) off[c] = copy_src(r0 + c);
-            failed = !copy_chunks<8, false>(ring, slot_byte, off, off, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            failed = !copy_chunks<8, false, kHalf>(ring, slot_byte, off, off, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
           }
         } else {
           // the same with a copy list: the sources of the next eight rounds are fetched while this round's data is
@@ -843,6 +915,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
       operate<B, NW, true>(acc, w_off, w_val, n_w, plane_bytes, gacc, &side);
     } else if constexpr (kTwoPart) {
       operate_span<B, NW>(acc, w_off, w_val, k_done, n_w, plane_bytes);
+    } else if constexpr (kHalf) {
+      operate_half<NW>(acc, w_off, w_val, n_w);
     } else {
       // Groups of eight words for batch 4 in the one-row-per-unit layouts (eight gathers in flight, half as many
       // waits for the LDS: 2.5 % on the headline shape); four otherwise: eight would spill at batch 8, measured no
@@ -964,7 +1038,32 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
     ts2 = tick<TL>(tl_on);
     if constexpr (!LBWD) {   // (the LSTM's backward pass has published its four elements above)
     jitter_pause(p.jitter, wave_id, g, 3);
-    if (solo) {
+    if constexpr (kHalf) {
+      // the four owner lanes of a row are one aligned quad, and lane q of it holds sample sample_of_lane(q) = 0, 2, 1, 3:
+      // the owner of sample 0 collects the four rounded values in sample order
+      const int mine = (int)half_bits_for_exchange(hval);
+      const int s2 = __builtin_amdgcn_update_dpp(0, mine, 0x55, 0xf, 0xf, false);   // quad_perm: lane 1 of the quad (sample 2)
+      const int s1 = __builtin_amdgcn_update_dpp(0, mine, 0xAA, 0xf, 0xf, false);   // lane 2 (sample 1)
+      const int s3 = __builtin_amdgcn_update_dpp(0, mine, 0xFF, 0xf, 0xf, false);   // lane 3 (sample 3)
+      i32x2 pair;
+      pair.x = mine | (s1 << 16);
+      pair.y = s2 | (s3 << 16);
+      if (solo) {
+        if (ring_voff != kOutOfRange) *reinterpret_cast<i32x2*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = pair;
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        i32x2 mark;
+        mark.x = (int)kSentinelHalfPair;
+        mark.y = (int)kSentinelHalfPair;
+        if (p.one_xcd) {
+          __builtin_amdgcn_raw_buffer_store_b64(pair, ring, ring_voff, slot_byte, 0);
+          if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b64(mark, ring, ring_voff, rearm_byte, 0);
+        } else {
+          __builtin_amdgcn_raw_buffer_store_b64(pair, ring, ring_voff, slot_byte, kAuxCoherent);
+          if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b64(mark, ring, ring_voff, rearm_byte, kAuxCoherent);
+        }
+      }
+    } else if (solo) {
       if (ring_voff != kOutOfRange) *reinterpret_cast<float*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = hval;
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,cells,training,casestudy] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,activations,cells,training,casestudy] [--reps 8]
     python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged|pool|two_part
                                                                   (one variant alone in the process, for counter passes)
 
@@ -16,6 +16,7 @@ closed libraries on other hardware and are not reproduced):
              the four axes of Section 5.2 around its base point (hidden 1792, density 10 %, batch 4, T 256).
   constnnz   Section 5.3's last experiment: about 1.32 M nonzeros spread over layers of 2304 to 11520 units.
   placement  small layers with their workgroups spread over all XCDs against confined to one XCD (options.xcd).
+  activations  binary32 against binary16 activations on layers of 1152 to 11520 units (options.activations).
   cells      the four cells (ReLU, tanh, LSTM, GRU) on one layer shape: hidden 1024, density 20 %, T 256, batch 4 and 8.
   training   the launches of one training step (forward, backward pass through time, weight gradient) of a ReLU cell,
              the LSTM and the GRU on the same layer shape.
@@ -48,8 +49,9 @@ def _time_us_per_step(torch, run, T, reps):
     return float(np.median(ts))
 
 
-def measure(torch, w, reps, stepwise=False, **options):
-    """Microseconds per timestep of one workload (whole launch / T) and the mapping the library chose."""
+def measure(torch, w, reps, stepwise=False, want_output=False, **options):
+    """Microseconds per timestep of one workload (whole launch / T) and the mapping the library chose (and, on request,
+    the output h of the last run as a numpy array)."""
     from . import binding
     dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
     x, h0, c0 = dev(w.x), dev(w.h0), dev(w.c0)
@@ -70,7 +72,8 @@ def measure(torch, w, reps, stepwise=False, **options):
         us = _time_us_per_step(torch, run, T, max(3, reps // 2) if stepwise else reps)
         if rnn.check() != 0:
             raise RuntimeError("spin watchdog tripped")
-    return us, info
+        out = h_out.cpu().numpy() if want_output else None
+    return (us, info, out) if want_output else (us, info)
 
 
 # The rungs of Table 1, each on top of the one before: no wide loads and a grid barrier ("naive"), wide loads
@@ -190,6 +193,23 @@ def placement(torch, wl, reps):
     print()
 
 
+def activations(torch, wl, reps):
+    """binary32 against binary16 activations (options.activations): half the exchange and LDS traffic, and the worst
+    difference between the two outputs as a fraction of max|h| per timestep."""
+    import numpy as np
+    print("## Activations exchanged as binary32 or binary16 (cf. Section 6, future work): batch 4, T 256\n")
+    print("| hidden | density | binary32 us/step | binary16 us/step | LDS for h | worst step difference / max abs h |")
+    print("|---|---|---|---|---|---|")
+    for (H, dens) in [(1152, 0.10), (2304, 0.30), (3072, 0.10), (4096, 0.10), (5120, 0.10), (7168, 0.026), (11520, 0.01)]:
+        w = wl.make_workload("sweep", "relu", H, 4, 256, dens, seed=0)
+        a, ia, oa = measure(torch, w, reps, want_output=True)
+        b, ib, ob = measure(torch, w, reps, want_output=True, activations=2)
+        diff = max(float(np.abs(oa[t] - ob[t]).max() / np.abs(oa[t]).max()) for t in range(w.steps))
+        print("| %d | %.1f %% | %.2f | %.2f | %d KB%s / %d KB | %.1e |" % (H, 100 * dens, a, b, ia["lds_bytes"] // 1024,
+              " (compacted)" if ia["compact"] else "", ib["lds_bytes"] // 1024, diff), flush=True)
+    print()
+
+
 def cells(torch, wl, reps):
     print("## Cells: hidden 1024, density 20 %, T 256\n")
     print("| cell | gate rows | batch | nonzeros | persistent us/step | grid x block | lanes/row | back-off |")
@@ -275,7 +295,7 @@ def casestudy(torch, wl, reps):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,cells,training,casestudy")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,activations,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
     ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged | pool | two_part")
     ap.add_argument("--config", default="cfg2", help="with --what rung: the configuration")
@@ -302,6 +322,8 @@ def main():
               (11520, 4, 0.01, 256)])
     if "placement" in what:
         placement(torch, wl, args.reps)
+    if "activations" in what:
+        activations(torch, wl, args.reps)
     if "cells" in what:
         cells(torch, wl, args.reps)
     if "training" in what:

@@ -63,14 +63,14 @@ def test_public_headers_are_plain_c(tmp_path):
 
 
 def test_struct_layouts_match_header_sizes():
-    # 17 ints; 16 ints + 3 int64 + double + 8 more ints
-    assert ctypes.sizeof(binding.Options) == 17 * 4
+    # 18 ints; 16 ints + 3 int64 + double + 8 more ints
+    assert ctypes.sizeof(binding.Options) == 18 * 4
     assert ctypes.sizeof(binding.Info) == 16 * 4 + 3 * 8 + 8 + 8 * 4
 
 
 def _unpack(words, lane_row, lane_words, info, hidden, batch):
     """Rows recovered from the packed image: {row: sorted [(col, bits)]} ignoring zero-valued filler."""
-    stride = 4 * min(batch, 4)
+    stride = 4 * min(batch, 4) // (2 if info.get("activations") == 2 else 1)
     out = {}
     g, nw, blk = words.shape
     for wg in range(g):
@@ -103,6 +103,8 @@ def _unpack(words, lane_row, lane_words, info, hidden, batch):
     ("relu", 640, 4, 0.4, "fixed", {"overlap": 2, "waves": 2}),
     ("tanh", 1000, 2, 0.4, "poisson", {"overlap": 2, "waves": 2}),
     ("relu", 1500, 1, 0.3, "poisson", {"overlap": 2, "waves": 1, "bank_aware": 2}),
+    ("relu", 300, 4, 0.3, "poisson", {"activations": 2}),
+    ("tanh", 2305, 4, 0.1, "fixed", {"activations": 2, "bank_aware": 2}),
 ])
 def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
     w = wl.make_workload("p", cell, H, B, 1, dens, seed=3, row_nnz=rownnz)
@@ -198,6 +200,31 @@ def test_two_part_order_keeps_the_leading_words_inside_the_first_part(H, B, dens
         want = sorted((int(c), int(b)) for c, b in zip(w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]], w.val_bits[w.row_ptr[r]:w.row_ptr[r + 1]])
                       if (int(b) & 0x7FFF) != 0)
         assert got.get(r, []) == want, r
+
+
+def test_binary16_activations_halve_the_exchange_and_are_refused_where_not_built():
+    w = wl.make_config("cfg3", steps=1)
+    full = binding.pack_host(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits)[3]
+    half = binding.pack_host(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, activations="binary16")[3]
+    assert full["activations"] == 1 and half["activations"] == 2
+    assert half["lds_bytes"] * 2 == full["lds_bytes"] and half["ring_bytes"] * 2 == full["ring_bytes"]
+    for k in ("grid", "block", "lanes_per_row", "template_words", "padded_words"):
+        assert half[k] == full[k], k
+    # the largest layer of Section 5.3 at batch 4: 184 KB of binary32 activations need column compaction, 92 KB of binary16 fit
+    big = wl.make_workload("big", "relu", 11520, 4, 1, 0.01, seed=0)
+    assert binding.pack_host(11520, 4, "relu", big.row_ptr, big.col_idx, big.val_bits)[3]["compact"] == 1
+    info = binding.pack_host(11520, 4, "relu", big.row_ptr, big.col_idx, big.val_bits, activations=2)[3]
+    assert info["compact"] == 0 and info["lds_bytes"] == 11520 * 8
+    for cell, H, B, opts in (("relu", 256, 2, {}), ("relu", 256, 8, {}), ("lstm", 128, 4, {}), ("gru", 128, 4, {}),
+                             ("relu", 2304, 4, {"layout": "lane_pool"}), ("relu", 4000, 4, {"compact": 1}), ("relu", 500, 4, {"gather": "narrow"}),
+                             ("relu", 2304, 4, {"overlap": 2}), ("relu", 500, 4, {"timeline": 1})):
+        v = wl.make_workload("h", cell, H, B, 1, 0.05 if H > 3000 else 0.2, seed=1)
+        with pytest.raises(binding.SprnnError) as e:
+            binding.pack_host(H, B, cell, v.row_ptr, v.col_idx, v.val_bits, activations=2, **opts)
+        assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED, (cell, H, B, opts)
+    with pytest.raises(binding.SprnnError) as e:
+        binding.pack_host(256, 4, "relu", w.row_ptr[:257] * 0, w.col_idx[:0], w.val_bits[:0], activations=3)
+    assert e.value.code == binding.SPRNN_ERR_INVALID
 
 
 def test_two_part_copy_is_refused_where_it_does_not_apply():
