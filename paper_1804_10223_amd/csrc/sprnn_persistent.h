@@ -267,6 +267,8 @@ __device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, 
 // binary16 activations (batch 4): a column of h is four binary16 values, one 8-byte read; products and sums stay
 // binary32 (the conversion is exact, and the compiler folds it into a mixed-precision multiply-add).
 typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wint-to-pointer-cast"   // (the host pass sees a 32-bit LDS address become one of its pointers; it never runs this)
 template <int N>
 __device__ __forceinline__ void mac_words_half(float (&acc)[4], const uint32_t* off, const float* wv) {
   halfx4 c[N];
@@ -279,6 +281,7 @@ __device__ __forceinline__ void mac_words_half(float (&acc)[4], const uint32_t* 
     for (int b = 0; b < 4; ++b) acc[b] = fmaf(wv[j], (float)c[j][b], acc[b]);
   }
 }
+#pragma clang diagnostic pop
 template <int NW>
 __device__ __forceinline__ void operate_half(float (&acc)[4], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w) {
 #pragma unroll
