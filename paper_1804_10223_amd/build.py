@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsprnn.so")
 PROBE_LIB = os.path.join(HERE, "libsprnn_probe.so")
 SOURCES = ["sprnn_pack.cpp", "sprnn_kernels.hip", "sprnn_kernels_bwd.hip", "sprnn_kernels_gated_bwd.hip",
-           "sprnn_kernels_timeline.hip", "sprnn_kernels_overlap.hip", "sprnn_kernels_pool.hip", "sprnn_kernels_pool_bwd.hip", "sprnn_kernels_pool_bwd_grad.hip", "sprnn_project.hip", "sprnn_api.hip"]
+           "sprnn_kernels_timeline.hip", "sprnn_kernels_overlap.hip", "sprnn_kernels_short.hip", "sprnn_kernels_pool.hip", "sprnn_kernels_pool_bwd.hip", "sprnn_kernels_pool_bwd_grad.hip", "sprnn_project.hip", "sprnn_api.hip"]
 PROBE_SOURCES = ["sprnn_probe.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -254,6 +254,13 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
                                : (m.seg_rounds ? persistent_overlap_kernel_for(m.batch, m.template_words, m.timeline != 0)
                                   : (m.half ? persistent_half_kernel_for(m.batch, m.template_words)
                                             : persistent_kernel_for(m.batch, m.template_words, m.cell, m.timeline != 0))));
+  // a short h (at most three rounds of the copy): the forward instantiation that issues exactly that many loads
+  const int copy_rounds = (m.h_bytes / 16 + m.block - 1) / m.block;
+  if (!pool && !m.narrow && !m.seg_rounds && !m.half && !m.timeline && !m.compact && m.grid > 1 && copy_rounds <= 3 &&
+      m.cell <= SPRNN_CELL_GRU) {
+    const void* k = persistent_short_kernel_for(m.batch, m.template_words, m.cell);
+    if (k) h->kernel = k;
+  }
   if (!h->kernel) { release(h); return SPRNN_ERR_UNSUPPORTED; }
 
   // One workgroup per CU: ask for more than half of a CU's LDS so that two can never share one.

@@ -521,9 +521,15 @@ __device__ __forceinline__ bool copy_two_parts(__amdgpu_buffer_rsrc_t ring, int 
 // useful work during the load stage),
 // 11 = the vanilla cell's forward pass with h exchanged and kept in LDS as binary16 (batch 4; options.activations;
 // Section 6 names lower-precision activations as future work): one 8-byte gather per nonzero, products and sums in
-// binary32, every h_t rounded to nearest once before it is published (h_out keeps the unrounded value).
-template <int B, int NW, int CELL, bool TL>
-__global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL == 8) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
+// binary32, every h_t rounded to nearest once before it is published (h_out keeps the unrounded value),
+// 12, 13, 14 = the forward passes 0, 1, 2 for a layer whose h takes at most three rounds of the copy (one 16-byte piece
+// per lane and round): the copy issues exactly that many loads.  The general code always issues four (rounds past the
+// end re-fetch the clamped last piece), which costs a small layer 0.1 us per surplus round; choosing between the two
+// inside one kernel cost the four-round layers 3 %, hence separate instantiations.
+template <int B, int NW, int CELLX, bool TL>
+__global__ __launch_bounds__(NW >= 48 ? 256 : ((CELLX == 4 || CELLX == 6 || CELLX == 8) && NW >= 24 ? 512 : 768)) void persistent_kernel(const KernelArgs p) {
+  constexpr bool kShort = CELLX >= 12 && CELLX <= 14;        // forward pass of cell CELLX - 12 for a short h (see the list above)
+  constexpr int CELL = kShort ? CELLX - 12 : CELLX;
   constexpr bool LSTM = CELL == 1 || CELL == 2;   // gated cell: four row groups per unit, cell lanes
   constexpr bool LBWD = CELL >= 5 && CELL <= 8;                // backward pass of a gated cell
   constexpr bool GBWD = CELL == 7 || CELL == 8;                // ... of the GRU
@@ -858,9 +864,19 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELL == 4 || CELL == 6 || CELL =
       } else if (!failed) {   // (after a grid barrier every chunk is valid at the first load)
         if (chunk_rounds <= 4) {
           if (!compacted) {
-            if (kHalf && chunk_rounds <= 2) {
-              // half the bytes, half the rounds: a copy of four would end with two rounds in which every lane fetches the
-              // clamped last chunk and writes it to one and the same LDS address (measured: 0.1 us per such round here)
+            if constexpr (kShort) {   // (the host selects these instantiations only for one to three rounds)
+              if (chunk_rounds <= 1) {
+                const int one[1] = {fsrc[0]};
+                failed = !copy_chunks<1, false>(ring, slot_byte, one, one, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+              } else if (chunk_rounds == 2) {
+                const int two[2] = {fsrc[0], fsrc[1]};
+                failed = !copy_chunks<2, false>(ring, slot_byte, two, two, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+              } else {
+                const int three[3] = {fsrc[0], fsrc[1], fsrc[2]};
+                failed = !copy_chunks<3, false>(ring, slot_byte, three, three, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+              }
+            } else if (kHalf && chunk_rounds <= 2) {
+              // half the bytes, half the rounds (see instantiations 12..14 for why the count is matched)
               const int two[2] = {fsrc[0], fsrc[1]};
               failed = !copy_chunks<2, false, kHalf>(ring, slot_byte, two, two, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
             } else {
