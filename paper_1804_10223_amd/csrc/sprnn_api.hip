@@ -46,6 +46,7 @@ struct sprnn_handle_s {
   bool one_xcd = false;          // launches hold 8 x grid workgroups and those of one XCD take the work
   bool poisoned = false;         // a watchdog trip was observed: the ring no longer holds a consistent state
   bool used_shared_exchange = false;   // sprnn_forward_noalloc ran on this handle: sprnn_check also reads its status word
+  float calibrated_us = 0.0f;    // microseconds per step of the setting the calibration kept (0: not measured)
 };
 
 // ---- storage of sprnn_forward_noalloc: one array per device, alive as long as the library is loaded.
@@ -153,7 +154,7 @@ struct LaunchExtras {
 };
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const LaunchExtras& ex = LaunchExtras());
-static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd);
+static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_runs);
 
 extern "C" {
 
@@ -201,20 +202,12 @@ int sprnn_pack_host(int hidden, int batch, int activation, const int32_t* row_pt
   return SPRNN_OK;
 }
 
-int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
-                    const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
-                    const sprnn_options_t* opt) {
-  if (!out) return SPRNN_ERR_INVALID;
-  *out = nullptr;
-  int ndev = 0;
-  if (!SPRNN_HIP(hipGetDeviceCount(&ndev))) return SPRNN_ERR_HIP;
-  if (device_id < 0 || device_id >= ndev) return SPRNN_ERR_INVALID;
-  DeviceGuard guard(device_id);
-  if (!guard.ok) return SPRNN_ERR_HIP;
-  hipDeviceProp_t prop;
-  if (!SPRNN_HIP(hipGetDeviceProperties(&prop, device_id))) return SPRNN_ERR_HIP;
-  if (!prop.cooperativeLaunch) return SPRNN_ERR_UNSUPPORTED;
-
+// One handle for one set of options: mapping, packing, upload, kernel choice, calibration.  `long_runs` makes the
+// calibration time runs long enough to be compared between two handles of different launch size.
+static int create_one(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
+                      const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
+                      const sprnn_options_t* opt, const hipDeviceProp_t& prop, bool free_choice, bool long_runs,
+                      int* fewer_grid) {
   Packed P;
   int rc;
   try {
@@ -358,11 +351,68 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     ok = SPRNN_HIP(upload(&h->d_timeline, zeros.data(), zeros.size()));
   }
   if (!ok || !SPRNN_HIP(hipDeviceSynchronize())) { release(h); return SPRNN_ERR_HIP; }
+  // Would the same rows fit the CUs of one XCD as fewer, larger workgroups?  (the caller then builds that mapping too)
+  int fewer = 0;
+  {
+    const int per_xcd = prop.multiProcessorCount / 8;
+    const int units_per_wave = (kWave / m.lanes_per_row) / ((m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU) ? 4 : 1);
+    const int wt = (m.hidden + units_per_wave - 1) / units_per_wave;          // wavefronts that own rows
+    const int wave_cap = m.template_words >= 48 ? 4 : kMaxWaves;
+    const int waves2 = per_xcd > 0 ? (wt + per_xcd - 1) / per_xcd : 0;
+    if (free_choice && calibrate && !pool && !m.compact && per_xcd >= 2 && m.grid > per_xcd && waves2 <= wave_cap &&
+        m.cell != SPRNN_CELL_LSTM_BACKWARD && m.cell != SPRNN_CELL_GRU_BACKWARD)
+      fewer = (wt + waves2 - 1) / waves2;
+  }
   if (calibrate) {
-    const int rc2 = calibrate_poll_delay(h, try_one_xcd);
+    const int rc2 = calibrate_poll_delay(h, try_one_xcd, long_runs || fewer > 0);
     if (rc2 != SPRNN_OK) { release(h); return rc2; }
   }
+  if (fewer_grid) *fewer_grid = fewer;
   *out = h;
+  return SPRNN_OK;
+}
+
+int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
+                    const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
+                    const sprnn_options_t* opt) {
+  if (!out) return SPRNN_ERR_INVALID;
+  *out = nullptr;
+  int ndev = 0;
+  if (!SPRNN_HIP(hipGetDeviceCount(&ndev))) return SPRNN_ERR_HIP;
+  if (device_id < 0 || device_id >= ndev) return SPRNN_ERR_INVALID;
+  DeviceGuard guard(device_id);
+  if (!guard.ok) return SPRNN_ERR_HIP;
+  hipDeviceProp_t prop;
+  if (!SPRNN_HIP(hipGetDeviceProperties(&prop, device_id))) return SPRNN_ERR_HIP;
+  if (!prop.cooperativeLaunch) return SPRNN_ERR_UNSUPPORTED;
+
+  // A layer whose own mapping needs a few more workgroups than one XCD has CUs may run faster on fewer, larger
+  // workgroups that fit one XCD (the exchange then stays inside one L2).  Which is faster depends on the matrix, so
+  // when nothing about the mapping was asked for, both are built and calibrated with runs of the same length, and
+  // the faster handle is kept.
+  const bool free_choice = !opt || (opt->grid == 0 && opt->waves == 0 && opt->fill_waves == 0 && opt->lanes_per_row == 0 &&
+                                    opt->layout == 0 && opt->poll_delay == 0 && opt->xcd == 0 && opt->sync == 0 &&
+                                    opt->timeline == 0 && opt->gather == 0 && opt->overlap == 0 && opt->compact == 0);
+  sprnn_handle_t first = nullptr;
+  int fewer_grid = 0;
+  const int rc = create_one(&first, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, opt, prop,
+                            free_choice, false, &fewer_grid);
+  if (rc != SPRNN_OK) return rc;
+  if (fewer_grid > 0 && first->calibrated_us > 0.0f) {
+    sprnn_options_t fewer = opt ? *opt : sprnn_options_t();
+    if (!opt) std::memset(&fewer, 0, sizeof(fewer));
+    fewer.grid = fewer_grid;
+    sprnn_handle_t second = nullptr;
+    const int rc2 = create_one(&second, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, &fewer, prop,
+                               false, true, nullptr);
+    if (rc2 == SPRNN_OK && second->calibrated_us > 0.0f && second->calibrated_us < 0.98f * first->calibrated_us) {
+      release(first);
+      first = second;
+    } else if (rc2 == SPRNN_OK) {
+      release(second);
+    }
+  }
+  *out = first;
   return SPRNN_OK;
 }
 
@@ -449,11 +499,11 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
 // conflicts, cell type).  Polling too early is far more expensive than polling late, and the sweet spot moves
 // from 3 to 12 units between the measured shapes, so it is measured once per handle: a short run on zero input
 // for a handful of candidates, keeping the fastest.  Timing does not depend on the data.
-static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd) {
+static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_runs) {
   const Mapping& m = h->map;
   // (a launch of the one-XCD mode holds eight times the workgroups and costs a few microseconds more to start: the
   // comparison of the two placements runs long enough for the per-step time to decide, as it does at real lengths)
-  const int T = try_one_xcd ? 160 : 48;
+  const int T = (try_one_xcd || long_runs) ? 160 : 48;
   // (the gated cells' backward passes read [T][B][4H] kept gate values from the zero buffer)
   const size_t xn = (size_t)T * m.batch * std::max(std::max(m.rows, m.cols), 4 * m.hidden), hn = (size_t)T * m.batch * m.cols;
   float *d_x = nullptr, *d_h = nullptr, *d_c = nullptr;
@@ -464,6 +514,7 @@ static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd) {
             SPRNN_HIP(hipEventCreate(&e0)) && SPRNN_HIP(hipEventCreate(&e1));
   int best = h->map.poll_delay;
   bool best_one_xcd = h->one_xcd;
+  float best_ms_kept = 0.0f;
   int rc = SPRNN_OK;
   if (ok) {
     // The exchange inside one XCD is shorter, so its candidates start lower; it is tried second, and dropped for good if
@@ -504,12 +555,14 @@ static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd) {
         if (best_ms == 0.0f || ms < best_ms) { best_ms = ms; best = h->map.poll_delay; best_one_xcd = mode == 1; }
       }
     }
+    best_ms_kept = best_ms;
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
   (void)hipFree(d_x); (void)hipFree(d_h); (void)hipFree(d_c);
   h->one_xcd = (ok && rc == SPRNN_OK) ? best_one_xcd : false;
   h->map.poll_delay = (ok && rc == SPRNN_OK) ? best : default_poll_delay(h->map);
+  h->calibrated_us = (ok && rc == SPRNN_OK) ? best_ms_kept * 1000.0f / (float)T : 0.0f;
   if (rc == SPRNN_OK && sprnn_check(h) != SPRNN_OK) rc = SPRNN_ERR_STATE;
   return rc;   // allocation or timing trouble is not fatal: the fallback value is used
 }

@@ -394,6 +394,27 @@ def test_one_xcd_mode_repeated_calls_and_refusal():
         assert np.array_equal(rnn.forward(x, h0).cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("cell,H,B,dens", [("relu", 1152, 4, 0.10), ("tanh", 1280, 2, 0.10), ("lstm", 640, 4, 0.1)])
+def test_layers_a_little_larger_than_one_xcd_are_also_tried_as_fewer_larger_workgroups(cell, H, B, dens):
+    # With nothing asked for, sprnn_create builds the mapping of its own choice and, where the same rows fit the CUs of
+    # one XCD as larger workgroups, that one too, and keeps the faster.  Whichever it keeps must give the oracle's result;
+    # a caller who fixes any part of the mapping gets exactly the mapping asked for.
+    w = wl.make_workload("f", cell, H, B, 12, dens, seed=11, gain=1.0 if cell == "lstm" else 0.9, h0_std=0.3)
+    want, wantc = oracle_run(w)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, xcd="spread") as rnn:
+        own = rnn.info()
+    assert own["grid"] > 32, own          # (the shapes are chosen so that the library's own mapping exceeds one XCD)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        info = rnn.info()
+        print("case", cell, H, B, "own grid", own["grid"], "x", own["block"], "kept", info["grid"], "x", info["block"],
+              "one xcd", info["one_xcd"], flush=True)
+        assert info["grid"] == own["grid"] or (info["grid"] <= 32 and info["one_xcd"] == 1), info
+        got, gotc = gpu_run(rnn, w)
+        assert_parity(got, want)
+        if cell == "lstm":
+            assert_parity(gotc, wantc)
+
+
 def test_narrow_gathers_are_refused_where_not_built():
     w = wl.make_workload("n", "relu", 200, 2, 2, 0.2, seed=0)
     with pytest.raises(binding.SprnnError) as e:
