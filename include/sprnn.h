@@ -72,13 +72,18 @@ typedef struct sprnn_options_s {
   int timeline;      /* 1 = workgroup 0..grid-1 accumulate per-phase times (see sprnn_read_timeline) */
   int fill_waves;    /* total wavefronts per workgroup when larger than `waves`: the extra ones own no
                         rows and only help to copy h into LDS                                      */
-  int plain_launch;  /* 1 = ordinary kernel launch instead of a cooperative one: about 10 us less per
-                        forward call, but the caller must then guarantee that nothing else runs on the
-                        device meanwhile (the workgroups spin on each other and must all be resident;
-                        the spin watchdog still bounds every wait).  Also the way to run in a second
-                        process on one device: the HIP runtime grants cooperative launches to one
-                        process per device at a time, and refuses the others' (then sprnn_create
-                        returns SPRNN_ERR_HIP from its first launch)                               */
+  int launch;        /* how the persistent kernel is started: 0 or 1 = ordinary kernel launch, 2 = cooperative
+                        launch.  The workgroups spin on each other and must all be resident at once.  The
+                        library checks at create time that the grid fits the device, and it orders its own
+                        persistent launches on a device one after the other, whatever streams they are given
+                        to (an event between consecutive launches on different streams; not inside a stream
+                        capture), so two of them never wait for each other's compute units.  Other kernels on
+                        other streams only delay a launch.  What an ordinary launch cannot rule out is another
+                        PROCESS spinning on the same device at the same time: every wait is bounded, so that
+                        ends in SPRNN_ERR_STATE from sprnn_check, not in a hang.  A cooperative launch has the
+                        runtime enforce exclusive residency instead; it costs about 16 us more per call, and
+                        the HIP runtime grants cooperative launches to one process per device at a time
+                        (another process gets SPRNN_ERR_HIP from sprnn_create)                         */
   int jitter;        /* test aid: non-zero seeds pseudo-random pauses (0..15 x 64 clocks) of every
                         wavefront before it publishes, before it polls and after it has copied h,
                         different in every step, to widen the windows of any race in the hand-off;

@@ -29,6 +29,7 @@ LAYOUT = {"auto": 0, "row_groups": 1, "lane_pool": 2}
 GATHER = {"auto": 0, "wide": 1, "narrow": 2}
 ACTIVATIONS = {"auto": 0, "binary32": 1, "binary16": 2}
 XCD = {"auto": 0, "spread": 1, "one": 2}
+LAUNCH = {"auto": 0, "ordinary": 1, "cooperative": 2}
 
 EXPORTS = ["sprnn_create", "sprnn_create_ex", "sprnn_forward", "sprnn_forward_noalloc", "sprnn_forward_lstm", "sprnn_forward_lstm_train", "sprnn_forward_gru",
            "sprnn_forward_stepwise", "sprnn_backward_lstm", "sprnn_backward_lstm_with_weights", "sprnn_forward_gru_train",
@@ -42,7 +43,7 @@ class Options(ctypes.Structure):
     _fields_ = [("grid", ctypes.c_int), ("waves", ctypes.c_int), ("lanes_per_row", ctypes.c_int),
                 ("sync", ctypes.c_int), ("bank_aware", ctypes.c_int), ("balance", ctypes.c_int),
                 ("poll_delay", ctypes.c_int), ("spin_limit", ctypes.c_int), ("timeline", ctypes.c_int),
-                ("fill_waves", ctypes.c_int), ("plain_launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
+                ("fill_waves", ctypes.c_int), ("launch", ctypes.c_int), ("jitter", ctypes.c_int), ("compact", ctypes.c_int), ("layout", ctypes.c_int),
                 ("gather", ctypes.c_int), ("xcd", ctypes.c_int), ("overlap", ctypes.c_int), ("activations", ctypes.c_int)]
 
 
@@ -187,6 +188,8 @@ def make_options(**kw) -> Options:
             v = XCD[v]
         if k == "activations" and isinstance(v, str):
             v = ACTIVATIONS[v]
+        if k == "launch" and isinstance(v, str):
+            v = LAUNCH[v]
         if not hasattr(o, k):
             raise TypeError("unknown option %r" % k)
         setattr(o, k, int(v))

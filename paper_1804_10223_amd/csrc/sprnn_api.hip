@@ -154,6 +154,51 @@ struct LaunchExtras {
 };
 static int forward_persistent(sprnn_handle_t h, int T, const float* x, const float* h0, const float* c0,
                               float* h_out, float* c_out, void* stream, const LaunchExtras& ex = LaunchExtras());
+// Ordinary launches of kernels whose workgroups spin on each other: two of them must never hold compute units while
+// waiting for the other's, so the library runs its persistent launches on a device one after the other.  Launches on
+// one stream are in order already and cost nothing extra.  A launch on another stream than the one before first
+// records an event on that earlier stream (behind the earlier launch and whatever followed it there) and waits for
+// it; if the earlier stream no longer exists, the device is synchronized instead.  Inside a stream capture nothing is
+// recorded or waited for (an event from outside cannot be waited on there): a captured graph's order is the caller's.
+struct LaunchOrder {
+  std::mutex mutex;
+  hipEvent_t done = nullptr;
+  hipStream_t stream = nullptr;   // the stream of the latest persistent launch
+  bool any = false;
+};
+static LaunchOrder g_launch_order[kMaxScratchDevices];
+
+static hipError_t launch_in_order(int device, const void* kernel, int grid, int block, void** args, unsigned lds, hipStream_t stream) {
+  if (device < 0 || device >= kMaxScratchDevices) return hipErrorInvalidDevice;
+  LaunchOrder& o = g_launch_order[device];
+  std::lock_guard<std::mutex> lock(o.mutex);
+  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) { (void)hipGetLastError(); capturing = hipStreamCaptureStatusNone; }
+  const bool ordered = capturing == hipStreamCaptureStatusNone;
+  hipStreamCaptureStatus earlier = hipStreamCaptureStatusNone;   // (an earlier stream that is being captured by now holds no running work of its own)
+  if (ordered && o.any && o.stream != stream && hipStreamIsCapturing(o.stream, &earlier) != hipSuccess) {
+    (void)hipGetLastError();            // the earlier stream is gone: whatever it left behind is waited for below
+    earlier = hipStreamCaptureStatusNone;
+  }
+  if (ordered && o.any && o.stream != stream && earlier == hipStreamCaptureStatusNone) {
+    if (!o.done) {
+      const hipError_t c = hipEventCreateWithFlags(&o.done, hipEventDisableTiming);
+      if (c != hipSuccess) { o.done = nullptr; return c; }
+    }
+    if (hipEventRecord(o.done, o.stream) == hipSuccess) {
+      const hipError_t w = hipStreamWaitEvent(stream, o.done, 0);
+      if (w != hipSuccess) return w;
+    } else {
+      (void)hipGetLastError();
+      const hipError_t w = hipDeviceSynchronize();
+      if (w != hipSuccess) return w;
+    }
+  }
+  const hipError_t e = hipLaunchKernel(kernel, dim3(grid), dim3(block), args, lds, stream);
+  if (e == hipSuccess && ordered) { o.stream = stream; o.any = true; }
+  return e;
+}
+
 static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_runs);
 
 extern "C" {
@@ -384,7 +429,7 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   if (!guard.ok) return SPRNN_ERR_HIP;
   hipDeviceProp_t prop;
   if (!SPRNN_HIP(hipGetDeviceProperties(&prop, device_id))) return SPRNN_ERR_HIP;
-  if (!prop.cooperativeLaunch) return SPRNN_ERR_UNSUPPORTED;
+  if (opt && opt->launch == 2 && !prop.cooperativeLaunch) return SPRNN_ERR_UNSUPPORTED;
 
   // A layer whose own mapping needs a few more workgroups than one XCD has CUs may run faster on fewer, larger
   // workgroups that fit one XCD (the exchange then stays inside one L2).  Which is faster depends on the matrix, so
@@ -478,14 +523,19 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
     a.step_base = ex.shared_exchange ? 0u : h->step_base;
     a.barrier_base = ex.shared_exchange ? 0u : h->barrier_base;
     void* args[] = {&a};
-    // a single workgroup waits for nobody, so it needs no co-residency guarantee and takes the cheaper launch
-    const bool plain = m.plain_launch != 0 || m.grid == 1;
     const bool lstm_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;   // the handle's own kernel is the backward pass
     const void* kernel = ex.backward ? (ex.dU ? h->kernel_bwd_grad : (lstm_bwd ? h->kernel : h->kernel_bwd)) : h->kernel;
     const int launch_grid = m.grid * (h->one_xcd ? 8 : 1);
-    hipError_t e = plain ? hipLaunchKernel(kernel, dim3(launch_grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream)
-                         : hipLaunchCooperativeKernel(kernel, dim3(launch_grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
-    if (!hip_ok(e, "hipLaunchCooperativeKernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
+    hipError_t e;
+    if (m.cooperative && m.grid > 1) {
+      e = hipLaunchCooperativeKernel(kernel, dim3(launch_grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+    } else if (m.grid == 1) {
+      // a single workgroup waits for nobody
+      e = hipLaunchKernel(kernel, dim3(launch_grid), dim3(m.block), args, (unsigned)h->launch_lds, (hipStream_t)stream);
+    } else {
+      e = launch_in_order(h->device, kernel, launch_grid, m.block, args, (unsigned)h->launch_lds, (hipStream_t)stream);
+    }
+    if (!hip_ok(e, "launch of the persistent kernel")) return e == hipErrorCooperativeLaunchTooLarge ? SPRNN_ERR_CAPACITY : SPRNN_ERR_HIP;
     if (ex.shared_exchange) continue;   // (the handle's own ring did not move)
     h->launch_epoch += 1;
     const int ran = tn + ((ex.backward && (ex.dh0 || ex.dU)) ? 1 : 0);   // the backward pass adds the step that pairs delta_1 with h_0

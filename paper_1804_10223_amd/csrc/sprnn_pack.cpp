@@ -179,7 +179,8 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   m->poll_delay = opt ? opt->poll_delay : 0;
   m->spin_limit = (opt && opt->spin_limit > 0) ? opt->spin_limit : (1 << 22);
   m->timeline = (opt && opt->timeline) ? 1 : 0;
-  m->plain_launch = (opt && opt->plain_launch) ? 1 : 0;
+  if (opt && (opt->launch < 0 || opt->launch > 2)) return SPRNN_ERR_INVALID;
+  m->cooperative = (opt && opt->launch == 2) ? 1 : 0;
   m->jitter = opt ? opt->jitter : 0;
   m->narrow = (opt && opt->gather == 2) ? 1 : 0;
   if (opt && (opt->gather < 0 || opt->gather > 2)) return SPRNN_ERR_INVALID;
@@ -500,7 +501,8 @@ static int pack_pool(int hidden, int batch, int cell, const int32_t* row_ptr, co
   m.poll_delay = opt ? opt->poll_delay : 0;
   m.spin_limit = (opt && opt->spin_limit > 0) ? opt->spin_limit : (1 << 22);
   m.timeline = (opt && opt->timeline) ? 1 : 0;
-  m.plain_launch = (opt && opt->plain_launch) ? 1 : 0;
+  if (opt && (opt->launch < 0 || opt->launch > 2)) return SPRNN_ERR_INVALID;
+  m.cooperative = (opt && opt->launch == 2) ? 1 : 0;
   m.jitter = opt ? opt->jitter : 0;
 
   Packed& P = *out;

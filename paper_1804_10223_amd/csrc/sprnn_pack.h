@@ -29,7 +29,7 @@ struct Mapping {
   int cols = 0;              // columns of the matrix = length of the exchanged vector (4 * hidden for the LSTM's backward pass, else hidden)
   int grid = 0, waves = 0, row_waves = 0, block = 0, lanes_per_row = 0;   // waves = all, row_waves = those owning rows
   int sync = SPRNN_SYNC_TAGGED, bank_aware = 1, balance = 2, poll_delay = 0, spin_limit = 0, timeline = 0;
-  int plain_launch = 0;      // 1: ordinary kernel launch instead of a cooperative one
+  int cooperative = 0;       // 1: cooperative launch instead of an ordinary one
   int jitter = 0;            // test aid: seed of pseudo-random pauses in the hand-off (0 = none)
   int half = 0;              // 1: h is exchanged and kept in LDS as binary16 (options.activations = 2)
   int layout_batch = 0;      // samples' worth of 4-byte elements per column of the LDS copy: batch, or batch / 2 with binary16 activations

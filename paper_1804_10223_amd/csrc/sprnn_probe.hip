@@ -246,7 +246,7 @@ int sprnn_probe_fill(int device, int workgroups, int threads, int bytes, int rou
   for (int rep = 0; rep < 3; ++rep) {
     int* pb = (int*)d_buf.p; int n4 = bytes / 16; int r = rounds; long long* po = (long long*)d_out.p; int* ps = (int*)d_sink.p;
     void* args[] = {&pb, &n4, &r, &po, &ps};
-    PROBE_CHECK(hipLaunchCooperativeKernel((const void*)fill_probe_kernel, dim3(workgroups), dim3(threads), args, 96 * 1024, 0));
+    PROBE_CHECK(hipLaunchKernel((const void*)fill_probe_kernel, dim3(workgroups), dim3(threads), args, 96 * 1024, 0));   // (96 KB of LDS: one workgroup per CU, all at once)
     PROBE_CHECK(hipDeviceSynchronize());
     PROBE_CHECK(hipMemcpy(o.data(), d_out.p, (size_t)workgroups * 8, hipMemcpyDeviceToHost));
     const long long mx = *std::max_element(o.begin(), o.end());

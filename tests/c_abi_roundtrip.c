@@ -31,11 +31,10 @@ int main(void) {
   CHECK_HIP(hipMemcpy(d_x, x, sizeof(x), hipMemcpyHostToDevice));
   CHECK_HIP(hipMemcpy(d_h0, h0, sizeof(h0), hipMemcpyHostToDevice));
 
-  /* Ordinary launches: the test runner that starts this program may itself have used the library, and the HIP runtime
-   * grants cooperative launches to one process per device at a time.  Nothing else runs on the device meanwhile. */
+  /* Default options: ordinary launches, so this program can run beside the test runner that starts it (which may
+   * itself have used the library on this device; nothing of it runs meanwhile). */
   sprnn_options_t opt;
   memset(&opt, 0, sizeof(opt));
-  opt.plain_launch = 1;
   sprnn_handle_t handle = NULL;
   CHECK_RC(sprnn_create_ex(&handle, H, B, SPRNN_ACT_RELU, row_ptr, col, val, 0, &opt));
   sprnn_info_t info;

@@ -102,7 +102,7 @@ SMALL = [
     ("relu", 1152, 4, 20, 0.3, "fixed", {"overlap": 2, "xcd": "one", "grid": 32, "lanes_per_row": 16}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"gather": "narrow"}),                       # one 4-byte LDS read per sample (ablation rung)
     ("tanh", 1152, 4, 12, 0.1, "fixed", {"gather": "narrow", "sync": "barrier", "bank_aware": 2}),   # the ablation's first rung
-    ("relu", 500, 4, 10, 0.2, "fixed", {"plain_launch": 1}),
+    ("relu", 500, 4, 10, 0.2, "fixed", {"launch": "cooperative"}),
     ("relu", 500, 4, 10, 0.2, "fixed", {"compact": 1}),
     ("relu", 2000, 4, 8, 0.01, "poisson", {"compact": 1, "grid": 50}),
     ("tanh", 1500, 2, 8, 0.01, "fixed", {"compact": 1, "grid": 40}),
@@ -365,6 +365,37 @@ def test_side_stream():
         st.synchronize()
         assert rnn.check() == binding.SPRNN_OK
         assert_parity(h.cpu().numpy(), want)
+
+
+def test_two_full_size_handles_on_two_streams_take_turns():
+    # Each of the two layers needs every compute unit, and their workgroups spin on each other: started side by side
+    # they would wait for each other's compute units until the watchdog ends both.  The library orders its persistent
+    # launches on a device, whatever streams they go to, so alternating launches on two streams without any host
+    # synchronisation in between must give the same results as one after the other.
+    wa = wl.make_workload("a", "relu", 2304, 4, 24, 0.3, seed=21, h0_std=0.3)
+    wb = wl.make_workload("b", "tanh", 2048, 4, 24, 0.3, seed=22, h0_std=0.3)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    with binding.SparseRNN(wa.hidden, wa.batch, wa.cell, wa.row_ptr, wa.col_idx, wa.val_bits) as ra, \
+            binding.SparseRNN(wb.hidden, wb.batch, wb.cell, wb.row_ptr, wb.col_idx, wb.val_bits) as rb:
+        print("case grids", ra.info()["grid"], rb.info()["grid"], flush=True)
+        assert ra.info()["grid"] + rb.info()["grid"] > 256
+        xa, ha, xb, hb = _dev(wa.x), _dev(wa.h0), _dev(wb.x), _dev(wb.h0)
+        want_a = ra.forward(xa, ha).cpu().numpy()
+        want_b = rb.forward(xb, hb).cpu().numpy()
+        outs = []
+        torch.cuda.synchronize()
+        for i in range(6):
+            with torch.cuda.stream(s1):
+                oa = ra.forward(xa, ha)
+            with torch.cuda.stream(s2):
+                ob = rb.forward(xb, hb)
+            outs.append((oa, ob))
+        torch.cuda.synchronize()
+        assert ra.check() == binding.SPRNN_OK and rb.check() == binding.SPRNN_OK
+        for oa, ob in outs:
+            assert np.array_equal(oa.cpu().numpy(), want_a) and np.array_equal(ob.cpu().numpy(), want_b)
+    want, _ = oracle_run(wa)
+    assert_parity(want_a, want)
 
 
 # ------------------------------------------------------------------ error paths that need a device
