@@ -411,7 +411,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: sparse %s RNN, hidden %d, batch %d, T %d, density %.0f%%, fp16 weights + u16 indices" % (
             w.name, w.cell, w.hidden, w.batch, T, 100 * w.meta["density"]),
-            "timesteps_per_step": T, "grid": info["grid"], "block": info["block"], "sync": "tagged" if info["sync"] == 1 else "barrier"},
+            "timesteps_per_step": T, "grid": info["grid"], "block": info["block"], "sync": "tagged" if info["sync"] == 1 else "barrier",
+            "launch": "ordinary kernel launch, the library's persistent launches ordered per device (the default)"},
         "roofline": {
             "bound": "lds+exchange",
             "achieved": us_per_ts,
