@@ -166,9 +166,10 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 
 /* Same, with tuning knobs (opt may be NULL).  Unless opt fixes the back-off (poll_delay), creation runs a few short
  * launches on zero input on the device's default stream to measure it (and the XCD placement, if xcd is 0) and
- * synchronizes the device.  When opt fixes nothing about the mapping and the layer needs only a few more workgroups
- * than one XCD has compute units, a second mapping of fewer, larger workgroups is built and measured as well and the
- * faster of the two is kept; sprnn_get_info reports the one in use. */
+ * synchronizes the device.  When opt fixes nothing about the mapping, a second mapping is built and measured as well
+ * in two cases, and the faster of the two is kept (sprnn_get_info reports the one in use): the layer needs only a few
+ * more workgroups than one XCD has compute units (then: fewer, larger workgroups), or another number of wavefronts per
+ * workgroup would copy a large h with at least a tenth fewer loads. */
 int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
                     const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
                     const sprnn_options_t* opt);

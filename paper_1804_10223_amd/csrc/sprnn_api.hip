@@ -247,12 +247,19 @@ int sprnn_pack_host(int hidden, int batch, int activation, const int32_t* row_pt
   return SPRNN_OK;
 }
 
+// A second mapping worth measuring against the library's own choice (0 = none): fewer, larger workgroups that fit one
+// XCD, or more wavefronts per workgroup so that the copy of h issues fewer surplus loads.
+struct Alternative {
+  int grid = 0;
+  int fill_waves = 0;
+};
+
 // One handle for one set of options: mapping, packing, upload, kernel choice, calibration.  `long_runs` makes the
 // calibration time runs long enough to be compared between two handles of different launch size.
 static int create_one(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
                       const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
                       const sprnn_options_t* opt, const hipDeviceProp_t& prop, bool free_choice, bool long_runs,
-                      int* fewer_grid) {
+                      Alternative* alternative) {
   Packed P;
   int rc;
   try {
@@ -397,22 +404,39 @@ static int create_one(sprnn_handle_t* out, int hidden, int batch, int activation
   }
   if (!ok || !SPRNN_HIP(hipDeviceSynchronize())) { release(h); return SPRNN_ERR_HIP; }
   // Would the same rows fit the CUs of one XCD as fewer, larger workgroups?  (the caller then builds that mapping too)
-  int fewer = 0;
-  {
+  Alternative alt;
+  if (free_choice && calibrate && !pool && !m.compact) {
     const int per_xcd = prop.multiProcessorCount / 8;
     const int units_per_wave = (kWave / m.lanes_per_row) / ((m.cell == SPRNN_CELL_LSTM || m.cell == SPRNN_CELL_GRU) ? 4 : 1);
     const int wt = (m.hidden + units_per_wave - 1) / units_per_wave;          // wavefronts that own rows
     const int wave_cap = m.template_words >= 48 ? 4 : kMaxWaves;
     const int waves2 = per_xcd > 0 ? (wt + per_xcd - 1) / per_xcd : 0;
-    if (free_choice && calibrate && !pool && !m.compact && per_xcd >= 2 && m.grid > per_xcd && waves2 <= wave_cap &&
-        m.cell != SPRNN_CELL_LSTM_BACKWARD && m.cell != SPRNN_CELL_GRU_BACKWARD)
-      fewer = (wt + waves2 - 1) / waves2;
+    if (per_xcd >= 2 && m.grid > per_xcd && waves2 <= wave_cap &&
+        m.cell != SPRNN_CELL_LSTM_BACKWARD && m.cell != SPRNN_CELL_GRU_BACKWARD) {
+      alt.grid = (wt + waves2 - 1) / waves2;
+    } else {
+      // The copy of h issues its 16-byte loads in rounds of one per lane: exactly the rounds it needs up to three (in
+      // the instantiations built for that), four up to four, and groups of eight beyond; a load past the end of h
+      // fetches the last piece again and costs the CU's memory port as much as a useful one.  More wavefronts per
+      // workgroup change the count: where some number of them would issue at least a tenth fewer loads per workgroup,
+      // that mapping is measured as well.
+      const int n4 = m.h_bytes / 16;
+      auto issued = [&](int waves) {
+        const int rounds = (n4 + waves * kWave - 1) / (waves * kWave);
+        const int loads = rounds <= 3 && m.cell <= SPRNN_CELL_GRU ? rounds : (rounds <= 4 ? 4 : (rounds + 7) / 8 * 8);
+        return (int64_t)loads * waves;
+      };
+      int best_waves = m.waves;
+      for (int w2 = m.waves + 1; w2 <= wave_cap; ++w2)
+        if (issued(w2) < issued(best_waves)) best_waves = w2;
+      if (best_waves != m.waves && issued(best_waves) * 10 <= issued(m.waves) * 9) alt.fill_waves = best_waves;
+    }
   }
   if (calibrate) {
-    const int rc2 = calibrate_poll_delay(h, try_one_xcd, long_runs || fewer > 0);
+    const int rc2 = calibrate_poll_delay(h, try_one_xcd, long_runs || alt.grid > 0 || alt.fill_waves > 0);
     if (rc2 != SPRNN_OK) { release(h); return rc2; }
   }
-  if (fewer_grid) *fewer_grid = fewer;
+  if (alternative) *alternative = alt;
   *out = h;
   return SPRNN_OK;
 }
@@ -432,23 +456,24 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   if (opt && opt->launch == 2 && !prop.cooperativeLaunch) return SPRNN_ERR_UNSUPPORTED;
 
   // A layer whose own mapping needs a few more workgroups than one XCD has CUs may run faster on fewer, larger
-  // workgroups that fit one XCD (the exchange then stays inside one L2).  Which is faster depends on the matrix, so
-  // when nothing about the mapping was asked for, both are built and calibrated with runs of the same length, and
-  // the faster handle is kept.
+  // workgroups that fit one XCD (the exchange then stays inside one L2), and a layer with a large h on workgroups of
+  // more wavefronts (see create_one).  Which is faster depends on the matrix, so when nothing about the mapping was
+  // asked for, both are built and calibrated with runs of the same length, and the faster handle is kept.
   const bool free_choice = !opt || (opt->grid == 0 && opt->waves == 0 && opt->fill_waves == 0 && opt->lanes_per_row == 0 &&
                                     opt->layout == 0 && opt->poll_delay == 0 && opt->xcd == 0 && opt->sync == 0 &&
                                     opt->timeline == 0 && opt->gather == 0 && opt->overlap == 0 && opt->compact == 0);
   sprnn_handle_t first = nullptr;
-  int fewer_grid = 0;
+  Alternative alt;
   const int rc = create_one(&first, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, opt, prop,
-                            free_choice, false, &fewer_grid);
+                            free_choice, false, &alt);
   if (rc != SPRNN_OK) return rc;
-  if (fewer_grid > 0 && first->calibrated_us > 0.0f) {
-    sprnn_options_t fewer = opt ? *opt : sprnn_options_t();
-    if (!opt) std::memset(&fewer, 0, sizeof(fewer));
-    fewer.grid = fewer_grid;
+  if ((alt.grid > 0 || alt.fill_waves > 0) && first->calibrated_us > 0.0f) {
+    sprnn_options_t other = opt ? *opt : sprnn_options_t();
+    if (!opt) std::memset(&other, 0, sizeof(other));
+    other.grid = alt.grid;
+    other.fill_waves = alt.fill_waves;
     sprnn_handle_t second = nullptr;
-    const int rc2 = create_one(&second, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, &fewer, prop,
+    const int rc2 = create_one(&second, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, &other, prop,
                                false, true, nullptr);
     if (rc2 == SPRNN_OK && second->calibrated_us > 0.0f && second->calibrated_us < 0.98f * first->calibrated_us) {
       release(first);

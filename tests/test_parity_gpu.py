@@ -367,6 +367,24 @@ def test_side_stream():
         assert_parity(h.cpu().numpy(), want)
 
 
+def test_a_large_h_gets_the_wavefront_count_with_fewer_surplus_loads():
+    # 3072 x batch 4: h is 3072 pieces of 16 bytes.  Eight wavefronts copy it in six rounds and issue eight; twelve copy
+    # it in four exactly.  With nothing asked for, both mappings are measured; whichever is kept gives the oracle's
+    # result, and a caller who fixes the count gets that count.
+    w = wl.make_workload("w", "relu", 3072, 4, 6, 0.1, seed=31, h0_std=0.3)
+    want, _ = oracle_run(w)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, fill_waves=8) as rnn:
+        assert rnn.info()["block"] == 512
+        got, _ = gpu_run(rnn, w)
+        assert_parity(got, want)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        info = rnn.info()
+        print("case kept", info["grid"], "x", info["block"], flush=True)
+        assert info["block"] in (512, 768), info
+        got, _ = gpu_run(rnn, w)
+        assert_parity(got, want)
+
+
 def test_two_full_size_handles_on_two_streams_take_turns():
     # Each of the two layers needs every compute unit, and their workgroups spin on each other: started side by side
     # they would wait for each other's compute units until the watchdog ends both.  The library orders its persistent
