@@ -89,8 +89,9 @@ RUNGS = [
 
 def ablation(torch, wl, reps):
     print("## Ablation (cf. Table 1): microseconds per timestep, whole launch / T (layout: one lane group per row)\n")
-    print("| shape | per-timestep launches | persistent: 4-byte gathers, CSR order, grid barrier | + wide gathers | + bank-aware order | + tagged hand-off (default) | tagged hand-off with CSR order | modelled LDS cycles per gather: CSR order / bank-aware |")
-    print("|---|---|---|---|---|---|---|---|")
+    print("The rungs share one mapping (the one the packer picks first); the last column is what `sprnn_create` arrives at when it may also\nmeasure a second mapping and the XCD placement.\n")
+    print("| shape | per-timestep launches | persistent: 4-byte gathers, CSR order, grid barrier | + wide gathers | + bank-aware order | + tagged hand-off | tagged hand-off with CSR order | modelled LDS cycles per gather: CSR order / bank-aware | the library's own choice (grid x block) |")
+    print("|---|---|---|---|---|---|---|---|---|")
     for name in ("cfg2", "cfg3"):
         w = wl.make_config(name)
         step, _ = measure(torch, w, reps, stepwise=True)
@@ -98,9 +99,11 @@ def ablation(torch, wl, reps):
         for rung, opts in RUNGS:
             got[rung] = measure(torch, w, reps, layout=1, **opts)
         tn, _ = measure(torch, w, reps, layout=1, sync="tagged", bank_aware=2)
-        print("| %s: hidden %d, batch %d, density %.0f %%, T %d | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f / %.2f |" % (
+        own, io = measure(torch, w, reps)
+        print("| %s: hidden %d, batch %d, density %.0f %%, T %d | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f / %.2f | %.2f (%d x %d%s) |" % (
             name, w.hidden, w.batch, 100 * w.meta["density"], w.steps, step, got["naive"][0], got["wide"][0], got["bank_aware"][0],
-            got["tagged"][0], tn, got["wide"][1]["lds_pass_factor"], got["bank_aware"][1]["lds_pass_factor"]), flush=True)
+            got["tagged"][0], tn, got["wide"][1]["lds_pass_factor"], got["bank_aware"][1]["lds_pass_factor"],
+            own, io["grid"], io["block"], ", one XCD" if io["one_xcd"] else ""), flush=True)
     print()
     w = wl.make_config("cfg4")
     b1, i1 = measure(torch, w, reps, balance=1)
