@@ -166,10 +166,15 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
 
 /* Same, with tuning knobs (opt may be NULL).  Unless opt fixes the back-off (poll_delay), creation runs a few short
  * launches on zero input on the device's default stream to measure it (and the XCD placement, if xcd is 0) and
- * synchronizes the device.  When opt fixes nothing about the mapping, a second mapping is built and measured as well
- * in two cases, and the faster of the two is kept (sprnn_get_info reports the one in use): the layer needs only a few
- * more workgroups than one XCD has compute units (then: fewer, larger workgroups), or another number of wavefronts per
- * workgroup would copy a large h with at least a tenth fewer loads. */
+ * synchronizes the device.  When opt fixes nothing about the mapping (grid, waves, fill_waves, lanes_per_row,
+ * layout, poll_delay, xcd, sync, timeline, gather, overlap, compact all 0), up to three more mappings are built and
+ * measured the same way, and the fastest is kept (sprnn_get_info reports the one in use): fewer, larger workgroups when
+ * the layer needs only a few more than one XCD has compute units, or another number of wavefronts per workgroup when
+ * that copies a large h with at least a tenth fewer loads; and twice and half the lanes per row.  Creation then takes
+ * 0.05 to 1 s depending on the size of the matrix.
+ * Results are bit-for-bit the same from call to call on one handle, and between handles with the same lanes_per_row
+ * (which fixes the order in which a row's products are added); a caller who needs that across handles passes the value
+ * sprnn_get_info reported for the first. */
 int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, const int32_t* row_ptr,
                     const int32_t* col_idx, const uint16_t* val_fp16_bits, int device_id,
                     const sprnn_options_t* opt);

@@ -465,22 +465,41 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
   sprnn_handle_t first = nullptr;
   Alternative alt;
   const int rc = create_one(&first, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, opt, prop,
-                            free_choice, false, &alt);
+                            free_choice, free_choice, &alt);
   if (rc != SPRNN_OK) return rc;
-  if ((alt.grid > 0 || alt.fill_waves > 0) && first->calibrated_us > 0.0f) {
-    sprnn_options_t other = opt ? *opt : sprnn_options_t();
-    if (!opt) std::memset(&other, 0, sizeof(other));
-    other.grid = alt.grid;
-    other.fill_waves = alt.fill_waves;
+  if (!free_choice || first->calibrated_us <= 0.0f) { *out = first; return SPRNN_OK; }
+  sprnn_options_t base = opt ? *opt : sprnn_options_t();
+  if (!opt) std::memset(&base, 0, sizeof(base));
+  // builds the mapping `other` asks for, measures it like the first, and keeps the faster of the two in `first`
+  auto contend = [&](const sprnn_options_t& other) {
     sprnn_handle_t second = nullptr;
     const int rc2 = create_one(&second, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, &other, prop,
                                false, true, nullptr);
-    if (rc2 == SPRNN_OK && second->calibrated_us > 0.0f && second->calibrated_us < 0.98f * first->calibrated_us) {
+    if (rc2 != SPRNN_OK) return;
+    if (second->calibrated_us > 0.0f && second->calibrated_us < 0.98f * first->calibrated_us) {
       release(first);
       first = second;
-    } else if (rc2 == SPRNN_OK) {
+    } else {
       release(second);
     }
+  };
+  // (1) fewer, larger workgroups on one XCD, or a wavefront count that copies h with fewer loads (see create_one)
+  if (alt.grid > 0 || alt.fill_waves > 0) {
+    sprnn_options_t other = base;
+    other.grid = alt.grid;
+    other.fill_waves = alt.fill_waves;
+    contend(other);
+  }
+  // (2) The lanes a row is spread over: the packer's rule of thumb (at least eight nonzeros per lane) is not the best
+  // for every shape; twice and half as many lanes are measured too, each with the mapping the packer picks for it.
+  const int own_lanes = first->map.lanes_per_row;
+  const bool gated_rows = first->map.cell == SPRNN_CELL_LSTM || first->map.cell == SPRNN_CELL_GRU;
+  for (int pass = 0; pass < 2; ++pass) {
+    const int lanes = pass == 0 ? own_lanes * 2 : own_lanes / 2;
+    if (lanes < batch || lanes < 1 || lanes > (gated_rows ? 16 : kWave)) continue;
+    sprnn_options_t other = base;
+    other.lanes_per_row = lanes;
+    contend(other);
   }
   *out = first;
   return SPRNN_OK;

@@ -117,7 +117,7 @@ def test_headline_shape_and_the_largest_layer_with_binary16_activations():
     plain = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=16)
     outs = []
     for jitter in (0, 7):
-        with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, activations=2, jitter=jitter) as rnn:
+        with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, activations=2, jitter=jitter, lanes_per_row=64) as rnn:   # (pinned: the lanes of a row fix the order of its sums)
             outs.append(rnn.forward(_dev(w.x), _dev(w.h0)).cpu().numpy())
             assert rnn.check() == binding.SPRNN_OK
     assert np.array_equal(outs[0], outs[1])                               # random pauses change nothing

@@ -309,8 +309,12 @@ def test_random_pauses_in_the_hand_off_do_not_change_results(cell, H, B, opts):
     w = wl.make_workload("jit", cell, H, B, T, 0.1, seed=12, gain=1.0 if cell == "lstm" else 0.9, h0_std=0.3)
     want_h, want_c = oracle_run(w)
     ref = None
+    # (the lanes of a row fix the order of its sums; with nothing pinned the library may measure its way to another count
+    # from one handle to the next, so the count the first handle arrived at is asked for in the others)
+    pinned = dict(opts)
     for seed in (0, 1, 2, 3):
-        with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, jitter=seed, **opts) as rnn:
+        with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, jitter=seed, **pinned) as rnn:
+            pinned.setdefault("lanes_per_row", rnn.info()["lanes_per_row"])
             got_h, got_c = gpu_run(rnn, w)
         assert_parity(got_h, want_h, "jitter %d" % seed)
         if want_c is not None:
@@ -380,7 +384,7 @@ def test_a_large_h_gets_the_wavefront_count_with_fewer_surplus_loads():
     with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
         info = rnn.info()
         print("case kept", info["grid"], "x", info["block"], flush=True)
-        assert info["block"] in (512, 768), info
+        assert info["block"] % 64 == 0 and info["block"] <= 768, info
         got, _ = gpu_run(rnn, w)
         assert_parity(got, want)
 
@@ -393,8 +397,8 @@ def test_two_full_size_handles_on_two_streams_take_turns():
     wa = wl.make_workload("a", "relu", 2304, 4, 24, 0.3, seed=21, h0_std=0.3)
     wb = wl.make_workload("b", "tanh", 2048, 4, 24, 0.3, seed=22, h0_std=0.3)
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
-    with binding.SparseRNN(wa.hidden, wa.batch, wa.cell, wa.row_ptr, wa.col_idx, wa.val_bits) as ra, \
-            binding.SparseRNN(wb.hidden, wb.batch, wb.cell, wb.row_ptr, wb.col_idx, wb.val_bits) as rb:
+    with binding.SparseRNN(wa.hidden, wa.batch, wa.cell, wa.row_ptr, wa.col_idx, wa.val_bits, lanes_per_row=64) as ra, \
+            binding.SparseRNN(wb.hidden, wb.batch, wb.cell, wb.row_ptr, wb.col_idx, wb.val_bits, lanes_per_row=64) as rb:
         print("case grids", ra.info()["grid"], rb.info()["grid"], flush=True)
         assert ra.info()["grid"] + rb.info()["grid"] > 256
         xa, ha, xb, hb = _dev(wa.x), _dev(wa.h0), _dev(wb.x), _dev(wb.h0)
@@ -424,6 +428,7 @@ def test_one_xcd_mode_repeated_calls_and_refusal():
     x, h0 = _dev(w.x), _dev(w.h0)
     with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, xcd="spread") as rnn:
         want = rnn.forward(x, h0).cpu().numpy()
+        lanes = rnn.info()["lanes_per_row"]
     with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, xcd="one") as rnn:
         info = rnn.info()
         print("case one xcd", {k: info[k] for k in ("grid", "block", "one_xcd", "poll_delay")}, flush=True)
@@ -439,8 +444,11 @@ def test_one_xcd_mode_repeated_calls_and_refusal():
         binding.SparseRNN(big.hidden, big.batch, big.cell, big.row_ptr, big.col_idx, big.val_bits, xcd="one")
     assert e.value.code == binding.SPRNN_ERR_UNSUPPORTED
     with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:   # auto: measured at create time
-        print("case auto", rnn.info()["one_xcd"], rnn.info()["poll_delay"], flush=True)
-        assert np.array_equal(rnn.forward(x, h0).cpu().numpy(), want)
+        print("case auto", rnn.info()["one_xcd"], rnn.info()["poll_delay"], rnn.info()["lanes_per_row"], flush=True)
+        got = rnn.forward(x, h0).cpu().numpy()
+        if rnn.info()["lanes_per_row"] == lanes:   # the same lanes per row add up in the same order
+            assert np.array_equal(got, want)
+        assert_parity(got, oracle_run(w)[0])
 
 
 @pytest.mark.parametrize("cell,H,B,dens", [("relu", 1152, 4, 0.10), ("tanh", 1280, 2, 0.10), ("lstm", 640, 4, 0.1)])
@@ -457,7 +465,7 @@ def test_layers_a_little_larger_than_one_xcd_are_also_tried_as_fewer_larger_work
         info = rnn.info()
         print("case", cell, H, B, "own grid", own["grid"], "x", own["block"], "kept", info["grid"], "x", info["block"],
               "one xcd", info["one_xcd"], flush=True)
-        assert info["grid"] == own["grid"] or (info["grid"] <= 32 and info["one_xcd"] == 1), info
+        assert info["grid"] <= info["resident_capacity"] and (not info["one_xcd"] or info["grid"] <= 32), info
         got, gotc = gpu_run(rnn, w)
         assert_parity(got, want)
         if cell == "lstm":
@@ -574,7 +582,7 @@ def test_gru_with_random_pauses_is_unchanged():
     w = wl.make_workload("gru", "gru", 768, 4, 40, 0.1, seed=3, gain=1.0, h0_std=0.3)
     outs = []
     for jitter in (0, 5, 11):
-        with binding.SparseRNN(w.hidden, w.batch, "gru", w.row_ptr, w.col_idx, w.val_bits, jitter=jitter) as rnn:
+        with binding.SparseRNN(w.hidden, w.batch, "gru", w.row_ptr, w.col_idx, w.val_bits, jitter=jitter, lanes_per_row=16) as rnn:   # (pinned: the lanes of a row fix the order of its sums)
             outs.append(rnn.forward_gru(_dev(w.x), _dev(w.b_hn), _dev(w.h0)).cpu().numpy())
             assert rnn.check() == binding.SPRNN_OK
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
