@@ -475,6 +475,11 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
     sprnn_handle_t second = nullptr;
     const int rc2 = create_one(&second, hidden, batch, activation, row_ptr, col_idx, val_fp16_bits, device_id, &other, prop,
                                false, true, nullptr);
+    static const bool verbose = std::getenv("SPRNN_DEBUG") != nullptr;
+    if (verbose)
+      std::fprintf(stderr, "sprnn_create: contender (lanes %d, grid %d, fill %d) -> %s, %d x %d, %.3f us per step against %.3f\n",
+                   other.lanes_per_row, other.grid, other.fill_waves, sprnn_status_string(rc2), rc2 == SPRNN_OK ? second->map.grid : 0,
+                   rc2 == SPRNN_OK ? second->map.block : 0, rc2 == SPRNN_OK ? second->calibrated_us : 0.0f, first->calibrated_us);
     if (rc2 != SPRNN_OK) return;
     if (second->calibrated_us > 0.0f && second->calibrated_us < 0.98f * first->calibrated_us) {
       release(first);
@@ -600,11 +605,13 @@ static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_r
   const int T = (try_one_xcd || long_runs) ? 160 : 48;
   // (the gated cells' backward passes read [T][B][4H] kept gate values from the zero buffer)
   const size_t xn = (size_t)T * m.batch * std::max(std::max(m.rows, m.cols), 4 * m.hidden), hn = (size_t)T * m.batch * m.cols;
-  float *d_x = nullptr, *d_h = nullptr, *d_c = nullptr;
+  float *d_x = nullptr, *d_h = nullptr, *d_c = nullptr, *d_v = nullptr;
+  const bool gru_bwd = m.cell == SPRNN_CELL_GRU_BACKWARD;   // (its second output costs stores in every step: measured with it)
   hipEvent_t e0 = nullptr, e1 = nullptr;
   const bool lstm = m.cell == SPRNN_CELL_LSTM;
   bool ok = SPRNN_HIP(hipMalloc((void**)&d_x, xn * 4)) && SPRNN_HIP(hipMemset(d_x, 0, xn * 4)) &&
             SPRNN_HIP(hipMalloc((void**)&d_h, hn * 4)) && (!lstm || SPRNN_HIP(hipMalloc((void**)&d_c, hn * 4))) &&
+            (!gru_bwd || SPRNN_HIP(hipMalloc((void**)&d_v, hn * 4))) &&
             SPRNN_HIP(hipEventCreate(&e0)) && SPRNN_HIP(hipEventCreate(&e1));
   int best = h->map.poll_delay;
   bool best_one_xcd = h->one_xcd;
@@ -629,7 +636,7 @@ static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_r
           // (the LSTM's backward pass reads e_t, the gate values and the cell states: all from the zero buffer)
           LaunchExtras ex;
           const bool gated_bwd = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;
-          if (gated_bwd) { ex.backward = true; ex.saved = d_x; }
+          if (gated_bwd) { ex.backward = true; ex.saved = d_x; ex.gates_out = d_v; }
           rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, gated_bwd ? d_x : d_c, nullptr, ex);
           if (rc != SPRNN_OK) break;
           if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
@@ -653,7 +660,7 @@ static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_r
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
-  (void)hipFree(d_x); (void)hipFree(d_h); (void)hipFree(d_c);
+  (void)hipFree(d_x); (void)hipFree(d_h); (void)hipFree(d_c); (void)hipFree(d_v);
   h->one_xcd = (ok && rc == SPRNN_OK) ? best_one_xcd : false;
   h->map.poll_delay = (ok && rc == SPRNN_OK) ? best : default_poll_delay(h->map);
   h->calibrated_us = (ok && rc == SPRNN_OK) ? best_ms_kept * 1000.0f / (float)T : 0.0f;
