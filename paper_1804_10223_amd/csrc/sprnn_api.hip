@@ -657,6 +657,29 @@ static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_r
       }
     }
     best_ms_kept = best_ms;
+    // A gated cell's backward handle serves two kernels, the plain pass and the one with the weight gradient fused in,
+    // and a mapping that suits one may not suit the other: handles are compared by the sum of both.
+    const bool gated_bwd_cell = m.cell == SPRNN_CELL_LSTM_BACKWARD || m.cell == SPRNN_CELL_GRU_BACKWARD;
+    if (ok && rc == SPRNN_OK && gated_bwd_cell && h->kernel_bwd_grad && best_ms > 0.0f) {
+      float* d_dU = nullptr;
+      h->map.poll_delay = best;
+      h->one_xcd = best_one_xcd;
+      if (SPRNN_HIP(hipMalloc((void**)&d_dU, std::max<size_t>((size_t)m.nnz, 1) * 4))) {
+        float fused = 0.0f;
+        for (int rep = 0; rep < 3 && ok && rc == SPRNN_OK; ++rep) {
+          float ms = 0.0f;
+          LaunchExtras ex;
+          ex.backward = true; ex.saved = d_x; ex.gates_out = d_v; ex.wgrad_h_fwd = d_x; ex.dU = d_dU;
+          if (!SPRNN_HIP(hipEventRecord(e0, nullptr))) { ok = false; break; }
+          rc = forward_persistent(h, T, d_x, nullptr, nullptr, d_h, d_x, nullptr, ex);
+          if (rc != SPRNN_OK) break;
+          if (!SPRNN_HIP(hipEventRecord(e1, nullptr)) || !SPRNN_HIP(hipEventSynchronize(e1)) || !SPRNN_HIP(hipEventElapsedTime(&ms, e0, e1))) { ok = false; break; }
+          if (rep > 0 && (fused == 0.0f || ms < fused)) fused = ms;
+        }
+        if (ok && rc == SPRNN_OK) best_ms_kept += fused;
+      }
+      (void)hipFree(d_dU);
+    }
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
