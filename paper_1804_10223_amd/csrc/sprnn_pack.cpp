@@ -3,7 +3,10 @@
 
 #include <algorithm>
 #include <cstring>
+#include <atomic>
+#include <new>
 #include <numeric>
+#include <thread>
 
 namespace sprnn {
 
@@ -710,8 +713,6 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   m.index_shift = 0;
   if (lds_plane > 65536) { while ((1 << m.index_shift) < m.col_stride) ++m.index_shift; }
   // LDS column position of a column for a workgroup
-  std::vector<int32_t> chunk_pos(compact ? (size_t)chunks_per_plane : 0);
-  auto lds_col = [&](int col) { return compact ? chunk_pos[col / cpc] * cpc + col % cpc : col; };
 
   // Overlap of the copy with the gathers: the first seg_rounds of the copy's rounds (a round = one 16-byte chunk per
   // lane of the workgroup) bring the columns below seg_col; see order_wave_phased.
@@ -762,60 +763,97 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   std::vector<char> is_real_zero(P.words.size(), 0);   // positions holding a stored (explicit) zero weight
   int words_max = 0;
   int64_t padded = 0;
-  std::vector<RowGroup> rg;
-  int pos_wg = -1;
   std::vector<int> wg_cols(m.grid, cols);     // LDS column positions a workgroup may address
-  for (int gw = 0; gw < total_waves; ++gw) {
-    const int wg = gw / m.waves, wave = gw % m.waves;
-    if (compact && wg != pos_wg) {
-      pos_wg = wg;
-      for (size_t i = 0; i < wg_chunks[wg].size(); ++i) chunk_pos[wg_chunks[wg][i]] = (int32_t)i;
-      wg_cols[wg] = std::min<int64_t>((int64_t)wg_chunks[wg].size() * cpc, cols);
-    }
-    const int ncols = wg_cols[wg];
-    int trip = 0;
-    for (int s = 0; s < upw; ++s) {
-      const int u = wave_units[(size_t)gw * upw + s];
-      if (u >= 0) trip = std::max(trip, ceil_div(unit_cost(u), L));
-    }
-    P.wave_words[gw] = trip;
-    words_max = std::max(words_max, trip);
-    padded += (int64_t)trip * kWave;
-    rg.clear();
-    for (int s = 0; s < upw; ++s) {
-      const int u = wave_units[(size_t)gw * upw + s];
-      for (int g = 0; g < gpu_; ++g) {
-        RowGroup q;
-        q.lane0 = (s * gpu_ + g) * L;
-        if (u >= 0) {
-          q.row = unit_row(u, g);
-          for (int32_t k = row_ptr[q.row]; k < row_ptr[q.row + 1]; ++k) q.items.push_back({lds_col(col_idx[k]), val_bits[k]});   // bank classes follow LDS positions
+  // The wavefronts are packed independently of each other (the bank-aware order is most of the time this function
+  // takes), so the workgroups of a large matrix are dealt to a few host threads; each writes only its own workgroups'
+  // parts of the arrays.
+  std::atomic<bool> out_of_memory(false);
+  auto pack_workgroups = [&](int wg_begin, int wg_end, int* words_max_out, int64_t* padded_out) {
+    try {
+      std::vector<int32_t> pos_of_chunk(compact ? (size_t)chunks_per_plane : 0);   // this thread's view of its current workgroup
+      auto col_in_lds = [&](int col) { return compact ? pos_of_chunk[col / cpc] * cpc + col % cpc : col; };
+      std::vector<RowGroup> rg;
+      int local_max = 0;
+      int64_t local_padded = 0;
+      for (int wg = wg_begin; wg < wg_end; ++wg) {
+        if (compact) {
+          for (size_t i = 0; i < wg_chunks[wg].size(); ++i) pos_of_chunk[wg_chunks[wg][i]] = (int32_t)i;
+          wg_cols[wg] = std::min<int64_t>((int64_t)wg_chunks[wg].size() * cpc, cols);
         }
-        rg.push_back(std::move(q));
+        const int ncols = wg_cols[wg];
+        for (int wave = 0; wave < m.waves; ++wave) {
+          const int gw = wg * m.waves + wave;
+          int trip = 0;
+          for (int s = 0; s < upw; ++s) {
+            const int u = wave_units[(size_t)gw * upw + s];
+            if (u >= 0) trip = std::max(trip, ceil_div(unit_cost(u), L));
+          }
+          P.wave_words[gw] = trip;
+          local_max = std::max(local_max, trip);
+          local_padded += (int64_t)trip * kWave;
+          rg.clear();
+          for (int s = 0; s < upw; ++s) {
+            const int u = wave_units[(size_t)gw * upw + s];
+            for (int g = 0; g < gpu_; ++g) {
+              RowGroup q;
+              q.lane0 = (s * gpu_ + g) * L;
+              if (u >= 0) {
+                q.row = unit_row(u, g);
+                for (int32_t k = row_ptr[q.row]; k < row_ptr[q.row + 1]; ++k) q.items.push_back({col_in_lds(col_idx[k]), val_bits[k]});   // bank classes follow LDS positions
+              }
+              rg.push_back(std::move(q));
+            }
+          }
+          if (m.seg_rounds) {
+            const int k1 = phase_words(rg, L, trip, seg_col);
+            P.wave_early[gw] = k1;
+            order_wave_phased(rg, L, trip, k1, seg_col, pm, m.bank_aware == 1);
+          } else {
+            order_wave(rg, L, trip, pm, m.bank_aware == 1);
+          }
+          for (const RowGroup& q : rg) {
+            const size_t tid0 = (size_t)wg * m.block + (size_t)wave * kWave + q.lane0;
+            for (int l = 0; l < L; ++l) P.lane_row[tid0 + l] = q.row < m.rows ? q.row : -1;   // the GRU's empty fourth row owns nothing
+            for (int k = 0; k < trip; ++k)
+              for (int l = 0; l < L; ++l) {
+                const size_t at = ((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + q.lane0 + l;
+                const int i = q.pos[(size_t)k * L + l];
+                if (i < 0) { P.words[at] = pad_word(q.lane0 + l, k, ncols); continue; }
+                const uint32_t idx = ((uint32_t)q.items[i].col * (uint32_t)m.col_stride) >> m.index_shift;
+                P.words[at] = (idx << 16) | q.items[i].bits;
+                P.word_src[at] = row_ptr[q.row] + i;   // items are the row's nonzeros in CSR order
+                if ((q.items[i].bits & 0x7FFFu) == 0) is_real_zero[at] = 1;
+                P.lane_words[tid0 + l] += 1;
+              }
+          }
+        }
+      }
+      *words_max_out = local_max;
+      *padded_out = local_padded;
+    } catch (const std::bad_alloc&) {
+      out_of_memory = true;
+    }
+  };
+  {
+    const int hw = (int)std::thread::hardware_concurrency();
+    const int nthreads = (m.nnz < 100000 || m.grid < 2) ? 1 : std::max(1, std::min(std::min(hw, 16), m.grid));
+    std::vector<int> part_max(nthreads, 0);
+    std::vector<int64_t> part_padded(nthreads, 0);
+    std::vector<std::thread> workers;
+    bool spawn_failed = false;
+    for (int t = 1; t < nthreads && !spawn_failed; ++t) {
+      const int b0 = (int)((int64_t)m.grid * t / nthreads), b1 = (int)((int64_t)m.grid * (t + 1) / nthreads);
+      try {
+        workers.emplace_back(pack_workgroups, b0, b1, &part_max[t], &part_padded[t]);
+      } catch (...) {   // no more threads to be had: this thread does the rest
+        spawn_failed = true;
+        pack_workgroups(b0, m.grid, &part_max[t], &part_padded[t]);
       }
     }
-    if (m.seg_rounds) {
-      const int k1 = phase_words(rg, L, trip, seg_col);
-      P.wave_early[gw] = k1;
-      order_wave_phased(rg, L, trip, k1, seg_col, pm, m.bank_aware == 1);
-    } else {
-      order_wave(rg, L, trip, pm, m.bank_aware == 1);
-    }
-    for (const RowGroup& q : rg) {
-      const size_t tid0 = (size_t)wg * m.block + (size_t)wave * kWave + q.lane0;
-      for (int l = 0; l < L; ++l) P.lane_row[tid0 + l] = q.row < m.rows ? q.row : -1;   // the GRU's empty fourth row owns nothing
-      for (int k = 0; k < trip; ++k)
-        for (int l = 0; l < L; ++l) {
-          const size_t at = ((size_t)wg * NW + k) * m.block + (size_t)wave * kWave + q.lane0 + l;
-          const int i = q.pos[(size_t)k * L + l];
-          if (i < 0) { P.words[at] = pad_word(q.lane0 + l, k, ncols); continue; }
-          const uint32_t idx = ((uint32_t)q.items[i].col * (uint32_t)m.col_stride) >> m.index_shift;
-          P.words[at] = (idx << 16) | q.items[i].bits;
-          P.word_src[at] = row_ptr[q.row] + i;   // items are the row's nonzeros in CSR order
-          if ((q.items[i].bits & 0x7FFFu) == 0) is_real_zero[at] = 1;
-          P.lane_words[tid0 + l] += 1;
-        }
-    }
+    pack_workgroups(0, (int)((int64_t)m.grid / nthreads), &part_max[0], &part_padded[0]);
+    for (auto& w : workers) w.join();
+    if (out_of_memory) throw std::bad_alloc();
+    for (int t = 0; t < nthreads; ++t) { words_max = std::max(words_max, part_max[t]); padded += part_padded[t]; }
   }
   place_fillers(P, wg_cols, is_real_zero);
   P.map.words_max = words_max;
