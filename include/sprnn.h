@@ -171,7 +171,7 @@ int sprnn_create(sprnn_handle_t* out, int hidden, int batch, int activation, con
  * measured the same way, and the fastest is kept (sprnn_get_info reports the one in use): fewer, larger workgroups when
  * the layer needs only a few more than one XCD has compute units, or another number of wavefronts per workgroup when
  * that copies a large h with at least a tenth fewer loads; and twice and half the lanes per row.  Creation then takes
- * 0.05 to 1 s depending on the size of the matrix.
+ * 0.05 to 0.25 s depending on the size of the matrix (the packing runs on several host threads).
  * Results are bit-for-bit the same from call to call on one handle, and between handles with the same lanes_per_row
  * (which fixes the order in which a row's products are added); a caller who needs that across handles passes the value
  * sprnn_get_info reported for the first. */
