@@ -76,7 +76,8 @@ typedef struct sprnn_options_s {
                         launch.  The workgroups spin on each other and must all be resident at once.  The
                         library checks at create time that the grid fits the device, and it orders its own
                         persistent launches on a device one after the other, whatever streams they are given
-                        to (an event between consecutive launches on different streams; not inside a stream
+                        to (an event behind every launch on a caller-made stream, a few microseconds per
+                        call, and between the default stream and others when needed; not inside a stream
                         capture), so two of them never wait for each other's compute units.  Other kernels on
                         other streams only delay a launch.  What an ordinary launch cannot rule out is another
                         PROCESS spinning on the same device at the same time: every wait is bounded, so that

@@ -156,15 +156,18 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
                               float* h_out, float* c_out, void* stream, const LaunchExtras& ex = LaunchExtras());
 // Ordinary launches of kernels whose workgroups spin on each other: two of them must never hold compute units while
 // waiting for the other's, so the library runs its persistent launches on a device one after the other.  Launches on
-// one stream are in order already and cost nothing extra.  A launch on another stream than the one before first
-// records an event on that earlier stream (behind the earlier launch and whatever followed it there) and waits for
-// it; if the earlier stream no longer exists, the device is synchronized instead.  Inside a stream capture nothing is
-// recorded or waited for (an event from outside cannot be waited on there): a captured graph's order is the caller's.
+// one stream are in order already.  A launch on another stream than the one before waits for an event that lies
+// behind that earlier launch.  A stream the caller created may be destroyed at any time, and a destroyed stream must
+// not be handed to the runtime again, so the event is recorded right behind every launch on such a stream (a few
+// microseconds per call); the default stream cannot go away, and a launch there is followed by the event only when
+// the next launch turns out to use another stream.  Inside a stream capture nothing is recorded or waited for (an
+// event from outside cannot be waited on there): a captured graph's order is the caller's.
 struct LaunchOrder {
   std::mutex mutex;
   hipEvent_t done = nullptr;
-  hipStream_t stream = nullptr;   // the stream of the latest persistent launch
-  bool any = false;
+  bool any = false;               // a persistent launch has been made on this device
+  bool on_default = false;        // ... the latest one on the default stream, not yet followed by the event
+  hipStream_t stream = nullptr;   // the stream of the latest launch: compared, never used
 };
 static LaunchOrder g_launch_order[kMaxScratchDevices];
 
@@ -175,28 +178,34 @@ static hipError_t launch_in_order(int device, const void* kernel, int grid, int 
   hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
   if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) { (void)hipGetLastError(); capturing = hipStreamCaptureStatusNone; }
   const bool ordered = capturing == hipStreamCaptureStatusNone;
-  hipStreamCaptureStatus earlier = hipStreamCaptureStatusNone;   // (an earlier stream that is being captured by now holds no running work of its own)
-  if (ordered && o.any && o.stream != stream && hipStreamIsCapturing(o.stream, &earlier) != hipSuccess) {
-    (void)hipGetLastError();            // the earlier stream is gone: whatever it left behind is waited for below
-    earlier = hipStreamCaptureStatusNone;
+  if (!o.done) {
+    const hipError_t c = hipEventCreateWithFlags(&o.done, hipEventDisableTiming);
+    if (c != hipSuccess) { o.done = nullptr; return c; }
   }
-  if (ordered && o.any && o.stream != stream && earlier == hipStreamCaptureStatusNone) {
-    if (!o.done) {
-      const hipError_t c = hipEventCreateWithFlags(&o.done, hipEventDisableTiming);
-      if (c != hipSuccess) { o.done = nullptr; return c; }
+  if (ordered && o.any && o.stream != stream) {
+    bool recorded = !o.on_default;
+    if (o.on_default) {
+      // (this fails while another stream is being captured in the global mode; nothing can be ordered against then)
+      if (hipEventRecord(o.done, nullptr) == hipSuccess) { recorded = true; o.on_default = false; }
+      else (void)hipGetLastError();
     }
-    if (hipEventRecord(o.done, o.stream) == hipSuccess) {
+    if (recorded) {
       const hipError_t w = hipStreamWaitEvent(stream, o.done, 0);
-      if (w != hipSuccess) return w;
-    } else {
-      (void)hipGetLastError();
-      const hipError_t w = hipDeviceSynchronize();
       if (w != hipSuccess) return w;
     }
   }
   const hipError_t e = hipLaunchKernel(kernel, dim3(grid), dim3(block), args, lds, stream);
-  if (e == hipSuccess && ordered) { o.stream = stream; o.any = true; }
-  return e;
+  if (e != hipSuccess || !ordered) return e;
+  o.any = true;
+  o.stream = stream;
+  if (stream == nullptr) {
+    o.on_default = true;
+  } else {
+    o.on_default = false;
+    const hipError_t r = hipEventRecord(o.done, stream);
+    if (r != hipSuccess) return r;
+  }
+  return hipSuccess;
 }
 
 static int calibrate_poll_delay(sprnn_handle_s* h, bool try_one_xcd, bool long_runs);

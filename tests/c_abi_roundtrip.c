@@ -48,6 +48,24 @@ int main(void) {
     for (int b = 0; b < B; ++b)
       for (int i = 0; i < H; ++i)
         if (memcmp(&out[t][b][i], &h0[b][(i + t + 1) % H], sizeof(float)) != 0) ++bad;
+  /* The library orders its persistent launches on a device whatever streams they go to.  Streams that come and go:
+   * a launch on a stream of its own, the stream destroyed, then a launch on another new stream and one on the
+   * default stream; every result must again be the rotation. */
+  for (int round = 0; round < 3; ++round) {
+    hipStream_t s = NULL;
+    if (round < 2) CHECK_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+    CHECK_HIP(hipMemset(d_out, 0xFF, sizeof(out)));
+    CHECK_HIP(hipDeviceSynchronize());
+    CHECK_RC(sprnn_forward(handle, T, d_x, d_h0, d_out, s));
+    CHECK_HIP(hipStreamSynchronize(s));
+    CHECK_RC(sprnn_check(handle));
+    CHECK_HIP(hipMemcpy(out, d_out, sizeof(out), hipMemcpyDeviceToHost));
+    for (int t = 0; t < T; ++t)
+      for (int b = 0; b < B; ++b)
+        for (int i = 0; i < H; ++i)
+          if (memcmp(&out[t][b][i], &h0[b][(i + t + 1) % H], sizeof(float)) != 0) ++bad;
+    if (s) CHECK_HIP(hipStreamDestroy(s));
+  }
   /* wrong call for the cell, and a NULL output: clean refusals */
   if (sprnn_forward_lstm(handle, T, d_x, NULL, NULL, d_out, d_out, NULL) != SPRNN_ERR_UNSUPPORTED) ++bad;
   if (sprnn_forward(handle, T, d_x, d_h0, NULL, NULL) != SPRNN_ERR_INVALID) ++bad;
