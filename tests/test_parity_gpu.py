@@ -420,6 +420,33 @@ def test_two_full_size_handles_on_two_streams_take_turns():
     assert_parity(want_a, want)
 
 
+def test_a_full_size_layer_beside_other_work_on_another_stream():
+    # Ordinary kernels on another stream may hold compute units when the persistent kernel starts: its workgroups that
+    # are already resident wait (bounded) for the others, which get their compute units as the other work drains.
+    # The result must be the same as on an idle device.
+    w = wl.make_workload("busy", "relu", 2304, 4, 32, 0.3, seed=41, h0_std=0.3)
+    side, main = torch.cuda.Stream(), torch.cuda.Stream()
+    a = torch.randn((4096, 4096), device="cuda")
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, lanes_per_row=64) as rnn:
+        assert rnn.info()["grid"] == 256
+        x, h0 = _dev(w.x), _dev(w.h0)
+        want = rnn.forward(x, h0).cpu().numpy()
+        torch.cuda.synchronize()
+        outs = []
+        for i in range(4):
+            with torch.cuda.stream(side):
+                b = a
+                for _ in range(6):
+                    b = torch.mm(b, a) * 1e-3     # a few milliseconds of work that fills the device
+            with torch.cuda.stream(main):
+                outs.append(rnn.forward(x, h0))
+        torch.cuda.synchronize()
+        assert rnn.check() == binding.SPRNN_OK
+        for o in outs:
+            assert np.array_equal(o.cpu().numpy(), want)
+    assert_parity(want, oracle_run(w)[0])
+
+
 # ------------------------------------------------------------------ error paths that need a device
 def test_one_xcd_mode_repeated_calls_and_refusal():
     # many launches on one handle (the placement counters alternate between two sets and are cleared by the launch in
