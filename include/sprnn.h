@@ -13,6 +13,11 @@
  * in the process; streams and device pointers of one runtime are invalid in another.  The Python binding
  * enforces this (it imports torch before loading the library and refuses to run with two runtimes mapped).
  *
+ * Threads: different handles may be used from different host threads at the same time (the library's own per-device
+ * state is guarded); calls on ONE handle must not overlap, on the host (each call advances the handle's position in
+ * its exchange ring) or on the device (two launches of one handle share that ring: give them to one stream, or order
+ * the streams yourself).
+ *
  * What is computed (paper, Section 3.1, Eq. 2):  h_t = g(U_r h_{t-1} + b'_t)  for t = 1..T, with
  * U_r the pruned recurrent weight matrix held in on-chip storage for the whole sequence
  * (Section 3.3) and b'_t = W x_t + b computed by the caller ahead of time (Eq. 1 -> Eq. 2).
