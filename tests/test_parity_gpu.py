@@ -447,6 +447,46 @@ def test_a_full_size_layer_beside_other_work_on_another_stream():
     assert_parity(want, oracle_run(w)[0])
 
 
+def test_two_host_threads_with_a_handle_each():
+    # different handles from different host threads at the same time, each thread on a stream of its own: the
+    # library's per-device launch order is the only state they share
+    import threading
+    ws = [wl.make_workload("t%d" % i, "relu", 2048, 4, 16, 0.2, seed=50 + i, h0_std=0.3) for i in range(2)]
+    rnns = [binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) for w in ws]
+    try:
+        ins = [(_dev(w.x), _dev(w.h0)) for w in ws]
+        wants = [r.forward(x, h0).cpu().numpy() for r, (x, h0) in zip(rnns, ins)]
+        torch.cuda.synchronize()
+        results, errors = [[], []], []
+
+        def work(i):
+            try:
+                st = torch.cuda.Stream()
+                with torch.cuda.stream(st):
+                    for _ in range(25):
+                        results[i].append(rnns[i].forward(*ins[i]))
+                st.synchronize()
+            except Exception as e:  # noqa: BLE001  (reported by the asserting thread)
+                errors.append(e)
+
+        threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        assert not errors, errors
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert rnns[i].check() == binding.SPRNN_OK
+            assert len(results[i]) == 25
+            for o in results[i]:
+                assert np.array_equal(o.cpu().numpy(), wants[i])
+            assert_parity(wants[i], oracle_run(ws[i])[0])
+    finally:
+        for r in rnns:
+            r.close()
+
+
 # ------------------------------------------------------------------ error paths that need a device
 def test_one_xcd_mode_repeated_calls_and_refusal():
     # many launches on one handle (the placement counters alternate between two sets and are cleared by the launch in
