@@ -94,7 +94,7 @@ const void* persistent_kernel_for(int batch, int template_words, int cell, bool 
 const void* persistent_timeline_kernel_for(int batch, int template_words, bool lstm);        // forward pass with the phase timeline
 const void* persistent_overlap_kernel_for(int batch, int template_words, bool timeline);     // vanilla forward with the copy of h consumed in two parts (batch <= 4; timeline: batch 4)
 const void* persistent_short_kernel_for(int batch, int template_words, int cell);              // forward pass of a layer whose h takes at most three copy rounds
-const void* persistent_half_kernel_for(int batch, int template_words);                       // vanilla forward with h exchanged as binary16 (batch 4)
+const void* persistent_half_kernel_for(int batch, int template_words);                       // vanilla forward with h exchanged as binary16 (batch 4, 8)
 const void* persistent_narrow_kernel_for(int batch, int template_words);                     // vanilla forward, batch 4, 4-byte gathers (ablation)
 const void* persistent_backward_kernel_for(int batch, int template_words, int cell);         // kCellBackward, kCellBackwardGrad
 const void* persistent_gated_backward_kernel_for(int batch, int template_words, int cell);   // SPRNN_CELL_*_BACKWARD, kCell{Lstm,Gru}BackwardGrad

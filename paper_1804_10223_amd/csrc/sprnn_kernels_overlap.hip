@@ -1,6 +1,6 @@
 // Device code of libsprnn: the persistent kernel's instantiations that consume the copy of h in two parts
 // (options.overlap): forward pass of the vanilla cells at batch 1, 2 and 4; with the phase timeline at batch 4; and
-// the instantiations with binary16 activations (options.activations): vanilla forward pass, batch 4.
+// the instantiations with binary16 activations (options.activations): vanilla forward pass, batch 4 and 8.
 #include "sprnn_persistent.h"
 
 namespace sprnn {
@@ -16,7 +16,7 @@ const void* persistent_overlap_kernel_for(int batch, int template_words, bool ti
 }
 
 const void* persistent_half_kernel_for(int batch, int template_words) {
-  return batch == 4 ? pick_nw<4, 11, false>(template_words) : nullptr;
+  return batch == 4 ? pick_nw<4, 11, false>(template_words) : (batch == 8 ? pick_nw<8, 11, false>(template_words) : nullptr);
 }
 
 }  // namespace sprnn

@@ -140,7 +140,7 @@ static int choose_mapping(int hidden, int batch, int cell, const std::vector<int
   const int activations = opt ? opt->activations : 0;
   if (activations < 0 || activations > 2) return SPRNN_ERR_INVALID;
   m->half = activations == 2 ? 1 : 0;
-  if (m->half && (batch != 4 || cell > SPRNN_ACT_IDENTITY)) return SPRNN_ERR_UNSUPPORTED;
+  if (m->half && ((batch != 4 && batch != 8) || cell > SPRNN_ACT_IDENTITY)) return SPRNN_ERR_UNSUPPORTED;
   // binary16 activations: a column of h is batch x 2 bytes, which is the geometry of binary32 activations at half the batch
   const int lb = m->half ? batch / 2 : batch;
   m->layout_batch = lb;

@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "sprnn_device.h"
 
@@ -267,37 +268,40 @@ __device__ __forceinline__ void mac_words(float (&acc)[B], const uint32_t* off, 
 // binary16 activations (batch 4): a column of h is four binary16 values, one 8-byte read; products and sums stay
 // binary32 (the conversion is exact, and the compiler folds it into a mixed-precision multiply-add).
 typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wint-to-pointer-cast"   // (the host pass sees a 32-bit LDS address become one of its pointers; it never runs this)
-template <int N>
-__device__ __forceinline__ void mac_words_half(float (&acc)[4], const uint32_t* off, const float* wv) {
-  halfx4 c[N];
+template <int N, int B>
+__device__ __forceinline__ void mac_words_half(float (&acc)[B], const uint32_t* off, const float* wv) {
+  static_assert(B == 4 || B == 8, "a column of binary16 activations is one 8- or 16-byte read");
+  using column = typename std::conditional<B == 4, halfx4, halfx8>::type;
+  column c[N];
 #pragma unroll
-  for (int j = 0; j < N; ++j) c[j] = *SPRNN_LDS_PTR(halfx4, off[j]);
+  for (int j = 0; j < N; ++j) c[j] = *SPRNN_LDS_PTR(column, off[j]);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int j = 0; j < N; ++j) {
 #pragma unroll
-    for (int b = 0; b < 4; ++b) acc[b] = fmaf(wv[j], (float)c[j][b], acc[b]);
+    for (int b = 0; b < B; ++b) acc[b] = fmaf(wv[j], (float)c[j][b], acc[b]);
   }
 }
 #pragma clang diagnostic pop
-template <int NW>
-__device__ __forceinline__ void operate_half(float (&acc)[4], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w) {
+template <int NW, int B>
+__device__ __forceinline__ void operate_half(float (&acc)[B], const uint32_t (&w_off)[NW], const float (&w_val)[NW], int n_w) {
 #pragma unroll
   for (int k = 0; k < NW; k += 8) {
     if (k + 8 <= n_w) {
-      mac_words_half<8>(acc, &w_off[k], &w_val[k]);
+      mac_words_half<8, B>(acc, &w_off[k], &w_val[k]);
     } else if (k < n_w) {
       const int rem = n_w - k;
       if (rem >= 4) {
-        mac_words_half<4>(acc, &w_off[k], &w_val[k]);
-        if (rem == 7) mac_words_half<3>(acc, &w_off[k + 4], &w_val[k + 4]);
-        else if (rem == 6) mac_words_half<2>(acc, &w_off[k + 4], &w_val[k + 4]);
-        else if (rem == 5) mac_words_half<1>(acc, &w_off[k + 4], &w_val[k + 4]);
-      } else if (rem == 3) mac_words_half<3>(acc, &w_off[k], &w_val[k]);
-      else if (rem == 2) mac_words_half<2>(acc, &w_off[k], &w_val[k]);
-      else mac_words_half<1>(acc, &w_off[k], &w_val[k]);
+        mac_words_half<4, B>(acc, &w_off[k], &w_val[k]);
+        if (rem == 7) mac_words_half<3, B>(acc, &w_off[k + 4], &w_val[k + 4]);
+        else if (rem == 6) mac_words_half<2, B>(acc, &w_off[k + 4], &w_val[k + 4]);
+        else if (rem == 5) mac_words_half<1, B>(acc, &w_off[k + 4], &w_val[k + 4]);
+      } else if (rem == 3) mac_words_half<3, B>(acc, &w_off[k], &w_val[k]);
+      else if (rem == 2) mac_words_half<2, B>(acc, &w_off[k], &w_val[k]);
+      else mac_words_half<1, B>(acc, &w_off[k], &w_val[k]);
     }
   }
 }
@@ -602,8 +606,8 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELLX == 4 || CELLX == 6 || CELL
   // Two-part copy (vanilla forward pass, one plane): the first p.seg_rounds rounds of the copy bring the low columns of
   // h, and the first k_early words of every lane of this wavefront read only those.
   constexpr bool kTwoPart = CELL == 10;
-  constexpr bool kHalf = CELL == 11;   // h travels and sits in LDS as binary16: [H][B] halves, 8 bytes per column at batch 4
-  static_assert(!kHalf || B == 4, "binary16 activations are built for batch 4");
+  constexpr bool kHalf = CELL == 11;   // h travels and sits in LDS as binary16: [H][B] halves, 8 bytes per column at batch 4, 16 at batch 8
+  static_assert(!kHalf || B == 4 || B == 8, "binary16 activations are built for batch 4 and 8");
   const int k_early = kTwoPart ? __builtin_amdgcn_readfirstlane(p.wave_early[wg * (block >> 6) + wave]) : 0;
   uint32_t w_off[NW];
   float w_val[NW];
@@ -935,7 +939,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELLX == 4 || CELLX == 6 || CELL
     } else if constexpr (kTwoPart) {
       operate_span<B, NW>(acc, w_off, w_val, k_done, n_w, plane_bytes);
     } else if constexpr (kHalf) {
-      operate_half<NW>(acc, w_off, w_val, n_w);
+      operate_half<NW, B>(acc, w_off, w_val, n_w);
     } else {
       // Groups of eight words for batch 4 in the one-row-per-unit layouts (eight gathers in flight, half as many
       // waits for the LDS: 2.5 % on the headline shape); four otherwise: eight would spill at batch 8, measured no
@@ -1058,28 +1062,55 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELLX == 4 || CELLX == 6 || CELL
     if constexpr (!LBWD) {   // (the LSTM's backward pass has published its four elements above)
     jitter_pause(p.jitter, wave_id, g, 3);
     if constexpr (kHalf) {
-      // the four owner lanes of a row are one aligned quad, and lane q of it holds sample sample_of_lane(q) = 0, 2, 1, 3:
-      // the owner of sample 0 collects the four rounded values in sample order
       const int mine = (int)half_bits_for_exchange(hval);
-      const int s2 = __builtin_amdgcn_update_dpp(0, mine, 0x55, 0xf, 0xf, false);   // quad_perm: lane 1 of the quad (sample 2)
-      const int s1 = __builtin_amdgcn_update_dpp(0, mine, 0xAA, 0xf, 0xf, false);   // lane 2 (sample 1)
-      const int s3 = __builtin_amdgcn_update_dpp(0, mine, 0xFF, 0xf, 0xf, false);   // lane 3 (sample 3)
-      i32x2 pair;
-      pair.x = mine | (s1 << 16);
-      pair.y = s2 | (s3 << 16);
-      if (solo) {
-        if (ring_voff != kOutOfRange) *reinterpret_cast<i32x2*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = pair;
-      } else {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        i32x2 mark;
-        mark.x = (int)kSentinelHalfPair;
-        mark.y = (int)kSentinelHalfPair;
-        if (p.one_xcd) {
-          __builtin_amdgcn_raw_buffer_store_b64(pair, ring, ring_voff, slot_byte, 0);
-          if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b64(mark, ring, ring_voff, rearm_byte, 0);
+      if constexpr (B == 4) {
+        // the four owner lanes of a row are one aligned quad, and lane q of it holds sample sample_of_lane(q) = 0, 2, 1, 3:
+        // the owner of sample 0 collects the four rounded values in sample order
+        const int s2 = __builtin_amdgcn_update_dpp(0, mine, 0x55, 0xf, 0xf, false);   // quad_perm: lane 1 of the quad (sample 2)
+        const int s1 = __builtin_amdgcn_update_dpp(0, mine, 0xAA, 0xf, 0xf, false);   // lane 2 (sample 1)
+        const int s3 = __builtin_amdgcn_update_dpp(0, mine, 0xFF, 0xf, 0xf, false);   // lane 3 (sample 3)
+        i32x2 pair;
+        pair.x = mine | (s1 << 16);
+        pair.y = s2 | (s3 << 16);
+        if (solo) {
+          if (ring_voff != kOutOfRange) *reinterpret_cast<i32x2*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = pair;
         } else {
-          __builtin_amdgcn_raw_buffer_store_b64(pair, ring, ring_voff, slot_byte, kAuxCoherent);
-          if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b64(mark, ring, ring_voff, rearm_byte, kAuxCoherent);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          i32x2 mark;
+          mark.x = (int)kSentinelHalfPair;
+          mark.y = (int)kSentinelHalfPair;
+          if (p.one_xcd) {
+            __builtin_amdgcn_raw_buffer_store_b64(pair, ring, ring_voff, slot_byte, 0);
+            if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b64(mark, ring, ring_voff, rearm_byte, 0);
+          } else {
+            __builtin_amdgcn_raw_buffer_store_b64(pair, ring, ring_voff, slot_byte, kAuxCoherent);
+            if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b64(mark, ring, ring_voff, rearm_byte, kAuxCoherent);
+          }
+        }
+      } else {
+        // the eight owner lanes of a row are two aligned quads of one row of 16 lanes; lane q holds sample
+        // sample_of_lane(q) = 0, 4, 2, 6 | 1, 5, 3, 7.  A lane of the first quad pairs its value with the one four lanes
+        // up (samples s and s + 1), and the owner of sample 0 collects the four pairs in sample order.
+        const int up = __builtin_amdgcn_update_dpp(0, mine, 0x104, 0xf, 0xf, false);   // row_shl:4: the value of lane + 4
+        const int both = mine | (up << 16);
+        i32x4 column;
+        column.x = both;                                                                // samples 0, 1 (lanes 0 and 4)
+        column.y = __builtin_amdgcn_update_dpp(0, both, 0xAA, 0xf, 0xf, false);          // lane 2 of the quad: samples 2, 3
+        column.z = __builtin_amdgcn_update_dpp(0, both, 0x55, 0xf, 0xf, false);          // lane 1: samples 4, 5
+        column.w = __builtin_amdgcn_update_dpp(0, both, 0xFF, 0xf, 0xf, false);          // lane 3: samples 6, 7
+        if (solo) {
+          if (ring_voff != kOutOfRange) *reinterpret_cast<i32x4*>(lds + (cur ^ 1) * p.lds_h_bytes + ring_voff) = column;
+        } else {
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          i32x4 mark;
+          mark.x = mark.y = mark.z = mark.w = (int)kSentinelHalfPair;
+          if (p.one_xcd) {
+            __builtin_amdgcn_raw_buffer_store_b128(column, ring, ring_voff, slot_byte, 0);
+            if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b128(mark, ring, ring_voff, rearm_byte, 0);
+          } else {
+            __builtin_amdgcn_raw_buffer_store_b128(column, ring, ring_voff, slot_byte, kAuxCoherent);
+            if (p.sync == SPRNN_SYNC_TAGGED) __builtin_amdgcn_raw_buffer_store_b128(mark, ring, ring_voff, rearm_byte, kAuxCoherent);
+          }
         }
       }
     } else if (solo) {

@@ -200,15 +200,16 @@ def activations(torch, wl, reps):
     """binary32 against binary16 activations (options.activations): half the exchange and LDS traffic, and the worst
     difference between the two outputs as a fraction of max|h| per timestep."""
     import numpy as np
-    print("## Activations exchanged as binary32 or binary16 (cf. Section 6, future work): batch 4, T 256\n")
-    print("| hidden | density | binary32 us/step | binary16 us/step | LDS for h | worst step difference / max abs h |")
-    print("|---|---|---|---|---|---|")
-    for (H, dens) in [(1152, 0.10), (2304, 0.30), (3072, 0.10), (4096, 0.10), (5120, 0.10), (7168, 0.026), (11520, 0.01)]:
-        w = wl.make_workload("sweep", "relu", H, 4, 256, dens, seed=0)
+    print("## Activations exchanged as binary32 or binary16 (cf. Section 6, future work): batch 4 and 8, T 256\n")
+    print("| hidden | batch | density | binary32 us/step | binary16 us/step | LDS for h | worst step difference / max abs h |")
+    print("|---|---|---|---|---|---|---|")
+    for (H, B, dens) in [(1152, 4, 0.10), (2304, 4, 0.30), (3072, 4, 0.10), (4096, 4, 0.10), (5120, 4, 0.10), (7168, 4, 0.026), (11520, 4, 0.01),
+                         (1024, 8, 0.20), (1760, 8, 0.12), (2560, 8, 0.12), (3072, 8, 0.12), (5120, 8, 0.05)]:
+        w = wl.make_workload("sweep", "relu", H, B, 256, dens, seed=0)
         a, ia, oa = measure(torch, w, reps, want_output=True)
         b, ib, ob = measure(torch, w, reps, want_output=True, activations=2)
         diff = max(float(np.abs(oa[t] - ob[t]).max() / np.abs(oa[t]).max()) for t in range(w.steps))
-        print("| %d | %.1f %% | %.2f | %.2f | %d KB%s / %d KB | %.1e |" % (H, 100 * dens, a, b, ia["lds_bytes"] // 1024,
+        print("| %d | %d | %.1f %% | %.2f | %.2f | %d KB%s / %d KB | %.1e |" % (H, B, 100 * dens, a, b, ia["lds_bytes"] // 1024,
               " (compacted)" if ia["compact"] else "", ib["lds_bytes"] // 1024, diff), flush=True)
     print()
 

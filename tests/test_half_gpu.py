@@ -50,14 +50,25 @@ CASES = [
     ("relu", 640, 10, 0.5, "fixed", {"lanes_per_row": 8, "bank_aware": 2}),       # 40 words per lane: the 48-slot kernel
     ("tanh", 4608, 6, 0.02, "fixed", {}),                                # 36 KB of binary16 h: more than two copy rounds
 ]
+# batch 8: a column is eight binary16 values, one 16-byte read; the eight owner lanes of a row pack it
+CASES_8 = [
+    ("relu", 96, 9, 0.3, "fixed", {}),                                   # one workgroup
+    ("tanh", 640, 12, 0.3, "fixed", {"waves": 2}),
+    ("identity", 300, 8, 0.2, "poisson", {"jitter": 3}),
+    ("relu", 500, 10, 0.2, "fixed", {"sync": "barrier"}),
+    ("relu", 500, 10, 0.2, "fixed", {"xcd": "one"}),
+    ("tanh", 333, 7, 0.25, "poisson", {"balance": 1, "lanes_per_row": 8}),
+    ("relu", 1760, 12, 0.12, "fixed", {"lanes_per_row": 32, "jitter": 5}),
+    ("tanh", 3072, 6, 0.05, "fixed", {}),                                # 48 KB of binary16 h
+]
 
 
-@pytest.mark.parametrize("cell,H,T,dens,rownnz,opts", CASES)
-def test_binary16_activations_match_both_oracles(cell, H, T, dens, rownnz, opts):
-    w = wl.make_workload("half", cell, H, 4, T, dens, seed=H + T, row_nnz=rownnz, h0_std=0.5)
-    plain = oracle.rnn_forward(H, 4, cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=8)
+@pytest.mark.parametrize("B,cell,H,T,dens,rownnz,opts", [(4,) + c for c in CASES] + [(8,) + c for c in CASES_8])
+def test_binary16_activations_match_both_oracles(B, cell, H, T, dens, rownnz, opts):
+    w = wl.make_workload("half", cell, H, B, T, dens, seed=H + T, row_nnz=rownnz, h0_std=0.5)
+    plain = oracle.rnn_forward(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, w.x, w.h0, threads=8)
     rounded = _stepwise_rounded_oracle(w)
-    with binding.SparseRNN(H, 4, cell, w.row_ptr, w.col_idx, w.val_bits, activations="binary16", **opts) as rnn:
+    with binding.SparseRNN(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, activations="binary16", **opts) as rnn:
         info = rnn.info()
         got = rnn.forward(_dev(w.x), _dev(w.h0)).cpu().numpy()
         assert rnn.check() == binding.SPRNN_OK
@@ -75,20 +86,20 @@ def test_binary16_activations_match_both_oracles(cell, H, T, dens, rownnz, opts)
         if t < 3:   # (the flips add up over the steps of a recurrence: the tight comparison is for the first ones)
             assert np.median(diff) <= 1e-5 * scale and np.quantile(diff, 0.99) <= 2e-4 * scale, (t, np.median(diff) / scale, np.quantile(diff, 0.99) / scale)
         assert diff.max() <= REL_TOL * scale, t
-    print("case", cell, H, T, dens, rownnz, opts, {k: info[k] for k in ("grid", "block", "lanes_per_row", "lds_bytes")},
+    print("case batch", B, cell, H, T, dens, rownnz, opts, {k: info[k] for k in ("grid", "block", "lanes_per_row", "lds_bytes")},
           "worst step against the binary32 oracle: %.2e of max|h|" % worst, flush=True)
 
 
-@pytest.mark.parametrize("H", [7, 1000, 4099, 16384])
-def test_permutation_of_binary16_values_is_bit_exact(H):
+@pytest.mark.parametrize("H,B", [(7, 4), (1000, 4), (4099, 4), (16384, 4), (7, 8), (1000, 8), (4099, 8), (9999, 8)])   # (the largest h that fits in LDS)
+def test_permutation_of_binary16_values_is_bit_exact(H, B):
     rng = np.random.default_rng(H)
     perm = rng.permutation(H).astype(np.int32)
     row_ptr = np.arange(H + 1, dtype=np.int32)
     ones = np.full(H, 0x3C00, dtype=np.uint16)
     T = 5
-    x = np.zeros((T, 4, H), dtype=np.float32)
-    h0 = (rng.integers(1, 2048, (4, H)) / 64.0).astype(np.float32)      # exactly representable in binary16, never zero
-    with binding.SparseRNN(H, 4, "relu", row_ptr, perm, ones, activations=2) as rnn:
+    x = np.zeros((T, B, H), dtype=np.float32)
+    h0 = (rng.integers(1, 2048, (B, H)) / 64.0).astype(np.float32)      # exactly representable in binary16, never zero
+    with binding.SparseRNN(H, B, "relu", row_ptr, perm, ones, activations=2) as rnn:
         h = rnn.forward(_dev(x), _dev(h0)).cpu().numpy()
         assert rnn.check() == binding.SPRNN_OK
     cur = h0

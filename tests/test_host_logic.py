@@ -70,7 +70,7 @@ def test_struct_layouts_match_header_sizes():
 
 def _unpack(words, lane_row, lane_words, info, hidden, batch):
     """Rows recovered from the packed image: {row: sorted [(col, bits)]} ignoring zero-valued filler."""
-    stride = 4 * min(batch, 4) // (2 if info.get("activations") == 2 else 1)
+    stride = 4 * min(batch // 2 if info.get("activations") == 2 else batch, 4)   # bytes of a column in one plane
     out = {}
     g, nw, blk = words.shape
     for wg in range(g):
@@ -104,6 +104,7 @@ def _unpack(words, lane_row, lane_words, info, hidden, batch):
     ("tanh", 1000, 2, 0.4, "poisson", {"overlap": 2, "waves": 2}),
     ("relu", 1500, 1, 0.3, "poisson", {"overlap": 2, "waves": 1, "bank_aware": 2}),
     ("relu", 300, 4, 0.3, "poisson", {"activations": 2}),
+    ("tanh", 700, 8, 0.2, "poisson", {"activations": 2}),
     ("tanh", 2305, 4, 0.1, "fixed", {"activations": 2, "bank_aware": 2}),
 ])
 def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
@@ -215,7 +216,12 @@ def test_binary16_activations_halve_the_exchange_and_are_refused_where_not_built
     assert binding.pack_host(11520, 4, "relu", big.row_ptr, big.col_idx, big.val_bits)[3]["compact"] == 1
     info = binding.pack_host(11520, 4, "relu", big.row_ptr, big.col_idx, big.val_bits, activations=2)[3]
     assert info["compact"] == 0 and info["lds_bytes"] == 11520 * 8
-    for cell, H, B, opts in (("relu", 256, 2, {}), ("relu", 256, 8, {}), ("lstm", 128, 4, {}), ("gru", 128, 4, {}),
+    # batch 8: a column of binary16 activations is the 16 bytes that a column of binary32 ones is at batch 4, in one plane
+    eight = wl.make_workload("b8", "relu", 1760, 8, 1, 0.12, seed=0)
+    full8 = binding.pack_host(1760, 8, "relu", eight.row_ptr, eight.col_idx, eight.val_bits)[3]
+    half8 = binding.pack_host(1760, 8, "relu", eight.row_ptr, eight.col_idx, eight.val_bits, activations=2)[3]
+    assert full8["lds_bytes"] == 1760 * 32 and half8["lds_bytes"] == 1760 * 16 and half8["ring_bytes"] * 2 == full8["ring_bytes"]
+    for cell, H, B, opts in (("relu", 256, 2, {}), ("relu", 256, 1, {}), ("lstm", 128, 4, {}), ("gru", 128, 4, {}),
                              ("relu", 2304, 4, {"layout": "lane_pool"}), ("relu", 4000, 4, {"compact": 1}), ("relu", 500, 4, {"gather": "narrow"}),
                              ("relu", 2304, 4, {"overlap": 2}), ("relu", 500, 4, {"timeline": 1})):
         v = wl.make_workload("h", cell, H, B, 1, 0.05 if H > 3000 else 0.2, seed=1)
