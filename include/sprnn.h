@@ -114,7 +114,7 @@ typedef struct sprnn_options_s {
                         parts; a row's nonzeros of the first part sit in its lanes' leading slots and are worked
                         through while the second part is still arriving                                    */
   int activations;   /* precision in which h travels between workgroups and sits in LDS (vanilla cells, forward pass, batch 4
-                        and 8, one lane group per row, no column compaction): 0 auto = 1 = binary32 (the default everywhere);
+                        and 8, one lane group per row): 0 auto = 1 = binary32 (the default everywhere);
                         2 = binary16 (Section 6 names lower-precision activations as future work): every h_t is rounded
                         to nearest once before it is published, sums, b' and h_out stay binary32, so h_out[t] is the
                         unrounded value while step t + 1 reads the rounded one.  Half the exchange and LDS traffic;

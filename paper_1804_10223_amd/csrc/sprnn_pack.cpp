@@ -692,10 +692,6 @@ int pack(int hidden, int batch, int cell, const int32_t* row_ptr, const int32_t*
   // (scattered 16-byte reads cost more per byte than the contiguous copy: measured break-even near one half)
   bool compact = m.compact == 1 || (m.compact == 0 && (!identity_fits || need_max * 2 < (size_t)chunks_per_plane));
   if (m.grid == 1) compact = false;          // a single workgroup produces all of h itself
-  if (m.half && compact) {                   // (the compacted copy is built for binary32 elements)
-    if (m.compact == 1 || !identity_fits) return SPRNN_ERR_UNSUPPORTED;
-    compact = false;
-  }
   if (!compact && !identity_fits) return SPRNN_ERR_CAPACITY;
   m.compact = compact ? 1 : 0;
   int64_t lds_plane;                          // bytes of one plane of the LDS copy (bounds the packed offsets)

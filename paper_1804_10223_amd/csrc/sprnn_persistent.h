@@ -700,6 +700,16 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELLX == 4 || CELLX == 6 || CELL
     for (int c = 0; c < chunk_rounds; ++c) {
       const int src = copy_src(c), dst = copy_dst(c, src);
       if (dst < 0) continue;
+      if constexpr (kHalf) {                       // eight binary16 elements of the [H][B] slot layout
+        halfx8 v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int f = (src >> 1) + i, j = f / B, b = f % B;
+          v[i] = (_Float16)((p.h0 && j < H) ? p.h0[(size_t)b * H + j] : 0.0f);
+        }
+        *reinterpret_cast<halfx8*>(lds + dst) = v;
+        continue;
+      }
       f32x4 v;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -890,7 +900,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELLX == 4 || CELLX == 6 || CELL
             int to[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) to[c] = copy_dst(c, fsrc[c]);
-            failed = !copy_chunks<4, true>(ring, slot_byte, fsrc, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            failed = !copy_chunks<4, true, kHalf>(ring, slot_byte, fsrc, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
           }
         } else if (!compacted) {
           // a large h or a small workgroup: eight loads per lane in flight, as many rounds as it takes
@@ -912,7 +922,7 @@ __global__ __launch_bounds__(NW >= 48 ? 256 : ((CELLX == 4 || CELLX == 6 || CELL
             for (int c = 0; c < 8; ++c) to[c] = copy_dst(r0 + c, off[c]);
 #pragma unroll
             for (int c = 0; c < 8; ++c) next[c] = (r0 + 8 < chunk_rounds) ? copy_src(r0 + 8 + c) : kOutOfRange;
-            failed = !copy_chunks<8, true>(ring, slot_byte, off, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
+            failed = !copy_chunks<8, true, kHalf>(ring, slot_byte, off, to, dst, p.spin_limit, p.ctrl + kCtrlStatus, repolls);
 #pragma unroll
             for (int c = 0; c < 8; ++c) off[c] = next[c];
           }

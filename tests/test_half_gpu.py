@@ -49,6 +49,8 @@ CASES = [
     ("relu", 1152, 20, 0.1, "fixed", {"lanes_per_row": 64, "jitter": 5}),
     ("relu", 640, 10, 0.5, "fixed", {"lanes_per_row": 8, "bank_aware": 2}),       # 40 words per lane: the 48-slot kernel
     ("tanh", 4608, 6, 0.02, "fixed", {}),                                # 36 KB of binary16 h: more than two copy rounds
+    ("relu", 3000, 6, 0.01, "poisson", {"compact": 1}),                  # column compaction: two columns per 16-byte piece
+    ("tanh", 2000, 6, 0.02, "fixed", {"compact": 1, "grid": 125, "jitter": 2}),
 ]
 # batch 8: a column is eight binary16 values, one 16-byte read; the eight owner lanes of a row pack it
 CASES_8 = [
@@ -60,6 +62,8 @@ CASES_8 = [
     ("tanh", 333, 7, 0.25, "poisson", {"balance": 1, "lanes_per_row": 8}),
     ("relu", 1760, 12, 0.12, "fixed", {"lanes_per_row": 32, "jitter": 5}),
     ("tanh", 3072, 6, 0.05, "fixed", {}),                                # 48 KB of binary16 h
+    ("relu", 2000, 6, 0.02, "fixed", {"compact": 1, "grid": 100}),       # column compaction: one column per 16-byte piece
+    ("relu", 11520, 4, 0.01, "fixed", {}),                               # 180 KB of binary16 h: runs compacted
 ]
 
 

@@ -221,8 +221,13 @@ def test_binary16_activations_halve_the_exchange_and_are_refused_where_not_built
     full8 = binding.pack_host(1760, 8, "relu", eight.row_ptr, eight.col_idx, eight.val_bits)[3]
     half8 = binding.pack_host(1760, 8, "relu", eight.row_ptr, eight.col_idx, eight.val_bits, activations=2)[3]
     assert full8["lds_bytes"] == 1760 * 32 and half8["lds_bytes"] == 1760 * 16 and half8["ring_bytes"] * 2 == full8["ring_bytes"]
+    # with column compaction on top, layers fit whose binary16 h alone would not: 11520 x batch 8 at 1 % (180 KB of h)
+    huge = wl.make_workload("huge8", "relu", 11520, 8, 1, 0.01, seed=0)
+    full = binding.pack_host(11520, 8, "relu", huge.row_ptr, huge.col_idx, huge.val_bits)[3]
+    info = binding.pack_host(11520, 8, "relu", huge.row_ptr, huge.col_idx, huge.val_bits, activations=2)[3]
+    assert full["compact"] == 1 and info["compact"] == 1 and info["lds_bytes"] * 2 <= full["lds_bytes"] + 32 * 1024
     for cell, H, B, opts in (("relu", 256, 2, {}), ("relu", 256, 1, {}), ("lstm", 128, 4, {}), ("gru", 128, 4, {}),
-                             ("relu", 2304, 4, {"layout": "lane_pool"}), ("relu", 4000, 4, {"compact": 1}), ("relu", 500, 4, {"gather": "narrow"}),
+                             ("relu", 2304, 4, {"layout": "lane_pool"}), ("relu", 500, 4, {"gather": "narrow"}),
                              ("relu", 2304, 4, {"overlap": 2}), ("relu", 500, 4, {"timeline": 1})):
         v = wl.make_workload("h", cell, H, B, 1, 0.05 if H > 3000 else 0.2, seed=1)
         with pytest.raises(binding.SprnnError) as e:
