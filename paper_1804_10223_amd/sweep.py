@@ -2,7 +2,7 @@
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
     python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,activations,cells,training,casestudy] [--reps 8]
-    python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged|pool|two_part
+    python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged|pool|two_part|spread32|one_xcd32
                                                                   (one variant alone in the process, for counter passes)
 
 Mirrors the structure of the paper's evaluation on this library's own kernels (its comparison systems are
@@ -140,7 +140,9 @@ def ablation(torch, wl, reps):
 
 
 # further variants that --what rung can run alone: the lane-pool layout and the two-part copy
-VARIANTS = dict(RUNGS, pool=dict(layout=2), two_part=dict(overlap=2))
+VARIANTS = dict(RUNGS, pool=dict(layout=2), two_part=dict(overlap=2),
+                # 32 workgroups (cfg2 fits them) spread over all XCDs or confined to one
+                spread32=dict(grid=32, xcd="spread", poll_delay=1), one_xcd32=dict(grid=32, xcd="one", poll_delay=1))
 
 
 def one_rung(torch, wl, reps, config, rung):
@@ -301,7 +303,7 @@ def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,activations,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
-    ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged | pool | two_part")
+    ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged | pool | two_part | spread32 | one_xcd32")
     ap.add_argument("--config", default="cfg2", help="with --what rung: the configuration")
     args = ap.parse_args()
     import torch
