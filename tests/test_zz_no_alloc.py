@@ -82,3 +82,36 @@ def test_noalloc_refuses_a_ring_beyond_the_static_array():
         assert e.value.code == binding.SPRNN_ERR_CAPACITY
         rnn.forward(x, None, out)        # the handle itself still works
         assert rnn.check() == binding.SPRNN_OK
+
+
+@pytest.mark.parametrize("H,dens,opts", [(2304, 0.05, {}), (1152, 0.1, {"xcd": "one", "grid": 32})])
+def test_noalloc_call_captured_in_a_graph_and_replayed(H, dens, opts):
+    # What the entry point is for: a caller under stream capture.  The captured call (a fill kernel that re-marks the
+    # ring, then the persistent kernel as an ordinary launch) is replayed several times with new inputs, with eager work
+    # of the same handle and synchronisations in between; every replay must equal the eager result for that input.
+    w = wl.make_workload("graph", "tanh", H, 4, 24, dens, seed=17, h0_std=0.3)
+    rng = np.random.default_rng(3)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, **opts) as rnn:
+        x, h0 = _dev(w.x), _dev(w.h0)
+        out = torch.empty_like(x)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            rnn.forward_noalloc(x, h0, out)            # warm-up outside the capture
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            rnn.forward_noalloc(x, h0, out)
+        for i in range(4):
+            new_x = torch.from_numpy((rng.standard_normal(w.x.shape) * 0.5).astype(np.float32)).cuda()
+            x.copy_(new_x)
+            out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            eager = rnn.forward(new_x, h0).cpu().numpy()            # the handle's own ring, between two replays
+            assert rnn.check() == binding.SPRNN_OK
+            assert np.array_equal(got.view(np.uint32), eager.view(np.uint32)), "replay %d" % i
+        want = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, new_x.cpu().numpy(), w.h0, threads=8)
+        for t in range(w.steps):
+            assert np.abs(got[t] - want[t]).max() <= REL_TOL * np.abs(want[t]).max() + 1e-30, t
