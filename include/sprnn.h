@@ -197,6 +197,9 @@ int sprnn_create_ex(sprnn_handle_t* out, int hidden, int batch, int activation, 
  *
  * Only enqueues work on `stream` and returns.  One forward per handle at a time, in stream order;
  * calls on different handles are independent.  T = 0 is a no-op.  All activations must be finite.
+ * Not under stream capture (SPRNN_ERR_UNSUPPORTED): every call on a handle's own exchange ring, this one and all
+ * the others except sprnn_forward_noalloc, carries the handle's position in that ring in its launch and moves it on,
+ * so a replayed launch would not find the ring where it expects it.  sprnn_forward_noalloc may be captured.
  */
 int sprnn_forward(sprnn_handle_t h, int T, const float* x, const float* h0, float* h_out, void* stream);
 

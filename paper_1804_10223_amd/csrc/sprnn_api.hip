@@ -530,6 +530,14 @@ static int forward_persistent(sprnn_handle_t h, int T, const float* x, const flo
   if (T == 0) return SPRNN_OK;
   DeviceGuard guard(h->device);
   if (!guard.ok) return SPRNN_ERR_HIP;
+  if (!ex.shared_exchange) {
+    // A launch on the handle's own ring carries the handle's position in that ring in its arguments and moves it on: a
+    // captured launch would be replayed with a position the ring has left behind, and would take the last replay's
+    // values for its own.  Under capture only the entry point that starts every call from a fresh ring may be used.
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)stream, &capturing) != hipSuccess) { (void)hipGetLastError(); capturing = hipStreamCaptureStatusNone; }
+    if (capturing != hipStreamCaptureStatusNone) return SPRNN_ERR_UNSUPPORTED;
+  }
   const Mapping& m = h->map;
   // The kernel addresses x and the outputs with 32-bit byte offsets from the start of the call, so a very
   // long sequence is run as several launches, each continuing from the last state of the one before.

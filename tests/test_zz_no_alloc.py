@@ -115,3 +115,28 @@ def test_noalloc_call_captured_in_a_graph_and_replayed(H, dens, opts):
         want = oracle.rnn_forward(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits, new_x.cpu().numpy(), w.h0, threads=8)
         for t in range(w.steps):
             assert np.abs(got[t] - want[t]).max() <= REL_TOL * np.abs(want[t]).max() + 1e-30, t
+
+
+def test_calls_on_the_handles_own_ring_are_refused_under_capture():
+    # a launch on the handle's own ring carries the handle's position in that ring: replayed, it would accept the last
+    # replay's values as its own, so it is refused while the stream is being captured (and works again afterwards)
+    w = wl.make_workload("cap", "relu", 512, 4, 6, 0.2, seed=19)
+    with binding.SparseRNN(w.hidden, w.batch, w.cell, w.row_ptr, w.col_idx, w.val_bits) as rnn:
+        x = _dev(w.x)
+        out = torch.empty_like(x)
+        want = rnn.forward(x, None).cpu().numpy()
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        refused = None
+        with torch.cuda.graph(graph, stream=side):
+            try:
+                rnn.forward(x, None, out)
+            except binding.SprnnError as e:
+                refused = e.code
+            rnn.forward_noalloc(x, None, out)
+        assert refused == binding.SPRNN_ERR_UNSUPPORTED
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want)
+        assert np.array_equal(rnn.forward(x, None).cpu().numpy(), want) and rnn.check() == binding.SPRNN_OK
