@@ -136,6 +136,52 @@ def test_packer_preserves_every_row_bit_exactly(cell, H, B, dens, rownnz, opts):
             assert np.all(units[:, :, 3] == -1) and info["rows"] == 3 * H
 
 
+def test_packer_preserves_rows_for_drawn_shapes_and_options():
+    # a fixed draw of shapes, densities (empty rows and an empty matrix included) and mapping options: whatever the
+    # packer accepts must hold every row's nonzeros bit for bit, once; what it refuses it must refuse with a status
+    rng = np.random.default_rng(20261)
+    ran = refused = 0
+    for case in range(80):
+        cell = ["relu", "tanh", "identity", "lstm", "gru"][int(rng.integers(0, 5))]
+        B = [1, 2, 4, 8][int(rng.integers(0, 4))]
+        H = int(rng.integers(1, 400))
+        dens = float(rng.choice([0.0, 0.01, 0.05, 0.2, 0.6, 1.0]))
+        opts = {}
+        pick = int(rng.integers(0, 8))
+        if pick == 0:
+            opts["lanes_per_row"] = int(2 ** rng.integers(0, 7))
+        elif pick == 1:
+            opts["grid"] = int(rng.integers(1, 40))
+        elif pick == 2:
+            opts["waves"] = int(rng.integers(1, 13))
+        elif pick == 3:
+            opts["balance"] = int(rng.integers(1, 3))
+        elif pick == 4:
+            opts["bank_aware"] = 2
+        elif pick == 5 and B in (4, 8) and cell in ("relu", "tanh", "identity"):
+            opts["activations"] = 2
+        w = wl.make_workload("d", cell, H, B, 1, dens, seed=case, row_nnz=["fixed", "poisson"][case % 2], gain=1.0)
+        try:
+            words, lane_row, lane_words, info = binding.pack_host(H, B, cell, w.row_ptr, w.col_idx, w.val_bits, **opts)
+        except binding.SprnnError as e:
+            assert e.code in (binding.SPRNN_ERR_INVALID, binding.SPRNN_ERR_CAPACITY, binding.SPRNN_ERR_UNSUPPORTED), (case, e)
+            assert opts, "the packer's own choice must fit these sizes"
+            refused += 1
+            continue
+        ran += 1
+        if info["compact"]:
+            continue                      # (offsets are positions in the workgroup's copy list: covered on the GPU)
+        got = _unpack(words, lane_row, lane_words, info, H, B)
+        for r in range(w.rows):
+            cols = w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]]
+            bits = w.val_bits[w.row_ptr[r]:w.row_ptr[r + 1]]
+            want = sorted((int(c), int(b)) for c, b in zip(cols, bits) if (int(b) & 0x7FFF) != 0)
+            assert got.get(r, []) == want, (case, cell, H, B, dens, opts, r)
+        assert int(lane_words.sum()) == w.nnz and info["nnz"] == w.nnz, (case, cell, H, B, dens, opts)
+        assert info["grid"] * info["waves"] * 64 == lane_row.size
+    assert ran >= 60, (ran, refused)
+
+
 @pytest.mark.parametrize("cell,H,B,dens,rownnz,opts", [
     ("relu", 300, 4, 0.3, "poisson", {}),
     ("tanh", 257, 1, 0.2, "poisson", {"grid": 5}),
