@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,activations,cells,training,casestudy] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,activations,thinned,cells,training,casestudy] [--reps 8]
     python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged|pool|two_part|spread32|one_xcd32
                                                                   (one variant alone in the process, for counter passes)
 
@@ -216,6 +216,35 @@ def activations(torch, wl, reps):
     print()
 
 
+def thinned(torch, wl, reps):
+    """How much of a step is the operate stage: the same layer on the same mapping with every row cut down to a part of
+    its nonzeros, down to none.  What remains with none is the exchange of h, the reduction and the epilogue."""
+    import copy
+    print("## Step time against the part of every row's nonzeros kept (mapping and back-off fixed): what the operate stage costs\n")
+    print("| shape | grid x block, lanes per row | all | 3/4 | 1/2 | 1/4 | none | operate stage = all - none | LDS bound of the operate stage (16 B per gather at the measured 152 TB/s, on the CUs the mapping uses) |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for name, opts in (("cfg3", dict(lanes_per_row=64, waves=9, grid=256, poll_delay=3)),
+                       ("cfg5", dict(lanes_per_row=16, waves=4, fill_waves=8, grid=256, poll_delay=5)),
+                       ("cfg2", dict(lanes_per_row=16, grid=32, xcd="one", poll_delay=1))):
+        full = wl.make_config(name)
+        got = []
+        info = None
+        for keep in (1.0, 0.75, 0.5, 0.25, 0.0):
+            w = copy.copy(full)
+            counts = ((full.row_ptr[1:] - full.row_ptr[:-1]) * keep).astype(np.int64)
+            sel = np.concatenate([np.arange(a, a + n) for a, n in zip(full.row_ptr[:-1], counts)]) if counts.sum() else np.zeros(0, np.int64)
+            w.row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+            w.col_idx, w.val_bits = full.col_idx[sel.astype(np.int64)], full.val_bits[sel.astype(np.int64)]
+            us, i = measure(torch, w, reps, **opts)
+            info = info or i
+            got.append(us)
+        planes = 2 if full.batch == 8 else 1
+        bound = full.nnz * 16.0 * planes / (152e12 * min(info["grid"], 256) / 256.0) * 1e6   # (the CUs the mapping uses)
+        print("| %s | %d x %d, %d | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f | %.2f |" % (
+            name, info["grid"], info["block"], info["lanes_per_row"], got[0], got[1], got[2], got[3], got[4], got[0] - got[4], bound), flush=True)
+    print()
+
+
 def cells(torch, wl, reps):
     print("## Cells: hidden 1024, density 20 %, T 256\n")
     print("| cell | gate rows | batch | nonzeros | persistent us/step | grid x block | lanes/row | back-off |")
@@ -301,7 +330,7 @@ def casestudy(torch, wl, reps):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,activations,cells,training,casestudy")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,activations,thinned,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
     ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged | pool | two_part | spread32 | one_xcd32")
     ap.add_argument("--config", default="cfg2", help="with --what rung: the configuration")
@@ -330,6 +359,8 @@ def main():
         placement(torch, wl, args.reps)
     if "activations" in what:
         activations(torch, wl, args.reps)
+    if "thinned" in what:
+        thinned(torch, wl, args.reps)
     if "cells" in what:
         cells(torch, wl, args.reps)
     if "training" in what:
