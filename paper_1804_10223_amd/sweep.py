@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Ablation and parameter sweeps of the persistent sparse recurrent kernel on synthetic layers.
 
-    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,activations,thinned,cells,training,casestudy] [--reps 8]
+    python -m paper_1804_10223_amd.sweep [--what ablation,density,size,constnnz,batch,steps,placement,activations,thinned,exchange,cells,training,casestudy] [--reps 8]
     python -m paper_1804_10223_amd.sweep --what rung --config cfg2 --rung naive|wide|bank_aware|tagged|pool|two_part|spread32|one_xcd32
                                                                   (one variant alone in the process, for counter passes)
 
@@ -245,6 +245,34 @@ def thinned(torch, wl, reps):
     print()
 
 
+def exchange(torch, wl, reps):
+    """The hand-off alone: a matrix with no nonzeros at all (every row empty), so a step is publish, exchange of h,
+    reduction of zeros and epilogue, against the number of workgroups that take part and the bytes of h."""
+    from . import binding
+    print("## The exchange alone (a matrix without nonzeros): microseconds per timestep against participants and bytes of h, T 256\n")
+    print("| hidden | batch | h | grid x block | placement | us/step |")
+    print("|---|---|---|---|---|---|")
+    cases = [(2304, 4, dict(grid=256, waves=9, lanes_per_row=64, xcd="spread")),
+             (2304, 4, dict(grid=128, waves=9, lanes_per_row=32, xcd="spread")),
+             (2304, 4, dict(grid=64, waves=9, lanes_per_row=16, xcd="spread")),
+             (2304, 4, dict(grid=32, waves=9, lanes_per_row=8, xcd="spread")),
+             (2304, 4, dict(grid=32, waves=9, lanes_per_row=8, xcd="one")),
+             (2304, 4, dict(grid=16, waves=9, lanes_per_row=4, xcd="one")),
+             (256, 4, dict(grid=256, waves=1, lanes_per_row=64, xcd="spread")),
+             (2304, 2, dict(grid=256, waves=9, lanes_per_row=64, xcd="spread")),
+             (4096, 4, dict(grid=256, waves=8, lanes_per_row=32, xcd="spread")),
+             (2304, 8, dict(grid=256, waves=9, lanes_per_row=64, xcd="spread"))]
+    for H, B, opts in cases:
+        w = wl.make_workload("x", "relu", H, B, 256, 0.0, seed=0)
+        try:
+            us, info = measure(torch, w, reps, **opts)
+            print("| %d | %d | %d KB | %d x %d | %s | %.2f |" % (H, B, H * B * 4 // 1024, info["grid"], info["block"],
+                                                             "one XCD" if info["one_xcd"] else "all XCDs", us), flush=True)
+        except Exception as e:
+            print("| %d | %d | %d KB | | refused: %s | |" % (H, B, H * B * 4 // 1024, e), flush=True)
+    print()
+
+
 def cells(torch, wl, reps):
     print("## Cells: hidden 1024, density 20 %, T 256\n")
     print("| cell | gate rows | batch | nonzeros | persistent us/step | grid x block | lanes/row | back-off |")
@@ -330,7 +358,7 @@ def casestudy(torch, wl, reps):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,activations,thinned,cells,training,casestudy")
+    ap.add_argument("--what", default="ablation,density,size,constnnz,batch,steps,placement,activations,thinned,exchange,cells,training,casestudy")
     ap.add_argument("--reps", type=int, default=8)
     ap.add_argument("--rung", default="", help="with --what rung: naive | wide | bank_aware | tagged | pool | two_part | spread32 | one_xcd32")
     ap.add_argument("--config", default="cfg2", help="with --what rung: the configuration")
@@ -361,6 +389,8 @@ def main():
         activations(torch, wl, args.reps)
     if "thinned" in what:
         thinned(torch, wl, args.reps)
+    if "exchange" in what:
+        exchange(torch, wl, args.reps)
     if "cells" in what:
         cells(torch, wl, args.reps)
     if "training" in what:
